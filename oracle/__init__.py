@@ -1,0 +1,20 @@
+"""CPU oracle (float64, plain C + OpenMP) for spherical attention.
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the
+cpu_baseline leg of the benchmark.  The product package never imports this.
+"""
+from .s2_oracle import (  # noqa: F401
+    EQUIANGULAR,
+    LEGENDRE_GAUSS,
+    build,
+    geodesic,
+    global_bwd,
+    global_fwd,
+    grid,
+    indicator,
+    indicator_point,
+    nattn_bwd,
+    nattn_fwd,
+    neighbor_csr,
+    omega,
+)

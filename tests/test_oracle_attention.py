@@ -1,0 +1,213 @@
+"""Pins for the oracle's attention forward/backward (App. B.1-B.4).
+
+Nothing here compares the oracle with itself through the same formula: the
+reference values come from a dense masked softmax in torch (library routine +
+autograd), from torch's scaled_dot_product_attention with an additive log-omega
+mask (App. B.2), from finite differences, and from invariants of the definition.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+from indep import dense_attention, log_omega_tokens
+from paper_2505_11157_amd.workloads import CONFIGS, grid_dict, make_inputs
+
+SMALL = [
+    dict(kind="nattn", grid_type=0, nlat_in=17, nlon_in=32, nlat_out=17, nlon_out=32, theta=math.pi / 8,
+         batch=1, heads=1, d=8, dtype="f32"),
+    dict(kind="nattn", grid_type=1, nlat_in=12, nlon_in=24, nlat_out=12, nlon_out=24, theta=0.6,
+         batch=1, heads=2, d=4, dtype="f32"),
+    dict(kind="nattn", grid_type=0, nlat_in=17, nlon_in=32, nlat_out=9, nlon_out=16, theta=0.45,
+         batch=1, heads=2, d=5, dtype="f32"),
+    dict(kind="nattn", grid_type=1, nlat_in=16, nlon_in=36, nlat_out=8, nlon_out=12, theta=0.5,
+         batch=2, heads=1, d=3, dtype="f32"),
+]
+
+
+def _inputs(c, seed):
+    _, (q, k, v, g) = make_inputs(c, seed=seed)
+    return [a.astype(np.float64) for a in (q, k, v, g)]
+
+
+@pytest.mark.parametrize("ci", range(len(SMALL)))
+@pytest.mark.parametrize("brute", [False, True])
+def test_forward_backward_vs_dense_torch(ci, brute):
+    c = SMALL[ci]
+    g = grid_dict(c)
+    q, k, v, dout = _inputs(c, 10 + ci)
+    scale = 1 / math.sqrt(c["d"])
+    out, lse = O.nattn_fwd(g, q, k, v, scale, brute=brute)
+    dq, dk, dv = O.nattn_bwd(g, q, k, v, dout, scale, brute=brute)
+    r_out, r_lse, r_dq, r_dk, r_dv = dense_attention(g, q, k, v, scale, dout)
+    for a, b in ((out, r_out), (lse, r_lse), (dq, r_dq), (dk, r_dk), (dv, r_dv)):
+        assert a.shape == b.shape
+        assert np.allclose(a, b, rtol=1e-11, atol=1e-13)
+
+
+def test_different_value_width_vs_dense_torch():
+    c = dict(SMALL[1])
+    g = grid_dict(c)
+    rng = np.random.default_rng(5)
+    q = rng.standard_normal((2, 4, 12, 24)); k = rng.standard_normal((2, 4, 12, 24))
+    v = rng.standard_normal((2, 7, 12, 24)); dout = rng.standard_normal((2, 7, 12, 24))
+    out, lse = O.nattn_fwd(g, q, k, v, 0.37)
+    dq, dk, dv = O.nattn_bwd(g, q, k, v, dout, 0.37)
+    ref = dense_attention(g, q, k, v, 0.37, dout)
+    for a, b in zip((out, lse, dq, dk, dv), ref):
+        assert np.allclose(a, b, rtol=1e-11, atol=1e-13)
+
+
+@pytest.mark.parametrize("gt,nlat,nlon", [(0, 9, 16), (1, 8, 12)])
+def test_global_vs_sdpa_with_log_omega_mask(gt, nlat, nlon):
+    rng = np.random.default_rng(3)
+    nbh, d, N = 3, 6, nlat * nlon
+    q, k, v, dout = (rng.standard_normal((nbh, N, d)) for _ in range(4))
+    scale = 1 / math.sqrt(d)
+    out, lse = O.global_fwd(gt, nlat, nlon, q, k, v, scale)
+    dq, dk, dv = O.global_bwd(gt, nlat, nlon, q, k, v, dout, scale)
+    g = dict(grid_type=gt, nlat_in=nlat, nlon_in=nlon, nlat_out=nlat, nlon_out=nlon, theta=math.pi)
+    bias = torch.tensor(log_omega_tokens(g))
+    qt, kt, vt = (torch.tensor(a, requires_grad=True) for a in (q, k, v))
+    ref = torch.nn.functional.scaled_dot_product_attention(qt, kt, vt, attn_mask=bias.expand(N, N), scale=scale)
+    (ref * torch.tensor(dout)).sum().backward()
+    assert np.allclose(out, ref.detach().numpy(), rtol=1e-11, atol=1e-13)
+    ref_lse = torch.logsumexp(qt.detach() @ kt.detach().transpose(1, 2) * scale + bias, -1).numpy()
+    assert np.allclose(lse, ref_lse, rtol=1e-12, atol=1e-13)
+    assert np.allclose(dq, qt.grad.numpy(), rtol=1e-10, atol=1e-13)
+    assert np.allclose(dk, kt.grad.numpy(), rtol=1e-10, atol=1e-13)
+    assert np.allclose(dv, vt.grad.numpy(), rtol=1e-10, atol=1e-13)
+
+
+@pytest.mark.parametrize("gt,nlat,nlon", [(0, 9, 16), (1, 8, 12)])
+def test_theta_pi_equals_global(gt, nlat, nlon):
+    rng = np.random.default_rng(4)
+    nbh, d = 2, 5
+    q, k, v, dout = (rng.standard_normal((nbh, d, nlat, nlon)) for _ in range(4))
+    g = dict(grid_type=gt, nlat_in=nlat, nlon_in=nlon, nlat_out=nlat, nlon_out=nlon, theta=math.pi)
+    tok = lambda a: a.reshape(nbh, d, -1).transpose(0, 2, 1)
+    out, lse = O.nattn_fwd(g, q, k, v, 0.4)
+    dq, dk, dv = O.nattn_bwd(g, q, k, v, dout, 0.4)
+    gout, glse = O.global_fwd(gt, nlat, nlon, tok(q), tok(k), tok(v), 0.4)
+    gdq, gdk, gdv = O.global_bwd(gt, nlat, nlon, tok(q), tok(k), tok(v), tok(dout), 0.4)
+    assert np.allclose(tok(out), gout, rtol=1e-12, atol=1e-14)
+    assert np.allclose(lse.reshape(nbh, -1), glse, rtol=1e-12, atol=1e-14)
+    for a, b in ((dq, gdq), (dk, gdk), (dv, gdv)):
+        assert np.allclose(tok(a), b, rtol=1e-11, atol=1e-14)
+
+
+def test_finite_differences_config1():
+    c, (q, k, v, dout) = make_inputs(1)
+    q, k, v, dout = (a.astype(np.float64) for a in (q, k, v, dout))
+    g = grid_dict(1)
+    scale = 1 / math.sqrt(c["d"])
+    dq, dk, dv = O.nattn_bwd(g, q, k, v, dout, scale)
+    loss = lambda q_, k_, v_: float((O.nattn_fwd(g, q_, k_, v_, scale)[0] * dout).sum())
+    rng = np.random.default_rng(7)
+    eps = 1e-6
+    for which, grad in enumerate((dq, dk, dv)):
+        for _ in range(50):
+            idx = tuple(rng.integers(0, s) for s in grad.shape)
+            args_p = [q.copy(), k.copy(), v.copy()]; args_m = [q.copy(), k.copy(), v.copy()]
+            args_p[which][idx] += eps; args_m[which][idx] -= eps
+            fd = (loss(*args_p) - loss(*args_m)) / (2 * eps)
+            assert abs(fd - grad[idx]) < 1e-6 * max(1.0, abs(grad[idx])), (which, idx, fd, grad[idx])
+
+
+def test_forward_invariants():
+    c = SMALL[2]
+    g = grid_dict(c)
+    q, k, v, _ = _inputs(c, 21)
+    scale = 1 / math.sqrt(c["d"])
+    # constant v passes through (the weights are a probability distribution)
+    out, _ = O.nattn_fwd(g, q, k, np.full_like(v, 1.75), scale)
+    assert np.allclose(out, 1.75, rtol=0, atol=1e-14)
+    # q = 0: omega-weighted mean over the disk, lse = ln of the disk's quadrature area
+    out, lse = O.nattn_fwd(g, np.zeros_like(q), k, v, scale)
+    m = O.indicator(**g).astype(np.float64)
+    om = O.omega(g["grid_type"], g["nlat_in"], g["nlon_in"])
+    area = (m * om[None, :, None]).sum(axis=(1, 2))
+    assert np.allclose(lse, np.log(area)[None, :, None], rtol=1e-13, atol=1e-14)
+    ps = g["nlon_in"] // g["nlon_out"]
+    for h in (0, 3, 8):
+        for w in (0, 5):
+            wgt = np.roll(m[h], w * ps, axis=1) * om[:, None]
+            want = (v * wgt[None, None]).sum(axis=(2, 3)) / wgt.sum()
+            assert np.allclose(out[:, :, h, w], want, rtol=1e-12, atol=1e-14)
+
+
+def test_theta_pi_zero_query_gives_ln_4pi_and_spherical_mean():
+    nlat, nlon = 9, 16
+    g = dict(grid_type=0, nlat_in=nlat, nlon_in=nlon, nlat_out=nlat, nlon_out=nlon, theta=math.pi)
+    rng = np.random.default_rng(8)
+    k = rng.standard_normal((1, 4, nlat, nlon)); v = rng.standard_normal((1, 4, nlat, nlon))
+    out, lse = O.nattn_fwd(g, np.zeros_like(k), k, v, 0.5)
+    assert np.allclose(lse, 2.5310242469692907, rtol=0, atol=1e-14)
+    # independent quadrature: Clenshaw-Curtis pole weight and symmetry are pinned elsewhere; here use the
+    # mean of v == 1 on the northern cap and 0 elsewhere -> area fraction of rows is sum of omega over them
+    om = O.omega(0, nlat, nlon)
+    mean = (v * om[None, None, :, None]).sum(axis=(2, 3)) / (4 * math.pi)
+    assert np.allclose(out, mean[:, :, None, None], rtol=1e-12, atol=1e-14)
+    glse = O.global_fwd(0, nlat, nlon, np.zeros((1, nlat * nlon, 4)), np.ones((1, nlat * nlon, 4)),
+                        np.ones((1, nlat * nlon, 4)), 1.0)[1]
+    assert np.allclose(glse, math.log(4 * math.pi), rtol=0, atol=1e-14)
+
+
+@pytest.mark.parametrize("ci", [0, 2])
+def test_equivariance_longitude_roll_flip_reflection(ci):
+    c = SMALL[ci]
+    g = grid_dict(c)
+    q, k, v, dout = _inputs(c, 30 + ci)
+    scale = 1 / math.sqrt(c["d"])
+    ps = g["nlon_in"] // g["nlon_out"]
+    out, lse = O.nattn_fwd(g, q, k, v, scale)
+    dq, dk, dv = O.nattn_bwd(g, q, k, v, dout, scale)
+    # roll by one output longitude step: same terms, summed in a rotated order
+    r = lambda a, s: np.roll(a, s, axis=-1)
+    eq = lambda a, b: np.allclose(a, b, rtol=1e-12, atol=1e-14)
+    out2, lse2 = O.nattn_fwd(g, r(q, 1), r(k, ps), r(v, ps), scale)
+    assert eq(out2, r(out, 1)) and eq(lse2, r(lse, 1))
+    dq2, dk2, dv2 = O.nattn_bwd(g, r(q, 1), r(k, ps), r(v, ps), r(dout, 1), scale)
+    assert eq(dq2, r(dq, 1)) and eq(dk2, r(dk, ps)) and eq(dv2, r(dv, ps))
+    # north-south flip and longitude reflection (w -> -w): equal up to summation order
+    f = lambda a: a[..., ::-1, :]
+    out3, lse3 = O.nattn_fwd(g, f(q), f(k), f(v), scale)
+    assert np.allclose(out3, f(out), rtol=1e-12, atol=1e-14) and np.allclose(lse3, f(lse), rtol=1e-12, atol=1e-14)
+    m = lambda a: np.roll(a[..., ::-1], 1, axis=-1)
+    out4, lse4 = O.nattn_fwd(g, m(q), m(k), m(v), scale)
+    assert np.allclose(out4, m(out), rtol=1e-12, atol=1e-14) and np.allclose(lse4, m(lse), rtol=1e-12, atol=1e-14)
+
+
+def test_backward_invariants():
+    c = SMALL[3]
+    g = grid_dict(c)
+    q, k, v, dout = _inputs(c, 40)
+    scale = 0.8
+    dq, dk, dv = O.nattn_bwd(g, q, k, v, dout, scale)
+    # sum_j p_ij = 1  =>  sum_j dv_j = sum_i dout_i (per slice and channel)
+    assert np.allclose(dv.sum(axis=(2, 3)), dout.sum(axis=(2, 3)), rtol=1e-12, atol=1e-13)
+    # both equal scale * sum_ij dS_ij s_ij / scale
+    assert abs((q * dq).sum() - (k * dk).sum()) < 1e-11 * max(1.0, abs((q * dq).sum()))
+    # constant k: logits do not depend on j beyond ln omega, softmax is q-independent => dq = 0
+    kc = np.broadcast_to(k[:, :, :1, :1], k.shape).copy()
+    dq0, _, _ = O.nattn_bwd(g, q, kc, v, dout, scale)
+    assert np.abs(dq0).max() < 1e-13
+    # constant v: out is constant => no gradient reaches q or k
+    vc = np.broadcast_to(v[:, :, :1, :1], v.shape).copy()
+    dq1, dk1, _ = O.nattn_bwd(g, q, k, vc, dout, scale)
+    assert np.abs(dq1).max() < 1e-13 and np.abs(dk1).max() < 1e-13
+
+
+def test_config2_slice_vs_dense_torch():
+    # 64x128 Legendre-Gauss, N = 8192: one (b, head) slice against the dense 8192 x 8192 masked softmax.
+    c, arrs = make_inputs(2)
+    q, k, v, dout = (a[:1].astype(np.float64) for a in arrs)
+    g = grid_dict(2)
+    scale = 1 / math.sqrt(c["d"])
+    out, lse = O.nattn_fwd(g, q, k, v, scale)
+    dq, dk, dv = O.nattn_bwd(g, q, k, v, dout, scale)
+    ref = dense_attention(g, q, k, v, scale, dout)
+    for a, b in zip((out, lse, dq, dk, dv), ref):
+        assert np.allclose(a, b, rtol=1e-10, atol=1e-12)
