@@ -1,0 +1,159 @@
+/*
+ * s2attn.h -- C ABI of the MI355X (gfx950) spherical attention library.
+ *
+ * Quadrature-weighted attention on latitude-longitude grids of the sphere
+ * ("Attention on the Sphere"): the neighborhood variant restricted to a
+ * geodesic disk and the global variant, forward and backward.
+ *
+ * Conventions
+ *   - Every tensor pointer is DEVICE memory owned by the caller; the library
+ *     reads inputs, writes outputs and never keeps a pointer after the call.
+ *   - Calls enqueue work on `hip_stream` (a hipStream_t passed as void*; NULL
+ *     is the default stream) and return without synchronising.
+ *   - The only allocations happen in s2_grid_init (host tables plus one small
+ *     device upload).  Scratch memory for the backward passes is passed in as
+ *     `workspace`; its size comes from the *_workspace_bytes queries.
+ *   - Return value: S2_OK or a negative S2_ERR_* code; s2_last_error() gives
+ *     a thread-local message for the last failure on the calling thread.
+ *   - Batch and heads are independent problems; tensors carry them as the two
+ *     leading axes [batch][heads]... contiguous (App. B.3: B x C x H x W with
+ *     C = heads * d).
+ */
+#ifndef S2ATTN_H
+#define S2ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct s2_grid s2_grid_t; /* opaque; immutable after init; usable from any stream */
+
+/* Grid types (Sec. 3.3: equiangular and Gaussian grids). */
+enum {
+    S2_GRID_EQUIANGULAR = 0,   /* colat_h = pi*h/(nlat-1), both poles, Clenshaw-Curtis weights */
+    S2_GRID_LEGENDRE_GAUSS = 1 /* Gauss-Legendre nodes in cos(colat), north first */
+};
+
+enum { S2_F32 = 0, S2_BF16 = 1 };
+
+enum {
+    S2_OK = 0,
+    S2_ERR_INVALID_ARG = -1,
+    S2_ERR_UNSUPPORTED = -2,
+    S2_ERR_EMPTY_NEIGHBORHOOD = -3,
+    S2_ERR_ALLOC = -4,
+    S2_ERR_DEVICE = -5,
+    S2_ERR_WORKSPACE = -6,
+    S2_ERR_AMBIGUOUS_CUTOFF = -7
+};
+
+/*
+ * Host precompute (App. A.1 quadrature; Sec. 3.2 eq. (5) disk; App. B.3
+ * shift-invariant indicator 1[h,h',w']).
+ *
+ * Builds, in float64 on the host: colatitudes and quadrature weights
+ * omega[h'] = latitude weight * 2*pi/nlon_in of the INPUT grid, and for every
+ * output latitude h the input points (h', w') whose great-circle distance to
+ * the output point (h, longitude 0) is <= theta_cutoff + 1e-9 rad.  The lists
+ * are reused for every output longitude w by the shift w' -> w' + w*pscale,
+ * pscale = nlon_in / nlon_out.  Both grids have the same grid_type.
+ *
+ * If a HIP device is present the compact tables are uploaded to the current
+ * device; without a device the handle is host-only (the introspection calls
+ * work, the attention calls return S2_ERR_DEVICE).
+ *
+ * Errors: S2_ERR_INVALID_ARG (nlat < 2, nlon < 1, theta outside (0, pi], NULL
+ * out_grid, unknown grid_type); S2_ERR_UNSUPPORTED (nlon_in not a multiple of
+ * nlon_out); S2_ERR_EMPTY_NEIGHBORHOOD (some output point sees no input point);
+ * S2_ERR_AMBIGUOUS_CUTOFF (a point lies within 1e-12 rad of the inclusion
+ * threshold, so membership would depend on rounding: perturb theta_cutoff);
+ * S2_ERR_ALLOC / S2_ERR_DEVICE.
+ * Ownership: *out_grid is owned by the library; release with s2_grid_destroy.
+ */
+int s2_grid_init(int grid_type, int nlat_in, int nlon_in, int nlat_out, int nlon_out,
+                 double theta_cutoff, s2_grid_t **out_grid);
+void s2_grid_destroy(s2_grid_t *g);
+
+/* Introspection (host buffers; any pointer may be NULL to skip it).
+ * colat_in, omega_in: nlat_in doubles (omega includes 2*pi/nlon_in). */
+int s2_grid_get_weights(const s2_grid_t *g, double *colat_in, double *omega_in);
+/* Number of entries of the canonical neighbor list (sum over output latitudes). */
+int64_t s2_grid_num_neighbors(const s2_grid_t *g);
+/* Canonical CSR of 1[h,h',w']: row_ptr has nlat_out+1 entries; col holds
+ * h'*nlon_in + w' with w' in [0, nlon_in), ascending within each output
+ * latitude; col needs s2_grid_num_neighbors(g) entries. */
+int s2_grid_get_neighbors(const s2_grid_t *g, int64_t *row_ptr, int32_t *col);
+
+/* Bytes of device scratch s2_nattn_bwd needs (0 for the forward pass). */
+size_t s2_nattn_bwd_workspace_bytes(const s2_grid_t *g, int batch, int heads, int d_qk, int d_v, int dtype);
+
+/*
+ * Neighborhood attention forward (App. B.1 second equation; index form of
+ * App. B.3):
+ *   out[b,hd,c,h,w] = sum_{(h',w') in list(h)} p * v[b,hd,c,h',(w*pscale+w') mod nlon_in]
+ *   p = exp(scale * q[b,hd,:,h,w].k[b,hd,:,h',...] + ln omega[h'] - lse[b,hd,h,w])
+ *   lse = ln sum exp(scale*q.k + ln omega)        (natural log, omega included)
+ * Layouts (contiguous): q, out [batch][heads][d][nlat_out][nlon_out] (out has
+ * d_v channels); k [batch][heads][d_qk][nlat_in][nlon_in]; v likewise with d_v;
+ * lse float32 [batch][heads][nlat_out][nlon_out].
+ * dtype: S2_F32 (float32 arithmetic throughout).  d_qk, d_v in [1, 128].
+ * Errors: S2_ERR_INVALID_ARG (NULL pointers, sizes < 1), S2_ERR_UNSUPPORTED
+ * (dtype, head dims), S2_ERR_DEVICE (host-only handle or launch failure).
+ */
+int s2_nattn_fwd(const s2_grid_t *g, int batch, int heads, int d_qk, int d_v, int dtype, float scale,
+                 const void *q, const void *k, const void *v, void *out, float *lse,
+                 void *hip_stream);
+
+/*
+ * Neighborhood attention backward (App. B.4, with the derivation's typos
+ * fixed): given dout = dL/dout and the forward's out and lse,
+ *   p_ij = exp(scale*q_i.k_j + ln omega_j - lse_i),  D_i = dout_i.out_i,
+ *   dS_ij = p_ij (dout_i.v_j - D_i),
+ *   dq_i = scale * sum_{j in N(i)} dS_ij k_j,
+ *   dk_j = scale * sum_{i: j in N(i)} dS_ij q_i,   dv_j = sum_{i: j in N(i)} p_ij dout_i.
+ * dk and dv are gathered through the transposed neighborhood (input point ->
+ * output points): no atomics, bit-reproducible.  omega carries no gradient.
+ * dq like q, dk like k, dv like v.  workspace: device scratch of at least
+ * s2_nattn_bwd_workspace_bytes(...) bytes (S2_ERR_WORKSPACE if smaller).
+ */
+int s2_nattn_bwd(const s2_grid_t *g, int batch, int heads, int d_qk, int d_v, int dtype, float scale,
+                 const void *q, const void *k, const void *v, const void *out, const float *lse,
+                 const void *dout, void *dq, void *dk, void *dv,
+                 void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Bytes of device scratch s2_attn_global_bwd needs. */
+size_t s2_attn_global_bwd_workspace_bytes(const s2_grid_t *g, int batch, int heads, int d, int dtype);
+
+/*
+ * Global quadrature-weighted attention forward (App. B.1 first equation;
+ * App. B.2: softmax with the additive column bias ln omega_j):
+ *   out_i = sum_j softmax_j(scale*q_i.k_j + ln omega_j) v_j over all N tokens.
+ * The handle must have identical input and output grids; token j = h*nlon + w,
+ * N = nlat*nlon.  Layouts (contiguous, token-major): q, k, v, out
+ * [batch][heads][N][d]; lse float32 [batch][heads][N].
+ * dtype: S2_BF16 (bf16 tensors, MFMA with float32 accumulation, float32
+ * softmax and lse).  d in {64, 128}... see S2_ERR_UNSUPPORTED.
+ */
+int s2_attn_global_fwd(const s2_grid_t *g, int batch, int heads, int d, int dtype, float scale,
+                       const void *q, const void *k, const void *v, void *out, float *lse,
+                       void *hip_stream);
+
+/*
+ * Global attention backward: the formulas of s2_nattn_bwd with every token a
+ * member of every neighborhood.  dq, dk, dv in the tensors' dtype.
+ */
+int s2_attn_global_bwd(const s2_grid_t *g, int batch, int heads, int d, int dtype, float scale,
+                       const void *q, const void *k, const void *v, const void *out, const float *lse,
+                       const void *dout, void *dq, void *dk, void *dv,
+                       void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Message for the last error on the calling thread ("" if none). */
+const char *s2_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* S2ATTN_H */

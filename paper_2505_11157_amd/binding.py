@@ -1,0 +1,224 @@
+"""Thin ctypes binding of libs2attn.so: same names as the C ABI (include/s2attn.h).
+
+Argument marshalling only.  Tensors are torch tensors used as device-memory
+handles (data_ptr) and the current torch stream is passed as the HIP stream;
+nothing is computed here.  There is no fallback: a missing library raises.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+S2_GRID_EQUIANGULAR = 0
+S2_GRID_LEGENDRE_GAUSS = 1
+S2_F32 = 0
+S2_BF16 = 1
+S2_OK = 0
+S2_ERR_INVALID_ARG = -1
+S2_ERR_UNSUPPORTED = -2
+S2_ERR_EMPTY_NEIGHBORHOOD = -3
+S2_ERR_ALLOC = -4
+S2_ERR_DEVICE = -5
+S2_ERR_WORKSPACE = -6
+S2_ERR_AMBIGUOUS_CUTOFF = -7
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libs2attn.so")
+_lib = None
+
+_vp = ctypes.c_void_p
+_i = ctypes.c_int
+
+
+class S2Error(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__("s2attn error %d: %s" % (code, msg))
+        self.code = code
+
+
+def lib():
+    """Load libs2attn.so (built in-tree by paper_2505_11157_amd/build.py)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError("libs2attn.so is not built: run `python -m paper_2505_11157_amd.build` "
+                              "(or __graft_entry__.build()); there is no fallback path")
+        L = ctypes.CDLL(LIB_PATH)
+        L.s2_grid_init.argtypes = [_i, _i, _i, _i, _i, ctypes.c_double, ctypes.POINTER(_vp)]
+        L.s2_grid_init.restype = _i
+        L.s2_grid_destroy.argtypes = [_vp]
+        L.s2_grid_destroy.restype = None
+        L.s2_grid_get_weights.argtypes = [_vp, _vp, _vp]
+        L.s2_grid_get_weights.restype = _i
+        L.s2_grid_num_neighbors.argtypes = [_vp]
+        L.s2_grid_num_neighbors.restype = ctypes.c_int64
+        L.s2_grid_get_neighbors.argtypes = [_vp, _vp, _vp]
+        L.s2_grid_get_neighbors.restype = _i
+        L.s2_nattn_bwd_workspace_bytes.argtypes = [_vp, _i, _i, _i, _i, _i]
+        L.s2_nattn_bwd_workspace_bytes.restype = ctypes.c_size_t
+        L.s2_nattn_fwd.argtypes = [_vp, _i, _i, _i, _i, _i, ctypes.c_float, _vp, _vp, _vp, _vp, _vp, _vp]
+        L.s2_nattn_fwd.restype = _i
+        L.s2_nattn_bwd.argtypes = [_vp, _i, _i, _i, _i, _i, ctypes.c_float, _vp, _vp, _vp, _vp, _vp, _vp,
+                                   _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
+        L.s2_nattn_bwd.restype = _i
+        L.s2_attn_global_bwd_workspace_bytes.argtypes = [_vp, _i, _i, _i, _i]
+        L.s2_attn_global_bwd_workspace_bytes.restype = ctypes.c_size_t
+        L.s2_attn_global_fwd.argtypes = [_vp, _i, _i, _i, _i, ctypes.c_float, _vp, _vp, _vp, _vp, _vp, _vp]
+        L.s2_attn_global_fwd.restype = _i
+        L.s2_attn_global_bwd.argtypes = [_vp, _i, _i, _i, _i, ctypes.c_float, _vp, _vp, _vp, _vp, _vp, _vp,
+                                         _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
+        L.s2_attn_global_bwd.restype = _i
+        L.s2_last_error.argtypes = []
+        L.s2_last_error.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def s2_last_error():
+    return lib().s2_last_error().decode()
+
+
+def _check(rc):
+    if rc != S2_OK:
+        raise S2Error(rc, s2_last_error())
+
+
+class Grid:
+    """Owner of an s2_grid_t* (released on garbage collection)."""
+
+    def __init__(self, handle, grid_type, nlat_in, nlon_in, nlat_out, nlon_out, theta):
+        self.handle = handle
+        self.grid_type, self.theta = grid_type, theta
+        self.nlat_in, self.nlon_in, self.nlat_out, self.nlon_out = nlat_in, nlon_in, nlat_out, nlon_out
+
+    def __del__(self):
+        if getattr(self, "handle", None) and _lib is not None:
+            _lib.s2_grid_destroy(self.handle)
+            self.handle = None
+
+
+def s2_grid_init(grid_type, nlat_in, nlon_in, nlat_out, nlon_out, theta_cutoff):
+    h = _vp()
+    _check(lib().s2_grid_init(int(grid_type), int(nlat_in), int(nlon_in), int(nlat_out), int(nlon_out),
+                              float(theta_cutoff), ctypes.byref(h)))
+    return Grid(h, grid_type, nlat_in, nlon_in, nlat_out, nlon_out, theta_cutoff)
+
+
+def s2_grid_get_weights(g):
+    colat = np.empty(g.nlat_in, np.float64)
+    om = np.empty(g.nlat_in, np.float64)
+    _check(lib().s2_grid_get_weights(g.handle, colat.ctypes.data, om.ctypes.data))
+    return colat, om
+
+
+def s2_grid_num_neighbors(g):
+    return int(lib().s2_grid_num_neighbors(g.handle))
+
+
+def s2_grid_get_neighbors(g):
+    row_ptr = np.empty(g.nlat_out + 1, np.int64)
+    col = np.empty(s2_grid_num_neighbors(g), np.int32)
+    _check(lib().s2_grid_get_neighbors(g.handle, row_ptr.ctypes.data, col.ctypes.data))
+    return row_ptr, col
+
+
+def _stream():
+    import torch
+    return _vp(torch.cuda.current_stream().cuda_stream)
+
+
+def _dtype_code(t):
+    import torch
+    if t.dtype == torch.float32:
+        return S2_F32
+    if t.dtype == torch.bfloat16:
+        return S2_BF16
+    raise TypeError("unsupported tensor dtype %s" % t.dtype)
+
+
+def _dev(*ts):
+    for t in ts:
+        if not (t.is_cuda and t.is_contiguous()):
+            raise ValueError("tensors must be contiguous device tensors")
+
+
+def s2_nattn_bwd_workspace_bytes(g, batch, heads, d_qk, d_v, dtype=S2_F32):
+    return int(lib().s2_nattn_bwd_workspace_bytes(g.handle, batch, heads, d_qk, d_v, dtype))
+
+
+def s2_nattn_fwd(g, q, k, v, scale, out=None, lse=None):
+    """q [B,H,d,nlat_out,nlon_out], k [B,H,d,nlat_in,nlon_in], v [B,H,e,nlat_in,nlon_in] -> out, lse."""
+    import torch
+    _dev(q, k, v)
+    B, H, d = q.shape[:3]
+    e = v.shape[2]
+    if q.shape[3:] != (g.nlat_out, g.nlon_out) or k.shape != (B, H, d, g.nlat_in, g.nlon_in) \
+            or v.shape != (B, H, e, g.nlat_in, g.nlon_in):
+        raise ValueError("tensor shapes do not match the grid handle")
+    if out is None:
+        out = torch.empty((B, H, e, g.nlat_out, g.nlon_out), dtype=q.dtype, device=q.device)
+    if lse is None:
+        lse = torch.empty((B, H, g.nlat_out, g.nlon_out), dtype=torch.float32, device=q.device)
+    _dev(out, lse)
+    _check(lib().s2_nattn_fwd(g.handle, B, H, d, e, _dtype_code(q), float(scale), q.data_ptr(), k.data_ptr(),
+                              v.data_ptr(), out.data_ptr(), lse.data_ptr(), _stream()))
+    return out, lse
+
+
+def s2_nattn_bwd(g, q, k, v, out, lse, dout, scale, dq=None, dk=None, dv=None, workspace=None):
+    import torch
+    _dev(q, k, v, out, lse, dout)
+    B, H, d = q.shape[:3]
+    e = v.shape[2]
+    if out.shape != (B, H, e, g.nlat_out, g.nlon_out) or dout.shape != out.shape \
+            or lse.shape != (B, H, g.nlat_out, g.nlon_out) or k.shape != (B, H, d, g.nlat_in, g.nlon_in):
+        raise ValueError("tensor shapes do not match the grid handle")
+    dq = torch.empty_like(q) if dq is None else dq
+    dk = torch.empty_like(k) if dk is None else dk
+    dv = torch.empty_like(v) if dv is None else dv
+    need = s2_nattn_bwd_workspace_bytes(g, B, H, d, e, _dtype_code(q))
+    if workspace is None:
+        workspace = torch.empty(max(need, 1), dtype=torch.uint8, device=q.device)
+    _dev(dq, dk, dv, workspace)
+    _check(lib().s2_nattn_bwd(g.handle, B, H, d, e, _dtype_code(q), float(scale), q.data_ptr(), k.data_ptr(),
+                              v.data_ptr(), out.data_ptr(), lse.data_ptr(), dout.data_ptr(), dq.data_ptr(),
+                              dk.data_ptr(), dv.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream()))
+    return dq, dk, dv
+
+
+def s2_attn_global_bwd_workspace_bytes(g, batch, heads, d, dtype=S2_BF16):
+    return int(lib().s2_attn_global_bwd_workspace_bytes(g.handle, batch, heads, d, dtype))
+
+
+def s2_attn_global_fwd(g, q, k, v, scale, out=None, lse=None):
+    """Token-major q, k, v [B,H,N,d] -> out [B,H,N,d], lse float32 [B,H,N]."""
+    import torch
+    _dev(q, k, v)
+    B, H, N, d = q.shape
+    if N != g.nlat_in * g.nlon_in or k.shape != q.shape or v.shape != q.shape:
+        raise ValueError("tensor shapes do not match the grid handle")
+    out = torch.empty_like(q) if out is None else out
+    lse = torch.empty((B, H, N), dtype=torch.float32, device=q.device) if lse is None else lse
+    _dev(out, lse)
+    _check(lib().s2_attn_global_fwd(g.handle, B, H, d, _dtype_code(q), float(scale), q.data_ptr(), k.data_ptr(),
+                                    v.data_ptr(), out.data_ptr(), lse.data_ptr(), _stream()))
+    return out, lse
+
+
+def s2_attn_global_bwd(g, q, k, v, out, lse, dout, scale, dq=None, dk=None, dv=None, workspace=None):
+    import torch
+    _dev(q, k, v, out, lse, dout)
+    B, H, N, d = q.shape
+    if N != g.nlat_in * g.nlon_in or out.shape != q.shape or dout.shape != q.shape or lse.shape != (B, H, N):
+        raise ValueError("tensor shapes do not match the grid handle")
+    dq = torch.empty_like(q) if dq is None else dq
+    dk = torch.empty_like(k) if dk is None else dk
+    dv = torch.empty_like(v) if dv is None else dv
+    need = s2_attn_global_bwd_workspace_bytes(g, B, H, d, _dtype_code(q))
+    if workspace is None:
+        workspace = torch.empty(max(need, 1), dtype=torch.uint8, device=q.device)
+    _dev(dq, dk, dv, workspace)
+    _check(lib().s2_attn_global_bwd(g.handle, B, H, d, _dtype_code(q), float(scale), q.data_ptr(), k.data_ptr(),
+                                    v.data_ptr(), out.data_ptr(), lse.data_ptr(), dout.data_ptr(), dq.data_ptr(),
+                                    dk.data_ptr(), dv.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream()))
+    return dq, dk, dv

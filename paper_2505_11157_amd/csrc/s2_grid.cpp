@@ -1,0 +1,320 @@
+// Host precompute for spherical attention: quadrature weights and the compact
+// geodesic-disk tables, in float64, plus the one upload to the device.
+//
+// Follows App. A.1 (quadrature on a lat-lon grid), Sec. 3.3 (equiangular and
+// Gaussian grids), Sec. 3.2 eq. (5) (disk of geodesic radius theta_cutoff) and
+// App. B.3 (the indicator depends on the output latitude only; every output
+// longitude reuses it by a shift).
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <numeric>
+
+#include "s2_internal.h"
+
+namespace {
+
+constexpr double kPi = 3.141592653589793238462643383279502884;
+constexpr double kTieTol = 1e-9;      // points within this of the cutoff count as inside
+constexpr double kAmbiguous = 1e-12;  // |d - (theta + kTieTol)| below this is rejected
+
+thread_local std::string g_last_error;
+
+// Clenshaw-Curtis weights for int_0^pi f(t) sin t dt on t_h = pi h / n, written
+// as the cosine series  w_h = (c_h / n) * sum''_{k even} 2/(1-k^2) cos(k h pi / n),
+// the double prime halving the k = 0 and k = n terms.
+void clenshaw_curtis_nodes(int nlat, std::vector<double> &colat, std::vector<double> &w)
+{
+    const int n = nlat - 1;
+    colat.resize(nlat);
+    w.resize(nlat);
+    for (int h = 0; h <= n; ++h) {
+        colat[h] = kPi * h / n;
+        double series = 0.0;
+        for (int k = 0; k <= n; k += 2) {
+            double term = 2.0 / (1.0 - double(k) * double(k)) * std::cos(kPi * double(k) * double(h) / double(n));
+            if (k == 0 || k == n) term *= 0.5;
+            series += term;
+        }
+        w[h] = ((h == 0 || h == n) ? 1.0 : 2.0) / n * series;
+    }
+}
+
+// Gauss-Legendre nodes by Newton iteration from Tricomi's estimate; weights
+// from  w = 2 (1 - x^2) / (n P_{n-1}(x))^2.
+void gauss_legendre_nodes(int n, std::vector<double> &colat, std::vector<double> &w)
+{
+    colat.resize(n);
+    w.resize(n);
+    for (int h = 0; h < n; ++h) {
+        double x = (1.0 - (n - 1.0) / (8.0 * double(n) * n * n)) * std::cos(kPi * (4.0 * h + 3.0) / (4.0 * n + 2.0));
+        double pm1 = 1.0;
+        for (int it = 0; it < 64; ++it) {
+            double p_prev = 1.0, p = x;
+            for (int m = 1; m < n; ++m) {
+                double p_next = ((2.0 * m + 1.0) * x * p - m * p_prev) / (m + 1.0);
+                p_prev = p;
+                p = p_next;
+            }
+            pm1 = p_prev;
+            double deriv = n * (pm1 - x * p) / (1.0 - x * x);
+            double step = p / deriv;
+            x -= step;
+            if (std::fabs(step) < 4e-16) break;
+        }
+        {   // P_{n-1} at the converged node
+            double p_prev = 1.0, p = x;
+            for (int m = 1; m < n; ++m) {
+                double p_next = ((2.0 * m + 1.0) * x * p - m * p_prev) / (m + 1.0);
+                p_prev = p;
+                p = p_next;
+            }
+            pm1 = p_prev;
+        }
+        colat[h] = std::acos(x);
+        w[h] = 2.0 * (1.0 - x * x) / (double(n) * n * pm1 * pm1);
+    }
+}
+
+// Great-circle distance in haversine form, with hav and 1-hav both written as
+// sums of non-negative terms so the result is accurate from 0 to pi:
+//   hav   = sin^2(dt/2) cos^2(dp/2) + sin^2(st/2) sin^2(dp/2)
+//   1-hav = cos^2(dt/2) cos^2(dp/2) + cos^2(st/2) sin^2(dp/2),  dt = t1-t2, st = t1+t2.
+double great_circle(double t1, double t2, double dphi)
+{
+    const double sd = std::sin(0.5 * (t1 - t2)), cd = std::cos(0.5 * (t1 - t2));
+    const double ss = std::sin(0.5 * (t1 + t2)), cs = std::cos(0.5 * (t1 + t2));
+    const double sp = std::sin(0.5 * dphi), cp = std::cos(0.5 * dphi);
+    const double hav = sd * sd * cp * cp + ss * ss * sp * sp;
+    const double cohav = cd * cd * cp * cp + cs * cs * sp * sp;
+    return 2.0 * std::atan2(std::sqrt(hav), std::sqrt(cohav));
+}
+
+int nodes(int grid_type, int nlat, std::vector<double> &colat, std::vector<double> &w)
+{
+    if (grid_type == S2_GRID_EQUIANGULAR) clenshaw_curtis_nodes(nlat, colat, w);
+    else if (grid_type == S2_GRID_LEGENDRE_GAUSS) gauss_legendre_nodes(nlat, colat, w);
+    else return -1;
+    return 0;
+}
+
+}  // namespace
+
+void s2_set_error(const std::string &msg) { g_last_error = msg; }
+int s2_fail(int code, const std::string &msg)
+{
+    g_last_error = msg;
+    return code;
+}
+
+extern "C" const char *s2_last_error(void) { return g_last_error.c_str(); }
+
+static int upload_tables(s2_grid *g)
+{
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || ndev <= 0) {
+        (void)hipGetLastError();
+        g->on_device = false;
+        return S2_OK;
+    }
+    S2_HIP_CHECK(hipGetDevice(&g->device));
+    std::vector<float> l2w(g->nlat_in);
+    const double omega_ref = *std::max_element(g->omega_in.begin(), g->omega_in.end());
+    for (int h = 0; h < g->nlat_in; ++h) l2w[h] = float(g->omega_in[h] / omega_ref);
+    // one blob: floats first, then the int tables, each 256-byte aligned
+    struct Part { const void *src; size_t bytes; size_t off; };
+    std::vector<Part> parts = {
+        {l2w.data(), l2w.size() * sizeof(float), 0},
+        {g->band_lo.data(), g->band_lo.size() * sizeof(int), 0},
+        {g->band_n.data(), g->band_n.size() * sizeof(int), 0},
+        {g->cnt.data(), g->cnt.size() * sizeof(int), 0},
+        {g->tband_lo.data(), g->tband_lo.size() * sizeof(int), 0},
+        {g->tband_n.data(), g->tband_n.size() * sizeof(int), 0},
+        {g->tcnt.data(), g->tcnt.size() * sizeof(int), 0},
+        {g->row_order.data(), g->row_order.size() * sizeof(int), 0},
+        {g->trow_order.data(), g->trow_order.size() * sizeof(int), 0},
+    };
+    size_t total = 0;
+    for (auto &p : parts) {
+        p.off = total;
+        total += (p.bytes + 255) / 256 * 256;
+    }
+    std::vector<char> host(total, 0);
+    for (auto &p : parts) std::memcpy(host.data() + p.off, p.src, p.bytes);
+    if (hipMalloc(&g->dev_blob, total) != hipSuccess) {
+        (void)hipGetLastError();
+        return s2_fail(S2_ERR_ALLOC, "hipMalloc of the grid tables failed");
+    }
+    S2_HIP_CHECK(hipMemcpy(g->dev_blob, host.data(), total, hipMemcpyHostToDevice));
+    char *base = static_cast<char *>(g->dev_blob);
+    S2DeviceTables &t = g->dt;
+    t.omega_rel = reinterpret_cast<const float *>(base + parts[0].off);
+    t.ln_omega_ref = float(std::log(omega_ref));
+    t.band_lo = reinterpret_cast<const int *>(base + parts[1].off);
+    t.band_n = reinterpret_cast<const int *>(base + parts[2].off);
+    t.cnt = reinterpret_cast<const int *>(base + parts[3].off);
+    t.tband_lo = reinterpret_cast<const int *>(base + parts[4].off);
+    t.tband_n = reinterpret_cast<const int *>(base + parts[5].off);
+    t.tcnt = reinterpret_cast<const int *>(base + parts[6].off);
+    t.row_order = reinterpret_cast<const int *>(base + parts[7].off);
+    t.trow_order = reinterpret_cast<const int *>(base + parts[8].off);
+    t.band_max = g->band_max;
+    t.tband_max = g->tband_max;
+    t.nlat_in = g->nlat_in; t.nlon_in = g->nlon_in;
+    t.nlat_out = g->nlat_out; t.nlon_out = g->nlon_out;
+    t.pscale = g->pscale;
+    g->on_device = true;
+    return S2_OK;
+}
+
+extern "C" int s2_grid_init(int grid_type, int nlat_in, int nlon_in, int nlat_out, int nlon_out,
+                            double theta_cutoff, s2_grid_t **out_grid)
+{
+    if (!out_grid) return s2_fail(S2_ERR_INVALID_ARG, "out_grid is NULL");
+    *out_grid = nullptr;
+    if (grid_type != S2_GRID_EQUIANGULAR && grid_type != S2_GRID_LEGENDRE_GAUSS)
+        return s2_fail(S2_ERR_INVALID_ARG, "unknown grid_type");
+    if (nlat_in < 2 || nlat_out < 2 || nlon_in < 1 || nlon_out < 1)
+        return s2_fail(S2_ERR_INVALID_ARG, "need nlat >= 2 and nlon >= 1 on both grids");
+    if (nlat_in > 32768 || nlon_in > 65536 || nlat_out > 32768 || nlon_out > 65536)
+        return s2_fail(S2_ERR_INVALID_ARG, "grid too large");
+    if (!(theta_cutoff > 0.0) || theta_cutoff > kPi + 1e-12)
+        return s2_fail(S2_ERR_INVALID_ARG, "theta_cutoff must lie in (0, pi]");
+    if (nlon_in % nlon_out != 0)
+        return s2_fail(S2_ERR_UNSUPPORTED, "nlon_in must be a multiple of nlon_out (longitude shift invariance)");
+
+    s2_grid *g = new (std::nothrow) s2_grid();
+    if (!g) return s2_fail(S2_ERR_ALLOC, "out of host memory");
+    g->grid_type = grid_type;
+    g->nlat_in = nlat_in; g->nlon_in = nlon_in; g->nlat_out = nlat_out; g->nlon_out = nlon_out;
+    g->pscale = nlon_in / nlon_out;
+    g->theta = theta_cutoff;
+    std::vector<double> wlat_in, wlat_out;
+    nodes(grid_type, nlat_in, g->colat_in, wlat_in);
+    nodes(grid_type, nlat_out, g->colat_out, wlat_out);
+    g->omega_in.resize(nlat_in);
+    for (int h = 0; h < nlat_in; ++h) g->omega_in[h] = wlat_in[h] * (2.0 * kPi / nlon_in);
+
+    // cnt_full[h][h'] = number of member longitudes of input latitude h'
+    const double limit = theta_cutoff + kTieTol;
+    std::vector<int> cnt_full(size_t(nlat_out) * nlat_in, 0);
+    std::vector<char> member(nlon_in);
+    for (int h = 0; h < nlat_out; ++h) {
+        for (int hp = 0; hp < nlat_in; ++hp) {
+            // the closest point of latitude circle h' lies on the output meridian
+            if (std::fabs(g->colat_out[h] - g->colat_in[hp]) > limit + 1e-6) continue;
+            int c = 0;
+            for (int wp = 0; wp < nlon_in; ++wp) {
+                const double dist = great_circle(g->colat_out[h], g->colat_in[hp], 2.0 * kPi * wp / nlon_in);
+                if (std::fabs(dist - limit) < kAmbiguous && limit < kPi) {
+                    delete g;
+                    return s2_fail(S2_ERR_AMBIGUOUS_CUTOFF,
+                                   "a grid point lies within 1e-12 rad of the inclusion threshold; perturb theta_cutoff");
+                }
+                member[wp] = dist <= limit;
+                c += member[wp];
+            }
+            // the disk cuts a latitude circle in one arc centred on the output meridian
+            const int hw = (c - 1) / 2;
+            for (int wp = 0; wp < nlon_in && c > 0 && c < nlon_in; ++wp) {
+                const bool want = std::min(wp, nlon_in - wp) <= hw;
+                if (want != bool(member[wp]) || c % 2 == 0) {
+                    delete g;
+                    return s2_fail(S2_ERR_UNSUPPORTED, "internal: neighborhood is not a centred arc");
+                }
+            }
+            cnt_full[size_t(h) * nlat_in + hp] = c;
+        }
+    }
+
+    auto build_bands = [&](int n_rows, int n_cols, auto at, std::vector<int> &lo, std::vector<int> &n,
+                           std::vector<int> &tab, int &bmax) -> bool {
+        lo.assign(n_rows, 0);
+        n.assign(n_rows, 0);
+        bmax = 0;
+        for (int r = 0; r < n_rows; ++r) {
+            int first = -1, last = -1;
+            for (int c = 0; c < n_cols; ++c)
+                if (at(r, c) > 0) { if (first < 0) first = c; last = c; }
+            if (first < 0) continue;
+            for (int c = first; c <= last; ++c)
+                if (at(r, c) <= 0) return false;   // band must be contiguous
+            lo[r] = first;
+            n[r] = last - first + 1;
+            bmax = std::max(bmax, n[r]);
+        }
+        tab.assign(size_t(n_rows) * std::max(bmax, 1), 0);
+        for (int r = 0; r < n_rows; ++r)
+            for (int b = 0; b < n[r]; ++b) tab[size_t(r) * bmax + b] = at(r, lo[r] + b);
+        return true;
+    };
+    bool ok = build_bands(nlat_out, nlat_in, [&](int h, int hp) { return cnt_full[size_t(h) * nlat_in + hp]; },
+                          g->band_lo, g->band_n, g->cnt, g->band_max);
+    ok = ok && build_bands(nlat_in, nlat_out, [&](int hp, int h) { return cnt_full[size_t(h) * nlat_in + hp]; },
+                           g->tband_lo, g->tband_n, g->tcnt, g->tband_max);
+    if (!ok) { delete g; return s2_fail(S2_ERR_UNSUPPORTED, "internal: latitude band is not contiguous"); }
+    for (int h = 0; h < nlat_out; ++h)
+        if (g->band_n[h] == 0) {
+            delete g;
+            return s2_fail(S2_ERR_EMPTY_NEIGHBORHOOD, "an output point has no input point within theta_cutoff");
+        }
+
+    // canonical CSR: ascending h'*nlon_in + w', w' in [0, nlon_in)
+    g->row_ptr.assign(nlat_out + 1, 0);
+    for (int h = 0; h < nlat_out; ++h) {
+        for (int b = 0; b < g->band_n[h]; ++b) {
+            const int hp = g->band_lo[h] + b, c = g->cnt[size_t(h) * g->band_max + b];
+            if (c == nlon_in) {
+                for (int wp = 0; wp < nlon_in; ++wp) g->col.push_back(hp * nlon_in + wp);
+            } else {
+                const int hw = (c - 1) / 2;
+                for (int wp = 0; wp <= hw; ++wp) g->col.push_back(hp * nlon_in + wp);
+                for (int wp = nlon_in - hw; wp < nlon_in; ++wp) g->col.push_back(hp * nlon_in + wp);
+            }
+        }
+        g->row_ptr[h + 1] = int64_t(g->col.size());
+    }
+
+    // latitudes sorted by work (pairs per point), heaviest first: launch order for load balance
+    auto order_by_work = [](int n_rows, const std::vector<int> &n, const std::vector<int> &tab, int bmax,
+                            std::vector<int> &order) {
+        std::vector<long> work(n_rows, 0);
+        for (int r = 0; r < n_rows; ++r)
+            for (int b = 0; b < n[r]; ++b) work[r] += tab[size_t(r) * bmax + b];
+        order.resize(n_rows);
+        std::iota(order.begin(), order.end(), 0);
+        std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return work[a] > work[b]; });
+    };
+    order_by_work(nlat_out, g->band_n, g->cnt, g->band_max, g->row_order);
+    order_by_work(nlat_in, g->tband_n, g->tcnt, g->tband_max, g->trow_order);
+
+    int rc = upload_tables(g);
+    if (rc != S2_OK) { delete g; return rc; }
+    *out_grid = g;
+    return S2_OK;
+}
+
+extern "C" void s2_grid_destroy(s2_grid_t *g)
+{
+    if (!g) return;
+    if (g->dev_blob) (void)hipFree(g->dev_blob);
+    delete g;
+}
+
+extern "C" int s2_grid_get_weights(const s2_grid_t *g, double *colat_in, double *omega_in)
+{
+    if (!g) return s2_fail(S2_ERR_INVALID_ARG, "grid is NULL");
+    if (colat_in) std::memcpy(colat_in, g->colat_in.data(), sizeof(double) * g->nlat_in);
+    if (omega_in) std::memcpy(omega_in, g->omega_in.data(), sizeof(double) * g->nlat_in);
+    return S2_OK;
+}
+
+extern "C" int64_t s2_grid_num_neighbors(const s2_grid_t *g) { return g ? int64_t(g->col.size()) : 0; }
+
+extern "C" int s2_grid_get_neighbors(const s2_grid_t *g, int64_t *row_ptr, int32_t *col)
+{
+    if (!g) return s2_fail(S2_ERR_INVALID_ARG, "grid is NULL");
+    if (row_ptr) std::memcpy(row_ptr, g->row_ptr.data(), sizeof(int64_t) * g->row_ptr.size());
+    if (col) std::memcpy(col, g->col.data(), sizeof(int32_t) * g->col.size());
+    return S2_OK;
+}

@@ -1,0 +1,58 @@
+// Internal definitions shared by the translation units of libs2attn.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "s2attn.h"
+
+// Device-resident compact form of the indicator 1[h,h',w'] (App. B.3).
+// For output latitude h the disk meets the input latitudes
+// band_lo[h] .. band_lo[h]+band_n[h]-1; on input latitude h' it covers `cnt`
+// consecutive longitude offsets centred on w' = 0 (cnt odd), or the whole
+// circle (cnt == nlon_in).  tband_*/tcnt hold the same numbers indexed by the
+// input latitude (input point -> output latitudes), used by the dk/dv gather.
+struct S2DeviceTables {
+    const float *omega_rel;   // [nlat_in]   omega[h'] / max omega
+    const int *band_lo;       // [nlat_out]
+    const int *band_n;        // [nlat_out]
+    const int *cnt;           // [nlat_out][band_max]
+    const int *tband_lo;      // [nlat_in]
+    const int *tband_n;       // [nlat_in]
+    const int *tcnt;          // [nlat_in][tband_max]
+    const int *row_order;     // [nlat_out]  output latitudes, heaviest first
+    const int *trow_order;    // [nlat_in]   input latitudes, heaviest first
+    int band_max, tband_max;
+    int nlat_in, nlon_in, nlat_out, nlon_out, pscale;
+    float ln_omega_ref;       // ln(max omega): added back to the stored logsumexp
+};
+
+struct s2_grid {
+    int grid_type;
+    int nlat_in, nlon_in, nlat_out, nlon_out, pscale;
+    double theta;
+    std::vector<double> colat_in, omega_in, colat_out;
+    // host copies of the compact tables
+    std::vector<int> band_lo, band_n, cnt, tband_lo, tband_n, tcnt, row_order, trow_order;
+    int band_max = 0, tband_max = 0;
+    // canonical CSR
+    std::vector<int64_t> row_ptr;
+    std::vector<int32_t> col;
+    // device side
+    bool on_device = false;
+    int device = -1;
+    void *dev_blob = nullptr;
+    S2DeviceTables dt{};
+};
+
+void s2_set_error(const std::string &msg);
+int s2_fail(int code, const std::string &msg);
+
+#define S2_HIP_CHECK(expr)                                                                   \
+    do {                                                                                     \
+        hipError_t e_ = (expr);                                                              \
+        if (e_ != hipSuccess)                                                                \
+            return s2_fail(S2_ERR_DEVICE, std::string(#expr) + ": " + hipGetErrorString(e_)); \
+    } while (0)

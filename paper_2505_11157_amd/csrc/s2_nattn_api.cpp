@@ -1,0 +1,58 @@
+// C entry points of the neighborhood attention: argument checks and dispatch.
+#include "s2_nattn_kernels.h"
+
+namespace {
+
+int check_common(const s2_grid_t *g, int batch, int heads, int d_qk, int d_v, int dtype)
+{
+    if (!g) return s2_fail(S2_ERR_INVALID_ARG, "grid is NULL");
+    if (batch < 1 || heads < 1 || d_qk < 1 || d_v < 1) return s2_fail(S2_ERR_INVALID_ARG, "batch, heads, d must be >= 1");
+    if (dtype != S2_F32) return s2_fail(S2_ERR_UNSUPPORTED, "neighborhood attention supports S2_F32 only");
+    if (d_qk > 128 || d_v > 128) return s2_fail(S2_ERR_UNSUPPORTED, "head dimensions above 128 are not supported");
+    if (long(batch) * heads > (1l << 20)) return s2_fail(S2_ERR_INVALID_ARG, "batch*heads too large");
+    if (!g->on_device) return s2_fail(S2_ERR_DEVICE, "grid handle has no device tables (no HIP device at init)");
+    return S2_OK;
+}
+
+}  // namespace
+
+extern "C" size_t s2_nattn_bwd_workspace_bytes(const s2_grid_t *g, int batch, int heads, int d_qk, int d_v, int dtype)
+{
+    (void)d_qk; (void)d_v; (void)dtype;
+    if (!g || batch < 1 || heads < 1) return 0;
+    // D_i = dout_i . out_i, one float per output point and (batch, head)
+    return size_t(batch) * heads * g->nlat_out * g->nlon_out * sizeof(float);
+}
+
+extern "C" int s2_nattn_fwd(const s2_grid_t *g, int batch, int heads, int d_qk, int d_v, int dtype, float scale,
+                            const void *q, const void *k, const void *v, void *out, float *lse, void *hip_stream)
+{
+    int rc = check_common(g, batch, heads, d_qk, d_v, dtype);
+    if (rc) return rc;
+    if (!q || !k || !v || !out || !lse) return s2_fail(S2_ERR_INVALID_ARG, "NULL tensor pointer");
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    s2_nattn_fwd_generic(g->dt, batch * heads, d_qk, d_v, scale, static_cast<const float *>(q),
+                         static_cast<const float *>(k), static_cast<const float *>(v), static_cast<float *>(out), lse, st);
+    S2_HIP_CHECK(hipGetLastError());
+    return S2_OK;
+}
+
+extern "C" int s2_nattn_bwd(const s2_grid_t *g, int batch, int heads, int d_qk, int d_v, int dtype, float scale,
+                            const void *q, const void *k, const void *v, const void *out, const float *lse,
+                            const void *dout, void *dq, void *dk, void *dv, void *workspace, size_t workspace_bytes,
+                            void *hip_stream)
+{
+    int rc = check_common(g, batch, heads, d_qk, d_v, dtype);
+    if (rc) return rc;
+    if (!q || !k || !v || !out || !lse || !dout || !dq || !dk || !dv)
+        return s2_fail(S2_ERR_INVALID_ARG, "NULL tensor pointer");
+    if (!workspace || workspace_bytes < s2_nattn_bwd_workspace_bytes(g, batch, heads, d_qk, d_v, dtype))
+        return s2_fail(S2_ERR_WORKSPACE, "workspace missing or smaller than s2_nattn_bwd_workspace_bytes()");
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    s2_nattn_bwd_generic(g->dt, batch * heads, d_qk, d_v, scale, static_cast<const float *>(q),
+                         static_cast<const float *>(k), static_cast<const float *>(v), static_cast<const float *>(out),
+                         lse, static_cast<const float *>(dout), static_cast<float *>(dq), static_cast<float *>(dk),
+                         static_cast<float *>(dv), static_cast<float *>(workspace), st);
+    S2_HIP_CHECK(hipGetLastError());
+    return S2_OK;
+}

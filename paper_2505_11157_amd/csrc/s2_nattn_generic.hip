@@ -1,0 +1,292 @@
+// Generic float32 kernels for spherical neighborhood attention: any head
+// dimension up to 128, any grid ratio.  One lane owns one output point (forward,
+// dq) or one input point (dk/dv); the geodesic disk is walked as latitude rows
+// times a centred longitude arc (App. B.3), operands come straight from
+// global memory with lanes on consecutive longitudes.
+//
+// These are the shape-agnostic path.  The tuned kernels in s2_nattn_tiled.hip
+// take over for the head dimensions and grids they are specialised for.
+#include "s2_nattn_kernels.h"
+
+namespace {
+
+constexpr int kChunk = 8;   // logits evaluated together before one softmax rescale
+
+__device__ __forceinline__ int wrap(int x, int n)
+{
+    x = x < 0 ? x + n : x;
+    return x >= n ? x - n : x;
+}
+
+// Forward: App. B.1 (second equation) in the index form of App. B.3, with an
+// online softmax in base 2.  q is pre-multiplied by scale*log2(e).  The
+// quadrature weight enters as a factor omega[h']/omega_ref on exp2(s - m)
+// rather than as an additive log term: the running maximum is taken over the
+// bare logits, whose magnitude is a few units, so float32 rounding of the
+// logit stays near 1e-7 instead of growing with |log2 omega| ~ 10..20.
+template <int DMAX>
+__global__ void __launch_bounds__(64)
+nattn_fwd_generic(S2DeviceTables t, int nbh, int d, int e, float qscale,
+                  const float *__restrict__ q, const float *__restrict__ k, const float *__restrict__ v,
+                  float *__restrict__ out, float *__restrict__ lse)
+{
+    const int ntile = (t.nlon_out + 63) / 64;
+    int id = blockIdx.x;
+    const int tile = id % ntile; id /= ntile;
+    const int bh = id % nbh;
+    const int h = t.row_order[id / nbh];
+    const int w = tile * 64 + threadIdx.x;
+    if (w >= t.nlon_out) return;
+
+    const size_t so = size_t(t.nlat_out) * t.nlon_out, si = size_t(t.nlat_in) * t.nlon_in;
+    const size_t io = size_t(h) * t.nlon_out + w;
+    const float *qb = q + size_t(bh) * d * so + io;
+    float qr[DMAX], acc[DMAX];
+#pragma unroll
+    for (int l = 0; l < DMAX; ++l) {
+        qr[l] = l < d ? qb[l * so] * qscale : 0.f;
+        acc[l] = 0.f;
+    }
+    float m = -INFINITY, lsum = 0.f;
+    const int wi0 = w * t.pscale;
+    const int nb = t.band_n[h], hp0 = t.band_lo[h];
+    for (int b = 0; b < nb; ++b) {
+        const int hp = hp0 + b;
+        const int c = t.cnt[h * t.band_max + b];
+        const int lo = (c == t.nlon_in) ? 0 : -((c - 1) >> 1);
+        const float wq = t.omega_rel[hp];
+        const float *kb = k + size_t(bh) * d * si + size_t(hp) * t.nlon_in;
+        const float *vb = v + size_t(bh) * e * si + size_t(hp) * t.nlon_in;
+        for (int t0 = 0; t0 < c; t0 += kChunk) {
+            float s[kChunk];
+            int col[kChunk];
+            float mc = -INFINITY;
+#pragma unroll
+            for (int j = 0; j < kChunk; ++j) {
+                col[j] = wrap(wi0 + lo + t0 + j, t.nlon_in);
+                s[j] = -INFINITY;
+                if (t0 + j < c) {
+                    float dot = 0.f;
+#pragma unroll
+                    for (int l = 0; l < DMAX; ++l)
+                        if (l < d) dot = fmaf(qr[l], kb[l * si + col[j]], dot);
+                    s[j] = dot;
+                }
+                mc = fmaxf(mc, s[j]);
+            }
+            const float m_new = fmaxf(m, mc);
+            const float corr = __builtin_amdgcn_exp2f(m - m_new);
+            m = m_new;
+            lsum *= corr;
+#pragma unroll
+            for (int l = 0; l < DMAX; ++l) acc[l] *= corr;
+#pragma unroll
+            for (int j = 0; j < kChunk; ++j) {
+                if (t0 + j < c) {
+                    const float p = wq * __builtin_amdgcn_exp2f(s[j] - m_new);
+                    lsum += p;
+#pragma unroll
+                    for (int l = 0; l < DMAX; ++l)
+                        if (l < e) acc[l] = fmaf(p, vb[l * si + col[j]], acc[l]);
+                }
+            }
+        }
+    }
+    const float inv = 1.f / lsum;
+    float *ob = out + size_t(bh) * e * so + io;
+#pragma unroll
+    for (int l = 0; l < DMAX; ++l)
+        if (l < e) ob[l * so] = acc[l] * inv;
+    lse[size_t(bh) * so + io] = (m + log2f(lsum)) * 0.6931471805599453f + t.ln_omega_ref;
+}
+
+// Backward, query side (App. B.4): D_i = dout_i.out_i, then
+// dq_i = scale * sum_j p_ij (dout_i.v_j - D_i) k_j over the same lists as the
+// forward pass, p_ij recomputed from the saved logsumexp.  Also stores D_i.
+template <int DMAX>
+__global__ void __launch_bounds__(64)
+nattn_bwd_dq_generic(S2DeviceTables t, int nbh, int d, int e, float scale,
+                     const float *__restrict__ q, const float *__restrict__ k, const float *__restrict__ v,
+                     const float *__restrict__ o, const float *__restrict__ lse, const float *__restrict__ go,
+                     float *__restrict__ dq, float *__restrict__ Dws)
+{
+    const int ntile = (t.nlon_out + 63) / 64;
+    int id = blockIdx.x;
+    const int tile = id % ntile; id /= ntile;
+    const int bh = id % nbh;
+    const int h = t.row_order[id / nbh];
+    const int w = tile * 64 + threadIdx.x;
+    if (w >= t.nlon_out) return;
+
+    const float qscale = scale * 1.4426950408889634f;
+    const size_t so = size_t(t.nlat_out) * t.nlon_out, si = size_t(t.nlat_in) * t.nlon_in;
+    const size_t io = size_t(h) * t.nlon_out + w;
+    float qr[DMAX], gr[DMAX], dqr[DMAX];
+    float Di = 0.f;
+#pragma unroll
+    for (int l = 0; l < DMAX; ++l) {
+        qr[l] = l < d ? q[(size_t(bh) * d + l) * so + io] * qscale : 0.f;
+        gr[l] = l < e ? go[(size_t(bh) * e + l) * so + io] : 0.f;
+        if (l < e) Di = fmaf(gr[l], o[(size_t(bh) * e + l) * so + io], Di);
+        dqr[l] = 0.f;
+    }
+    Dws[size_t(bh) * so + io] = Di;
+    // base-2 logsumexp relative to omega_ref: p_ij = omega_rel_j * exp2(s_ij - lse2)
+    const float lse2 = (lse[size_t(bh) * so + io] - t.ln_omega_ref) * 1.4426950408889634f;
+    const int wi0 = w * t.pscale;
+    const int nb = t.band_n[h], hp0 = t.band_lo[h];
+    for (int b = 0; b < nb; ++b) {
+        const int hp = hp0 + b;
+        const int c = t.cnt[h * t.band_max + b];
+        const int lo = (c == t.nlon_in) ? 0 : -((c - 1) >> 1);
+        const float wq = t.omega_rel[hp];
+        const float *kb = k + size_t(bh) * d * si + size_t(hp) * t.nlon_in;
+        const float *vb = v + size_t(bh) * e * si + size_t(hp) * t.nlon_in;
+        for (int tt = 0; tt < c; ++tt) {
+            const int col = wrap(wi0 + lo + tt, t.nlon_in);
+            float kr[DMAX];
+            float dot = 0.f, gv = -Di;
+#pragma unroll
+            for (int l = 0; l < DMAX; ++l) {
+                kr[l] = l < d ? kb[l * si + col] : 0.f;
+                dot = fmaf(qr[l], kr[l], dot);
+                if (l < e) gv = fmaf(gr[l], vb[l * si + col], gv);
+            }
+            const float dS = wq * __builtin_amdgcn_exp2f(dot - lse2) * gv;
+#pragma unroll
+            for (int l = 0; l < DMAX; ++l) dqr[l] = fmaf(dS, kr[l], dqr[l]);
+        }
+    }
+#pragma unroll
+    for (int l = 0; l < DMAX; ++l)
+        if (l < d) dq[(size_t(bh) * d + l) * so + io] = dqr[l] * scale;
+}
+
+// Backward, key/value side (App. B.4): one lane per INPUT point j gathers
+//   dk_j = scale * sum_i dS_ij q_i,   dv_j = sum_i p_ij dout_i
+// over the output points whose disk contains j.  By the symmetry of the
+// distance these are, on output latitude h, the longitudes w with
+// |w*pscale - w_in| <= half-width(h, h') on the circle.
+template <int DMAX>
+__global__ void __launch_bounds__(64)
+nattn_bwd_dkdv_generic(S2DeviceTables t, int nbh, int d, int e, float scale,
+                       const float *__restrict__ q, const float *__restrict__ k, const float *__restrict__ v,
+                       const float *__restrict__ lse, const float *__restrict__ go, const float *__restrict__ Dws,
+                       float *__restrict__ dk, float *__restrict__ dv)
+{
+    const int ntile = (t.nlon_in + 63) / 64;
+    int id = blockIdx.x;
+    const int tile = id % ntile; id /= ntile;
+    const int bh = id % nbh;
+    const int hp = t.trow_order[id / nbh];
+    const int win = tile * 64 + threadIdx.x;
+    if (win >= t.nlon_in) return;
+
+    const float log2e = 1.4426950408889634f;
+    const float qscale = scale * log2e;
+    const size_t so = size_t(t.nlat_out) * t.nlon_out, si = size_t(t.nlat_in) * t.nlon_in;
+    const size_t ii = size_t(hp) * t.nlon_in + win;
+    float kr[DMAX], vr[DMAX], dkr[DMAX], dvr[DMAX];
+#pragma unroll
+    for (int l = 0; l < DMAX; ++l) {
+        kr[l] = l < d ? k[(size_t(bh) * d + l) * si + ii] * qscale : 0.f;
+        vr[l] = l < e ? v[(size_t(bh) * e + l) * si + ii] : 0.f;
+        dkr[l] = 0.f;
+        dvr[l] = 0.f;
+    }
+    const float wq = t.omega_rel[hp];
+    const float lref2 = t.ln_omega_ref * log2e;
+    const int ps = t.pscale;
+    const int nb = t.tband_n[hp], h0 = t.tband_lo[hp];
+    for (int b = 0; b < nb; ++b) {
+        const int h = h0 + b;
+        const int c = t.tcnt[hp * t.tband_max + b];
+        // x = w*pscale runs over the multiples of pscale in [win-hw, win+hw] (whole circle if c == nlon_in)
+        // (whole circle: start at the lane's own longitude so that the summation order is shift invariant)
+        const int hw = (c == t.nlon_in) ? 0 : (c - 1) >> 1;
+        int x = win - hw + t.nlon_in;             // shifted by nlon_in (a multiple of pscale) to stay positive
+        const int r = x % ps;
+        if (r) x += ps - r;
+        const int x_end = (c == t.nlon_in) ? x + t.nlon_in - ps : win + hw + t.nlon_in;
+        const float *qb = q + size_t(bh) * d * so + size_t(h) * t.nlon_out;
+        const float *gb = go + size_t(bh) * e * so + size_t(h) * t.nlon_out;
+        const float *lb = lse + size_t(bh) * so + size_t(h) * t.nlon_out;
+        const float *Db = Dws + size_t(bh) * so + size_t(h) * t.nlon_out;
+        for (; x <= x_end; x += ps) {
+            int w = x / ps;
+            w = w >= t.nlon_out ? w - t.nlon_out : w;
+            w = w >= t.nlon_out ? w - t.nlon_out : w;
+            float qr[DMAX], gr[DMAX];
+            const float lse2 = fmaf(lb[w], log2e, -lref2);
+            float dot = 0.f, gv = -Db[w];
+#pragma unroll
+            for (int l = 0; l < DMAX; ++l) {
+                qr[l] = l < d ? qb[l * so + w] : 0.f;
+                gr[l] = l < e ? gb[l * so + w] : 0.f;
+                dot = fmaf(qr[l], kr[l], dot);
+                gv = fmaf(gr[l], vr[l], gv);
+            }
+            const float p = wq * __builtin_amdgcn_exp2f(dot - lse2);
+            const float dS = p * gv;
+#pragma unroll
+            for (int l = 0; l < DMAX; ++l) {
+                dkr[l] = fmaf(dS, qr[l], dkr[l]);
+                dvr[l] = fmaf(p, gr[l], dvr[l]);
+            }
+        }
+    }
+#pragma unroll
+    for (int l = 0; l < DMAX; ++l) {
+        if (l < d) dk[(size_t(bh) * d + l) * si + ii] = dkr[l] * scale;
+        if (l < e) dv[(size_t(bh) * e + l) * si + ii] = dvr[l];
+    }
+}
+
+template <int DMAX>
+int launch_fwd(const S2DeviceTables &t, int nbh, int d, int e, float scale, const float *q, const float *k,
+               const float *v, float *out, float *lse, hipStream_t st)
+{
+    const int ntile = (t.nlon_out + 63) / 64;
+    const long nblk = long(ntile) * nbh * t.nlat_out;
+    hipLaunchKernelGGL(nattn_fwd_generic<DMAX>, dim3((unsigned)nblk), dim3(64), 0, st, t, nbh, d, e,
+                       scale * 1.4426950408889634f, q, k, v, out, lse);
+    return 0;
+}
+
+template <int DMAX>
+int launch_bwd(const S2DeviceTables &t, int nbh, int d, int e, float scale, const float *q, const float *k,
+               const float *v, const float *o, const float *lse, const float *go, float *dq, float *dk, float *dv,
+               float *Dws, hipStream_t st)
+{
+    const int nto = (t.nlon_out + 63) / 64, nti = (t.nlon_in + 63) / 64;
+    hipLaunchKernelGGL(nattn_bwd_dq_generic<DMAX>, dim3((unsigned)(long(nto) * nbh * t.nlat_out)), dim3(64), 0, st,
+                       t, nbh, d, e, scale, q, k, v, o, lse, go, dq, Dws);
+    hipLaunchKernelGGL(nattn_bwd_dkdv_generic<DMAX>, dim3((unsigned)(long(nti) * nbh * t.nlat_in)), dim3(64), 0, st,
+                       t, nbh, d, e, scale, q, k, v, lse, go, Dws, dk, dv);
+    return 0;
+}
+
+}  // namespace
+
+int s2_nattn_fwd_generic(const S2DeviceTables &t, int nbh, int d, int e, float scale, const float *q,
+                         const float *k, const float *v, float *out, float *lse, hipStream_t st)
+{
+    const int dm = d > e ? d : e;
+    if (dm <= 8) return launch_fwd<8>(t, nbh, d, e, scale, q, k, v, out, lse, st);
+    if (dm <= 16) return launch_fwd<16>(t, nbh, d, e, scale, q, k, v, out, lse, st);
+    if (dm <= 32) return launch_fwd<32>(t, nbh, d, e, scale, q, k, v, out, lse, st);
+    if (dm <= 64) return launch_fwd<64>(t, nbh, d, e, scale, q, k, v, out, lse, st);
+    return launch_fwd<128>(t, nbh, d, e, scale, q, k, v, out, lse, st);
+}
+
+int s2_nattn_bwd_generic(const S2DeviceTables &t, int nbh, int d, int e, float scale, const float *q,
+                         const float *k, const float *v, const float *o, const float *lse, const float *go,
+                         float *dq, float *dk, float *dv, float *Dws, hipStream_t st)
+{
+    const int dm = d > e ? d : e;
+    if (dm <= 8) return launch_bwd<8>(t, nbh, d, e, scale, q, k, v, o, lse, go, dq, dk, dv, Dws, st);
+    if (dm <= 16) return launch_bwd<16>(t, nbh, d, e, scale, q, k, v, o, lse, go, dq, dk, dv, Dws, st);
+    if (dm <= 32) return launch_bwd<32>(t, nbh, d, e, scale, q, k, v, o, lse, go, dq, dk, dv, Dws, st);
+    if (dm <= 64) return launch_bwd<64>(t, nbh, d, e, scale, q, k, v, o, lse, go, dq, dk, dv, Dws, st);
+    return launch_bwd<128>(t, nbh, d, e, scale, q, k, v, o, lse, go, dq, dk, dv, Dws, st);
+}

@@ -1,0 +1,10 @@
+// Launchers of the neighborhood-attention kernels (internal).
+#pragma once
+#include "s2_internal.h"
+
+// Shape-agnostic float32 path: 1 <= d, e <= 128.
+int s2_nattn_fwd_generic(const S2DeviceTables &t, int nbh, int d, int e, float scale, const float *q,
+                         const float *k, const float *v, float *out, float *lse, hipStream_t st);
+int s2_nattn_bwd_generic(const S2DeviceTables &t, int nbh, int d, int e, float scale, const float *q,
+                         const float *k, const float *v, const float *o, const float *lse, const float *go,
+                         float *dq, float *dk, float *dv, float *Dws, hipStream_t st);
