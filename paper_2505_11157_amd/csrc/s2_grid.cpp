@@ -150,6 +150,7 @@ static int upload_tables(s2_grid *g)
     S2DeviceTables &t = g->dt;
     t.omega_rel = reinterpret_cast<const float *>(base + parts[0].off);
     t.ln_omega_ref = float(std::log(omega_ref));
+    t.omega_ref = float(omega_ref);
     t.band_lo = reinterpret_cast<const int *>(base + parts[1].off);
     t.band_n = reinterpret_cast<const int *>(base + parts[2].off);
     t.cnt = reinterpret_cast<const int *>(base + parts[3].off);

@@ -26,7 +26,8 @@ struct S2DeviceTables {
     const int *trow_order;    // [nlat_in]   input latitudes, heaviest first
     int band_max, tband_max;
     int nlat_in, nlon_in, nlat_out, nlon_out, pscale;
-    float ln_omega_ref;       // ln(max omega): added back to the stored logsumexp
+    float ln_omega_ref;       // ln(max omega): the stored logsumexp is relative to the true omega
+    float omega_ref;          // max omega
 };
 
 struct s2_grid {

@@ -31,8 +31,9 @@ extern "C" int s2_nattn_fwd(const s2_grid_t *g, int batch, int heads, int d_qk, 
     if (rc) return rc;
     if (!q || !k || !v || !out || !lse) return s2_fail(S2_ERR_INVALID_ARG, "NULL tensor pointer");
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    s2_nattn_fwd_generic(g->dt, batch * heads, d_qk, d_v, scale, static_cast<const float *>(q),
-                         static_cast<const float *>(k), static_cast<const float *>(v), static_cast<float *>(out), lse, st);
+    auto *fwd = s2_nattn_fwd_tiled_supported(g->dt, d_qk, d_v) ? s2_nattn_fwd_tiled : s2_nattn_fwd_generic;
+    fwd(g->dt, batch * heads, d_qk, d_v, scale, static_cast<const float *>(q), static_cast<const float *>(k),
+        static_cast<const float *>(v), static_cast<float *>(out), lse, st);
     S2_HIP_CHECK(hipGetLastError());
     return S2_OK;
 }

@@ -97,7 +97,7 @@ nattn_fwd_generic(S2DeviceTables t, int nbh, int d, int e, float qscale,
 #pragma unroll
     for (int l = 0; l < DMAX; ++l)
         if (l < e) ob[l * so] = acc[l] * inv;
-    lse[size_t(bh) * so + io] = (m + log2f(lsum)) * 0.6931471805599453f + t.ln_omega_ref;
+    lse[size_t(bh) * so + io] = (m + log2f(lsum * t.omega_ref)) * 0.6931471805599453f;
 }
 
 // Backward, query side (App. B.4): D_i = dout_i.out_i, then
