@@ -25,6 +25,8 @@ struct S2DeviceTables {
     const int *row_order;     // [nlat_out]  output latitudes, heaviest first
     const int *trow_order;    // [nlat_in]   input latitudes, heaviest first
     int band_max, tband_max;
+    int fwd_cls[4];           // output latitudes (in row_order) whose run list is split 8, 4, 2, 1 ways
+    int bwd_cls[4];           // same for input latitudes (trow_order)
     int nlat_in, nlon_in, nlat_out, nlon_out, pscale;
     float ln_omega_ref;       // ln(max omega): the stored logsumexp is relative to the true omega
     float omega_ref;          // max omega

@@ -8,11 +8,11 @@
 // then accumulates its own half of the output channels, so q and the output
 // accumulator cost D/2 * 4 registers each and two waves fit per SIMD.
 //
-// Data path.  The disk is walked as (input latitude, run of <= 12 longitude
+// Data path.  The disk is walked as (input latitude, run of <= 9 longitude
 // offsets).  For a run, the window of K (then V) columns the 128 outputs touch
 // is staged through LDS four channels per half at a time (double buffered,
-// next group's global loads in flight while the current one is consumed).
-// Each lane then reads ONE contiguous strip of 4*PS-... + NT floats per channel
+// next group's global -> LDS copies in flight while the current one is consumed).
+// Each lane then reads ONE contiguous strip of 3*PS + NT floats per channel
 // with aligned ds_read_b128 and reuses it for all 4 x NT (output, offset)
 // pairs from registers: about three FMAs per LDS float, so the kernel is bound
 // by the vector ALU, not by LDS or cache bandwidth.
@@ -20,6 +20,8 @@
 // Softmax.  Online, base 2, with the quadrature weight as a factor (see the
 // generic kernel); the running reference maximum is only moved when a logit
 // exceeds it by more than 2^8, which removes almost all accumulator rescales.
+#include <cstdlib>
+
 #include "s2_nattn_kernels.h"
 
 namespace {
@@ -27,18 +29,20 @@ namespace {
 constexpr int kSeg = 128;    // outputs per wavefront
 constexpr int kNTMax = 9;    // longest run of offsets handled at once
 constexpr int kCG = 4;       // channels per half staged together
-constexpr int kBlk = 72;     // floats per staged block: 8 channel rows x 8 columns + 8 pad
-
-// Staged window geometry.  A stage holds 2*kCG channel rows of the
-// kSeg*PS + 8 input columns a run can touch, stored as blocks of 8 columns:
-// element (row, col) lives at (col / 8) * kBlk + row * 8 + col % 8.  One
-// global_load_lds_dword fills one block (lane = row * 8 + column), and the
-// 8-float pad rotates the banks from block to block so that the b128 strip
-// reads of a lane pair (rows r and r + 4) and of its neighbours are conflict free.
+// Staged window geometry.  A stage holds 2*kCG channel rows (kCG per half)
+// of the kSeg*PS + 8 input columns a run can touch, row-major with a pitch of
+// kSeg*PS + 8 floats.  The pitch is 8 mod 16, so the two rows a lane pair reads
+// (r and r + kCG) sit 32 banks apart and the b128 strip reads are conflict free.
+// One global_load_lds_dword moves 64 consecutive columns of one row (lane =
+// column, any alignment, wrap handled per lane).  The last 8 columns of the 8
+// rows are one ordinary load (lane = row * 8 + column) written to LDS when the
+// stage is consumed: LDS-direct loads with a partial exec mask proved very slow.
 template <int PS>
 struct Geo {
-    static constexpr int NBLK = (kSeg * PS + 8) / 8;   // 17 (PS = 1) or 33 (PS = 2)
-    static constexpr int TILE = NBLK * kBlk;           // floats per buffer
+    static constexpr int PITCH = kSeg * PS + 8;
+    static constexpr int NFULL = 2 * PS;                      // full 64-column loads per row
+    static constexpr int NLOAD = 2 * kCG * NFULL + 1;         // vector-memory loads per stage
+    static constexpr int TILE = 2 * kCG * PITCH;              // floats per buffer
 };
 
 typedef __attribute__((address_space(1))) const void *gptr_t;
@@ -50,33 +54,51 @@ __device__ __forceinline__ float dpp_swap_pair(float x)
     return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0xB1, 0xf, 0xf, true));
 }
 
-// Byte offsets of the lane's element in each staged block relative to the
-// channel-row base: window columns start at the lane's x0 = (first window
-// column + lane % 8) mod nlon_in and advance by 8 per block around the circle.
+// Byte offsets (within a channel row) of the lane's column in each 64-column
+// piece of the window; x0 = (first window column + lane) mod nlon_in.  The last
+// entry addresses the lane's element of the 8-column tail, channel row included.
 template <int PS>
-__device__ __forceinline__ void stage_offsets(unsigned rowterm, int x0, int nlon_in, unsigned (&voff)[Geo<PS>::NBLK])
+__device__ __forceinline__ void stage_offsets(int x0, int xt, int nlon_in, unsigned trow,
+                                              unsigned (&voff)[Geo<PS>::NFULL + 1])
 {
-    int x = x0;
 #pragma unroll
-    for (int u = 0; u < Geo<PS>::NBLK; ++u) {
-        voff[u] = rowterm + 4u * unsigned(x);
-        x += 8;
+    for (int a = 0; a < Geo<PS>::NFULL; ++a) {
+        int x = x0 + 64 * a;
         x = x >= nlon_in ? x - nlon_in : x;
+        x = x >= nlon_in ? x - nlon_in : x;
+        voff[a] = 4u * unsigned(x);
     }
+    int x = xt + 64 * Geo<PS>::NFULL;
+    x = x >= nlon_in ? x - nlon_in : x;
+    x = x >= nlon_in ? x - nlon_in : x;
+    voff[Geo<PS>::NFULL] = trow + 4u * unsigned(x);
 }
 
 // Start the asynchronous global -> LDS copy of one stage: kCG channel rows per
-// half starting at chan0 (uniform pointer: first channel of the group, input
-// latitude h', column 0).  One instruction per block of 8 columns.
-template <int PS>
-__device__ __forceinline__ void stage_issue(const float *chan0, unsigned (&voff)[Geo<PS>::NBLK], float *buf)
+// half starting at chan0 (uniform pointer: first channel of the group for the
+// even lanes, input latitude h', column 0); the odd lanes' channels lie DH rows on.
+// Returns the lane's tail element (to be stored with stage_tail_store).
+template <int D, int PS>
+__device__ __forceinline__ float stage_issue(const float *chan0, size_t si, unsigned (&voff)[Geo<PS>::NFULL + 1],
+                                             float *buf)
 {
+    using G = Geo<PS>;
 #pragma unroll
-    for (int u = 0; u < Geo<PS>::NBLK; ++u) {
-        asm volatile("" : "+v"(voff[u]));   // keep the offsets as 32-bit registers (no widened copies kept live)
-        __builtin_amdgcn_global_load_lds((gptr_t)(reinterpret_cast<const char *>(chan0) + voff[u]),
-                                         (lptr_t)(buf + u * kBlk), 4, 0, 0);
+    for (int a = 0; a <= G::NFULL; ++a) asm volatile("" : "+v"(voff[a]));   // keep 32-bit offsets, no widened copies
+    // walk the channel rows with a running uniform pointer (kept opaque so that the row bases of
+    // all stages are not computed up front and parked in scalar registers)
+    const char *rb = reinterpret_cast<const char *>(chan0);
+    asm volatile("" : "+s"(rb));
+    const float tail = *reinterpret_cast<const float *>(rb + voff[G::NFULL]);
+    const size_t rs = si * sizeof(float);
+#pragma unroll
+    for (int r = 0; r < 2 * kCG; ++r) {
+#pragma unroll
+        for (int a = 0; a < G::NFULL; ++a)
+            __builtin_amdgcn_global_load_lds((gptr_t)(rb + voff[a]), (lptr_t)(buf + r * G::PITCH + 64 * a), 4, 0, 0);
+        rb += (r == kCG - 1) ? rs * (D / 2 - kCG + 1) : rs;
     }
+    return tail;
 }
 
 template <int N>
@@ -89,12 +111,12 @@ __device__ __forceinline__ void wait_vm()
 }
 
 // Strip of SL4 float4 for the lane's four outputs from channel row `cc` of a stage.
-template <int SL4>
-__device__ __forceinline__ void read_strip(const float *buf, int bE, int bO, int cc, float (&st)[4 * SL4])
+template <int PS, int SL4>
+__device__ __forceinline__ void read_strip(const float *buf, int sbase, int cc, float (&st)[4 * SL4])
 {
 #pragma unroll
     for (int a = 0; a < SL4; ++a) {
-        const float4 x = *reinterpret_cast<const float4 *>(buf + ((a & 1) ? bO : bE) + (a >> 1) * kBlk + cc * 8);
+        const float4 x = *reinterpret_cast<const float4 *>(buf + sbase + cc * Geo<PS>::PITCH + 4 * a);
         st[4 * a] = x.x; st[4 * a + 1] = x.y; st[4 * a + 2] = x.z; st[4 * a + 3] = x.w;
     }
 }
@@ -102,8 +124,8 @@ __device__ __forceinline__ void read_strip(const float *buf, int bE, int bO, int
 // One run of NT offsets on one input latitude: logits, softmax update, P.V.
 template <int D, int PS, int NT>
 __device__ __forceinline__ void run_chunk(float *buf0, float *buf1, const float *__restrict__ kb,
-                                          const float *__restrict__ vb, size_t si, unsigned rowterm, int x0,
-                                          int nlon_in, int bE, int bO, float wq, const float (&q)[4][D / 2],
+                                          const float *__restrict__ vb, size_t si, int x0, int xt, unsigned trow,
+                                          int taddr, int nlon_in, int sbase, float wq, const float (&q)[4][D / 2],
                                           float (&acc)[4][D / 2], float (&mref)[4], float (&lsum)[4])
 {
     using G = Geo<PS>;
@@ -115,20 +137,22 @@ __device__ __forceinline__ void run_chunk(float *buf0, float *buf1, const float 
     for (int r = 0; r < 4; ++r)
 #pragma unroll
         for (int tt = 0; tt < NT; ++tt) s[r][tt] = 0.f;
-    unsigned voff[G::NBLK];
-    stage_offsets<PS>(rowterm, x0, nlon_in, voff);
+    unsigned voff[G::NFULL + 1];
+    stage_offsets<PS>(x0, xt, nlon_in, trow, voff);
 
-    stage_issue<PS>(kb, voff, buf0);
+    float tail = stage_issue<D, PS>(kb, si, voff, buf0), tail_next = 0.f;
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
         float *cur = (g & 1) ? buf1 : buf0, *nxt = (g & 1) ? buf0 : buf1;
-        if (g + 1 < NG) stage_issue<PS>(kb + size_t(g + 1) * kCG * si, voff, nxt);
-        else stage_issue<PS>(vb, voff, nxt);
-        wait_vm<G::NBLK>();
+        if (g + 1 < NG) tail_next = stage_issue<D, PS>(kb + size_t(g + 1) * kCG * si, si, voff, nxt);
+        else tail_next = stage_issue<D, PS>(vb, si, voff, nxt);
+        wait_vm<G::NLOAD>();
+        cur[taddr] = tail;
+        tail = tail_next;
 #pragma unroll
         for (int cc = 0; cc < kCG; ++cc) {
             float st[4 * SL4];
-            read_strip<SL4>(cur, bE, bO, cc, st);
+            read_strip<PS, SL4>(cur, sbase, cc, st);
 #pragma unroll
             for (int tt = 0; tt < NT; ++tt)
 #pragma unroll
@@ -170,15 +194,17 @@ __device__ __forceinline__ void run_chunk(float *buf0, float *buf1, const float 
     for (int g = 0; g < NG; ++g) {
         float *cur = (g & 1) ? buf1 : buf0, *nxt = (g & 1) ? buf0 : buf1;
         if (g + 1 < NG) {
-            stage_issue<PS>(vb + size_t(g + 1) * kCG * si, voff, nxt);
-            wait_vm<G::NBLK>();
+            tail_next = stage_issue<D, PS>(vb + size_t(g + 1) * kCG * si, si, voff, nxt);
+            wait_vm<G::NLOAD>();
         } else {
             wait_vm<0>();
         }
+        cur[taddr] = tail;
+        tail = tail_next;
 #pragma unroll
         for (int cc = 0; cc < kCG; ++cc) {
             float st[4 * SL4];
-            read_strip<SL4>(cur, bE, bO, cc, st);
+            read_strip<PS, SL4>(cur, sbase, cc, st);
 #pragma unroll
             for (int tt = 0; tt < NT; ++tt)
 #pragma unroll
@@ -188,34 +214,75 @@ __device__ __forceinline__ void run_chunk(float *buf0, float *buf1, const float 
     }
 }
 
-template <int D, int PS>
-__global__ void __launch_bounds__(64, 2)
-nattn_fwd_tiled(S2DeviceTables t, int nbh, float qscale, const float *__restrict__ q, const float *__restrict__ k,
-                const float *__restrict__ v, float *__restrict__ out, float *__restrict__ lse)
+constexpr int kWaves = 8;          // wavefronts per workgroup
+constexpr int kState = 4 * 16 + 8; // floats of softmax state per lane: acc[4][16], mref[4], lsum[4]
+
+// Workgroup = 8 wavefronts working on one output latitude h and one segment of
+// 128 longitudes.  Output latitudes are sorted by work and grouped in four
+// classes: a latitude of class P in {8, 4, 2, 1} has its list of runs split
+// over P wavefronts (their partial softmax states are merged through LDS at
+// the end), and the workgroup covers 8 / P different (batch, head) slices.
+// Near the poles of an equiangular grid a disk holds over twenty times more
+// points than at the equator; without the split those rows set the makespan.
+template <int D, int PS, int WAVES>
+__global__ void __launch_bounds__(64 * WAVES, 2)
+nattn_fwd_tiled(S2DeviceTables t, int nbh, int first_row, float qscale, const float *__restrict__ q,
+                const float *__restrict__ k, const float *__restrict__ v, float *__restrict__ out,
+                float *__restrict__ lse)
 {
     using G = Geo<PS>;
     constexpr int DH = D / 2;
-    __shared__ __attribute__((aligned(16))) float buf0[G::TILE];
-    __shared__ __attribute__((aligned(16))) float buf1[G::TILE];
+    static_assert(DH == 16, "state layout assumes 16 channels per lane");
+    extern __shared__ __attribute__((aligned(16))) float smem[];
+    const int wave = WAVES == 1 ? 0 : __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // uniform by construction
+    const int lane = threadIdx.x & 63;
+    float *buf0 = smem + wave * 2 * G::TILE, *buf1 = buf0 + G::TILE;
 
     const int nseg = (t.nlon_out + kSeg - 1) / kSeg;
-    int id = blockIdx.x;
-    const int seg = id % nseg; id /= nseg;
-    const int bh = id % nbh;
-    const int h = t.row_order[id / nbh];
-    const int lane = threadIdx.x, p = lane >> 1, half = lane & 1;
+    int P, seg, h, part, bh;
+    if constexpr (WAVES == 1) {
+        // one wavefront per workgroup, no split: block -> (latitude by work, slice, segment)
+        int id = blockIdx.x;
+        seg = id % nseg; id /= nseg;
+        bh = id % nbh;
+        h = t.row_order[first_row + id / nbh];
+        P = 1; part = 0;
+    } else {
+        // block -> (group of 8 (batch, head) slices, class, output latitude, segment, slices of the group).
+        // Slices are the outer loop: the K/V of 8 slices (tens of MB) stay resident in the 256 MB
+        // last-level cache while all their latitudes are processed; heavy latitudes come first in a group.
+        const int per_group = nseg * (8 * t.fwd_cls[0] + 4 * t.fwd_cls[1] + 2 * t.fwd_cls[2] + (first_row ? 0 : t.fwd_cls[3]));
+        const int grp8 = blockIdx.x / per_group;
+        int id = blockIdx.x - grp8 * per_group, rows_before = 0;
+        P = WAVES;
+#pragma unroll
+        for (int cls = 0; cls < 3; ++cls) {
+            const int Pc = WAVES >> cls;
+            const int nblk_c = t.fwd_cls[cls] * nseg * Pc;
+            if (P == Pc && id >= nblk_c) { id -= nblk_c; rows_before += t.fwd_cls[cls]; P = Pc >> 1; }
+        }
+        // within a class: P blocks per (latitude, segment), each covering 8 / P slices
+        const int tpb = WAVES / P;
+        const int sub = id % P; id /= P;
+        seg = id % nseg;
+        h = t.row_order[rows_before + id / nseg];
+        part = wave & (P - 1);
+        bh = grp8 * WAVES + sub * tpb + wave / P;
+    }
+    const bool wave_active = bh < nbh;
+
+    const int p = lane >> 1, half = lane & 1;
     const int w0 = seg * kSeg + 4 * p;
-    const bool active = w0 < t.nlon_out;       // nlon_out is a multiple of 4: all four outputs or none
+    const bool active = wave_active && w0 < t.nlon_out;   // nlon_out is a multiple of 4: all four outputs or none
 
     const size_t so = size_t(t.nlat_out) * t.nlon_out, si = size_t(t.nlat_in) * t.nlon_in;
     const size_t io = size_t(h) * t.nlon_out + w0;
-    // staging: lane = (channel row, column within a block of 8); rows 0..3 are the even lanes' channels
-    const int srow = lane >> 3;
-    const unsigned rowterm = unsigned((srow < kCG ? srow : srow - kCG + DH) * si * sizeof(float));
-    // strip bases (floats) for float4 #a: even a -> bE + (a/2)*kBlk, odd a -> bO + (a/2)*kBlk
-    const int c0 = 4 * p * PS;
-    const int bE = (c0 >> 3) * kBlk + (c0 & 7) + half * (kCG * 8);
-    const int bO = ((c0 + 4) >> 3) * kBlk + ((c0 + 4) & 7) + half * (kCG * 8);
+    // strip base (floats) in a staged buffer: the lane's channel rows start at half*kCG, its columns at 4*p*PS
+    const int sbase = half * kCG * G::PITCH + 4 * p * PS;
+    // window tail: lane = (channel row, one of the last 8 columns)
+    const int trl = lane >> 3;
+    const unsigned trow = unsigned((trl < kCG ? trl : trl - kCG + DH) * si * sizeof(float));
+    const int taddr = trl * G::PITCH + kSeg * PS + (lane & 7);
     float qr[4][DH], acc[4][DH], mref[4], lsum[4];
 #pragma unroll
     for (int c = 0; c < DH; ++c) {
@@ -228,31 +295,77 @@ nattn_fwd_tiled(S2DeviceTables t, int nbh, float qscale, const float *__restrict
     for (int r = 0; r < 4; ++r) { mref[r] = -INFINITY; lsum[r] = 0.f; }
 
     const int nb = t.band_n[h], hp0 = t.band_lo[h];
-    for (int b = 0; b < nb; ++b) {
-        const int hp = hp0 + b;
-        const int c = t.cnt[h * t.band_max + b];
-        const int lo = (c == t.nlon_in) ? 0 : -((c - 1) >> 1);
-        const float wq = t.omega_rel[hp];
-        const float *kb = k + size_t(bh) * D * si + size_t(hp) * t.nlon_in;
-        const float *vb = v + size_t(bh) * D * si + size_t(hp) * t.nlon_in;
-        const int nchunk = (c + kNTMax - 1) / kNTMax;
-        const int base = c / nchunk, rem = c - base * nchunk;
-        int t0 = 0;
-        for (int ci = 0; ci < nchunk; ++ci) {
-            const int nt = base + (ci < rem ? 1 : 0);
-            int x0 = seg * kSeg * PS + lo + t0 + t.nlon_in + (lane & 7);
-            x0 = x0 >= t.nlon_in ? x0 - t.nlon_in : x0;
-            x0 = x0 >= t.nlon_in ? x0 - t.nlon_in : x0;
-#define S2_RUN(N) case N: run_chunk<D, PS, N>(buf0, buf1, kb, vb, si, rowterm, x0, t.nlon_in, bE, bO, wq, qr, acc, mref, lsum); break;
-            switch (nt) {
-                S2_RUN(1) S2_RUN(2) S2_RUN(3) S2_RUN(4) S2_RUN(5) S2_RUN(6)
-                S2_RUN(7) S2_RUN(8) S2_RUN(9)
-            }
+    // this wavefront's share of the runs of latitude h
+    int nrun = 0;
+    for (int b = 0; b < nb; ++b) nrun += (t.cnt[h * t.band_max + b] + kNTMax - 1) / kNTMax;
+    const int run_lo = part * nrun / P, run_hi = (part + 1) * nrun / P;
+    int run = 0;
+    if (wave_active) {
+        for (int b = 0; b < nb; ++b) {
+            const int hp = hp0 + b;
+            const int c = t.cnt[h * t.band_max + b];
+            const int nchunk = (c + kNTMax - 1) / kNTMax;
+            if (run + nchunk <= run_lo || run >= run_hi) { run += nchunk; continue; }
+            const int lo = (c == t.nlon_in) ? 0 : -((c - 1) >> 1);
+            const float wq = t.omega_rel[hp];
+            const float *kb = k + size_t(bh) * D * si + size_t(hp) * t.nlon_in;
+            const float *vb = v + size_t(bh) * D * si + size_t(hp) * t.nlon_in;
+            const int base = c / nchunk, rem = c - base * nchunk;
+            int t0 = 0;
+            for (int ci = 0; ci < nchunk; ++ci, ++run) {
+                const int nt = base + (ci < rem ? 1 : 0);
+                if (run >= run_lo && run < run_hi) {
+                    int xw = seg * kSeg * PS + lo + t0 + t.nlon_in;      // first window column
+                    xw = xw >= t.nlon_in ? xw - t.nlon_in : xw;
+                    xw = xw >= t.nlon_in ? xw - t.nlon_in : xw;
+                    int x0 = xw + lane, xt = xw + (lane & 7);
+                    x0 = x0 >= t.nlon_in ? x0 - t.nlon_in : x0;
+                    xt = xt >= t.nlon_in ? xt - t.nlon_in : xt;
+#define S2_RUN(N) case N: run_chunk<D, PS, N>(buf0, buf1, kb, vb, si, x0, xt, trow, taddr, t.nlon_in, sbase, wq, qr, acc, mref, lsum); break;
+                    switch (nt) {
+                        S2_RUN(1) S2_RUN(2) S2_RUN(3) S2_RUN(4) S2_RUN(5) S2_RUN(6)
+                        S2_RUN(7) S2_RUN(8) S2_RUN(9)
+                    }
 #undef S2_RUN
-            t0 += nt;
+                }
+                t0 += nt;
+            }
         }
     }
-    if (!active) return;
+
+    // merge the P partial states pairwise through LDS (the staging buffers are free now)
+    if (P > 1) {
+        __syncthreads();
+        for (int s = 1; s < P; s <<= 1) {
+            float *slot = smem + (wave / (2 * s)) * (kState * 64) + lane;
+            if ((part & (2 * s - 1)) == s) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+#pragma unroll
+                    for (int c = 0; c < DH; ++c) slot[(r * DH + c) * 64] = acc[r][c];
+                    slot[(64 + r) * 64] = mref[r];
+                    slot[(68 + r) * 64] = lsum[r];
+                }
+            }
+            __syncthreads();
+            if ((part & (2 * s - 1)) == 0) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float mo = slot[(64 + r) * 64], lo2 = slot[(68 + r) * 64];
+                    const float M = fmaxf(mref[r], mo);
+                    // a part that saw no run has m = -inf, l = 0: its factor must be 0, never NaN
+                    const float fa = mref[r] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(mref[r] - M);
+                    const float fb = mo == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(mo - M);
+                    mref[r] = M;
+                    lsum[r] = lsum[r] * fa + lo2 * fb;
+#pragma unroll
+                    for (int c = 0; c < DH; ++c) acc[r][c] = acc[r][c] * fa + slot[(r * DH + c) * 64] * fb;
+                }
+            }
+            __syncthreads();
+        }
+    }
+    if (!active || part != 0) return;
     float inv[4];
 #pragma unroll
     for (int r = 0; r < 4; ++r) inv[r] = 1.f / lsum[r];
@@ -268,6 +381,42 @@ nattn_fwd_tiled(S2DeviceTables t, int nbh, float qscale, const float *__restrict
     }
 }
 
+template <int D, int PS>
+int launch_fwd_tiled(const S2DeviceTables &t, int nbh, float qscale, const float *q, const float *k, const float *v,
+                     float *out, float *lse, hipStream_t st)
+{
+    const int nseg = (t.nlon_out + kSeg - 1) / kSeg;
+    const int nsplit = t.fwd_cls[0] + t.fwd_cls[1] + t.fwd_cls[2];   // latitudes split over several wavefronts
+    const char *env = std::getenv("S2_FWD_MODE");                    // experiment knob
+    const int mode = env ? std::atoi(env) : 0;
+    // heavy latitudes: 8-wave workgroups with an in-LDS merge
+    if (mode != 1 && (nsplit > 0 || mode == 2)) {
+        const int first_row = mode == 2 ? 0 : 1;   // mode 2: every latitude through the 8-wave kernel
+        const long nblk = long((nbh + kWaves - 1) / kWaves) * nseg *
+                          (8 * t.fwd_cls[0] + 4 * t.fwd_cls[1] + 2 * t.fwd_cls[2] + (first_row ? 0 : t.fwd_cls[3]));
+        constexpr size_t stage_fl = size_t(kWaves) * 2 * Geo<PS>::TILE, merge_fl = size_t(kWaves / 2) * kState * 64;
+        const size_t lds = (stage_fl > merge_fl ? stage_fl : merge_fl) * sizeof(float);
+        auto kern = nattn_fwd_tiled<D, PS, kWaves>;
+        static bool configured = false;   // raise the dynamic LDS limit once (above 64 KiB needs the attribute)
+        if (!configured) {
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    int(lds)) != hipSuccess)
+                return -1;
+            configured = true;
+        }
+        hipLaunchKernelGGL(kern, dim3((unsigned)nblk), dim3(64 * kWaves), lds, st, t, nbh, first_row, qscale, q, k, v,
+                           out, lse);
+        if (mode == 2) return 0;
+    }
+    // the rest: one wavefront per workgroup
+    const int first_row = mode == 1 ? 0 : nsplit;
+    const long nrows = t.nlat_out - first_row;
+    if (nrows > 0)
+        hipLaunchKernelGGL((nattn_fwd_tiled<D, PS, 1>), dim3((unsigned)(nrows * nbh * nseg)), dim3(64),
+                           2 * Geo<PS>::TILE * sizeof(float), st, t, nbh, first_row, qscale, q, k, v, out, lse);
+    return 0;
+}
+
 }  // namespace
 
 bool s2_nattn_fwd_tiled_supported(const S2DeviceTables &t, int d, int e)
@@ -280,12 +429,7 @@ int s2_nattn_fwd_tiled(const S2DeviceTables &t, int nbh, int d, int e, float sca
                        const float *v, float *out, float *lse, hipStream_t st)
 {
     (void)d; (void)e;
-    const int nseg = (t.nlon_out + kSeg - 1) / kSeg;
-    const unsigned nblk = unsigned(long(nseg) * nbh * t.nlat_out);
     const float qscale = scale * 1.4426950408889634f;
-    if (t.pscale == 1)
-        hipLaunchKernelGGL((nattn_fwd_tiled<32, 1>), dim3(nblk), dim3(64), 0, st, t, nbh, qscale, q, k, v, out, lse);
-    else
-        hipLaunchKernelGGL((nattn_fwd_tiled<32, 2>), dim3(nblk), dim3(64), 0, st, t, nbh, qscale, q, k, v, out, lse);
-    return 0;
+    if (t.pscale == 1) return launch_fwd_tiled<32, 1>(t, nbh, qscale, q, k, v, out, lse, st);
+    return launch_fwd_tiled<32, 2>(t, nbh, qscale, q, k, v, out, lse, st);
 }
