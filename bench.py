@@ -78,7 +78,8 @@ def main():
         out = torch.empty_like(q)
         lse = torch.empty((B, H, q.shape[2]), dtype=torch.float32, device=dev)
         ws = torch.empty(max(S.s2_attn_global_bwd_workspace_bytes(g, B, H, d), 1), dtype=torch.uint8, device=dev)
-        fwd = lambda: S.s2_attn_global_fwd(g, q, k, v, scale, out=out, lse=lse)
+        wsf = torch.empty(max(S.s2_attn_global_fwd_workspace_bytes(g, B, H, d), 1), dtype=torch.uint8, device=dev)
+        fwd = lambda: S.s2_attn_global_fwd(g, q, k, v, scale, out=out, lse=lse, workspace=wsf)
         bwd = lambda: S.s2_attn_global_bwd(g, q, k, v, out, lse, dout, scale, dq=dq, dk=dk, dv=dv, workspace=ws)
     else:
         out = torch.empty((B, H, v.shape[2], c["nlat_out"], c["nlon_out"]), dtype=tdt, device=dev)

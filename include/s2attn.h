@@ -124,7 +124,9 @@ int s2_nattn_bwd(const s2_grid_t *g, int batch, int heads, int d_qk, int d_v, in
                  const void *dout, void *dq, void *dk, void *dv,
                  void *workspace, size_t workspace_bytes, void *hip_stream);
 
-/* Bytes of device scratch s2_attn_global_bwd needs. */
+/* Bytes of device scratch s2_attn_global_fwd / s2_attn_global_bwd need (token-transposed
+ * copies of the operands that are contracted over tokens, and D_i = dout_i.out_i). */
+size_t s2_attn_global_fwd_workspace_bytes(const s2_grid_t *g, int batch, int heads, int d, int dtype);
 size_t s2_attn_global_bwd_workspace_bytes(const s2_grid_t *g, int batch, int heads, int d, int dtype);
 
 /*
@@ -135,11 +137,13 @@ size_t s2_attn_global_bwd_workspace_bytes(const s2_grid_t *g, int batch, int hea
  * N = nlat*nlon.  Layouts (contiguous, token-major): q, k, v, out
  * [batch][heads][N][d]; lse float32 [batch][heads][N].
  * dtype: S2_BF16 (bf16 tensors, MFMA with float32 accumulation, float32
- * softmax and lse).  d in {64, 128}... see S2_ERR_UNSUPPORTED.
+ * softmax and lse); d = 64.  Other dtypes or head dimensions: S2_ERR_UNSUPPORTED.
+ * workspace: device scratch of at least s2_attn_global_fwd_workspace_bytes(...)
+ * bytes (S2_ERR_WORKSPACE if smaller); its contents are undefined afterwards.
  */
 int s2_attn_global_fwd(const s2_grid_t *g, int batch, int heads, int d, int dtype, float scale,
                        const void *q, const void *k, const void *v, void *out, float *lse,
-                       void *hip_stream);
+                       void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
  * Global attention backward: the formulas of s2_nattn_bwd with every token a

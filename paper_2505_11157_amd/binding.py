@@ -61,9 +61,12 @@ def lib():
         L.s2_nattn_bwd.argtypes = [_vp, _i, _i, _i, _i, _i, ctypes.c_float, _vp, _vp, _vp, _vp, _vp, _vp,
                                    _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
         L.s2_nattn_bwd.restype = _i
+        L.s2_attn_global_fwd_workspace_bytes.argtypes = [_vp, _i, _i, _i, _i]
+        L.s2_attn_global_fwd_workspace_bytes.restype = ctypes.c_size_t
         L.s2_attn_global_bwd_workspace_bytes.argtypes = [_vp, _i, _i, _i, _i]
         L.s2_attn_global_bwd_workspace_bytes.restype = ctypes.c_size_t
-        L.s2_attn_global_fwd.argtypes = [_vp, _i, _i, _i, _i, ctypes.c_float, _vp, _vp, _vp, _vp, _vp, _vp]
+        L.s2_attn_global_fwd.argtypes = [_vp, _i, _i, _i, _i, ctypes.c_float, _vp, _vp, _vp, _vp, _vp, _vp,
+                                         ctypes.c_size_t, _vp]
         L.s2_attn_global_fwd.restype = _i
         L.s2_attn_global_bwd.argtypes = [_vp, _i, _i, _i, _i, ctypes.c_float, _vp, _vp, _vp, _vp, _vp, _vp,
                                          _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
@@ -186,11 +189,15 @@ def s2_nattn_bwd(g, q, k, v, out, lse, dout, scale, dq=None, dk=None, dv=None, w
     return dq, dk, dv
 
 
+def s2_attn_global_fwd_workspace_bytes(g, batch, heads, d, dtype=S2_BF16):
+    return int(lib().s2_attn_global_fwd_workspace_bytes(g.handle, batch, heads, d, dtype))
+
+
 def s2_attn_global_bwd_workspace_bytes(g, batch, heads, d, dtype=S2_BF16):
     return int(lib().s2_attn_global_bwd_workspace_bytes(g.handle, batch, heads, d, dtype))
 
 
-def s2_attn_global_fwd(g, q, k, v, scale, out=None, lse=None):
+def s2_attn_global_fwd(g, q, k, v, scale, out=None, lse=None, workspace=None):
     """Token-major q, k, v [B,H,N,d] -> out [B,H,N,d], lse float32 [B,H,N]."""
     import torch
     _dev(q, k, v)
@@ -199,9 +206,13 @@ def s2_attn_global_fwd(g, q, k, v, scale, out=None, lse=None):
         raise ValueError("tensor shapes do not match the grid handle")
     out = torch.empty_like(q) if out is None else out
     lse = torch.empty((B, H, N), dtype=torch.float32, device=q.device) if lse is None else lse
-    _dev(out, lse)
+    if workspace is None:
+        need = s2_attn_global_fwd_workspace_bytes(g, B, H, d, _dtype_code(q))
+        workspace = torch.empty(max(need, 1), dtype=torch.uint8, device=q.device)
+    _dev(out, lse, workspace)
     _check(lib().s2_attn_global_fwd(g.handle, B, H, d, _dtype_code(q), float(scale), q.data_ptr(), k.data_ptr(),
-                                    v.data_ptr(), out.data_ptr(), lse.data_ptr(), _stream()))
+                                    v.data_ptr(), out.data_ptr(), lse.data_ptr(), workspace.data_ptr(),
+                                    workspace.numel(), _stream()))
     return out, lse
 
 

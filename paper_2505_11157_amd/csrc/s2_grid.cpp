@@ -122,6 +122,10 @@ static int upload_tables(s2_grid *g)
     std::vector<float> l2w(g->nlat_in);
     const double omega_ref = *std::max_element(g->omega_in.begin(), g->omega_in.end());
     for (int h = 0; h < g->nlat_in; ++h) l2w[h] = float(g->omega_in[h] / omega_ref);
+    const int ntok = g->nlat_in * g->nlon_in;
+    g->npad_tok = (ntok + 31) / 32 * 32;
+    std::vector<float> bias(g->npad_tok, -INFINITY);
+    for (int j = 0; j < ntok; ++j) bias[j] = float(std::log2(g->omega_in[j / g->nlon_in]));
     // one blob: floats first, then the int tables, each 256-byte aligned
     struct Part { const void *src; size_t bytes; size_t off; };
     std::vector<Part> parts = {
@@ -134,6 +138,7 @@ static int upload_tables(s2_grid *g)
         {g->tcnt.data(), g->tcnt.size() * sizeof(int), 0},
         {g->row_order.data(), g->row_order.size() * sizeof(int), 0},
         {g->trow_order.data(), g->trow_order.size() * sizeof(int), 0},
+        {bias.data(), bias.size() * sizeof(float), 0},
     };
     size_t total = 0;
     for (auto &p : parts) {
@@ -160,6 +165,7 @@ static int upload_tables(s2_grid *g)
     t.tcnt = reinterpret_cast<const int *>(base + parts[6].off);
     t.row_order = reinterpret_cast<const int *>(base + parts[7].off);
     t.trow_order = reinterpret_cast<const int *>(base + parts[8].off);
+    g->dev_bias_tok = reinterpret_cast<const float *>(base + parts[9].off);
     t.band_max = g->band_max;
     t.tband_max = g->tband_max;
     t.nlat_in = g->nlat_in; t.nlon_in = g->nlon_in;

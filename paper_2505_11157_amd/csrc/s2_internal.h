@@ -47,6 +47,9 @@ struct s2_grid {
     bool on_device = false;
     int device = -1;
     void *dev_blob = nullptr;
+    // global attention: log2(omega) per input token, -inf on the padding up to npad_tok (multiple of 32)
+    int npad_tok = 0;
+    const float *dev_bias_tok = nullptr;
     S2DeviceTables dt{};
 };
 

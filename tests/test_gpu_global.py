@@ -1,0 +1,107 @@
+"""GPU parity of the global quadrature-weighted attention (bf16 MFMA path) against the float64 oracle.
+
+Inputs are rounded to bf16 before either side sees them.  Tolerance for bf16 tensors:
+|x - ref| <= 2e-2 |ref| + 2e-2 rms(ref) elementwise (a pure relative bound is meaningless at zero
+crossings); the float32 logsumexp is held to 1e-3 absolute.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+import paper_2505_11157_amd as S
+from paper_2505_11157_amd.workloads import CONFIGS, make_inputs, round_to_bf16
+
+pytestmark = pytest.mark.gpu
+
+
+def _close(x, ref, what, rel=2e-2):
+    err = np.abs(x - ref)
+    tol = rel * np.abs(ref) + rel * np.sqrt((ref ** 2).mean())
+    assert np.isfinite(x).all(), what
+    assert (err <= tol).all(), "%s: max err %.3e, max excess %.3e" % (what, err.max(), (err - tol).max())
+
+
+def run_global(grid_type, nlat, nlon, B, H, arrs, slices, scale=None, rel=2e-2):
+    d = arrs[0].shape[-1]
+    scale = 1 / math.sqrt(d) if scale is None else scale
+    g = S.s2_grid_init(grid_type, nlat, nlon, nlat, nlon, math.pi)
+    dev = torch.device("cuda:0")
+    fold = lambda a: torch.from_numpy(a).to(dev).reshape((B, H) + a.shape[1:]).to(torch.bfloat16).contiguous()
+    q, k, v, dout = (fold(a) for a in arrs)
+    out, lse = S.s2_attn_global_fwd(g, q, k, v, scale)
+    dq, dk, dv = S.s2_attn_global_bwd(g, q, k, v, out, lse, dout, scale)
+    torch.cuda.synchronize()
+    unfold = lambda t: t.float().reshape((B * H,) + t.shape[2:]).cpu().numpy().astype(np.float64)
+    out, lse, dq, dk, dv = (unfold(t) for t in (out, lse, dq, dk, dv))
+    for s in slices:
+        sl = slice(s, s + 1)
+        a64 = [a[sl].astype(np.float64) for a in arrs]
+        r_out, r_lse = O.global_fwd(grid_type, nlat, nlon, a64[0], a64[1], a64[2], scale)
+        r_dq, r_dk, r_dv = O.global_bwd(grid_type, nlat, nlon, *a64, scale)
+        assert np.abs(lse[sl] - r_lse).max() < 1e-3, "lse[%d]: %.3e" % (s, np.abs(lse[sl] - r_lse).max())
+        _close(out[sl], r_out, "out[%d]" % s, rel)
+        _close(dq[sl], r_dq, "dq[%d]" % s, rel)
+        _close(dk[sl], r_dk, "dk[%d]" % s, rel)
+        _close(dv[sl], r_dv, "dv[%d]" % s, rel)
+    return out, lse, dq, dk, dv
+
+
+@pytest.mark.parametrize("gt,nlat,nlon,B,H", [(0, 9, 16, 1, 2), (1, 8, 12, 2, 1), (0, 5, 7, 1, 1), (0, 17, 32, 1, 3),
+                                             (1, 2, 1, 1, 1), (0, 13, 20, 1, 1)])
+def test_global_small_grids(gt, nlat, nlon, B, H):
+    rng = np.random.default_rng(nlat * 100 + nlon)
+    N = nlat * nlon
+    arrs = [round_to_bf16(rng.standard_normal((B * H, N, 64)).astype(np.float32)) for _ in range(4)]
+    # with a handful of tokens the bf16 rounding of each probability is not averaged over a long sum:
+    # the two-token grid gets twice the bound
+    run_global(gt, nlat, nlon, B, H, arrs, range(B * H), rel=4e-2 if N < 8 else 2e-2)
+
+
+def test_global_config5_slice():
+    c, arrs = make_inputs(5)
+    nbh = c["batch"] * c["heads"]
+    r1 = run_global(c["grid_type"], c["nlat_in"], c["nlon_in"], c["batch"], c["heads"], arrs, [nbh - 1])
+    r2 = run_global(c["grid_type"], c["nlat_in"], c["nlon_in"], c["batch"], c["heads"], arrs, [])
+    for a, b in zip(r1, r2):
+        assert np.array_equal(a, b)      # no atomics: bit-reproducible
+
+
+def test_global_matches_neighborhood_with_full_disk():
+    # theta = pi: the float32 neighborhood path and the bf16 global path compute the same quantity
+    nlat, nlon, d = 9, 16, 64
+    rng = np.random.default_rng(3)
+    a = [round_to_bf16(rng.standard_normal((1, nlat * nlon, d)).astype(np.float32)) for _ in range(4)]
+    out, lse, dq, dk, dv = run_global(0, nlat, nlon, 1, 1, a, [])
+    g = S.s2_grid_init(0, nlat, nlon, nlat, nlon, math.pi)
+    dev = torch.device("cuda:0")
+    cf = lambda x: torch.from_numpy(x.reshape(1, 1, nlat, nlon, d).transpose(0, 1, 4, 2, 3).copy()).to(dev)
+    q, k, v, go = (cf(x) for x in a)
+    o2, l2 = S.s2_nattn_fwd(g, q, k, v, 1 / math.sqrt(d))
+    o2 = o2.cpu().numpy().reshape(d, -1).T
+    assert np.abs(lse.reshape(-1) - l2.cpu().numpy().reshape(-1)).max() < 1e-3
+    _close(out.reshape(-1, d), o2.astype(np.float64), "out vs neighborhood(theta=pi)")
+
+
+def test_global_errors():
+    g = S.s2_grid_init(0, 9, 16, 9, 16, math.pi)
+    dev = torch.device("cuda:0")
+    x = torch.zeros((1, 1, 144, 64), device=dev, dtype=torch.bfloat16)
+    with pytest.raises(S.S2Error) as ei:
+        S.s2_attn_global_fwd(g, x.float(), x.float(), x.float(), 1.0)
+    assert ei.value.code == S.S2_ERR_UNSUPPORTED
+    y = torch.zeros((1, 1, 144, 32), device=dev, dtype=torch.bfloat16)
+    with pytest.raises(S.S2Error) as ei:
+        S.s2_attn_global_fwd(g, y, y, y, 1.0)
+    assert ei.value.code == S.S2_ERR_UNSUPPORTED
+    with pytest.raises(S.S2Error) as ei:
+        S.s2_attn_global_fwd(g, x, x, x, 1.0, workspace=torch.empty(8, dtype=torch.uint8, device=dev))
+    assert ei.value.code == S.S2_ERR_WORKSPACE
+    g2 = S.s2_grid_init(0, 17, 32, 9, 16, 0.5)
+    z = torch.zeros((1, 1, 17 * 32, 64), device=dev, dtype=torch.bfloat16)
+    with pytest.raises(S.S2Error) as ei:
+        S.s2_attn_global_fwd(g2, z, z, z, 1.0)
+    assert ei.value.code == S.S2_ERR_INVALID_ARG
+    torch.cuda.synchronize()
