@@ -50,10 +50,12 @@ extern "C" int s2_nattn_bwd(const s2_grid_t *g, int batch, int heads, int d_qk, 
     if (!workspace || workspace_bytes < s2_nattn_bwd_workspace_bytes(g, batch, heads, d_qk, d_v, dtype))
         return s2_fail(S2_ERR_WORKSPACE, "workspace missing or smaller than s2_nattn_bwd_workspace_bytes()");
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    s2_nattn_bwd_generic(g->dt, batch * heads, d_qk, d_v, scale, static_cast<const float *>(q),
-                         static_cast<const float *>(k), static_cast<const float *>(v), static_cast<const float *>(out),
-                         lse, static_cast<const float *>(dout), static_cast<float *>(dq), static_cast<float *>(dk),
-                         static_cast<float *>(dv), static_cast<float *>(workspace), st);
+    auto *bwd = s2_nattn_bwd_tiled_supported(g->dt, d_qk, d_v) ? s2_nattn_bwd_tiled : s2_nattn_bwd_generic;
+    if (bwd(g->dt, batch * heads, d_qk, d_v, scale, static_cast<const float *>(q), static_cast<const float *>(k),
+            static_cast<const float *>(v), static_cast<const float *>(out), lse, static_cast<const float *>(dout),
+            static_cast<float *>(dq), static_cast<float *>(dk), static_cast<float *>(dv),
+            static_cast<float *>(workspace), st))
+        return s2_fail(S2_ERR_DEVICE, "backward launch configuration failed");
     S2_HIP_CHECK(hipGetLastError());
     return S2_OK;
 }

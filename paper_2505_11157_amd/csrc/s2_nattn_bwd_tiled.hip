@@ -1,0 +1,635 @@
+// Tuned float32 backward kernels for spherical neighborhood attention on gfx950
+// (App. B.4 with the typos of the derivation fixed):
+//   p_ij = omega_j exp(s_ij - lse_i),  D_i = dout_i . out_i,  dS_ij = p_ij (dout_i . v_j - D_i)
+//   dq_i = scale sum_j dS_ij k_j ;  dk_j = scale sum_i dS_ij q_i ;  dv_j = sum_i p_ij dout_i
+//
+// Same data path as the tuned forward kernel (runs of <= 9 longitude offsets on
+// one latitude, windows staged with LDS-direct loads, one aligned b128 strip
+// per channel reused from registers), with a different register budget: the
+// backward keeps three (dq) or four (dk/dv) per-point vectors live, so FOUR
+// adjacent lanes share four consecutive points and each carries 8 of the 32
+// channels; partial dot products are combined with two DPP adds.  A wavefront
+// owns 64 consecutive longitudes.
+//
+//   dq kernel   : owners are output points; K, V windows stream by
+//                 (s = q.K, dP = dout.V, then dq += dS K).  Also stores D_i.
+//   dk/dv kernel: owners are INPUT points (transposed neighborhood: by symmetry
+//                 of the distance, input (h', w) lies in the disks of outputs
+//                 (h, w + t), |t| <= half-arc(h, h')); q, dout windows stream by
+//                 together with the lse and D rows.  Equal grids only.
+// No atomics anywhere; heavy latitudes are split over the wavefronts of a
+// workgroup and summed through LDS, as in the forward kernel.
+#include <cstdlib>
+
+#include "s2_nattn_kernels.h"
+
+namespace {
+
+constexpr int kSegB = 64;    // points per wavefront
+constexpr int kNTMax = 9;    // longest run of offsets handled at once
+constexpr int kCGB = 4;      // channels per lane staged together
+constexpr int kRows = 16;    // channel rows per stage: 4 lanes x kCGB
+constexpr int kDL = 8;       // channels per lane (head dimension 32)
+constexpr int kWavesB = 8;
+constexpr float kLog2e = 1.4426950408889634f;
+
+// Row-major staged window of kRows channel rows x (64*PS + 8) columns.  The
+// pitch is 4 mod 16: the four rows a lane quad reads (r, r+4, r+8, r+12) start
+// 16 banks apart, so 4 quads x 4 lanes x b128 cover the 64 banks exactly once.
+template <int PS>
+struct GeoB {
+    static constexpr int PITCH = PS == 1 ? 84 : 148;
+    static constexpr int NFULL = PS;                       // full 64-column loads per row
+    static constexpr int NLOAD = kRows * NFULL + 2;        // vector-memory loads per stage (2 = tail)
+    static constexpr int TILE = kRows * PITCH;
+    static_assert(PITCH >= 64 * PS + 8 + 4, "pitch too small");
+};
+
+typedef __attribute__((address_space(1))) const void *gptr_t;
+typedef __attribute__((address_space(3))) void *lptr_t;
+
+__device__ __forceinline__ float quad_sum(float x)
+{
+    x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0xB1, 0xf, 0xf, true));
+    x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x4E, 0xf, 0xf, true));
+    return x;
+}
+
+__device__ __forceinline__ int wrap2(int x, int n)
+{
+    x = x >= n ? x - n : x;
+    return x >= n ? x - n : x;
+}
+
+// channel (relative to the group's first channel) held by stage row r: lane quarter r/4 owns channels 8*(r/4)..+7
+__device__ __forceinline__ int chan_of_row(int r) { return (r >> 2) * kDL + (r & 3); }
+
+struct StageOff {
+    unsigned full[2];   // byte offset of the lane's column in each 64-column piece
+    unsigned tail[2];   // byte offsets (channel row included) of the lane's two tail elements
+};
+
+// xw = first window column (already in [0, ncol)), ncol = longitudes of the streamed grid
+template <int PS>
+__device__ __forceinline__ StageOff stage_offsets(int xw, int ncol, size_t sstride, int lane)
+{
+    StageOff o;
+#pragma unroll
+    for (int a = 0; a < 2; ++a) o.full[a] = 4u * unsigned(wrap2(xw + lane + 64 * a, ncol));
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+        const int e = lane + 64 * u, row = e >> 3, col = e & 7;
+        o.tail[u] = unsigned(chan_of_row(row) * sstride * sizeof(float)) + 4u * unsigned(wrap2(xw + 64 * PS + col, ncol));
+    }
+    return o;
+}
+
+// Start the asynchronous copy of one stage (kRows channel rows starting at the
+// uniform pointer chan0: channel g*kCGB of lane quarter 0, streamed latitude, column 0).
+template <int PS>
+__device__ __forceinline__ void stage_issue(const float *chan0, size_t sstride, StageOff &o, float *buf, float (&tail)[2])
+{
+    using G = GeoB<PS>;
+#pragma unroll
+    for (int a = 0; a < 2; ++a) { asm volatile("" : "+v"(o.full[a])); asm volatile("" : "+v"(o.tail[a])); }
+    const char *rb = reinterpret_cast<const char *>(chan0);
+    asm volatile("" : "+s"(rb));
+    tail[0] = *reinterpret_cast<const float *>(rb + o.tail[0]);
+    tail[1] = *reinterpret_cast<const float *>(rb + o.tail[1]);
+    const size_t rs = sstride * sizeof(float);
+#pragma unroll
+    for (int r = 0; r < kRows; ++r) {
+#pragma unroll
+        for (int a = 0; a < G::NFULL; ++a)
+            __builtin_amdgcn_global_load_lds((gptr_t)(rb + o.full[a]), (lptr_t)(buf + r * G::PITCH + 64 * a), 4, 0, 0);
+        rb += ((r & 3) == 3) ? rs * (kDL - kCGB + 1) : rs;
+    }
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vm()
+{
+    if constexpr (N == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    else if constexpr (N == 18) asm volatile("s_waitcnt vmcnt(18)" ::: "memory");
+    else if constexpr (N == 34) asm volatile("s_waitcnt vmcnt(34)" ::: "memory");
+    else static_assert(N == 0, "unsupported wait count");
+}
+
+template <int PS>
+__device__ __forceinline__ void tail_store(float *buf, const int (&taddr)[2], const float (&tail)[2])
+{
+    buf[taddr[0]] = tail[0];
+    buf[taddr[1]] = tail[1];
+}
+
+template <int PS, int SL4>
+__device__ __forceinline__ void read_strip(const float *buf, int sbase, int cc, float (&st)[4 * SL4])
+{
+#pragma unroll
+    for (int a = 0; a < SL4; ++a) {
+        const float4 x = *reinterpret_cast<const float4 *>(buf + sbase + cc * GeoB<PS>::PITCH + 4 * a);
+        st[4 * a] = x.x; st[4 * a + 1] = x.y; st[4 * a + 2] = x.z; st[4 * a + 3] = x.w;
+    }
+}
+
+// acc[r][t] += own[r][c0 + cc] * window(r, t) over the kCGB channels of one stage
+template <int PS, int NT>
+__device__ __forceinline__ void dot_stage(const float *buf, int sbase, const float (&own)[4][kDL], int c0, float (&acc)[4][NT])
+{
+    constexpr int SL4 = (3 * PS + NT + 3) / 4;
+#pragma unroll
+    for (int cc = 0; cc < kCGB; ++cc) {
+        float st[4 * SL4];
+        read_strip<PS, SL4>(buf, sbase, cc, st);
+#pragma unroll
+        for (int tt = 0; tt < NT; ++tt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[r][tt] = fmaf(own[r][c0 + cc], st[r * PS + tt], acc[r][tt]);
+    }
+}
+
+// out[r][c0 + cc] += sum_t w[r][t] * window(r, t)
+template <int PS, int NT>
+__device__ __forceinline__ void axpy_stage(const float *buf, int sbase, const float (&w)[4][NT], int c0, float (&out)[4][kDL])
+{
+    constexpr int SL4 = (3 * PS + NT + 3) / 4;
+#pragma unroll
+    for (int cc = 0; cc < kCGB; ++cc) {
+        float st[4 * SL4];
+        read_strip<PS, SL4>(buf, sbase, cc, st);
+#pragma unroll
+        for (int tt = 0; tt < NT; ++tt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) out[r][c0 + cc] = fmaf(w[r][tt], st[r * PS + tt], out[r][c0 + cc]);
+    }
+}
+
+// Per-lane addressing shared by both kernels.
+struct LaneGeo {
+    int sbase;       // strip base (floats) in a staged buffer
+    int taddr[2];    // LDS addresses (floats) of the lane's two tail elements
+};
+
+template <int PS>
+__device__ __forceinline__ LaneGeo lane_geo(int lane)
+{
+    using G = GeoB<PS>;
+    LaneGeo g;
+    g.sbase = (lane & 3) * kCGB * G::PITCH + 4 * (lane >> 2) * PS;
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+        const int e = lane + 64 * u;
+        g.taddr[u] = (e >> 3) * G::PITCH + 64 * PS + (e & 7);
+    }
+    return g;
+}
+
+// ---------------------------------------------------------------- dq ----------
+
+template <int PS, int NT>
+__device__ __forceinline__ void run_chunk_dq(float *buf0, float *buf1, const float *__restrict__ kb,
+                                             const float *__restrict__ vb, size_t si, int xw, int nlon_in, int lane,
+                                             const LaneGeo &lg, float wq, const float (&q)[4][kDL],
+                                             const float (&go)[4][kDL], const float (&lse2)[4], const float (&Dr)[4],
+                                             float (&dq)[4][kDL])
+{
+    using G = GeoB<PS>;
+    float s[4][NT], dp[4][NT];
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int tt = 0; tt < NT; ++tt) { s[r][tt] = 0.f; dp[r][tt] = 0.f; }
+    StageOff so = stage_offsets<PS>(xw, nlon_in, si, lane);
+    float ta[2], tb[2];
+    const float *k1 = kb + size_t(kCGB) * si, *v1 = vb + size_t(kCGB) * si;
+
+    stage_issue<PS>(kb, si, so, buf0, ta);
+    // s = q . K
+    stage_issue<PS>(k1, si, so, buf1, tb);
+    wait_vm<G::NLOAD>(); tail_store<PS>(buf0, lg.taddr, ta);
+    dot_stage<PS, NT>(buf0, lg.sbase, q, 0, s);
+    stage_issue<PS>(vb, si, so, buf0, ta);
+    wait_vm<G::NLOAD>(); tail_store<PS>(buf1, lg.taddr, tb);
+    dot_stage<PS, NT>(buf1, lg.sbase, q, kCGB, s);
+    // dP = dout . V
+    stage_issue<PS>(v1, si, so, buf1, tb);
+    wait_vm<G::NLOAD>(); tail_store<PS>(buf0, lg.taddr, ta);
+    dot_stage<PS, NT>(buf0, lg.sbase, go, 0, dp);
+    stage_issue<PS>(kb, si, so, buf0, ta);
+    wait_vm<G::NLOAD>(); tail_store<PS>(buf1, lg.taddr, tb);
+    dot_stage<PS, NT>(buf1, lg.sbase, go, kCGB, dp);
+    // dS = p (dP - D)
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int tt = 0; tt < NT; ++tt) {
+            const float sv = quad_sum(s[r][tt]), dv = quad_sum(dp[r][tt]);
+            s[r][tt] = wq * __builtin_amdgcn_exp2f(sv - lse2[r]) * (dv - Dr[r]);
+        }
+    // dq += dS K
+    stage_issue<PS>(k1, si, so, buf1, tb);
+    wait_vm<G::NLOAD>(); tail_store<PS>(buf0, lg.taddr, ta);
+    axpy_stage<PS, NT>(buf0, lg.sbase, s, 0, dq);
+    wait_vm<0>(); tail_store<PS>(buf1, lg.taddr, tb);
+    axpy_stage<PS, NT>(buf1, lg.sbase, s, kCGB, dq);
+}
+
+// Decode a workgroup into (latitude, segment, slice, part): same scheme as the forward kernel.
+struct Task { int P, seg, row, part, bh; };
+
+template <int WAVES>
+__device__ __forceinline__ Task decode_task(const int (&cls)[4], const int *order, int nseg, int nbh, int first_row,
+                                            int wave)
+{
+    Task t;
+    if constexpr (WAVES == 1) {
+        int id = blockIdx.x;
+        t.seg = id % nseg; id /= nseg;
+        t.bh = id % nbh;
+        t.row = order[first_row + id / nbh];
+        t.P = 1; t.part = 0;
+    } else {
+        const int per_group = nseg * (8 * cls[0] + 4 * cls[1] + 2 * cls[2] + (first_row ? 0 : cls[3]));
+        const int grp8 = blockIdx.x / per_group;
+        int id = blockIdx.x - grp8 * per_group, rows_before = 0;
+        int P = WAVES;
+#pragma unroll
+        for (int c = 0; c < 3; ++c) {
+            const int Pc = WAVES >> c;
+            const int nblk_c = cls[c] * nseg * Pc;
+            if (P == Pc && id >= nblk_c) { id -= nblk_c; rows_before += cls[c]; P = Pc >> 1; }
+        }
+        const int tpb = WAVES / P;
+        const int sub = id % P; id /= P;
+        t.seg = id % nseg;
+        t.row = order[rows_before + id / nseg];
+        t.part = wave & (P - 1);
+        t.bh = grp8 * WAVES + sub * tpb + wave / P;
+        t.P = P;
+    }
+    return t;
+}
+
+// Sum NV per-lane vectors of 4 x kDL floats over the P wavefronts of a task (pairwise through LDS).
+template <int NV>
+__device__ __forceinline__ void merge_sum(float *smem, int wave, int lane, int P, int part, float (&a)[4][kDL],
+                                          float (&b)[4][kDL])
+{
+    __syncthreads();
+    for (int s = 1; s < P; s <<= 1) {
+        float *slot = smem + (wave / (2 * s)) * (NV * 4 * kDL * 64) + lane;
+        if ((part & (2 * s - 1)) == s) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+#pragma unroll
+                for (int c = 0; c < kDL; ++c) {
+                    slot[(r * kDL + c) * 64] = a[r][c];
+                    if (NV == 2) slot[(4 * kDL + r * kDL + c) * 64] = b[r][c];
+                }
+        }
+        __syncthreads();
+        if ((part & (2 * s - 1)) == 0) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+#pragma unroll
+                for (int c = 0; c < kDL; ++c) {
+                    a[r][c] += slot[(r * kDL + c) * 64];
+                    if (NV == 2) b[r][c] += slot[(4 * kDL + r * kDL + c) * 64];
+                }
+        }
+        __syncthreads();
+    }
+}
+
+template <int PS, int WAVES>
+__global__ void __launch_bounds__(64 * WAVES, 2)
+nattn_bwd_dq_tiled(S2DeviceTables t, int nbh, int first_row, float scale, const float *__restrict__ q,
+                   const float *__restrict__ k, const float *__restrict__ v, const float *__restrict__ o,
+                   const float *__restrict__ lse, const float *__restrict__ go, float *__restrict__ dq,
+                   float *__restrict__ Dws)
+{
+    using G = GeoB<PS>;
+    constexpr int D = 4 * kDL;
+    extern __shared__ __attribute__((aligned(16))) float smem[];
+    const int wave = WAVES == 1 ? 0 : __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    float *buf0 = smem + wave * 2 * G::TILE, *buf1 = buf0 + G::TILE;
+    const int nseg = (t.nlon_out + kSegB - 1) / kSegB;
+    const Task tk = decode_task<WAVES>(t.fwd_cls, t.row_order, nseg, nbh, first_row, wave);
+    const int h = tk.row, bh = tk.bh;
+    const bool wave_active = bh < nbh;
+    const int qd = lane & 3;
+    const int w0 = tk.seg * kSegB + 4 * (lane >> 2);
+    const bool active = wave_active && w0 < t.nlon_out;
+    const LaneGeo lg = lane_geo<PS>(lane);
+    const size_t so = size_t(t.nlat_out) * t.nlon_out, si = size_t(t.nlat_in) * t.nlon_in;
+    const size_t io = size_t(h) * t.nlon_out + w0;
+    const float qscale = scale * kLog2e;
+
+    float qr[4][kDL], gr[4][kDL], dqa[4][kDL], lse2[4], Dr[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int c = 0; c < kDL; ++c) {
+        float4 x = make_float4(0.f, 0.f, 0.f, 0.f), y = x, z = x;
+        if (active) {
+            const size_t off = (size_t(bh) * D + qd * kDL + c) * so + io;
+            x = *reinterpret_cast<const float4 *>(q + off);
+            y = *reinterpret_cast<const float4 *>(go + off);
+            z = *reinterpret_cast<const float4 *>(o + off);
+        }
+        qr[0][c] = x.x * qscale; qr[1][c] = x.y * qscale; qr[2][c] = x.z * qscale; qr[3][c] = x.w * qscale;
+        gr[0][c] = y.x; gr[1][c] = y.y; gr[2][c] = y.z; gr[3][c] = y.w;
+        Dr[0] = fmaf(y.x, z.x, Dr[0]); Dr[1] = fmaf(y.y, z.y, Dr[1]);
+        Dr[2] = fmaf(y.z, z.z, Dr[2]); Dr[3] = fmaf(y.w, z.w, Dr[3]);
+        dqa[0][c] = dqa[1][c] = dqa[2][c] = dqa[3][c] = 0.f;
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) Dr[r] = quad_sum(Dr[r]);
+    {
+        float4 L = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (active) L = *reinterpret_cast<const float4 *>(lse + size_t(bh) * so + io);
+        lse2[0] = (L.x - t.ln_omega_ref) * kLog2e; lse2[1] = (L.y - t.ln_omega_ref) * kLog2e;
+        lse2[2] = (L.z - t.ln_omega_ref) * kLog2e; lse2[3] = (L.w - t.ln_omega_ref) * kLog2e;
+        if (active && qd == 0 && tk.part == 0)
+            *reinterpret_cast<float4 *>(Dws + size_t(bh) * so + io) = make_float4(Dr[0], Dr[1], Dr[2], Dr[3]);
+    }
+
+    const int nb = t.band_n[h], hp0 = t.band_lo[h];
+    int nrun = 0;
+    for (int b = 0; b < nb; ++b) nrun += (t.cnt[h * t.band_max + b] + kNTMax - 1) / kNTMax;
+    const int run_lo = tk.part * nrun / tk.P, run_hi = (tk.part + 1) * nrun / tk.P;
+    int run = 0;
+    if (wave_active) {
+        for (int b = 0; b < nb; ++b) {
+            const int hp = hp0 + b;
+            const int c = t.cnt[h * t.band_max + b];
+            const int nchunk = (c + kNTMax - 1) / kNTMax;
+            if (run + nchunk <= run_lo || run >= run_hi) { run += nchunk; continue; }
+            const int lo = (c == t.nlon_in) ? 0 : -((c - 1) >> 1);
+            const float wq = t.omega_rel[hp];
+            const float *kb = k + size_t(bh) * D * si + size_t(hp) * t.nlon_in;
+            const float *vb = v + size_t(bh) * D * si + size_t(hp) * t.nlon_in;
+            const int base = c / nchunk, rem = c - base * nchunk;
+            int t0 = 0;
+            for (int ci = 0; ci < nchunk; ++ci, ++run) {
+                const int nt = base + (ci < rem ? 1 : 0);
+                if (run >= run_lo && run < run_hi) {
+                    const int xw = wrap2(tk.seg * kSegB * PS + lo + t0 + t.nlon_in, t.nlon_in);
+#define S2_RUN(N) case N: run_chunk_dq<PS, N>(buf0, buf1, kb, vb, si, xw, t.nlon_in, lane, lg, wq, qr, gr, lse2, Dr, dqa); break;
+                    switch (nt) {
+                        S2_RUN(1) S2_RUN(2) S2_RUN(3) S2_RUN(4) S2_RUN(5) S2_RUN(6)
+                        S2_RUN(7) S2_RUN(8) S2_RUN(9)
+                    }
+#undef S2_RUN
+                }
+                t0 += nt;
+            }
+        }
+    }
+    if (WAVES > 1 && tk.P > 1) merge_sum<1>(smem, wave, lane, tk.P, tk.part, dqa, dqa);
+    if (!active || tk.part != 0) return;
+#pragma unroll
+    for (int c = 0; c < kDL; ++c)
+        *reinterpret_cast<float4 *>(dq + (size_t(bh) * D + qd * kDL + c) * so + io) =
+            make_float4(dqa[0][c] * scale, dqa[1][c] * scale, dqa[2][c] * scale, dqa[3][c] * scale);
+}
+
+// -------------------------------------------------------------- dk, dv ----------
+
+template <int NT>
+__device__ __forceinline__ void run_chunk_dkdv(float *buf0, float *buf1, float *aux, const float *__restrict__ qb,
+                                               const float *__restrict__ gb, const float *__restrict__ lrow,
+                                               const float *__restrict__ drow, size_t so, int xw, int nlon, int lane,
+                                               const LaneGeo &lg, float wq, float lref2, const float (&kr)[4][kDL],
+                                               const float (&vr)[4][kDL], float (&dk)[4][kDL], float (&dv)[4][kDL])
+{
+    using G = GeoB<1>;
+    float s[4][NT], dp[4][NT];
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int tt = 0; tt < NT; ++tt) { s[r][tt] = 0.f; dp[r][tt] = 0.f; }
+    StageOff of = stage_offsets<1>(xw, nlon, so, lane);
+    // lse and D rows of the window: 64 columns by LDS-direct load, the last 8 by an ordinary load
+    // (every lane fetches one of the 16 tail elements; duplicates store the same value)
+    __builtin_amdgcn_global_load_lds((gptr_t)(reinterpret_cast<const char *>(lrow) + of.full[0]), (lptr_t)aux, 4, 0, 0);
+    __builtin_amdgcn_global_load_lds((gptr_t)(reinterpret_cast<const char *>(drow) + of.full[0]),
+                                     (lptr_t)(aux + G::PITCH), 4, 0, 0);
+    const int acol = wrap2(xw + 64 + (lane & 7), nlon);
+    const float atail = ((lane >> 3) & 1) ? drow[acol] : lrow[acol];
+    float ta[2], tb[2];
+    const float *q1 = qb + size_t(kCGB) * so, *g1 = gb + size_t(kCGB) * so;
+
+    stage_issue<1>(qb, so, of, buf0, ta);
+    // s = k . Q
+    stage_issue<1>(q1, so, of, buf1, tb);
+    wait_vm<G::NLOAD>(); tail_store<1>(buf0, lg.taddr, ta);
+    aux[((lane >> 3) & 1) * G::PITCH + 64 + (lane & 7)] = atail;
+    dot_stage<1, NT>(buf0, lg.sbase, kr, 0, s);
+    stage_issue<1>(gb, so, of, buf0, ta);
+    wait_vm<G::NLOAD>(); tail_store<1>(buf1, lg.taddr, tb);
+    dot_stage<1, NT>(buf1, lg.sbase, kr, kCGB, s);
+    // dP = v . dout
+    stage_issue<1>(g1, so, of, buf1, tb);
+    wait_vm<G::NLOAD>(); tail_store<1>(buf0, lg.taddr, ta);
+    dot_stage<1, NT>(buf0, lg.sbase, vr, 0, dp);
+    stage_issue<1>(qb, so, of, buf0, ta);
+    wait_vm<G::NLOAD>(); tail_store<1>(buf1, lg.taddr, tb);
+    dot_stage<1, NT>(buf1, lg.sbase, vr, kCGB, dp);
+    // p = omega exp2(s - lse2_i), dS = p (dP - D_i): lse and D of output column (own column + r + t)
+    {
+        constexpr int SL4 = (3 + NT + 3) / 4;
+        float ls[4 * SL4], ds[4 * SL4];
+        const int ab = 4 * (lane >> 2);
+#pragma unroll
+        for (int a = 0; a < SL4; ++a) {
+            const float4 x = *reinterpret_cast<const float4 *>(aux + ab + 4 * a);
+            const float4 y = *reinterpret_cast<const float4 *>(aux + G::PITCH + ab + 4 * a);
+            ls[4 * a] = fmaf(x.x, kLog2e, -lref2); ls[4 * a + 1] = fmaf(x.y, kLog2e, -lref2);
+            ls[4 * a + 2] = fmaf(x.z, kLog2e, -lref2); ls[4 * a + 3] = fmaf(x.w, kLog2e, -lref2);
+            ds[4 * a] = y.x; ds[4 * a + 1] = y.y; ds[4 * a + 2] = y.z; ds[4 * a + 3] = y.w;
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int tt = 0; tt < NT; ++tt) {
+                const float sv = quad_sum(s[r][tt]), dv2 = quad_sum(dp[r][tt]);
+                const float p = wq * __builtin_amdgcn_exp2f(sv - ls[r + tt]);
+                s[r][tt] = p;
+                dp[r][tt] = p * (dv2 - ds[r + tt]);
+            }
+    }
+    // dk += dS Q ; dv += p dout
+    stage_issue<1>(q1, so, of, buf1, tb);
+    wait_vm<G::NLOAD>(); tail_store<1>(buf0, lg.taddr, ta);
+    axpy_stage<1, NT>(buf0, lg.sbase, dp, 0, dk);
+    stage_issue<1>(gb, so, of, buf0, ta);
+    wait_vm<G::NLOAD>(); tail_store<1>(buf1, lg.taddr, tb);
+    axpy_stage<1, NT>(buf1, lg.sbase, dp, kCGB, dk);
+    stage_issue<1>(g1, so, of, buf1, tb);
+    wait_vm<G::NLOAD>(); tail_store<1>(buf0, lg.taddr, ta);
+    axpy_stage<1, NT>(buf0, lg.sbase, s, 0, dv);
+    wait_vm<0>(); tail_store<1>(buf1, lg.taddr, tb);
+    axpy_stage<1, NT>(buf1, lg.sbase, s, kCGB, dv);
+}
+
+template <int WAVES>
+__global__ void __launch_bounds__(64 * WAVES, 2)
+nattn_bwd_dkdv_tiled(S2DeviceTables t, int nbh, int first_row, float scale, const float *__restrict__ q,
+                     const float *__restrict__ k, const float *__restrict__ v, const float *__restrict__ lse,
+                     const float *__restrict__ go, const float *__restrict__ Dws, float *__restrict__ dk,
+                     float *__restrict__ dv)
+{
+    using G = GeoB<1>;
+    constexpr int D = 4 * kDL;
+    constexpr int WSZ = 2 * G::TILE + 2 * G::PITCH;   // floats of LDS per wavefront: two stages + lse/D rows
+    extern __shared__ __attribute__((aligned(16))) float smem[];
+    const int wave = WAVES == 1 ? 0 : __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    float *buf0 = smem + wave * WSZ, *buf1 = buf0 + G::TILE, *aux = buf1 + G::TILE;
+    const int nlon = t.nlon_in;                       // equal grids: nlon_out == nlon_in
+    const int nseg = (nlon + kSegB - 1) / kSegB;
+    const Task tk = decode_task<WAVES>(t.bwd_cls, t.trow_order, nseg, nbh, first_row, wave);
+    const int hp = tk.row, bh = tk.bh;
+    const bool wave_active = bh < nbh;
+    const int qd = lane & 3;
+    const int w0 = tk.seg * kSegB + 4 * (lane >> 2);
+    const bool active = wave_active && w0 < nlon;
+    const LaneGeo lg = lane_geo<1>(lane);
+    const size_t so = size_t(t.nlat_out) * t.nlon_out, si = size_t(t.nlat_in) * t.nlon_in;
+    const size_t ii = size_t(hp) * nlon + w0;
+    const float qscale = scale * kLog2e;
+    const float wq = t.omega_rel[hp], lref2 = t.ln_omega_ref * kLog2e;
+
+    float kr[4][kDL], vr[4][kDL], dka[4][kDL], dva[4][kDL];
+#pragma unroll
+    for (int c = 0; c < kDL; ++c) {
+        float4 x = make_float4(0.f, 0.f, 0.f, 0.f), y = x;
+        if (active) {
+            const size_t off = (size_t(bh) * D + qd * kDL + c) * si + ii;
+            x = *reinterpret_cast<const float4 *>(k + off);
+            y = *reinterpret_cast<const float4 *>(v + off);
+        }
+        kr[0][c] = x.x * qscale; kr[1][c] = x.y * qscale; kr[2][c] = x.z * qscale; kr[3][c] = x.w * qscale;
+        vr[0][c] = y.x; vr[1][c] = y.y; vr[2][c] = y.z; vr[3][c] = y.w;
+        dka[0][c] = dka[1][c] = dka[2][c] = dka[3][c] = 0.f;
+        dva[0][c] = dva[1][c] = dva[2][c] = dva[3][c] = 0.f;
+    }
+
+    const int nb = t.tband_n[hp], h0 = t.tband_lo[hp];
+    int nrun = 0;
+    for (int b = 0; b < nb; ++b) nrun += (t.tcnt[hp * t.tband_max + b] + kNTMax - 1) / kNTMax;
+    const int run_lo = tk.part * nrun / tk.P, run_hi = (tk.part + 1) * nrun / tk.P;
+    int run = 0;
+    if (wave_active) {
+        for (int b = 0; b < nb; ++b) {
+            const int h = h0 + b;
+            const int c = t.tcnt[hp * t.tband_max + b];
+            const int nchunk = (c + kNTMax - 1) / kNTMax;
+            if (run + nchunk <= run_lo || run >= run_hi) { run += nchunk; continue; }
+            const int lo = (c == nlon) ? 0 : -((c - 1) >> 1);
+            const float *qb = q + size_t(bh) * D * so + size_t(h) * nlon;
+            const float *gb = go + size_t(bh) * D * so + size_t(h) * nlon;
+            const float *lrow = lse + size_t(bh) * so + size_t(h) * nlon;
+            const float *drow = Dws + size_t(bh) * so + size_t(h) * nlon;
+            const int base = c / nchunk, rem = c - base * nchunk;
+            int t0 = 0;
+            for (int ci = 0; ci < nchunk; ++ci, ++run) {
+                const int nt = base + (ci < rem ? 1 : 0);
+                if (run >= run_lo && run < run_hi) {
+                    const int xw = wrap2(tk.seg * kSegB + lo + t0 + nlon, nlon);
+#define S2_RUN(N) case N: run_chunk_dkdv<N>(buf0, buf1, aux, qb, gb, lrow, drow, so, xw, nlon, lane, lg, wq, lref2, kr, vr, dka, dva); break;
+                    switch (nt) {
+                        S2_RUN(1) S2_RUN(2) S2_RUN(3) S2_RUN(4) S2_RUN(5) S2_RUN(6)
+                        S2_RUN(7) S2_RUN(8) S2_RUN(9)
+                    }
+#undef S2_RUN
+                }
+                t0 += nt;
+            }
+        }
+    }
+    if (WAVES > 1 && tk.P > 1) merge_sum<2>(smem, wave, lane, tk.P, tk.part, dka, dva);
+    if (!active || tk.part != 0) return;
+#pragma unroll
+    for (int c = 0; c < kDL; ++c) {
+        const size_t off = (size_t(bh) * D + qd * kDL + c) * si + ii;
+        *reinterpret_cast<float4 *>(dk + off) =
+            make_float4(dka[0][c] * scale, dka[1][c] * scale, dka[2][c] * scale, dka[3][c] * scale);
+        *reinterpret_cast<float4 *>(dv + off) = make_float4(dva[0][c], dva[1][c], dva[2][c], dva[3][c]);
+    }
+}
+
+}  // namespace
+
+bool s2_nattn_bwd_tiled_supported(const S2DeviceTables &t, int d, int e)
+{
+    return d == 32 && e == 32 && (t.pscale == 1 || t.pscale == 2) && t.nlon_in % 4 == 0 && t.nlon_out % 4 == 0 &&
+           t.nlon_out >= 72;
+}
+
+int s2_nattn_bwd_tiled(const S2DeviceTables &t, int nbh, int d, int e, float scale, const float *q, const float *k,
+                       const float *v, const float *o, const float *lse, const float *go, float *dq, float *dk,
+                       float *dv, float *Dws, hipStream_t st)
+{
+    const int nseg_o = (t.nlon_out + kSegB - 1) / kSegB;
+    static bool cfg_dq1 = false, cfg_dq2 = false, cfg_kv = false;
+    // the two launches of a kernel pair differ only in which latitudes they take: first_row = 1 tells the
+    // 8-wave kernel to skip the unsplit class, first_row = nsplit tells the 1-wave kernel where its rows start
+    const int nsplit_o = t.fwd_cls[0] + t.fwd_cls[1] + t.fwd_cls[2];
+    auto run_dq = [&](auto k8, auto k1, size_t lds_wave, bool &cfg) {
+        if (nsplit_o > 0) {
+            const long nblk = long((nbh + kWavesB - 1) / kWavesB) * nseg_o *
+                              (8 * t.fwd_cls[0] + 4 * t.fwd_cls[1] + 2 * t.fwd_cls[2]);
+            size_t lds = lds_wave * kWavesB;
+            const size_t mg = size_t(kWavesB / 2) * 4 * kDL * 64 * sizeof(float);
+            if (lds < mg) lds = mg;
+            if (!cfg) {
+                if (hipFuncSetAttribute(reinterpret_cast<const void *>(k8),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, int(lds)) != hipSuccess)
+                    return -1;
+                cfg = true;
+            }
+            hipLaunchKernelGGL(k8, dim3((unsigned)nblk), dim3(64 * kWavesB), lds, st, t, nbh, 1, scale, q, k, v, o, lse,
+                               go, dq, Dws);
+        }
+        const long nrows = t.nlat_out - nsplit_o;
+        if (nrows > 0)
+            hipLaunchKernelGGL(k1, dim3((unsigned)(nrows * nbh * nseg_o)), dim3(64), lds_wave, st, t, nbh, nsplit_o,
+                               scale, q, k, v, o, lse, go, dq, Dws);
+        return 0;
+    };
+    int rc;
+    if (t.pscale == 1)
+        rc = run_dq(nattn_bwd_dq_tiled<1, kWavesB>, nattn_bwd_dq_tiled<1, 1>, 2 * GeoB<1>::TILE * sizeof(float), cfg_dq1);
+    else
+        rc = run_dq(nattn_bwd_dq_tiled<2, kWavesB>, nattn_bwd_dq_tiled<2, 1>, 2 * GeoB<2>::TILE * sizeof(float), cfg_dq2);
+    if (rc) return rc;
+
+    if (t.pscale != 1) {   // the tuned dk/dv gather assumes equal grids
+        return s2_nattn_bwd_dkdv_generic(t, nbh, d, e, scale, q, k, v, lse, go, Dws, dk, dv, st);
+    }
+    const int nseg_i = (t.nlon_in + kSegB - 1) / kSegB;
+    const int nsplit_i = t.bwd_cls[0] + t.bwd_cls[1] + t.bwd_cls[2];
+    const size_t lds_wave = (2 * GeoB<1>::TILE + 2 * GeoB<1>::PITCH) * sizeof(float);
+    if (nsplit_i > 0) {
+        const long nblk = long((nbh + kWavesB - 1) / kWavesB) * nseg_i *
+                          (8 * t.bwd_cls[0] + 4 * t.bwd_cls[1] + 2 * t.bwd_cls[2]);
+        size_t lds = lds_wave * kWavesB;
+        const size_t mg = size_t(kWavesB / 2) * 2 * 4 * kDL * 64 * sizeof(float);
+        if (lds < mg) lds = mg;
+        auto k8 = nattn_bwd_dkdv_tiled<kWavesB>;
+        if (!cfg_kv) {
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(k8), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    int(lds)) != hipSuccess)
+                return -1;
+            cfg_kv = true;
+        }
+        hipLaunchKernelGGL(k8, dim3((unsigned)nblk), dim3(64 * kWavesB), lds, st, t, nbh, 1, scale, q, k, v, lse, go,
+                           Dws, dk, dv);
+    }
+    const long nrows = t.nlat_in - nsplit_i;
+    if (nrows > 0)
+        hipLaunchKernelGGL((nattn_bwd_dkdv_tiled<1>), dim3((unsigned)(nrows * nbh * nseg_i)), dim3(64), lds_wave, st, t,
+                           nbh, nsplit_i, scale, q, k, v, lse, go, Dws, dk, dv);
+    return 0;
+}

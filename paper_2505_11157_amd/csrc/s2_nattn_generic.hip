@@ -266,6 +266,17 @@ int launch_bwd(const S2DeviceTables &t, int nbh, int d, int e, float scale, cons
     return 0;
 }
 
+template <int DMAX>
+int launch_dkdv(const S2DeviceTables &t, int nbh, int d, int e, float scale, const float *q, const float *k,
+                const float *v, const float *lse, const float *go, const float *Dws, float *dk, float *dv,
+                hipStream_t st)
+{
+    const int nti = (t.nlon_in + 63) / 64;
+    hipLaunchKernelGGL(nattn_bwd_dkdv_generic<DMAX>, dim3((unsigned)(long(nti) * nbh * t.nlat_in)), dim3(64), 0, st,
+                       t, nbh, d, e, scale, q, k, v, lse, go, Dws, dk, dv);
+    return 0;
+}
+
 }  // namespace
 
 int s2_nattn_fwd_generic(const S2DeviceTables &t, int nbh, int d, int e, float scale, const float *q,
@@ -277,6 +288,18 @@ int s2_nattn_fwd_generic(const S2DeviceTables &t, int nbh, int d, int e, float s
     if (dm <= 32) return launch_fwd<32>(t, nbh, d, e, scale, q, k, v, out, lse, st);
     if (dm <= 64) return launch_fwd<64>(t, nbh, d, e, scale, q, k, v, out, lse, st);
     return launch_fwd<128>(t, nbh, d, e, scale, q, k, v, out, lse, st);
+}
+
+int s2_nattn_bwd_dkdv_generic(const S2DeviceTables &t, int nbh, int d, int e, float scale, const float *q,
+                              const float *k, const float *v, const float *lse, const float *go, const float *Dws,
+                              float *dk, float *dv, hipStream_t st)
+{
+    const int dm = d > e ? d : e;
+    if (dm <= 8) return launch_dkdv<8>(t, nbh, d, e, scale, q, k, v, lse, go, Dws, dk, dv, st);
+    if (dm <= 16) return launch_dkdv<16>(t, nbh, d, e, scale, q, k, v, lse, go, Dws, dk, dv, st);
+    if (dm <= 32) return launch_dkdv<32>(t, nbh, d, e, scale, q, k, v, lse, go, Dws, dk, dv, st);
+    if (dm <= 64) return launch_dkdv<64>(t, nbh, d, e, scale, q, k, v, lse, go, Dws, dk, dv, st);
+    return launch_dkdv<128>(t, nbh, d, e, scale, q, k, v, lse, go, Dws, dk, dv, st);
 }
 
 int s2_nattn_bwd_generic(const S2DeviceTables &t, int nbh, int d, int e, float scale, const float *q,

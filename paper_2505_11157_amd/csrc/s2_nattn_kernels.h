@@ -13,3 +13,13 @@ int s2_nattn_bwd_generic(const S2DeviceTables &t, int nbh, int d, int e, float s
 bool s2_nattn_fwd_tiled_supported(const S2DeviceTables &t, int d, int e);
 int s2_nattn_fwd_tiled(const S2DeviceTables &t, int nbh, int d, int e, float scale, const float *q, const float *k,
                        const float *v, float *out, float *lse, hipStream_t st);
+
+// dk/dv part of the shape-agnostic backward alone (D_i must already be in Dws).
+int s2_nattn_bwd_dkdv_generic(const S2DeviceTables &t, int nbh, int d, int e, float scale, const float *q,
+                              const float *k, const float *v, const float *lse, const float *go, const float *Dws,
+                              float *dk, float *dv, hipStream_t st);
+// Tuned float32 backward for d = e = 32 (dq for nlon_in / nlon_out in {1, 2}; dk/dv tuned on equal grids).
+bool s2_nattn_bwd_tiled_supported(const S2DeviceTables &t, int d, int e);
+int s2_nattn_bwd_tiled(const S2DeviceTables &t, int nbh, int d, int e, float scale, const float *q, const float *k,
+                       const float *v, const float *o, const float *lse, const float *go, float *dq, float *dk,
+                       float *dv, float *Dws, hipStream_t st);
