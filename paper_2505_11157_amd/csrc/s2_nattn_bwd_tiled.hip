@@ -110,6 +110,7 @@ template <int N>
 __device__ __forceinline__ void wait_vm()
 {
     if constexpr (N == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    else if constexpr (N == 16) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
     else if constexpr (N == 18) asm volatile("s_waitcnt vmcnt(18)" ::: "memory");
     else if constexpr (N == 34) asm volatile("s_waitcnt vmcnt(34)" ::: "memory");
     else static_assert(N == 0, "unsupported wait count");
@@ -559,6 +560,223 @@ nattn_bwd_dkdv_tiled(S2DeviceTables t, int nbh, int first_row, float scale, cons
     }
 }
 
+// ------------------------------------------ dk, dv with nlon_in = 2 * nlon_out ----------
+//
+// Input point (h', w_in) lies in the disk of output (h, w) iff |2w - w_in| <= half-arc(h, h').
+// A lane quad owns inputs w_in = 4p .. 4p+3 and walks OUTPUT columns w = 2p + (r >> 1) + jj:
+// the slot jj is valid for owner r iff |2 jj - (r & 1)| <= half-arc, which only trims the two
+// ends of the slot range for one parity; invalid slots get weight 0.  The window of output
+// columns a wavefront touches is at most 31 + 10 wide, so one 64-column load per row fills it.
+
+constexpr int kPitch2 = 68;               // = 4 mod 16, >= 64
+constexpr int kTile2 = kRows * kPitch2;
+
+__device__ __forceinline__ void stage_issue2(const float *chan0, size_t sstride, unsigned voff, float *buf)
+{
+    asm volatile("" : "+v"(voff));
+    const char *rb = reinterpret_cast<const char *>(chan0);
+    asm volatile("" : "+s"(rb));
+    const size_t rs = sstride * sizeof(float);
+#pragma unroll
+    for (int r = 0; r < kRows; ++r) {
+        __builtin_amdgcn_global_load_lds((gptr_t)(rb + voff), (lptr_t)(buf + r * kPitch2), 4, 0, 0);
+        rb += ((r & 3) == 3) ? rs * (kDL - kCGB + 1) : rs;
+    }
+}
+
+template <int NT>
+__device__ __forceinline__ void read_strip2(const float *p, float (&st)[NT + 2])
+{
+#pragma unroll
+    for (int a = 0; a < (NT + 2) / 2; ++a) {
+        const float2 x = *reinterpret_cast<const float2 *>(p + 2 * a);
+        st[2 * a] = x.x; st[2 * a + 1] = x.y;
+    }
+}
+
+template <int NT>
+__device__ __forceinline__ void dot_stage2(const float *buf, int sbase, const float (&own)[4][kDL], int c0, float (&acc)[4][NT])
+{
+#pragma unroll
+    for (int cc = 0; cc < kCGB; ++cc) {
+        float st[NT + 2];
+        read_strip2<NT>(buf + sbase + cc * kPitch2, st);
+#pragma unroll
+        for (int tt = 0; tt < NT; ++tt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[r][tt] = fmaf(own[r][c0 + cc], st[(r >> 1) + tt], acc[r][tt]);
+    }
+}
+
+template <int NT>
+__device__ __forceinline__ void axpy_stage2(const float *buf, int sbase, const float (&w)[4][NT], int c0, float (&out)[4][kDL])
+{
+#pragma unroll
+    for (int cc = 0; cc < kCGB; ++cc) {
+        float st[NT + 2];
+        read_strip2<NT>(buf + sbase + cc * kPitch2, st);
+#pragma unroll
+        for (int tt = 0; tt < NT; ++tt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) out[r][c0 + cc] = fmaf(w[r][tt], st[(r >> 1) + tt], out[r][c0 + cc]);
+    }
+}
+
+// one run of NT slots jj0 .. jj0+NT-1 on output latitude h; wv[parity][tt] = omega weight or 0
+template <int NT>
+__device__ __forceinline__ void run_chunk_dkdv2(float *buf0, float *buf1, float *aux, const float *__restrict__ qb,
+                                                const float *__restrict__ gb, const float *__restrict__ lrow,
+                                                const float *__restrict__ drow, size_t so, unsigned voff, int sbase,
+                                                int abase, const float (&wv)[2][NT], float lref2,
+                                                const float (&kr)[4][kDL], const float (&vr)[4][kDL],
+                                                float (&dk)[4][kDL], float (&dv)[4][kDL])
+{
+    float s[4][NT], dp[4][NT];
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int tt = 0; tt < NT; ++tt) { s[r][tt] = 0.f; dp[r][tt] = 0.f; }
+    unsigned vo = voff;
+    asm volatile("" : "+v"(vo));
+    __builtin_amdgcn_global_load_lds((gptr_t)(reinterpret_cast<const char *>(lrow) + vo), (lptr_t)aux, 4, 0, 0);
+    __builtin_amdgcn_global_load_lds((gptr_t)(reinterpret_cast<const char *>(drow) + vo), (lptr_t)(aux + kPitch2), 4, 0, 0);
+    const float *q1 = qb + size_t(kCGB) * so, *g1 = gb + size_t(kCGB) * so;
+    stage_issue2(qb, so, voff, buf0);
+    stage_issue2(q1, so, voff, buf1);
+    wait_vm<16>(); dot_stage2<NT>(buf0, sbase, kr, 0, s);
+    stage_issue2(gb, so, voff, buf0);
+    wait_vm<16>(); dot_stage2<NT>(buf1, sbase, kr, kCGB, s);
+    stage_issue2(g1, so, voff, buf1);
+    wait_vm<16>(); dot_stage2<NT>(buf0, sbase, vr, 0, dp);
+    stage_issue2(qb, so, voff, buf0);
+    wait_vm<16>(); dot_stage2<NT>(buf1, sbase, vr, kCGB, dp);
+    {
+        float ls[NT + 2], ds[NT + 2];
+        read_strip2<NT>(aux + abase, ls);
+        read_strip2<NT>(aux + kPitch2 + abase, ds);
+#pragma unroll
+        for (int a = 0; a < NT + 2; ++a) ls[a] = fmaf(ls[a], kLog2e, -lref2);
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int tt = 0; tt < NT; ++tt) {
+                const float sv = quad_sum(s[r][tt]), dv2 = quad_sum(dp[r][tt]);
+                const float p = wv[r & 1][tt] * __builtin_amdgcn_exp2f(sv - ls[(r >> 1) + tt]);
+                s[r][tt] = p;
+                dp[r][tt] = p * (dv2 - ds[(r >> 1) + tt]);
+            }
+    }
+    stage_issue2(q1, so, voff, buf1);
+    wait_vm<16>(); axpy_stage2<NT>(buf0, sbase, dp, 0, dk);
+    stage_issue2(gb, so, voff, buf0);
+    wait_vm<16>(); axpy_stage2<NT>(buf1, sbase, dp, kCGB, dk);
+    stage_issue2(g1, so, voff, buf1);
+    wait_vm<16>(); axpy_stage2<NT>(buf0, sbase, s, 0, dv);
+    wait_vm<0>(); axpy_stage2<NT>(buf1, sbase, s, kCGB, dv);
+}
+
+template <int WAVES>
+__global__ void __launch_bounds__(64 * WAVES, 2)
+nattn_bwd_dkdv2_tiled(S2DeviceTables t, int nbh, int first_row, float scale, const float *__restrict__ q,
+                      const float *__restrict__ k, const float *__restrict__ v, const float *__restrict__ lse,
+                      const float *__restrict__ go, const float *__restrict__ Dws, float *__restrict__ dk,
+                      float *__restrict__ dv)
+{
+    constexpr int D = 4 * kDL;
+    constexpr int WSZ = 2 * kTile2 + 2 * kPitch2;
+    extern __shared__ __attribute__((aligned(16))) float smem[];
+    const int wave = WAVES == 1 ? 0 : __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    float *buf0 = smem + wave * WSZ, *buf1 = buf0 + kTile2, *aux = buf1 + kTile2;
+    const int nlon_i = t.nlon_in, nlon_o = t.nlon_out;
+    const int nseg = (nlon_i + kSegB - 1) / kSegB;
+    const Task tk = decode_task<WAVES>(t.bwd_cls, t.trow_order, nseg, nbh, first_row, wave);
+    const int hp = tk.row, bh = tk.bh;
+    const bool wave_active = bh < nbh;
+    const int qd = lane & 3, pq = lane >> 2;
+    const int w0 = tk.seg * kSegB + 4 * pq;
+    const bool active = wave_active && w0 < nlon_i;
+    const size_t so = size_t(t.nlat_out) * nlon_o, si = size_t(t.nlat_in) * nlon_i;
+    const size_t ii = size_t(hp) * nlon_i + w0;
+    const float qscale = scale * kLog2e;
+    const float wq = t.omega_rel[hp], lref2 = t.ln_omega_ref * kLog2e;
+    const int sbase = qd * kCGB * kPitch2 + 2 * pq, abase = 2 * pq;
+
+    float kr[4][kDL], vr[4][kDL], dka[4][kDL], dva[4][kDL];
+#pragma unroll
+    for (int c = 0; c < kDL; ++c) {
+        float4 x = make_float4(0.f, 0.f, 0.f, 0.f), y = x;
+        if (active) {
+            const size_t off = (size_t(bh) * D + qd * kDL + c) * si + ii;
+            x = *reinterpret_cast<const float4 *>(k + off);
+            y = *reinterpret_cast<const float4 *>(v + off);
+        }
+        kr[0][c] = x.x * qscale; kr[1][c] = x.y * qscale; kr[2][c] = x.z * qscale; kr[3][c] = x.w * qscale;
+        vr[0][c] = y.x; vr[1][c] = y.y; vr[2][c] = y.z; vr[3][c] = y.w;
+        dka[0][c] = dka[1][c] = dka[2][c] = dka[3][c] = 0.f;
+        dva[0][c] = dva[1][c] = dva[2][c] = dva[3][c] = 0.f;
+    }
+
+    // slots per band row: full circle -> nlon_o slots from 0; arc of half-width hw -> hw + 1 slots from -(hw / 2)
+    const int nb = t.tband_n[hp], h0 = t.tband_lo[hp];
+    auto nslots = [&](int c) { return c == nlon_i ? nlon_o : ((c - 1) >> 1) + 1; };
+    int nrun = 0;
+    for (int b = 0; b < nb; ++b) nrun += (nslots(t.tcnt[hp * t.tband_max + b]) + kNTMax - 1) / kNTMax;
+    const int run_lo = tk.part * nrun / tk.P, run_hi = (tk.part + 1) * nrun / tk.P;
+    int run = 0;
+    if (wave_active) {
+        for (int b = 0; b < nb; ++b) {
+            const int h = h0 + b;
+            const int c = t.tcnt[hp * t.tband_max + b];
+            const bool full = c == nlon_i;
+            const int hw = (c - 1) >> 1, nj = nslots(c);
+            const int nchunk = (nj + kNTMax - 1) / kNTMax;
+            if (run + nchunk <= run_lo || run >= run_hi) { run += nchunk; continue; }
+            const int jlo = full ? 0 : -(hw >> 1);
+            const float *qb = q + size_t(bh) * D * so + size_t(h) * nlon_o;
+            const float *gb = go + size_t(bh) * D * so + size_t(h) * nlon_o;
+            const float *lrow = lse + size_t(bh) * so + size_t(h) * nlon_o;
+            const float *drow = Dws + size_t(bh) * so + size_t(h) * nlon_o;
+            const int base = nj / nchunk, rem = nj - base * nchunk;
+            int t0 = 0;
+            for (int ci = 0; ci < nchunk; ++ci, ++run) {
+                const int nt = base + (ci < rem ? 1 : 0);
+                if (run >= run_lo && run < run_hi) {
+                    const int jj0 = jlo + t0;
+                    const int xw = wrap2(tk.seg * (kSegB / 2) + jj0 + nlon_o, nlon_o);
+                    const unsigned voff = 4u * unsigned(wrap2(xw + lane, nlon_o));
+#define S2_RUN(N)                                                                                              \
+    case N: {                                                                                                  \
+        float wv[2][N];                                                                                        \
+        _Pragma("unroll") for (int tt = 0; tt < N; ++tt) {                                                    \
+            const int j2 = 2 * (jj0 + tt);                                                                     \
+            wv[0][tt] = (full || (j2 <= hw && -j2 <= hw)) ? wq : 0.f;                                           \
+            wv[1][tt] = (full || (j2 - 1 <= hw && 1 - j2 <= hw)) ? wq : 0.f;                                    \
+        }                                                                                                      \
+        run_chunk_dkdv2<N>(buf0, buf1, aux, qb, gb, lrow, drow, so, voff, sbase, abase, wv, lref2, kr, vr, dka, \
+                           dva);                                                                               \
+    } break;
+                    switch (nt) {
+                        S2_RUN(1) S2_RUN(2) S2_RUN(3) S2_RUN(4) S2_RUN(5) S2_RUN(6)
+                        S2_RUN(7) S2_RUN(8) S2_RUN(9)
+                    }
+#undef S2_RUN
+                }
+                t0 += nt;
+            }
+        }
+    }
+    if (WAVES > 1 && tk.P > 1) merge_sum<2>(smem, wave, lane, tk.P, tk.part, dka, dva);
+    if (!active || tk.part != 0) return;
+#pragma unroll
+    for (int c = 0; c < kDL; ++c) {
+        const size_t off = (size_t(bh) * D + qd * kDL + c) * si + ii;
+        *reinterpret_cast<float4 *>(dk + off) =
+            make_float4(dka[0][c] * scale, dka[1][c] * scale, dka[2][c] * scale, dka[3][c] * scale);
+        *reinterpret_cast<float4 *>(dv + off) = make_float4(dva[0][c], dva[1][c], dva[2][c], dva[3][c]);
+    }
+}
+
 }  // namespace
 
 bool s2_nattn_bwd_tiled_supported(const S2DeviceTables &t, int d, int e)
@@ -605,8 +823,32 @@ int s2_nattn_bwd_tiled(const S2DeviceTables &t, int nbh, int d, int e, float sca
         rc = run_dq(nattn_bwd_dq_tiled<2, kWavesB>, nattn_bwd_dq_tiled<2, 1>, 2 * GeoB<2>::TILE * sizeof(float), cfg_dq2);
     if (rc) return rc;
 
-    if (t.pscale != 1) {   // the tuned dk/dv gather assumes equal grids
-        return s2_nattn_bwd_dkdv_generic(t, nbh, d, e, scale, q, k, v, lse, go, Dws, dk, dv, st);
+    if (t.pscale == 2) {
+        const int nseg_i = (t.nlon_in + kSegB - 1) / kSegB;
+        const int nsplit_i = t.bwd_cls[0] + t.bwd_cls[1] + t.bwd_cls[2];
+        const size_t lds_wave = (2 * kTile2 + 2 * kPitch2) * sizeof(float);
+        static bool cfg_kv2 = false;
+        if (nsplit_i > 0) {
+            const long nblk = long((nbh + kWavesB - 1) / kWavesB) * nseg_i *
+                              (8 * t.bwd_cls[0] + 4 * t.bwd_cls[1] + 2 * t.bwd_cls[2]);
+            size_t lds = lds_wave * kWavesB;
+            const size_t mg = size_t(kWavesB / 2) * 2 * 4 * kDL * 64 * sizeof(float);
+            if (lds < mg) lds = mg;
+            auto k8 = nattn_bwd_dkdv2_tiled<kWavesB>;
+            if (!cfg_kv2) {
+                if (hipFuncSetAttribute(reinterpret_cast<const void *>(k8),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, int(lds)) != hipSuccess)
+                    return -1;
+                cfg_kv2 = true;
+            }
+            hipLaunchKernelGGL(k8, dim3((unsigned)nblk), dim3(64 * kWavesB), lds, st, t, nbh, 1, scale, q, k, v, lse,
+                               go, Dws, dk, dv);
+        }
+        const long nrows = t.nlat_in - nsplit_i;
+        if (nrows > 0)
+            hipLaunchKernelGGL((nattn_bwd_dkdv2_tiled<1>), dim3((unsigned)(nrows * nbh * nseg_i)), dim3(64), lds_wave,
+                               st, t, nbh, nsplit_i, scale, q, k, v, lse, go, Dws, dk, dv);
+        return 0;
     }
     const int nseg_i = (t.nlon_in + kSegB - 1) / kSegB;
     const int nsplit_i = t.bwd_cls[0] + t.bwd_cls[1] + t.bwd_cls[2];

@@ -78,6 +78,10 @@ SMALL = [
     dict(kind="nattn", grid_type=0, nlat_in=33, nlon_in=64, nlat_out=33, nlon_out=1, theta=0.3, batch=1, heads=2, d=8, dtype="f32"),
     dict(kind="nattn", grid_type=1, nlat_in=2, nlon_in=1, nlat_out=2, nlon_out=1, theta=0.2, batch=1, heads=1, d=1, dtype="f32"),
     dict(kind="nattn", grid_type=0, nlat_in=20, nlon_in=96, nlat_out=10, nlon_out=32, theta=0.35, batch=1, heads=2, d=32, dtype="f32"),
+    # tuned kernels (d = 32) with ragged last segments, equal grids and 2:1 downsampling, 3 and 9 slices
+    dict(kind="nattn", grid_type=1, nlat_in=24, nlon_in=100, nlat_out=24, nlon_out=100, theta=0.4, batch=3, heads=1, d=32, dtype="f32"),
+    dict(kind="nattn", grid_type=0, nlat_in=19, nlon_in=152, nlat_out=10, nlon_out=76, theta=0.3, batch=3, heads=3, d=32, dtype="f32"),
+    dict(kind="nattn", grid_type=0, nlat_in=21, nlon_in=192, nlat_out=21, nlon_out=192, theta=0.6, batch=1, heads=2, d=32, dtype="f32"),
 ]
 
 
