@@ -71,226 +71,311 @@ transpose_tokens(const bf16raw *__restrict__ in, bf16raw *__restrict__ out, int 
     }
 }
 
-// D[bh][i] = dout_i . out_i
+// Per-token backward constants, padded to Npad tokens per slice so that the kernels can read them
+// with 16-byte loads: L2[bh][i] = lse_i * log2(e) (+inf on the padding: p = exp2(-inf) = 0) and
+// D[bh][i] = dout_i . out_i (0 on the padding).
 __global__ void __launch_bounds__(256)
-rowdot(const bf16raw *__restrict__ a, const bf16raw *__restrict__ b, float *__restrict__ D, size_t ntok)
+rowstats(const bf16raw *__restrict__ go, const bf16raw *__restrict__ o, const float *__restrict__ lse,
+         float *__restrict__ L2, float *__restrict__ D, int N, int Npad)
 {
-    const size_t i = size_t(blockIdx.x) * 256 + threadIdx.x;
-    if (i >= ntok) return;
-    float acc = 0.f;
+    const int bh = blockIdx.y, i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= Npad) return;
+    float acc = 0.f, l2 = INFINITY;
+    if (i < N) {
+        const size_t t = size_t(bh) * N + i;
 #pragma unroll
-    for (int c = 0; c < kD; c += 8) {
-        const bf16x8 x = ld8(a + i * kD + c), y = ld8(b + i * kD + c);
+        for (int c = 0; c < kD; c += 8) {
+            const bf16x8 x = ld8(go + t * kD + c), y = ld8(o + t * kD + c);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) acc = fmaf(float(x[j]), float(y[j]), acc);
+            for (int j = 0; j < 8; ++j) acc = fmaf(float(x[j]), float(y[j]), acc);
+        }
+        l2 = lse[t] * kLog2e;
     }
-    D[i] = acc;
+    L2[size_t(bh) * Npad + i] = l2;
+    D[size_t(bh) * Npad + i] = acc;
 }
 
-// Forward.  One wavefront = 32 queries; bias = log2(omega) per token, -inf on the padding.
+// Forward.  One wavefront = 64 queries (two 32-query MFMA tiles sharing every K, V^T and bias
+// operand they load); bias = log2(omega) per token, -inf on the padding.
 __global__ void __launch_bounds__(256)
 global_fwd(const bf16raw *__restrict__ q, const bf16raw *__restrict__ k, const bf16raw *__restrict__ vt,
            const float *__restrict__ bias, bf16raw *__restrict__ out, float *__restrict__ lse, int N, int Npad,
            float c2)
 {
+    constexpr int NQ = 2;
     const int bh = blockIdx.y;
-    const int q0 = (blockIdx.x * 4 + (threadIdx.x >> 6)) * 32;
+    const int q0 = (blockIdx.x * 4 + (threadIdx.x >> 6)) * (32 * NQ);
     if (q0 >= N) return;
     const int lane = threadIdx.x & 63, col = lane & 31, hl = lane >> 5;
-    const int query = min(q0 + col, N - 1);
     const int prow = perm_row(col);
-    bf16x8 qop[4];
+    bf16x8 qop[NQ][4];
+    f32x16 o0[NQ], o1[NQ];
+    float m[NQ], l[NQ];
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) qop[ks] = ld8(q + (size_t(bh) * N + query) * kD + 16 * ks + 8 * hl);
-    f32x16 o0 = {0}, o1 = {0};
-    float m = -INFINITY, l = 0.f;
+    for (int t = 0; t < NQ; ++t) {
+        const int query = min(q0 + 32 * t + col, N - 1);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) qop[t][ks] = ld8(q + (size_t(bh) * N + query) * kD + 16 * ks + 8 * hl);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) { o0[t][i] = 0.f; o1[t][i] = 0.f; }
+        m[t] = -INFINITY; l[t] = 0.f;
+    }
     const bf16raw *kb = k + size_t(bh) * N * kD + 8 * hl;
     const bf16raw *vb0 = vt + (size_t(bh) * kD + col) * Npad + 16 * hl;
     const bf16raw *vb1 = vb0 + size_t(32) * Npad;
     for (int key0 = 0; key0 < Npad; key0 += 32) {
         const int key = min(key0 + prow, N - 1);
-        f32x16 s = {0};
+        bf16x8 kc[4], va[2], vb[2];
+        float4 bc[4];
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) s = mfma(ld8(kb + size_t(key) * kD + 16 * ks), qop[ks], s);
-        float p[16];
-        float mloc = -INFINITY;
+        for (int ks = 0; ks < 4; ++ks) kc[ks] = ld8(kb + size_t(key) * kD + 16 * ks);
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const float4 b = *reinterpret_cast<const float4 *>(bias + key0 + 16 * hl + 4 * g);
-            p[4 * g + 0] = fmaf(s[4 * g + 0], c2, b.x);
-            p[4 * g + 1] = fmaf(s[4 * g + 1], c2, b.y);
-            p[4 * g + 2] = fmaf(s[4 * g + 2], c2, b.z);
-            p[4 * g + 3] = fmaf(s[4 * g + 3], c2, b.w);
+        for (int g = 0; g < 4; ++g) bc[g] = *reinterpret_cast<const float4 *>(bias + key0 + 16 * hl + 4 * g);
 #pragma unroll
-            for (int t = 0; t < 4; ++t) mloc = fmaxf(mloc, p[4 * g + t]);
-        }
-        mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
-        // move the reference maximum only when a logit exceeds it by more than 2^8
-        if (__any(mloc > m + 8.f)) {
-            const float m_new = mloc > m + 8.f ? mloc : m;
-            const float corr = __builtin_amdgcn_exp2f(m - m_new);
-            m = m_new;
-            l *= corr;
+        for (int j = 0; j < 2; ++j) { va[j] = ld8(vb0 + key0 + 8 * j); vb[j] = ld8(vb1 + key0 + 8 * j); }
 #pragma unroll
-            for (int i = 0; i < 16; ++i) { o0[i] *= corr; o1[i] *= corr; }
-        }
+        for (int t = 0; t < NQ; ++t) {
+            f32x16 s = {0};
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            p[i] = __builtin_amdgcn_exp2f(p[i] - m);
-            l += p[i];
-        }
+            for (int ks = 0; ks < 4; ++ks) s = mfma(kc[ks], qop[t][ks], s);
+            float p[16];
+            float mloc = -INFINITY;
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const bf16x8 pb = pack8(p + 8 * j);
-            o0 = mfma(ld8(vb0 + key0 + 8 * j), pb, o0);
-            o1 = mfma(ld8(vb1 + key0 + 8 * j), pb, o1);
+            for (int g = 0; g < 4; ++g) {
+                const float4 b = bc[g];
+                p[4 * g + 0] = fmaf(s[4 * g + 0], c2, b.x);
+                p[4 * g + 1] = fmaf(s[4 * g + 1], c2, b.y);
+                p[4 * g + 2] = fmaf(s[4 * g + 2], c2, b.z);
+                p[4 * g + 3] = fmaf(s[4 * g + 3], c2, b.w);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) mloc = fmaxf(mloc, p[4 * g + u]);
+            }
+            mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
+            // move the reference maximum only when a logit exceeds it by more than 2^8
+            if (__any(mloc > m[t] + 8.f)) {
+                const float m_new = mloc > m[t] + 8.f ? mloc : m[t];
+                const float corr = __builtin_amdgcn_exp2f(m[t] - m_new);
+                m[t] = m_new;
+                l[t] *= corr;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) { o0[t][i] *= corr; o1[t][i] *= corr; }
+            }
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                p[i] = __builtin_amdgcn_exp2f(p[i] - m[t]);
+                l[t] += p[i];
+            }
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const bf16x8 pb = pack8(p + 8 * j);
+                o0[t] = mfma(va[j], pb, o0[t]);
+                o1[t] = mfma(vb[j], pb, o1[t]);
+            }
         }
     }
-    l += __shfl_xor(l, 32);
-    if (q0 + col >= N) return;
-    const float inv = 1.f / l;
-    bf16raw *ob = out + (size_t(bh) * N + query) * kD + 4 * hl;
 #pragma unroll
-    for (int g = 0; g < 4; ++g) {
-        bf16x4 a, b;
+    for (int t = 0; t < NQ; ++t) {
+        const float lt = l[t] + __shfl_xor(l[t], 32);
+        const int qi = q0 + 32 * t + col;
+        if (qi < N) {
+            const float inv = 1.f / lt;
+            bf16raw *ob = out + (size_t(bh) * N + qi) * kD + 4 * hl;
 #pragma unroll
-        for (int t = 0; t < 4; ++t) { a[t] = (__bf16)(o0[4 * g + t] * inv); b[t] = (__bf16)(o1[4 * g + t] * inv); }
-        *reinterpret_cast<bf16x4 *>(ob + 8 * g) = a;
-        *reinterpret_cast<bf16x4 *>(ob + 32 + 8 * g) = b;
+            for (int g = 0; g < 4; ++g) {
+                bf16x4 a, b;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) { a[u] = (__bf16)(o0[t][4 * g + u] * inv); b[u] = (__bf16)(o1[t][4 * g + u] * inv); }
+                *reinterpret_cast<bf16x4 *>(ob + 8 * g) = a;
+                *reinterpret_cast<bf16x4 *>(ob + 32 + 8 * g) = b;
+            }
+            if (hl == 0) lse[size_t(bh) * N + qi] = (m[t] + log2f(lt)) * 0.6931471805599453f;
+        }
     }
-    if (hl == 0) lse[size_t(bh) * N + query] = (m + log2f(l)) * 0.6931471805599453f;
 }
 
-// Backward, key side: one wavefront = 32 keys, streaming 32-query tiles.
+// Backward, key side: one wavefront = 64 keys (two MFMA tiles sharing the streamed operands),
+// streaming 32-query tiles.
 //   S = Q K^T and dP = dout V^T land with lane = key, registers = 16 queries;
 //   dV^T += dout^T P,  dK^T += Q^T dS  with the transposed operands from the workspace.
 __global__ void __launch_bounds__(256)
 global_bwd_dkdv(const bf16raw *__restrict__ q, const bf16raw *__restrict__ k, const bf16raw *__restrict__ v,
                 const bf16raw *__restrict__ go, const bf16raw *__restrict__ qt, const bf16raw *__restrict__ got,
-                const float *__restrict__ bias, const float *__restrict__ lse, const float *__restrict__ Dv,
+                const float *__restrict__ bias, const float *__restrict__ L2, const float *__restrict__ Dv,
                 bf16raw *__restrict__ dk, bf16raw *__restrict__ dv, int N, int Npad, float c2, float scale)
 {
+    constexpr int NK = 2;
     const int bh = blockIdx.y;
-    const int k0 = (blockIdx.x * 4 + (threadIdx.x >> 6)) * 32;
+    const int k0 = (blockIdx.x * 4 + (threadIdx.x >> 6)) * (32 * NK);
     if (k0 >= N) return;
     const int lane = threadIdx.x & 63, col = lane & 31, hl = lane >> 5;
-    const int key = min(k0 + col, N - 1);
     const int prow = perm_row(col);
-    bf16x8 kop[4], vop[4];
+    bf16x8 kop[NK][4], vop[NK][4];
+    float bk[NK];
+    f32x16 dk0[NK], dk1[NK], dv0[NK], dv1[NK];
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-        kop[ks] = ld8(k + (size_t(bh) * N + key) * kD + 16 * ks + 8 * hl);
-        vop[ks] = ld8(v + (size_t(bh) * N + key) * kD + 16 * ks + 8 * hl);
+    for (int t = 0; t < NK; ++t) {
+        const int key = min(k0 + 32 * t + col, N - 1);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            kop[t][ks] = ld8(k + (size_t(bh) * N + key) * kD + 16 * ks + 8 * hl);
+            vop[t][ks] = ld8(v + (size_t(bh) * N + key) * kD + 16 * ks + 8 * hl);
+        }
+        bk[t] = bias[min(k0 + 32 * t + col, Npad - 1)];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) { dk0[t][i] = 0.f; dk1[t][i] = 0.f; dv0[t][i] = 0.f; dv1[t][i] = 0.f; }
     }
-    const float bk = bias[k0 + col];
-    f32x16 dk0 = {0}, dk1 = {0}, dv0 = {0}, dv1 = {0};
     const bf16raw *qb = q + size_t(bh) * N * kD + 8 * hl, *gb = go + size_t(bh) * N * kD + 8 * hl;
     const bf16raw *qt0 = qt + (size_t(bh) * kD + col) * Npad + 16 * hl, *qt1 = qt0 + size_t(32) * Npad;
     const bf16raw *gt0 = got + (size_t(bh) * kD + col) * Npad + 16 * hl, *gt1 = gt0 + size_t(32) * Npad;
-    const float *lb = lse + size_t(bh) * N, *Db = Dv + size_t(bh) * N;
+    const float *lb = L2 + size_t(bh) * Npad + 16 * hl, *Db = Dv + size_t(bh) * Npad + 16 * hl;
     for (int q0 = 0; q0 < Npad; q0 += 32) {
         const int qrow = min(q0 + prow, N - 1);
-        f32x16 s = {0}, dp = {0};
+        bf16x8 qa[4], ga[4], qta[2], qtb[2], gta[2], gtb[2];
+        float l2[16], dd[16];
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
-            s = mfma(ld8(qb + size_t(qrow) * kD + 16 * ks), kop[ks], s);
-            dp = mfma(ld8(gb + size_t(qrow) * kD + 16 * ks), vop[ks], dp);
+            qa[ks] = ld8(qb + size_t(qrow) * kD + 16 * ks);
+            ga[ks] = ld8(gb + size_t(qrow) * kD + 16 * ks);
         }
-        float p[16], ds[16];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int qi = q0 + 16 * hl + i;
-            const int qc = min(qi, N - 1);
-            const float pi = qi < N ? __builtin_amdgcn_exp2f(fmaf(s[i], c2, bk) - lb[qc] * kLog2e) : 0.f;
-            p[i] = pi;
-            ds[i] = pi * (dp[i] - Db[qc]);
+        for (int g = 0; g < 4; ++g) {
+            const float4 x = *reinterpret_cast<const float4 *>(lb + q0 + 4 * g);
+            const float4 y = *reinterpret_cast<const float4 *>(Db + q0 + 4 * g);
+            l2[4 * g] = x.x; l2[4 * g + 1] = x.y; l2[4 * g + 2] = x.z; l2[4 * g + 3] = x.w;
+            dd[4 * g] = y.x; dd[4 * g + 1] = y.y; dd[4 * g + 2] = y.z; dd[4 * g + 3] = y.w;
         }
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
-            const bf16x8 pb = pack8(p + 8 * j), sb = pack8(ds + 8 * j);
-            dv0 = mfma(ld8(gt0 + q0 + 8 * j), pb, dv0);
-            dv1 = mfma(ld8(gt1 + q0 + 8 * j), pb, dv1);
-            dk0 = mfma(ld8(qt0 + q0 + 8 * j), sb, dk0);
-            dk1 = mfma(ld8(qt1 + q0 + 8 * j), sb, dk1);
+            qta[j] = ld8(qt0 + q0 + 8 * j); qtb[j] = ld8(qt1 + q0 + 8 * j);
+            gta[j] = ld8(gt0 + q0 + 8 * j); gtb[j] = ld8(gt1 + q0 + 8 * j);
+        }
+#pragma unroll
+        for (int t = 0; t < NK; ++t) {
+            f32x16 s = {0}, dp = {0};
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                s = mfma(qa[ks], kop[t][ks], s);
+                dp = mfma(ga[ks], vop[t][ks], dp);
+            }
+            float p[16], ds[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                p[i] = __builtin_amdgcn_exp2f(fmaf(s[i], c2, bk[t]) - l2[i]);
+                ds[i] = p[i] * (dp[i] - dd[i]);
+            }
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const bf16x8 pb = pack8(p + 8 * j), sb = pack8(ds + 8 * j);
+                dv0[t] = mfma(gta[j], pb, dv0[t]);
+                dv1[t] = mfma(gtb[j], pb, dv1[t]);
+                dk0[t] = mfma(qta[j], sb, dk0[t]);
+                dk1[t] = mfma(qtb[j], sb, dk1[t]);
+            }
         }
     }
-    if (k0 + col >= N) return;
-    bf16raw *dkb = dk + (size_t(bh) * N + key) * kD + 4 * hl, *dvb = dv + (size_t(bh) * N + key) * kD + 4 * hl;
 #pragma unroll
-    for (int g = 0; g < 4; ++g) {
-        bf16x4 a, b, c, d;
+    for (int t = 0; t < NK; ++t) {
+        const int key = k0 + 32 * t + col;
+        if (key >= N) continue;
+        bf16raw *dkb = dk + (size_t(bh) * N + key) * kD + 4 * hl, *dvb = dv + (size_t(bh) * N + key) * kD + 4 * hl;
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            a[t] = (__bf16)(dk0[4 * g + t] * scale); b[t] = (__bf16)(dk1[4 * g + t] * scale);
-            c[t] = (__bf16)dv0[4 * g + t]; d[t] = (__bf16)dv1[4 * g + t];
+        for (int g = 0; g < 4; ++g) {
+            bf16x4 a, b, c, d;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                a[u] = (__bf16)(dk0[t][4 * g + u] * scale); b[u] = (__bf16)(dk1[t][4 * g + u] * scale);
+                c[u] = (__bf16)dv0[t][4 * g + u]; d[u] = (__bf16)dv1[t][4 * g + u];
+            }
+            *reinterpret_cast<bf16x4 *>(dkb + 8 * g) = a;
+            *reinterpret_cast<bf16x4 *>(dkb + 32 + 8 * g) = b;
+            *reinterpret_cast<bf16x4 *>(dvb + 8 * g) = c;
+            *reinterpret_cast<bf16x4 *>(dvb + 32 + 8 * g) = d;
         }
-        *reinterpret_cast<bf16x4 *>(dkb + 8 * g) = a;
-        *reinterpret_cast<bf16x4 *>(dkb + 32 + 8 * g) = b;
-        *reinterpret_cast<bf16x4 *>(dvb + 8 * g) = c;
-        *reinterpret_cast<bf16x4 *>(dvb + 32 + 8 * g) = d;
     }
 }
 
-// Backward, query side: one wavefront = 32 queries, streaming 32-key tiles.
+// Backward, query side: one wavefront = 64 queries, streaming 32-key tiles.
 //   S^T = K Q^T and dP^T = V dout^T land with lane = query, registers = 16 keys;
 //   dQ^T += K^T dS^T with K^T from the workspace.
 __global__ void __launch_bounds__(256)
 global_bwd_dq(const bf16raw *__restrict__ q, const bf16raw *__restrict__ k, const bf16raw *__restrict__ v,
               const bf16raw *__restrict__ go, const bf16raw *__restrict__ kt, const float *__restrict__ bias,
-              const float *__restrict__ lse, const float *__restrict__ Dv, bf16raw *__restrict__ dq, int N, int Npad,
+              const float *__restrict__ L2, const float *__restrict__ Dv, bf16raw *__restrict__ dq, int N, int Npad,
               float c2, float scale)
 {
+    constexpr int NQ = 2;
     const int bh = blockIdx.y;
-    const int q0 = (blockIdx.x * 4 + (threadIdx.x >> 6)) * 32;
+    const int q0 = (blockIdx.x * 4 + (threadIdx.x >> 6)) * (32 * NQ);
     if (q0 >= N) return;
     const int lane = threadIdx.x & 63, col = lane & 31, hl = lane >> 5;
-    const int query = min(q0 + col, N - 1);
     const int prow = perm_row(col);
-    bf16x8 qop[4], gop[4];
+    bf16x8 qop[NQ][4], gop[NQ][4];
+    float lse2[NQ], Dq[NQ];
+    f32x16 dq0[NQ], dq1[NQ];
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-        qop[ks] = ld8(q + (size_t(bh) * N + query) * kD + 16 * ks + 8 * hl);
-        gop[ks] = ld8(go + (size_t(bh) * N + query) * kD + 16 * ks + 8 * hl);
+    for (int t = 0; t < NQ; ++t) {
+        const int query = min(q0 + 32 * t + col, N - 1);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            qop[t][ks] = ld8(q + (size_t(bh) * N + query) * kD + 16 * ks + 8 * hl);
+            gop[t][ks] = ld8(go + (size_t(bh) * N + query) * kD + 16 * ks + 8 * hl);
+        }
+        lse2[t] = L2[size_t(bh) * Npad + query];
+        Dq[t] = Dv[size_t(bh) * Npad + query];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) { dq0[t][i] = 0.f; dq1[t][i] = 0.f; }
     }
-    const float lse2 = lse[size_t(bh) * N + query] * kLog2e, Dq = Dv[size_t(bh) * N + query];
-    f32x16 dq0 = {0}, dq1 = {0};
     const bf16raw *kb = k + size_t(bh) * N * kD + 8 * hl, *vb = v + size_t(bh) * N * kD + 8 * hl;
     const bf16raw *kt0 = kt + (size_t(bh) * kD + col) * Npad + 16 * hl, *kt1 = kt0 + size_t(32) * Npad;
     for (int key0 = 0; key0 < Npad; key0 += 32) {
         const int key = min(key0 + prow, N - 1);
-        f32x16 s = {0}, dp = {0};
+        bf16x8 ka[4], va[4], kta[2], ktb[2];
+        float bb[16];
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
-            s = mfma(ld8(kb + size_t(key) * kD + 16 * ks), qop[ks], s);
-            dp = mfma(ld8(vb + size_t(key) * kD + 16 * ks), gop[ks], dp);
+            ka[ks] = ld8(kb + size_t(key) * kD + 16 * ks);
+            va[ks] = ld8(vb + size_t(key) * kD + 16 * ks);
         }
-        float ds[16];
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
             const float4 b = *reinterpret_cast<const float4 *>(bias + key0 + 16 * hl + 4 * g);
-            const float bb[4] = {b.x, b.y, b.z, b.w};
+            bb[4 * g] = b.x; bb[4 * g + 1] = b.y; bb[4 * g + 2] = b.z; bb[4 * g + 3] = b.w;
+        }
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const int i = 4 * g + t;
-                ds[i] = __builtin_amdgcn_exp2f(fmaf(s[i], c2, bb[t]) - lse2) * (dp[i] - Dq);
+        for (int j = 0; j < 2; ++j) { kta[j] = ld8(kt0 + key0 + 8 * j); ktb[j] = ld8(kt1 + key0 + 8 * j); }
+#pragma unroll
+        for (int t = 0; t < NQ; ++t) {
+            f32x16 s = {0}, dp = {0};
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                s = mfma(ka[ks], qop[t][ks], s);
+                dp = mfma(va[ks], gop[t][ks], dp);
+            }
+            float ds[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+                ds[i] = __builtin_amdgcn_exp2f(fmaf(s[i], c2, bb[i]) - lse2[t]) * (dp[i] - Dq[t]);
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const bf16x8 sb = pack8(ds + 8 * j);
+                dq0[t] = mfma(kta[j], sb, dq0[t]);
+                dq1[t] = mfma(ktb[j], sb, dq1[t]);
             }
         }
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const bf16x8 sb = pack8(ds + 8 * j);
-            dq0 = mfma(ld8(kt0 + key0 + 8 * j), sb, dq0);
-            dq1 = mfma(ld8(kt1 + key0 + 8 * j), sb, dq1);
-        }
     }
-    if (q0 + col >= N) return;
-    bf16raw *dqb = dq + (size_t(bh) * N + query) * kD + 4 * hl;
 #pragma unroll
-    for (int g = 0; g < 4; ++g) {
-        bf16x4 a, b;
+    for (int t = 0; t < NQ; ++t) {
+        const int qi = q0 + 32 * t + col;
+        if (qi >= N) continue;
+        bf16raw *dqb = dq + (size_t(bh) * N + qi) * kD + 4 * hl;
 #pragma unroll
-        for (int t = 0; t < 4; ++t) { a[t] = (__bf16)(dq0[4 * g + t] * scale); b[t] = (__bf16)(dq1[4 * g + t] * scale); }
-        *reinterpret_cast<bf16x4 *>(dqb + 8 * g) = a;
-        *reinterpret_cast<bf16x4 *>(dqb + 32 + 8 * g) = b;
+        for (int g = 0; g < 4; ++g) {
+            bf16x4 a, b;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) { a[u] = (__bf16)(dq0[t][4 * g + u] * scale); b[u] = (__bf16)(dq1[t][4 * g + u] * scale); }
+            *reinterpret_cast<bf16x4 *>(dqb + 8 * g) = a;
+            *reinterpret_cast<bf16x4 *>(dqb + 32 + 8 * g) = b;
+        }
     }
 }
 
@@ -328,8 +413,8 @@ extern "C" size_t s2_attn_global_bwd_workspace_bytes(const s2_grid_t *g, int bat
 {
     (void)d; (void)dtype;
     if (!g || batch < 1 || heads < 1) return 0;
-    const size_t ntok = size_t(batch) * heads * g->nlat_in * g->nlon_in;
-    return 3 * transposed_bytes(g, batch * heads) + (ntok * sizeof(float) + 255) / 256 * 256;
+    const size_t npad = size_t(batch) * heads * g->npad_tok;
+    return 3 * transposed_bytes(g, batch * heads) + 2 * ((npad * sizeof(float) + 255) / 256 * 256);
 }
 
 extern "C" int s2_attn_global_fwd(const s2_grid_t *g, int batch, int heads, int d, int dtype, float scale,
@@ -344,7 +429,7 @@ extern "C" int s2_attn_global_fwd(const s2_grid_t *g, int batch, int heads, int 
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const int nbh = batch * heads, N = g->nlat_in * g->nlon_in, Npad = g->npad_tok;
     launch_transpose(v, workspace, nbh, N, Npad, st);
-    hipLaunchKernelGGL(global_fwd, dim3((N + 127) / 128, nbh), dim3(256), 0, st, static_cast<const bf16raw *>(q),
+    hipLaunchKernelGGL(global_fwd, dim3((N + 255) / 256, nbh), dim3(256), 0, st, static_cast<const bf16raw *>(q),
                        static_cast<const bf16raw *>(k), static_cast<const bf16raw *>(workspace), g->dev_bias_tok,
                        static_cast<bf16raw *>(out), lse, N, Npad, scale * kLog2e);
     S2_HIP_CHECK(hipGetLastError());
@@ -364,24 +449,25 @@ extern "C" int s2_attn_global_bwd(const s2_grid_t *g, int batch, int heads, int 
         return s2_fail(S2_ERR_WORKSPACE, "workspace missing or smaller than s2_attn_global_bwd_workspace_bytes()");
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const int nbh = batch * heads, N = g->nlat_in * g->nlon_in, Npad = g->npad_tok;
-    const size_t tb = transposed_bytes(g, nbh), ntok = size_t(nbh) * N;
+    const size_t tb = transposed_bytes(g, nbh);
+    const size_t sb = (size_t(nbh) * Npad * sizeof(float) + 255) / 256 * 256;
     char *ws = static_cast<char *>(workspace);
     bf16raw *qt = reinterpret_cast<bf16raw *>(ws), *kt = reinterpret_cast<bf16raw *>(ws + tb),
             *got = reinterpret_cast<bf16raw *>(ws + 2 * tb);
-    float *Dv = reinterpret_cast<float *>(ws + 3 * tb);
+    float *L2 = reinterpret_cast<float *>(ws + 3 * tb), *Dv = reinterpret_cast<float *>(ws + 3 * tb + sb);
     launch_transpose(q, qt, nbh, N, Npad, st);
     launch_transpose(k, kt, nbh, N, Npad, st);
     launch_transpose(dout, got, nbh, N, Npad, st);
-    hipLaunchKernelGGL(rowdot, dim3((unsigned)((ntok + 255) / 256)), dim3(256), 0, st,
-                       static_cast<const bf16raw *>(dout), static_cast<const bf16raw *>(out), Dv, ntok);
+    hipLaunchKernelGGL(rowstats, dim3((Npad + 255) / 256, nbh), dim3(256), 0, st, static_cast<const bf16raw *>(dout),
+                       static_cast<const bf16raw *>(out), lse, L2, Dv, N, Npad);
     const float c2 = scale * kLog2e;
-    hipLaunchKernelGGL(global_bwd_dkdv, dim3((N + 127) / 128, nbh), dim3(256), 0, st, static_cast<const bf16raw *>(q),
+    hipLaunchKernelGGL(global_bwd_dkdv, dim3((N + 255) / 256, nbh), dim3(256), 0, st, static_cast<const bf16raw *>(q),
                        static_cast<const bf16raw *>(k), static_cast<const bf16raw *>(v),
-                       static_cast<const bf16raw *>(dout), qt, got, g->dev_bias_tok, lse, Dv,
+                       static_cast<const bf16raw *>(dout), qt, got, g->dev_bias_tok, L2, Dv,
                        static_cast<bf16raw *>(dk), static_cast<bf16raw *>(dv), N, Npad, c2, scale);
-    hipLaunchKernelGGL(global_bwd_dq, dim3((N + 127) / 128, nbh), dim3(256), 0, st, static_cast<const bf16raw *>(q),
+    hipLaunchKernelGGL(global_bwd_dq, dim3((N + 255) / 256, nbh), dim3(256), 0, st, static_cast<const bf16raw *>(q),
                        static_cast<const bf16raw *>(k), static_cast<const bf16raw *>(v),
-                       static_cast<const bf16raw *>(dout), kt, g->dev_bias_tok, lse, Dv, static_cast<bf16raw *>(dq), N,
+                       static_cast<const bf16raw *>(dout), kt, g->dev_bias_tok, L2, Dv, static_cast<bf16raw *>(dq), N,
                        Npad, c2, scale);
     S2_HIP_CHECK(hipGetLastError());
     return S2_OK;
