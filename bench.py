@@ -22,6 +22,10 @@ PEAK_FP32_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
 PEAK_BF16_TFLOPS = 2500.0
 
+# HBM bytes per launch (FETCH_SIZE + WRITE_SIZE from rocprofv3 --pmc, scaled by the factors a plain
+# copy gives: see profiles/), keyed by (workload, kernel name).  Measured offline; None if not measured.
+TRAFFIC_BYTES = {}
+
 
 def pairs_per_slice(S, g, c):
     """P = sum over output points of the neighborhood size (from the library's own lists)."""
@@ -119,17 +123,40 @@ def main():
     fl_f, fl_b, by_f, by_b = algorithmic(c, P)
     units = B * H * c["nlat_out"] * c["nlon_out"]
 
-    # dominant kernel: the forward kernel is a single launch; the backward is its own group of launches.
-    # Both are reported; the roofline object describes the forward kernel (one launch per step), whose
-    # duration is directly bracketed by events.
-    if is_global:
-        roof = {"bound": "mfma", "kernel": "global_fwd", "achieved": fl_f / t_fwd / 1e12, "peak": PEAK_BF16_TFLOPS,
-                "unit": "TFLOP/s", "frac": fl_f / t_fwd / 1e12 / PEAK_BF16_TFLOPS, "traffic": None}
-    else:
-        roof = {"bound": "alu", "kernel": "nattn_fwd", "achieved": fl_f / t_fwd / 1e12, "peak": PEAK_FP32_TFLOPS,
-                "unit": "TFLOP/s", "frac": fl_f / t_fwd / 1e12 / PEAK_FP32_TFLOPS, "traffic": None}
-    roof["bwd"] = {"achieved": fl_b / t_bwd / 1e12, "frac": fl_b / t_bwd / 1e12 / roof["peak"], "unit": "TFLOP/s"}
-    roof["hbm"] = {"fwd_GBs": by_f / t_fwd / 1e9, "bwd_GBs": by_b / t_bwd / 1e9, "peak": PEAK_HBM_GBS}
+    # per-kernel device time: the library brackets each of its launches with HIP events on the launch
+    # stream (s2_trace_*); the roofline object describes the launch with the largest average duration
+    S.s2_trace_reset()
+    S.s2_trace_enable(True)
+    n_tr = max(min(args.steps, 10), 3)
+    for _ in range(n_tr):
+        step()
+    torch.cuda.synchronize()
+    S.s2_trace_enable(False)
+    per = {}
+    for name, ms, pairs in S.s2_trace_entries():
+        a = per.setdefault(name, [0.0, 0, pairs])
+        a[0] += ms
+        a[1] += 1
+    S.s2_trace_reset()
+
+    def flops_per_pair(name):
+        # algorithmic: forward 4d (QK^T, PV); dq launch 6d (s, dP, dq); dk/dv launch 4d (dk, dv)
+        return (4.0 if "fwd" in name else 6.0 if "dq" in name else 4.0) * d
+
+    peak = PEAK_BF16_TFLOPS if is_global else PEAK_FP32_TFLOPS
+    kernels = {}
+    for name, (tot, cnt, pairs) in per.items():
+        ms = tot / cnt
+        kernels[name] = {"ms": ms, "launches_per_step": cnt // n_tr, "pairs": pairs,
+                         "TFLOPs": flops_per_pair(name) * pairs / (ms * 1e-3) / 1e12 if ms > 0 else None}
+    dom = max(kernels, key=lambda n: kernels[n]["ms"])
+    ach = kernels[dom]["TFLOPs"]
+    roof = {"bound": "mfma" if is_global else "alu", "kernel": dom, "achieved": ach, "peak": peak,
+            "unit": "TFLOP/s", "frac": ach / peak, "ms": kernels[dom]["ms"],
+            "traffic": TRAFFIC_BYTES.get((args.config, dom))}
+    roof["step"] = {"fwd_TFLOPs": fl_f / t_fwd / 1e12, "bwd_TFLOPs": fl_b / t_bwd / 1e12,
+                    "fwd_frac": fl_f / t_fwd / 1e12 / peak, "bwd_frac": fl_b / t_bwd / 1e12 / peak,
+                    "fwd_GBs": by_f / t_fwd / 1e9, "bwd_GBs": by_b / t_bwd / 1e9, "hbm_peak_GBs": PEAK_HBM_GBS}
 
     res = {
         "metric": "S2 neighborhood attn fwd+bwd: out-pts*heads/s" if not is_global else
@@ -141,7 +168,7 @@ def main():
             args.config, "LG" if c["grid_type"] else "equiangular-CC", c["nlat_in"], c["nlon_in"], c["nlat_out"],
             c["nlon_out"], c["theta"], B, H, d), "pairs_per_slice": P},
         "ms_fwd": t_fwd * 1e3, "ms_bwd": t_bwd * 1e3,
-        "roofline": roof,
+        "roofline": roof, "kernels": kernels,
     }
 
     if not args.no_cpu_baseline:

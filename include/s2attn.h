@@ -154,6 +154,18 @@ int s2_attn_global_bwd(const s2_grid_t *g, int batch, int heads, int d, int dtyp
                        const void *dout, void *dq, void *dk, void *dv,
                        void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/*
+ * Per-launch timing for benchmarks (not part of the method).  While enabled, every kernel launch
+ * of the attention calls is bracketed by HIP events on the launch stream.  s2_trace_get waits for
+ * entry `index` and returns the kernel's name, its duration in ms and the number of (output, input)
+ * pairs it covered (batch and heads included); s2_trace_reset drops all entries.  Creates events,
+ * so do not enable it under graph capture.  Not thread safe.
+ */
+int s2_trace_enable(int on);   /* returns the previous setting */
+int s2_trace_count(void);
+int s2_trace_get(int index, const char **name, float *ms, double *pairs);
+void s2_trace_reset(void);
+
 /* Message for the last error on the calling thread ("" if none). */
 const char *s2_last_error(void);
 

@@ -71,6 +71,15 @@ def lib():
         L.s2_attn_global_bwd.argtypes = [_vp, _i, _i, _i, _i, ctypes.c_float, _vp, _vp, _vp, _vp, _vp, _vp,
                                          _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
         L.s2_attn_global_bwd.restype = _i
+        L.s2_trace_enable.argtypes = [_i]
+        L.s2_trace_enable.restype = _i
+        L.s2_trace_count.argtypes = []
+        L.s2_trace_count.restype = _i
+        L.s2_trace_get.argtypes = [_i, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(ctypes.c_float),
+                                   ctypes.POINTER(ctypes.c_double)]
+        L.s2_trace_get.restype = _i
+        L.s2_trace_reset.argtypes = []
+        L.s2_trace_reset.restype = None
         L.s2_last_error.argtypes = []
         L.s2_last_error.restype = ctypes.c_char_p
         _lib = L
@@ -233,3 +242,22 @@ def s2_attn_global_bwd(g, q, k, v, out, lse, dout, scale, dq=None, dk=None, dv=N
                                     v.data_ptr(), out.data_ptr(), lse.data_ptr(), dout.data_ptr(), dq.data_ptr(),
                                     dk.data_ptr(), dv.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream()))
     return dq, dk, dv
+
+
+def s2_trace_enable(on):
+    return int(lib().s2_trace_enable(1 if on else 0))
+
+
+def s2_trace_reset():
+    lib().s2_trace_reset()
+
+
+def s2_trace_entries():
+    """[(kernel name, ms, pairs)] of every launch recorded since the last reset (waits for them)."""
+    L = lib()
+    out = []
+    for i in range(L.s2_trace_count()):
+        name, ms, pairs = ctypes.c_char_p(), ctypes.c_float(), ctypes.c_double()
+        _check(L.s2_trace_get(i, ctypes.byref(name), ctypes.byref(ms), ctypes.byref(pairs)))
+        out.append((name.value.decode(), ms.value, pairs.value))
+    return out

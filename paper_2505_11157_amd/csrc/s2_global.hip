@@ -429,6 +429,7 @@ extern "C" int s2_attn_global_fwd(const s2_grid_t *g, int batch, int heads, int 
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const int nbh = batch * heads, N = g->nlat_in * g->nlon_in, Npad = g->npad_tok;
     launch_transpose(v, workspace, nbh, N, Npad, st);
+    S2TraceScope tr("global_fwd", double(nbh) * N * N, st);
     hipLaunchKernelGGL(global_fwd, dim3((N + 255) / 256, nbh), dim3(256), 0, st, static_cast<const bf16raw *>(q),
                        static_cast<const bf16raw *>(k), static_cast<const bf16raw *>(workspace), g->dev_bias_tok,
                        static_cast<bf16raw *>(out), lse, N, Npad, scale * kLog2e);
@@ -461,10 +462,14 @@ extern "C" int s2_attn_global_bwd(const s2_grid_t *g, int batch, int heads, int 
     hipLaunchKernelGGL(rowstats, dim3((Npad + 255) / 256, nbh), dim3(256), 0, st, static_cast<const bf16raw *>(dout),
                        static_cast<const bf16raw *>(out), lse, L2, Dv, N, Npad);
     const float c2 = scale * kLog2e;
+    {
+    S2TraceScope tr("global_bwd_dkdv", double(nbh) * N * N, st);
     hipLaunchKernelGGL(global_bwd_dkdv, dim3((N + 255) / 256, nbh), dim3(256), 0, st, static_cast<const bf16raw *>(q),
                        static_cast<const bf16raw *>(k), static_cast<const bf16raw *>(v),
                        static_cast<const bf16raw *>(dout), qt, got, g->dev_bias_tok, L2, Dv,
                        static_cast<bf16raw *>(dk), static_cast<bf16raw *>(dv), N, Npad, c2, scale);
+    }
+    S2TraceScope tr("global_bwd_dq", double(nbh) * N * N, st);
     hipLaunchKernelGGL(global_bwd_dq, dim3((N + 255) / 256, nbh), dim3(256), 0, st, static_cast<const bf16raw *>(q),
                        static_cast<const bf16raw *>(k), static_cast<const bf16raw *>(v),
                        static_cast<const bf16raw *>(dout), kt, g->dev_bias_tok, L2, Dv, static_cast<bf16raw *>(dq), N,

@@ -298,16 +298,20 @@ extern "C" int s2_grid_init(int grid_type, int nlat_in, int nlon_in, int nlat_ou
     // split classes: a latitude whose disk holds more than 260 * P / 2 offsets per point is split P ways
     const char *env_t = std::getenv("S2_SPLIT_T");   // experiment knob: work per part
     const long T = env_t ? std::atol(env_t) : 260;
-    auto classify = [T](int n_rows, const std::vector<int> &n, const std::vector<int> &tab, int bmax, int (&cls)[4]) {
+    auto classify = [T](int n_rows, const std::vector<int> &n, const std::vector<int> &tab, int bmax, int (&cls)[4],
+                        double (&pairs)[4], double per_entry) {
         cls[0] = cls[1] = cls[2] = cls[3] = 0;
+        pairs[0] = pairs[1] = pairs[2] = pairs[3] = 0.0;
         for (int r = 0; r < n_rows; ++r) {
             long work = 0;
             for (int b = 0; b < n[r]; ++b) work += tab[size_t(r) * bmax + b];
-            ++cls[work > 4 * T ? 0 : work > 2 * T ? 1 : work > T ? 2 : 3];
+            const int c = work > 4 * T ? 0 : work > 2 * T ? 1 : work > T ? 2 : 3;
+            ++cls[c];
+            pairs[c] += double(work) * per_entry;
         }
     };
-    classify(nlat_out, g->band_n, g->cnt, g->band_max, g->dt.fwd_cls);
-    classify(nlat_in, g->tband_n, g->tcnt, g->tband_max, g->dt.bwd_cls);
+    classify(nlat_out, g->band_n, g->cnt, g->band_max, g->dt.fwd_cls, g->dt.fwd_pairs, double(nlon_out));
+    classify(nlat_in, g->tband_n, g->tcnt, g->tband_max, g->dt.bwd_cls, g->dt.bwd_pairs, double(nlon_out));
 
     int rc = upload_tables(g);
     if (rc != S2_OK) { delete g; return rc; }

@@ -27,6 +27,8 @@ struct S2DeviceTables {
     int band_max, tband_max;
     int fwd_cls[4];           // output latitudes (in row_order) whose run list is split 8, 4, 2, 1 ways
     int bwd_cls[4];           // same for input latitudes (trow_order)
+    double fwd_pairs[4];      // (output, input) pairs per slice handled by each class of output latitudes
+    double bwd_pairs[4];      // the same pairs counted per class of input latitudes
     int nlat_in, nlon_in, nlat_out, nlon_out, pscale;
     float ln_omega_ref;       // ln(max omega): the stored logsumexp is relative to the true omega
     float omega_ref;          // max omega
@@ -51,6 +53,16 @@ struct s2_grid {
     int npad_tok = 0;
     const float *dev_bias_tok = nullptr;
     S2DeviceTables dt{};
+};
+
+// Optional per-launch timing (s2_trace_* in the C ABI): when enabled, a scope records a HIP event
+// before and after the launches it encloses, on the stream they go to.
+void s2_trace_begin(const char *name, double pairs, hipStream_t st);
+void s2_trace_end(hipStream_t st);
+struct S2TraceScope {
+    hipStream_t st;
+    S2TraceScope(const char *name, double pairs, hipStream_t s) : st(s) { s2_trace_begin(name, pairs, s); }
+    ~S2TraceScope() { s2_trace_end(st); }
 };
 
 void s2_set_error(const std::string &msg);

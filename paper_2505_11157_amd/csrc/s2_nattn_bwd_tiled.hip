@@ -807,10 +807,12 @@ int s2_nattn_bwd_tiled(const S2DeviceTables &t, int nbh, int d, int e, float sca
                     return -1;
                 cfg = true;
             }
+            S2TraceScope tr("nattn_bwd_dq_tiled<8 waves>", nbh * (t.fwd_pairs[0] + t.fwd_pairs[1] + t.fwd_pairs[2]), st);
             hipLaunchKernelGGL(k8, dim3((unsigned)nblk), dim3(64 * kWavesB), lds, st, t, nbh, 1, scale, q, k, v, o, lse,
                                go, dq, Dws);
         }
         const long nrows = t.nlat_out - nsplit_o;
+        S2TraceScope tr("nattn_bwd_dq_tiled<1 wave>", nbh * t.fwd_pairs[3], st);
         if (nrows > 0)
             hipLaunchKernelGGL(k1, dim3((unsigned)(nrows * nbh * nseg_o)), dim3(64), lds_wave, st, t, nbh, nsplit_o,
                                scale, q, k, v, o, lse, go, dq, Dws);
@@ -841,10 +843,12 @@ int s2_nattn_bwd_tiled(const S2DeviceTables &t, int nbh, int d, int e, float sca
                     return -1;
                 cfg_kv2 = true;
             }
+            S2TraceScope tr("nattn_bwd_dkdv2_tiled<8 waves>", nbh * (t.bwd_pairs[0] + t.bwd_pairs[1] + t.bwd_pairs[2]), st);
             hipLaunchKernelGGL(k8, dim3((unsigned)nblk), dim3(64 * kWavesB), lds, st, t, nbh, 1, scale, q, k, v, lse,
                                go, Dws, dk, dv);
         }
         const long nrows = t.nlat_in - nsplit_i;
+        S2TraceScope tr("nattn_bwd_dkdv2_tiled<1 wave>", nbh * t.bwd_pairs[3], st);
         if (nrows > 0)
             hipLaunchKernelGGL((nattn_bwd_dkdv2_tiled<1>), dim3((unsigned)(nrows * nbh * nseg_i)), dim3(64), lds_wave,
                                st, t, nbh, nsplit_i, scale, q, k, v, lse, go, Dws, dk, dv);
@@ -866,10 +870,12 @@ int s2_nattn_bwd_tiled(const S2DeviceTables &t, int nbh, int d, int e, float sca
                 return -1;
             cfg_kv = true;
         }
+        S2TraceScope tr("nattn_bwd_dkdv_tiled<8 waves>", nbh * (t.bwd_pairs[0] + t.bwd_pairs[1] + t.bwd_pairs[2]), st);
         hipLaunchKernelGGL(k8, dim3((unsigned)nblk), dim3(64 * kWavesB), lds, st, t, nbh, 1, scale, q, k, v, lse, go,
                            Dws, dk, dv);
     }
     const long nrows = t.nlat_in - nsplit_i;
+    S2TraceScope tr("nattn_bwd_dkdv_tiled<1 wave>", nbh * t.bwd_pairs[3], st);
     if (nrows > 0)
         hipLaunchKernelGGL((nattn_bwd_dkdv_tiled<1>), dim3((unsigned)(nrows * nbh * nseg_i)), dim3(64), lds_wave, st, t,
                            nbh, nsplit_i, scale, q, k, v, lse, go, Dws, dk, dv);

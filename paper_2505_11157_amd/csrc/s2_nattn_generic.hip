@@ -248,6 +248,7 @@ int launch_fwd(const S2DeviceTables &t, int nbh, int d, int e, float scale, cons
 {
     const int ntile = (t.nlon_out + 63) / 64;
     const long nblk = long(ntile) * nbh * t.nlat_out;
+    S2TraceScope tr("nattn_fwd_generic", nbh * (t.fwd_pairs[0] + t.fwd_pairs[1] + t.fwd_pairs[2] + t.fwd_pairs[3]), st);
     hipLaunchKernelGGL(nattn_fwd_generic<DMAX>, dim3((unsigned)nblk), dim3(64), 0, st, t, nbh, d, e,
                        scale * 1.4426950408889634f, q, k, v, out, lse);
     return 0;
@@ -259,8 +260,12 @@ int launch_bwd(const S2DeviceTables &t, int nbh, int d, int e, float scale, cons
                float *Dws, hipStream_t st)
 {
     const int nto = (t.nlon_out + 63) / 64, nti = (t.nlon_in + 63) / 64;
+    {
+    S2TraceScope tr("nattn_bwd_dq_generic", nbh * (t.fwd_pairs[0] + t.fwd_pairs[1] + t.fwd_pairs[2] + t.fwd_pairs[3]), st);
     hipLaunchKernelGGL(nattn_bwd_dq_generic<DMAX>, dim3((unsigned)(long(nto) * nbh * t.nlat_out)), dim3(64), 0, st,
                        t, nbh, d, e, scale, q, k, v, o, lse, go, dq, Dws);
+    }
+    S2TraceScope tr("nattn_bwd_dkdv_generic", nbh * (t.fwd_pairs[0] + t.fwd_pairs[1] + t.fwd_pairs[2] + t.fwd_pairs[3]), st);
     hipLaunchKernelGGL(nattn_bwd_dkdv_generic<DMAX>, dim3((unsigned)(long(nti) * nbh * t.nlat_in)), dim3(64), 0, st,
                        t, nbh, d, e, scale, q, k, v, lse, go, Dws, dk, dv);
     return 0;
@@ -272,6 +277,7 @@ int launch_dkdv(const S2DeviceTables &t, int nbh, int d, int e, float scale, con
                 hipStream_t st)
 {
     const int nti = (t.nlon_in + 63) / 64;
+    S2TraceScope tr("nattn_bwd_dkdv_generic", nbh * (t.fwd_pairs[0] + t.fwd_pairs[1] + t.fwd_pairs[2] + t.fwd_pairs[3]), st);
     hipLaunchKernelGGL(nattn_bwd_dkdv_generic<DMAX>, dim3((unsigned)(long(nti) * nbh * t.nlat_in)), dim3(64), 0, st,
                        t, nbh, d, e, scale, q, k, v, lse, go, Dws, dk, dv);
     return 0;

@@ -404,6 +404,8 @@ int launch_fwd_tiled(const S2DeviceTables &t, int nbh, float qscale, const float
                 return -1;
             configured = true;
         }
+        S2TraceScope tr("nattn_fwd_tiled<8 waves>",
+                        nbh * (t.fwd_pairs[0] + t.fwd_pairs[1] + t.fwd_pairs[2] + (first_row ? 0.0 : t.fwd_pairs[3])), st);
         hipLaunchKernelGGL(kern, dim3((unsigned)nblk), dim3(64 * kWaves), lds, st, t, nbh, first_row, qscale, q, k, v,
                            out, lse);
         if (mode == 2) return 0;
@@ -411,9 +413,12 @@ int launch_fwd_tiled(const S2DeviceTables &t, int nbh, float qscale, const float
     // the rest: one wavefront per workgroup
     const int first_row = mode == 1 ? 0 : nsplit;
     const long nrows = t.nlat_out - first_row;
-    if (nrows > 0)
+    if (nrows > 0) {
+        S2TraceScope tr("nattn_fwd_tiled<1 wave>",
+                        nbh * (t.fwd_pairs[3] + (mode == 1 ? t.fwd_pairs[0] + t.fwd_pairs[1] + t.fwd_pairs[2] : 0.0)), st);
         hipLaunchKernelGGL((nattn_fwd_tiled<D, PS, 1>), dim3((unsigned)(nrows * nbh * nseg)), dim3(64),
                            2 * Geo<PS>::TILE * sizeof(float), st, t, nbh, first_row, qscale, q, k, v, out, lse);
+    }
     return 0;
 }
 

@@ -111,6 +111,18 @@ def test_deterministic_and_roll_equivariant():
         assert np.array_equal(np.roll(a, 1, axis=-1), b)   # shift invariance in longitude is exact
 
 
+@pytest.mark.parametrize("cfg", [3, 4])
+def test_bit_reproducible_full_configs(cfg):
+    # every kernel of the tuned path (staged windows, split latitudes merged through LDS) must give
+    # identical bits run after run: there are no atomics and no order-dependent reductions
+    c, arrs = make_inputs(cfg)
+    ref = run_case(c, arrs, [])
+    for _ in range(3):
+        again = run_case(c, arrs, [])
+        for a, b in zip(ref, again):
+            assert np.array_equal(a, b)
+
+
 def test_errors_on_device():
     gd = grid_dict(1)
     g = _grid(gd)
