@@ -206,18 +206,18 @@ __device__ __forceinline__ void run_chunk_dq(float *buf0, float *buf1, const flo
 
     stage_issue<PS>(kb, si, so, buf0, ta);
     // s = q . K
+    wait_vm<0>(); tail_store<PS>(buf0, lg.taddr, ta);
     stage_issue<PS>(k1, si, so, buf1, tb);
-    wait_vm<G::NLOAD>(); tail_store<PS>(buf0, lg.taddr, ta);
     dot_stage<PS, NT>(buf0, lg.sbase, q, 0, s);
+    wait_vm<0>(); tail_store<PS>(buf1, lg.taddr, tb);
     stage_issue<PS>(vb, si, so, buf0, ta);
-    wait_vm<G::NLOAD>(); tail_store<PS>(buf1, lg.taddr, tb);
     dot_stage<PS, NT>(buf1, lg.sbase, q, kCGB, s);
     // dP = dout . V
+    wait_vm<0>(); tail_store<PS>(buf0, lg.taddr, ta);
     stage_issue<PS>(v1, si, so, buf1, tb);
-    wait_vm<G::NLOAD>(); tail_store<PS>(buf0, lg.taddr, ta);
     dot_stage<PS, NT>(buf0, lg.sbase, go, 0, dp);
+    wait_vm<0>(); tail_store<PS>(buf1, lg.taddr, tb);
     stage_issue<PS>(kb, si, so, buf0, ta);
-    wait_vm<G::NLOAD>(); tail_store<PS>(buf1, lg.taddr, tb);
     dot_stage<PS, NT>(buf1, lg.sbase, go, kCGB, dp);
     // dS = p (dP - D)
 #pragma unroll
@@ -228,8 +228,8 @@ __device__ __forceinline__ void run_chunk_dq(float *buf0, float *buf1, const flo
             s[r][tt] = wq * __builtin_amdgcn_exp2f(sv - lse2[r]) * (dv - Dr[r]);
         }
     // dq += dS K
+    wait_vm<0>(); tail_store<PS>(buf0, lg.taddr, ta);
     stage_issue<PS>(k1, si, so, buf1, tb);
-    wait_vm<G::NLOAD>(); tail_store<PS>(buf0, lg.taddr, ta);
     axpy_stage<PS, NT>(buf0, lg.sbase, s, 0, dq);
     wait_vm<0>(); tail_store<PS>(buf1, lg.taddr, tb);
     axpy_stage<PS, NT>(buf1, lg.sbase, s, kCGB, dq);
@@ -422,19 +422,19 @@ __device__ __forceinline__ void run_chunk_dkdv(float *buf0, float *buf1, float *
 
     stage_issue<1>(qb, so, of, buf0, ta);
     // s = k . Q
+    wait_vm<0>(); tail_store<1>(buf0, lg.taddr, ta);
     stage_issue<1>(q1, so, of, buf1, tb);
-    wait_vm<G::NLOAD>(); tail_store<1>(buf0, lg.taddr, ta);
     aux[((lane >> 3) & 1) * G::PITCH + 64 + (lane & 7)] = atail;
     dot_stage<1, NT>(buf0, lg.sbase, kr, 0, s);
+    wait_vm<0>(); tail_store<1>(buf1, lg.taddr, tb);
     stage_issue<1>(gb, so, of, buf0, ta);
-    wait_vm<G::NLOAD>(); tail_store<1>(buf1, lg.taddr, tb);
     dot_stage<1, NT>(buf1, lg.sbase, kr, kCGB, s);
     // dP = v . dout
+    wait_vm<0>(); tail_store<1>(buf0, lg.taddr, ta);
     stage_issue<1>(g1, so, of, buf1, tb);
-    wait_vm<G::NLOAD>(); tail_store<1>(buf0, lg.taddr, ta);
     dot_stage<1, NT>(buf0, lg.sbase, vr, 0, dp);
+    wait_vm<0>(); tail_store<1>(buf1, lg.taddr, tb);
     stage_issue<1>(qb, so, of, buf0, ta);
-    wait_vm<G::NLOAD>(); tail_store<1>(buf1, lg.taddr, tb);
     dot_stage<1, NT>(buf1, lg.sbase, vr, kCGB, dp);
     // p = omega exp2(s - lse2_i), dS = p (dP - D_i): lse and D of output column (own column + r + t)
     {
@@ -460,14 +460,14 @@ __device__ __forceinline__ void run_chunk_dkdv(float *buf0, float *buf1, float *
             }
     }
     // dk += dS Q ; dv += p dout
+    wait_vm<0>(); tail_store<1>(buf0, lg.taddr, ta);
     stage_issue<1>(q1, so, of, buf1, tb);
-    wait_vm<G::NLOAD>(); tail_store<1>(buf0, lg.taddr, ta);
     axpy_stage<1, NT>(buf0, lg.sbase, dp, 0, dk);
+    wait_vm<0>(); tail_store<1>(buf1, lg.taddr, tb);
     stage_issue<1>(gb, so, of, buf0, ta);
-    wait_vm<G::NLOAD>(); tail_store<1>(buf1, lg.taddr, tb);
     axpy_stage<1, NT>(buf1, lg.sbase, dp, kCGB, dk);
+    wait_vm<0>(); tail_store<1>(buf0, lg.taddr, ta);
     stage_issue<1>(g1, so, of, buf1, tb);
-    wait_vm<G::NLOAD>(); tail_store<1>(buf0, lg.taddr, ta);
     axpy_stage<1, NT>(buf0, lg.sbase, s, 0, dv);
     wait_vm<0>(); tail_store<1>(buf1, lg.taddr, tb);
     axpy_stage<1, NT>(buf1, lg.sbase, s, kCGB, dv);
@@ -642,14 +642,18 @@ __device__ __forceinline__ void run_chunk_dkdv2(float *buf0, float *buf1, float 
     __builtin_amdgcn_global_load_lds((gptr_t)(reinterpret_cast<const char *>(drow) + vo), (lptr_t)(aux + kPitch2), 4, 0, 0);
     const float *q1 = qb + size_t(kCGB) * so, *g1 = gb + size_t(kCGB) * so;
     stage_issue2(qb, so, voff, buf0);
+    wait_vm<0>();
     stage_issue2(q1, so, voff, buf1);
-    wait_vm<16>(); dot_stage2<NT>(buf0, sbase, kr, 0, s);
+    dot_stage2<NT>(buf0, sbase, kr, 0, s);
+    wait_vm<0>();
     stage_issue2(gb, so, voff, buf0);
-    wait_vm<16>(); dot_stage2<NT>(buf1, sbase, kr, kCGB, s);
+    dot_stage2<NT>(buf1, sbase, kr, kCGB, s);
+    wait_vm<0>();
     stage_issue2(g1, so, voff, buf1);
-    wait_vm<16>(); dot_stage2<NT>(buf0, sbase, vr, 0, dp);
+    dot_stage2<NT>(buf0, sbase, vr, 0, dp);
+    wait_vm<0>();
     stage_issue2(qb, so, voff, buf0);
-    wait_vm<16>(); dot_stage2<NT>(buf1, sbase, vr, kCGB, dp);
+    dot_stage2<NT>(buf1, sbase, vr, kCGB, dp);
     {
         float ls[NT + 2], ds[NT + 2];
         read_strip2<NT>(aux + abase, ls);
@@ -666,12 +670,15 @@ __device__ __forceinline__ void run_chunk_dkdv2(float *buf0, float *buf1, float 
                 dp[r][tt] = p * (dv2 - ds[(r >> 1) + tt]);
             }
     }
+    wait_vm<0>();
     stage_issue2(q1, so, voff, buf1);
-    wait_vm<16>(); axpy_stage2<NT>(buf0, sbase, dp, 0, dk);
+    axpy_stage2<NT>(buf0, sbase, dp, 0, dk);
+    wait_vm<0>();
     stage_issue2(gb, so, voff, buf0);
-    wait_vm<16>(); axpy_stage2<NT>(buf1, sbase, dp, kCGB, dk);
+    axpy_stage2<NT>(buf1, sbase, dp, kCGB, dk);
+    wait_vm<0>();
     stage_issue2(g1, so, voff, buf1);
-    wait_vm<16>(); axpy_stage2<NT>(buf0, sbase, s, 0, dv);
+    axpy_stage2<NT>(buf0, sbase, s, 0, dv);
     wait_vm<0>(); axpy_stage2<NT>(buf1, sbase, s, kCGB, dv);
 }
 

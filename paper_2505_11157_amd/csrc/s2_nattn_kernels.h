@@ -23,3 +23,9 @@ bool s2_nattn_bwd_tiled_supported(const S2DeviceTables &t, int d, int e);
 int s2_nattn_bwd_tiled(const S2DeviceTables &t, int nbh, int d, int e, float scale, const float *q, const float *k,
                        const float *v, const float *o, const float *lse, const float *go, float *dq, float *dk,
                        float *dv, float *Dws, hipStream_t st);
+
+// Forward on the fp32 matrix cores for the heaviest output latitudes (dense neighborhoods near the
+// poles): number of leading latitudes of row_order it takes (0 if the shape does not qualify), and the launch.
+int s2_nattn_fwd_mfma_rows(const S2DeviceTables &t, int d, int e);
+int s2_nattn_fwd_mfma(const S2DeviceTables &t, int nbh, int nrows, float scale, const float *q, const float *k,
+                      const float *v, float *out, float *lse, hipStream_t st);

@@ -1,0 +1,197 @@
+// Neighborhood attention forward for the latitudes near the poles, on the fp32 matrix cores.
+//
+// Near a pole the geodesic disk covers whole latitude circles (App. B.3: the indicator row is
+// all ones), so for those output latitudes the neighborhood sum IS a dense contraction: every
+// output of the row against every input column of 5..9 input rows.  That part of the path runs
+// as a flash-style kernel on v_mfma_f32_32x32x2_f32 (products and sums in float32, same
+// arithmetic class as the vector path); partial arcs in the same band are handled by masking.
+// The rest of the sphere, where a disk cuts ~9 of 256 columns, stays on the vector ALU.
+//
+// One workgroup = one (batch, head, output latitude); one wavefront = 32 consecutive outputs.
+// Input rows are streamed as super-tiles of 64 columns x 32 channels of K and V, staged once
+// per workgroup in LDS (LDS-direct loads, double buffered) and shared by all wavefronts.
+//
+//   S^T = K Q^T   two 32x32 tiles (64 inputs x 32 outputs), 16 MFMAs each (2 channels per MFMA)
+//   O^T += V^T P^T  32 MFMAs (2 input columns per MFMA)
+//
+// Tile row r of S^T tile mt is mapped to super-tile column 32*((r>>2)&1) + 16*mt + 4*(r>>3) + (r&3):
+// in the result layout lane (output, half hl) then holds columns 32*hl + 16*mt + i in register i, so
+// the probabilities feed the second product straight from registers, and the two halves of a
+// wavefront read LDS columns 32 apart (disjoint banks).
+#include <cstdlib>
+
+#include "s2_nattn_kernels.h"
+
+namespace {
+
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((address_space(1))) const void *gptr_t;
+typedef __attribute__((address_space(3))) void *lptr_t;
+
+constexpr int kD = 32;          // channels
+constexpr int kTileCols = 64;   // input columns per super-tile
+constexpr int kPK = 80;         // K tile pitch: = 16 mod 64, the two channel rows of one MFMA step hit disjoint banks
+constexpr int kPV = 65;         // V tile pitch: odd, the 32 channel rows read by one wavefront hit 32 banks
+constexpr int kTileFloats = kD * kPK + kD * kPV;
+
+__device__ __forceinline__ f32x16 mfma(float a, float b, f32x16 c)
+{
+    return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ int wrapn(int x, int n)
+{
+    x = x < 0 ? x + n : x;
+    return x >= n ? x - n : x;
+}
+
+// Each wavefront copies its share of the 64 channel rows (K: 0..31, V: 32..63) of super-tile
+// columns x0 .. x0+63 (mod nlon) of input latitude hp: lane = column.
+__device__ __forceinline__ void stage_tile(const float *kb, const float *vb, size_t si, int x0, int nlon, float *tile,
+                                           int wave, int nwaves, int lane)
+{
+    const unsigned voff = 4u * unsigned(wrapn(x0 + lane, nlon));
+    for (int r = wave; r < 2 * kD; r += nwaves) {
+        const bool isv = r >= kD;
+        const int c = isv ? r - kD : r;
+        const char *rb = reinterpret_cast<const char *>((isv ? vb : kb) + size_t(c) * si);
+        float *dst = isv ? tile + kD * kPK + c * kPV : tile + c * kPK;
+        __builtin_amdgcn_global_load_lds((gptr_t)(rb + voff), (lptr_t)dst, 4, 0, 0);
+    }
+}
+
+__global__ void __launch_bounds__(1024)
+nattn_fwd_mfma(S2DeviceTables t, int nbh, int nrows, float qscale, const float *__restrict__ q,
+               const float *__restrict__ k, const float *__restrict__ v, float *__restrict__ out,
+               float *__restrict__ lse)
+{
+    extern __shared__ __attribute__((aligned(16))) float smem[];
+    const int nwaves = blockDim.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int col = lane & 31, hl = lane >> 5;
+    const int nlon = t.nlon_in;                       // equal longitude counts
+    const int bh = blockIdx.x / nrows;
+    const int h = t.row_order[blockIdx.x - bh * nrows];
+    const int w = wave * 32 + col;                    // this lane's output longitude
+    const size_t so = size_t(t.nlat_out) * t.nlon_out, si = size_t(t.nlat_in) * t.nlon_in;
+    const size_t io = size_t(h) * t.nlon_out + w;
+
+    // B operand of S^T = K Q^T: lane (output, hl) supplies channel 2s + hl at step s
+    float qop[16];
+#pragma unroll
+    for (int s = 0; s < 16; ++s) qop[s] = q[(size_t(bh) * kD + 2 * s + hl) * so + io] * qscale;
+    f32x16 o = {0};
+    float m = -INFINITY, l = 0.f;
+    // LDS column (within a super-tile) of S^T tile row `col`, tile mt = 0: see header
+    const int arow = 32 * ((col >> 2) & 1) + 4 * (col >> 3) + (col & 3);
+
+    const int nb = t.band_n[h], hp0 = t.band_lo[h];
+    const int ntile = nlon / kTileCols;
+    const int total = nb * ntile;
+    // prologue: stage the first super-tile
+    {
+        const float *kb = k + size_t(bh) * kD * si + size_t(hp0) * nlon;
+        const float *vb = v + size_t(bh) * kD * si + size_t(hp0) * nlon;
+        stage_tile(kb, vb, si, 0, nlon, smem, wave, nwaves, lane);
+    }
+    for (int it = 0; it < total; ++it) {
+        const int b = it / ntile, x0 = (it - b * ntile) * kTileCols;
+        const int hp = hp0 + b;
+        float *tile = smem + (it & 1) * kTileFloats;
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();     // tile `it` is complete; everyone has finished reading tile it-1
+        if (it + 1 < total) {
+            const int b2 = (it + 1) / ntile, x2 = (it + 1 - b2 * ntile) * kTileCols;
+            const float *kb = k + size_t(bh) * kD * si + size_t(hp0 + b2) * nlon;
+            const float *vb = v + size_t(bh) * kD * si + size_t(hp0 + b2) * nlon;
+            stage_tile(kb, vb, si, x2, nlon, smem + ((it + 1) & 1) * kTileFloats, wave, nwaves, lane);
+        }
+        const int c = t.cnt[h * t.band_max + b];
+        const bool full = c == nlon;
+        const int lo = full ? 0 : -((c - 1) >> 1);
+        // does this wavefront's span of outputs touch the super-tile at all?
+        if (!full) {
+            // columns needed by outputs wave*32 .. wave*32+31: [wave*32 + lo, wave*32 + 31 + lo + c) on the circle
+            const int need0 = wrapn(wave * 32 + lo, nlon), len = c + 31;
+            const int rel = wrapn(x0 - need0, nlon);          // tile start relative to the needed range
+            const bool overlap = rel < len || rel + kTileCols > nlon;
+            if (!overlap) continue;
+        }
+        const float wq = t.omega_rel[hp];
+        const float *tk = tile, *tv = tile + kD * kPK;
+        f32x16 s0 = {0}, s1 = {0};
+#pragma unroll
+        for (int s = 0; s < 16; ++s) {
+            const float a0 = tk[(2 * s + hl) * kPK + arow], a1 = tk[(2 * s + hl) * kPK + arow + 16];
+            s0 = mfma(a0, qop[s], s0);
+            s1 = mfma(a1, qop[s], s1);
+        }
+        float p[32];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) { p[i] = s0[i]; p[16 + i] = s1[i]; }
+        if (!full) {
+            // register i of tile mt is super-tile column 32*hl + 16*mt + i; valid iff its offset from the
+            // output's own longitude lies in [lo, lo + c)
+            const int base = (x0 + 32 * hl - w - lo + 2 * nlon) % nlon;
+#pragma unroll
+            for (int i = 0; i < 32; ++i) {
+                int rel = base + i;           // (16*mt + i) is just i for i in 0..31
+                rel = rel >= nlon ? rel - nlon : rel;
+                p[i] = rel < c ? p[i] : -INFINITY;
+            }
+        }
+        float mloc = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < 32; ++i) mloc = fmaxf(mloc, p[i]);
+        mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
+        if (__any(mloc > m + 8.f)) {
+            const float m_new = mloc > m + 8.f ? mloc : m;
+            // m = -inf until this output has seen a valid column: then corr = 0 (or 1 while it still has none)
+            const float corr = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(m - m_new);
+            m = m_new;
+            l *= corr;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) o[i] *= corr;
+        }
+        const float mm = m == -INFINITY ? 0.f : m;   // all 64 columns masked for this output so far: p = exp2(-inf) = 0
+#pragma unroll
+        for (int i = 0; i < 32; ++i) {
+            p[i] = wq * __builtin_amdgcn_exp2f(p[i] - mm);
+            l += p[i];
+        }
+        // O^T += V^T P^T: step i contracts super-tile columns (32*hl + i); A = V[channel = col][that column]
+#pragma unroll
+        for (int i = 0; i < 32; ++i) o = mfma(tv[col * kPV + 32 * hl + i], p[i], o);
+    }
+    l += __shfl_xor(l, 32);
+    const float inv = 1.f / l;
+    // lane (output, hl) holds channels 8*(i/4) + 4*hl + i%4 in register i
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int ch = 8 * (i >> 2) + 4 * hl + (i & 3);
+        out[(size_t(bh) * kD + ch) * so + io] = o[i] * inv;
+    }
+    if (hl == 0) lse[size_t(bh) * so + io] = (m + log2f(l * t.omega_ref)) * 0.6931471805599453f;
+}
+
+}  // namespace
+
+// latitudes whose disk holds more than 520 points per output (the two heaviest classes) take the matrix-core path
+int s2_nattn_fwd_mfma_rows(const S2DeviceTables &t, int d, int e)
+{
+    const int nw = t.nlon_out / 32;
+    if (d != 32 || e != 32 || t.pscale != 1 || t.nlon_in % kTileCols != 0 || t.nlon_out % 32 != 0 || nw < 2 || nw > 16)
+        return 0;
+    if (std::getenv("S2_NO_MFMA")) return 0;
+    return t.fwd_cls[0] + t.fwd_cls[1];
+}
+
+int s2_nattn_fwd_mfma(const S2DeviceTables &t, int nbh, int nrows, float scale, const float *q, const float *k,
+                      const float *v, float *out, float *lse, hipStream_t st)
+{
+    const size_t lds = 2 * size_t(kTileFloats) * sizeof(float);
+    S2TraceScope tr("nattn_fwd_mfma", nbh * (t.fwd_pairs[0] + t.fwd_pairs[1]), st);
+    hipLaunchKernelGGL(nattn_fwd_mfma, dim3((unsigned)(long(nrows) * nbh)), dim3(t.nlon_out * 2), lds, st, t, nbh, nrows,
+                       scale * 1.4426950408889634f, q, k, v, out, lse);
+    return 0;
+}

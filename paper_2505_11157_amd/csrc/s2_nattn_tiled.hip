@@ -140,15 +140,17 @@ __device__ __forceinline__ void run_chunk(float *buf0, float *buf1, const float 
     unsigned voff[G::NFULL + 1];
     stage_offsets<PS>(x0, xt, nlon_in, trow, voff);
 
-    float tail = stage_issue<D, PS>(kb, si, voff, buf0), tail_next = 0.f;
+    float tail = stage_issue<D, PS>(kb, si, voff, buf0);
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
         float *cur = (g & 1) ? buf1 : buf0, *nxt = (g & 1) ? buf0 : buf1;
-        if (g + 1 < NG) tail_next = stage_issue<D, PS>(kb + size_t(g + 1) * kCG * si, si, voff, nxt);
-        else tail_next = stage_issue<D, PS>(vb, si, voff, nxt);
-        wait_vm<G::NLOAD>();
+        // everything in flight (this stage) must have landed before the next stage is requested: the
+        // counter is waited down to zero because LDS-direct loads and ordinary loads (the tail, register
+        // spills) are not guaranteed to complete in issue order relative to each other
+        wait_vm<0>();
         cur[taddr] = tail;
-        tail = tail_next;
+        if (g + 1 < NG) tail = stage_issue<D, PS>(kb + size_t(g + 1) * kCG * si, si, voff, nxt);
+        else tail = stage_issue<D, PS>(vb, si, voff, nxt);
 #pragma unroll
         for (int cc = 0; cc < kCG; ++cc) {
             float st[4 * SL4];
@@ -193,14 +195,9 @@ __device__ __forceinline__ void run_chunk(float *buf0, float *buf1, const float 
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
         float *cur = (g & 1) ? buf1 : buf0, *nxt = (g & 1) ? buf0 : buf1;
-        if (g + 1 < NG) {
-            tail_next = stage_issue<D, PS>(vb + size_t(g + 1) * kCG * si, si, voff, nxt);
-            wait_vm<G::NLOAD>();
-        } else {
-            wait_vm<0>();
-        }
+        wait_vm<0>();
         cur[taddr] = tail;
-        tail = tail_next;
+        if (g + 1 < NG) tail = stage_issue<D, PS>(vb + size_t(g + 1) * kCG * si, si, voff, nxt);
 #pragma unroll
         for (int cc = 0; cc < kCG; ++cc) {
             float st[4 * SL4];
@@ -382,9 +379,9 @@ nattn_fwd_tiled(S2DeviceTables t, int nbh, int first_row, float qscale, const fl
 }
 
 template <int D, int PS>
-int launch_fwd_tiled(const S2DeviceTables &t, int nbh, float qscale, const float *q, const float *k, const float *v,
-                     float *out, float *lse, hipStream_t st)
-{
+int launch_fwd_tiled(const S2DeviceTables &t, int skip_rows, int nbh, float qscale, const float *q, const float *k,
+                     const float *v, float *out, float *lse, hipStream_t st)
+{   // t.row_order already points past the skip_rows latitudes another kernel has taken
     const int nseg = (t.nlon_out + kSeg - 1) / kSeg;
     const int nsplit = t.fwd_cls[0] + t.fwd_cls[1] + t.fwd_cls[2];   // latitudes split over several wavefronts
     const char *env = std::getenv("S2_FWD_MODE");                    // experiment knob
@@ -412,7 +409,7 @@ int launch_fwd_tiled(const S2DeviceTables &t, int nbh, float qscale, const float
     }
     // the rest: one wavefront per workgroup
     const int first_row = mode == 1 ? 0 : nsplit;
-    const long nrows = t.nlat_out - first_row;
+    const long nrows = t.nlat_out - skip_rows - first_row;
     if (nrows > 0) {
         S2TraceScope tr("nattn_fwd_tiled<1 wave>",
                         nbh * (t.fwd_pairs[3] + (mode == 1 ? t.fwd_pairs[0] + t.fwd_pairs[1] + t.fwd_pairs[2] : 0.0)), st);
@@ -433,8 +430,16 @@ bool s2_nattn_fwd_tiled_supported(const S2DeviceTables &t, int d, int e)
 int s2_nattn_fwd_tiled(const S2DeviceTables &t, int nbh, int d, int e, float scale, const float *q, const float *k,
                        const float *v, float *out, float *lse, hipStream_t st)
 {
-    (void)d; (void)e;
     const float qscale = scale * 1.4426950408889634f;
-    if (t.pscale == 1) return launch_fwd_tiled<32, 1>(t, nbh, qscale, q, k, v, out, lse, st);
-    return launch_fwd_tiled<32, 2>(t, nbh, qscale, q, k, v, out, lse, st);
+    // dense polar latitudes go to the matrix-core kernel; the vector kernels see the remaining latitudes
+    S2DeviceTables tv = t;
+    const int nm = s2_nattn_fwd_mfma_rows(t, d, e);
+    if (nm > 0) {
+        s2_nattn_fwd_mfma(t, nbh, nm, scale, q, k, v, out, lse, st);
+        tv.row_order = t.row_order + nm;
+        tv.fwd_cls[0] = tv.fwd_cls[1] = 0;
+        tv.fwd_pairs[0] = tv.fwd_pairs[1] = 0.0;
+    }
+    if (t.pscale == 1) return launch_fwd_tiled<32, 1>(tv, nm, nbh, qscale, q, k, v, out, lse, st);
+    return launch_fwd_tiled<32, 2>(tv, nm, nbh, qscale, q, k, v, out, lse, st);
 }
