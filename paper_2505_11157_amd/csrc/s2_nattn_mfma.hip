@@ -176,21 +176,21 @@ nattn_fwd_mfma(S2DeviceTables t, int nbh, int nrows, float qscale, const float *
 
 }  // namespace
 
-// latitudes whose disk holds more than 520 points per output (the two heaviest classes) take the matrix-core path
+// latitudes whose disk holds more than 260 points per output (the three heaviest classes) take the matrix-core path
 int s2_nattn_fwd_mfma_rows(const S2DeviceTables &t, int d, int e)
 {
     const int nw = t.nlon_out / 32;
     if (d != 32 || e != 32 || t.pscale != 1 || t.nlon_in % kTileCols != 0 || t.nlon_out % 32 != 0 || nw < 2 || nw > 16)
         return 0;
     if (std::getenv("S2_NO_MFMA")) return 0;
-    return t.fwd_cls[0] + t.fwd_cls[1];
+    return t.fwd_cls[0] + t.fwd_cls[1] + t.fwd_cls[2];
 }
 
 int s2_nattn_fwd_mfma(const S2DeviceTables &t, int nbh, int nrows, float scale, const float *q, const float *k,
                       const float *v, float *out, float *lse, hipStream_t st)
 {
     const size_t lds = 2 * size_t(kTileFloats) * sizeof(float);
-    S2TraceScope tr("nattn_fwd_mfma", nbh * (t.fwd_pairs[0] + t.fwd_pairs[1]), st);
+    S2TraceScope tr("nattn_fwd_mfma", nbh * (t.fwd_pairs[0] + t.fwd_pairs[1] + t.fwd_pairs[2]), st);
     hipLaunchKernelGGL(nattn_fwd_mfma, dim3((unsigned)(long(nrows) * nbh)), dim3(t.nlon_out * 2), lds, st, t, nbh, nrows,
                        scale * 1.4426950408889634f, q, k, v, out, lse);
     return 0;
