@@ -798,13 +798,21 @@ int s2_nattn_bwd_tiled(const S2DeviceTables &t, int nbh, int d, int e, float sca
 {
     const int nseg_o = (t.nlon_out + kSegB - 1) / kSegB;
     static bool cfg_dq1 = false, cfg_dq2 = false, cfg_kv = false;
-    // the two launches of a kernel pair differ only in which latitudes they take: first_row = 1 tells the
-    // 8-wave kernel to skip the unsplit class, first_row = nsplit tells the 1-wave kernel where its rows start
-    const int nsplit_o = t.fwd_cls[0] + t.fwd_cls[1] + t.fwd_cls[2];
+    // dense polar latitudes: dq on the matrix cores; the vector kernels see the remaining latitudes
+    const S2DeviceTables &t_all = t;
+    S2DeviceTables t_dq = t_all;
+    const int nm = s2_nattn_fwd_mfma_rows(t_all, d, e);
+    if (nm > 0) {
+        if (s2_nattn_bwd_dq_mfma(t_all, nbh, nm, scale, q, k, v, o, lse, go, dq, Dws, st)) return -1;
+        t_dq.row_order = t_all.row_order + nm;
+        t_dq.fwd_cls[0] = t_dq.fwd_cls[1] = t_dq.fwd_cls[2] = 0;
+        t_dq.fwd_pairs[0] = t_dq.fwd_pairs[1] = t_dq.fwd_pairs[2] = 0.0;
+    }
+    const int nsplit_o = t_dq.fwd_cls[0] + t_dq.fwd_cls[1] + t_dq.fwd_cls[2];
     auto run_dq = [&](auto k8, auto k1, size_t lds_wave, bool &cfg) {
         if (nsplit_o > 0) {
             const long nblk = long((nbh + kWavesB - 1) / kWavesB) * nseg_o *
-                              (8 * t.fwd_cls[0] + 4 * t.fwd_cls[1] + 2 * t.fwd_cls[2]);
+                              (8 * t_dq.fwd_cls[0] + 4 * t_dq.fwd_cls[1] + 2 * t_dq.fwd_cls[2]);
             size_t lds = lds_wave * kWavesB;
             const size_t mg = size_t(kWavesB / 2) * 4 * kDL * 64 * sizeof(float);
             if (lds < mg) lds = mg;
@@ -814,14 +822,14 @@ int s2_nattn_bwd_tiled(const S2DeviceTables &t, int nbh, int d, int e, float sca
                     return -1;
                 cfg = true;
             }
-            S2TraceScope tr("nattn_bwd_dq_tiled<8 waves>", nbh * (t.fwd_pairs[0] + t.fwd_pairs[1] + t.fwd_pairs[2]), st);
-            hipLaunchKernelGGL(k8, dim3((unsigned)nblk), dim3(64 * kWavesB), lds, st, t, nbh, 1, scale, q, k, v, o, lse,
+            S2TraceScope tr("nattn_bwd_dq_tiled<8 waves>", nbh * (t_dq.fwd_pairs[0] + t_dq.fwd_pairs[1] + t_dq.fwd_pairs[2]), st);
+            hipLaunchKernelGGL(k8, dim3((unsigned)nblk), dim3(64 * kWavesB), lds, st, t_dq, nbh, 1, scale, q, k, v, o, lse,
                                go, dq, Dws);
         }
-        const long nrows = t.nlat_out - nsplit_o;
-        S2TraceScope tr("nattn_bwd_dq_tiled<1 wave>", nbh * t.fwd_pairs[3], st);
+        const long nrows = t.nlat_out - nm - nsplit_o;
+        S2TraceScope tr("nattn_bwd_dq_tiled<1 wave>", nbh * t_dq.fwd_pairs[3], st);
         if (nrows > 0)
-            hipLaunchKernelGGL(k1, dim3((unsigned)(nrows * nbh * nseg_o)), dim3(64), lds_wave, st, t, nbh, nsplit_o,
+            hipLaunchKernelGGL(k1, dim3((unsigned)(nrows * nbh * nseg_o)), dim3(64), lds_wave, st, t_dq, nbh, nsplit_o,
                                scale, q, k, v, o, lse, go, dq, Dws);
         return 0;
     };

@@ -29,3 +29,6 @@ int s2_nattn_bwd_tiled(const S2DeviceTables &t, int nbh, int d, int e, float sca
 int s2_nattn_fwd_mfma_rows(const S2DeviceTables &t, int d, int e);
 int s2_nattn_fwd_mfma(const S2DeviceTables &t, int nbh, int nrows, float scale, const float *q, const float *k,
                       const float *v, float *out, float *lse, hipStream_t st);
+int s2_nattn_bwd_dq_mfma(const S2DeviceTables &t, int nbh, int nrows, float scale, const float *q, const float *k,
+                         const float *v, const float *o, const float *lse, const float *go, float *dq, float *Dws,
+                         hipStream_t st);

@@ -174,6 +174,126 @@ nattn_fwd_mfma(S2DeviceTables t, int nbh, int nrows, float qscale, const float *
     if (hl == 0) lse[size_t(bh) * so + io] = (m + log2f(l * t.omega_ref)) * 0.6931471805599453f;
 }
 
+// ------------------------------------------------------------------ backward, dq ----------
+//
+// Same tiling for dq_i = scale sum_j dS_ij k_j on the dense latitudes:
+//   S^T = K Q^T, dP^T = V dout^T (2 x 32 MFMAs), dS = p (dP - D) in registers,
+//   dQ^T += K^T-read-by-channel dS^T (32 MFMAs).
+// K is read both ways (by column for S^T, by channel for dQ^T); a pitch of 81 floats keeps both
+// patterns (almost) free of bank conflicts: 81 = 17 mod 64 is odd, so 32 channel rows hit 32 banks,
+// and the two channel rows of one S^T step are 17 banks apart.
+
+constexpr int kPB = 81;
+constexpr int kTileB = 2 * kD * kPB;     // K rows then V rows
+
+__device__ __forceinline__ void stage_tile_b(const float *ab, const float *bb, size_t stride, int x0, int ncol,
+                                             float *tile, int wave, int nwaves, int lane)
+{
+    const unsigned voff = 4u * unsigned(wrapn(x0 + lane, ncol));
+    for (int r = wave; r < 2 * kD; r += nwaves) {
+        const int c = r >= kD ? r - kD : r;
+        const char *rb = reinterpret_cast<const char *>((r >= kD ? bb : ab) + size_t(c) * stride);
+        __builtin_amdgcn_global_load_lds((gptr_t)(rb + voff), (lptr_t)(tile + r * kPB), 4, 0, 0);
+    }
+}
+
+__global__ void __launch_bounds__(1024)
+nattn_bwd_dq_mfma(S2DeviceTables t, int nbh, int nrows, float scale, const float *__restrict__ q,
+                  const float *__restrict__ k, const float *__restrict__ v, const float *__restrict__ outp,
+                  const float *__restrict__ lse, const float *__restrict__ go, float *__restrict__ dq,
+                  float *__restrict__ Dws)
+{
+    extern __shared__ __attribute__((aligned(16))) float smem[];
+    const int nwaves = blockDim.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int col = lane & 31, hl = lane >> 5;
+    const int nlon = t.nlon_in;
+    const int bh = blockIdx.x / nrows;
+    const int h = t.row_order[blockIdx.x - bh * nrows];
+    const int w = wave * 32 + col;
+    const size_t so = size_t(t.nlat_out) * t.nlon_out, si = size_t(t.nlat_in) * t.nlon_in;
+    const size_t io = size_t(h) * t.nlon_out + w;
+    const float qscale = scale * 1.4426950408889634f;
+
+    float qop[16], gop[16], Dp = 0.f;
+#pragma unroll
+    for (int s = 0; s < 16; ++s) {
+        const size_t off = (size_t(bh) * kD + 2 * s + hl) * so + io;
+        qop[s] = q[off] * qscale;
+        gop[s] = go[off];
+        Dp = fmaf(gop[s], outp[off], Dp);
+    }
+    const float Di = Dp + __shfl_xor(Dp, 32);        // D_i = dout_i . out_i over all 32 channels
+    if (hl == 0) Dws[size_t(bh) * so + io] = Di;
+    const float lse2 = (lse[size_t(bh) * so + io] - t.ln_omega_ref) * 1.4426950408889634f;
+    f32x16 acc = {0};
+    const int arow = 32 * ((col >> 2) & 1) + 4 * (col >> 3) + (col & 3);
+
+    const int nb = t.band_n[h], hp0 = t.band_lo[h];
+    const int ntile = nlon / kTileCols;
+    const int total = nb * ntile;
+    {
+        const float *kb = k + size_t(bh) * kD * si + size_t(hp0) * nlon;
+        const float *vb = v + size_t(bh) * kD * si + size_t(hp0) * nlon;
+        stage_tile_b(kb, vb, si, 0, nlon, smem, wave, nwaves, lane);
+    }
+    for (int it = 0; it < total; ++it) {
+        const int b = it / ntile, x0 = (it - b * ntile) * kTileCols;
+        const int hp = hp0 + b;
+        float *tile = smem + (it & 1) * kTileB;
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (it + 1 < total) {
+            const int b2 = (it + 1) / ntile, x2 = (it + 1 - b2 * ntile) * kTileCols;
+            const float *kb = k + size_t(bh) * kD * si + size_t(hp0 + b2) * nlon;
+            const float *vb = v + size_t(bh) * kD * si + size_t(hp0 + b2) * nlon;
+            stage_tile_b(kb, vb, si, x2, nlon, smem + ((it + 1) & 1) * kTileB, wave, nwaves, lane);
+        }
+        const int c = t.cnt[h * t.band_max + b];
+        const bool full = c == nlon;
+        const int lo = full ? 0 : -((c - 1) >> 1);
+        if (!full) {
+            const int need0 = wrapn(wave * 32 + lo, nlon), len = c + 31;
+            const int rel = wrapn(x0 - need0, nlon);
+            if (!(rel < len || rel + kTileCols > nlon)) continue;
+        }
+        const float wq = t.omega_rel[hp];
+        const float *tk = tile, *tv = tile + kD * kPB;
+        f32x16 s0 = {0}, s1 = {0}, d0 = {0}, d1 = {0};
+#pragma unroll
+        for (int s = 0; s < 16; ++s) {
+            const int ro = (2 * s + hl) * kPB + arow;
+            s0 = mfma(tk[ro], qop[s], s0);
+            s1 = mfma(tk[ro + 16], qop[s], s1);
+            d0 = mfma(tv[ro], gop[s], d0);
+            d1 = mfma(tv[ro + 16], gop[s], d1);
+        }
+        float ds[32];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            ds[i] = wq * __builtin_amdgcn_exp2f(s0[i] - lse2) * (d0[i] - Di);
+            ds[16 + i] = wq * __builtin_amdgcn_exp2f(s1[i] - lse2) * (d1[i] - Di);
+        }
+        if (!full) {
+            const int base = (x0 + 32 * hl - w - lo + 2 * nlon) % nlon;
+#pragma unroll
+            for (int i = 0; i < 32; ++i) {
+                int rel = base + i;
+                rel = rel >= nlon ? rel - nlon : rel;
+                ds[i] = rel < c ? ds[i] : 0.f;
+            }
+        }
+        // dQ^T += K dS^T: A = K[channel = col][super-tile column 32*hl + i]
+#pragma unroll
+        for (int i = 0; i < 32; ++i) acc = mfma(tk[col * kPB + 32 * hl + i], ds[i], acc);
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int ch = 8 * (i >> 2) + 4 * hl + (i & 3);
+        dq[(size_t(bh) * kD + ch) * so + io] = acc[i] * scale;
+    }
+}
+
 }  // namespace
 
 // latitudes whose disk holds more than 260 points per output (the three heaviest classes) take the matrix-core path
@@ -193,5 +313,23 @@ int s2_nattn_fwd_mfma(const S2DeviceTables &t, int nbh, int nrows, float scale, 
     S2TraceScope tr("nattn_fwd_mfma", nbh * (t.fwd_pairs[0] + t.fwd_pairs[1] + t.fwd_pairs[2]), st);
     hipLaunchKernelGGL(nattn_fwd_mfma, dim3((unsigned)(long(nrows) * nbh)), dim3(t.nlon_out * 2), lds, st, t, nbh, nrows,
                        scale * 1.4426950408889634f, q, k, v, out, lse);
+    return 0;
+}
+
+int s2_nattn_bwd_dq_mfma(const S2DeviceTables &t, int nbh, int nrows, float scale, const float *q, const float *k,
+                         const float *v, const float *o, const float *lse, const float *go, float *dq, float *Dws,
+                         hipStream_t st)
+{
+    const size_t lds = 2 * size_t(kTileB) * sizeof(float);
+    static bool configured = false;
+    if (!configured) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(nattn_bwd_dq_mfma),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, int(lds)) != hipSuccess)
+            return -1;
+        configured = true;
+    }
+    S2TraceScope tr("nattn_bwd_dq_mfma", nbh * (t.fwd_pairs[0] + t.fwd_pairs[1] + t.fwd_pairs[2]), st);
+    hipLaunchKernelGGL(nattn_bwd_dq_mfma, dim3((unsigned)(long(nrows) * nbh)), dim3(t.nlon_out * 2), lds, st, t, nbh,
+                       nrows, scale, q, k, v, o, lse, go, dq, Dws);
     return 0;
 }
