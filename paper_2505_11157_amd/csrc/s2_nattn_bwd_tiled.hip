@@ -870,11 +870,20 @@ int s2_nattn_bwd_tiled(const S2DeviceTables &t, int nbh, int d, int e, float sca
         return 0;
     }
     const int nseg_i = (t.nlon_in + kSegB - 1) / kSegB;
-    const int nsplit_i = t.bwd_cls[0] + t.bwd_cls[1] + t.bwd_cls[2];
+    // dense polar input latitudes: dk/dv on the matrix cores
+    S2DeviceTables t_kv = t_all;
+    const int nmi = s2_nattn_bwd_dkdv_mfma_rows(t_all, d, e);
+    if (nmi > 0) {
+        if (s2_nattn_bwd_dkdv_mfma(t_all, nbh, nmi, scale, q, k, v, lse, go, Dws, dk, dv, st)) return -1;
+        t_kv.trow_order = t_all.trow_order + nmi;
+        t_kv.bwd_cls[0] = t_kv.bwd_cls[1] = t_kv.bwd_cls[2] = 0;
+        t_kv.bwd_pairs[0] = t_kv.bwd_pairs[1] = t_kv.bwd_pairs[2] = 0.0;
+    }
+    const int nsplit_i = t_kv.bwd_cls[0] + t_kv.bwd_cls[1] + t_kv.bwd_cls[2];
     const size_t lds_wave = (2 * GeoB<1>::TILE + 2 * GeoB<1>::PITCH) * sizeof(float);
     if (nsplit_i > 0) {
         const long nblk = long((nbh + kWavesB - 1) / kWavesB) * nseg_i *
-                          (8 * t.bwd_cls[0] + 4 * t.bwd_cls[1] + 2 * t.bwd_cls[2]);
+                          (8 * t_kv.bwd_cls[0] + 4 * t_kv.bwd_cls[1] + 2 * t_kv.bwd_cls[2]);
         size_t lds = lds_wave * kWavesB;
         const size_t mg = size_t(kWavesB / 2) * 2 * 4 * kDL * 64 * sizeof(float);
         if (lds < mg) lds = mg;
@@ -885,14 +894,14 @@ int s2_nattn_bwd_tiled(const S2DeviceTables &t, int nbh, int d, int e, float sca
                 return -1;
             cfg_kv = true;
         }
-        S2TraceScope tr("nattn_bwd_dkdv_tiled<8 waves>", nbh * (t.bwd_pairs[0] + t.bwd_pairs[1] + t.bwd_pairs[2]), st);
-        hipLaunchKernelGGL(k8, dim3((unsigned)nblk), dim3(64 * kWavesB), lds, st, t, nbh, 1, scale, q, k, v, lse, go,
+        S2TraceScope tr("nattn_bwd_dkdv_tiled<8 waves>", nbh * (t_kv.bwd_pairs[0] + t_kv.bwd_pairs[1] + t_kv.bwd_pairs[2]), st);
+        hipLaunchKernelGGL(k8, dim3((unsigned)nblk), dim3(64 * kWavesB), lds, st, t_kv, nbh, 1, scale, q, k, v, lse, go,
                            Dws, dk, dv);
     }
-    const long nrows = t.nlat_in - nsplit_i;
+    const long nrows = t.nlat_in - nmi - nsplit_i;
     S2TraceScope tr("nattn_bwd_dkdv_tiled<1 wave>", nbh * t.bwd_pairs[3], st);
     if (nrows > 0)
-        hipLaunchKernelGGL((nattn_bwd_dkdv_tiled<1>), dim3((unsigned)(nrows * nbh * nseg_i)), dim3(64), lds_wave, st, t,
-                           nbh, nsplit_i, scale, q, k, v, lse, go, Dws, dk, dv);
+        hipLaunchKernelGGL((nattn_bwd_dkdv_tiled<1>), dim3((unsigned)(nrows * nbh * nseg_i)), dim3(64), lds_wave, st,
+                           t_kv, nbh, nsplit_i, scale, q, k, v, lse, go, Dws, dk, dv);
     return 0;
 }

@@ -32,3 +32,7 @@ int s2_nattn_fwd_mfma(const S2DeviceTables &t, int nbh, int nrows, float scale, 
 int s2_nattn_bwd_dq_mfma(const S2DeviceTables &t, int nbh, int nrows, float scale, const float *q, const float *k,
                          const float *v, const float *o, const float *lse, const float *go, float *dq, float *Dws,
                          hipStream_t st);
+int s2_nattn_bwd_dkdv_mfma_rows(const S2DeviceTables &t, int d, int e);
+int s2_nattn_bwd_dkdv_mfma(const S2DeviceTables &t, int nbh, int nrows, float scale, const float *q, const float *k,
+                           const float *v, const float *lse, const float *go, const float *Dws, float *dk, float *dv,
+                           hipStream_t st);

@@ -294,6 +294,127 @@ nattn_bwd_dq_mfma(S2DeviceTables t, int nbh, int nrows, float scale, const float
     }
 }
 
+// --------------------------------------------------------------- backward, dk and dv ----------
+//
+// Transposed roles for the dense INPUT latitudes: a wavefront owns 32 input points (k_j, v_j as B
+// operands), output latitudes stream by as super-tiles of q and dout (plus their lse and D rows):
+//   S = Q K^T, dP = dout V^T  (lane = owner, registers = output columns),
+//   p = omega exp2(s - lse_i), dS = p (dP - D_i),
+//   dK^T += Q-read-by-channel dS,  dV^T += dout-read-by-channel p.
+// Output (h, w) holds input (h', w_in) iff (w - w_in) mod nlon lies in the arc of (h, h'): same mask.
+
+constexpr int kTileC = (2 * kD + 2) * kPB;     // q rows, dout rows, lse row, D row
+
+__device__ __forceinline__ void stage_tile_c(const float *qb, const float *gb, const float *lrow, const float *drow,
+                                             size_t stride, int x0, int ncol, float *tile, int wave, int nwaves, int lane)
+{
+    const unsigned voff = 4u * unsigned(wrapn(x0 + lane, ncol));
+    for (int r = wave; r < 2 * kD + 2; r += nwaves) {
+        const char *rb;
+        if (r < kD) rb = reinterpret_cast<const char *>(qb + size_t(r) * stride);
+        else if (r < 2 * kD) rb = reinterpret_cast<const char *>(gb + size_t(r - kD) * stride);
+        else rb = reinterpret_cast<const char *>(r == 2 * kD ? lrow : drow);
+        __builtin_amdgcn_global_load_lds((gptr_t)(rb + voff), (lptr_t)(tile + r * kPB), 4, 0, 0);
+    }
+}
+
+__global__ void __launch_bounds__(1024)
+nattn_bwd_dkdv_mfma(S2DeviceTables t, int nbh, int nrows, float scale, const float *__restrict__ q,
+                    const float *__restrict__ k, const float *__restrict__ v, const float *__restrict__ lse,
+                    const float *__restrict__ go, const float *__restrict__ Dws, float *__restrict__ dk,
+                    float *__restrict__ dv)
+{
+    extern __shared__ __attribute__((aligned(16))) float smem[];
+    const int nwaves = blockDim.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int col = lane & 31, hl = lane >> 5;
+    const int nlon = t.nlon_in;                       // equal grids
+    const int bh = blockIdx.x / nrows;
+    const int hp = t.trow_order[blockIdx.x - bh * nrows];
+    const int w = wave * 32 + col;                    // owner's input longitude
+    const size_t so = size_t(t.nlat_out) * t.nlon_out, si = size_t(t.nlat_in) * t.nlon_in;
+    const size_t ii = size_t(hp) * nlon + w;
+    const float log2e = 1.4426950408889634f;
+    const float qscale = scale * log2e, lref2 = t.ln_omega_ref * log2e, wq = t.omega_rel[hp];
+
+    float kop[16], vop[16];
+#pragma unroll
+    for (int s = 0; s < 16; ++s) {
+        const size_t off = (size_t(bh) * kD + 2 * s + hl) * si + ii;
+        kop[s] = k[off] * qscale;
+        vop[s] = v[off];
+    }
+    f32x16 adk = {0}, adv = {0};
+    const int arow = 32 * ((col >> 2) & 1) + 4 * (col >> 3) + (col & 3);
+
+    const int nb = t.tband_n[hp], h0 = t.tband_lo[hp];
+    const int ntile = nlon / kTileCols;
+    const int total = nb * ntile;
+    auto issue = [&](int itx, float *dst) {
+        const int b2 = itx / ntile, x2 = (itx - b2 * ntile) * kTileCols;
+        const size_t rowoff = size_t(h0 + b2) * nlon;
+        stage_tile_c(q + size_t(bh) * kD * so + rowoff, go + size_t(bh) * kD * so + rowoff,
+                     lse + size_t(bh) * so + rowoff, Dws + size_t(bh) * so + rowoff, so, x2, nlon, dst, wave, nwaves, lane);
+    };
+    issue(0, smem);
+    for (int it = 0; it < total; ++it) {
+        const int b = it / ntile, x0 = (it - b * ntile) * kTileCols;
+        float *tile = smem + (it & 1) * kTileC;
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (it + 1 < total) issue(it + 1, smem + ((it + 1) & 1) * kTileC);
+        const int c = t.tcnt[hp * t.tband_max + b];
+        const bool full = c == nlon;
+        const int lo = full ? 0 : -((c - 1) >> 1);
+        if (!full) {
+            const int need0 = wrapn(wave * 32 + lo, nlon), len = c + 31;
+            const int rel = wrapn(x0 - need0, nlon);
+            if (!(rel < len || rel + kTileCols > nlon)) continue;
+        }
+        const float *tq = tile, *tg = tile + kD * kPB, *tl = tile + 2 * kD * kPB, *td = tl + kPB;
+        const int base = (x0 + 32 * hl - w - lo + 2 * nlon) % nlon;
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt) {
+            f32x16 s = {0}, d = {0};
+#pragma unroll
+            for (int st = 0; st < 16; ++st) {
+                const int ro = (2 * st + hl) * kPB + arow + 16 * mt;
+                s = mfma(tq[ro], kop[st], s);
+                d = mfma(tg[ro], vop[st], d);
+            }
+            float p[16], ds[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int j = 32 * hl + 16 * mt + i;          // super-tile column of this register
+                const float pi = wq * __builtin_amdgcn_exp2f(s[i] - fmaf(tl[j], log2e, -lref2));
+                p[i] = pi;
+                ds[i] = pi * (d[i] - td[j]);
+            }
+            if (!full) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    int rel = base + 16 * mt + i;
+                    rel = rel >= nlon ? rel - nlon : rel;
+                    if (rel >= c) { p[i] = 0.f; ds[i] = 0.f; }
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int ao = col * kPB + 32 * hl + 16 * mt + i;
+                adk = mfma(tq[ao], ds[i], adk);
+                adv = mfma(tg[ao], p[i], adv);
+            }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int ch = 8 * (i >> 2) + 4 * hl + (i & 3);
+        const size_t off = (size_t(bh) * kD + ch) * si + ii;
+        dk[off] = adk[i] * scale;
+        dv[off] = adv[i];
+    }
+}
+
 }  // namespace
 
 // latitudes whose disk holds more than 260 points per output (the three heaviest classes) take the matrix-core path
@@ -331,5 +452,31 @@ int s2_nattn_bwd_dq_mfma(const S2DeviceTables &t, int nbh, int nrows, float scal
     S2TraceScope tr("nattn_bwd_dq_mfma", nbh * (t.fwd_pairs[0] + t.fwd_pairs[1] + t.fwd_pairs[2]), st);
     hipLaunchKernelGGL(nattn_bwd_dq_mfma, dim3((unsigned)(long(nrows) * nbh)), dim3(t.nlon_out * 2), lds, st, t, nbh,
                        nrows, scale, q, k, v, o, lse, go, dq, Dws);
+    return 0;
+}
+
+int s2_nattn_bwd_dkdv_mfma_rows(const S2DeviceTables &t, int d, int e)
+{
+    const int nw = t.nlon_in / 32;
+    if (d != 32 || e != 32 || t.pscale != 1 || t.nlon_in % kTileCols != 0 || nw < 2 || nw > 16) return 0;
+    if (std::getenv("S2_NO_MFMA")) return 0;
+    return t.bwd_cls[0] + t.bwd_cls[1] + t.bwd_cls[2];
+}
+
+int s2_nattn_bwd_dkdv_mfma(const S2DeviceTables &t, int nbh, int nrows, float scale, const float *q, const float *k,
+                           const float *v, const float *lse, const float *go, const float *Dws, float *dk, float *dv,
+                           hipStream_t st)
+{
+    const size_t lds = 2 * size_t(kTileC) * sizeof(float);
+    static bool configured = false;
+    if (!configured) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(nattn_bwd_dkdv_mfma),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, int(lds)) != hipSuccess)
+            return -1;
+        configured = true;
+    }
+    S2TraceScope tr("nattn_bwd_dkdv_mfma", nbh * (t.bwd_pairs[0] + t.bwd_pairs[1] + t.bwd_pairs[2]), st);
+    hipLaunchKernelGGL(nattn_bwd_dkdv_mfma, dim3((unsigned)(long(nrows) * nbh)), dim3(t.nlon_in * 2), lds, st, t, nbh,
+                       nrows, scale, q, k, v, lse, go, Dws, dk, dv);
     return 0;
 }
