@@ -296,9 +296,8 @@ extern "C" int s2_grid_init(int grid_type, int nlat_in, int nlon_in, int nlat_ou
     order_by_work(nlat_out, g->band_n, g->cnt, g->band_max, g->row_order);
     order_by_work(nlat_in, g->tband_n, g->tcnt, g->tband_max, g->trow_order);
     // split classes: a latitude whose disk holds more than 260 * P / 2 offsets per point is split P ways
-    const char *env_t = std::getenv("S2_SPLIT_T");   // experiment knob: work per part
-    const long T = env_t ? std::atol(env_t) : 260;
-    auto classify = [T](int n_rows, const std::vector<int> &n, const std::vector<int> &tab, int bmax, int (&cls)[4],
+    constexpr long T = 260;
+    auto classify = [](int n_rows, const std::vector<int> &n, const std::vector<int> &tab, int bmax, int (&cls)[4],
                         double (&pairs)[4], double per_entry) {
         cls[0] = cls[1] = cls[2] = cls[3] = 0;
         pairs[0] = pairs[1] = pairs[2] = pairs[3] = 0.0;

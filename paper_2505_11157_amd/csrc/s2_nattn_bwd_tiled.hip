@@ -194,7 +194,6 @@ __device__ __forceinline__ void run_chunk_dq(float *buf0, float *buf1, const flo
                                              const float (&go)[4][kDL], const float (&lse2)[4], const float (&Dr)[4],
                                              float (&dq)[4][kDL])
 {
-    using G = GeoB<PS>;
     float s[4][NT], dp[4][NT];
 #pragma unroll
     for (int r = 0; r < 4; ++r)

@@ -423,7 +423,8 @@ int s2_nattn_fwd_mfma_rows(const S2DeviceTables &t, int d, int e)
     const int nw = t.nlon_out / 32;
     if (d != 32 || e != 32 || t.pscale != 1 || t.nlon_in % kTileCols != 0 || t.nlon_out % 32 != 0 || nw < 2 || nw > 16)
         return 0;
-    if (std::getenv("S2_NO_MFMA")) return 0;
+    static const bool off = std::getenv("S2_NO_MFMA") != nullptr;   // debugging aid: force the vector kernels
+    if (off) return 0;
     return t.fwd_cls[0] + t.fwd_cls[1] + t.fwd_cls[2];
 }
 
@@ -459,7 +460,8 @@ int s2_nattn_bwd_dkdv_mfma_rows(const S2DeviceTables &t, int d, int e)
 {
     const int nw = t.nlon_in / 32;
     if (d != 32 || e != 32 || t.pscale != 1 || t.nlon_in % kTileCols != 0 || nw < 2 || nw > 16) return 0;
-    if (std::getenv("S2_NO_MFMA")) return 0;
+    static const bool off = std::getenv("S2_NO_MFMA") != nullptr;
+    if (off) return 0;
     return t.bwd_cls[0] + t.bwd_cls[1] + t.bwd_cls[2];
 }
 

@@ -384,8 +384,7 @@ int launch_fwd_tiled(const S2DeviceTables &t, int skip_rows, int nbh, float qsca
 {   // t.row_order already points past the skip_rows latitudes another kernel has taken
     const int nseg = (t.nlon_out + kSeg - 1) / kSeg;
     const int nsplit = t.fwd_cls[0] + t.fwd_cls[1] + t.fwd_cls[2];   // latitudes split over several wavefronts
-    const char *env = std::getenv("S2_FWD_MODE");                    // experiment knob
-    const int mode = env ? std::atoi(env) : 0;
+    constexpr int mode = 0;   // 1: everything through the one-wave kernel, 2: everything through the 8-wave kernel
     // heavy latitudes: 8-wave workgroups with an in-LDS merge
     if (mode != 1 && (nsplit > 0 || mode == 2)) {
         const int first_row = mode == 2 ? 0 : 1;   // mode 2: every latitude through the 8-wave kernel

@@ -127,6 +127,20 @@ def test_bit_reproducible_full_configs(cfg):
             assert np.array_equal(a, b)
 
 
+def test_vector_kernels_cover_dense_latitudes_too():
+    # S2_NO_MFMA=1 (read once per process) sends the polar latitudes through the split vector kernels
+    # instead of the matrix-core kernels: same parity bar, in a child process
+    import os, subprocess, sys
+    code = ("import sys; sys.path.insert(0, %r); sys.path.insert(0, %r)\n"
+            "import test_gpu_nattn as T\n"
+            "from paper_2505_11157_amd.workloads import make_inputs\n"
+            "c, arrs = make_inputs(2); T.run_case(c, arrs, [0, 7]); print('child ok')\n"
+            % (os.path.dirname(os.path.abspath(__file__)), os.path.dirname(os.path.dirname(os.path.abspath(__file__)))))
+    env = dict(os.environ, S2_NO_MFMA="1")
+    r = subprocess.run([sys.executable, "-c", code], env=env, capture_output=True, text=True, timeout=240)
+    assert r.returncode == 0 and "child ok" in r.stdout, r.stdout[-2000:] + r.stderr[-2000:]
+
+
 def test_errors_on_device():
     gd = grid_dict(1)
     g = _grid(gd)
