@@ -359,7 +359,14 @@ nattn_bwd_dq_tiled(S2DeviceTables t, int nbh, int first_row, float scale, const 
     const int run_lo = tk.part * nrun / tk.P, run_hi = (tk.part + 1) * nrun / tk.P;
     int run = 0;
     if (wave_active) {
-        for (int b = 0; b < nb; ++b) {
+        // Band rows are visited in a rotated order: first the one whose absolute latitude index is 0 modulo
+        // the band size, and so on.  Workgroups of neighbouring latitudes run at the same time and advance at
+        // the same pace; with this order they all want the SAME input latitudes at the same moment (one
+        // ninth of the slice instead of all of it), so the re-reads hit the 4 MB L2 of the XCD instead of
+        // streaming the slice from memory nine times.
+        const int rot = (t.band_max - hp0 % t.band_max) % t.band_max % nb;
+        for (int bb = 0; bb < nb; ++bb) {
+            const int b = bb + rot < nb ? bb + rot : bb + rot - nb;
             const int hp = hp0 + b;
             const int c = t.cnt[h * t.band_max + b];
             const int nchunk = (c + kNTMax - 1) / kNTMax;
@@ -521,7 +528,10 @@ nattn_bwd_dkdv_tiled(S2DeviceTables t, int nbh, int first_row, float scale, cons
     const int run_lo = tk.part * nrun / tk.P, run_hi = (tk.part + 1) * nrun / tk.P;
     int run = 0;
     if (wave_active) {
-        for (int b = 0; b < nb; ++b) {
+        // rotated band order (see the dq kernel): concurrent workgroups read the same latitudes together
+        const int rot = (t.tband_max - h0 % t.tband_max) % t.tband_max % nb;
+        for (int bb = 0; bb < nb; ++bb) {
+            const int b = bb + rot < nb ? bb + rot : bb + rot - nb;
             const int h = h0 + b;
             const int c = t.tcnt[hp * t.tband_max + b];
             const int nchunk = (c + kNTMax - 1) / kNTMax;
@@ -731,7 +741,10 @@ nattn_bwd_dkdv2_tiled(S2DeviceTables t, int nbh, int first_row, float scale, con
     const int run_lo = tk.part * nrun / tk.P, run_hi = (tk.part + 1) * nrun / tk.P;
     int run = 0;
     if (wave_active) {
-        for (int b = 0; b < nb; ++b) {
+        // rotated band order (see the dq kernel): concurrent workgroups read the same latitudes together
+        const int rot = (t.tband_max - h0 % t.tband_max) % t.tband_max % nb;
+        for (int bb = 0; bb < nb; ++bb) {
+            const int b = bb + rot < nb ? bb + rot : bb + rot - nb;
             const int h = h0 + b;
             const int c = t.tcnt[hp * t.tband_max + b];
             const bool full = c == nlon_i;

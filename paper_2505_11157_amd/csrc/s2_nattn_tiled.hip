@@ -298,7 +298,14 @@ nattn_fwd_tiled(S2DeviceTables t, int nbh, int first_row, float qscale, const fl
     const int run_lo = part * nrun / P, run_hi = (part + 1) * nrun / P;
     int run = 0;
     if (wave_active) {
-        for (int b = 0; b < nb; ++b) {
+        // Band rows are visited in a rotated order: first the one whose absolute latitude index is 0 modulo
+        // the band size, and so on.  Workgroups of neighbouring latitudes run at the same time and advance at
+        // the same pace; with this order they all want the SAME input latitudes at the same moment (one
+        // ninth of the slice instead of all of it), so the re-reads hit the 4 MB L2 of the XCD instead of
+        // streaming the slice from memory nine times.
+        const int rot = (t.band_max - hp0 % t.band_max) % t.band_max % nb;
+        for (int bb = 0; bb < nb; ++bb) {
+            const int b = bb + rot < nb ? bb + rot : bb + rot - nb;
             const int hp = hp0 + b;
             const int c = t.cnt[h * t.band_max + b];
             const int nchunk = (c + kNTMax - 1) / kNTMax;
