@@ -24,7 +24,24 @@ PEAK_BF16_TFLOPS = 2500.0
 
 # HBM bytes per launch (FETCH_SIZE + WRITE_SIZE from rocprofv3 --pmc, scaled by the factors a plain
 # copy gives: see profiles/), keyed by (workload, kernel name).  Measured offline; None if not measured.
-TRAFFIC_BYTES = {}
+TRAFFIC_BYTES = {
+    (3, "nattn_fwd_mfma"): 278e6, (3, "nattn_fwd_tiled<1 wave>"): 2364e6,
+    (3, "nattn_bwd_dq_mfma"): 382e6, (3, "nattn_bwd_dq_tiled<1 wave>"): 3801e6,
+    (3, "nattn_bwd_dkdv_mfma"): 324e6, (3, "nattn_bwd_dkdv_tiled<1 wave>"): 5298e6,
+}
+
+
+def copy_calibration():
+    """Three 1 GiB device-to-device copies: what FETCH_SIZE / WRITE_SIZE read for a known transfer."""
+    import torch
+    a = torch.empty(1 << 28, dtype=torch.float32, device="cuda")
+    b = torch.empty_like(a)
+    a.fill_(1.0)
+    torch.cuda.synchronize()
+    for _ in range(3):
+        b.copy_(a)
+    torch.cuda.synchronize()
+    print(json.dumps({"copy_calibration": {"bytes_per_copy": 1 << 30, "copies": 3}}))
 
 
 def pairs_per_slice(S, g, c):
@@ -55,12 +72,17 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=3, help="workload number (1-5), default 3 = 129x256 equiangular")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run three 1 GiB device copies (scale for the rocprofv3 HBM counters)")
     ap.add_argument("--cpu-slices", type=int, default=0, help="(batch*head) slices the oracle is timed on (0 = auto)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (--gpus 1); batch*heads shards need no exchange, "
               "see DESIGN.md", file=sys.stderr)
         sys.exit(2)
+    if args.copy_calibration:
+        copy_calibration()
+        return
 
     import numpy as np
     import torch
