@@ -139,6 +139,8 @@ static int upload_tables(s2_grid *g)
         {g->row_order.data(), g->row_order.size() * sizeof(int), 0},
         {g->trow_order.data(), g->trow_order.size() * sizeof(int), 0},
         {bias.data(), bias.size() * sizeof(float), 0},
+        {g->st_cum.data(), g->st_cum.size() * sizeof(int), 0},
+        {g->tst_cum.data(), g->tst_cum.size() * sizeof(int), 0},
     };
     size_t total = 0;
     for (auto &p : parts) {
@@ -166,6 +168,8 @@ static int upload_tables(s2_grid *g)
     t.row_order = reinterpret_cast<const int *>(base + parts[7].off);
     t.trow_order = reinterpret_cast<const int *>(base + parts[8].off);
     g->dev_bias_tok = reinterpret_cast<const float *>(base + parts[9].off);
+    t.st_cum = reinterpret_cast<const int *>(base + parts[10].off);
+    t.tst_cum = reinterpret_cast<const int *>(base + parts[11].off);
     t.band_max = g->band_max;
     t.tband_max = g->tband_max;
     t.nlat_in = g->nlat_in; t.nlon_in = g->nlon_in;
@@ -311,6 +315,49 @@ extern "C" int s2_grid_init(int grid_type, int nlat_in, int nlon_in, int nlat_ou
     };
     classify(nlat_out, g->band_n, g->cnt, g->band_max, g->dt.fwd_cls, g->dt.fwd_pairs, double(nlon_out));
     classify(nlat_in, g->tband_n, g->tcnt, g->tband_max, g->dt.bwd_cls, g->dt.bwd_pairs, double(nlon_out));
+
+    // streaming plan for the light latitudes (work <= T): they must form one contiguous range whose bands
+    // move monotonically, with short odd arcs (at most 65 offsets) on every row of the band
+    auto stream_plan = [](int n_rows, const std::vector<int> &lo, const std::vector<int> &n, const std::vector<int> &tab,
+                          int bmax, int &p_lo, int &p_hi, int &p_nw, std::vector<int> &cum) {
+        p_lo = p_hi = p_nw = 0;
+        cum.assign(1, 0);
+        int first = -1, last = -1, count = 0;
+        for (int r = 0; r < n_rows; ++r) {
+            long work = 0;
+            for (int b = 0; b < n[r]; ++b) work += tab[size_t(r) * bmax + b];
+            if (work > T) continue;
+            if (first < 0) first = r;
+            last = r;
+            ++count;
+        }
+        if (count == 0 || last - first + 1 != count) return;
+        for (int r = first; r <= last; ++r) {
+            if (n[r] < 1) return;
+            for (int b = 0; b < n[r]; ++b) {
+                const int c = tab[size_t(r) * bmax + b];
+                if (c < 1 || c > 65 || c % 2 == 0) return;
+            }
+            if (r > first && (lo[r] < lo[r - 1] || lo[r] + n[r] < lo[r - 1] + n[r - 1])) return;
+        }
+        for (int w = 1; w <= 8; ++w) {
+            bool ok = true;
+            for (int r = first; r + w <= last && ok; ++r) ok = lo[r + w] >= lo[r] + n[r] - 1;
+            if (!ok) continue;
+            p_lo = first; p_hi = last + 1; p_nw = w;
+            // cost of a latitude: offsets plus a fixed charge per band row (run set-up, softmax bookkeeping)
+            for (int r = first; r <= last; ++r) {
+                int c = 0;
+                for (int b = 0; b < n[r]; ++b) c += tab[size_t(r) * bmax + b] + 4;
+                cum.push_back(cum.back() + c);
+            }
+            return;
+        }
+    };
+    stream_plan(nlat_out, g->band_lo, g->band_n, g->cnt, g->band_max, g->dt.st_lo, g->dt.st_hi, g->dt.st_nw,
+                g->st_cum);
+    stream_plan(nlat_in, g->tband_lo, g->tband_n, g->tcnt, g->tband_max, g->dt.tst_lo, g->dt.tst_hi, g->dt.tst_nw,
+                g->tst_cum);
 
     int rc = upload_tables(g);
     if (rc != S2_OK) { delete g; return rc; }

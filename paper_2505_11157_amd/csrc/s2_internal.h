@@ -30,6 +30,14 @@ struct S2DeviceTables {
     double fwd_pairs[4];      // (output, input) pairs per slice handled by each class of output latitudes
     double bwd_pairs[4];      // the same pairs counted per class of input latitudes
     int nlat_in, nlon_in, nlat_out, nlon_out, pscale;
+    // streaming kernels for the light latitudes (the last class): contiguous range [st_lo, st_hi) of output
+    // latitudes and the number of wavefronts st_nw such that the band of latitude h + st_nw starts no earlier
+    // than the last row of the band of h; st_nw = 0 if the light latitudes do not have that structure.
+    // tst_*: the same for input latitudes and the transposed bands.
+    int st_lo, st_hi, st_nw;
+    int tst_lo, tst_hi, tst_nw;
+    const int *st_cum;        // [st_hi - st_lo + 1]   running cost of the light latitudes (for equal-work segments)
+    const int *tst_cum;       // [tst_hi - tst_lo + 1]
     float ln_omega_ref;       // ln(max omega): the stored logsumexp is relative to the true omega
     float omega_ref;          // max omega
 };
@@ -40,7 +48,7 @@ struct s2_grid {
     double theta;
     std::vector<double> colat_in, omega_in, colat_out;
     // host copies of the compact tables
-    std::vector<int> band_lo, band_n, cnt, tband_lo, tband_n, tcnt, row_order, trow_order;
+    std::vector<int> band_lo, band_n, cnt, tband_lo, tband_n, tcnt, row_order, trow_order, st_cum, tst_cum;
     int band_max = 0, tband_max = 0;
     // canonical CSR
     std::vector<int64_t> row_ptr;

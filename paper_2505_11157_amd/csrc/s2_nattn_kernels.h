@@ -36,3 +36,9 @@ int s2_nattn_bwd_dkdv_mfma_rows(const S2DeviceTables &t, int d, int e);
 int s2_nattn_bwd_dkdv_mfma(const S2DeviceTables &t, int nbh, int nrows, float scale, const float *q, const float *k,
                            const float *v, const float *lse, const float *go, const float *Dws, float *dk, float *dv,
                            hipStream_t st);
+
+// Streaming kernels for the light latitudes (last class) on equal grids: each input latitude is staged in LDS once
+// per workgroup and shared by the wavefronts that walk down consecutive output latitudes.
+bool s2_nattn_stream_supported(const S2DeviceTables &t, int d, int e);
+int s2_nattn_fwd_stream(const S2DeviceTables &t, int nbh, float qscale, const float *q, const float *k,
+                        const float *v, float *out, float *lse, hipStream_t st);

@@ -416,6 +416,9 @@ int launch_fwd_tiled(const S2DeviceTables &t, int skip_rows, int nbh, float qsca
     // the rest: one wavefront per workgroup
     const int first_row = mode == 1 ? 0 : nsplit;
     const long nrows = t.nlat_out - skip_rows - first_row;
+    static const bool no_stream = std::getenv("S2_NO_STREAM") != nullptr;   // debugging aid: one-wave kernel instead
+    if (nrows > 0 && mode == 0 && !no_stream && s2_nattn_stream_supported(t, D, D))
+        return s2_nattn_fwd_stream(t, nbh, qscale, q, k, v, out, lse, st);
     if (nrows > 0) {
         S2TraceScope tr("nattn_fwd_tiled<1 wave>",
                         nbh * (t.fwd_pairs[3] + (mode == 1 ? t.fwd_pairs[0] + t.fwd_pairs[1] + t.fwd_pairs[2] : 0.0)), st);

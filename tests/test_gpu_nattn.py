@@ -82,6 +82,12 @@ SMALL = [
     dict(kind="nattn", grid_type=1, nlat_in=24, nlon_in=100, nlat_out=24, nlon_out=100, theta=0.4, batch=3, heads=1, d=32, dtype="f32"),
     dict(kind="nattn", grid_type=0, nlat_in=19, nlon_in=152, nlat_out=10, nlon_out=76, theta=0.3, batch=3, heads=3, d=32, dtype="f32"),
     dict(kind="nattn", grid_type=0, nlat_in=21, nlon_in=192, nlat_out=21, nlon_out=192, theta=0.6, batch=1, heads=2, d=32, dtype="f32"),
+    # streaming kernels for the light latitudes (equal grids, at least 192 longitudes): ragged last strip, bands of
+    # 9 / about 6 / 5 latitudes (8, 5-6 and 4 wavefronts per workgroup), more slices than compute units need
+    dict(kind="nattn", grid_type=0, nlat_in=41, nlon_in=196, nlat_out=41, nlon_out=196, theta=4 * math.pi / 40, batch=1, heads=3, d=32, dtype="f32"),
+    dict(kind="nattn", grid_type=1, nlat_in=40, nlon_in=200, nlat_out=40, nlon_out=200, theta=0.2, batch=2, heads=1, d=32, dtype="f32"),
+    dict(kind="nattn", grid_type=0, nlat_in=65, nlon_in=256, nlat_out=65, nlon_out=256, theta=2 * math.pi / 64, batch=1, heads=2, d=32, dtype="f32"),
+    dict(kind="nattn", grid_type=0, nlat_in=33, nlon_in=192, nlat_out=33, nlon_out=192, theta=0.3, batch=9, heads=2, d=32, dtype="f32"),
 ]
 
 
