@@ -810,6 +810,7 @@ int s2_nattn_bwd_tiled(const S2DeviceTables &t, int nbh, int d, int e, float sca
 {
     const int nseg_o = (t.nlon_out + kSegB - 1) / kSegB;
     static bool cfg_dq1 = false, cfg_dq2 = false, cfg_kv = false;
+    static const bool no_stream = std::getenv("S2_NO_STREAM") != nullptr;   // debugging aid: one-wave kernels instead
     // dense polar latitudes: dq on the matrix cores; the vector kernels see the remaining latitudes
     const S2DeviceTables &t_all = t;
     S2DeviceTables t_dq = t_all;
@@ -839,6 +840,8 @@ int s2_nattn_bwd_tiled(const S2DeviceTables &t, int nbh, int d, int e, float sca
                                go, dq, Dws);
         }
         const long nrows = t.nlat_out - nm - nsplit_o;
+        if (nrows > 0 && !no_stream && s2_nattn_stream_supported(t_dq, d, e))
+            return s2_nattn_bwd_dq_stream(t_dq, nbh, scale, q, k, v, o, lse, go, dq, Dws, st);
         S2TraceScope tr("nattn_bwd_dq_tiled<1 wave>", nbh * t_dq.fwd_pairs[3], st);
         if (nrows > 0)
             hipLaunchKernelGGL(k1, dim3((unsigned)(nrows * nbh * nseg_o)), dim3(64), lds_wave, st, t_dq, nbh, nsplit_o,
@@ -911,6 +914,8 @@ int s2_nattn_bwd_tiled(const S2DeviceTables &t, int nbh, int d, int e, float sca
                            Dws, dk, dv);
     }
     const long nrows = t.nlat_in - nmi - nsplit_i;
+    if (nrows > 0 && !no_stream && s2_nattn_stream_dkdv_supported(t_kv, d, e))
+        return s2_nattn_bwd_dkdv_stream(t_kv, nbh, scale, q, k, v, lse, go, Dws, dk, dv, st);
     S2TraceScope tr("nattn_bwd_dkdv_tiled<1 wave>", nbh * t.bwd_pairs[3], st);
     if (nrows > 0)
         hipLaunchKernelGGL((nattn_bwd_dkdv_tiled<1>), dim3((unsigned)(nrows * nbh * nseg_i)), dim3(64), lds_wave, st,

@@ -308,7 +308,438 @@ nattn_fwd_stream(S2DeviceTables t, int nbh, int nsl, float qscale, const float *
     }
 }
 
+
+// ------------------------------------------------------------- backward ----------
+//
+// Same streaming structure with the register budget of the gradient kernels: FOUR adjacent lanes share four
+// consecutive points and each carries 8 of the 32 channels (channel 4 i + quarter, so the four lanes read
+// adjacent LDS rows; with a pitch of 16 mod 64 floats their b128 strips cover the 64 banks exactly once).
+// A wavefront owns 64 longitudes, a workgroup one strip of 64 longitudes plus the halo (128 window columns).
+//   dq    : owners are output points; rows of K and V stream by (s = q.K, dP = dout.V, dq += dS K); stores D_i.
+//   dk/dv : owners are INPUT points (transposed neighborhood); rows of q, dout, lse and D stream by.
+
+constexpr int kDL = 8;                    // channels per lane
+constexpr int kSegQ = 64;                 // owner longitudes per workgroup
+constexpr int kWinQ = kSegQ + 2 * kHalo;  // 128 window columns = two 64-lane loads per row
+constexpr int kPitchQ = kWinQ + 16;       // 16 mod 64
+constexpr float kLog2e = 1.4426950408889634f;
+
+__device__ __forceinline__ float quad_sum(float x)
+{
+    x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0xB1, 0xf, 0xf, true));
+    x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x4E, 0xf, 0xf, true));
+    return x;
+}
+
+// This wavefront's share of the copy of one streamed latitude into a ring slot: rows wave, wave + nw, ... of
+// the nrows rows; row rr comes from base[rr / 32] + (rr % 32) * stride for the 64 channel rows and from
+// extra[rr - 64] for the per-point rows (lse, D) behind them.
+__device__ __forceinline__ void stage_row_q(const float *a, const float *b, size_t stride, const float *x0,
+                                            const float *x1, int nrows, unsigned (&voff)[2], float *slot, int wave,
+                                            int nw)
+{
+#pragma unroll
+    for (int c = 0; c < 2; ++c) asm volatile("" : "+v"(voff[c]));
+    for (int rr = wave; rr < nrows; rr += nw) {
+        const float *src = rr < kD ? a + size_t(rr) * stride
+                                   : rr < 2 * kD ? b + size_t(rr - kD) * stride : rr == 2 * kD ? x0 : x1;
+        const char *rb = reinterpret_cast<const char *>(src);
+        asm volatile("" : "+s"(rb));
+        float *dst = slot + rr * kPitchQ;
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+            __builtin_amdgcn_global_load_lds((gptr_t)(rb + voff[c]), (lptr_t)(dst + 64 * c), 4, 0, 0);
+    }
+}
+
+template <int SL4>
+__device__ __forceinline__ void read_strip_q(const float *p, float (&st)[4 * SL4])
+{
+#pragma unroll
+    for (int a = 0; a < SL4; ++a) {
+        const float4 x = *reinterpret_cast<const float4 *>(p + 4 * a);
+        st[4 * a] = x.x; st[4 * a + 1] = x.y; st[4 * a + 2] = x.z; st[4 * a + 3] = x.w;
+    }
+}
+
+// acc[r][tt] += own[r][i] * row_i[r + tt] over the lane's 8 channels (rows 4 i of p)
+template <int NT>
+__device__ __forceinline__ void dot_rows(const float *p, const float (&own)[4][kDL], float (&acc)[4][NT])
+{
+    constexpr int SL4 = (NT + 6) / 4;
+#pragma unroll
+    for (int i = 0; i < kDL; ++i) {
+        float st[4 * SL4];
+        read_strip_q<SL4>(p + 4 * i * kPitchQ, st);
+#pragma unroll
+        for (int tt = 0; tt < NT; ++tt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[r][tt] = fmaf(own[r][i], st[r + tt], acc[r][tt]);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+// out[r][i] += sum_tt w[r][tt] * row_i[r + tt]
+template <int NT>
+__device__ __forceinline__ void axpy_rows(const float *p, const float (&w)[4][NT], float (&out)[4][kDL])
+{
+    constexpr int SL4 = (NT + 6) / 4;
+#pragma unroll
+    for (int i = 0; i < kDL; ++i) {
+        float st[4 * SL4];
+        read_strip_q<SL4>(p + 4 * i * kPitchQ, st);
+#pragma unroll
+        for (int tt = 0; tt < NT; ++tt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) out[r][i] = fmaf(w[r][tt], st[r + tt], out[r][i]);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+template <int NT>
+__device__ __forceinline__ void stream_run_dq(const float *slot, int soff, int lead, float wq,
+                                              const float (&q)[4][kDL], const float (&go)[4][kDL],
+                                              const float (&lse2)[4], const float (&Dr)[4], float (&dq)[4][kDL])
+{
+    float s[4][NT], dp[4][NT];
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int tt = 0; tt < NT; ++tt) { s[r][tt] = 0.f; dp[r][tt] = 0.f; }
+    const float *kp = slot + soff, *vp = kp + kD * kPitchQ;
+    dot_rows<NT>(kp, q, s);
+    dot_rows<NT>(vp, go, dp);
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int tt = 0; tt < NT; ++tt) {
+            const float sv = quad_sum(s[r][tt]), dv = quad_sum(dp[r][tt]);
+            const float w = wq * __builtin_amdgcn_exp2f(sv - lse2[r]) * (dv - Dr[r]);
+            s[r][tt] = (tt < 3 && tt < lead) ? 0.f : w;   // offsets in front of the arc
+        }
+    axpy_rows<NT>(kp, s, dq);
+}
+
+__global__ void __launch_bounds__(64 * kMaxWaves)
+nattn_bwd_dq_stream(S2DeviceTables t, int nbh, int nsl, float scale, const float *__restrict__ q,
+                    const float *__restrict__ k, const float *__restrict__ v, const float *__restrict__ o,
+                    const float *__restrict__ lse, const float *__restrict__ go, float *__restrict__ dq,
+                    float *__restrict__ Dws)
+{
+    extern __shared__ __attribute__((aligned(16))) float smem[];
+    constexpr int kSlotQ = 2 * kD * kPitchQ;
+    const int nw = blockDim.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int nseg = (t.nlon_out + kSegQ - 1) / kSegQ;
+    int id = blockIdx.x;
+    const int seg = id % nseg; id /= nseg;
+    const int bh = id % nbh;
+    int h_lo, h_hi;
+    segment_bounds(id / nbh, nsl, t.st_lo, t.st_hi, t.st_cum, h_lo, h_hi);
+    if (h_lo >= h_hi) return;
+
+    const int nlon = t.nlon_in;
+    const int qd = lane & 3, u = lane >> 2;
+    const int w0 = seg * kSegQ + 4 * u;
+    const bool active = w0 < t.nlon_out;
+    const size_t so = size_t(t.nlat_out) * t.nlon_out, si = size_t(t.nlat_in) * t.nlon_in;
+    const int sbase = qd * kPitchQ + 4 * u;
+    const float qscale = scale * kLog2e;
+    unsigned voff[2];
+    {
+        const int xw = wrap2(seg * kSegQ - kHalo + nlon, nlon);
+#pragma unroll
+        for (int c = 0; c < 2; ++c) voff[c] = 4u * unsigned(wrap2(wrap2(xw + lane, nlon) + 64 * c, nlon));
+    }
+    const float *kslice = k + size_t(bh) * kD * si, *vslice = v + size_t(bh) * kD * si;
+    const int r_first = t.band_lo[h_lo];
+    const int r_last = t.band_lo[h_hi - 1] + t.band_n[h_hi - 1] - 1;
+
+    float qr[4][kDL], gr[4][kDL], dqa[4][kDL], lse2[4], Dr[4];
+    unsigned lane_off = unsigned((size_t(qd) * so + w0) * sizeof(float));
+    const size_t row4 = 4 * so * sizeof(float);   // the lane's next channel is four channel rows on
+    int h = h_lo + wave;
+    auto load_owner = [&](int hh) {
+        const size_t rowoff = (size_t(bh) * kD * so + size_t(hh) * t.nlon_out) * sizeof(float);
+        const char *pq = reinterpret_cast<const char *>(q) + rowoff;
+        const char *pg = reinterpret_cast<const char *>(go) + rowoff;
+        const char *po = reinterpret_cast<const char *>(o) + rowoff;
+        asm volatile("" : "+s"(pq)); asm volatile("" : "+s"(pg)); asm volatile("" : "+s"(po));
+        asm volatile("" : "+v"(lane_off));
+#pragma unroll
+        for (int r = 0; r < 4; ++r) Dr[r] = 0.f;
+#pragma unroll
+        for (int i = 0; i < kDL; ++i) {
+            float4 x = make_float4(0.f, 0.f, 0.f, 0.f), y = x, z = x;
+            if (active) {
+                x = *reinterpret_cast<const float4 *>(pq + lane_off);
+                y = *reinterpret_cast<const float4 *>(pg + lane_off);
+                z = *reinterpret_cast<const float4 *>(po + lane_off);
+            }
+            pq += row4; pg += row4; po += row4;
+            qr[0][i] = x.x * qscale; qr[1][i] = x.y * qscale; qr[2][i] = x.z * qscale; qr[3][i] = x.w * qscale;
+            gr[0][i] = y.x; gr[1][i] = y.y; gr[2][i] = y.z; gr[3][i] = y.w;
+            Dr[0] = fmaf(y.x, z.x, Dr[0]); Dr[1] = fmaf(y.y, z.y, Dr[1]);
+            Dr[2] = fmaf(y.z, z.z, Dr[2]); Dr[3] = fmaf(y.w, z.w, Dr[3]);
+            dqa[0][i] = dqa[1][i] = dqa[2][i] = dqa[3][i] = 0.f;
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) Dr[r] = quad_sum(Dr[r]);
+        const size_t io = size_t(bh) * so + size_t(hh) * t.nlon_out + w0;
+        float4 L = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (active) L = *reinterpret_cast<const float4 *>(lse + io);
+        lse2[0] = (L.x - t.ln_omega_ref) * kLog2e; lse2[1] = (L.y - t.ln_omega_ref) * kLog2e;
+        lse2[2] = (L.z - t.ln_omega_ref) * kLog2e; lse2[3] = (L.w - t.ln_omega_ref) * kLog2e;
+        if (active && qd == 0) *reinterpret_cast<float4 *>(Dws + io) = make_float4(Dr[0], Dr[1], Dr[2], Dr[3]);
+    };
+    auto store_owner = [&](int hh) {
+        if (!active) return;
+        char *pd = reinterpret_cast<char *>(dq) + (size_t(bh) * kD * so + size_t(hh) * t.nlon_out) * sizeof(float);
+        asm volatile("" : "+s"(pd));
+        asm volatile("" : "+v"(lane_off));
+#pragma unroll
+        for (int i = 0; i < kDL; ++i) {
+            *reinterpret_cast<float4 *>(pd + lane_off) =
+                make_float4(dqa[0][i] * scale, dqa[1][i] * scale, dqa[2][i] * scale, dqa[3][i] * scale);
+            pd += row4;
+        }
+    };
+    if (h < h_hi) load_owner(h);
+
+    stage_row_q(kslice + size_t(r_first) * nlon, vslice + size_t(r_first) * nlon, si, nullptr, nullptr, 2 * kD, voff,
+                smem, wave, nw);
+    for (int r = r_first; r <= r_last; ++r) {
+        const int cur = (r - r_first) & 1;
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (r < r_last)
+            stage_row_q(kslice + size_t(r + 1) * nlon, vslice + size_t(r + 1) * nlon, si, nullptr, nullptr, 2 * kD,
+                        voff, smem + (cur ^ 1) * kSlotQ, wave, nw);
+        const float *slot = smem + cur * kSlotQ;
+        const float wq = table_f(t.omega_rel, r);
+        while (h < h_hi) {
+            const int b = r - table_i(t.band_lo, h), nb = table_i(t.band_n, h);
+            if (b < 0) break;
+            if (b < nb) {
+                const int c = table_i(t.cnt, h * t.band_max + b);
+                const int a = kHalo - ((c - 1) >> 1);
+                int A = a & ~3, lead = a - A, span = a + c - A;
+                int soff = sbase + A;
+                while (span > kNTS) {
+                    stream_run_dq<kNTS>(slot, soff, lead, wq, qr, gr, lse2, Dr, dqa);
+                    lead = 0; soff += kNTS; span -= kNTS;
+                }
+#define S2_RUN(N) case N: stream_run_dq<N>(slot, soff, lead, wq, qr, gr, lse2, Dr, dqa); break;
+                switch (span) {
+                    S2_RUN(1) S2_RUN(2) S2_RUN(3) S2_RUN(4) S2_RUN(5) S2_RUN(6) S2_RUN(7) S2_RUN(8)
+                }
+#undef S2_RUN
+            }
+            if (b < nb - 1) break;
+            store_owner(h);
+            __builtin_amdgcn_sched_barrier(0);
+            h += nw;
+            if (h < h_hi) load_owner(h);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+}
+
+template <int NT>
+__device__ __forceinline__ void stream_run_dkdv(const float *slot, int soff, int xoff, int lead, float wq, float lref2,
+                                                const float (&kr)[4][kDL], const float (&vr)[4][kDL],
+                                                float (&dk)[4][kDL], float (&dv)[4][kDL])
+{
+    constexpr int SL4 = (NT + 6) / 4;
+    float s[4][NT], dp[4][NT];
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int tt = 0; tt < NT; ++tt) { s[r][tt] = 0.f; dp[r][tt] = 0.f; }
+    const float *qp = slot + soff, *gp = qp + kD * kPitchQ;
+    dot_rows<NT>(qp, kr, s);
+    dot_rows<NT>(gp, vr, dp);
+    {
+        // the streamed points' logsumexp and D (rows 64 and 65 of the slot, same columns for the four lanes)
+        float L2[4 * SL4], Dd[4 * SL4];
+        read_strip_q<SL4>(slot + 2 * kD * kPitchQ + xoff, L2);
+        read_strip_q<SL4>(slot + (2 * kD + 1) * kPitchQ + xoff, Dd);
+#pragma unroll
+        for (int j = 0; j < NT + 3; ++j) L2[j] = fmaf(L2[j], kLog2e, -lref2);
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int tt = 0; tt < NT; ++tt) {
+                const float sv = quad_sum(s[r][tt]), dvv = quad_sum(dp[r][tt]);
+                float pr = wq * __builtin_amdgcn_exp2f(sv - L2[r + tt]);
+                pr = (tt < 3 && tt < lead) ? 0.f : pr;   // offsets in front of the arc
+                dp[r][tt] = pr;
+                s[r][tt] = pr * (dvv - Dd[r + tt]);
+            }
+    }
+    axpy_rows<NT>(qp, s, dk);
+    axpy_rows<NT>(gp, dp, dv);
+}
+
+__global__ void __launch_bounds__(64 * kMaxWaves)
+nattn_bwd_dkdv_stream(S2DeviceTables t, int nbh, int nsl, float scale, const float *__restrict__ q,
+                      const float *__restrict__ k, const float *__restrict__ v, const float *__restrict__ lse,
+                      const float *__restrict__ go, const float *__restrict__ Dws, float *__restrict__ dk,
+                      float *__restrict__ dv)
+{
+    extern __shared__ __attribute__((aligned(16))) float smem[];
+    constexpr int kRowsKV = 2 * kD + 2;
+    constexpr int kSlotKV = kRowsKV * kPitchQ;
+    const int nw = blockDim.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int nseg = (t.nlon_in + kSegQ - 1) / kSegQ;
+    int id = blockIdx.x;
+    const int seg = id % nseg; id /= nseg;
+    const int bh = id % nbh;
+    int h_lo, h_hi;   // input latitudes owned by this workgroup
+    segment_bounds(id / nbh, nsl, t.tst_lo, t.tst_hi, t.tst_cum, h_lo, h_hi);
+    if (h_lo >= h_hi) return;
+
+    const int nlon = t.nlon_out;   // equal longitude counts: streamed rows are output latitudes
+    const int qd = lane & 3, u = lane >> 2;
+    const int w0 = seg * kSegQ + 4 * u;
+    const bool active = w0 < t.nlon_in;
+    const size_t so = size_t(t.nlat_out) * t.nlon_out, si = size_t(t.nlat_in) * t.nlon_in;
+    const int sbase = qd * kPitchQ + 4 * u, xbase = 4 * u;
+    const float qscale = scale * kLog2e, lref2 = t.ln_omega_ref * kLog2e;
+    unsigned voff[2];
+    {
+        const int xw = wrap2(seg * kSegQ - kHalo + nlon, nlon);
+#pragma unroll
+        for (int c = 0; c < 2; ++c) voff[c] = 4u * unsigned(wrap2(wrap2(xw + lane, nlon) + 64 * c, nlon));
+    }
+    const float *qslice = q + size_t(bh) * kD * so, *gslice = go + size_t(bh) * kD * so;
+    const float *lslice = lse + size_t(bh) * so, *dslice = Dws + size_t(bh) * so;
+    const int r_first = t.tband_lo[h_lo];
+    const int r_last = t.tband_lo[h_hi - 1] + t.tband_n[h_hi - 1] - 1;
+
+    float kr[4][kDL], vr[4][kDL], dka[4][kDL], dva[4][kDL];
+    unsigned lane_off = unsigned((size_t(qd) * si + w0) * sizeof(float));
+    const size_t row4 = 4 * si * sizeof(float);
+    int h = h_lo + wave;
+    float wq = 0.f;
+    auto load_owner = [&](int hh) {
+        const size_t rowoff = (size_t(bh) * kD * si + size_t(hh) * t.nlon_in) * sizeof(float);
+        const char *pk = reinterpret_cast<const char *>(k) + rowoff;
+        const char *pv = reinterpret_cast<const char *>(v) + rowoff;
+        asm volatile("" : "+s"(pk)); asm volatile("" : "+s"(pv));
+        asm volatile("" : "+v"(lane_off));
+#pragma unroll
+        for (int i = 0; i < kDL; ++i) {
+            float4 x = make_float4(0.f, 0.f, 0.f, 0.f), y = x;
+            if (active) {
+                x = *reinterpret_cast<const float4 *>(pk + lane_off);
+                y = *reinterpret_cast<const float4 *>(pv + lane_off);
+            }
+            pk += row4; pv += row4;
+            kr[0][i] = x.x * qscale; kr[1][i] = x.y * qscale; kr[2][i] = x.z * qscale; kr[3][i] = x.w * qscale;
+            vr[0][i] = y.x; vr[1][i] = y.y; vr[2][i] = y.z; vr[3][i] = y.w;
+            dka[0][i] = dka[1][i] = dka[2][i] = dka[3][i] = 0.f;
+            dva[0][i] = dva[1][i] = dva[2][i] = dva[3][i] = 0.f;
+        }
+        wq = table_f(t.omega_rel, hh);
+    };
+    auto store_owner = [&](int hh) {
+        if (!active) return;
+        const size_t rowoff = (size_t(bh) * kD * si + size_t(hh) * t.nlon_in) * sizeof(float);
+        char *pk = reinterpret_cast<char *>(dk) + rowoff;
+        char *pv = reinterpret_cast<char *>(dv) + rowoff;
+        asm volatile("" : "+s"(pk)); asm volatile("" : "+s"(pv));
+        asm volatile("" : "+v"(lane_off));
+#pragma unroll
+        for (int i = 0; i < kDL; ++i) {
+            *reinterpret_cast<float4 *>(pk + lane_off) =
+                make_float4(dka[0][i] * scale, dka[1][i] * scale, dka[2][i] * scale, dka[3][i] * scale);
+            *reinterpret_cast<float4 *>(pv + lane_off) = make_float4(dva[0][i], dva[1][i], dva[2][i], dva[3][i]);
+            pk += row4; pv += row4;
+        }
+    };
+    if (h < h_hi) load_owner(h);
+
+    stage_row_q(qslice + size_t(r_first) * nlon, gslice + size_t(r_first) * nlon, so, lslice + size_t(r_first) * nlon,
+                dslice + size_t(r_first) * nlon, kRowsKV, voff, smem, wave, nw);
+    for (int r = r_first; r <= r_last; ++r) {
+        const int cur = (r - r_first) & 1;
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (r < r_last)
+            stage_row_q(qslice + size_t(r + 1) * nlon, gslice + size_t(r + 1) * nlon, so,
+                        lslice + size_t(r + 1) * nlon, dslice + size_t(r + 1) * nlon, kRowsKV, voff,
+                        smem + (cur ^ 1) * kSlotKV, wave, nw);
+        const float *slot = smem + cur * kSlotKV;
+        while (h < h_hi) {
+            const int b = r - table_i(t.tband_lo, h), nb = table_i(t.tband_n, h);
+            if (b < 0) break;
+            if (b < nb) {
+                const int c = table_i(t.tcnt, h * t.tband_max + b);
+                const int a = kHalo - ((c - 1) >> 1);
+                int A = a & ~3, lead = a - A, span = a + c - A;
+                int soff = sbase + A, xoff = xbase + A;
+                while (span > kNTS) {
+                    stream_run_dkdv<kNTS>(slot, soff, xoff, lead, wq, lref2, kr, vr, dka, dva);
+                    lead = 0; soff += kNTS; xoff += kNTS; span -= kNTS;
+                }
+#define S2_RUN(N) case N: stream_run_dkdv<N>(slot, soff, xoff, lead, wq, lref2, kr, vr, dka, dva); break;
+                switch (span) {
+                    S2_RUN(1) S2_RUN(2) S2_RUN(3) S2_RUN(4) S2_RUN(5) S2_RUN(6) S2_RUN(7) S2_RUN(8)
+                }
+#undef S2_RUN
+            }
+            if (b < nb - 1) break;
+            store_owner(h);
+            __builtin_amdgcn_sched_barrier(0);
+            h += nw;
+            if (h < h_hi) load_owner(h);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+}
+
 }  // namespace
+
+namespace {
+
+int num_compute_units()
+{
+    static const int ncu = [] {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1)
+            n = 256;
+        return n;
+    }();
+    return ncu;
+}
+
+// equal-cost latitude segments; one workgroup fills a compute unit, so aim at one workgroup per unit
+int num_segments(int per, int lo, int hi, int nw)
+{
+    const int ncu = num_compute_units();
+    int nsl = (ncu + per / 2) / per;
+    nsl = nsl < 1 ? 1 : nsl;
+    const int max_nsl = (hi - lo + nw - 1) / nw;
+    return nsl > max_nsl ? max_nsl : nsl;
+}
+
+template <class K>
+bool raise_lds(K kern, size_t lds, bool &done)
+{
+    if (!done) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                int(lds)) != hipSuccess)
+            return false;
+        done = true;
+    }
+    return true;
+}
+
+}  // namespace
+
 
 bool s2_nattn_stream_supported(const S2DeviceTables &t, int d, int e)
 {
@@ -321,28 +752,47 @@ int s2_nattn_fwd_stream(const S2DeviceTables &t, int nbh, float qscale, const fl
 {
     const int nw = t.st_nw;
     const int nseg = (t.nlon_out + kSegS - 1) / kSegS;
-    // equal-cost latitude segments; one workgroup fills a compute unit, so aim at one workgroup per unit
-    static const int ncu = [] {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1)
-            n = 256;
-        return n;
-    }();
-    const int per = nbh * nseg;
-    int nsl = (ncu + per / 2) / per;
-    nsl = nsl < 1 ? 1 : nsl;
-    const int max_nsl = (t.st_hi - t.st_lo + nw - 1) / nw;
-    nsl = nsl > max_nsl ? max_nsl : nsl;
+    const int nsl = num_segments(nbh * nseg, t.st_lo, t.st_hi, nw);
     const size_t lds = 2 * size_t(kSlot) * sizeof(float);
     static bool configured = false;
-    if (!configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(nattn_fwd_stream),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, int(lds)) != hipSuccess)
-            return -1;
-        configured = true;
-    }
+    if (!raise_lds(nattn_fwd_stream, lds, configured)) return -1;
     S2TraceScope tr("nattn_fwd_stream", nbh * t.fwd_pairs[3], st);
     hipLaunchKernelGGL(nattn_fwd_stream, dim3(unsigned(nsl * nbh * nseg)), dim3(64 * nw), lds, st, t, nbh, nsl, qscale, q,
                        k, v, out, lse);
+    return 0;
+}
+bool s2_nattn_stream_dkdv_supported(const S2DeviceTables &t, int d, int e)
+{
+    return d == kD && e == kD && t.pscale == 1 && t.nlon_in == t.nlon_out && t.nlon_in % 4 == 0 && t.nlon_in >= kWin &&
+           t.tst_nw >= 1 && t.tst_hi > t.tst_lo;
+}
+
+int s2_nattn_bwd_dq_stream(const S2DeviceTables &t, int nbh, float scale, const float *q, const float *k,
+                           const float *v, const float *o, const float *lse, const float *go, float *dq, float *Dws,
+                           hipStream_t st)
+{
+    const int nseg = (t.nlon_out + kSegQ - 1) / kSegQ;
+    const int nsl = num_segments(nbh * nseg, t.st_lo, t.st_hi, t.st_nw);
+    const size_t lds = 2 * size_t(2 * kD * kPitchQ) * sizeof(float);
+    static bool configured = false;
+    if (!raise_lds(nattn_bwd_dq_stream, lds, configured)) return -1;
+    S2TraceScope tr("nattn_bwd_dq_stream", nbh * t.fwd_pairs[3], st);
+    hipLaunchKernelGGL(nattn_bwd_dq_stream, dim3(unsigned(nsl * nbh * nseg)), dim3(64 * t.st_nw), lds, st, t, nbh, nsl,
+                       scale, q, k, v, o, lse, go, dq, Dws);
+    return 0;
+}
+
+int s2_nattn_bwd_dkdv_stream(const S2DeviceTables &t, int nbh, float scale, const float *q, const float *k,
+                             const float *v, const float *lse, const float *go, const float *Dws, float *dk, float *dv,
+                             hipStream_t st)
+{
+    const int nseg = (t.nlon_in + kSegQ - 1) / kSegQ;
+    const int nsl = num_segments(nbh * nseg, t.tst_lo, t.tst_hi, t.tst_nw);
+    const size_t lds = 2 * size_t((2 * kD + 2) * kPitchQ) * sizeof(float);
+    static bool configured = false;
+    if (!raise_lds(nattn_bwd_dkdv_stream, lds, configured)) return -1;
+    S2TraceScope tr("nattn_bwd_dkdv_stream", nbh * t.bwd_pairs[3], st);
+    hipLaunchKernelGGL(nattn_bwd_dkdv_stream, dim3(unsigned(nsl * nbh * nseg)), dim3(64 * t.tst_nw), lds, st, t, nbh,
+                       nsl, scale, q, k, v, lse, go, Dws, dk, dv);
     return 0;
 }
