@@ -7,7 +7,7 @@
 // workgroup walks DOWN a range of consecutive output latitudes for one strip of
 // 128 longitudes and one (batch, head): input latitude r is copied into LDS
 // once (all 32 K channels and all 32 V channels of the strip plus a halo of 32
-// columns on each side, LDS-direct loads, double buffered) and consumed by
+// columns on each side, LDS-direct loads into a ring of three slots) and consumed by
 // every wavefront whose current output latitude has r in its band.  Wavefront
 // w owns output latitudes first + w, first + w + NW, ...; NW is chosen on the
 // host so that the band of latitude h + NW begins no earlier than the last row
@@ -267,16 +267,18 @@ nattn_fwd_stream(S2DeviceTables t, int nbh, int nsl, float qscale, const float *
     };
     if (h < h_hi) load_q(h);
 
+    // Ring of three slots, rows requested two steps ahead.  A step is: barrier (row r is complete for everybody,
+    // everybody is done with row r - 1), work on row r, wait for this wavefront's share of row r + 1 (requested a
+    // whole step ago), request row r + 2 into the slot row r - 1 occupied.  Wavefronts with little work in a
+    // step reach the request early, so their copies overlap the arithmetic of the busy ones.
     stage_row(kslice + size_t(r_first) * nlon, vslice + size_t(r_first) * nlon, si, voff, smem, wave, nw);
+    if (r_first < r_last)
+        stage_row(kslice + size_t(r_first + 1) * nlon, vslice + size_t(r_first + 1) * nlon, si, voff, smem + kSlot,
+                  wave, nw);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    int cur = 0;
     for (int r = r_first; r <= r_last; ++r) {
-        const int cur = (r - r_first) & 1;
-        // row r has landed (everything this wavefront had in flight) and, after the barrier, everybody's share
-        // of it; everybody is also done with row r - 1, whose slot takes row r + 1
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
-        if (r < r_last)
-            stage_row(kslice + size_t(r + 1) * nlon, vslice + size_t(r + 1) * nlon, si, voff,
-                      smem + (cur ^ 1) * kSlot, wave, nw);
         const float *slot = smem + cur * kSlot;
         const float wq = table_f(t.omega_rel, r);
         while (h < h_hi) {
@@ -305,6 +307,12 @@ nattn_fwd_stream(S2DeviceTables t, int nbh, int nsl, float qscale, const float *
             if (h < h_hi) load_q(h);
             __builtin_amdgcn_sched_barrier(0);
         }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        const int nxt2 = cur == 0 ? 2 : cur - 1;   // (cur + 2) % 3
+        if (r + 2 <= r_last)
+            stage_row(kslice + size_t(r + 2) * nlon, vslice + size_t(r + 2) * nlon, si, voff, smem + nxt2 * kSlot, wave,
+                      nw);
+        cur = cur == 2 ? 0 : cur + 1;
     }
 }
 
@@ -318,6 +326,16 @@ nattn_fwd_stream(S2DeviceTables t, int nbh, int nsl, float qscale, const float *
 //   dq    : owners are output points; rows of K and V stream by (s = q.K, dP = dout.V, dq += dS K); stores D_i.
 //   dk/dv : owners are INPUT points (transposed neighborhood); rows of q, dout, lse and D stream by.
 
+#ifndef S2_NBQ
+#define S2_NBQ 2
+#define S2_NBK 2
+#endif
+#ifndef S2_FENCEB
+#define S2_FENCEB 1
+#endif
+#ifndef S2_NTQ
+#define S2_NTQ 8
+#endif
 constexpr int kDL = 8;                    // channels per lane
 constexpr int kSegQ = 64;                 // owner longitudes per workgroup
 constexpr int kWinQ = kSegQ + 2 * kHalo;  // 128 window columns = two 64-lane loads per row
@@ -362,37 +380,42 @@ __device__ __forceinline__ void read_strip_q(const float *p, float (&st)[4 * SL4
     }
 }
 
-// acc[r][tt] += own[r][i] * row_i[r + tt] over the lane's 8 channels (rows 4 i of p)
-template <int NT>
+// acc[r][tt] += own[r][i] * row_i[r + tt] over the lane's 8 channels (rows 4 i of p).  NB = 2: the next
+// channel's strip is requested before this channel's FMAs (where the register budget allows).
+template <int NT, int NB>
 __device__ __forceinline__ void dot_rows(const float *p, const float (&own)[4][kDL], float (&acc)[4][NT])
 {
     constexpr int SL4 = (NT + 6) / 4;
+    float st[NB][4 * SL4];
+    if (NB == 2) read_strip_q<SL4>(p, st[0]);
 #pragma unroll
     for (int i = 0; i < kDL; ++i) {
-        float st[4 * SL4];
-        read_strip_q<SL4>(p + 4 * i * kPitchQ, st);
+        if (NB == 1) read_strip_q<SL4>(p + 4 * i * kPitchQ, st[0]);
+        else if (i + 1 < kDL) read_strip_q<SL4>(p + 4 * (i + 1) * kPitchQ, st[(i + 1) % NB]);
 #pragma unroll
         for (int tt = 0; tt < NT; ++tt)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) acc[r][tt] = fmaf(own[r][i], st[r + tt], acc[r][tt]);
-        __builtin_amdgcn_sched_barrier(0);
+            for (int r = 0; r < 4; ++r) acc[r][tt] = fmaf(own[r][i], st[i % NB][r + tt], acc[r][tt]);
+        if (S2_FENCEB) __builtin_amdgcn_sched_barrier(0);
     }
 }
 
 // out[r][i] += sum_tt w[r][tt] * row_i[r + tt]
-template <int NT>
+template <int NT, int NB>
 __device__ __forceinline__ void axpy_rows(const float *p, const float (&w)[4][NT], float (&out)[4][kDL])
 {
     constexpr int SL4 = (NT + 6) / 4;
+    float st[NB][4 * SL4];
+    if (NB == 2) read_strip_q<SL4>(p, st[0]);
 #pragma unroll
     for (int i = 0; i < kDL; ++i) {
-        float st[4 * SL4];
-        read_strip_q<SL4>(p + 4 * i * kPitchQ, st);
+        if (NB == 1) read_strip_q<SL4>(p + 4 * i * kPitchQ, st[0]);
+        else if (i + 1 < kDL) read_strip_q<SL4>(p + 4 * (i + 1) * kPitchQ, st[(i + 1) % NB]);
 #pragma unroll
         for (int tt = 0; tt < NT; ++tt)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) out[r][i] = fmaf(w[r][tt], st[r + tt], out[r][i]);
-        __builtin_amdgcn_sched_barrier(0);
+            for (int r = 0; r < 4; ++r) out[r][i] = fmaf(w[r][tt], st[i % NB][r + tt], out[r][i]);
+        if (S2_FENCEB) __builtin_amdgcn_sched_barrier(0);
     }
 }
 
@@ -407,8 +430,8 @@ __device__ __forceinline__ void stream_run_dq(const float *slot, int soff, int l
 #pragma unroll
         for (int tt = 0; tt < NT; ++tt) { s[r][tt] = 0.f; dp[r][tt] = 0.f; }
     const float *kp = slot + soff, *vp = kp + kD * kPitchQ;
-    dot_rows<NT>(kp, q, s);
-    dot_rows<NT>(vp, go, dp);
+    dot_rows<NT, S2_NBQ>(kp, q, s);
+    dot_rows<NT, S2_NBQ>(vp, go, dp);
 #pragma unroll
     for (int r = 0; r < 4; ++r)
 #pragma unroll
@@ -417,7 +440,7 @@ __device__ __forceinline__ void stream_run_dq(const float *slot, int soff, int l
             const float w = wq * __builtin_amdgcn_exp2f(sv - lse2[r]) * (dv - Dr[r]);
             s[r][tt] = (tt < 3 && tt < lead) ? 0.f : w;   // offsets in front of the arc
         }
-    axpy_rows<NT>(kp, s, dq);
+    axpy_rows<NT, S2_NBQ>(kp, s, dq);
 }
 
 __global__ void __launch_bounds__(64 * kMaxWaves)
@@ -508,13 +531,13 @@ nattn_bwd_dq_stream(S2DeviceTables t, int nbh, int nsl, float scale, const float
 
     stage_row_q(kslice + size_t(r_first) * nlon, vslice + size_t(r_first) * nlon, si, nullptr, nullptr, 2 * kD, voff,
                 smem, wave, nw);
+    if (r_first < r_last)
+        stage_row_q(kslice + size_t(r_first + 1) * nlon, vslice + size_t(r_first + 1) * nlon, si, nullptr, nullptr,
+                    2 * kD, voff, smem + kSlotQ, wave, nw);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    int cur = 0;
     for (int r = r_first; r <= r_last; ++r) {
-        const int cur = (r - r_first) & 1;
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
-        if (r < r_last)
-            stage_row_q(kslice + size_t(r + 1) * nlon, vslice + size_t(r + 1) * nlon, si, nullptr, nullptr, 2 * kD,
-                        voff, smem + (cur ^ 1) * kSlotQ, wave, nw);
         const float *slot = smem + cur * kSlotQ;
         const float wq = table_f(t.omega_rel, r);
         while (h < h_hi) {
@@ -525,13 +548,16 @@ nattn_bwd_dq_stream(S2DeviceTables t, int nbh, int nsl, float scale, const float
                 const int a = kHalo - ((c - 1) >> 1);
                 int A = a & ~3, lead = a - A, span = a + c - A;
                 int soff = sbase + A;
-                while (span > kNTS) {
-                    stream_run_dq<kNTS>(slot, soff, lead, wq, qr, gr, lse2, Dr, dqa);
-                    lead = 0; soff += kNTS; span -= kNTS;
+                while (span > S2_NTQ) {
+                    stream_run_dq<8>(slot, soff, lead, wq, qr, gr, lse2, Dr, dqa);
+                    lead = 0; soff += 8; span -= 8;
                 }
 #define S2_RUN(N) case N: stream_run_dq<N>(slot, soff, lead, wq, qr, gr, lse2, Dr, dqa); break;
                 switch (span) {
                     S2_RUN(1) S2_RUN(2) S2_RUN(3) S2_RUN(4) S2_RUN(5) S2_RUN(6) S2_RUN(7) S2_RUN(8)
+#if S2_NTQ > 8
+                    S2_RUN(9) S2_RUN(10) S2_RUN(11) S2_RUN(12)
+#endif
                 }
 #undef S2_RUN
             }
@@ -542,6 +568,12 @@ nattn_bwd_dq_stream(S2DeviceTables t, int nbh, int nsl, float scale, const float
             if (h < h_hi) load_owner(h);
             __builtin_amdgcn_sched_barrier(0);
         }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        const int nxt2 = cur == 0 ? 2 : cur - 1;
+        if (r + 2 <= r_last)
+            stage_row_q(kslice + size_t(r + 2) * nlon, vslice + size_t(r + 2) * nlon, si, nullptr, nullptr, 2 * kD,
+                        voff, smem + nxt2 * kSlotQ, wave, nw);
+        cur = cur == 2 ? 0 : cur + 1;
     }
 }
 
@@ -557,8 +589,8 @@ __device__ __forceinline__ void stream_run_dkdv(const float *slot, int soff, int
 #pragma unroll
         for (int tt = 0; tt < NT; ++tt) { s[r][tt] = 0.f; dp[r][tt] = 0.f; }
     const float *qp = slot + soff, *gp = qp + kD * kPitchQ;
-    dot_rows<NT>(qp, kr, s);
-    dot_rows<NT>(gp, vr, dp);
+    dot_rows<NT, S2_NBK>(qp, kr, s);
+    dot_rows<NT, S2_NBK>(gp, vr, dp);
     {
         // the streamed points' logsumexp and D (rows 64 and 65 of the slot, same columns for the four lanes)
         float L2[4 * SL4], Dd[4 * SL4];
@@ -577,8 +609,8 @@ __device__ __forceinline__ void stream_run_dkdv(const float *slot, int soff, int
                 s[r][tt] = pr * (dvv - Dd[r + tt]);
             }
     }
-    axpy_rows<NT>(qp, s, dk);
-    axpy_rows<NT>(gp, dp, dv);
+    axpy_rows<NT, S2_NBK>(qp, s, dk);
+    axpy_rows<NT, S2_NBK>(gp, dp, dv);
 }
 
 __global__ void __launch_bounds__(64 * kMaxWaves)
@@ -661,16 +693,16 @@ nattn_bwd_dkdv_stream(S2DeviceTables t, int nbh, int nsl, float scale, const flo
     };
     if (h < h_hi) load_owner(h);
 
-    stage_row_q(qslice + size_t(r_first) * nlon, gslice + size_t(r_first) * nlon, so, lslice + size_t(r_first) * nlon,
-                dslice + size_t(r_first) * nlon, kRowsKV, voff, smem, wave, nw);
+    auto stage = [&](int rr, int slot_idx) {
+        stage_row_q(qslice + size_t(rr) * nlon, gslice + size_t(rr) * nlon, so, lslice + size_t(rr) * nlon,
+                    dslice + size_t(rr) * nlon, kRowsKV, voff, smem + slot_idx * kSlotKV, wave, nw);
+    };
+    stage(r_first, 0);
+    if (r_first < r_last) stage(r_first + 1, 1);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    int cur = 0;
     for (int r = r_first; r <= r_last; ++r) {
-        const int cur = (r - r_first) & 1;
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
-        if (r < r_last)
-            stage_row_q(qslice + size_t(r + 1) * nlon, gslice + size_t(r + 1) * nlon, so,
-                        lslice + size_t(r + 1) * nlon, dslice + size_t(r + 1) * nlon, kRowsKV, voff,
-                        smem + (cur ^ 1) * kSlotKV, wave, nw);
         const float *slot = smem + cur * kSlotKV;
         while (h < h_hi) {
             const int b = r - table_i(t.tband_lo, h), nb = table_i(t.tband_n, h);
@@ -697,6 +729,9 @@ nattn_bwd_dkdv_stream(S2DeviceTables t, int nbh, int nsl, float scale, const flo
             if (h < h_hi) load_owner(h);
             __builtin_amdgcn_sched_barrier(0);
         }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        if (r + 2 <= r_last) stage(r + 2, cur == 0 ? 2 : cur - 1);
+        cur = cur == 2 ? 0 : cur + 1;
     }
 }
 
@@ -753,7 +788,7 @@ int s2_nattn_fwd_stream(const S2DeviceTables &t, int nbh, float qscale, const fl
     const int nw = t.st_nw;
     const int nseg = (t.nlon_out + kSegS - 1) / kSegS;
     const int nsl = num_segments(nbh * nseg, t.st_lo, t.st_hi, nw);
-    const size_t lds = 2 * size_t(kSlot) * sizeof(float);
+    const size_t lds = 3 * size_t(kSlot) * sizeof(float);
     static bool configured = false;
     if (!raise_lds(nattn_fwd_stream, lds, configured)) return -1;
     S2TraceScope tr("nattn_fwd_stream", nbh * t.fwd_pairs[3], st);
@@ -773,7 +808,7 @@ int s2_nattn_bwd_dq_stream(const S2DeviceTables &t, int nbh, float scale, const 
 {
     const int nseg = (t.nlon_out + kSegQ - 1) / kSegQ;
     const int nsl = num_segments(nbh * nseg, t.st_lo, t.st_hi, t.st_nw);
-    const size_t lds = 2 * size_t(2 * kD * kPitchQ) * sizeof(float);
+    const size_t lds = 3 * size_t(2 * kD * kPitchQ) * sizeof(float);
     static bool configured = false;
     if (!raise_lds(nattn_bwd_dq_stream, lds, configured)) return -1;
     S2TraceScope tr("nattn_bwd_dq_stream", nbh * t.fwd_pairs[3], st);
@@ -788,7 +823,7 @@ int s2_nattn_bwd_dkdv_stream(const S2DeviceTables &t, int nbh, float scale, cons
 {
     const int nseg = (t.nlon_in + kSegQ - 1) / kSegQ;
     const int nsl = num_segments(nbh * nseg, t.tst_lo, t.tst_hi, t.tst_nw);
-    const size_t lds = 2 * size_t((2 * kD + 2) * kPitchQ) * sizeof(float);
+    const size_t lds = 3 * size_t((2 * kD + 2) * kPitchQ) * sizeof(float);
     static bool configured = false;
     if (!raise_lds(nattn_bwd_dkdv_stream, lds, configured)) return -1;
     S2TraceScope tr("nattn_bwd_dkdv_stream", nbh * t.bwd_pairs[3], st);
