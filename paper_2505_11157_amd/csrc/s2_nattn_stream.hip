@@ -370,6 +370,29 @@ __device__ __forceinline__ void stage_row_q(const float *a, const float *b, size
     }
 }
 
+// Counting semaphores in LDS for the ring of row slots of the gradient kernels.  The wavefronts of a workgroup
+// do very different amounts of work on one streamed row (1 to 9+ offsets, depending on where the row lies in the
+// band of their latitude), so a barrier per row leaves them idle for a third of the time.  Instead, every
+// wavefront counts "my share of the row in this slot has landed" and "I am done reading this slot"; a wavefront
+// waits only for the count it needs, which lets the fast ones run one row ahead of the slow ones.  The waits are
+// bounded: if a count never arrives (which would be a bug) the wavefront goes on after about ten milliseconds
+// instead of hanging the device, and the results are then wrong rather than missing.
+__device__ __forceinline__ void sem_signal(unsigned *p, int lane)
+{
+    if (lane == 0) __hip_atomic_fetch_add(p, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+
+__device__ __forceinline__ void sem_wait(unsigned *p, unsigned target, bool &gave_up)
+{
+    if (gave_up) return;
+    for (int spin = 0; spin < (1 << 17); ++spin) {
+        const unsigned v = __hip_atomic_load(p, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP);
+        if (__builtin_amdgcn_readfirstlane(v) >= target) return;
+        __builtin_amdgcn_s_sleep(2);
+    }
+    gave_up = true;   // no further waiting in this wavefront: the kernel ends quickly whatever went wrong
+}
+
 template <int SL4>
 __device__ __forceinline__ void read_strip_q(const float *p, float (&st)[4 * SL4])
 {
@@ -529,15 +552,26 @@ nattn_bwd_dq_stream(S2DeviceTables t, int nbh, int nsl, float scale, const float
     };
     if (h < h_hi) load_owner(h);
 
-    stage_row_q(kslice + size_t(r_first) * nlon, vslice + size_t(r_first) * nlon, si, nullptr, nullptr, 2 * kD, voff,
-                smem, wave, nw);
-    if (r_first < r_last)
-        stage_row_q(kslice + size_t(r_first + 1) * nlon, vslice + size_t(r_first + 1) * nlon, si, nullptr, nullptr,
-                    2 * kD, voff, smem + kSlotQ, wave, nw);
+    // Ring of four slots, rows requested three steps ahead; see sem_signal / sem_wait.  A step is: wait until row r
+    // has landed for everybody, work on it, mark the slot as read, announce this wavefront's share of row r + 2
+    // (requested a whole step ago), wait until everybody has read row r - 1 and request row r + 3 into its slot.
+    unsigned *arrived = reinterpret_cast<unsigned *>(smem + 4 * kSlotQ), *released = arrived + 4;
+    if (threadIdx.x < 8) arrived[threadIdx.x] = 0u;
+    __syncthreads();
+    auto stage = [&](int rr, int slot_idx) {
+        stage_row_q(kslice + size_t(rr) * nlon, vslice + size_t(rr) * nlon, si, nullptr, nullptr, 2 * kD, voff,
+                    smem + slot_idx * kSlotQ, wave, nw);
+    };
+    for (int j = 0; j < 3; ++j)
+        if (r_first + j <= r_last) stage(r_first + j, j);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    for (int j = 0; j < 2; ++j)
+        if (r_first + j <= r_last) sem_signal(arrived + j, lane);
     int cur = 0;
+    bool gave_up = false;
+    unsigned fill = unsigned(nw);   // count that completes the current use of slot `cur`
     for (int r = r_first; r <= r_last; ++r) {
-        __syncthreads();
+        sem_wait(arrived + cur, fill, gave_up);
         const float *slot = smem + cur * kSlotQ;
         const float wq = table_f(t.omega_rel, r);
         while (h < h_hi) {
@@ -568,12 +602,17 @@ nattn_bwd_dq_stream(S2DeviceTables t, int nbh, int nsl, float scale, const float
             if (h < h_hi) load_owner(h);
             __builtin_amdgcn_sched_barrier(0);
         }
+        sem_signal(released + cur, lane);
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        const int nxt2 = cur == 0 ? 2 : cur - 1;
-        if (r + 2 <= r_last)
-            stage_row_q(kslice + size_t(r + 2) * nlon, vslice + size_t(r + 2) * nlon, si, nullptr, nullptr, 2 * kD,
-                        voff, smem + nxt2 * kSlotQ, wave, nw);
-        cur = cur == 2 ? 0 : cur + 1;
+        if (r + 2 <= r_last) sem_signal(arrived + ((cur + 2) & 3), lane);
+        if (r + 3 <= r_last) {
+            const int prev = (cur + 3) & 3;   // slot of row r - 1
+            // uses of that slot completed so far: one less than `fill / nw` if it lies ahead of `cur` in the ring
+            if (r > r_first) sem_wait(released + prev, cur == 0 ? fill - unsigned(nw) : fill, gave_up);
+            stage(r + 3, prev);
+        }
+        cur = (cur + 1) & 3;
+        if (cur == 0) fill += unsigned(nw);
     }
 }
 
@@ -697,12 +736,19 @@ nattn_bwd_dkdv_stream(S2DeviceTables t, int nbh, int nsl, float scale, const flo
         stage_row_q(qslice + size_t(rr) * nlon, gslice + size_t(rr) * nlon, so, lslice + size_t(rr) * nlon,
                     dslice + size_t(rr) * nlon, kRowsKV, voff, smem + slot_idx * kSlotKV, wave, nw);
     };
-    stage(r_first, 0);
-    if (r_first < r_last) stage(r_first + 1, 1);
+    unsigned *arrived = reinterpret_cast<unsigned *>(smem + 4 * kSlotKV), *released = arrived + 4;
+    if (threadIdx.x < 8) arrived[threadIdx.x] = 0u;
+    __syncthreads();
+    for (int j = 0; j < 3; ++j)
+        if (r_first + j <= r_last) stage(r_first + j, j);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    for (int j = 0; j < 2; ++j)
+        if (r_first + j <= r_last) sem_signal(arrived + j, lane);
     int cur = 0;
+    bool gave_up = false;
+    unsigned fill = unsigned(nw);
     for (int r = r_first; r <= r_last; ++r) {
-        __syncthreads();
+        sem_wait(arrived + cur, fill, gave_up);
         const float *slot = smem + cur * kSlotKV;
         while (h < h_hi) {
             const int b = r - table_i(t.tband_lo, h), nb = table_i(t.tband_n, h);
@@ -729,9 +775,16 @@ nattn_bwd_dkdv_stream(S2DeviceTables t, int nbh, int nsl, float scale, const flo
             if (h < h_hi) load_owner(h);
             __builtin_amdgcn_sched_barrier(0);
         }
+        sem_signal(released + cur, lane);
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        if (r + 2 <= r_last) stage(r + 2, cur == 0 ? 2 : cur - 1);
-        cur = cur == 2 ? 0 : cur + 1;
+        if (r + 2 <= r_last) sem_signal(arrived + ((cur + 2) & 3), lane);
+        if (r + 3 <= r_last) {
+            const int prev = (cur + 3) & 3;
+            if (r > r_first) sem_wait(released + prev, cur == 0 ? fill - unsigned(nw) : fill, gave_up);
+            stage(r + 3, prev);
+        }
+        cur = (cur + 1) & 3;
+        if (cur == 0) fill += unsigned(nw);
     }
 }
 
@@ -808,7 +861,7 @@ int s2_nattn_bwd_dq_stream(const S2DeviceTables &t, int nbh, float scale, const 
 {
     const int nseg = (t.nlon_out + kSegQ - 1) / kSegQ;
     const int nsl = num_segments(nbh * nseg, t.st_lo, t.st_hi, t.st_nw);
-    const size_t lds = 3 * size_t(2 * kD * kPitchQ) * sizeof(float);
+    const size_t lds = 4 * size_t(2 * kD * kPitchQ) * sizeof(float) + 8 * sizeof(unsigned);
     static bool configured = false;
     if (!raise_lds(nattn_bwd_dq_stream, lds, configured)) return -1;
     S2TraceScope tr("nattn_bwd_dq_stream", nbh * t.fwd_pairs[3], st);
@@ -823,7 +876,7 @@ int s2_nattn_bwd_dkdv_stream(const S2DeviceTables &t, int nbh, float scale, cons
 {
     const int nseg = (t.nlon_in + kSegQ - 1) / kSegQ;
     const int nsl = num_segments(nbh * nseg, t.tst_lo, t.tst_hi, t.tst_nw);
-    const size_t lds = 3 * size_t((2 * kD + 2) * kPitchQ) * sizeof(float);
+    const size_t lds = 4 * size_t((2 * kD + 2) * kPitchQ) * sizeof(float) + 8 * sizeof(unsigned);
     static bool configured = false;
     if (!raise_lds(nattn_bwd_dkdv_stream, lds, configured)) return -1;
     S2TraceScope tr("nattn_bwd_dkdv_stream", nbh * t.bwd_pairs[3], st);
