@@ -840,7 +840,7 @@ int s2_nattn_bwd_tiled(const S2DeviceTables &t, int nbh, int d, int e, float sca
                                go, dq, Dws);
         }
         const long nrows = t.nlat_out - nm - nsplit_o;
-        if (nrows > 0 && !no_stream && s2_nattn_stream_supported(t_dq, d, e))
+        if (nrows > 0 && !no_stream && s2_nattn_stream_dq_supported(t_dq, d, e))
             return s2_nattn_bwd_dq_stream(t_dq, nbh, scale, q, k, v, o, lse, go, dq, Dws, st);
         S2TraceScope tr("nattn_bwd_dq_tiled<1 wave>", nbh * t_dq.fwd_pairs[3], st);
         if (nrows > 0)

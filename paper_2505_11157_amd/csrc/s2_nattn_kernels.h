@@ -42,6 +42,7 @@ int s2_nattn_bwd_dkdv_mfma(const S2DeviceTables &t, int nbh, int nrows, float sc
 bool s2_nattn_stream_supported(const S2DeviceTables &t, int d, int e);
 int s2_nattn_fwd_stream(const S2DeviceTables &t, int nbh, float qscale, const float *q, const float *k,
                         const float *v, float *out, float *lse, hipStream_t st);
+bool s2_nattn_stream_dq_supported(const S2DeviceTables &t, int d, int e);
 bool s2_nattn_stream_dkdv_supported(const S2DeviceTables &t, int d, int e);
 int s2_nattn_bwd_dq_stream(const S2DeviceTables &t, int nbh, float scale, const float *q, const float *k,
                            const float *v, const float *o, const float *lse, const float *go, float *dq, float *Dws,

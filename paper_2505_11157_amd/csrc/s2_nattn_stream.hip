@@ -849,9 +849,15 @@ int s2_nattn_fwd_stream(const S2DeviceTables &t, int nbh, float qscale, const fl
                        k, v, out, lse);
     return 0;
 }
+bool s2_nattn_stream_dq_supported(const S2DeviceTables &t, int d, int e)
+{
+    return d == kD && e == kD && t.pscale == 1 && t.nlon_in == t.nlon_out && t.nlon_in % 4 == 0 && t.nlon_in >= kWinQ &&
+           t.st_nw >= 1 && t.st_hi > t.st_lo;
+}
+
 bool s2_nattn_stream_dkdv_supported(const S2DeviceTables &t, int d, int e)
 {
-    return d == kD && e == kD && t.pscale == 1 && t.nlon_in == t.nlon_out && t.nlon_in % 4 == 0 && t.nlon_in >= kWin &&
+    return d == kD && e == kD && t.pscale == 1 && t.nlon_in == t.nlon_out && t.nlon_in % 4 == 0 && t.nlon_in >= kWinQ &&
            t.tst_nw >= 1 && t.tst_hi > t.tst_lo;
 }
 

@@ -147,6 +147,44 @@ def test_vector_kernels_cover_dense_latitudes_too():
     assert r.returncode == 0 and "child ok" in r.stdout, r.stdout[-2000:] + r.stderr[-2000:]
 
 
+def test_one_wave_kernels_on_streaming_shapes():
+    # S2_NO_STREAM=1 (read once per process) keeps the light latitudes on the one-wavefront kernels, S2_NO_MFMA=1 the
+    # dense ones on the split vector kernels: the paths a shape takes when the streaming / matrix-core kernels do
+    # not apply, checked here on a shape where they do
+    import os, subprocess, sys
+    code = ("import sys; sys.path.insert(0, %r); sys.path.insert(0, %r)\n"
+            "import test_gpu_nattn as T\n"
+            "from paper_2505_11157_amd.workloads import make_inputs\n"
+            "c, arrs = make_inputs(T.SMALL[11], seed=5); T.run_case(c, arrs, [0, 2]); print('child ok')\n"
+            % (os.path.dirname(os.path.abspath(__file__)), os.path.dirname(os.path.dirname(os.path.abspath(__file__)))))
+    env = dict(os.environ, S2_NO_MFMA="1", S2_NO_STREAM="1")
+    r = subprocess.run([sys.executable, "-c", code], env=env, capture_output=True, text=True, timeout=240)
+    assert r.returncode == 0 and "child ok" in r.stdout, r.stdout[-2000:] + r.stderr[-2000:]
+
+
+@pytest.mark.parametrize("which", ["cfg3", "small11", "small13"])
+def test_streaming_kernels_take_the_light_latitudes(which):
+    # the launches the library reports for one forward + backward: streaming kernels for the light latitudes
+    # wherever the shape allows them, never the one-wavefront kernels
+    if which == "cfg3":
+        c, arrs = make_inputs(3)
+        arrs = [a[:2] for a in arrs]
+        c = dict(c, batch=1, heads=2)
+    else:
+        c, arrs = make_inputs(SMALL[int(which[5:])], seed=9)
+    S.s2_trace_reset()
+    S.s2_trace_enable(True)
+    try:
+        run_case(c, arrs, [])
+        torch.cuda.synchronize()
+        names = {n for n, _, _ in S.s2_trace_entries()}
+    finally:
+        S.s2_trace_enable(False)
+        S.s2_trace_reset()
+    assert {"nattn_fwd_stream", "nattn_bwd_dq_stream", "nattn_bwd_dkdv_stream"} <= names, names
+    assert not any("1 wave" in n for n in names), names
+
+
 def test_errors_on_device():
     gd = grid_dict(1)
     g = _grid(gd)
