@@ -301,20 +301,22 @@ extern "C" int s2_grid_init(int grid_type, int nlat_in, int nlon_in, int nlat_ou
     order_by_work(nlat_in, g->tband_n, g->tcnt, g->tband_max, g->trow_order);
     // split classes: a latitude whose disk holds more than 260 * P / 2 offsets per point is split P ways
     constexpr long T = 260;
-    auto classify = [](int n_rows, const std::vector<int> &n, const std::vector<int> &tab, int bmax, int (&cls)[4],
-                        double (&pairs)[4], double per_entry) {
+    auto classify = [](int n_rows, const std::vector<int> &n, const std::vector<int> &tab, int bmax, long thr,
+                       int (&cls)[4], double (&pairs)[4], double per_entry) {
         cls[0] = cls[1] = cls[2] = cls[3] = 0;
         pairs[0] = pairs[1] = pairs[2] = pairs[3] = 0.0;
         for (int r = 0; r < n_rows; ++r) {
             long work = 0;
             for (int b = 0; b < n[r]; ++b) work += tab[size_t(r) * bmax + b];
-            const int c = work > 4 * T ? 0 : work > 2 * T ? 1 : work > T ? 2 : 3;
+            const int c = work > 4 * thr ? 0 : work > 2 * thr ? 1 : work > thr ? 2 : 3;
             ++cls[c];
             pairs[c] += double(work) * per_entry;
         }
     };
-    classify(nlat_out, g->band_n, g->cnt, g->band_max, g->dt.fwd_cls, g->dt.fwd_pairs, double(nlon_out));
-    classify(nlat_in, g->tband_n, g->tcnt, g->tband_max, g->dt.bwd_cls, g->dt.bwd_pairs, double(nlon_out));
+    classify(nlat_out, g->band_n, g->cnt, g->band_max, T, g->dt.fwd_cls, g->dt.fwd_pairs, double(nlon_out));
+    classify(nlat_in, g->tband_n, g->tcnt, g->tband_max, T, g->dt.bwd_cls, g->dt.bwd_pairs, double(nlon_out));
+    classify(nlat_out, g->band_n, g->cnt, g->band_max, T / 4, g->dt.fwd_cls_fine, g->dt.fwd_pairs_fine, double(nlon_out));
+    classify(nlat_in, g->tband_n, g->tcnt, g->tband_max, T / 4, g->dt.bwd_cls_fine, g->dt.bwd_pairs_fine, double(nlon_out));
 
     // streaming plan for the light latitudes (work <= T): they must form one contiguous range whose bands
     // move monotonically, with short odd arcs (at most 65 offsets) on every row of the band

@@ -29,6 +29,10 @@ struct S2DeviceTables {
     int bwd_cls[4];           // same for input latitudes (trow_order)
     double fwd_pairs[4];      // (output, input) pairs per slice handled by each class of output latitudes
     double bwd_pairs[4];      // the same pairs counted per class of input latitudes
+    // the same four tables with all class thresholds divided by four: used when there are too few
+    // (batch, head) slices for the coarse split to fill the machine
+    int fwd_cls_fine[4], bwd_cls_fine[4];
+    double fwd_pairs_fine[4], bwd_pairs_fine[4];
     int nlat_in, nlon_in, nlat_out, nlon_out, pscale;
     // streaming kernels for the light latitudes (the last class): contiguous range [st_lo, st_hi) of output
     // latitudes and the number of wavefronts st_nw such that the band of latitude h + st_nw starts no earlier
@@ -62,6 +66,27 @@ struct s2_grid {
     const float *dev_bias_tok = nullptr;
     S2DeviceTables dt{};
 };
+
+// Class table for the split vector kernels.  `dense_taken`: another kernel has taken the latitudes above the
+// coarse threshold (classes 0-2 of the coarse table = class 0 of the fine one).  If the coarse split would start
+// so few wavefronts that most SIMDs hold fewer than eight, the copy `t` is switched to the fine split.
+inline void s2_pick_split(S2DeviceTables &t, bool fwd, int nbh, int nseg, bool dense_taken)
+{
+    int *c = fwd ? t.fwd_cls : t.bwd_cls;
+    double *p = fwd ? t.fwd_pairs : t.bwd_pairs;
+    if (dense_taken) {
+        c[0] = c[1] = c[2] = 0;
+        p[0] = p[1] = p[2] = 0.0;
+    }
+    const long waves = long(nbh) * nseg * (8 * c[0] + 4 * c[1] + 2 * c[2] + c[3]);
+    if (waves >= 8192) return;
+    const int *cf = fwd ? t.fwd_cls_fine : t.bwd_cls_fine;
+    const double *pf = fwd ? t.fwd_pairs_fine : t.bwd_pairs_fine;
+    for (int i = 0; i < 4; ++i) {
+        c[i] = dense_taken && i == 0 ? 0 : cf[i];
+        p[i] = dense_taken && i == 0 ? 0.0 : pf[i];
+    }
+}
 
 // Optional per-launch timing (s2_trace_* in the C ABI): when enabled, a scope records a HIP event
 // before and after the launches it encloses, on the stream they go to.

@@ -818,8 +818,14 @@ int s2_nattn_bwd_tiled(const S2DeviceTables &t, int nbh, int d, int e, float sca
     if (nm > 0) {
         if (s2_nattn_bwd_dq_mfma(t_all, nbh, nm, scale, q, k, v, o, lse, go, dq, Dws, st)) return -1;
         t_dq.row_order = t_all.row_order + nm;
-        t_dq.fwd_cls[0] = t_dq.fwd_cls[1] = t_dq.fwd_cls[2] = 0;
-        t_dq.fwd_pairs[0] = t_dq.fwd_pairs[1] = t_dq.fwd_pairs[2] = 0.0;
+    }
+    if (s2_nattn_stream_dq_supported(t_all, d, e)) {
+        if (nm > 0) {
+            t_dq.fwd_cls[0] = t_dq.fwd_cls[1] = t_dq.fwd_cls[2] = 0;
+            t_dq.fwd_pairs[0] = t_dq.fwd_pairs[1] = t_dq.fwd_pairs[2] = 0.0;
+        }
+    } else {
+        s2_pick_split(t_dq, true, nbh, nseg_o, nm > 0);
     }
     const int nsplit_o = t_dq.fwd_cls[0] + t_dq.fwd_cls[1] + t_dq.fwd_cls[2];
     auto run_dq = [&](auto k8, auto k1, size_t lds_wave, bool &cfg) {
@@ -842,9 +848,9 @@ int s2_nattn_bwd_tiled(const S2DeviceTables &t, int nbh, int d, int e, float sca
         const long nrows = t.nlat_out - nm - nsplit_o;
         if (nrows > 0 && !no_stream && s2_nattn_stream_dq_supported(t_dq, d, e))
             return s2_nattn_bwd_dq_stream(t_dq, nbh, scale, q, k, v, o, lse, go, dq, Dws, st);
+        if (nrows <= 0) return 0;
         S2TraceScope tr("nattn_bwd_dq_tiled<1 wave>", nbh * t_dq.fwd_pairs[3], st);
-        if (nrows > 0)
-            hipLaunchKernelGGL(k1, dim3((unsigned)(nrows * nbh * nseg_o)), dim3(64), lds_wave, st, t_dq, nbh, nsplit_o,
+        hipLaunchKernelGGL(k1, dim3((unsigned)(nrows * nbh * nseg_o)), dim3(64), lds_wave, st, t_dq, nbh, nsplit_o,
                                scale, q, k, v, o, lse, go, dq, Dws);
         return 0;
     };
@@ -855,8 +861,10 @@ int s2_nattn_bwd_tiled(const S2DeviceTables &t, int nbh, int d, int e, float sca
         rc = run_dq(nattn_bwd_dq_tiled<2, kWavesB>, nattn_bwd_dq_tiled<2, 1>, 2 * GeoB<2>::TILE * sizeof(float), cfg_dq2);
     if (rc) return rc;
 
-    if (t.pscale == 2) {
-        const int nseg_i = (t.nlon_in + kSegB - 1) / kSegB;
+    if (t_all.pscale == 2) {
+        const int nseg_i = (t_all.nlon_in + kSegB - 1) / kSegB;
+        S2DeviceTables t = t_all;
+        s2_pick_split(t, false, nbh, nseg_i, false);
         const int nsplit_i = t.bwd_cls[0] + t.bwd_cls[1] + t.bwd_cls[2];
         const size_t lds_wave = (2 * kTile2 + 2 * kPitch2) * sizeof(float);
         static bool cfg_kv2 = false;
@@ -878,9 +886,9 @@ int s2_nattn_bwd_tiled(const S2DeviceTables &t, int nbh, int d, int e, float sca
                                go, Dws, dk, dv);
         }
         const long nrows = t.nlat_in - nsplit_i;
+        if (nrows <= 0) return 0;
         S2TraceScope tr("nattn_bwd_dkdv2_tiled<1 wave>", nbh * t.bwd_pairs[3], st);
-        if (nrows > 0)
-            hipLaunchKernelGGL((nattn_bwd_dkdv2_tiled<1>), dim3((unsigned)(nrows * nbh * nseg_i)), dim3(64), lds_wave,
+        hipLaunchKernelGGL((nattn_bwd_dkdv2_tiled<1>), dim3((unsigned)(nrows * nbh * nseg_i)), dim3(64), lds_wave,
                                st, t, nbh, nsplit_i, scale, q, k, v, lse, go, Dws, dk, dv);
         return 0;
     }
@@ -891,8 +899,14 @@ int s2_nattn_bwd_tiled(const S2DeviceTables &t, int nbh, int d, int e, float sca
     if (nmi > 0) {
         if (s2_nattn_bwd_dkdv_mfma(t_all, nbh, nmi, scale, q, k, v, lse, go, Dws, dk, dv, st)) return -1;
         t_kv.trow_order = t_all.trow_order + nmi;
-        t_kv.bwd_cls[0] = t_kv.bwd_cls[1] = t_kv.bwd_cls[2] = 0;
-        t_kv.bwd_pairs[0] = t_kv.bwd_pairs[1] = t_kv.bwd_pairs[2] = 0.0;
+    }
+    if (s2_nattn_stream_dkdv_supported(t_all, d, e)) {
+        if (nmi > 0) {
+            t_kv.bwd_cls[0] = t_kv.bwd_cls[1] = t_kv.bwd_cls[2] = 0;
+            t_kv.bwd_pairs[0] = t_kv.bwd_pairs[1] = t_kv.bwd_pairs[2] = 0.0;
+        }
+    } else {
+        s2_pick_split(t_kv, false, nbh, nseg_i, nmi > 0);
     }
     const int nsplit_i = t_kv.bwd_cls[0] + t_kv.bwd_cls[1] + t_kv.bwd_cls[2];
     const size_t lds_wave = (2 * GeoB<1>::TILE + 2 * GeoB<1>::PITCH) * sizeof(float);
@@ -916,9 +930,9 @@ int s2_nattn_bwd_tiled(const S2DeviceTables &t, int nbh, int d, int e, float sca
     const long nrows = t.nlat_in - nmi - nsplit_i;
     if (nrows > 0 && !no_stream && s2_nattn_stream_dkdv_supported(t_kv, d, e))
         return s2_nattn_bwd_dkdv_stream(t_kv, nbh, scale, q, k, v, lse, go, Dws, dk, dv, st);
-    S2TraceScope tr("nattn_bwd_dkdv_tiled<1 wave>", nbh * t.bwd_pairs[3], st);
-    if (nrows > 0)
-        hipLaunchKernelGGL((nattn_bwd_dkdv_tiled<1>), dim3((unsigned)(nrows * nbh * nseg_i)), dim3(64), lds_wave, st,
+    if (nrows <= 0) return 0;
+    S2TraceScope tr("nattn_bwd_dkdv_tiled<1 wave>", nbh * t_kv.bwd_pairs[3], st);
+    hipLaunchKernelGGL((nattn_bwd_dkdv_tiled<1>), dim3((unsigned)(nrows * nbh * nseg_i)), dim3(64), lds_wave, st,
                            t_kv, nbh, nsplit_i, scale, q, k, v, lse, go, Dws, dk, dv);
     return 0;
 }

@@ -446,8 +446,14 @@ int s2_nattn_fwd_tiled(const S2DeviceTables &t, int nbh, int d, int e, float sca
     if (nm > 0) {
         s2_nattn_fwd_mfma(t, nbh, nm, scale, q, k, v, out, lse, st);
         tv.row_order = t.row_order + nm;
-        tv.fwd_cls[0] = tv.fwd_cls[1] = tv.fwd_cls[2] = 0;
-        tv.fwd_pairs[0] = tv.fwd_pairs[1] = tv.fwd_pairs[2] = 0.0;
+    }
+    if (s2_nattn_stream_supported(t, d, e)) {
+        if (nm > 0) {
+            tv.fwd_cls[0] = tv.fwd_cls[1] = tv.fwd_cls[2] = 0;
+            tv.fwd_pairs[0] = tv.fwd_pairs[1] = tv.fwd_pairs[2] = 0.0;
+        }
+    } else {
+        s2_pick_split(tv, true, nbh, (t.nlon_out + kSeg - 1) / kSeg, nm > 0);
     }
     if (t.pscale == 1) return launch_fwd_tiled<32, 1>(tv, nm, nbh, qscale, q, k, v, out, lse, st);
     return launch_fwd_tiled<32, 2>(tv, nm, nbh, qscale, q, k, v, out, lse, st);
