@@ -195,7 +195,7 @@ def main():
 
     if not args.no_cpu_baseline:
         import oracle as O
-        ns = args.cpu_slices or (4 if not is_global else 1)
+        ns = args.cpu_slices or (24 if not is_global else 1)   # about 10-20 s of oracle time on 16 cores
         ns = min(ns, B * H)
         a64 = [a[:ns].astype(np.float64) for a in arrs]
         t0 = time.perf_counter()

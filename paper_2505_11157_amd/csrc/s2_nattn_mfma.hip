@@ -60,6 +60,8 @@ __device__ __forceinline__ void stage_tile(const float *kb, const float *vb, siz
     }
 }
 
+// NSUB adjacent super-tiles are staged (and consumed) per barrier: half as many workgroup-wide waits for NSUB = 2.
+template <int NSUB>
 __global__ void __launch_bounds__(1024)
 nattn_fwd_mfma(S2DeviceTables t, int nbh, int nrows, float qscale, const float *__restrict__ q,
                const float *__restrict__ k, const float *__restrict__ v, float *__restrict__ out,
@@ -86,29 +88,39 @@ nattn_fwd_mfma(S2DeviceTables t, int nbh, int nrows, float qscale, const float *
     const int arow = 32 * ((col >> 2) & 1) + 4 * (col >> 3) + (col & 3);
 
     const int nb = t.band_n[h], hp0 = t.band_lo[h];
-    const int ntile = nlon / kTileCols;
+    const int ntile = nlon / (kTileCols * NSUB);
     const int total = nb * ntile;
     // prologue: stage the first super-tile
     {
         const float *kb = k + size_t(bh) * kD * si + size_t(hp0) * nlon;
         const float *vb = v + size_t(bh) * kD * si + size_t(hp0) * nlon;
-        stage_tile(kb, vb, si, 0, nlon, smem, wave, nwaves, lane);
+#pragma unroll
+        for (int sub = 0; sub < NSUB; ++sub)
+            stage_tile(kb, vb, si, kTileCols * sub, nlon, smem + sub * kTileFloats, wave, nwaves, lane);
     }
     for (int it = 0; it < total; ++it) {
-        const int b = it / ntile, x0 = (it - b * ntile) * kTileCols;
+        const int b = it / ntile, xg = (it - b * ntile) * kTileCols * NSUB;
         const int hp = hp0 + b;
-        float *tile = smem + (it & 1) * kTileFloats;
+        float *tiles = smem + (it & 1) * NSUB * kTileFloats;
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();     // tile `it` is complete; everyone has finished reading tile it-1
         if (it + 1 < total) {
-            const int b2 = (it + 1) / ntile, x2 = (it + 1 - b2 * ntile) * kTileCols;
+            const int b2 = (it + 1) / ntile, x2 = (it + 1 - b2 * ntile) * kTileCols * NSUB;
             const float *kb = k + size_t(bh) * kD * si + size_t(hp0 + b2) * nlon;
             const float *vb = v + size_t(bh) * kD * si + size_t(hp0 + b2) * nlon;
-            stage_tile(kb, vb, si, x2, nlon, smem + ((it + 1) & 1) * kTileFloats, wave, nwaves, lane);
+#pragma unroll
+            for (int sub = 0; sub < NSUB; ++sub)
+                stage_tile(kb, vb, si, x2 + kTileCols * sub, nlon,
+                           smem + (((it + 1) & 1) * NSUB + sub) * kTileFloats, wave, nwaves, lane);
         }
         const int c = t.cnt[h * t.band_max + b];
         const bool full = c == nlon;
         const int lo = full ? 0 : -((c - 1) >> 1);
+        const float wq = t.omega_rel[hp];
+#pragma unroll 1
+        for (int sub = 0; sub < NSUB; ++sub) {
+        const int x0 = xg + kTileCols * sub;
+        const float *tile = tiles + sub * kTileFloats;
         // does this wavefront's span of outputs touch the super-tile at all?
         if (!full) {
             // columns needed by outputs wave*32 .. wave*32+31: [wave*32 + lo, wave*32 + 31 + lo + c) on the circle
@@ -117,7 +129,6 @@ nattn_fwd_mfma(S2DeviceTables t, int nbh, int nrows, float qscale, const float *
             const bool overlap = rel < len || rel + kTileCols > nlon;
             if (!overlap) continue;
         }
-        const float wq = t.omega_rel[hp];
         const float *tk = tile, *tv = tile + kD * kPK;
         f32x16 s0 = {0}, s1 = {0};
 #pragma unroll
@@ -162,6 +173,7 @@ nattn_fwd_mfma(S2DeviceTables t, int nbh, int nrows, float qscale, const float *
         // O^T += V^T P^T: step i contracts super-tile columns (32*hl + i); A = V[channel = col][that column]
 #pragma unroll
         for (int i = 0; i < 32; ++i) o = mfma(tv[col * kPV + 32 * hl + i], p[i], o);
+        }
     }
     l += __shfl_xor(l, 32);
     const float inv = 1.f / l;
@@ -431,10 +443,22 @@ int s2_nattn_fwd_mfma_rows(const S2DeviceTables &t, int d, int e)
 int s2_nattn_fwd_mfma(const S2DeviceTables &t, int nbh, int nrows, float scale, const float *q, const float *k,
                       const float *v, float *out, float *lse, hipStream_t st)
 {
-    const size_t lds = 2 * size_t(kTileFloats) * sizeof(float);
+    const bool two = t.nlon_in % (2 * kTileCols) == 0;
+    const size_t lds = (two ? 4 : 2) * size_t(kTileFloats) * sizeof(float);
+    static bool configured = false;
+    if (!configured) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(nattn_fwd_mfma<2>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, int(4 * kTileFloats * sizeof(float))) != hipSuccess)
+            return -1;
+        configured = true;
+    }
     S2TraceScope tr("nattn_fwd_mfma", nbh * (t.fwd_pairs[0] + t.fwd_pairs[1] + t.fwd_pairs[2]), st);
-    hipLaunchKernelGGL(nattn_fwd_mfma, dim3((unsigned)(long(nrows) * nbh)), dim3(t.nlon_out * 2), lds, st, t, nbh, nrows,
-                       scale * 1.4426950408889634f, q, k, v, out, lse);
+    if (two)
+        hipLaunchKernelGGL(nattn_fwd_mfma<2>, dim3((unsigned)(long(nrows) * nbh)), dim3(t.nlon_out * 2), lds, st, t, nbh,
+                           nrows, scale * 1.4426950408889634f, q, k, v, out, lse);
+    else
+        hipLaunchKernelGGL(nattn_fwd_mfma<1>, dim3((unsigned)(long(nrows) * nbh)), dim3(t.nlon_out * 2), lds, st, t, nbh,
+                           nrows, scale * 1.4426950408889634f, q, k, v, out, lse);
     return 0;
 }
 
