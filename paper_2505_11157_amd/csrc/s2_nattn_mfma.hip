@@ -191,12 +191,15 @@ nattn_fwd_mfma(S2DeviceTables t, int nbh, int nrows, float qscale, const float *
 // Same tiling for dq_i = scale sum_j dS_ij k_j on the dense latitudes:
 //   S^T = K Q^T, dP^T = V dout^T (2 x 32 MFMAs), dS = p (dP - D) in registers,
 //   dQ^T += K^T-read-by-channel dS^T (32 MFMAs).
-// K is read both ways (by column for S^T, by channel for dQ^T); a pitch of 81 floats keeps both
-// patterns (almost) free of bank conflicts: 81 = 17 mod 64 is odd, so 32 channel rows hit 32 banks,
-// and the two channel rows of one S^T step are 17 banks apart.
+// K is read both ways (by column for S^T, by channel for dQ^T); a pitch of 79 floats keeps both
+// patterns (almost) free of bank conflicts: 79 = 15 mod 64 is odd, so 32 channel rows hit 32 banks,
+// and the two channel rows of one S^T step are 15 banks apart (one of 16 columns collides).  V is only
+// read by column: pitch 80 as in the forward.  With these pitches two workgroups with four tiles each
+// (two super-tiles per barrier, double buffered) still fit one compute unit's LDS.
 
-constexpr int kPB = 81;
-constexpr int kTileB = 2 * kD * kPB;     // K rows then V rows
+constexpr int kPB = 81;                  // dk/dv kernel: q and dout rows, both read both ways
+constexpr int kPQK = 79, kPQV = 80;
+constexpr int kTileB = kD * kPQK + kD * kPQV;     // K rows then V rows
 
 __device__ __forceinline__ void stage_tile_b(const float *ab, const float *bb, size_t stride, int x0, int ncol,
                                              float *tile, int wave, int nwaves, int lane)
@@ -205,10 +208,11 @@ __device__ __forceinline__ void stage_tile_b(const float *ab, const float *bb, s
     for (int r = wave; r < 2 * kD; r += nwaves) {
         const int c = r >= kD ? r - kD : r;
         const char *rb = reinterpret_cast<const char *>((r >= kD ? bb : ab) + size_t(c) * stride);
-        __builtin_amdgcn_global_load_lds((gptr_t)(rb + voff), (lptr_t)(tile + r * kPB), 4, 0, 0);
+        __builtin_amdgcn_global_load_lds((gptr_t)(rb + voff), (lptr_t)(r >= kD ? tile + kD * kPQK + c * kPQV : tile + c * kPQK), 4, 0, 0);
     }
 }
 
+template <int NSUB>
 __global__ void __launch_bounds__(1024)
 nattn_bwd_dq_mfma(S2DeviceTables t, int nbh, int nrows, float scale, const float *__restrict__ q,
                   const float *__restrict__ k, const float *__restrict__ v, const float *__restrict__ outp,
@@ -242,43 +246,52 @@ nattn_bwd_dq_mfma(S2DeviceTables t, int nbh, int nrows, float scale, const float
     const int arow = 32 * ((col >> 2) & 1) + 4 * (col >> 3) + (col & 3);
 
     const int nb = t.band_n[h], hp0 = t.band_lo[h];
-    const int ntile = nlon / kTileCols;
+    const int ntile = nlon / (kTileCols * NSUB);
     const int total = nb * ntile;
     {
         const float *kb = k + size_t(bh) * kD * si + size_t(hp0) * nlon;
         const float *vb = v + size_t(bh) * kD * si + size_t(hp0) * nlon;
-        stage_tile_b(kb, vb, si, 0, nlon, smem, wave, nwaves, lane);
+#pragma unroll
+        for (int sub = 0; sub < NSUB; ++sub)
+            stage_tile_b(kb, vb, si, kTileCols * sub, nlon, smem + sub * kTileB, wave, nwaves, lane);
     }
     for (int it = 0; it < total; ++it) {
-        const int b = it / ntile, x0 = (it - b * ntile) * kTileCols;
+        const int b = it / ntile, xg = (it - b * ntile) * kTileCols * NSUB;
         const int hp = hp0 + b;
-        float *tile = smem + (it & 1) * kTileB;
+        float *tiles = smem + (it & 1) * NSUB * kTileB;
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
         if (it + 1 < total) {
-            const int b2 = (it + 1) / ntile, x2 = (it + 1 - b2 * ntile) * kTileCols;
+            const int b2 = (it + 1) / ntile, x2 = (it + 1 - b2 * ntile) * kTileCols * NSUB;
             const float *kb = k + size_t(bh) * kD * si + size_t(hp0 + b2) * nlon;
             const float *vb = v + size_t(bh) * kD * si + size_t(hp0 + b2) * nlon;
-            stage_tile_b(kb, vb, si, x2, nlon, smem + ((it + 1) & 1) * kTileB, wave, nwaves, lane);
+#pragma unroll
+            for (int sub = 0; sub < NSUB; ++sub)
+                stage_tile_b(kb, vb, si, x2 + kTileCols * sub, nlon, smem + (((it + 1) & 1) * NSUB + sub) * kTileB, wave,
+                             nwaves, lane);
         }
         const int c = t.cnt[h * t.band_max + b];
         const bool full = c == nlon;
         const int lo = full ? 0 : -((c - 1) >> 1);
+        const float wq = t.omega_rel[hp];
+#pragma unroll 1
+        for (int sub = 0; sub < NSUB; ++sub) {
+        const int x0 = xg + kTileCols * sub;
+        const float *tile = tiles + sub * kTileB;
         if (!full) {
             const int need0 = wrapn(wave * 32 + lo, nlon), len = c + 31;
             const int rel = wrapn(x0 - need0, nlon);
             if (!(rel < len || rel + kTileCols > nlon)) continue;
         }
-        const float wq = t.omega_rel[hp];
-        const float *tk = tile, *tv = tile + kD * kPB;
+        const float *tk = tile, *tv = tile + kD * kPQK;
         f32x16 s0 = {0}, s1 = {0}, d0 = {0}, d1 = {0};
 #pragma unroll
         for (int s = 0; s < 16; ++s) {
-            const int ro = (2 * s + hl) * kPB + arow;
-            s0 = mfma(tk[ro], qop[s], s0);
-            s1 = mfma(tk[ro + 16], qop[s], s1);
-            d0 = mfma(tv[ro], gop[s], d0);
-            d1 = mfma(tv[ro + 16], gop[s], d1);
+            const int rk = (2 * s + hl) * kPQK + arow, rv = (2 * s + hl) * kPQV + arow;
+            s0 = mfma(tk[rk], qop[s], s0);
+            s1 = mfma(tk[rk + 16], qop[s], s1);
+            d0 = mfma(tv[rv], gop[s], d0);
+            d1 = mfma(tv[rv + 16], gop[s], d1);
         }
         float ds[32];
 #pragma unroll
@@ -297,7 +310,8 @@ nattn_bwd_dq_mfma(S2DeviceTables t, int nbh, int nrows, float scale, const float
         }
         // dQ^T += K dS^T: A = K[channel = col][super-tile column 32*hl + i]
 #pragma unroll
-        for (int i = 0; i < 32; ++i) acc = mfma(tk[col * kPB + 32 * hl + i], ds[i], acc);
+        for (int i = 0; i < 32; ++i) acc = mfma(tk[col * kPQK + 32 * hl + i], ds[i], acc);
+        }
     }
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
@@ -466,17 +480,22 @@ int s2_nattn_bwd_dq_mfma(const S2DeviceTables &t, int nbh, int nrows, float scal
                          const float *v, const float *o, const float *lse, const float *go, float *dq, float *Dws,
                          hipStream_t st)
 {
-    const size_t lds = 2 * size_t(kTileB) * sizeof(float);
+    const bool two = t.nlon_in % (2 * kTileCols) == 0;
+    const size_t lds = (two ? 4 : 2) * size_t(kTileB) * sizeof(float);
     static bool configured = false;
     if (!configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(nattn_bwd_dq_mfma),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, int(lds)) != hipSuccess)
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(nattn_bwd_dq_mfma<2>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, int(4 * kTileB * sizeof(float))) != hipSuccess)
             return -1;
         configured = true;
     }
     S2TraceScope tr("nattn_bwd_dq_mfma", nbh * (t.fwd_pairs[0] + t.fwd_pairs[1] + t.fwd_pairs[2]), st);
-    hipLaunchKernelGGL(nattn_bwd_dq_mfma, dim3((unsigned)(long(nrows) * nbh)), dim3(t.nlon_out * 2), lds, st, t, nbh,
-                       nrows, scale, q, k, v, o, lse, go, dq, Dws);
+    if (two)
+        hipLaunchKernelGGL(nattn_bwd_dq_mfma<2>, dim3((unsigned)(long(nrows) * nbh)), dim3(t.nlon_out * 2), lds, st, t,
+                           nbh, nrows, scale, q, k, v, o, lse, go, dq, Dws);
+    else
+        hipLaunchKernelGGL(nattn_bwd_dq_mfma<1>, dim3((unsigned)(long(nrows) * nbh)), dim3(t.nlon_out * 2), lds, st, t,
+                           nbh, nrows, scale, q, k, v, o, lse, go, dq, Dws);
     return 0;
 }
 
