@@ -197,7 +197,9 @@ nattn_fwd_mfma(S2DeviceTables t, int nbh, int nrows, float qscale, const float *
 // read by column: pitch 80 as in the forward.  With these pitches two workgroups with four tiles each
 // (two super-tiles per barrier, double buffered) still fit one compute unit's LDS.
 
-constexpr int kPB = 81;                  // dk/dv kernel: q and dout rows, both read both ways
+constexpr int kPC = 77;                  // dk/dv kernel: q and dout rows are both read both ways; 77 = 13 mod 64 is
+                                         // odd (32 channel rows hit 32 banks) and small enough for four tiles per
+                                         // workgroup at two workgroups per compute unit
 constexpr int kPQK = 79, kPQV = 80;
 constexpr int kTileB = kD * kPQK + kD * kPQV;     // K rows then V rows
 
@@ -329,7 +331,7 @@ nattn_bwd_dq_mfma(S2DeviceTables t, int nbh, int nrows, float scale, const float
 //   dK^T += Q-read-by-channel dS,  dV^T += dout-read-by-channel p.
 // Output (h, w) holds input (h', w_in) iff (w - w_in) mod nlon lies in the arc of (h, h'): same mask.
 
-constexpr int kTileC = (2 * kD + 2) * kPB;     // q rows, dout rows, lse row, D row
+constexpr int kTileC = 2 * kD * kPC + 2 * kTileCols;     // q rows, dout rows (pitch kPC), lse row, D row (64 each)
 
 __device__ __forceinline__ void stage_tile_c(const float *qb, const float *gb, const float *lrow, const float *drow,
                                              size_t stride, int x0, int ncol, float *tile, int wave, int nwaves, int lane)
@@ -340,10 +342,12 @@ __device__ __forceinline__ void stage_tile_c(const float *qb, const float *gb, c
         if (r < kD) rb = reinterpret_cast<const char *>(qb + size_t(r) * stride);
         else if (r < 2 * kD) rb = reinterpret_cast<const char *>(gb + size_t(r - kD) * stride);
         else rb = reinterpret_cast<const char *>(r == 2 * kD ? lrow : drow);
-        __builtin_amdgcn_global_load_lds((gptr_t)(rb + voff), (lptr_t)(tile + r * kPB), 4, 0, 0);
+        float *dst = r < 2 * kD ? tile + r * kPC : tile + 2 * kD * kPC + (r - 2 * kD) * kTileCols;
+        __builtin_amdgcn_global_load_lds((gptr_t)(rb + voff), (lptr_t)dst, 4, 0, 0);
     }
 }
 
+template <int NSUB>
 __global__ void __launch_bounds__(1024)
 nattn_bwd_dkdv_mfma(S2DeviceTables t, int nbh, int nrows, float scale, const float *__restrict__ q,
                     const float *__restrict__ k, const float *__restrict__ v, const float *__restrict__ lse,
@@ -374,37 +378,44 @@ nattn_bwd_dkdv_mfma(S2DeviceTables t, int nbh, int nrows, float scale, const flo
     const int arow = 32 * ((col >> 2) & 1) + 4 * (col >> 3) + (col & 3);
 
     const int nb = t.tband_n[hp], h0 = t.tband_lo[hp];
-    const int ntile = nlon / kTileCols;
+    const int ntile = nlon / (kTileCols * NSUB);
     const int total = nb * ntile;
     auto issue = [&](int itx, float *dst) {
-        const int b2 = itx / ntile, x2 = (itx - b2 * ntile) * kTileCols;
+        const int b2 = itx / ntile, x2 = (itx - b2 * ntile) * kTileCols * NSUB;
         const size_t rowoff = size_t(h0 + b2) * nlon;
-        stage_tile_c(q + size_t(bh) * kD * so + rowoff, go + size_t(bh) * kD * so + rowoff,
-                     lse + size_t(bh) * so + rowoff, Dws + size_t(bh) * so + rowoff, so, x2, nlon, dst, wave, nwaves, lane);
+#pragma unroll
+        for (int sub = 0; sub < NSUB; ++sub)
+            stage_tile_c(q + size_t(bh) * kD * so + rowoff, go + size_t(bh) * kD * so + rowoff,
+                         lse + size_t(bh) * so + rowoff, Dws + size_t(bh) * so + rowoff, so, x2 + kTileCols * sub, nlon,
+                         dst + sub * kTileC, wave, nwaves, lane);
     };
     issue(0, smem);
     for (int it = 0; it < total; ++it) {
-        const int b = it / ntile, x0 = (it - b * ntile) * kTileCols;
-        float *tile = smem + (it & 1) * kTileC;
+        const int b = it / ntile, xg = (it - b * ntile) * kTileCols * NSUB;
+        float *tiles = smem + (it & 1) * NSUB * kTileC;
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
-        if (it + 1 < total) issue(it + 1, smem + ((it + 1) & 1) * kTileC);
+        if (it + 1 < total) issue(it + 1, smem + ((it + 1) & 1) * NSUB * kTileC);
         const int c = t.tcnt[hp * t.tband_max + b];
         const bool full = c == nlon;
         const int lo = full ? 0 : -((c - 1) >> 1);
+#pragma unroll 1
+        for (int sub = 0; sub < NSUB; ++sub) {
+        const int x0 = xg + kTileCols * sub;
+        const float *tile = tiles + sub * kTileC;
         if (!full) {
             const int need0 = wrapn(wave * 32 + lo, nlon), len = c + 31;
             const int rel = wrapn(x0 - need0, nlon);
             if (!(rel < len || rel + kTileCols > nlon)) continue;
         }
-        const float *tq = tile, *tg = tile + kD * kPB, *tl = tile + 2 * kD * kPB, *td = tl + kPB;
+        const float *tq = tile, *tg = tile + kD * kPC, *tl = tile + 2 * kD * kPC, *td = tl + kTileCols;
         const int base = (x0 + 32 * hl - w - lo + 2 * nlon) % nlon;
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt) {
             f32x16 s = {0}, d = {0};
 #pragma unroll
             for (int st = 0; st < 16; ++st) {
-                const int ro = (2 * st + hl) * kPB + arow + 16 * mt;
+                const int ro = (2 * st + hl) * kPC + arow + 16 * mt;
                 s = mfma(tq[ro], kop[st], s);
                 d = mfma(tg[ro], vop[st], d);
             }
@@ -426,10 +437,11 @@ nattn_bwd_dkdv_mfma(S2DeviceTables t, int nbh, int nrows, float scale, const flo
             }
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                const int ao = col * kPB + 32 * hl + 16 * mt + i;
+                const int ao = col * kPC + 32 * hl + 16 * mt + i;
                 adk = mfma(tq[ao], ds[i], adk);
                 adv = mfma(tg[ao], p[i], adv);
             }
+        }
         }
     }
 #pragma unroll
@@ -512,16 +524,21 @@ int s2_nattn_bwd_dkdv_mfma(const S2DeviceTables &t, int nbh, int nrows, float sc
                            const float *v, const float *lse, const float *go, const float *Dws, float *dk, float *dv,
                            hipStream_t st)
 {
-    const size_t lds = 2 * size_t(kTileC) * sizeof(float);
+    const bool two = t.nlon_in % (2 * kTileCols) == 0;
+    const size_t lds = (two ? 4 : 2) * size_t(kTileC) * sizeof(float);
     static bool configured = false;
     if (!configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(nattn_bwd_dkdv_mfma),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, int(lds)) != hipSuccess)
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(nattn_bwd_dkdv_mfma<2>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, int(4 * kTileC * sizeof(float))) != hipSuccess)
             return -1;
         configured = true;
     }
     S2TraceScope tr("nattn_bwd_dkdv_mfma", nbh * (t.bwd_pairs[0] + t.bwd_pairs[1] + t.bwd_pairs[2]), st);
-    hipLaunchKernelGGL(nattn_bwd_dkdv_mfma, dim3((unsigned)(long(nrows) * nbh)), dim3(t.nlon_in * 2), lds, st, t, nbh,
-                       nrows, scale, q, k, v, lse, go, Dws, dk, dv);
+    if (two)
+        hipLaunchKernelGGL(nattn_bwd_dkdv_mfma<2>, dim3((unsigned)(long(nrows) * nbh)), dim3(t.nlon_in * 2), lds, st, t,
+                           nbh, nrows, scale, q, k, v, lse, go, Dws, dk, dv);
+    else
+        hipLaunchKernelGGL(nattn_bwd_dkdv_mfma<1>, dim3((unsigned)(long(nrows) * nbh)), dim3(t.nlon_in * 2), lds, st, t,
+                           nbh, nrows, scale, q, k, v, lse, go, Dws, dk, dv);
     return 0;
 }
