@@ -349,6 +349,26 @@ __device__ __forceinline__ float quad_sum(float x)
     return x;
 }
 
+// Reduce-scatter over a lane quad: a0..a3 are the lanes' partial sums for the quad's four points; lane qd gets
+// the full sum for point qd (b0, b1 = bits of qd).  The softmax arithmetic that follows is then done once per
+// (point, offset) by the lane that owns the point and handed back to the other three with quad_bcast, instead
+// of being repeated by all four lanes.
+__device__ __forceinline__ float quad_reduce_scatter(float a0, float a1, float a2, float a3, bool b0, bool b1)
+{
+    const float u01 = b0 ? a1 : a0, w01 = b0 ? a0 : a1;
+    const float t01 = u01 + __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, w01), 0xB1, 0xf, 0xf, true));
+    const float u23 = b0 ? a3 : a2, w23 = b0 ? a2 : a3;
+    const float t23 = u23 + __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, w23), 0xB1, 0xf, 0xf, true));
+    const float x = b1 ? t23 : t01, y = b1 ? t01 : t23;
+    return x + __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, y), 0x4E, 0xf, 0xf, true));
+}
+
+template <int R>
+__device__ __forceinline__ float quad_bcast(float x)   // value of lane R of the quad
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), R * 0x55, 0xf, 0xf, true));
+}
+
 // This wavefront's share of the copy of one streamed latitude into a ring slot: rows wave, wave + nw, ... of
 // the nrows rows; row rr comes from base[rr / 32] + (rr % 32) * stride for the 64 channel rows and from
 // extra[rr - 64] for the per-point rows (lse, D) behind them.
@@ -442,10 +462,11 @@ __device__ __forceinline__ void axpy_rows(const float *p, const float (&w)[4][NT
     }
 }
 
+// lse2o, Dro: logsumexp (base 2, relative) and D of the point this lane owns within its quad (point qd)
 template <int NT>
-__device__ __forceinline__ void stream_run_dq(const float *slot, int soff, int lead, float wq,
-                                              const float (&q)[4][kDL], const float (&go)[4][kDL],
-                                              const float (&lse2)[4], const float (&Dr)[4], float (&dq)[4][kDL])
+__device__ __forceinline__ void stream_run_dq(const float *slot, int soff, int lead, float wq, bool b0, bool b1,
+                                              const float (&q)[4][kDL], const float (&go)[4][kDL], float lse2o,
+                                              float Dro, float (&dq)[4][kDL])
 {
     float s[4][NT], dp[4][NT];
 #pragma unroll
@@ -456,13 +477,14 @@ __device__ __forceinline__ void stream_run_dq(const float *slot, int soff, int l
     dot_rows<NT, S2_NBQ>(kp, q, s);
     dot_rows<NT, S2_NBQ>(vp, go, dp);
 #pragma unroll
-    for (int r = 0; r < 4; ++r)
-#pragma unroll
-        for (int tt = 0; tt < NT; ++tt) {
-            const float sv = quad_sum(s[r][tt]), dv = quad_sum(dp[r][tt]);
-            const float w = wq * __builtin_amdgcn_exp2f(sv - lse2[r]) * (dv - Dr[r]);
-            s[r][tt] = (tt < 3 && tt < lead) ? 0.f : w;   // offsets in front of the arc
-        }
+    for (int tt = 0; tt < NT; ++tt) {
+        const float sv = quad_reduce_scatter(s[0][tt], s[1][tt], s[2][tt], s[3][tt], b0, b1);
+        const float dv = quad_reduce_scatter(dp[0][tt], dp[1][tt], dp[2][tt], dp[3][tt], b0, b1);
+        float w = wq * __builtin_amdgcn_exp2f(sv - lse2o) * (dv - Dro);
+        if (tt < 3) w = tt < lead ? 0.f : w;   // offsets in front of the arc
+        s[0][tt] = quad_bcast<0>(w); s[1][tt] = quad_bcast<1>(w);
+        s[2][tt] = quad_bcast<2>(w); s[3][tt] = quad_bcast<3>(w);
+    }
     axpy_rows<NT, S2_NBQ>(kp, s, dq);
 }
 
@@ -501,7 +523,8 @@ nattn_bwd_dq_stream(S2DeviceTables t, int nbh, int nsl, float scale, const float
     const int r_first = t.band_lo[h_lo];
     const int r_last = t.band_lo[h_hi - 1] + t.band_n[h_hi - 1] - 1;
 
-    float qr[4][kDL], gr[4][kDL], dqa[4][kDL], lse2[4], Dr[4];
+    float qr[4][kDL], gr[4][kDL], dqa[4][kDL], lse2[4], Dr[4], lse2o = 0.f, Dro = 0.f;
+    const bool b0 = qd & 1, b1 = qd & 2;
     unsigned lane_off = unsigned((size_t(qd) * so + w0) * sizeof(float));
     const size_t row4 = 4 * so * sizeof(float);   // the lane's next channel is four channel rows on
     int h = h_lo + wave;
@@ -537,6 +560,8 @@ nattn_bwd_dq_stream(S2DeviceTables t, int nbh, int nsl, float scale, const float
         lse2[0] = (L.x - t.ln_omega_ref) * kLog2e; lse2[1] = (L.y - t.ln_omega_ref) * kLog2e;
         lse2[2] = (L.z - t.ln_omega_ref) * kLog2e; lse2[3] = (L.w - t.ln_omega_ref) * kLog2e;
         if (active && qd == 0) *reinterpret_cast<float4 *>(Dws + io) = make_float4(Dr[0], Dr[1], Dr[2], Dr[3]);
+        lse2o = b1 ? (b0 ? lse2[3] : lse2[2]) : (b0 ? lse2[1] : lse2[0]);
+        Dro = b1 ? (b0 ? Dr[3] : Dr[2]) : (b0 ? Dr[1] : Dr[0]);
     };
     auto store_owner = [&](int hh) {
         if (!active) return;
@@ -583,10 +608,10 @@ nattn_bwd_dq_stream(S2DeviceTables t, int nbh, int nsl, float scale, const float
                 int A = a & ~3, lead = a - A, span = a + c - A;
                 int soff = sbase + A;
                 while (span > S2_NTQ) {
-                    stream_run_dq<8>(slot, soff, lead, wq, qr, gr, lse2, Dr, dqa);
+                    stream_run_dq<8>(slot, soff, lead, wq, b0, b1, qr, gr, lse2o, Dro, dqa);
                     lead = 0; soff += 8; span -= 8;
                 }
-#define S2_RUN(N) case N: stream_run_dq<N>(slot, soff, lead, wq, qr, gr, lse2, Dr, dqa); break;
+#define S2_RUN(N) case N: stream_run_dq<N>(slot, soff, lead, wq, b0, b1, qr, gr, lse2o, Dro, dqa); break;
                 switch (span) {
                     S2_RUN(1) S2_RUN(2) S2_RUN(3) S2_RUN(4) S2_RUN(5) S2_RUN(6) S2_RUN(7) S2_RUN(8)
 #if S2_NTQ > 8
@@ -616,12 +641,12 @@ nattn_bwd_dq_stream(S2DeviceTables t, int nbh, int nsl, float scale, const float
     }
 }
 
+// xoff: float offset of the quad's first point in the lse / D rows of the slot; qd: the lane's own point
 template <int NT>
 __device__ __forceinline__ void stream_run_dkdv(const float *slot, int soff, int xoff, int lead, float wq, float lref2,
-                                                const float (&kr)[4][kDL], const float (&vr)[4][kDL],
-                                                float (&dk)[4][kDL], float (&dv)[4][kDL])
+                                                bool b0, bool b1, int qd, const float (&kr)[4][kDL],
+                                                const float (&vr)[4][kDL], float (&dk)[4][kDL], float (&dv)[4][kDL])
 {
-    constexpr int SL4 = (NT + 6) / 4;
     float s[4][NT], dp[4][NT];
 #pragma unroll
     for (int r = 0; r < 4; ++r)
@@ -630,23 +655,19 @@ __device__ __forceinline__ void stream_run_dkdv(const float *slot, int soff, int
     const float *qp = slot + soff, *gp = qp + kD * kPitchQ;
     dot_rows<NT, S2_NBK>(qp, kr, s);
     dot_rows<NT, S2_NBK>(gp, vr, dp);
-    {
-        // the streamed points' logsumexp and D (rows 64 and 65 of the slot, same columns for the four lanes)
-        float L2[4 * SL4], Dd[4 * SL4];
-        read_strip_q<SL4>(slot + 2 * kD * kPitchQ + xoff, L2);
-        read_strip_q<SL4>(slot + (2 * kD + 1) * kPitchQ + xoff, Dd);
+    // the streamed points' logsumexp and D for this lane's own point (rows 64 and 65 of the slot)
+    const float *lp = slot + 2 * kD * kPitchQ + xoff + qd, *dp_row = lp + kPitchQ;
 #pragma unroll
-        for (int j = 0; j < NT + 3; ++j) L2[j] = fmaf(L2[j], kLog2e, -lref2);
-#pragma unroll
-        for (int r = 0; r < 4; ++r)
-#pragma unroll
-            for (int tt = 0; tt < NT; ++tt) {
-                const float sv = quad_sum(s[r][tt]), dvv = quad_sum(dp[r][tt]);
-                float pr = wq * __builtin_amdgcn_exp2f(sv - L2[r + tt]);
-                pr = (tt < 3 && tt < lead) ? 0.f : pr;   // offsets in front of the arc
-                dp[r][tt] = pr;
-                s[r][tt] = pr * (dvv - Dd[r + tt]);
-            }
+    for (int tt = 0; tt < NT; ++tt) {
+        const float sv = quad_reduce_scatter(s[0][tt], s[1][tt], s[2][tt], s[3][tt], b0, b1);
+        const float dvv = quad_reduce_scatter(dp[0][tt], dp[1][tt], dp[2][tt], dp[3][tt], b0, b1);
+        float pr = wq * __builtin_amdgcn_exp2f(sv - fmaf(lp[tt], kLog2e, -lref2));
+        if (tt < 3) pr = tt < lead ? 0.f : pr;   // offsets in front of the arc
+        const float ds = pr * (dvv - dp_row[tt]);
+        s[0][tt] = quad_bcast<0>(ds); s[1][tt] = quad_bcast<1>(ds);
+        s[2][tt] = quad_bcast<2>(ds); s[3][tt] = quad_bcast<3>(ds);
+        dp[0][tt] = quad_bcast<0>(pr); dp[1][tt] = quad_bcast<1>(pr);
+        dp[2][tt] = quad_bcast<2>(pr); dp[3][tt] = quad_bcast<3>(pr);
     }
     axpy_rows<NT, S2_NBK>(qp, s, dk);
     axpy_rows<NT, S2_NBK>(gp, dp, dv);
@@ -690,6 +711,7 @@ nattn_bwd_dkdv_stream(S2DeviceTables t, int nbh, int nsl, float scale, const flo
     const int r_last = t.tband_lo[h_hi - 1] + t.tband_n[h_hi - 1] - 1;
 
     float kr[4][kDL], vr[4][kDL], dka[4][kDL], dva[4][kDL];
+    const bool b0 = qd & 1, b1 = qd & 2;
     unsigned lane_off = unsigned((size_t(qd) * si + w0) * sizeof(float));
     const size_t row4 = 4 * si * sizeof(float);
     int h = h_lo + wave;
@@ -759,10 +781,10 @@ nattn_bwd_dkdv_stream(S2DeviceTables t, int nbh, int nsl, float scale, const flo
                 int A = a & ~3, lead = a - A, span = a + c - A;
                 int soff = sbase + A, xoff = xbase + A;
                 while (span > kNTS) {
-                    stream_run_dkdv<kNTS>(slot, soff, xoff, lead, wq, lref2, kr, vr, dka, dva);
+                    stream_run_dkdv<kNTS>(slot, soff, xoff, lead, wq, lref2, b0, b1, qd, kr, vr, dka, dva);
                     lead = 0; soff += kNTS; xoff += kNTS; span -= kNTS;
                 }
-#define S2_RUN(N) case N: stream_run_dkdv<N>(slot, soff, xoff, lead, wq, lref2, kr, vr, dka, dva); break;
+#define S2_RUN(N) case N: stream_run_dkdv<N>(slot, soff, xoff, lead, wq, lref2, b0, b1, qd, kr, vr, dka, dva); break;
                 switch (span) {
                     S2_RUN(1) S2_RUN(2) S2_RUN(3) S2_RUN(4) S2_RUN(5) S2_RUN(6) S2_RUN(7) S2_RUN(8)
                 }
