@@ -350,7 +350,7 @@ extern "C" int s2_grid_init(int grid_type, int nlat_in, int nlon_in, int nlat_ou
             // cost of a latitude: offsets plus a fixed charge per band row (run set-up, softmax bookkeeping)
             for (int r = first; r <= last; ++r) {
                 int c = 0;
-                for (int b = 0; b < n[r]; ++b) c += tab[size_t(r) * bmax + b] + 4;
+                for (int b = 0; b < n[r]; ++b) c += tab[size_t(r) * bmax + b] + 2;
                 cum.push_back(cum.back() + c);
             }
             return;
