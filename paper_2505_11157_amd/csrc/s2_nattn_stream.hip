@@ -326,16 +326,6 @@ nattn_fwd_stream(S2DeviceTables t, int nbh, int nsl, float qscale, const float *
 //   dq    : owners are output points; rows of K and V stream by (s = q.K, dP = dout.V, dq += dS K); stores D_i.
 //   dk/dv : owners are INPUT points (transposed neighborhood); rows of q, dout, lse and D stream by.
 
-#ifndef S2_NBQ
-#define S2_NBQ 2
-#define S2_NBK 2
-#endif
-#ifndef S2_FENCEB
-#define S2_FENCEB 1
-#endif
-#ifndef S2_NTQ
-#define S2_NTQ 8
-#endif
 constexpr int kDL = 8;                    // channels per lane
 constexpr int kSegQ = 64;                 // owner longitudes per workgroup
 constexpr int kWinQ = kSegQ + 2 * kHalo;  // 128 window columns = two 64-lane loads per row
@@ -423,42 +413,41 @@ __device__ __forceinline__ void read_strip_q(const float *p, float (&st)[4 * SL4
     }
 }
 
-// acc[r][tt] += own[r][i] * row_i[r + tt] over the lane's 8 channels (rows 4 i of p).  NB = 2: the next
-// channel's strip is requested before this channel's FMAs (where the register budget allows).
-template <int NT, int NB>
+// acc[r][tt] += own[r][i] * row_i[r + tt] over the lane's 8 channels (rows 4 i of p).  The next channel's strip is
+// requested before this channel's FMAs; the fence keeps the scheduler from pulling more strips to the front
+// (without it the kernels spill).
+template <int NT>
 __device__ __forceinline__ void dot_rows(const float *p, const float (&own)[4][kDL], float (&acc)[4][NT])
 {
     constexpr int SL4 = (NT + 6) / 4;
-    float st[NB][4 * SL4];
-    if (NB == 2) read_strip_q<SL4>(p, st[0]);
+    float st[2][4 * SL4];
+    read_strip_q<SL4>(p, st[0]);
 #pragma unroll
     for (int i = 0; i < kDL; ++i) {
-        if (NB == 1) read_strip_q<SL4>(p + 4 * i * kPitchQ, st[0]);
-        else if (i + 1 < kDL) read_strip_q<SL4>(p + 4 * (i + 1) * kPitchQ, st[(i + 1) % NB]);
+        if (i + 1 < kDL) read_strip_q<SL4>(p + 4 * (i + 1) * kPitchQ, st[(i + 1) & 1]);
 #pragma unroll
         for (int tt = 0; tt < NT; ++tt)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) acc[r][tt] = fmaf(own[r][i], st[i % NB][r + tt], acc[r][tt]);
-        if (S2_FENCEB) __builtin_amdgcn_sched_barrier(0);
+            for (int r = 0; r < 4; ++r) acc[r][tt] = fmaf(own[r][i], st[i & 1][r + tt], acc[r][tt]);
+        __builtin_amdgcn_sched_barrier(0);
     }
 }
 
 // out[r][i] += sum_tt w[r][tt] * row_i[r + tt]
-template <int NT, int NB>
+template <int NT>
 __device__ __forceinline__ void axpy_rows(const float *p, const float (&w)[4][NT], float (&out)[4][kDL])
 {
     constexpr int SL4 = (NT + 6) / 4;
-    float st[NB][4 * SL4];
-    if (NB == 2) read_strip_q<SL4>(p, st[0]);
+    float st[2][4 * SL4];
+    read_strip_q<SL4>(p, st[0]);
 #pragma unroll
     for (int i = 0; i < kDL; ++i) {
-        if (NB == 1) read_strip_q<SL4>(p + 4 * i * kPitchQ, st[0]);
-        else if (i + 1 < kDL) read_strip_q<SL4>(p + 4 * (i + 1) * kPitchQ, st[(i + 1) % NB]);
+        if (i + 1 < kDL) read_strip_q<SL4>(p + 4 * (i + 1) * kPitchQ, st[(i + 1) & 1]);
 #pragma unroll
         for (int tt = 0; tt < NT; ++tt)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) out[r][i] = fmaf(w[r][tt], st[i % NB][r + tt], out[r][i]);
-        if (S2_FENCEB) __builtin_amdgcn_sched_barrier(0);
+            for (int r = 0; r < 4; ++r) out[r][i] = fmaf(w[r][tt], st[i & 1][r + tt], out[r][i]);
+        __builtin_amdgcn_sched_barrier(0);
     }
 }
 
@@ -474,8 +463,8 @@ __device__ __forceinline__ void stream_run_dq(const float *slot, int soff, int l
 #pragma unroll
         for (int tt = 0; tt < NT; ++tt) { s[r][tt] = 0.f; dp[r][tt] = 0.f; }
     const float *kp = slot + soff, *vp = kp + kD * kPitchQ;
-    dot_rows<NT, S2_NBQ>(kp, q, s);
-    dot_rows<NT, S2_NBQ>(vp, go, dp);
+    dot_rows<NT>(kp, q, s);
+    dot_rows<NT>(vp, go, dp);
 #pragma unroll
     for (int tt = 0; tt < NT; ++tt) {
         const float sv = quad_reduce_scatter(s[0][tt], s[1][tt], s[2][tt], s[3][tt], b0, b1);
@@ -485,7 +474,7 @@ __device__ __forceinline__ void stream_run_dq(const float *slot, int soff, int l
         s[0][tt] = quad_bcast<0>(w); s[1][tt] = quad_bcast<1>(w);
         s[2][tt] = quad_bcast<2>(w); s[3][tt] = quad_bcast<3>(w);
     }
-    axpy_rows<NT, S2_NBQ>(kp, s, dq);
+    axpy_rows<NT>(kp, s, dq);
 }
 
 __global__ void __launch_bounds__(64 * kMaxWaves)
@@ -607,16 +596,13 @@ nattn_bwd_dq_stream(S2DeviceTables t, int nbh, int nsl, float scale, const float
                 const int a = kHalo - ((c - 1) >> 1);
                 int A = a & ~3, lead = a - A, span = a + c - A;
                 int soff = sbase + A;
-                while (span > S2_NTQ) {
-                    stream_run_dq<8>(slot, soff, lead, wq, b0, b1, qr, gr, lse2o, Dro, dqa);
-                    lead = 0; soff += 8; span -= 8;
+                while (span > kNTS) {
+                    stream_run_dq<kNTS>(slot, soff, lead, wq, b0, b1, qr, gr, lse2o, Dro, dqa);
+                    lead = 0; soff += kNTS; span -= kNTS;
                 }
 #define S2_RUN(N) case N: stream_run_dq<N>(slot, soff, lead, wq, b0, b1, qr, gr, lse2o, Dro, dqa); break;
                 switch (span) {
                     S2_RUN(1) S2_RUN(2) S2_RUN(3) S2_RUN(4) S2_RUN(5) S2_RUN(6) S2_RUN(7) S2_RUN(8)
-#if S2_NTQ > 8
-                    S2_RUN(9) S2_RUN(10) S2_RUN(11) S2_RUN(12)
-#endif
                 }
 #undef S2_RUN
             }
@@ -653,8 +639,8 @@ __device__ __forceinline__ void stream_run_dkdv(const float *slot, int soff, int
 #pragma unroll
         for (int tt = 0; tt < NT; ++tt) { s[r][tt] = 0.f; dp[r][tt] = 0.f; }
     const float *qp = slot + soff, *gp = qp + kD * kPitchQ;
-    dot_rows<NT, S2_NBK>(qp, kr, s);
-    dot_rows<NT, S2_NBK>(gp, vr, dp);
+    dot_rows<NT>(qp, kr, s);
+    dot_rows<NT>(gp, vr, dp);
     // the streamed points' logsumexp and D for this lane's own point (rows 64 and 65 of the slot)
     const float *lp = slot + 2 * kD * kPitchQ + xoff + qd, *dp_row = lp + kPitchQ;
 #pragma unroll
@@ -669,8 +655,8 @@ __device__ __forceinline__ void stream_run_dkdv(const float *slot, int soff, int
         dp[0][tt] = quad_bcast<0>(pr); dp[1][tt] = quad_bcast<1>(pr);
         dp[2][tt] = quad_bcast<2>(pr); dp[3][tt] = quad_bcast<3>(pr);
     }
-    axpy_rows<NT, S2_NBK>(qp, s, dk);
-    axpy_rows<NT, S2_NBK>(gp, dp, dv);
+    axpy_rows<NT>(qp, s, dk);
+    axpy_rows<NT>(gp, dp, dv);
 }
 
 __global__ void __launch_bounds__(64 * kMaxWaves)
