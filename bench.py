@@ -25,9 +25,9 @@ PEAK_BF16_TFLOPS = 2500.0
 # HBM bytes per launch (FETCH_SIZE + WRITE_SIZE from rocprofv3 --pmc, scaled by the factors a plain
 # copy gives: see profiles/), keyed by (workload, kernel name).  Measured offline; None if not measured.
 TRAFFIC_BYTES = {
-    (3, "nattn_fwd_mfma"): 278e6, (3, "nattn_fwd_stream"): 750e6,
-    (3, "nattn_bwd_dq_mfma"): 382e6, (3, "nattn_bwd_dq_stream"): 1023e6,
-    (3, "nattn_bwd_dkdv_mfma"): 324e6, (3, "nattn_bwd_dkdv_stream"): 1045e6,
+    (3, "nattn_fwd_mfma"): 280e6, (3, "nattn_fwd_stream"): 747e6,
+    (3, "nattn_bwd_dq_mfma"): 333e6, (3, "nattn_bwd_dq_stream"): 1023e6,
+    (3, "nattn_bwd_dkdv_mfma"): 349e6, (3, "nattn_bwd_dkdv_stream"): 1058e6,
 }
 
 
