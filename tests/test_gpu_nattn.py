@@ -185,6 +185,52 @@ def test_streaming_kernels_take_the_light_latitudes(which):
     assert not any("1 wave" in n for n in names), names
 
 
+def test_hip_graph_replays_match_eager():
+    # the library only enqueues kernels on the caller's stream (no allocation, no memset, no synchronisation), so a
+    # forward + backward can be captured into a HIP graph once the kernels have been launched once (the first launch
+    # of a kernel raises its LDS limit, which is not a stream operation).  Every replay, with eager work and new
+    # inputs in between, must reproduce the eager result bit for bit.
+    c, arrs = make_inputs(SMALL[11], seed=21)
+    gd = grid_dict(c)
+    g = _grid(gd)
+    B, H, d = c["batch"], c["heads"], c["d"]
+    scale = 1 / math.sqrt(d)
+    dev = torch.device("cuda:0")
+    fold = lambda a: torch.from_numpy(a).to(dev).reshape((B, H) + a.shape[1:]).contiguous()
+    q, k, v, dout = (fold(a) for a in arrs)
+    out, lse = torch.empty_like(q), torch.empty((B, H) + q.shape[3:], dtype=torch.float32, device=dev)
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    ws = torch.empty(max(S.s2_nattn_bwd_workspace_bytes(g, B, H, d, d), 1), dtype=torch.uint8, device=dev)
+
+    def step():
+        S.s2_nattn_fwd(g, q, k, v, scale, out=out, lse=lse)
+        S.s2_nattn_bwd(g, q, k, v, out, lse, dout, scale, dq=dq, dk=dk, dv=dv, workspace=ws)
+
+    step()                                  # warm-up outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()              # default priority
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.current_stream().wait_stream(side)
+    rng = np.random.default_rng(3)
+    for rep in range(3):
+        q.copy_(torch.from_numpy(rng.standard_normal(tuple(q.shape)).astype(np.float32)).to(dev))
+        dout.copy_(torch.from_numpy(rng.standard_normal(tuple(dout.shape)).astype(np.float32)).to(dev))
+        step()
+        torch.cuda.synchronize()
+        eager = [t.clone() for t in (out, lse, dq, dk, dv)]
+        for t in (out, lse, dq, dk, dv):
+            t.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for name, a, b in zip(("out", "lse", "dq", "dk", "dv"), eager, (out, lse, dq, dk, dv)):
+            assert torch.equal(a, b), "replay %d: %s differs from the eager result" % (rep, name)
+
+
 def test_errors_on_device():
     gd = grid_dict(1)
     g = _grid(gd)
