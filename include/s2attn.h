@@ -166,6 +166,13 @@ int s2_trace_count(void);
 int s2_trace_get(int index, const char **name, float *ms, double *pairs);
 void s2_trace_reset(void);
 
+/* Device-side health of a grid handle (Sec. 3.2 / App. B.3 kernels that synchronise wavefronts through counters
+ * in LDS bound every wait; a wait that ran out - which would be a defect of the library, the results of that call
+ * are then wrong - sets a sticky flag in device memory).  Synchronises the device, copies the flag word to *flags
+ * (0 = healthy) and clears it.  Host pointer; S2_ERR_INVALID_ARG for NULL arguments, S2_ERR_DEVICE if the handle
+ * has no device tables or the copy fails. */
+int s2_grid_device_flags(const s2_grid_t *g, unsigned *flags);
+
 /* Message for the last error on the calling thread ("" if none). */
 const char *s2_last_error(void);
 

@@ -50,6 +50,8 @@ def lib():
         L.s2_grid_destroy.restype = None
         L.s2_grid_get_weights.argtypes = [_vp, _vp, _vp]
         L.s2_grid_get_weights.restype = _i
+        L.s2_grid_device_flags.argtypes = [_vp, ctypes.POINTER(ctypes.c_uint)]
+        L.s2_grid_device_flags.restype = _i
         L.s2_grid_num_neighbors.argtypes = [_vp]
         L.s2_grid_num_neighbors.restype = ctypes.c_int64
         L.s2_grid_get_neighbors.argtypes = [_vp, _vp, _vp]
@@ -121,6 +123,13 @@ def s2_grid_get_weights(g):
     om = np.empty(g.nlat_in, np.float64)
     _check(lib().s2_grid_get_weights(g.handle, colat.ctypes.data, om.ctypes.data))
     return colat, om
+
+
+def s2_grid_device_flags(g):
+    """Synchronise and return the device-side flag word of the handle (0 = healthy); clears it."""
+    flags = ctypes.c_uint(0)
+    _check(lib().s2_grid_device_flags(g.handle, ctypes.byref(flags)))
+    return int(flags.value)
 
 
 def s2_grid_num_neighbors(g):

@@ -126,6 +126,7 @@ static int upload_tables(s2_grid *g)
     g->npad_tok = (ntok + 31) / 32 * 32;
     std::vector<float> bias(g->npad_tok, -INFINITY);
     for (int j = 0; j < ntok; ++j) bias[j] = float(std::log2(g->omega_in[j / g->nlon_in]));
+    const unsigned zero_word = 0u;
     // one blob: floats first, then the int tables, each 256-byte aligned
     struct Part { const void *src; size_t bytes; size_t off; };
     std::vector<Part> parts = {
@@ -141,6 +142,7 @@ static int upload_tables(s2_grid *g)
         {bias.data(), bias.size() * sizeof(float), 0},
         {g->st_cum.data(), g->st_cum.size() * sizeof(int), 0},
         {g->tst_cum.data(), g->tst_cum.size() * sizeof(int), 0},
+        {&zero_word, sizeof(unsigned), 0},
     };
     size_t total = 0;
     for (auto &p : parts) {
@@ -170,6 +172,7 @@ static int upload_tables(s2_grid *g)
     g->dev_bias_tok = reinterpret_cast<const float *>(base + parts[9].off);
     t.st_cum = reinterpret_cast<const int *>(base + parts[10].off);
     t.tst_cum = reinterpret_cast<const int *>(base + parts[11].off);
+    t.dev_flags = reinterpret_cast<unsigned *>(base + parts[12].off);
     t.band_max = g->band_max;
     t.tband_max = g->tband_max;
     t.nlat_in = g->nlat_in; t.nlon_in = g->nlon_in;
@@ -372,6 +375,16 @@ extern "C" void s2_grid_destroy(s2_grid_t *g)
     if (!g) return;
     if (g->dev_blob) (void)hipFree(g->dev_blob);
     delete g;
+}
+
+extern "C" int s2_grid_device_flags(const s2_grid_t *g, unsigned *flags)
+{
+    if (!g || !flags) return s2_fail(S2_ERR_INVALID_ARG, "grid or flags is NULL");
+    if (!g->on_device) return s2_fail(S2_ERR_DEVICE, "the grid handle has no device tables");
+    S2_HIP_CHECK(hipDeviceSynchronize());
+    S2_HIP_CHECK(hipMemcpy(flags, g->dt.dev_flags, sizeof(unsigned), hipMemcpyDeviceToHost));
+    if (*flags) S2_HIP_CHECK(hipMemset(g->dt.dev_flags, 0, sizeof(unsigned)));
+    return S2_OK;
 }
 
 extern "C" int s2_grid_get_weights(const s2_grid_t *g, double *colat_in, double *omega_in)

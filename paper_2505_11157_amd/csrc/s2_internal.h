@@ -40,6 +40,7 @@ struct S2DeviceTables {
     // tst_*: the same for input latitudes and the transposed bands.
     int st_lo, st_hi, st_nw;
     int tst_lo, tst_hi, tst_nw;
+    unsigned *dev_flags;      // one word in device memory: bit 0 = a bounded wait inside a kernel ran out
     const int *st_cum;        // [st_hi - st_lo + 1]   running cost of the light latitudes (for equal-work segments)
     const int *tst_cum;       // [tst_hi - tst_lo + 1]
     float ln_omega_ref;       // ln(max omega): the stored logsumexp is relative to the true omega

@@ -386,7 +386,8 @@ __device__ __forceinline__ void stage_row_q(const float *a, const float *b, size
 // wavefront counts "my share of the row in this slot has landed" and "I am done reading this slot"; a wavefront
 // waits only for the count it needs, which lets the fast ones run one row ahead of the slow ones.  The waits are
 // bounded: if a count never arrives (which would be a bug) the wavefront goes on after about ten milliseconds
-// instead of hanging the device, and the results are then wrong rather than missing.
+// instead of hanging the device, the results are then wrong rather than missing, and the kernel sets a flag in
+// device memory that s2_grid_device_flags reports.
 __device__ __forceinline__ void sem_signal(unsigned *p, int lane)
 {
     if (lane == 0) __hip_atomic_fetch_add(p, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
@@ -625,6 +626,7 @@ nattn_bwd_dq_stream(S2DeviceTables t, int nbh, int nsl, float scale, const float
         cur = (cur + 1) & 3;
         if (cur == 0) fill += unsigned(nw);
     }
+    if (gave_up && lane == 0) atomicOr(t.dev_flags, 1u);
 }
 
 // xoff: float offset of the quad's first point in the lse / D rows of the slot; qd: the lane's own point
@@ -794,6 +796,7 @@ nattn_bwd_dkdv_stream(S2DeviceTables t, int nbh, int nsl, float scale, const flo
         cur = (cur + 1) & 3;
         if (cur == 0) fill += unsigned(nw);
     }
+    if (gave_up && lane == 0) atomicOr(t.dev_flags, 1u);
 }
 
 }  // namespace

@@ -46,6 +46,7 @@ def run_case(c, arrs, slices):
     out, lse = S.s2_nattn_fwd(g, q, k, v, scale)
     dq, dk, dv = S.s2_nattn_bwd(g, q, k, v, out, lse, dout, scale)
     torch.cuda.synchronize()
+    assert S.s2_grid_device_flags(g) == 0    # no bounded wait inside a kernel ran out
     unfold = lambda t: t.reshape((B * H,) + t.shape[2:]).cpu().numpy().astype(np.float64)
     out, lse, dq, dk, dv = (unfold(t) for t in (out, lse, dq, dk, dv))
     for s in slices:
