@@ -131,11 +131,21 @@ nattn_fwd_mfma(S2DeviceTables t, int nbh, int nrows, float qscale, const float *
         }
         const float *tk = tile, *tv = tile + kD * kPK;
         f32x16 s0 = {0}, s1 = {0};
+        {
+            // operands of all 16 steps are requested up front, in two halves: the matrix products of the first half
+            // cover the LDS latency of the second
+            float a0[16], a1[16];
 #pragma unroll
-        for (int s = 0; s < 16; ++s) {
-            const float a0 = tk[(2 * s + hl) * kPK + arow], a1 = tk[(2 * s + hl) * kPK + arow + 16];
-            s0 = mfma(a0, qop[s], s0);
-            s1 = mfma(a1, qop[s], s1);
+            for (int s = 0; s < 16; ++s) {
+                a0[s] = tk[(2 * s + hl) * kPK + arow];
+                a1[s] = tk[(2 * s + hl) * kPK + arow + 16];
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int s = 0; s < 16; ++s) {
+                s0 = mfma(a0[s], qop[s], s0);
+                s1 = mfma(a1[s], qop[s], s1);
+            }
         }
         float p[32];
 #pragma unroll
@@ -286,33 +296,31 @@ nattn_bwd_dq_mfma(S2DeviceTables t, int nbh, int nrows, float scale, const float
             if (!(rel < len || rel + kTileCols > nlon)) continue;
         }
         const float *tk = tile, *tv = tile + kD * kPQK;
-        f32x16 s0 = {0}, s1 = {0}, d0 = {0}, d1 = {0};
+        const int base = (x0 + 32 * hl - w - lo + 2 * nlon) % nlon;
+        // the two 32 x 32 tiles of the super-tile one after the other: half the logits live at a time
 #pragma unroll
-        for (int s = 0; s < 16; ++s) {
-            const int rk = (2 * s + hl) * kPQK + arow, rv = (2 * s + hl) * kPQV + arow;
-            s0 = mfma(tk[rk], qop[s], s0);
-            s1 = mfma(tk[rk + 16], qop[s], s1);
-            d0 = mfma(tv[rv], gop[s], d0);
-            d1 = mfma(tv[rv + 16], gop[s], d1);
-        }
-        float ds[32];
+        for (int mt = 0; mt < 2; ++mt) {
+            f32x16 sm = {0}, dm = {0};
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            ds[i] = wq * __builtin_amdgcn_exp2f(s0[i] - lse2) * (d0[i] - Di);
-            ds[16 + i] = wq * __builtin_amdgcn_exp2f(s1[i] - lse2) * (d1[i] - Di);
-        }
-        if (!full) {
-            const int base = (x0 + 32 * hl - w - lo + 2 * nlon) % nlon;
-#pragma unroll
-            for (int i = 0; i < 32; ++i) {
-                int rel = base + i;
-                rel = rel >= nlon ? rel - nlon : rel;
-                ds[i] = rel < c ? ds[i] : 0.f;
+            for (int s = 0; s < 16; ++s) {
+                sm = mfma(tk[(2 * s + hl) * kPQK + arow + 16 * mt], qop[s], sm);
+                dm = mfma(tv[(2 * s + hl) * kPQV + arow + 16 * mt], gop[s], dm);
             }
-        }
-        // dQ^T += K dS^T: A = K[channel = col][super-tile column 32*hl + i]
+            float ds[16];
 #pragma unroll
-        for (int i = 0; i < 32; ++i) acc = mfma(tk[col * kPQK + 32 * hl + i], ds[i], acc);
+            for (int i = 0; i < 16; ++i) ds[i] = wq * __builtin_amdgcn_exp2f(sm[i] - lse2) * (dm[i] - Di);
+            if (!full) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    int rel = base + 16 * mt + i;
+                    rel = rel >= nlon ? rel - nlon : rel;
+                    ds[i] = rel < c ? ds[i] : 0.f;
+                }
+            }
+            // dQ^T += K dS^T: A = K[channel = col][super-tile column 32*hl + 16*mt + i]
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc = mfma(tk[col * kPQK + 32 * hl + 16 * mt + i], ds[i], acc);
+        }
         }
     }
 #pragma unroll
