@@ -89,7 +89,17 @@ SMALL = [
     dict(kind="nattn", grid_type=1, nlat_in=40, nlon_in=200, nlat_out=40, nlon_out=200, theta=0.2, batch=2, heads=1, d=32, dtype="f32"),
     dict(kind="nattn", grid_type=0, nlat_in=65, nlon_in=256, nlat_out=65, nlon_out=256, theta=2 * math.pi / 64, batch=1, heads=2, d=32, dtype="f32"),
     dict(kind="nattn", grid_type=0, nlat_in=33, nlon_in=192, nlat_out=33, nlon_out=192, theta=0.3, batch=9, heads=2, d=32, dtype="f32"),
+    # a handful of light latitudes with bands of three rows (two wavefronts per workgroup, more segments than fit)
+    dict(kind="nattn", grid_type=0, nlat_in=9, nlon_in=256, nlat_out=9, nlon_out=256, theta=0.5, batch=1, heads=2, d=32, dtype="f32"),
 ]
+
+
+def test_streaming_with_many_slices():
+    # 160 (batch, head) slices: one latitude segment per strip, every workgroup walks the whole light range
+    c = dict(kind="nattn", grid_type=0, nlat_in=33, nlon_in=192, nlat_out=33, nlon_out=192, theta=0.3, batch=40, heads=4,
+             d=32, dtype="f32")
+    c, arrs = make_inputs(c, seed=77)
+    run_case(c, arrs, [0, 83, 159])
 
 
 @pytest.mark.parametrize("ci", range(len(SMALL)))
