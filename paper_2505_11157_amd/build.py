@@ -20,16 +20,22 @@ def sources():
     return sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith((".hip", ".cpp")))
 
 
-def build(verbose=False, extra=()):
-    objs = []
-    for s in sources():
+def build(verbose=False, extra=(), jobs=None):
+    from concurrent.futures import ThreadPoolExecutor
+
+    os.makedirs(os.path.join(HERE, "_build"), exist_ok=True)
+
+    def compile_one(s):
         o = os.path.join(HERE, "_build", os.path.basename(s) + ".o")
-        os.makedirs(os.path.dirname(o), exist_ok=True)
         cmd = ["hipcc", "-x", "hip", "-c", s, "-o", o] + [f for f in FLAGS if f != "-shared"] + list(extra)
         if verbose:
             print(" ".join(cmd), flush=True)
         subprocess.check_call(cmd)
-        objs.append(o)
+        return o
+
+    jobs = jobs or min(8, os.cpu_count() or 1)
+    with ThreadPoolExecutor(max_workers=jobs) as pool:
+        objs = list(pool.map(compile_one, sources()))
     cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
     if verbose:
         print(" ".join(cmd), flush=True)

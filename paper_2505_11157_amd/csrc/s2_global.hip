@@ -15,7 +15,7 @@
 // The MFMA "A" operand wants its contraction index contiguous in memory.  V
 // (forward) and Q, K, dout (backward) are contracted over tokens, so they are
 // transposed once per call into the caller's workspace ([b,h][64][Npad] bf16,
-// zero padded to a multiple of 32 tokens).
+// zero padded to a multiple of 64 tokens).
 //
 // Backward (App. B.4 with every token in every neighborhood): D_i = dout_i.out_i,
 // p_ij = exp(s_ij + ln omega_j - lse_i), dS_ij = p_ij (dout_i.v_j - D_i);
@@ -54,15 +54,19 @@ __device__ __forceinline__ bf16x8 pack8(const float *x)
 // key (or query) index of tile row r under the permutation described above
 __device__ __forceinline__ int perm_row(int r) { return 16 * ((r >> 2) & 1) + 4 * (r >> 3) + (r & 3); }
 
-// in [bh][N][64] -> out [bh][64][Npad], zero for tokens >= N
+// in [bh][N][64] -> out [bh][64][Npad], zero for tokens >= N; with `wtok` every token is multiplied by
+// its weight first (rounded to bf16 once, after the product)
 __global__ void __launch_bounds__(256)
-transpose_tokens(const bf16raw *__restrict__ in, bf16raw *__restrict__ out, int N, int Npad)
+transpose_tokens(const bf16raw *__restrict__ in, bf16raw *__restrict__ out, const float *__restrict__ wtok, int N,
+                 int Npad)
 {
     __shared__ bf16raw tile[64][kD + 2];
     const int bh = blockIdx.y, t0 = blockIdx.x * 64;
     for (int i = threadIdx.x; i < 64 * kD; i += 256) {
         const int tok = i / kD, c = i % kD;
-        tile[tok][c] = (t0 + tok < N) ? in[(size_t(bh) * N + t0 + tok) * kD + c] : bf16raw(0);
+        bf16raw x = (t0 + tok < N) ? in[(size_t(bh) * N + t0 + tok) * kD + c] : bf16raw(0);
+        if (wtok) x = __builtin_bit_cast(bf16raw, (__bf16)(float(__builtin_bit_cast(__bf16, x)) * wtok[t0 + tok]));
+        tile[tok][c] = x;
     }
     __syncthreads();
     for (int i = threadIdx.x; i < 64 * kD; i += 256) {
@@ -72,11 +76,11 @@ transpose_tokens(const bf16raw *__restrict__ in, bf16raw *__restrict__ out, int 
 }
 
 // Per-token backward constants, padded to Npad tokens per slice so that the kernels can read them
-// with 16-byte loads: L2[bh][i] = lse_i * log2(e) (+inf on the padding: p = exp2(-inf) = 0) and
-// D[bh][i] = dout_i . out_i (0 on the padding).
+// with 16-byte loads: L2[bh][i] = (lse_i - ln max omega) * log2(e) (+inf on the padding:
+// p = exp2(-inf) = 0) and D[bh][i] = dout_i . out_i (0 on the padding).
 __global__ void __launch_bounds__(256)
 rowstats(const bf16raw *__restrict__ go, const bf16raw *__restrict__ o, const float *__restrict__ lse,
-         float *__restrict__ L2, float *__restrict__ D, int N, int Npad)
+         float *__restrict__ L2, float *__restrict__ D, int N, int Npad, float ln_wref)
 {
     const int bh = blockIdx.y, i = blockIdx.x * 256 + threadIdx.x;
     if (i >= Npad) return;
@@ -89,202 +93,312 @@ rowstats(const bf16raw *__restrict__ go, const bf16raw *__restrict__ o, const fl
 #pragma unroll
             for (int j = 0; j < 8; ++j) acc = fmaf(float(x[j]), float(y[j]), acc);
         }
-        l2 = lse[t] * kLog2e;
+        l2 = (lse[t] - ln_wref) * kLog2e;
     }
     L2[size_t(bh) * Npad + i] = l2;
     D[size_t(bh) * Npad + i] = acc;
 }
 
-// Forward.  One wavefront = 64 queries (two 32-query MFMA tiles sharing every K, V^T and bias
-// operand they load); bias = log2(omega) per token, -inf on the padding.
-__global__ void __launch_bounds__(256)
-global_fwd(const bf16raw *__restrict__ q, const bf16raw *__restrict__ k, const bf16raw *__restrict__ vt,
-           const float *__restrict__ bias, bf16raw *__restrict__ out, float *__restrict__ lse, int N, int Npad,
-           float c2)
+// ---------------------------------------------------------------------------------------------
+// Staging of streamed operands in LDS.  A workgroup of four wavefronts streams 64-token stages; every
+// stage is fetched from global memory once per workgroup with coalesced 16-byte loads (held in
+// registers while the previous stage is being used), written to one of two LDS buffers, and read from
+// there by all four wavefronts as MFMA operands.  A staged tile is 64 rows of 128 bytes; the 16-byte
+// piece c of row r sits at piece c ^ ((r >> 1) & 7), so that the 16 consecutive lanes a 16-byte LDS read
+// serves together (16 consecutive rows, same logical piece) fall on 16 different bank groups, and so do
+// the writes of a row.  Token-major tiles ("row tiles": 64 tokens x 64 channels) additionally have the
+// rows of each 32-token half permuted so that lane `col` finds the token of MFMA row perm_row(col) in
+// LDS row `col`.  Channel-major tiles ("column tiles": 64 channels x 64 tokens) come from the
+// token-transposed copies in the workspace.
+constexpr int kTileBytes = 64 * 128;
+
+__device__ __forceinline__ int swz(int row, int piece) { return row * 128 + ((piece ^ ((row >> 1) & 7)) << 4); }
+
+// LDS row of token t (0..63) of a stage: inverse of perm_row inside each 32-token half
+__device__ __forceinline__ int lds_row_of_token(int t)
 {
-    constexpr int NQ = 2;
-    const int bh = blockIdx.y;
-    const int q0 = (blockIdx.x * 4 + (threadIdx.x >> 6)) * (32 * NQ);
-    if (q0 >= N) return;
-    const int lane = threadIdx.x & 63, col = lane & 31, hl = lane >> 5;
-    const int prow = perm_row(col);
-    bf16x8 qop[NQ][4];
-    f32x16 o0[NQ], o1[NQ];
-    float m[NQ], l[NQ];
+    const int k = t & 31;
+    return (t & 32) | (k & 3) | (((k >> 4) & 1) << 2) | (((k >> 2) & 3) << 3);
+}
+
+// The two 16-byte pieces of a tile that one thread moves: rows (tid >> 3) and 32 + (tid >> 3), piece tid & 7.
+struct TileRegs { uint4 a, b; };
+
+// token-major tile: tokens tok0 + (tid >> 3) and tok0 + 32 + (tid >> 3), clamped to N - 1
+__device__ __forceinline__ TileRegs fetch_row_tile(const bf16raw *base, int tok0, int N, int tid)
+{
+    TileRegs r;
+    const int t = tid >> 3, c = tid & 7;
+    r.a = *reinterpret_cast<const uint4 *>(base + size_t(min(tok0 + t, N - 1)) * kD + 8 * c);
+    r.b = *reinterpret_cast<const uint4 *>(base + size_t(min(tok0 + 32 + t, N - 1)) * kD + 8 * c);
+    return r;
+}
+__device__ __forceinline__ void store_row_tile(char *lds, const TileRegs &r, int tid)
+{
+    const int off = swz(lds_row_of_token(tid >> 3), tid & 7);
+    *reinterpret_cast<uint4 *>(lds + off) = r.a;
+    *reinterpret_cast<uint4 *>(lds + off + 32 * 128) = r.b;
+}
+// channel-major tile from a transposed operand [64][Npad] (Npad a multiple of 64: always in bounds)
+__device__ __forceinline__ TileRegs fetch_col_tile(const bf16raw *base, int tok0, int Npad, int tid)
+{
+    TileRegs r;
+    const int ch = tid >> 3, c = tid & 7;
+    r.a = *reinterpret_cast<const uint4 *>(base + size_t(ch) * Npad + tok0 + 8 * c);
+    r.b = *reinterpret_cast<const uint4 *>(base + size_t(ch + 32) * Npad + tok0 + 8 * c);
+    return r;
+}
+__device__ __forceinline__ void store_col_tile(char *lds, const TileRegs &r, int tid)
+{
+    const int off = swz(tid >> 3, tid & 7);
+    *reinterpret_cast<uint4 *>(lds + off) = r.a;
+    *reinterpret_cast<uint4 *>(lds + off + 32 * 128) = r.b;
+}
+__device__ __forceinline__ bf16x8 lds8(const char *p)
+{
+    return __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(p));
+}
+// MFMA operand reads by lane (col, hl).  Row tile, 32-token half `half`, contraction step ks (channels
+// 16 ks + 8 hl ..): piece 2 ks + hl of row 32 half + col.  Column tile, channel half `rt`, tokens
+// 32 half + 16 hl + 8 j ..: piece 4 half + 2 hl + j of row 32 rt + col.  (32 does not touch the swizzle bits.)
+__device__ __forceinline__ bf16x8 row_operand(const char *tile, int col, int hl, int half, int ks)
+{
+    return lds8(tile + half * 4096 + swz(col, 2 * ks + hl));
+}
+__device__ __forceinline__ bf16x8 col_operand(const char *tile, int col, int hl, int rt, int half, int j)
+{
+    return lds8(tile + rt * 4096 + swz(col, 4 * half + 2 * hl + j));
+}
+
+// Workgroups are numbered so that each of the eight XCDs (which take consecutive workgroup ids in turn)
+// works through one contiguous piece of the (slice, block) list: the operands of the few slices an XCD
+// has in flight then stay in its own L2.  Returns false for the padding ids at the end of the launch.
+__device__ __forceinline__ bool xcd_unit(int nunits, int &unit)
+{
+    const int per = (nunits + 7) >> 3;
+    unit = int(blockIdx.x & 7) * per + int(blockIdx.x >> 3);
+    return unit < nunits && int(blockIdx.x >> 3) < per;
+}
+
+// Forward.  A workgroup owns 128 queries of one slice (one 32-query MFMA tile per wavefront) and streams
+// the keys in stages of 64.  omega enters as a factor, not as a bias: V^T arrives premultiplied by
+// w_j = omega_j / max omega (transpose_tokens does that), the running sum is l_i = sum_j w_j 2^(x_ij - m_i)
+// with x = log2(e) scale q.k, and the reference m_i follows the bare logits (it moves only when a logit
+// exceeds it by more than 2^8).  lse_i = ln 2 (m_i + log2 l_i) + ln max omega.
+__global__ void __launch_bounds__(256, 3)
+global_fwd(const bf16raw *__restrict__ q, const bf16raw *__restrict__ k, const bf16raw *__restrict__ vt,
+           const float *__restrict__ wtok, bf16raw *__restrict__ out, float *__restrict__ lse, int N, int Npad,
+           int nqb, int nunits, float c2, float ln_wref)
+{
+    constexpr int kStage = 2 * kTileBytes + 256;     // K row tile, V^T column tile, 64 weights
+    __shared__ __attribute__((aligned(16))) char lds[2][kStage];
+    int unit;
+    if (!xcd_unit(nunits, unit)) return;
+    const int bh = unit / nqb, qb = unit - bh * nqb;
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = tid & 63, col = lane & 31, hl = lane >> 5;
+    const int qi = qb * 128 + wave * 32 + col;
+    bf16x8 qop[4];
+    {
+        const bf16raw *qp = q + (size_t(bh) * N + min(qi, N - 1)) * kD + 8 * hl;
 #pragma unroll
-    for (int t = 0; t < NQ; ++t) {
-        const int query = min(q0 + 32 * t + col, N - 1);
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) qop[t][ks] = ld8(q + (size_t(bh) * N + query) * kD + 16 * ks + 8 * hl);
-#pragma unroll
-        for (int i = 0; i < 16; ++i) { o0[t][i] = 0.f; o1[t][i] = 0.f; }
-        m[t] = -INFINITY; l[t] = 0.f;
+        for (int ks = 0; ks < 4; ++ks) qop[ks] = ld8(qp + 16 * ks);
     }
-    const bf16raw *kb = k + size_t(bh) * N * kD + 8 * hl;
-    const bf16raw *vb0 = vt + (size_t(bh) * kD + col) * Npad + 16 * hl;
-    const bf16raw *vb1 = vb0 + size_t(32) * Npad;
-    for (int key0 = 0; key0 < Npad; key0 += 32) {
-        const int key = min(key0 + prow, N - 1);
-        bf16x8 kc[4], va[2], vb[2];
-        float4 bc[4];
+    f32x16 o0 = {0}, o1 = {0};
+    float m = 0.f, l = 0.f;
+    const bf16raw *kb = k + size_t(bh) * N * kD;
+    const bf16raw *vb = vt + size_t(bh) * kD * Npad;
+    {
+        const TileRegs rk = fetch_row_tile(kb, 0, N, tid), rv = fetch_col_tile(vb, 0, Npad, tid);
+        store_row_tile(lds[0], rk, tid);
+        store_col_tile(lds[0] + kTileBytes, rv, tid);
+        if (tid < 16) *reinterpret_cast<float4 *>(lds[0] + 2 * kTileBytes + 16 * tid) =
+            *reinterpret_cast<const float4 *>(wtok + 4 * tid);
+    }
+    __syncthreads();
+    const int nst = Npad >> 6;
+    for (int st = 0; st < nst; ++st) {
+        const char *cur = lds[st & 1];
+        char *nxt = lds[(st + 1) & 1];
+        const bool more = st + 1 < nst;
+        TileRegs rk, rv;
+        float4 rw;
+        if (more) {
+            rk = fetch_row_tile(kb, 64 * (st + 1), N, tid);
+            rv = fetch_col_tile(vb, 64 * (st + 1), Npad, tid);
+            if (tid < 16) rw = *reinterpret_cast<const float4 *>(wtok + 64 * (st + 1) + 4 * tid);
+        }
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) kc[ks] = ld8(kb + size_t(key) * kD + 16 * ks);
-#pragma unroll
-        for (int g = 0; g < 4; ++g) bc[g] = *reinterpret_cast<const float4 *>(bias + key0 + 16 * hl + 4 * g);
-#pragma unroll
-        for (int j = 0; j < 2; ++j) { va[j] = ld8(vb0 + key0 + 8 * j); vb[j] = ld8(vb1 + key0 + 8 * j); }
-#pragma unroll
-        for (int t = 0; t < NQ; ++t) {
+        for (int kt = 0; kt < 2; ++kt) {
             f32x16 s = {0};
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) s = mfma(kc[ks], qop[t][ks], s);
-            float p[16];
-            float mloc = -INFINITY;
+            for (int ks = 0; ks < 4; ++ks) s = mfma(row_operand(cur, col, hl, kt, ks), qop[ks], s);
+            float x[16];
+            float mx = -INFINITY;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) { x[i] = fmaf(s[i], c2, -m); mx = fmaxf(mx, x[i]); }
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            const bool first = st == 0 && kt == 0;
+            if (first || __any(mx > 8.f)) {
+                const float delta = first ? mx : (mx > 8.f ? mx : 0.f);
+                const float corr = first ? 1.f : __builtin_amdgcn_exp2f(-delta);
+                m += delta;
+                l *= corr;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) { o0[i] *= corr; o1[i] *= corr; x[i] -= delta; }
+            }
+            const float *wp = reinterpret_cast<const float *>(cur + 2 * kTileBytes) + 32 * kt + 16 * hl;
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                const float4 b = bc[g];
-                p[4 * g + 0] = fmaf(s[4 * g + 0], c2, b.x);
-                p[4 * g + 1] = fmaf(s[4 * g + 1], c2, b.y);
-                p[4 * g + 2] = fmaf(s[4 * g + 2], c2, b.z);
-                p[4 * g + 3] = fmaf(s[4 * g + 3], c2, b.w);
-#pragma unroll
-                for (int u = 0; u < 4; ++u) mloc = fmaxf(mloc, p[4 * g + u]);
-            }
-            mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
-            // move the reference maximum only when a logit exceeds it by more than 2^8
-            if (__any(mloc > m[t] + 8.f)) {
-                const float m_new = mloc > m[t] + 8.f ? mloc : m[t];
-                const float corr = __builtin_amdgcn_exp2f(m[t] - m_new);
-                m[t] = m_new;
-                l[t] *= corr;
-#pragma unroll
-                for (int i = 0; i < 16; ++i) { o0[t][i] *= corr; o1[t][i] *= corr; }
-            }
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                p[i] = __builtin_amdgcn_exp2f(p[i] - m[t]);
-                l[t] += p[i];
+                const float4 w = *reinterpret_cast<const float4 *>(wp + 4 * g);
+                x[4 * g + 0] = __builtin_amdgcn_exp2f(x[4 * g + 0]); l = fmaf(x[4 * g + 0], w.x, l);
+                x[4 * g + 1] = __builtin_amdgcn_exp2f(x[4 * g + 1]); l = fmaf(x[4 * g + 1], w.y, l);
+                x[4 * g + 2] = __builtin_amdgcn_exp2f(x[4 * g + 2]); l = fmaf(x[4 * g + 2], w.z, l);
+                x[4 * g + 3] = __builtin_amdgcn_exp2f(x[4 * g + 3]); l = fmaf(x[4 * g + 3], w.w, l);
             }
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
-                const bf16x8 pb = pack8(p + 8 * j);
-                o0[t] = mfma(va[j], pb, o0[t]);
-                o1[t] = mfma(vb[j], pb, o1[t]);
+                const bf16x8 pb = pack8(x + 8 * j);
+                o0 = mfma(col_operand(cur + kTileBytes, col, hl, 0, kt, j), pb, o0);
+                o1 = mfma(col_operand(cur + kTileBytes, col, hl, 1, kt, j), pb, o1);
             }
         }
+        if (more) {
+            store_row_tile(nxt, rk, tid);
+            store_col_tile(nxt + kTileBytes, rv, tid);
+            if (tid < 16) *reinterpret_cast<float4 *>(nxt + 2 * kTileBytes + 16 * tid) = rw;
+        }
+        __syncthreads();
     }
+    const float lt = l + __shfl_xor(l, 32);
+    if (qi < N) {
+        const float inv = 1.f / lt;
+        bf16raw *ob = out + (size_t(bh) * N + qi) * kD + 4 * hl;
 #pragma unroll
-    for (int t = 0; t < NQ; ++t) {
-        const float lt = l[t] + __shfl_xor(l[t], 32);
-        const int qi = q0 + 32 * t + col;
-        if (qi < N) {
-            const float inv = 1.f / lt;
-            bf16raw *ob = out + (size_t(bh) * N + qi) * kD + 4 * hl;
+        for (int g = 0; g < 4; ++g) {
+            bf16x4 a, b;
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                bf16x4 a, b;
-#pragma unroll
-                for (int u = 0; u < 4; ++u) { a[u] = (__bf16)(o0[t][4 * g + u] * inv); b[u] = (__bf16)(o1[t][4 * g + u] * inv); }
-                *reinterpret_cast<bf16x4 *>(ob + 8 * g) = a;
-                *reinterpret_cast<bf16x4 *>(ob + 32 + 8 * g) = b;
-            }
-            if (hl == 0) lse[size_t(bh) * N + qi] = (m[t] + log2f(lt)) * 0.6931471805599453f;
+            for (int u = 0; u < 4; ++u) { a[u] = (__bf16)(o0[4 * g + u] * inv); b[u] = (__bf16)(o1[4 * g + u] * inv); }
+            *reinterpret_cast<bf16x4 *>(ob + 8 * g) = a;
+            *reinterpret_cast<bf16x4 *>(ob + 32 + 8 * g) = b;
         }
+        if (hl == 0) lse[size_t(bh) * N + qi] = (m + log2f(lt)) * 0.6931471805599453f + ln_wref;
     }
 }
 
-// Backward, key side: one wavefront = 64 keys (two MFMA tiles sharing the streamed operands),
-// streaming 32-query tiles.
-//   S = Q K^T and dP = dout V^T land with lane = key, registers = 16 queries;
-//   dV^T += dout^T P,  dK^T += Q^T dS  with the transposed operands from the workspace.
-__global__ void __launch_bounds__(256)
+// Backward (App. B.4 with every token in every neighborhood).  With w_j = omega_j / max omega and
+// L_i = log2(e) (lse_i - ln max omega):  p_ij = w_j pt_ij,  pt_ij = 2^(log2(e) scale q_i.k_j - L_i),
+// dS_ij = p_ij (dout_i.v_j - D_i).  The factor w_j never enters the inner loops: the key-side kernel
+// multiplies its finished sums by w_j (the lane's own key), the query-side kernel contracts with
+// K^T premultiplied by w_j (transpose_tokens).
+//
+// Key side: a workgroup owns 128 keys (one 32-key tile per wavefront) and streams the queries in stages
+// of 64: Q and dout token-major (for S = Q K^T and dP = dout V^T, which land with lane = key,
+// registers = 16 queries), Q^T and dout^T channel-major (dV^T += dout^T Pt, dK^T += Q^T dSt), L and D.
+__global__ void __launch_bounds__(256, 2)
 global_bwd_dkdv(const bf16raw *__restrict__ q, const bf16raw *__restrict__ k, const bf16raw *__restrict__ v,
                 const bf16raw *__restrict__ go, const bf16raw *__restrict__ qt, const bf16raw *__restrict__ got,
-                const float *__restrict__ bias, const float *__restrict__ L2, const float *__restrict__ Dv,
-                bf16raw *__restrict__ dk, bf16raw *__restrict__ dv, int N, int Npad, float c2, float scale)
+                const float *__restrict__ wtok, const float *__restrict__ L2, const float *__restrict__ Dv,
+                bf16raw *__restrict__ dk, bf16raw *__restrict__ dv, int N, int Npad, int nkb, int nunits, float c2,
+                float scale)
 {
-    constexpr int NK = 2;
-    const int bh = blockIdx.y;
-    const int k0 = (blockIdx.x * 4 + (threadIdx.x >> 6)) * (32 * NK);
-    if (k0 >= N) return;
-    const int lane = threadIdx.x & 63, col = lane & 31, hl = lane >> 5;
-    const int prow = perm_row(col);
-    bf16x8 kop[NK][4], vop[NK][4];
-    float bk[NK];
-    f32x16 dk0[NK], dk1[NK], dv0[NK], dv1[NK];
+    constexpr int kStage = 4 * kTileBytes + 512;     // Q, dout row tiles; Q^T, dout^T column tiles; L, D
+    __shared__ __attribute__((aligned(16))) char lds[2][kStage];
+    int unit;
+    if (!xcd_unit(nunits, unit)) return;
+    const int bh = unit / nkb, kb = unit - bh * nkb;
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = tid & 63, col = lane & 31, hl = lane >> 5;
+    const int ki = kb * 128 + wave * 32 + col;
+    bf16x8 kop[4], vop[4];
+    {
+        const size_t row = (size_t(bh) * N + min(ki, N - 1)) * kD + 8 * hl;
 #pragma unroll
-    for (int t = 0; t < NK; ++t) {
-        const int key = min(k0 + 32 * t + col, N - 1);
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            kop[t][ks] = ld8(k + (size_t(bh) * N + key) * kD + 16 * ks + 8 * hl);
-            vop[t][ks] = ld8(v + (size_t(bh) * N + key) * kD + 16 * ks + 8 * hl);
-        }
-        bk[t] = bias[min(k0 + 32 * t + col, Npad - 1)];
-#pragma unroll
-        for (int i = 0; i < 16; ++i) { dk0[t][i] = 0.f; dk1[t][i] = 0.f; dv0[t][i] = 0.f; dv1[t][i] = 0.f; }
+        for (int ks = 0; ks < 4; ++ks) { kop[ks] = ld8(k + row + 16 * ks); vop[ks] = ld8(v + row + 16 * ks); }
     }
-    const bf16raw *qb = q + size_t(bh) * N * kD + 8 * hl, *gb = go + size_t(bh) * N * kD + 8 * hl;
-    const bf16raw *qt0 = qt + (size_t(bh) * kD + col) * Npad + 16 * hl, *qt1 = qt0 + size_t(32) * Npad;
-    const bf16raw *gt0 = got + (size_t(bh) * kD + col) * Npad + 16 * hl, *gt1 = gt0 + size_t(32) * Npad;
-    const float *lb = L2 + size_t(bh) * Npad + 16 * hl, *Db = Dv + size_t(bh) * Npad + 16 * hl;
-    for (int q0 = 0; q0 < Npad; q0 += 32) {
-        const int qrow = min(q0 + prow, N - 1);
-        bf16x8 qa[4], ga[4], qta[2], qtb[2], gta[2], gtb[2];
-        float l2[16], dd[16];
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            qa[ks] = ld8(qb + size_t(qrow) * kD + 16 * ks);
-            ga[ks] = ld8(gb + size_t(qrow) * kD + 16 * ks);
+    f32x16 dk0 = {0}, dk1 = {0}, dv0 = {0}, dv1 = {0};
+    const bf16raw *qb = q + size_t(bh) * N * kD, *gb = go + size_t(bh) * N * kD;
+    const bf16raw *qtb = qt + size_t(bh) * kD * Npad, *gtb = got + size_t(bh) * kD * Npad;
+    const float *Lb = L2 + size_t(bh) * Npad, *Db = Dv + size_t(bh) * Npad;
+    {
+        const TileRegs r0 = fetch_row_tile(qb, 0, N, tid), r1 = fetch_row_tile(gb, 0, N, tid);
+        const TileRegs r2 = fetch_col_tile(qtb, 0, Npad, tid), r3 = fetch_col_tile(gtb, 0, Npad, tid);
+        store_row_tile(lds[0], r0, tid);
+        store_row_tile(lds[0] + kTileBytes, r1, tid);
+        store_col_tile(lds[0] + 2 * kTileBytes, r2, tid);
+        store_col_tile(lds[0] + 3 * kTileBytes, r3, tid);
+        if (tid < 32) {
+            const float *src = (tid < 16 ? Lb : Db) + 4 * (tid & 15);
+            *reinterpret_cast<float4 *>(lds[0] + 4 * kTileBytes + 16 * tid) = *reinterpret_cast<const float4 *>(src);
+        }
+    }
+    __syncthreads();
+    const int nst = Npad >> 6;
+    for (int st = 0; st < nst; ++st) {
+        const char *cur = lds[st & 1];
+        char *nxt = lds[(st + 1) & 1];
+        const bool more = st + 1 < nst;
+        TileRegs r0, r1, r2, r3;
+        float4 rs;
+        if (more) {
+            const int t0 = 64 * (st + 1);
+            r0 = fetch_row_tile(qb, t0, N, tid);
+            r1 = fetch_row_tile(gb, t0, N, tid);
+            r2 = fetch_col_tile(qtb, t0, Npad, tid);
+            r3 = fetch_col_tile(gtb, t0, Npad, tid);
+            if (tid < 32) rs = *reinterpret_cast<const float4 *>((tid < 16 ? Lb : Db) + t0 + 4 * (tid & 15));
         }
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const float4 x = *reinterpret_cast<const float4 *>(lb + q0 + 4 * g);
-            const float4 y = *reinterpret_cast<const float4 *>(Db + q0 + 4 * g);
-            l2[4 * g] = x.x; l2[4 * g + 1] = x.y; l2[4 * g + 2] = x.z; l2[4 * g + 3] = x.w;
-            dd[4 * g] = y.x; dd[4 * g + 1] = y.y; dd[4 * g + 2] = y.z; dd[4 * g + 3] = y.w;
-        }
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            qta[j] = ld8(qt0 + q0 + 8 * j); qtb[j] = ld8(qt1 + q0 + 8 * j);
-            gta[j] = ld8(gt0 + q0 + 8 * j); gtb[j] = ld8(gt1 + q0 + 8 * j);
-        }
-#pragma unroll
-        for (int t = 0; t < NK; ++t) {
+        for (int h = 0; h < 2; ++h) {
             f32x16 s = {0}, dp = {0};
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) {
-                s = mfma(qa[ks], kop[t][ks], s);
-                dp = mfma(ga[ks], vop[t][ks], dp);
+                s = mfma(row_operand(cur, col, hl, h, ks), kop[ks], s);
+                dp = mfma(row_operand(cur + kTileBytes, col, hl, h, ks), vop[ks], dp);
             }
+            const float *Lp = reinterpret_cast<const float *>(cur + 4 * kTileBytes) + 32 * h + 16 * hl;
             float p[16], ds[16];
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                p[i] = __builtin_amdgcn_exp2f(fmaf(s[i], c2, bk[t]) - l2[i]);
-                ds[i] = p[i] * (dp[i] - dd[i]);
+            for (int g = 0; g < 4; ++g) {
+                const float4 Lr = *reinterpret_cast<const float4 *>(Lp + 4 * g);
+                const float4 Dr = *reinterpret_cast<const float4 *>(Lp + 64 + 4 * g);
+                p[4 * g + 0] = __builtin_amdgcn_exp2f(fmaf(s[4 * g + 0], c2, -Lr.x));
+                p[4 * g + 1] = __builtin_amdgcn_exp2f(fmaf(s[4 * g + 1], c2, -Lr.y));
+                p[4 * g + 2] = __builtin_amdgcn_exp2f(fmaf(s[4 * g + 2], c2, -Lr.z));
+                p[4 * g + 3] = __builtin_amdgcn_exp2f(fmaf(s[4 * g + 3], c2, -Lr.w));
+                ds[4 * g + 0] = p[4 * g + 0] * (dp[4 * g + 0] - Dr.x);
+                ds[4 * g + 1] = p[4 * g + 1] * (dp[4 * g + 1] - Dr.y);
+                ds[4 * g + 2] = p[4 * g + 2] * (dp[4 * g + 2] - Dr.z);
+                ds[4 * g + 3] = p[4 * g + 3] * (dp[4 * g + 3] - Dr.w);
             }
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
                 const bf16x8 pb = pack8(p + 8 * j), sb = pack8(ds + 8 * j);
-                dv0[t] = mfma(gta[j], pb, dv0[t]);
-                dv1[t] = mfma(gtb[j], pb, dv1[t]);
-                dk0[t] = mfma(qta[j], sb, dk0[t]);
-                dk1[t] = mfma(qtb[j], sb, dk1[t]);
+                dv0 = mfma(col_operand(cur + 3 * kTileBytes, col, hl, 0, h, j), pb, dv0);
+                dv1 = mfma(col_operand(cur + 3 * kTileBytes, col, hl, 1, h, j), pb, dv1);
+                dk0 = mfma(col_operand(cur + 2 * kTileBytes, col, hl, 0, h, j), sb, dk0);
+                dk1 = mfma(col_operand(cur + 2 * kTileBytes, col, hl, 1, h, j), sb, dk1);
             }
         }
+        if (more) {
+            store_row_tile(nxt, r0, tid);
+            store_row_tile(nxt + kTileBytes, r1, tid);
+            store_col_tile(nxt + 2 * kTileBytes, r2, tid);
+            store_col_tile(nxt + 3 * kTileBytes, r3, tid);
+            if (tid < 32) *reinterpret_cast<float4 *>(nxt + 4 * kTileBytes + 16 * tid) = rs;
+        }
+        __syncthreads();
     }
-#pragma unroll
-    for (int t = 0; t < NK; ++t) {
-        const int key = k0 + 32 * t + col;
-        if (key >= N) continue;
-        bf16raw *dkb = dk + (size_t(bh) * N + key) * kD + 4 * hl, *dvb = dv + (size_t(bh) * N + key) * kD + 4 * hl;
+    if (ki < N) {
+        const float wk = wtok[ki], wks = wk * scale;
+        bf16raw *dkb = dk + (size_t(bh) * N + ki) * kD + 4 * hl, *dvb = dv + (size_t(bh) * N + ki) * kD + 4 * hl;
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
             bf16x4 a, b, c, d;
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                a[u] = (__bf16)(dk0[t][4 * g + u] * scale); b[u] = (__bf16)(dk1[t][4 * g + u] * scale);
-                c[u] = (__bf16)dv0[t][4 * g + u]; d[u] = (__bf16)dv1[t][4 * g + u];
+                a[u] = (__bf16)(dk0[4 * g + u] * wks); b[u] = (__bf16)(dk1[4 * g + u] * wks);
+                c[u] = (__bf16)(dv0[4 * g + u] * wk); d[u] = (__bf16)(dv1[4 * g + u] * wk);
             }
             *reinterpret_cast<bf16x4 *>(dkb + 8 * g) = a;
             *reinterpret_cast<bf16x4 *>(dkb + 32 + 8 * g) = b;
@@ -294,85 +408,85 @@ global_bwd_dkdv(const bf16raw *__restrict__ q, const bf16raw *__restrict__ k, co
     }
 }
 
-// Backward, query side: one wavefront = 64 queries, streaming 32-key tiles.
-//   S^T = K Q^T and dP^T = V dout^T land with lane = query, registers = 16 keys;
-//   dQ^T += K^T dS^T with K^T from the workspace.
-__global__ void __launch_bounds__(256)
+// Query side: a workgroup owns 128 queries and streams the keys in stages of 64: K and V token-major
+// (S^T = K Q^T and dP^T = V dout^T land with lane = query, registers = 16 keys) and w K^T channel-major
+// (dQ^T += (w K)^T dSt^T).
+__global__ void __launch_bounds__(256, 3)
 global_bwd_dq(const bf16raw *__restrict__ q, const bf16raw *__restrict__ k, const bf16raw *__restrict__ v,
-              const bf16raw *__restrict__ go, const bf16raw *__restrict__ kt, const float *__restrict__ bias,
-              const float *__restrict__ L2, const float *__restrict__ Dv, bf16raw *__restrict__ dq, int N, int Npad,
-              float c2, float scale)
+              const bf16raw *__restrict__ go, const bf16raw *__restrict__ ktw, const float *__restrict__ L2,
+              const float *__restrict__ Dv, bf16raw *__restrict__ dq, int N, int Npad, int nqb, int nunits, float c2,
+              float scale)
 {
-    constexpr int NQ = 2;
-    const int bh = blockIdx.y;
-    const int q0 = (blockIdx.x * 4 + (threadIdx.x >> 6)) * (32 * NQ);
-    if (q0 >= N) return;
-    const int lane = threadIdx.x & 63, col = lane & 31, hl = lane >> 5;
-    const int prow = perm_row(col);
-    bf16x8 qop[NQ][4], gop[NQ][4];
-    float lse2[NQ], Dq[NQ];
-    f32x16 dq0[NQ], dq1[NQ];
+    constexpr int kStage = 3 * kTileBytes;           // K, V row tiles; (w K)^T column tile
+    __shared__ __attribute__((aligned(16))) char lds[2][kStage];
+    int unit;
+    if (!xcd_unit(nunits, unit)) return;
+    const int bh = unit / nqb, qb = unit - bh * nqb;
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = tid & 63, col = lane & 31, hl = lane >> 5;
+    const int qi = qb * 128 + wave * 32 + col;
+    bf16x8 qop[4], gop[4];
+    {
+        const size_t row = (size_t(bh) * N + min(qi, N - 1)) * kD + 8 * hl;
 #pragma unroll
-    for (int t = 0; t < NQ; ++t) {
-        const int query = min(q0 + 32 * t + col, N - 1);
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            qop[t][ks] = ld8(q + (size_t(bh) * N + query) * kD + 16 * ks + 8 * hl);
-            gop[t][ks] = ld8(go + (size_t(bh) * N + query) * kD + 16 * ks + 8 * hl);
-        }
-        lse2[t] = L2[size_t(bh) * Npad + query];
-        Dq[t] = Dv[size_t(bh) * Npad + query];
-#pragma unroll
-        for (int i = 0; i < 16; ++i) { dq0[t][i] = 0.f; dq1[t][i] = 0.f; }
+        for (int ks = 0; ks < 4; ++ks) { qop[ks] = ld8(q + row + 16 * ks); gop[ks] = ld8(go + row + 16 * ks); }
     }
-    const bf16raw *kb = k + size_t(bh) * N * kD + 8 * hl, *vb = v + size_t(bh) * N * kD + 8 * hl;
-    const bf16raw *kt0 = kt + (size_t(bh) * kD + col) * Npad + 16 * hl, *kt1 = kt0 + size_t(32) * Npad;
-    for (int key0 = 0; key0 < Npad; key0 += 32) {
-        const int key = min(key0 + prow, N - 1);
-        bf16x8 ka[4], va[4], kta[2], ktb[2];
-        float bb[16];
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            ka[ks] = ld8(kb + size_t(key) * kD + 16 * ks);
-            va[ks] = ld8(vb + size_t(key) * kD + 16 * ks);
+    const float Lq = L2[size_t(bh) * Npad + min(qi, N - 1)], Dq = Dv[size_t(bh) * Npad + min(qi, N - 1)];
+    f32x16 dq0 = {0}, dq1 = {0};
+    const bf16raw *kb = k + size_t(bh) * N * kD, *vb = v + size_t(bh) * N * kD;
+    const bf16raw *ktb = ktw + size_t(bh) * kD * Npad;
+    {
+        const TileRegs r0 = fetch_row_tile(kb, 0, N, tid), r1 = fetch_row_tile(vb, 0, N, tid);
+        const TileRegs r2 = fetch_col_tile(ktb, 0, Npad, tid);
+        store_row_tile(lds[0], r0, tid);
+        store_row_tile(lds[0] + kTileBytes, r1, tid);
+        store_col_tile(lds[0] + 2 * kTileBytes, r2, tid);
+    }
+    __syncthreads();
+    const int nst = Npad >> 6;
+    for (int st = 0; st < nst; ++st) {
+        const char *cur = lds[st & 1];
+        char *nxt = lds[(st + 1) & 1];
+        const bool more = st + 1 < nst;
+        TileRegs r0, r1, r2;
+        if (more) {
+            const int t0 = 64 * (st + 1);
+            r0 = fetch_row_tile(kb, t0, N, tid);
+            r1 = fetch_row_tile(vb, t0, N, tid);
+            r2 = fetch_col_tile(ktb, t0, Npad, tid);
         }
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const float4 b = *reinterpret_cast<const float4 *>(bias + key0 + 16 * hl + 4 * g);
-            bb[4 * g] = b.x; bb[4 * g + 1] = b.y; bb[4 * g + 2] = b.z; bb[4 * g + 3] = b.w;
-        }
-#pragma unroll
-        for (int j = 0; j < 2; ++j) { kta[j] = ld8(kt0 + key0 + 8 * j); ktb[j] = ld8(kt1 + key0 + 8 * j); }
-#pragma unroll
-        for (int t = 0; t < NQ; ++t) {
+        for (int h = 0; h < 2; ++h) {
             f32x16 s = {0}, dp = {0};
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) {
-                s = mfma(ka[ks], qop[t][ks], s);
-                dp = mfma(va[ks], gop[t][ks], dp);
+                s = mfma(row_operand(cur, col, hl, h, ks), qop[ks], s);
+                dp = mfma(row_operand(cur + kTileBytes, col, hl, h, ks), gop[ks], dp);
             }
             float ds[16];
 #pragma unroll
-            for (int i = 0; i < 16; ++i)
-                ds[i] = __builtin_amdgcn_exp2f(fmaf(s[i], c2, bb[i]) - lse2[t]) * (dp[i] - Dq[t]);
+            for (int i = 0; i < 16; ++i) ds[i] = __builtin_amdgcn_exp2f(fmaf(s[i], c2, -Lq)) * (dp[i] - Dq);
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
                 const bf16x8 sb = pack8(ds + 8 * j);
-                dq0[t] = mfma(kta[j], sb, dq0[t]);
-                dq1[t] = mfma(ktb[j], sb, dq1[t]);
+                dq0 = mfma(col_operand(cur + 2 * kTileBytes, col, hl, 0, h, j), sb, dq0);
+                dq1 = mfma(col_operand(cur + 2 * kTileBytes, col, hl, 1, h, j), sb, dq1);
             }
         }
+        if (more) {
+            store_row_tile(nxt, r0, tid);
+            store_row_tile(nxt + kTileBytes, r1, tid);
+            store_col_tile(nxt + 2 * kTileBytes, r2, tid);
+        }
+        __syncthreads();
     }
-#pragma unroll
-    for (int t = 0; t < NQ; ++t) {
-        const int qi = q0 + 32 * t + col;
-        if (qi >= N) continue;
+    if (qi < N) {
         bf16raw *dqb = dq + (size_t(bh) * N + qi) * kD + 4 * hl;
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
             bf16x4 a, b;
 #pragma unroll
-            for (int u = 0; u < 4; ++u) { a[u] = (__bf16)(dq0[t][4 * g + u] * scale); b[u] = (__bf16)(dq1[t][4 * g + u] * scale); }
+            for (int u = 0; u < 4; ++u) { a[u] = (__bf16)(dq0[4 * g + u] * scale); b[u] = (__bf16)(dq1[4 * g + u] * scale); }
             *reinterpret_cast<bf16x4 *>(dqb + 8 * g) = a;
             *reinterpret_cast<bf16x4 *>(dqb + 32 + 8 * g) = b;
         }
@@ -394,10 +508,10 @@ int check_global(const s2_grid_t *g, int batch, int heads, int d, int dtype)
 
 size_t transposed_bytes(const s2_grid_t *g, int nbh) { return size_t(nbh) * kD * g->npad_tok * sizeof(bf16raw); }
 
-void launch_transpose(const void *in, void *out, int nbh, int N, int Npad, hipStream_t st)
+void launch_transpose(const void *in, void *out, const float *wtok, int nbh, int N, int Npad, hipStream_t st)
 {
     hipLaunchKernelGGL(transpose_tokens, dim3((Npad + 63) / 64, nbh), dim3(256), 0, st,
-                       static_cast<const bf16raw *>(in), static_cast<bf16raw *>(out), N, Npad);
+                       static_cast<const bf16raw *>(in), static_cast<bf16raw *>(out), wtok, N, Npad);
 }
 
 }  // namespace
@@ -428,11 +542,12 @@ extern "C" int s2_attn_global_fwd(const s2_grid_t *g, int batch, int heads, int 
         return s2_fail(S2_ERR_WORKSPACE, "workspace missing or smaller than s2_attn_global_fwd_workspace_bytes()");
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const int nbh = batch * heads, N = g->nlat_in * g->nlon_in, Npad = g->npad_tok;
-    launch_transpose(v, workspace, nbh, N, Npad, st);
+    launch_transpose(v, workspace, g->dev_w_tok, nbh, N, Npad, st);
     S2TraceScope tr("global_fwd", double(nbh) * N * N, st);
-    hipLaunchKernelGGL(global_fwd, dim3((N + 255) / 256, nbh), dim3(256), 0, st, static_cast<const bf16raw *>(q),
-                       static_cast<const bf16raw *>(k), static_cast<const bf16raw *>(workspace), g->dev_bias_tok,
-                       static_cast<bf16raw *>(out), lse, N, Npad, scale * kLog2e);
+    const int nqb = (N + 127) / 128, nunits = nbh * nqb;
+    hipLaunchKernelGGL(global_fwd, dim3(8 * ((nunits + 7) / 8)), dim3(256), 0, st, static_cast<const bf16raw *>(q),
+                       static_cast<const bf16raw *>(k), static_cast<const bf16raw *>(workspace), g->dev_w_tok,
+                       static_cast<bf16raw *>(out), lse, N, Npad, nqb, nunits, scale * kLog2e, g->dt.ln_omega_ref);
     S2_HIP_CHECK(hipGetLastError());
     return S2_OK;
 }
@@ -456,24 +571,26 @@ extern "C" int s2_attn_global_bwd(const s2_grid_t *g, int batch, int heads, int 
     bf16raw *qt = reinterpret_cast<bf16raw *>(ws), *kt = reinterpret_cast<bf16raw *>(ws + tb),
             *got = reinterpret_cast<bf16raw *>(ws + 2 * tb);
     float *L2 = reinterpret_cast<float *>(ws + 3 * tb), *Dv = reinterpret_cast<float *>(ws + 3 * tb + sb);
-    launch_transpose(q, qt, nbh, N, Npad, st);
-    launch_transpose(k, kt, nbh, N, Npad, st);
-    launch_transpose(dout, got, nbh, N, Npad, st);
+    launch_transpose(q, qt, nullptr, nbh, N, Npad, st);
+    launch_transpose(k, kt, g->dev_w_tok, nbh, N, Npad, st);
+    launch_transpose(dout, got, nullptr, nbh, N, Npad, st);
     hipLaunchKernelGGL(rowstats, dim3((Npad + 255) / 256, nbh), dim3(256), 0, st, static_cast<const bf16raw *>(dout),
-                       static_cast<const bf16raw *>(out), lse, L2, Dv, N, Npad);
+                       static_cast<const bf16raw *>(out), lse, L2, Dv, N, Npad, g->dt.ln_omega_ref);
     const float c2 = scale * kLog2e;
+    const int nblk = (N + 127) / 128, nunits = nbh * nblk;
+    const dim3 grid(8 * ((nunits + 7) / 8));
     {
     S2TraceScope tr("global_bwd_dkdv", double(nbh) * N * N, st);
-    hipLaunchKernelGGL(global_bwd_dkdv, dim3((N + 255) / 256, nbh), dim3(256), 0, st, static_cast<const bf16raw *>(q),
+    hipLaunchKernelGGL(global_bwd_dkdv, grid, dim3(256), 0, st, static_cast<const bf16raw *>(q),
                        static_cast<const bf16raw *>(k), static_cast<const bf16raw *>(v),
-                       static_cast<const bf16raw *>(dout), qt, got, g->dev_bias_tok, L2, Dv,
-                       static_cast<bf16raw *>(dk), static_cast<bf16raw *>(dv), N, Npad, c2, scale);
+                       static_cast<const bf16raw *>(dout), qt, got, g->dev_w_tok, L2, Dv,
+                       static_cast<bf16raw *>(dk), static_cast<bf16raw *>(dv), N, Npad, nblk, nunits, c2, scale);
     }
     S2TraceScope tr("global_bwd_dq", double(nbh) * N * N, st);
-    hipLaunchKernelGGL(global_bwd_dq, dim3((N + 255) / 256, nbh), dim3(256), 0, st, static_cast<const bf16raw *>(q),
+    hipLaunchKernelGGL(global_bwd_dq, grid, dim3(256), 0, st, static_cast<const bf16raw *>(q),
                        static_cast<const bf16raw *>(k), static_cast<const bf16raw *>(v),
-                       static_cast<const bf16raw *>(dout), kt, g->dev_bias_tok, L2, Dv, static_cast<bf16raw *>(dq), N,
-                       Npad, c2, scale);
+                       static_cast<const bf16raw *>(dout), kt, L2, Dv, static_cast<bf16raw *>(dq), N, Npad, nblk,
+                       nunits, c2, scale);
     S2_HIP_CHECK(hipGetLastError());
     return S2_OK;
 }

@@ -62,9 +62,11 @@ struct s2_grid {
     bool on_device = false;
     int device = -1;
     void *dev_blob = nullptr;
-    // global attention: log2(omega) per input token, -inf on the padding up to npad_tok (multiple of 32)
+    // global attention, per input token, padded to npad_tok (a multiple of 64): log2(omega) with -inf on
+    // the padding, and omega / max omega with 0 on the padding
     int npad_tok = 0;
     const float *dev_bias_tok = nullptr;
+    const float *dev_w_tok = nullptr;
     S2DeviceTables dt{};
 };
 
