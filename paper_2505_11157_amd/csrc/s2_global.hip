@@ -101,9 +101,11 @@ rowstats(const bf16raw *__restrict__ go, const bf16raw *__restrict__ o, const fl
 
 // ---------------------------------------------------------------------------------------------
 // Staging of streamed operands in LDS.  A workgroup of four wavefronts streams 64-token stages; every
-// stage is fetched from global memory once per workgroup with coalesced 16-byte loads (held in
-// registers while the previous stage is being used), written to one of two LDS buffers, and read from
-// there by all four wavefronts as MFMA operands.  A staged tile is 64 rows of 128 bytes; the 16-byte
+// stage is copied from global memory once per workgroup (coalesced 16-byte pieces, no registers in
+// between) into one of two LDS buffers while the other one is being used, and read from there by all
+// four wavefronts as MFMA operands.  The two buffers are separate arrays and the stage loop is unrolled
+// by two, so every access names its array: the compiler then knows that the reads of one buffer need
+// not wait for the copies in flight into the other; the barrier at the end of a stage waits for them.  A staged tile is 64 rows of 128 bytes; the 16-byte
 // piece c of row r sits at piece c ^ ((r >> 1) & 7), so that the 16 consecutive lanes a 16-byte LDS read
 // serves together (16 consecutive rows, same logical piece) fall on 16 different bank groups, and so do
 // the writes of a row.  Token-major tiles ("row tiles": 64 tokens x 64 channels) additionally have the
@@ -121,38 +123,40 @@ __device__ __forceinline__ int lds_row_of_token(int t)
     return (t & 32) | (k & 3) | (((k >> 4) & 1) << 2) | (((k >> 2) & 3) << 3);
 }
 
-// The two 16-byte pieces of a tile that one thread moves: rows (tid >> 3) and 32 + (tid >> 3), piece tid & 7.
-struct TileRegs { uint4 a, b; };
+// Copies go straight from global memory into LDS (global_load_lds_dwordx4: lane i of a wavefront
+// deposits its 16 bytes at base + 16 i, i.e. one instruction fills eight consecutive rows), so the
+// swizzle and the row permutation are applied on the source side: lane i fetches the piece that belongs
+// at physical position i.  Wavefront w of the four copies rows 16 w .. 16 w + 15 of every tile.
+typedef __attribute__((address_space(1))) const void *gptr_t;
+typedef __attribute__((address_space(3))) void *lptr_t;
 
-// token-major tile: tokens tok0 + (tid >> 3) and tok0 + 32 + (tid >> 3), clamped to N - 1
-__device__ __forceinline__ TileRegs fetch_row_tile(const bf16raw *base, int tok0, int N, int tid)
+// token-major tile: LDS row r holds token tok0 + (r & 32) + perm_row(r & 31), clamped to N - 1
+__device__ __forceinline__ void copy_row_tile(const bf16raw *base, int tok0, int N, char *tile, int wave, int lane)
 {
-    TileRegs r;
-    const int t = tid >> 3, c = tid & 7;
-    r.a = *reinterpret_cast<const uint4 *>(base + size_t(min(tok0 + t, N - 1)) * kD + 8 * c);
-    r.b = *reinterpret_cast<const uint4 *>(base + size_t(min(tok0 + 32 + t, N - 1)) * kD + 8 * c);
-    return r;
-}
-__device__ __forceinline__ void store_row_tile(char *lds, const TileRegs &r, int tid)
-{
-    const int off = swz(lds_row_of_token(tid >> 3), tid & 7);
-    *reinterpret_cast<uint4 *>(lds + off) = r.a;
-    *reinterpret_cast<uint4 *>(lds + off + 32 * 128) = r.b;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int r = 16 * wave + 8 * h + (lane >> 3);
+        const int c = (lane & 7) ^ ((r >> 1) & 7);
+        const int t = (r & 32) | perm_row(r & 31);
+        const char *src = reinterpret_cast<const char *>(base + size_t(min(tok0 + t, N - 1)) * kD) + 16 * c;
+        __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(tile + 2048 * wave + 1024 * h), 16, 0, 0);
+    }
 }
 // channel-major tile from a transposed operand [64][Npad] (Npad a multiple of 64: always in bounds)
-__device__ __forceinline__ TileRegs fetch_col_tile(const bf16raw *base, int tok0, int Npad, int tid)
+__device__ __forceinline__ void copy_col_tile(const bf16raw *base, int tok0, int Npad, char *tile, int wave, int lane)
 {
-    TileRegs r;
-    const int ch = tid >> 3, c = tid & 7;
-    r.a = *reinterpret_cast<const uint4 *>(base + size_t(ch) * Npad + tok0 + 8 * c);
-    r.b = *reinterpret_cast<const uint4 *>(base + size_t(ch + 32) * Npad + tok0 + 8 * c);
-    return r;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int r = 16 * wave + 8 * h + (lane >> 3);
+        const int c = (lane & 7) ^ ((r >> 1) & 7);
+        const char *src = reinterpret_cast<const char *>(base + size_t(r) * Npad + tok0 + 8 * c);
+        __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(tile + 2048 * wave + 1024 * h), 16, 0, 0);
+    }
 }
-__device__ __forceinline__ void store_col_tile(char *lds, const TileRegs &r, int tid)
+// 64 consecutive floats (one wavefront, lane = element)
+__device__ __forceinline__ void copy_floats(const float *src, char *dst, int lane)
 {
-    const int off = swz(tid >> 3, tid & 7);
-    *reinterpret_cast<uint4 *>(lds + off) = r.a;
-    *reinterpret_cast<uint4 *>(lds + off + 32 * 128) = r.b;
+    __builtin_amdgcn_global_load_lds((gptr_t)(src + lane), (lptr_t)dst, 4, 0, 0);
 }
 __device__ __forceinline__ bf16x8 lds8(const char *p)
 {
@@ -191,7 +195,8 @@ global_fwd(const bf16raw *__restrict__ q, const bf16raw *__restrict__ k, const b
            int nqb, int nunits, float c2, float ln_wref)
 {
     constexpr int kStage = 2 * kTileBytes + 256;     // K row tile, V^T column tile, 64 weights
-    __shared__ __attribute__((aligned(16))) char lds[2][kStage];
+    __shared__ __attribute__((aligned(16))) char buf0[kStage];
+    __shared__ __attribute__((aligned(16))) char buf1[kStage];
     int unit;
     if (!xcd_unit(nunits, unit)) return;
     const int bh = unit / nqb, qb = unit - bh * nqb;
@@ -208,26 +213,14 @@ global_fwd(const bf16raw *__restrict__ q, const bf16raw *__restrict__ k, const b
     float m = 0.f, l = 0.f;
     const bf16raw *kb = k + size_t(bh) * N * kD;
     const bf16raw *vb = vt + size_t(bh) * kD * Npad;
-    {
-        const TileRegs rk = fetch_row_tile(kb, 0, N, tid), rv = fetch_col_tile(vb, 0, Npad, tid);
-        store_row_tile(lds[0], rk, tid);
-        store_col_tile(lds[0] + kTileBytes, rv, tid);
-        if (tid < 16) *reinterpret_cast<float4 *>(lds[0] + 2 * kTileBytes + 16 * tid) =
-            *reinterpret_cast<const float4 *>(wtok + 4 * tid);
-    }
-    __syncthreads();
     const int nst = Npad >> 6;
-    for (int st = 0; st < nst; ++st) {
-        const char *cur = lds[st & 1];
-        char *nxt = lds[(st + 1) & 1];
-        const bool more = st + 1 < nst;
-        TileRegs rk, rv;
-        float4 rw;
-        if (more) {
-            rk = fetch_row_tile(kb, 64 * (st + 1), N, tid);
-            rv = fetch_col_tile(vb, 64 * (st + 1), Npad, tid);
-            if (tid < 16) rw = *reinterpret_cast<const float4 *>(wtok + 64 * (st + 1) + 4 * tid);
-        }
+    auto request = [&](char *buf, int st) {
+        copy_row_tile(kb, 64 * st, N, buf, wave, lane);
+        copy_col_tile(vb, 64 * st, Npad, buf + kTileBytes, wave, lane);
+        if (wave == 0) copy_floats(wtok + 64 * st, buf + 2 * kTileBytes, lane);
+    };
+    auto stage = [&](const char *cur, char *nxt, int st) {
+        if (st + 1 < nst) request(nxt, st + 1);
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt) {
             f32x16 s = {0};
@@ -237,9 +230,10 @@ global_fwd(const bf16raw *__restrict__ q, const bf16raw *__restrict__ k, const b
             float mx = -INFINITY;
 #pragma unroll
             for (int i = 0; i < 16; ++i) { x[i] = fmaf(s[i], c2, -m); mx = fmaxf(mx, x[i]); }
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            // the two half-wavefronts of a query exchange their maxima only when the reference has to move
             const bool first = st == 0 && kt == 0;
             if (first || __any(mx > 8.f)) {
+                mx = fmaxf(mx, __shfl_xor(mx, 32));
                 const float delta = first ? mx : (mx > 8.f ? mx : 0.f);
                 const float corr = first ? 1.f : __builtin_amdgcn_exp2f(-delta);
                 m += delta;
@@ -263,12 +257,13 @@ global_fwd(const bf16raw *__restrict__ q, const bf16raw *__restrict__ k, const b
                 o1 = mfma(col_operand(cur + kTileBytes, col, hl, 1, kt, j), pb, o1);
             }
         }
-        if (more) {
-            store_row_tile(nxt, rk, tid);
-            store_col_tile(nxt + kTileBytes, rv, tid);
-            if (tid < 16) *reinterpret_cast<float4 *>(nxt + 2 * kTileBytes + 16 * tid) = rw;
-        }
-        __syncthreads();
+        __syncthreads();   // everybody is done with `cur`, and the copies into `nxt` have landed
+    };
+    request(buf0, 0);
+    __syncthreads();
+    for (int st = 0; st < nst; st += 2) {
+        stage(buf0, buf1, st);
+        if (st + 1 < nst) stage(buf1, buf0, st + 1);
     }
     const float lt = l + __shfl_xor(l, 32);
     if (qi < N) {
@@ -303,7 +298,8 @@ global_bwd_dkdv(const bf16raw *__restrict__ q, const bf16raw *__restrict__ k, co
                 float scale)
 {
     constexpr int kStage = 4 * kTileBytes + 512;     // Q, dout row tiles; Q^T, dout^T column tiles; L, D
-    __shared__ __attribute__((aligned(16))) char lds[2][kStage];
+    __shared__ __attribute__((aligned(16))) char buf0[kStage];
+    __shared__ __attribute__((aligned(16))) char buf1[kStage];
     int unit;
     if (!xcd_unit(nunits, unit)) return;
     const int bh = unit / nkb, kb = unit - bh * nkb;
@@ -320,34 +316,18 @@ global_bwd_dkdv(const bf16raw *__restrict__ q, const bf16raw *__restrict__ k, co
     const bf16raw *qb = q + size_t(bh) * N * kD, *gb = go + size_t(bh) * N * kD;
     const bf16raw *qtb = qt + size_t(bh) * kD * Npad, *gtb = got + size_t(bh) * kD * Npad;
     const float *Lb = L2 + size_t(bh) * Npad, *Db = Dv + size_t(bh) * Npad;
-    {
-        const TileRegs r0 = fetch_row_tile(qb, 0, N, tid), r1 = fetch_row_tile(gb, 0, N, tid);
-        const TileRegs r2 = fetch_col_tile(qtb, 0, Npad, tid), r3 = fetch_col_tile(gtb, 0, Npad, tid);
-        store_row_tile(lds[0], r0, tid);
-        store_row_tile(lds[0] + kTileBytes, r1, tid);
-        store_col_tile(lds[0] + 2 * kTileBytes, r2, tid);
-        store_col_tile(lds[0] + 3 * kTileBytes, r3, tid);
-        if (tid < 32) {
-            const float *src = (tid < 16 ? Lb : Db) + 4 * (tid & 15);
-            *reinterpret_cast<float4 *>(lds[0] + 4 * kTileBytes + 16 * tid) = *reinterpret_cast<const float4 *>(src);
-        }
-    }
-    __syncthreads();
     const int nst = Npad >> 6;
-    for (int st = 0; st < nst; ++st) {
-        const char *cur = lds[st & 1];
-        char *nxt = lds[(st + 1) & 1];
-        const bool more = st + 1 < nst;
-        TileRegs r0, r1, r2, r3;
-        float4 rs;
-        if (more) {
-            const int t0 = 64 * (st + 1);
-            r0 = fetch_row_tile(qb, t0, N, tid);
-            r1 = fetch_row_tile(gb, t0, N, tid);
-            r2 = fetch_col_tile(qtb, t0, Npad, tid);
-            r3 = fetch_col_tile(gtb, t0, Npad, tid);
-            if (tid < 32) rs = *reinterpret_cast<const float4 *>((tid < 16 ? Lb : Db) + t0 + 4 * (tid & 15));
-        }
+    auto request = [&](char *buf, int st) {
+        const int t0 = 64 * st;
+        copy_row_tile(qb, t0, N, buf, wave, lane);
+        copy_row_tile(gb, t0, N, buf + kTileBytes, wave, lane);
+        copy_col_tile(qtb, t0, Npad, buf + 2 * kTileBytes, wave, lane);
+        copy_col_tile(gtb, t0, Npad, buf + 3 * kTileBytes, wave, lane);
+        if (wave == 0) copy_floats(Lb + t0, buf + 4 * kTileBytes, lane);
+        if (wave == 1) copy_floats(Db + t0, buf + 4 * kTileBytes + 256, lane);
+    };
+    auto stage = [&](const char *cur, char *nxt, int st) {
+        if (st + 1 < nst) request(nxt, st + 1);
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             f32x16 s = {0}, dp = {0};
@@ -380,14 +360,13 @@ global_bwd_dkdv(const bf16raw *__restrict__ q, const bf16raw *__restrict__ k, co
                 dk1 = mfma(col_operand(cur + 2 * kTileBytes, col, hl, 1, h, j), sb, dk1);
             }
         }
-        if (more) {
-            store_row_tile(nxt, r0, tid);
-            store_row_tile(nxt + kTileBytes, r1, tid);
-            store_col_tile(nxt + 2 * kTileBytes, r2, tid);
-            store_col_tile(nxt + 3 * kTileBytes, r3, tid);
-            if (tid < 32) *reinterpret_cast<float4 *>(nxt + 4 * kTileBytes + 16 * tid) = rs;
-        }
-        __syncthreads();
+        __syncthreads();   // everybody is done with `cur`, and the copies into `nxt` have landed
+    };
+    request(buf0, 0);
+    __syncthreads();
+    for (int st = 0; st < nst; st += 2) {
+        stage(buf0, buf1, st);
+        if (st + 1 < nst) stage(buf1, buf0, st + 1);
     }
     if (ki < N) {
         const float wk = wtok[ki], wks = wk * scale;
@@ -418,7 +397,8 @@ global_bwd_dq(const bf16raw *__restrict__ q, const bf16raw *__restrict__ k, cons
               float scale)
 {
     constexpr int kStage = 3 * kTileBytes;           // K, V row tiles; (w K)^T column tile
-    __shared__ __attribute__((aligned(16))) char lds[2][kStage];
+    __shared__ __attribute__((aligned(16))) char buf0[kStage];
+    __shared__ __attribute__((aligned(16))) char buf1[kStage];
     int unit;
     if (!xcd_unit(nunits, unit)) return;
     const int bh = unit / nqb, qb = unit - bh * nqb;
@@ -435,26 +415,15 @@ global_bwd_dq(const bf16raw *__restrict__ q, const bf16raw *__restrict__ k, cons
     f32x16 dq0 = {0}, dq1 = {0};
     const bf16raw *kb = k + size_t(bh) * N * kD, *vb = v + size_t(bh) * N * kD;
     const bf16raw *ktb = ktw + size_t(bh) * kD * Npad;
-    {
-        const TileRegs r0 = fetch_row_tile(kb, 0, N, tid), r1 = fetch_row_tile(vb, 0, N, tid);
-        const TileRegs r2 = fetch_col_tile(ktb, 0, Npad, tid);
-        store_row_tile(lds[0], r0, tid);
-        store_row_tile(lds[0] + kTileBytes, r1, tid);
-        store_col_tile(lds[0] + 2 * kTileBytes, r2, tid);
-    }
-    __syncthreads();
     const int nst = Npad >> 6;
-    for (int st = 0; st < nst; ++st) {
-        const char *cur = lds[st & 1];
-        char *nxt = lds[(st + 1) & 1];
-        const bool more = st + 1 < nst;
-        TileRegs r0, r1, r2;
-        if (more) {
-            const int t0 = 64 * (st + 1);
-            r0 = fetch_row_tile(kb, t0, N, tid);
-            r1 = fetch_row_tile(vb, t0, N, tid);
-            r2 = fetch_col_tile(ktb, t0, Npad, tid);
-        }
+    auto request = [&](char *buf, int st) {
+        const int t0 = 64 * st;
+        copy_row_tile(kb, t0, N, buf, wave, lane);
+        copy_row_tile(vb, t0, N, buf + kTileBytes, wave, lane);
+        copy_col_tile(ktb, t0, Npad, buf + 2 * kTileBytes, wave, lane);
+    };
+    auto stage = [&](const char *cur, char *nxt, int st) {
+        if (st + 1 < nst) request(nxt, st + 1);
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             f32x16 s = {0}, dp = {0};
@@ -473,12 +442,13 @@ global_bwd_dq(const bf16raw *__restrict__ q, const bf16raw *__restrict__ k, cons
                 dq1 = mfma(col_operand(cur + 2 * kTileBytes, col, hl, 1, h, j), sb, dq1);
             }
         }
-        if (more) {
-            store_row_tile(nxt, r0, tid);
-            store_row_tile(nxt + kTileBytes, r1, tid);
-            store_col_tile(nxt + 2 * kTileBytes, r2, tid);
-        }
-        __syncthreads();
+        __syncthreads();   // everybody is done with `cur`, and the copies into `nxt` have landed
+    };
+    request(buf0, 0);
+    __syncthreads();
+    for (int st = 0; st < nst; st += 2) {
+        stage(buf0, buf1, st);
+        if (st + 1 < nst) stage(buf1, buf0, st + 1);
     }
     if (qi < N) {
         bf16raw *dqb = dq + (size_t(bh) * N + qi) * kD + 4 * hl;
