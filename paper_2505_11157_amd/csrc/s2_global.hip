@@ -189,6 +189,8 @@ __device__ __forceinline__ bool xcd_unit(int nunits, int &unit)
 // w_j = omega_j / max omega (transpose_tokens does that), the running sum is l_i = sum_j w_j 2^(x_ij - m_i)
 // with x = log2(e) scale q.k, and the reference m_i follows the bare logits (it moves only when a logit
 // exceeds it by more than 2^8).  lse_i = ln 2 (m_i + log2 l_i) + ln max omega.
+// UNIFORM_W: the longitude count is a multiple of 32, so a 32-key tile never straddles two latitudes.
+template <bool UNIFORM_W>
 __global__ void __launch_bounds__(256, 3)
 global_fwd(const bf16raw *__restrict__ q, const bf16raw *__restrict__ k, const bf16raw *__restrict__ vt,
            const float *__restrict__ wtok, bf16raw *__restrict__ out, float *__restrict__ lse, int N, int Npad,
@@ -242,13 +244,21 @@ global_fwd(const bf16raw *__restrict__ q, const bf16raw *__restrict__ k, const b
                 for (int i = 0; i < 16; ++i) { o0[i] *= corr; o1[i] *= corr; x[i] -= delta; }
             }
             const float *wp = reinterpret_cast<const float *>(cur + 2 * kTileBytes) + 32 * kt + 16 * hl;
+            if (UNIFORM_W) {
+                // all 32 keys of the tile lie on one latitude: one weight for the whole tile
+                float psum = 0.f;
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const float4 w = *reinterpret_cast<const float4 *>(wp + 4 * g);
-                x[4 * g + 0] = __builtin_amdgcn_exp2f(x[4 * g + 0]); l = fmaf(x[4 * g + 0], w.x, l);
-                x[4 * g + 1] = __builtin_amdgcn_exp2f(x[4 * g + 1]); l = fmaf(x[4 * g + 1], w.y, l);
-                x[4 * g + 2] = __builtin_amdgcn_exp2f(x[4 * g + 2]); l = fmaf(x[4 * g + 2], w.z, l);
-                x[4 * g + 3] = __builtin_amdgcn_exp2f(x[4 * g + 3]); l = fmaf(x[4 * g + 3], w.w, l);
+                for (int i = 0; i < 16; ++i) { x[i] = __builtin_amdgcn_exp2f(x[i]); psum += x[i]; }
+                l = fmaf(psum, wp[0], l);
+            } else {
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const float4 w = *reinterpret_cast<const float4 *>(wp + 4 * g);
+                    x[4 * g + 0] = __builtin_amdgcn_exp2f(x[4 * g + 0]); l = fmaf(x[4 * g + 0], w.x, l);
+                    x[4 * g + 1] = __builtin_amdgcn_exp2f(x[4 * g + 1]); l = fmaf(x[4 * g + 1], w.y, l);
+                    x[4 * g + 2] = __builtin_amdgcn_exp2f(x[4 * g + 2]); l = fmaf(x[4 * g + 2], w.z, l);
+                    x[4 * g + 3] = __builtin_amdgcn_exp2f(x[4 * g + 3]); l = fmaf(x[4 * g + 3], w.w, l);
+                }
             }
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
@@ -515,7 +525,8 @@ extern "C" int s2_attn_global_fwd(const s2_grid_t *g, int batch, int heads, int 
     launch_transpose(v, workspace, g->dev_w_tok, nbh, N, Npad, st);
     S2TraceScope tr("global_fwd", double(nbh) * N * N, st);
     const int nqb = (N + 127) / 128, nunits = nbh * nqb;
-    hipLaunchKernelGGL(global_fwd, dim3(8 * ((nunits + 7) / 8)), dim3(256), 0, st, static_cast<const bf16raw *>(q),
+    auto kern = g->nlon_in % 32 == 0 ? global_fwd<true> : global_fwd<false>;
+    hipLaunchKernelGGL(kern, dim3(8 * ((nunits + 7) / 8)), dim3(256), 0, st, static_cast<const bf16raw *>(q),
                        static_cast<const bf16raw *>(k), static_cast<const bf16raw *>(workspace), g->dev_w_tok,
                        static_cast<bf16raw *>(out), lse, N, Npad, nqb, nunits, scale * kLog2e, g->dt.ln_omega_ref);
     S2_HIP_CHECK(hipGetLastError());
