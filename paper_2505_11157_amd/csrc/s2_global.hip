@@ -77,7 +77,8 @@ transpose_tokens(const bf16raw *__restrict__ in, bf16raw *__restrict__ out, cons
 
 // Per-token backward constants, padded to Npad tokens per slice so that the kernels can read them
 // with 16-byte loads: L2[bh][i] = (lse_i - ln max omega) * log2(e) (+inf on the padding:
-// p = exp2(-inf) = 0) and D[bh][i] = dout_i . out_i (0 on the padding).
+// p = exp2(-inf) = 0) and D[bh][i] = -(dout_i . out_i) (0 on the padding): the backward kernels start the
+// accumulation of dout.v from -D, so that the matrix core delivers dout_i.v_j - D_i directly.
 __global__ void __launch_bounds__(256)
 rowstats(const bf16raw *__restrict__ go, const bf16raw *__restrict__ o, const float *__restrict__ lse,
          float *__restrict__ L2, float *__restrict__ D, int N, int Npad, float ln_wref)
@@ -96,7 +97,7 @@ rowstats(const bf16raw *__restrict__ go, const bf16raw *__restrict__ o, const fl
         l2 = (lse[t] - ln_wref) * kLog2e;
     }
     L2[size_t(bh) * Npad + i] = l2;
-    D[size_t(bh) * Npad + i] = acc;
+    D[size_t(bh) * Npad + i] = -acc;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -340,27 +341,30 @@ global_bwd_dkdv(const bf16raw *__restrict__ q, const bf16raw *__restrict__ k, co
         if (st + 1 < nst) request(nxt, st + 1);
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
-            f32x16 s = {0}, dp = {0};
+            const float *Lp = reinterpret_cast<const float *>(cur + 4 * kTileBytes) + 32 * h + 16 * hl;
+            // dP starts from -D_i (the 16 queries this lane's registers stand for)
+            f32x16 s = {0}, dp;
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const float4 Dr = *reinterpret_cast<const float4 *>(Lp + 64 + 4 * g);
+                dp[4 * g + 0] = Dr.x; dp[4 * g + 1] = Dr.y; dp[4 * g + 2] = Dr.z; dp[4 * g + 3] = Dr.w;
+            }
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) {
                 s = mfma(row_operand(cur, col, hl, h, ks), kop[ks], s);
                 dp = mfma(row_operand(cur + kTileBytes, col, hl, h, ks), vop[ks], dp);
             }
-            const float *Lp = reinterpret_cast<const float *>(cur + 4 * kTileBytes) + 32 * h + 16 * hl;
             float p[16], ds[16];
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 const float4 Lr = *reinterpret_cast<const float4 *>(Lp + 4 * g);
-                const float4 Dr = *reinterpret_cast<const float4 *>(Lp + 64 + 4 * g);
                 p[4 * g + 0] = __builtin_amdgcn_exp2f(fmaf(s[4 * g + 0], c2, -Lr.x));
                 p[4 * g + 1] = __builtin_amdgcn_exp2f(fmaf(s[4 * g + 1], c2, -Lr.y));
                 p[4 * g + 2] = __builtin_amdgcn_exp2f(fmaf(s[4 * g + 2], c2, -Lr.z));
                 p[4 * g + 3] = __builtin_amdgcn_exp2f(fmaf(s[4 * g + 3], c2, -Lr.w));
-                ds[4 * g + 0] = p[4 * g + 0] * (dp[4 * g + 0] - Dr.x);
-                ds[4 * g + 1] = p[4 * g + 1] * (dp[4 * g + 1] - Dr.y);
-                ds[4 * g + 2] = p[4 * g + 2] * (dp[4 * g + 2] - Dr.z);
-                ds[4 * g + 3] = p[4 * g + 3] * (dp[4 * g + 3] - Dr.w);
             }
+#pragma unroll
+            for (int i = 0; i < 16; ++i) ds[i] = p[i] * dp[i];
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
                 const bf16x8 pb = pack8(p + 8 * j), sb = pack8(ds + 8 * j);
@@ -422,7 +426,9 @@ global_bwd_dq(const bf16raw *__restrict__ q, const bf16raw *__restrict__ k, cons
         for (int ks = 0; ks < 4; ++ks) { qop[ks] = ld8(q + row + 16 * ks); gop[ks] = ld8(go + row + 16 * ks); }
     }
     const float Lq = L2[size_t(bh) * Npad + min(qi, N - 1)], Dq = Dv[size_t(bh) * Npad + min(qi, N - 1)];
-    f32x16 dq0 = {0}, dq1 = {0};
+    f32x16 dq0 = {0}, dq1 = {0}, nd;     // nd: -D_q in every register, the start value of dout.v
+#pragma unroll
+    for (int i = 0; i < 16; ++i) nd[i] = Dq;
     const bf16raw *kb = k + size_t(bh) * N * kD, *vb = v + size_t(bh) * N * kD;
     const bf16raw *ktb = ktw + size_t(bh) * kD * Npad;
     const int nst = Npad >> 6;
@@ -436,7 +442,7 @@ global_bwd_dq(const bf16raw *__restrict__ q, const bf16raw *__restrict__ k, cons
         if (st + 1 < nst) request(nxt, st + 1);
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
-            f32x16 s = {0}, dp = {0};
+            f32x16 s = {0}, dp = nd;
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) {
                 s = mfma(row_operand(cur, col, hl, h, ks), qop[ks], s);
@@ -444,7 +450,7 @@ global_bwd_dq(const bf16raw *__restrict__ q, const bf16raw *__restrict__ k, cons
             }
             float ds[16];
 #pragma unroll
-            for (int i = 0; i < 16; ++i) ds[i] = __builtin_amdgcn_exp2f(fmaf(s[i], c2, -Lq)) * (dp[i] - Dq);
+            for (int i = 0; i < 16; ++i) ds[i] = __builtin_amdgcn_exp2f(fmaf(s[i], c2, -Lq)) * dp[i];
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
                 const bf16x8 sb = pack8(ds + 8 * j);

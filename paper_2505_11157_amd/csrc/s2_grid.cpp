@@ -124,11 +124,8 @@ static int upload_tables(s2_grid *g)
     for (int h = 0; h < g->nlat_in; ++h) l2w[h] = float(g->omega_in[h] / omega_ref);
     const int ntok = g->nlat_in * g->nlon_in;
     g->npad_tok = (ntok + 63) / 64 * 64;
-    std::vector<float> bias(g->npad_tok, -INFINITY), wtok(g->npad_tok, 0.f);
-    for (int j = 0; j < ntok; ++j) {
-        bias[j] = float(std::log2(g->omega_in[j / g->nlon_in]));
-        wtok[j] = l2w[j / g->nlon_in];
-    }
+    std::vector<float> wtok(g->npad_tok, 0.f);
+    for (int j = 0; j < ntok; ++j) wtok[j] = l2w[j / g->nlon_in];
     const unsigned zero_word = 0u;
     // one blob: floats first, then the int tables, each 256-byte aligned
     struct Part { const void *src; size_t bytes; size_t off; };
@@ -142,11 +139,10 @@ static int upload_tables(s2_grid *g)
         {g->tcnt.data(), g->tcnt.size() * sizeof(int), 0},
         {g->row_order.data(), g->row_order.size() * sizeof(int), 0},
         {g->trow_order.data(), g->trow_order.size() * sizeof(int), 0},
-        {bias.data(), bias.size() * sizeof(float), 0},
+        {wtok.data(), wtok.size() * sizeof(float), 0},
         {g->st_cum.data(), g->st_cum.size() * sizeof(int), 0},
         {g->tst_cum.data(), g->tst_cum.size() * sizeof(int), 0},
         {&zero_word, sizeof(unsigned), 0},
-        {wtok.data(), wtok.size() * sizeof(float), 0},
     };
     size_t total = 0;
     for (auto &p : parts) {
@@ -173,11 +169,10 @@ static int upload_tables(s2_grid *g)
     t.tcnt = reinterpret_cast<const int *>(base + parts[6].off);
     t.row_order = reinterpret_cast<const int *>(base + parts[7].off);
     t.trow_order = reinterpret_cast<const int *>(base + parts[8].off);
-    g->dev_bias_tok = reinterpret_cast<const float *>(base + parts[9].off);
+    g->dev_w_tok = reinterpret_cast<const float *>(base + parts[9].off);
     t.st_cum = reinterpret_cast<const int *>(base + parts[10].off);
     t.tst_cum = reinterpret_cast<const int *>(base + parts[11].off);
     t.dev_flags = reinterpret_cast<unsigned *>(base + parts[12].off);
-    g->dev_w_tok = reinterpret_cast<const float *>(base + parts[13].off);
     t.band_max = g->band_max;
     t.tband_max = g->tband_max;
     t.nlat_in = g->nlat_in; t.nlon_in = g->nlon_in;

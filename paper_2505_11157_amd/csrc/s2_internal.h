@@ -62,10 +62,8 @@ struct s2_grid {
     bool on_device = false;
     int device = -1;
     void *dev_blob = nullptr;
-    // global attention, per input token, padded to npad_tok (a multiple of 64): log2(omega) with -inf on
-    // the padding, and omega / max omega with 0 on the padding
+    // global attention: omega / max omega per input token, 0 on the padding up to npad_tok (a multiple of 64)
     int npad_tok = 0;
-    const float *dev_bias_tok = nullptr;
     const float *dev_w_tok = nullptr;
     S2DeviceTables dt{};
 };
