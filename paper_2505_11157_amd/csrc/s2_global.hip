@@ -54,50 +54,84 @@ __device__ __forceinline__ bf16x8 pack8(const float *x)
 // key (or query) index of tile row r under the permutation described above
 __device__ __forceinline__ int perm_row(int r) { return 16 * ((r >> 2) & 1) + 4 * (r >> 3) + (r & 3); }
 
-// in [bh][N][64] -> out [bh][64][Npad], zero for tokens >= N; with `wtok` every token is multiplied by
-// its weight first (rounded to bf16 once, after the product)
-__global__ void __launch_bounds__(256)
-transpose_tokens(const bf16raw *__restrict__ in, bf16raw *__restrict__ out, const float *__restrict__ wtok, int N,
-                 int Npad)
-{
-    __shared__ bf16raw tile[64][kD + 2];
-    const int bh = blockIdx.y, t0 = blockIdx.x * 64;
-    for (int i = threadIdx.x; i < 64 * kD; i += 256) {
-        const int tok = i / kD, c = i % kD;
-        bf16raw x = (t0 + tok < N) ? in[(size_t(bh) * N + t0 + tok) * kD + c] : bf16raw(0);
-        if (wtok) x = __builtin_bit_cast(bf16raw, (__bf16)(float(__builtin_bit_cast(__bf16, x)) * wtok[t0 + tok]));
-        tile[tok][c] = x;
-    }
-    __syncthreads();
-    for (int i = threadIdx.x; i < 64 * kD; i += 256) {
-        const int c = i / 64, tok = i % 64;
-        if (t0 + tok < Npad) out[(size_t(bh) * kD + c) * Npad + t0 + tok] = tile[tok][c];
-    }
-}
+// Preparation pass.  One launch handles up to three operands (blockIdx.z): each is transposed from
+// [bh][N][64] to [bh][64][Npad] (zero for tokens >= N), optionally with every token multiplied by its
+// weight first (rounded to bf16 once, after the product).  The block that transposes `stat_go` (dout) also
+// writes the per-token backward constants, padded to Npad tokens per slice:
+// L2[bh][i] = (lse_i - ln max omega) * log2(e) (+inf on the padding: p = exp2(-inf) = 0) and
+// D[bh][i] = -(dout_i . out_i) (0 on the padding): the backward kernels start the accumulation of dout.v
+// from -D, so that the matrix core delivers dout_i.v_j - D_i directly.
+// A block moves 64 tokens: four threads per token read 32 bytes each (coalesced rows), the tile is turned in
+// LDS, and four threads per channel write 32 bytes each.
+struct PrepOp {
+    const bf16raw *in;
+    bf16raw *out;
+    const float *wtok;      // weights to multiply with, or null
+};
+struct PrepArgs {
+    PrepOp op[3];
+    int stat_op;            // index of the operand that is dout (-1: no statistics)
+    const bf16raw *o;       // forward output
+    const float *lse;
+    float *L2, *D;
+    float ln_wref;
+};
 
-// Per-token backward constants, padded to Npad tokens per slice so that the kernels can read them
-// with 16-byte loads: L2[bh][i] = (lse_i - ln max omega) * log2(e) (+inf on the padding:
-// p = exp2(-inf) = 0) and D[bh][i] = -(dout_i . out_i) (0 on the padding): the backward kernels start the
-// accumulation of dout.v from -D, so that the matrix core delivers dout_i.v_j - D_i directly.
 __global__ void __launch_bounds__(256)
-rowstats(const bf16raw *__restrict__ go, const bf16raw *__restrict__ o, const float *__restrict__ lse,
-         float *__restrict__ L2, float *__restrict__ D, int N, int Npad, float ln_wref)
+prepare_operands(PrepArgs a, int N, int Npad)
 {
-    const int bh = blockIdx.y, i = blockIdx.x * 256 + threadIdx.x;
-    if (i >= Npad) return;
-    float acc = 0.f, l2 = INFINITY;
-    if (i < N) {
-        const size_t t = size_t(bh) * N + i;
+    constexpr int kP = 72;   // tile pitch in elements: rows start 16-byte aligned, 36 banks apart
+    __shared__ __attribute__((aligned(16))) bf16raw tile[kD][kP];
+    const PrepOp op = a.op[blockIdx.z];
+    const int bh = blockIdx.y, t0 = blockIdx.x * 64;
+    const int tid = threadIdx.x, tok = tid >> 2, part = tid & 3;
+    const int token = t0 + tok;
+    bf16x8 x[2];
 #pragma unroll
-        for (int c = 0; c < kD; c += 8) {
-            const bf16x8 x = ld8(go + t * kD + c), y = ld8(o + t * kD + c);
+    for (int j = 0; j < 2; ++j)
 #pragma unroll
-            for (int j = 0; j < 8; ++j) acc = fmaf(float(x[j]), float(y[j]), acc);
-        }
-        l2 = (lse[t] - ln_wref) * kLog2e;
+        for (int u = 0; u < 8; ++u) x[j][u] = (__bf16)0.f;
+    if (token < N) {
+        const bf16raw *src = op.in + (size_t(bh) * N + token) * kD + 16 * part;
+        x[0] = ld8(src);
+        x[1] = ld8(src + 8);
     }
-    L2[size_t(bh) * Npad + i] = l2;
-    D[size_t(bh) * Npad + i] = -acc;
+    if (int(blockIdx.z) == a.stat_op) {
+        float acc = 0.f;
+        if (token < N) {
+            const bf16raw *po = a.o + (size_t(bh) * N + token) * kD + 16 * part;
+            const bf16x8 y0 = ld8(po), y1 = ld8(po + 8);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) acc = fmaf(float(x[0][u]), float(y0[u]), fmaf(float(x[1][u]), float(y1[u]), acc));
+        }
+        acc += __shfl_xor(acc, 1);
+        acc += __shfl_xor(acc, 2);
+        if (part == 0 && token < Npad) {
+            a.L2[size_t(bh) * Npad + token] = token < N ? (a.lse[size_t(bh) * N + token] - a.ln_wref) * kLog2e : INFINITY;
+            a.D[size_t(bh) * Npad + token] = -acc;
+        }
+    }
+    if (op.wtok && token < N) {
+        const float w = op.wtok[token];
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int u = 0; u < 8; ++u) x[j][u] = (__bf16)(float(x[j][u]) * w);
+    }
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const __bf16 e = x[j][u];      // (a bit_cast applied to the vector element itself reads element 0)
+            tile[16 * part + 8 * j + u][tok] = __builtin_bit_cast(bf16raw, e);
+        }
+    __syncthreads();
+    const int ch = tid >> 2;
+    if (t0 + 16 * part < Npad) {       // Npad is a multiple of 64: a block's 64 tokens are all inside or all outside
+        bf16raw *dst = op.out + (size_t(bh) * kD + ch) * Npad + t0 + 16 * part;
+        *reinterpret_cast<uint4 *>(dst) = *reinterpret_cast<const uint4 *>(&tile[ch][16 * part]);
+        *reinterpret_cast<uint4 *>(dst + 8) = *reinterpret_cast<const uint4 *>(&tile[ch][16 * part + 8]);
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -187,7 +221,7 @@ __device__ __forceinline__ bool xcd_unit(int nunits, int &unit)
 
 // Forward.  A workgroup owns 128 queries of one slice (one 32-query MFMA tile per wavefront) and streams
 // the keys in stages of 64.  omega enters as a factor, not as a bias: V^T arrives premultiplied by
-// w_j = omega_j / max omega (transpose_tokens does that), the running sum is l_i = sum_j w_j 2^(x_ij - m_i)
+// w_j = omega_j / max omega (prepare_operands does that), the running sum is l_i = sum_j w_j 2^(x_ij - m_i)
 // with x = log2(e) scale q.k, and the reference m_i follows the bare logits (it moves only when a logit
 // exceeds it by more than 2^8).  lse_i = ln 2 (m_i + log2 l_i) + ln max omega.
 // UNIFORM_W: the longitude count is a multiple of 32, so a 32-key tile never straddles two latitudes.
@@ -296,7 +330,7 @@ global_fwd(const bf16raw *__restrict__ q, const bf16raw *__restrict__ k, const b
 // L_i = log2(e) (lse_i - ln max omega):  p_ij = w_j pt_ij,  pt_ij = 2^(log2(e) scale q_i.k_j - L_i),
 // dS_ij = p_ij (dout_i.v_j - D_i).  The factor w_j never enters the inner loops: the key-side kernel
 // multiplies its finished sums by w_j (the lane's own key), the query-side kernel contracts with
-// K^T premultiplied by w_j (transpose_tokens).
+// K^T premultiplied by w_j (prepare_operands).
 //
 // Key side: a workgroup owns 128 keys (one 32-key tile per wavefront) and streams the queries in stages
 // of 64: Q and dout token-major (for S = Q K^T and dP = dout V^T, which land with lane = key,
@@ -494,10 +528,9 @@ int check_global(const s2_grid_t *g, int batch, int heads, int d, int dtype)
 
 size_t transposed_bytes(const s2_grid_t *g, int nbh) { return size_t(nbh) * kD * g->npad_tok * sizeof(bf16raw); }
 
-void launch_transpose(const void *in, void *out, const float *wtok, int nbh, int N, int Npad, hipStream_t st)
+void launch_prepare(const PrepArgs &a, int nops, int nbh, int N, int Npad, hipStream_t st)
 {
-    hipLaunchKernelGGL(transpose_tokens, dim3((Npad + 63) / 64, nbh), dim3(256), 0, st,
-                       static_cast<const bf16raw *>(in), static_cast<bf16raw *>(out), wtok, N, Npad);
+    hipLaunchKernelGGL(prepare_operands, dim3(Npad / 64, nbh, nops), dim3(256), 0, st, a, N, Npad);
 }
 
 }  // namespace
@@ -528,7 +561,10 @@ extern "C" int s2_attn_global_fwd(const s2_grid_t *g, int batch, int heads, int 
         return s2_fail(S2_ERR_WORKSPACE, "workspace missing or smaller than s2_attn_global_fwd_workspace_bytes()");
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const int nbh = batch * heads, N = g->nlat_in * g->nlon_in, Npad = g->npad_tok;
-    launch_transpose(v, workspace, g->dev_w_tok, nbh, N, Npad, st);
+    PrepArgs pa{};
+    pa.op[0] = {static_cast<const bf16raw *>(v), static_cast<bf16raw *>(workspace), g->dev_w_tok};
+    pa.stat_op = -1;
+    launch_prepare(pa, 1, nbh, N, Npad, st);
     S2TraceScope tr("global_fwd", double(nbh) * N * N, st);
     const int nqb = (N + 127) / 128, nunits = nbh * nqb;
     auto kern = g->nlon_in % 32 == 0 ? global_fwd<true> : global_fwd<false>;
@@ -558,11 +594,17 @@ extern "C" int s2_attn_global_bwd(const s2_grid_t *g, int batch, int heads, int 
     bf16raw *qt = reinterpret_cast<bf16raw *>(ws), *kt = reinterpret_cast<bf16raw *>(ws + tb),
             *got = reinterpret_cast<bf16raw *>(ws + 2 * tb);
     float *L2 = reinterpret_cast<float *>(ws + 3 * tb), *Dv = reinterpret_cast<float *>(ws + 3 * tb + sb);
-    launch_transpose(q, qt, nullptr, nbh, N, Npad, st);
-    launch_transpose(k, kt, g->dev_w_tok, nbh, N, Npad, st);
-    launch_transpose(dout, got, nullptr, nbh, N, Npad, st);
-    hipLaunchKernelGGL(rowstats, dim3((Npad + 255) / 256, nbh), dim3(256), 0, st, static_cast<const bf16raw *>(dout),
-                       static_cast<const bf16raw *>(out), lse, L2, Dv, N, Npad, g->dt.ln_omega_ref);
+    PrepArgs pa{};
+    pa.op[0] = {static_cast<const bf16raw *>(q), qt, nullptr};
+    pa.op[1] = {static_cast<const bf16raw *>(k), kt, g->dev_w_tok};
+    pa.op[2] = {static_cast<const bf16raw *>(dout), got, nullptr};
+    pa.stat_op = 2;
+    pa.o = static_cast<const bf16raw *>(out);
+    pa.lse = lse;
+    pa.L2 = L2;
+    pa.D = Dv;
+    pa.ln_wref = g->dt.ln_omega_ref;
+    launch_prepare(pa, 3, nbh, N, Npad, st);
     const float c2 = scale * kLog2e;
     const int nblk = (N + 127) / 128, nunits = nbh * nblk;
     const dim3 grid(8 * ((nunits + 7) / 8));

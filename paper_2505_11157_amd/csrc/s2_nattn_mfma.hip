@@ -39,6 +39,21 @@ __device__ __forceinline__ f32x16 mfma(float a, float b, f32x16 c)
     return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
 }
 
+// Read of a grid table entry through the scalar cache.  The tables are never written by a kernel, but the
+// compiler cannot know that once the kernel has stored results, and would use vector loads whose
+// completion wait (vmcnt) also waits for the LDS-direct copies of the next tile that were just requested.
+__device__ __forceinline__ int table_i(const int *p, int idx)
+{
+    int v;
+    const int *a = p + idx;
+    asm("s_load_dword %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=s"(v) : "s"(a));
+    return v;
+}
+__device__ __forceinline__ float table_f(const float *p, int idx)
+{
+    return __builtin_bit_cast(float, table_i(reinterpret_cast<const int *>(p), idx));
+}
+
 __device__ __forceinline__ int wrapn(int x, int n)
 {
     x = x < 0 ? x + n : x;
@@ -113,10 +128,10 @@ nattn_fwd_mfma(S2DeviceTables t, int nbh, int nrows, float qscale, const float *
                 stage_tile(kb, vb, si, x2 + kTileCols * sub, nlon,
                            smem + (((it + 1) & 1) * NSUB + sub) * kTileFloats, wave, nwaves, lane);
         }
-        const int c = t.cnt[h * t.band_max + b];
+        const int c = table_i(t.cnt, h * t.band_max + b);
         const bool full = c == nlon;
         const int lo = full ? 0 : -((c - 1) >> 1);
-        const float wq = t.omega_rel[hp];
+        const float wq = table_f(t.omega_rel, hp);
 #pragma unroll 1
         for (int sub = 0; sub < NSUB; ++sub) {
         const int x0 = xg + kTileCols * sub;
@@ -282,10 +297,10 @@ nattn_bwd_dq_mfma(S2DeviceTables t, int nbh, int nrows, float scale, const float
                 stage_tile_b(kb, vb, si, x2 + kTileCols * sub, nlon, smem + (((it + 1) & 1) * NSUB + sub) * kTileB, wave,
                              nwaves, lane);
         }
-        const int c = t.cnt[h * t.band_max + b];
+        const int c = table_i(t.cnt, h * t.band_max + b);
         const bool full = c == nlon;
         const int lo = full ? 0 : -((c - 1) >> 1);
-        const float wq = t.omega_rel[hp];
+        const float wq = table_f(t.omega_rel, hp);
 #pragma unroll 1
         for (int sub = 0; sub < NSUB; ++sub) {
         const int x0 = xg + kTileCols * sub;
@@ -404,7 +419,7 @@ nattn_bwd_dkdv_mfma(S2DeviceTables t, int nbh, int nrows, float scale, const flo
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
         if (it + 1 < total) issue(it + 1, smem + ((it + 1) & 1) * NSUB * kTileC);
-        const int c = t.tcnt[hp * t.tband_max + b];
+        const int c = table_i(t.tcnt, hp * t.tband_max + b);
         const bool full = c == nlon;
         const int lo = full ? 0 : -((c - 1) >> 1);
 #pragma unroll 1
