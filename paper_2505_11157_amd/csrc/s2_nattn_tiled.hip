@@ -37,13 +37,36 @@ constexpr int kCG = 4;       // channels per half staged together
 // column, any alignment, wrap handled per lane).  The last 8 columns of the 8
 // rows are one ordinary load (lane = row * 8 + column) written to LDS when the
 // stage is consumed: LDS-direct loads with a partial exec mask proved very slow.
+//
+// 2:1 grids (PS = 2): runs start at a multiple of four input columns (the up to three offsets in front of
+// the arc get a logit of -inf), so a window never has a 16-byte piece astride the longitude seam and one
+// global_load_lds_dwordx4 (lane = four columns) copies the 256 columns of a row: a quarter of the copy
+// instructions, and the copy path moves 16-byte pieces about 1.5 times faster than dwords.
 template <int PS>
 struct Geo {
     static constexpr int PITCH = kSeg * PS + 8;
-    static constexpr int NFULL = 2 * PS;                      // full 64-column loads per row
+    static constexpr bool ALIGNED = PS == 2;                  // windows start at a multiple of 4 columns
+    static constexpr int LCOLS = ALIGNED ? 4 : 1;             // columns per lane and copy instruction
+    static constexpr int NFULL = kSeg * PS / (64 * LCOLS);    // full 64-lane copies per row
     static constexpr int NLOAD = 2 * kCG * NFULL + 1;         // vector-memory loads per stage
     static constexpr int TILE = 2 * kCG * PITCH;              // floats per buffer
 };
+
+// Runs of one arc of c offsets starting at offset lo.  Unaligned windows: nchunk near-equal runs of at most 9.
+// Aligned windows: the first run starts at the multiple of 4 at or below lo (`lead` masked offsets), runs of
+// 8, the last one of up to 9.
+template <int PS>
+__device__ __forceinline__ int num_runs(int c, int lo)
+{
+    if constexpr (Geo<PS>::ALIGNED) {
+        const int span = c + (lo - (lo & ~3));
+        const int n = (span + 6) >> 3;
+        return n < 1 ? 1 : n;
+    } else {
+        return (c + kNTMax - 1) / kNTMax;
+    }
+}
+__device__ __forceinline__ int arc_lo(int c, int nlon_in) { return c == nlon_in ? 0 : -((c - 1) >> 1); }
 
 typedef __attribute__((address_space(1))) const void *gptr_t;
 typedef __attribute__((address_space(3))) void *lptr_t;
@@ -63,12 +86,12 @@ __device__ __forceinline__ void stage_offsets(int x0, int xt, int nlon_in, unsig
 {
 #pragma unroll
     for (int a = 0; a < Geo<PS>::NFULL; ++a) {
-        int x = x0 + 64 * a;
+        int x = x0 + 64 * Geo<PS>::LCOLS * a;
         x = x >= nlon_in ? x - nlon_in : x;
         x = x >= nlon_in ? x - nlon_in : x;
         voff[a] = 4u * unsigned(x);
     }
-    int x = xt + 64 * Geo<PS>::NFULL;
+    int x = xt + kSeg * PS;
     x = x >= nlon_in ? x - nlon_in : x;
     x = x >= nlon_in ? x - nlon_in : x;
     voff[Geo<PS>::NFULL] = trow + 4u * unsigned(x);
@@ -95,7 +118,10 @@ __device__ __forceinline__ float stage_issue(const float *chan0, size_t si, unsi
     for (int r = 0; r < 2 * kCG; ++r) {
 #pragma unroll
         for (int a = 0; a < G::NFULL; ++a)
-            __builtin_amdgcn_global_load_lds((gptr_t)(rb + voff[a]), (lptr_t)(buf + r * G::PITCH + 64 * a), 4, 0, 0);
+            if constexpr (G::LCOLS == 4)
+                __builtin_amdgcn_global_load_lds((gptr_t)(rb + voff[a]), (lptr_t)(buf + r * G::PITCH + 256 * a), 16, 0, 0);
+            else
+                __builtin_amdgcn_global_load_lds((gptr_t)(rb + voff[a]), (lptr_t)(buf + r * G::PITCH + 64 * a), 4, 0, 0);
         rb += (r == kCG - 1) ? rs * (D / 2 - kCG + 1) : rs;
     }
     return tail;
@@ -125,8 +151,9 @@ __device__ __forceinline__ void read_strip(const float *buf, int sbase, int cc, 
 template <int D, int PS, int NT>
 __device__ __forceinline__ void run_chunk(float *buf0, float *buf1, const float *__restrict__ kb,
                                           const float *__restrict__ vb, size_t si, int x0, int xt, unsigned trow,
-                                          int taddr, int nlon_in, int sbase, float wq, const float (&q)[4][D / 2],
-                                          float (&acc)[4][D / 2], float (&mref)[4], float (&lsum)[4])
+                                          int taddr, int nlon_in, int sbase, float wq, int lead,
+                                          const float (&q)[4][D / 2], float (&acc)[4][D / 2], float (&mref)[4],
+                                          float (&lsum)[4])
 {
     using G = Geo<PS>;
     constexpr int DH = D / 2, NG = DH / kCG;
@@ -170,6 +197,7 @@ __device__ __forceinline__ void run_chunk(float *buf0, float *buf1, const float 
 #pragma unroll
         for (int tt = 0; tt < NT; ++tt) {
             s[r][tt] += dpp_swap_pair(s[r][tt]);
+            if (G::ALIGNED && tt < 3) s[r][tt] = tt < lead ? -INFINITY : s[r][tt];   // offsets in front of the arc
             cmax[r] = fmaxf(cmax[r], s[r][tt]);
         }
         need |= cmax[r] > mref[r] + 8.f;
@@ -294,7 +322,10 @@ nattn_fwd_tiled(S2DeviceTables t, int nbh, int first_row, float qscale, const fl
     const int nb = t.band_n[h], hp0 = t.band_lo[h];
     // this wavefront's share of the runs of latitude h
     int nrun = 0;
-    for (int b = 0; b < nb; ++b) nrun += (t.cnt[h * t.band_max + b] + kNTMax - 1) / kNTMax;
+    for (int b = 0; b < nb; ++b) {
+        const int cb = t.cnt[h * t.band_max + b];
+        nrun += num_runs<PS>(cb, arc_lo(cb, t.nlon_in));
+    }
     const int run_lo = part * nrun / P, run_hi = (part + 1) * nrun / P;
     int run = 0;
     if (wave_active) {
@@ -308,24 +339,27 @@ nattn_fwd_tiled(S2DeviceTables t, int nbh, int first_row, float qscale, const fl
             const int b = bb + rot < nb ? bb + rot : bb + rot - nb;
             const int hp = hp0 + b;
             const int c = t.cnt[h * t.band_max + b];
-            const int nchunk = (c + kNTMax - 1) / kNTMax;
+            const int lo = arc_lo(c, t.nlon_in);
+            const int nchunk = num_runs<PS>(c, lo);
             if (run + nchunk <= run_lo || run >= run_hi) { run += nchunk; continue; }
-            const int lo = (c == t.nlon_in) ? 0 : -((c - 1) >> 1);
             const float wq = t.omega_rel[hp];
             const float *kb = k + size_t(bh) * D * si + size_t(hp) * t.nlon_in;
             const float *vb = v + size_t(bh) * D * si + size_t(hp) * t.nlon_in;
             const int base = c / nchunk, rem = c - base * nchunk;
-            int t0 = 0;
+            const int lead0 = G::ALIGNED ? lo - (lo & ~3) : 0, span = c + lead0;
+            int t0 = -lead0;
             for (int ci = 0; ci < nchunk; ++ci, ++run) {
-                const int nt = base + (ci < rem ? 1 : 0);
+                const int nt = G::ALIGNED ? (ci == nchunk - 1 ? span - 8 * ci : 8) : base + (ci < rem ? 1 : 0);
+                const int lead = ci == 0 ? lead0 : 0;
                 if (run >= run_lo && run < run_hi) {
-                    int xw = seg * kSeg * PS + lo + t0 + t.nlon_in;      // first window column
+                    int xw = seg * kSeg * PS + lo + t0 + 2 * t.nlon_in;      // first window column
                     xw = xw >= t.nlon_in ? xw - t.nlon_in : xw;
                     xw = xw >= t.nlon_in ? xw - t.nlon_in : xw;
-                    int x0 = xw + lane, xt = xw + (lane & 7);
+                    xw = xw >= t.nlon_in ? xw - t.nlon_in : xw;
+                    int x0 = xw + G::LCOLS * lane, xt = xw + (lane & 7);
                     x0 = x0 >= t.nlon_in ? x0 - t.nlon_in : x0;
                     xt = xt >= t.nlon_in ? xt - t.nlon_in : xt;
-#define S2_RUN(N) case N: run_chunk<D, PS, N>(buf0, buf1, kb, vb, si, x0, xt, trow, taddr, t.nlon_in, sbase, wq, qr, acc, mref, lsum); break;
+#define S2_RUN(N) case N: run_chunk<D, PS, N>(buf0, buf1, kb, vb, si, x0, xt, trow, taddr, t.nlon_in, sbase, wq, lead, qr, acc, mref, lsum); break;
                     switch (nt) {
                         S2_RUN(1) S2_RUN(2) S2_RUN(3) S2_RUN(4) S2_RUN(5) S2_RUN(6)
                         S2_RUN(7) S2_RUN(8) S2_RUN(9)
