@@ -34,7 +34,10 @@ typedef struct s2_grid s2_grid_t; /* opaque; immutable after init; usable from a
 /* Grid types (Sec. 3.3: equiangular and Gaussian grids). */
 enum {
     S2_GRID_EQUIANGULAR = 0,   /* colat_h = pi*h/(nlat-1), both poles, Clenshaw-Curtis weights */
-    S2_GRID_LEGENDRE_GAUSS = 1 /* Gauss-Legendre nodes in cos(colat), north first */
+    S2_GRID_LEGENDRE_GAUSS = 1, /* Gauss-Legendre nodes in cos(colat), north first */
+    S2_GRID_EQUIANGULAR_TRAPEZOID = 2 /* the grid as printed in App. A.1: colat_i = pi*i/nlat, i < nlat (north pole
+                                         only), weights 2 pi^2 / (nlat nlon) sin(colat_i): zero at the pole, whose
+                                         points then never contribute; sums to 4 pi only approximately */
 };
 
 enum { S2_F32 = 0, S2_BF16 = 1 };

@@ -5,6 +5,7 @@ cpu_baseline leg of the benchmark.  The product package never imports this.
 """
 from .s2_oracle import (  # noqa: F401
     EQUIANGULAR,
+    EQUIANGULAR_TRAPEZOID,
     LEGENDRE_GAUSS,
     build,
     geodesic,

@@ -21,7 +21,8 @@
  *
  * Readings taken where the paper is silent:
  *   - equiangular grid = both poles, colat_h = pi*h/(nlat-1), Clenshaw-Curtis
- *     latitude weights (strictly positive, exact sum);
+ *     latitude weights (strictly positive, exact sum); the grid of App. A.1 as
+ *     printed (no south pole, trapezoidal weights, zero at the pole) is a third type;
  *   - Gaussian grid = Legendre-Gauss nodes in cos(colat), north first;
  *   - omega[h'] = latitude weight * 2*pi/nlon_in (input grid);
  *   - a point belongs to the disk iff d <= theta_cutoff + 1e-9 rad (cutoffs
@@ -50,6 +51,7 @@
 
 #define S2O_EQUIANGULAR 0
 #define S2O_LEGENDRE_GAUSS 1
+#define S2O_EQUIANGULAR_TRAPEZOID 2
 #define S2O_TIE_TOL 1e-9
 
 static const double S2O_PI = 3.14159265358979323846264338327950288;
@@ -105,12 +107,27 @@ static void legendre_gauss(int nlat, double *colat, double *w)
     }
 }
 
-/* colat[nlat], wlat[nlat] (wlat sums to 2).  Returns 0, or -1 on bad input. */
+/* The equiangular grid the paper itself writes down (App. A.1): colat_i = pi*i/nlat for
+ * i = 0..nlat-1 (north pole included, south pole not) with the trapezoidal weights
+ * q_ij = 2 pi^2 / (nlat nlon) sin(colat_i), i.e. latitude weight (pi/nlat) sin(colat_i) times
+ * 2 pi / nlon.  The pole row has weight zero: its points never contribute (ln 0 = -inf in the
+ * logits); the weights sum to 4 pi only approximately. */
+static void equiangular_trapezoid(int nlat, double *colat, double *w)
+{
+    for (int i = 0; i < nlat; ++i) {
+        colat[i] = S2O_PI * (double)i / (double)nlat;
+        w[i] = S2O_PI / (double)nlat * sin(colat[i]);
+    }
+}
+
+/* colat[nlat], wlat[nlat] (wlat sums to 2, approximately for the trapezoid grid).
+ * Returns 0, or -1 on bad input. */
 int s2o_grid(int grid_type, int nlat, double *colat, double *wlat)
 {
     if (nlat < 2) return -1;
     if (grid_type == S2O_EQUIANGULAR) clenshaw_curtis(nlat, colat, wlat);
     else if (grid_type == S2O_LEGENDRE_GAUSS) legendre_gauss(nlat, colat, wlat);
+    else if (grid_type == S2O_EQUIANGULAR_TRAPEZOID) equiangular_trapezoid(nlat, colat, wlat);
     else return -1;
     return 0;
 }

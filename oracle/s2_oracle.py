@@ -12,6 +12,7 @@ import numpy as np
 
 EQUIANGULAR = 0
 LEGENDRE_GAUSS = 1
+EQUIANGULAR_TRAPEZOID = 2   # the grid exactly as App. A.1 prints it (no south pole, zero weight at the pole)
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "s2_oracle.c")

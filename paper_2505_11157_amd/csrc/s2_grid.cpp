@@ -91,10 +91,24 @@ double great_circle(double t1, double t2, double dphi)
     return 2.0 * std::atan2(std::sqrt(hav), std::sqrt(cohav));
 }
 
+// App. A.1 as printed: nlat equally spaced colatitudes starting at the north pole, the south pole left out,
+// trapezoidal rule in colatitude: latitude weight = spacing * sin(colat).
+void trapezoid_nodes(int nlat, std::vector<double> &colat, std::vector<double> &w)
+{
+    colat.resize(nlat);
+    w.resize(nlat);
+    const double spacing = kPi / nlat;
+    for (int h = 0; h < nlat; ++h) {
+        colat[h] = spacing * h;
+        w[h] = h == 0 ? 0.0 : spacing * std::sin(colat[h]);
+    }
+}
+
 int nodes(int grid_type, int nlat, std::vector<double> &colat, std::vector<double> &w)
 {
     if (grid_type == S2_GRID_EQUIANGULAR) clenshaw_curtis_nodes(nlat, colat, w);
     else if (grid_type == S2_GRID_LEGENDRE_GAUSS) gauss_legendre_nodes(nlat, colat, w);
+    else if (grid_type == S2_GRID_EQUIANGULAR_TRAPEZOID) trapezoid_nodes(nlat, colat, w);
     else return -1;
     return 0;
 }
@@ -187,7 +201,8 @@ extern "C" int s2_grid_init(int grid_type, int nlat_in, int nlon_in, int nlat_ou
 {
     if (!out_grid) return s2_fail(S2_ERR_INVALID_ARG, "out_grid is NULL");
     *out_grid = nullptr;
-    if (grid_type != S2_GRID_EQUIANGULAR && grid_type != S2_GRID_LEGENDRE_GAUSS)
+    if (grid_type != S2_GRID_EQUIANGULAR && grid_type != S2_GRID_LEGENDRE_GAUSS &&
+        grid_type != S2_GRID_EQUIANGULAR_TRAPEZOID)
         return s2_fail(S2_ERR_INVALID_ARG, "unknown grid_type");
     if (nlat_in < 2 || nlat_out < 2 || nlon_in < 1 || nlon_out < 1)
         return s2_fail(S2_ERR_INVALID_ARG, "need nlat >= 2 and nlon >= 1 on both grids");
@@ -268,11 +283,16 @@ extern "C" int s2_grid_init(int grid_type, int nlat_in, int nlon_in, int nlat_ou
     ok = ok && build_bands(nlat_in, nlat_out, [&](int hp, int h) { return cnt_full[size_t(h) * nlat_in + hp]; },
                            g->tband_lo, g->tband_n, g->tcnt, g->tband_max);
     if (!ok) { delete g; return s2_fail(S2_ERR_UNSUPPORTED, "internal: latitude band is not contiguous"); }
-    for (int h = 0; h < nlat_out; ++h)
-        if (g->band_n[h] == 0) {
+    for (int h = 0; h < nlat_out; ++h) {
+        // a neighborhood must hold at least one point of positive weight (the trapezoid grid has a zero-weight pole row)
+        bool positive = false;
+        for (int b = 0; b < g->band_n[h]; ++b) positive = positive || g->omega_in[g->band_lo[h] + b] > 0.0;
+        if (!positive) {
             delete g;
-            return s2_fail(S2_ERR_EMPTY_NEIGHBORHOOD, "an output point has no input point within theta_cutoff");
+            return s2_fail(S2_ERR_EMPTY_NEIGHBORHOOD,
+                           "an output point has no input point of positive weight within theta_cutoff");
         }
+    }
 
     // canonical CSR: ascending h'*nlon_in + w', w' in [0, nlon_in)
     g->row_ptr.assign(nlat_out + 1, 0);

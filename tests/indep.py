@@ -11,6 +11,7 @@ import torch
 
 EQUIANGULAR = 0
 LEGENDRE_GAUSS = 1
+EQUIANGULAR_TRAPEZOID = 2
 TIE_TOL = 1e-9
 
 
@@ -20,6 +21,13 @@ def colat_weights(grid_type, nlat):
         x, w = np.polynomial.legendre.leggauss(nlat)
         order = np.argsort(-x)
         return np.arccos(x[order]), w[order]
+    if grid_type == EQUIANGULAR_TRAPEZOID:
+        # composite trapezoid rule for f(t) sin(t) on [0, pi] with nlat intervals; both end points carry sin = 0,
+        # which is why the south pole can be left out of the grid
+        t = np.linspace(0.0, np.pi, nlat + 1)
+        w = np.full(nlat + 1, np.pi / nlat)
+        w[[0, -1]] *= 0.5
+        return t[:-1], (w * np.sin(t))[:-1]
     # Clenshaw-Curtis: the unique weights on t_h = pi h / n that integrate
     # cos(m t) sin(t) exactly for m = 0..n; moments: (1 + cos(m pi)) / (1 - m^2), 0 for m = 1.
     n = nlat - 1
@@ -56,7 +64,8 @@ def dense_mask(g):
 def log_omega_tokens(g):
     """ln omega per input token j = h'*nlon_in + w'."""
     _, w = colat_weights(g["grid_type"], g["nlat_in"])
-    return np.repeat(np.log(w * 2.0 * np.pi / g["nlon_in"]), g["nlon_in"])
+    with np.errstate(divide="ignore"):      # the trapezoid grid has a zero-weight pole row: ln 0 = -inf
+        return np.repeat(np.log(w * 2.0 * np.pi / g["nlon_in"]), g["nlon_in"])
 
 
 def dense_attention(g, q, k, v, scale, dout=None, mask=None):

@@ -91,6 +91,11 @@ SMALL = [
     dict(kind="nattn", grid_type=0, nlat_in=33, nlon_in=192, nlat_out=33, nlon_out=192, theta=0.3, batch=9, heads=2, d=32, dtype="f32"),
     # a handful of light latitudes with bands of three rows (two wavefronts per workgroup, more segments than fit)
     dict(kind="nattn", grid_type=0, nlat_in=9, nlon_in=256, nlat_out=9, nlon_out=256, theta=0.5, batch=1, heads=2, d=32, dtype="f32"),
+    # the equiangular grid as the paper prints it (no south pole, zero weight on the pole row): generic, tuned
+    # equal-grid and tuned 2:1 kernels
+    dict(kind="nattn", grid_type=2, nlat_in=16, nlon_in=32, nlat_out=16, nlon_out=32, theta=0.45, batch=1, heads=2, d=8, dtype="f32"),
+    dict(kind="nattn", grid_type=2, nlat_in=64, nlon_in=256, nlat_out=64, nlon_out=256, theta=4 * math.pi / 64, batch=1, heads=2, d=32, dtype="f32"),
+    dict(kind="nattn", grid_type=2, nlat_in=40, nlon_in=160, nlat_out=20, nlon_out=80, theta=0.35, batch=1, heads=3, d=32, dtype="f32"),
 ]
 
 

@@ -21,6 +21,10 @@ EXTRA = [
     dict(grid_type=0, nlat_in=12, nlon_in=15, nlat_out=7, nlon_out=5, theta=1.1),
     dict(grid_type=0, nlat_in=33, nlon_in=64, nlat_out=33, nlon_out=1, theta=0.3),
     dict(grid_type=1, nlat_in=2, nlon_in=1, nlat_out=2, nlon_out=1, theta=0.2),
+    # the equiangular grid exactly as the paper prints it (no south pole, trapezoid weights)
+    dict(grid_type=2, nlat_in=16, nlon_in=32, nlat_out=16, nlon_out=32, theta=0.45),
+    dict(grid_type=2, nlat_in=128, nlon_in=256, nlat_out=128, nlon_out=256, theta=0.1),
+    dict(grid_type=2, nlat_in=64, nlon_in=128, nlat_out=32, nlon_out=64, theta=0.2),
 ]
 
 
@@ -41,7 +45,11 @@ def test_neighbor_lists_bit_exact_and_weights(gd):
     ocolat, _ = O.grid(gd["grid_type"], gd["nlat_in"])
     assert np.allclose(colat, ocolat, rtol=0, atol=4e-15)
     assert np.allclose(om, O.omega(gd["grid_type"], gd["nlat_in"], gd["nlon_in"]), rtol=1e-10, atol=0)
-    assert abs(om.sum() * gd["nlon_in"] - 4 * math.pi) < 1e-12
+    if gd["grid_type"] != 2:
+        assert abs(om.sum() * gd["nlon_in"] - 4 * math.pi) < 1e-12
+    else:   # the grid of App. A.1: zero weight at the pole, sum only close to 4 pi
+        assert om[0] == 0.0 and (om[1:] > 0).all()
+        assert abs(om.sum() * gd["nlon_in"] - 4 * math.pi) < 11.0 / gd["nlat_in"] ** 2
 
 
 def test_init_errors():
@@ -87,3 +95,12 @@ def test_null_arguments_return_codes():
     assert L.s2_nattn_fwd(None, 1, 1, 8, 8, 0, 1.0, None, None, None, None, None, None) == S.S2_ERR_INVALID_ARG
     assert L.s2_grid_num_neighbors(None) == 0
     L.s2_grid_destroy(None)
+
+
+def test_neighborhood_of_zero_weight_points_only_is_rejected():
+    # trapezoid grid: the pole row has weight zero; a cutoff below the latitude spacing leaves the pole outputs
+    # with pole points only
+    with pytest.raises(S.S2Error) as ei:
+        S.s2_grid_init(2, 16, 32, 16, 32, 0.1)
+    assert ei.value.code == S.S2_ERR_EMPTY_NEIGHBORHOOD
+    S.s2_grid_init(2, 16, 32, 16, 32, 0.3)

@@ -24,6 +24,11 @@ SMALL = [
          batch=1, heads=2, d=5, dtype="f32"),
     dict(kind="nattn", grid_type=1, nlat_in=16, nlon_in=36, nlat_out=8, nlon_out=12, theta=0.5,
          batch=2, heads=1, d=3, dtype="f32"),
+    # the grid as App. A.1 prints it: zero weight on the pole row
+    dict(kind="nattn", grid_type=2, nlat_in=12, nlon_in=24, nlat_out=12, nlon_out=24, theta=0.6,
+         batch=1, heads=2, d=4, dtype="f32"),
+    dict(kind="nattn", grid_type=2, nlat_in=16, nlon_in=32, nlat_out=8, nlon_out=16, theta=0.5,
+         batch=1, heads=1, d=5, dtype="f32"),
 ]
 
 

@@ -75,3 +75,22 @@ def test_bad_grid_rejected():
         O.grid(0, 1)
     with pytest.raises(ValueError):
         O.grid(7, 16)
+
+
+@pytest.mark.parametrize("nlat,nlon", [(8, 16), (65, 128), (128, 256), (257, 7)])
+def test_trapezoid_grid_of_the_paper(nlat, nlon):
+    # App. A.1: colat_i = pi i / nlat for i < nlat, q_ij = 2 pi^2 / (nlat nlon) sin(colat_i).
+    # Closed form of the sum: sum_i sin(pi i / n) = cot(pi / (2n)), so the weights add up to
+    # (2 pi^2 / n) cot(pi / (2n)) = 4 pi - pi^3 / (3 n^2) + O(n^-4): "approximately 4 pi".
+    colat, w = O.grid(O.EQUIANGULAR_TRAPEZOID, nlat)
+    om = O.omega(O.EQUIANGULAR_TRAPEZOID, nlat, nlon)
+    assert colat[0] == 0.0 and om[0] == 0.0                      # north pole, weight zero
+    assert np.allclose(np.diff(colat), math.pi / nlat, rtol=0, atol=1e-15)
+    assert abs(colat[-1] - math.pi * (nlat - 1) / nlat) < 1e-15   # the south pole is not a grid point
+    i = np.arange(nlat)
+    assert np.allclose(om, 2 * math.pi ** 2 / (nlat * nlon) * np.sin(math.pi * i / nlat), rtol=1e-14, atol=0)
+    total = om.sum() * nlon
+    assert abs(total - 2 * math.pi ** 2 / nlat / math.tan(math.pi / (2 * nlat))) < 1e-12
+    assert abs(total - (4 * math.pi - math.pi ** 3 / (3 * nlat ** 2))) < 2.0 / nlat ** 4 * 10
+    # trapezoid rule in colatitude: exact for the first cosine mode only up to O(n^-2)
+    assert abs((w * np.cos(colat) ** 2).sum() - 2.0 / 3.0) < 3.0 / nlat ** 2
