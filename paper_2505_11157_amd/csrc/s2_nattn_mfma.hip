@@ -78,13 +78,18 @@ __device__ __forceinline__ void stage_tile(const float *kb, const float *vb, siz
 // NSUB adjacent super-tiles are staged (and consumed) per barrier: half as many workgroup-wide waits for NSUB = 2.
 template <int NSUB>
 __global__ void __launch_bounds__(1024)
-nattn_fwd_mfma(S2DeviceTables t, int nbh, int nrows, float qscale, const float *__restrict__ q,
+nattn_fwd_mfma(S2DeviceTables t, int nbh, int nrows, int rgroups, float qscale, const float *__restrict__ q,
                const float *__restrict__ k, const float *__restrict__ v, float *__restrict__ out,
                float *__restrict__ lse)
 {
-    extern __shared__ __attribute__((aligned(16))) float smem[];
-    const int nwaves = blockDim.x >> 6;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    // rgroups = 2 (launches with fewer workgroups than compute units): the workgroup holds two sets of wavefronts,
+    // each set walks half of the band of input latitudes with its own tiles, and the two partial softmax states
+    // are merged through LDS at the end: twice the wavefronts per SIMD to overlap the matrix-instruction chains.
+    extern __shared__ __attribute__((aligned(16))) float smem_all[];
+    const int nwaves = (blockDim.x >> 6) / rgroups;   // wavefronts per set = nlon_out / 32
+    const int wave_all = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int grp = wave_all / nwaves, wave = wave_all - grp * nwaves;
+    float *smem = smem_all + grp * (2 * NSUB * kTileFloats);
     const int col = lane & 31, hl = lane >> 5;
     const int nlon = t.nlon_in;                       // equal longitude counts
     const int bh = blockIdx.x / nrows;
@@ -102,23 +107,26 @@ nattn_fwd_mfma(S2DeviceTables t, int nbh, int nrows, float qscale, const float *
     // LDS column (within a super-tile) of S^T tile row `col`, tile mt = 0: see header
     const int arow = 32 * ((col >> 2) & 1) + 4 * (col >> 3) + (col & 3);
 
-    const int nb = t.band_n[h], hp0 = t.band_lo[h];
+    const int nb_all = t.band_n[h];
+    const int b_lo = grp * nb_all / rgroups, nb = (grp + 1) * nb_all / rgroups - b_lo;   // this set's band rows
+    const int hp0 = t.band_lo[h] + b_lo;
     const int ntile = nlon / (kTileCols * NSUB);
-    const int total = nb * ntile;
+    const int total = nb * ntile, total_max = ((nb_all + rgroups - 1) / rgroups) * ntile;
     // prologue: stage the first super-tile
-    {
+    if (total > 0) {
         const float *kb = k + size_t(bh) * kD * si + size_t(hp0) * nlon;
         const float *vb = v + size_t(bh) * kD * si + size_t(hp0) * nlon;
 #pragma unroll
         for (int sub = 0; sub < NSUB; ++sub)
             stage_tile(kb, vb, si, kTileCols * sub, nlon, smem + sub * kTileFloats, wave, nwaves, lane);
     }
-    for (int it = 0; it < total; ++it) {
+    for (int it = 0; it < total_max; ++it) {
         const int b = it / ntile, xg = (it - b * ntile) * kTileCols * NSUB;
         const int hp = hp0 + b;
         float *tiles = smem + (it & 1) * NSUB * kTileFloats;
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();     // tile `it` is complete; everyone has finished reading tile it-1
+        if (it >= total) continue;   // (the other set has one more band row)
         if (it + 1 < total) {
             const int b2 = (it + 1) / ntile, x2 = (it + 1 - b2 * ntile) * kTileCols * NSUB;
             const float *kb = k + size_t(bh) * kD * si + size_t(hp0 + b2) * nlon;
@@ -128,7 +136,7 @@ nattn_fwd_mfma(S2DeviceTables t, int nbh, int nrows, float qscale, const float *
                 stage_tile(kb, vb, si, x2 + kTileCols * sub, nlon,
                            smem + (((it + 1) & 1) * NSUB + sub) * kTileFloats, wave, nwaves, lane);
         }
-        const int c = table_i(t.cnt, h * t.band_max + b);
+        const int c = table_i(t.cnt, h * t.band_max + b_lo + b);
         const bool full = c == nlon;
         const int lo = full ? 0 : -((c - 1) >> 1);
         const float wq = table_f(t.omega_rel, hp);
@@ -200,6 +208,29 @@ nattn_fwd_mfma(S2DeviceTables t, int nbh, int nrows, float qscale, const float *
         for (int i = 0; i < 32; ++i) o = mfma(tv[col * kPV + 32 * hl + i], p[i], o);
         }
     }
+    if (rgroups > 1) {
+        // the second set hands its partial state (o, m, l per lane) to the first through LDS
+        __syncthreads();     // everybody is done with the tiles
+        float *slot = smem_all + wave * 64 + lane;
+        const int pitch = nwaves * 64;
+        if (grp == 1) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) slot[i * pitch] = o[i];
+            slot[16 * pitch] = m;
+            slot[17 * pitch] = l;
+        }
+        __syncthreads();
+        if (grp != 0) return;
+        const float mo = slot[16 * pitch], lo2 = slot[17 * pitch];
+        const float M = fmaxf(m, mo);
+        // a set that saw no valid column has m = -inf, l = 0: its factor must be 0, never NaN
+        const float fa = m == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m - M);
+        const float fb = mo == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(mo - M);
+        m = M;
+        l = l * fa + lo2 * fb;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o[i] = o[i] * fa + slot[i * pitch] * fb;
+    }
     l += __shfl_xor(l, 32);
     const float inv = 1.f / l;
     // lane (output, hl) holds channels 8*(i/4) + 4*hl + i%4 in register i
@@ -241,14 +272,17 @@ __device__ __forceinline__ void stage_tile_b(const float *ab, const float *bb, s
 
 template <int NSUB>
 __global__ void __launch_bounds__(1024)
-nattn_bwd_dq_mfma(S2DeviceTables t, int nbh, int nrows, float scale, const float *__restrict__ q,
+nattn_bwd_dq_mfma(S2DeviceTables t, int nbh, int nrows, int rgroups, float scale, const float *__restrict__ q,
                   const float *__restrict__ k, const float *__restrict__ v, const float *__restrict__ outp,
                   const float *__restrict__ lse, const float *__restrict__ go, float *__restrict__ dq,
                   float *__restrict__ Dws)
 {
-    extern __shared__ __attribute__((aligned(16))) float smem[];
-    const int nwaves = blockDim.x >> 6;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    // rgroups = 2: two sets of wavefronts, each with half of the band rows and its own tiles (see the forward)
+    extern __shared__ __attribute__((aligned(16))) float smem_all[];
+    const int nwaves = (blockDim.x >> 6) / rgroups;
+    const int wave_all = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int grp = wave_all / nwaves, wave = wave_all - grp * nwaves;
+    float *smem = smem_all + grp * (2 * NSUB * kTileB);
     const int col = lane & 31, hl = lane >> 5;
     const int nlon = t.nlon_in;
     const int bh = blockIdx.x / nrows;
@@ -267,27 +301,30 @@ nattn_bwd_dq_mfma(S2DeviceTables t, int nbh, int nrows, float scale, const float
         Dp = fmaf(gop[s], outp[off], Dp);
     }
     const float Di = Dp + __shfl_xor(Dp, 32);        // D_i = dout_i . out_i over all 32 channels
-    if (hl == 0) Dws[size_t(bh) * so + io] = Di;
+    if (hl == 0 && grp == 0) Dws[size_t(bh) * so + io] = Di;
     const float lse2 = (lse[size_t(bh) * so + io] - t.ln_omega_ref) * 1.4426950408889634f;
     f32x16 acc = {0};
     const int arow = 32 * ((col >> 2) & 1) + 4 * (col >> 3) + (col & 3);
 
-    const int nb = t.band_n[h], hp0 = t.band_lo[h];
+    const int nb_all = t.band_n[h];
+    const int b_lo = grp * nb_all / rgroups, nb = (grp + 1) * nb_all / rgroups - b_lo;
+    const int hp0 = t.band_lo[h] + b_lo;
     const int ntile = nlon / (kTileCols * NSUB);
-    const int total = nb * ntile;
-    {
+    const int total = nb * ntile, total_max = ((nb_all + rgroups - 1) / rgroups) * ntile;
+    if (total > 0) {
         const float *kb = k + size_t(bh) * kD * si + size_t(hp0) * nlon;
         const float *vb = v + size_t(bh) * kD * si + size_t(hp0) * nlon;
 #pragma unroll
         for (int sub = 0; sub < NSUB; ++sub)
             stage_tile_b(kb, vb, si, kTileCols * sub, nlon, smem + sub * kTileB, wave, nwaves, lane);
     }
-    for (int it = 0; it < total; ++it) {
+    for (int it = 0; it < total_max; ++it) {
         const int b = it / ntile, xg = (it - b * ntile) * kTileCols * NSUB;
         const int hp = hp0 + b;
         float *tiles = smem + (it & 1) * NSUB * kTileB;
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
+        if (it >= total) continue;   // (the other set has one more band row)
         if (it + 1 < total) {
             const int b2 = (it + 1) / ntile, x2 = (it + 1 - b2 * ntile) * kTileCols * NSUB;
             const float *kb = k + size_t(bh) * kD * si + size_t(hp0 + b2) * nlon;
@@ -297,7 +334,7 @@ nattn_bwd_dq_mfma(S2DeviceTables t, int nbh, int nrows, float scale, const float
                 stage_tile_b(kb, vb, si, x2 + kTileCols * sub, nlon, smem + (((it + 1) & 1) * NSUB + sub) * kTileB, wave,
                              nwaves, lane);
         }
-        const int c = table_i(t.cnt, h * t.band_max + b);
+        const int c = table_i(t.cnt, h * t.band_max + b_lo + b);
         const bool full = c == nlon;
         const int lo = full ? 0 : -((c - 1) >> 1);
         const float wq = table_f(t.omega_rel, hp);
@@ -338,6 +375,20 @@ nattn_bwd_dq_mfma(S2DeviceTables t, int nbh, int nrows, float scale, const float
         }
         }
     }
+    if (rgroups > 1) {
+        // the second set hands its partial sums to the first through LDS
+        __syncthreads();
+        float *slot = smem_all + wave * 64 + lane;
+        const int pitch = nwaves * 64;
+        if (grp == 1) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) slot[i * pitch] = acc[i];
+        }
+        __syncthreads();
+        if (grp != 0) return;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[i] += slot[i * pitch];
+    }
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
         const int ch = 8 * (i >> 2) + 4 * hl + (i & 3);
@@ -372,14 +423,17 @@ __device__ __forceinline__ void stage_tile_c(const float *qb, const float *gb, c
 
 template <int NSUB>
 __global__ void __launch_bounds__(1024)
-nattn_bwd_dkdv_mfma(S2DeviceTables t, int nbh, int nrows, float scale, const float *__restrict__ q,
+nattn_bwd_dkdv_mfma(S2DeviceTables t, int nbh, int nrows, int rgroups, float scale, const float *__restrict__ q,
                     const float *__restrict__ k, const float *__restrict__ v, const float *__restrict__ lse,
                     const float *__restrict__ go, const float *__restrict__ Dws, float *__restrict__ dk,
                     float *__restrict__ dv)
 {
-    extern __shared__ __attribute__((aligned(16))) float smem[];
-    const int nwaves = blockDim.x >> 6;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    // rgroups = 2: two sets of wavefronts, each with half of the (transposed) band rows and its own tiles
+    extern __shared__ __attribute__((aligned(16))) float smem_all[];
+    const int nwaves = (blockDim.x >> 6) / rgroups;
+    const int wave_all = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int grp = wave_all / nwaves, wave = wave_all - grp * nwaves;
+    float *smem = smem_all + grp * (2 * NSUB * kTileC);
     const int col = lane & 31, hl = lane >> 5;
     const int nlon = t.nlon_in;                       // equal grids
     const int bh = blockIdx.x / nrows;
@@ -400,9 +454,11 @@ nattn_bwd_dkdv_mfma(S2DeviceTables t, int nbh, int nrows, float scale, const flo
     f32x16 adk = {0}, adv = {0};
     const int arow = 32 * ((col >> 2) & 1) + 4 * (col >> 3) + (col & 3);
 
-    const int nb = t.tband_n[hp], h0 = t.tband_lo[hp];
+    const int nb_all = t.tband_n[hp];
+    const int b_lo = grp * nb_all / rgroups, nb = (grp + 1) * nb_all / rgroups - b_lo;
+    const int h0 = t.tband_lo[hp] + b_lo;
     const int ntile = nlon / (kTileCols * NSUB);
-    const int total = nb * ntile;
+    const int total = nb * ntile, total_max = ((nb_all + rgroups - 1) / rgroups) * ntile;
     auto issue = [&](int itx, float *dst) {
         const int b2 = itx / ntile, x2 = (itx - b2 * ntile) * kTileCols * NSUB;
         const size_t rowoff = size_t(h0 + b2) * nlon;
@@ -412,14 +468,15 @@ nattn_bwd_dkdv_mfma(S2DeviceTables t, int nbh, int nrows, float scale, const flo
                          lse + size_t(bh) * so + rowoff, Dws + size_t(bh) * so + rowoff, so, x2 + kTileCols * sub, nlon,
                          dst + sub * kTileC, wave, nwaves, lane);
     };
-    issue(0, smem);
-    for (int it = 0; it < total; ++it) {
+    if (total > 0) issue(0, smem);
+    for (int it = 0; it < total_max; ++it) {
         const int b = it / ntile, xg = (it - b * ntile) * kTileCols * NSUB;
         float *tiles = smem + (it & 1) * NSUB * kTileC;
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
+        if (it >= total) continue;   // (the other set has one more band row)
         if (it + 1 < total) issue(it + 1, smem + ((it + 1) & 1) * NSUB * kTileC);
-        const int c = table_i(t.tcnt, hp * t.tband_max + b);
+        const int c = table_i(t.tcnt, hp * t.tband_max + b_lo + b);
         const bool full = c == nlon;
         const int lo = full ? 0 : -((c - 1) >> 1);
 #pragma unroll 1
@@ -467,6 +524,20 @@ nattn_bwd_dkdv_mfma(S2DeviceTables t, int nbh, int nrows, float scale, const flo
         }
         }
     }
+    if (rgroups > 1) {
+        // the second set hands its partial sums to the first through LDS
+        __syncthreads();
+        float *slot = smem_all + wave * 64 + lane;
+        const int pitch = nwaves * 64;
+        if (grp == 1) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) { slot[i * pitch] = adk[i]; slot[(16 + i) * pitch] = adv[i]; }
+        }
+        __syncthreads();
+        if (grp != 0) return;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) { adk[i] += slot[i * pitch]; adv[i] += slot[(16 + i) * pitch]; }
+    }
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
         const int ch = 8 * (i >> 2) + 4 * hl + (i & 3);
@@ -489,25 +560,45 @@ int s2_nattn_fwd_mfma_rows(const S2DeviceTables &t, int d, int e)
     return t.fwd_cls[0] + t.fwd_cls[1] + t.fwd_cls[2];
 }
 
+// Two sets of wavefronts per workgroup (each with half of the band rows) when the launch has no more workgroups
+// than the device has compute units: with one workgroup of nlon/32 wavefronts per compute unit a SIMD would hold a
+// single wavefront and every matrix-instruction chain would run exposed.
+static int row_groups(const S2DeviceTables &t, int nbh, int nrows)
+{
+    static int ncu = 0;
+    if (ncu == 0) {
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || ncu <= 0)
+            ncu = 256;
+    }
+    static const bool off = std::getenv("S2_NO_ROW_GROUPS") != nullptr;   // debugging aid
+    const bool fits = t.nlon_out * 4 <= 1024 && t.nlon_in % (2 * kTileCols) == 0;
+    return (!off && fits && long(nrows) * nbh <= ncu) ? 2 : 1;
+}
+
 int s2_nattn_fwd_mfma(const S2DeviceTables &t, int nbh, int nrows, float scale, const float *q, const float *k,
                       const float *v, float *out, float *lse, hipStream_t st)
 {
     const bool two = t.nlon_in % (2 * kTileCols) == 0;
-    const size_t lds = (two ? 4 : 2) * size_t(kTileFloats) * sizeof(float);
+    const int rgroups = row_groups(t, nbh, nrows);
+    const size_t lds = rgroups * (two ? 4 : 2) * size_t(kTileFloats) * sizeof(float);
     static bool configured = false;
     if (!configured) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(nattn_fwd_mfma<2>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, int(8 * kTileFloats * sizeof(float))) != hipSuccess ||
+            hipFuncSetAttribute(reinterpret_cast<const void *>(nattn_fwd_mfma<1>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, int(4 * kTileFloats * sizeof(float))) != hipSuccess)
             return -1;
         configured = true;
     }
     S2TraceScope tr("nattn_fwd_mfma", nbh * (t.fwd_pairs[0] + t.fwd_pairs[1] + t.fwd_pairs[2]), st);
     if (two)
-        hipLaunchKernelGGL(nattn_fwd_mfma<2>, dim3((unsigned)(long(nrows) * nbh)), dim3(t.nlon_out * 2), lds, st, t, nbh,
-                           nrows, scale * 1.4426950408889634f, q, k, v, out, lse);
+        hipLaunchKernelGGL(nattn_fwd_mfma<2>, dim3((unsigned)(long(nrows) * nbh)), dim3(t.nlon_out * 2 * rgroups), lds, st, t,
+                           nbh, nrows, rgroups, scale * 1.4426950408889634f, q, k, v, out, lse);
     else
-        hipLaunchKernelGGL(nattn_fwd_mfma<1>, dim3((unsigned)(long(nrows) * nbh)), dim3(t.nlon_out * 2), lds, st, t, nbh,
-                           nrows, scale * 1.4426950408889634f, q, k, v, out, lse);
+        hipLaunchKernelGGL(nattn_fwd_mfma<1>, dim3((unsigned)(long(nrows) * nbh)), dim3(t.nlon_out * 2 * rgroups), lds, st, t,
+                           nbh, nrows, rgroups, scale * 1.4426950408889634f, q, k, v, out, lse);
     return 0;
 }
 
@@ -516,21 +607,22 @@ int s2_nattn_bwd_dq_mfma(const S2DeviceTables &t, int nbh, int nrows, float scal
                          hipStream_t st)
 {
     const bool two = t.nlon_in % (2 * kTileCols) == 0;
-    const size_t lds = (two ? 4 : 2) * size_t(kTileB) * sizeof(float);
+    const int rgroups = row_groups(t, nbh, nrows);
+    const size_t lds = rgroups * (two ? 4 : 2) * size_t(kTileB) * sizeof(float);
     static bool configured = false;
     if (!configured) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(nattn_bwd_dq_mfma<2>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, int(4 * kTileB * sizeof(float))) != hipSuccess)
+                                hipFuncAttributeMaxDynamicSharedMemorySize, int(8 * kTileB * sizeof(float))) != hipSuccess)
             return -1;
         configured = true;
     }
     S2TraceScope tr("nattn_bwd_dq_mfma", nbh * (t.fwd_pairs[0] + t.fwd_pairs[1] + t.fwd_pairs[2]), st);
     if (two)
-        hipLaunchKernelGGL(nattn_bwd_dq_mfma<2>, dim3((unsigned)(long(nrows) * nbh)), dim3(t.nlon_out * 2), lds, st, t,
-                           nbh, nrows, scale, q, k, v, o, lse, go, dq, Dws);
+        hipLaunchKernelGGL(nattn_bwd_dq_mfma<2>, dim3((unsigned)(long(nrows) * nbh)), dim3(t.nlon_out * 2 * rgroups), lds, st,
+                           t, nbh, nrows, rgroups, scale, q, k, v, o, lse, go, dq, Dws);
     else
-        hipLaunchKernelGGL(nattn_bwd_dq_mfma<1>, dim3((unsigned)(long(nrows) * nbh)), dim3(t.nlon_out * 2), lds, st, t,
-                           nbh, nrows, scale, q, k, v, o, lse, go, dq, Dws);
+        hipLaunchKernelGGL(nattn_bwd_dq_mfma<1>, dim3((unsigned)(long(nrows) * nbh)), dim3(t.nlon_out * 2 * rgroups), lds, st,
+                           t, nbh, nrows, rgroups, scale, q, k, v, o, lse, go, dq, Dws);
     return 0;
 }
 
@@ -548,20 +640,21 @@ int s2_nattn_bwd_dkdv_mfma(const S2DeviceTables &t, int nbh, int nrows, float sc
                            hipStream_t st)
 {
     const bool two = t.nlon_in % (2 * kTileCols) == 0;
-    const size_t lds = (two ? 4 : 2) * size_t(kTileC) * sizeof(float);
+    const int rgroups = row_groups(t, nbh, nrows);
+    const size_t lds = rgroups * (two ? 4 : 2) * size_t(kTileC) * sizeof(float);
     static bool configured = false;
     if (!configured) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(nattn_bwd_dkdv_mfma<2>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, int(4 * kTileC * sizeof(float))) != hipSuccess)
+                                hipFuncAttributeMaxDynamicSharedMemorySize, int(8 * kTileC * sizeof(float))) != hipSuccess)
             return -1;
         configured = true;
     }
     S2TraceScope tr("nattn_bwd_dkdv_mfma", nbh * (t.bwd_pairs[0] + t.bwd_pairs[1] + t.bwd_pairs[2]), st);
     if (two)
-        hipLaunchKernelGGL(nattn_bwd_dkdv_mfma<2>, dim3((unsigned)(long(nrows) * nbh)), dim3(t.nlon_in * 2), lds, st, t,
-                           nbh, nrows, scale, q, k, v, lse, go, Dws, dk, dv);
+        hipLaunchKernelGGL(nattn_bwd_dkdv_mfma<2>, dim3((unsigned)(long(nrows) * nbh)), dim3(t.nlon_in * 2 * rgroups), lds, st,
+                           t, nbh, nrows, rgroups, scale, q, k, v, lse, go, Dws, dk, dv);
     else
-        hipLaunchKernelGGL(nattn_bwd_dkdv_mfma<1>, dim3((unsigned)(long(nrows) * nbh)), dim3(t.nlon_in * 2), lds, st, t,
-                           nbh, nrows, scale, q, k, v, lse, go, Dws, dk, dv);
+        hipLaunchKernelGGL(nattn_bwd_dkdv_mfma<1>, dim3((unsigned)(long(nrows) * nbh)), dim3(t.nlon_in * 2 * rgroups), lds, st,
+                           t, nbh, nrows, rgroups, scale, q, k, v, lse, go, Dws, dk, dv);
     return 0;
 }
