@@ -28,7 +28,7 @@ TRAFFIC_BYTES = {
     (3, "nattn_fwd_mfma"): 280e6, (3, "nattn_fwd_stream"): 747e6,
     (3, "nattn_bwd_dq_mfma"): 333e6, (3, "nattn_bwd_dq_stream"): 1023e6,
     (3, "nattn_bwd_dkdv_mfma"): 349e6, (3, "nattn_bwd_dkdv_stream"): 1058e6,
-    (5, "global_fwd"): 160e6, (5, "global_bwd_dkdv"): 499e6, (5, "global_bwd_dq"): 318e6,
+    (5, "global_fwd"): 160e6, (5, "global_bwd_dkdv"): 501e6, (5, "global_bwd_dq"): 287e6,
 }
 
 
