@@ -128,7 +128,8 @@ int s2_nattn_bwd(const s2_grid_t *g, int batch, int heads, int d_qk, int d_v, in
                  void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /* Bytes of device scratch s2_attn_global_fwd / s2_attn_global_bwd need (token-transposed
- * copies of the operands that are contracted over tokens, and D_i = dout_i.out_i). */
+ * copies of the operands that are contracted over tokens, and per-token constants of the
+ * backward pass). */
 size_t s2_attn_global_fwd_workspace_bytes(const s2_grid_t *g, int batch, int heads, int d, int dtype);
 size_t s2_attn_global_bwd_workspace_bytes(const s2_grid_t *g, int batch, int heads, int d, int dtype);
 

@@ -1,26 +1,30 @@
 // Global quadrature-weighted attention on gfx950: bf16 MFMA (32x32x16), fp32
 // softmax and accumulation, flash-style streaming over key tiles (App. B.1
-// first equation; App. B.2: the quadrature weight is an additive column bias
-// ln omega_j on the logits).
+// first equation; App. B.2 writes the quadrature weight as an additive column
+// bias ln omega_j on the logits: here it is carried as the equivalent factor
+// omega_j / max omega on the exponentials, folded into the transposed operands,
+// so that a zero weight needs no special case and the running maximum follows
+// the bare logits).
 //
 // Orientation.  Scores are produced TRANSPOSED, S^T = K Q^T, so that in the
 // MFMA result layout a lane owns one query column and 16 keys.  The softmax
-// over keys is then a per-lane loop plus one exchange between lanes l and l^32,
-// and the exponentials can be fed straight back as the B operand of the next
-// MFMA (O^T += V^T P^T) without moving data between lanes.  Row r of the K
-// tile is mapped to key 16*((r>>2)&1) + 4*(r>>3) + (r&3): with that
-// permutation the 16 keys a lane holds are contiguous, so bias, V^T and the
-// transposed operands of the backward pass are read with 16-byte loads.
+// over keys is then a per-lane loop (the two half-wavefronts of a query only
+// talk when the running maximum has to move), and the exponentials are fed
+// straight back as the B operand of the next MFMA (O^T += V^T P^T) without
+// moving data between lanes.  Row r of the K tile is mapped to key
+// 16*((r>>2)&1) + 4*(r>>3) + (r&3): with that permutation the 16 keys a lane
+// holds are contiguous.
 //
 // The MFMA "A" operand wants its contraction index contiguous in memory.  V
 // (forward) and Q, K, dout (backward) are contracted over tokens, so they are
 // transposed once per call into the caller's workspace ([b,h][64][Npad] bf16,
-// zero padded to a multiple of 64 tokens).
+// zero padded to a multiple of 64 tokens).  All streamed operands reach the
+// wavefronts through LDS tiles that a workgroup copies once (see below).
 //
 // Backward (App. B.4 with every token in every neighborhood): D_i = dout_i.out_i,
-// p_ij = exp(s_ij + ln omega_j - lse_i), dS_ij = p_ij (dout_i.v_j - D_i);
-// one kernel owns 32 keys and streams query tiles (dk, dv), one owns 32
-// queries and streams key tiles (dq): no atomics.
+// p_ij = omega_j exp(s_ij - lse_i), dS_ij = p_ij (dout_i.v_j - D_i);
+// one kernel owns 32 keys per wavefront and streams query tiles (dk, dv), one
+// owns 32 queries per wavefront and streams key tiles (dq): no atomics.
 #include "s2_internal.h"
 
 namespace {
