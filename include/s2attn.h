@@ -103,8 +103,9 @@ size_t s2_nattn_bwd_workspace_bytes(const s2_grid_t *g, int batch, int heads, in
  * d_v channels); k [batch][heads][d_qk][nlat_in][nlon_in]; v likewise with d_v;
  * lse float32 [batch][heads][nlat_out][nlon_out].
  * dtype: S2_F32 (float32 arithmetic throughout).  d_qk, d_v in [1, 128].
- * Errors: S2_ERR_INVALID_ARG (NULL pointers, sizes < 1), S2_ERR_UNSUPPORTED
- * (dtype, head dims), S2_ERR_DEVICE (host-only handle or launch failure).
+ * Errors: S2_ERR_INVALID_ARG (NULL or not 16-byte aligned pointers, sizes < 1),
+ * S2_ERR_UNSUPPORTED (dtype, head dims), S2_ERR_DEVICE (host-only handle or
+ * launch failure).
  */
 int s2_nattn_fwd(const s2_grid_t *g, int batch, int heads, int d_qk, int d_v, int dtype, float scale,
                  const void *q, const void *k, const void *v, void *out, float *lse,
@@ -143,7 +144,8 @@ size_t s2_attn_global_bwd_workspace_bytes(const s2_grid_t *g, int batch, int hea
  * dtype: S2_BF16 (bf16 tensors, MFMA with float32 accumulation, float32
  * softmax and lse); d = 64.  Other dtypes or head dimensions: S2_ERR_UNSUPPORTED.
  * workspace: device scratch of at least s2_attn_global_fwd_workspace_bytes(...)
- * bytes (S2_ERR_WORKSPACE if smaller); its contents are undefined afterwards.
+ * bytes, 256-byte aligned (S2_ERR_WORKSPACE otherwise); its contents are undefined
+ * afterwards.  Tensor pointers must be 16-byte aligned (S2_ERR_INVALID_ARG).
  */
 int s2_attn_global_fwd(const s2_grid_t *g, int batch, int heads, int d, int dtype, float scale,
                        const void *q, const void *k, const void *v, void *out, float *lse,

@@ -530,6 +530,9 @@ int check_global(const s2_grid_t *g, int batch, int heads, int d, int dtype)
     return S2_OK;
 }
 
+// the kernels move 16-byte pieces (LDS-direct copies, vector loads and stores)
+bool misaligned(const void *p, size_t a = 16) { return reinterpret_cast<uintptr_t>(p) % a != 0; }
+
 size_t transposed_bytes(const s2_grid_t *g, int nbh) { return size_t(nbh) * kD * g->npad_tok * sizeof(bf16raw); }
 
 void launch_prepare(const PrepArgs &a, int nops, int nbh, int N, int Npad, hipStream_t st)
@@ -561,8 +564,11 @@ extern "C" int s2_attn_global_fwd(const s2_grid_t *g, int batch, int heads, int 
     int rc = check_global(g, batch, heads, d, dtype);
     if (rc) return rc;
     if (!q || !k || !v || !out || !lse) return s2_fail(S2_ERR_INVALID_ARG, "NULL tensor pointer");
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out))
+        return s2_fail(S2_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
     if (!workspace || workspace_bytes < s2_attn_global_fwd_workspace_bytes(g, batch, heads, d, dtype))
         return s2_fail(S2_ERR_WORKSPACE, "workspace missing or smaller than s2_attn_global_fwd_workspace_bytes()");
+    if (misaligned(workspace, 256)) return s2_fail(S2_ERR_WORKSPACE, "workspace must be 256-byte aligned");
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const int nbh = batch * heads, N = g->nlat_in * g->nlon_in, Npad = g->npad_tok;
     PrepArgs pa{};
@@ -588,8 +594,12 @@ extern "C" int s2_attn_global_bwd(const s2_grid_t *g, int batch, int heads, int 
     if (rc) return rc;
     if (!q || !k || !v || !out || !lse || !dout || !dq || !dk || !dv)
         return s2_fail(S2_ERR_INVALID_ARG, "NULL tensor pointer");
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out) || misaligned(dout) || misaligned(dq) ||
+        misaligned(dk) || misaligned(dv))
+        return s2_fail(S2_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
     if (!workspace || workspace_bytes < s2_attn_global_bwd_workspace_bytes(g, batch, heads, d, dtype))
         return s2_fail(S2_ERR_WORKSPACE, "workspace missing or smaller than s2_attn_global_bwd_workspace_bytes()");
+    if (misaligned(workspace, 256)) return s2_fail(S2_ERR_WORKSPACE, "workspace must be 256-byte aligned");
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const int nbh = batch * heads, N = g->nlat_in * g->nlon_in, Npad = g->npad_tok;
     const size_t tb = transposed_bytes(g, nbh);

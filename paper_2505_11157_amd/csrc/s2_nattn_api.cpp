@@ -14,6 +14,9 @@ int check_common(const s2_grid_t *g, int batch, int heads, int d_qk, int d_v, in
     return S2_OK;
 }
 
+// the tuned kernels move 16-byte pieces (vector loads and stores, LDS-direct copies)
+bool misaligned(const void *p) { return reinterpret_cast<uintptr_t>(p) % 16 != 0; }
+
 }  // namespace
 
 extern "C" size_t s2_nattn_bwd_workspace_bytes(const s2_grid_t *g, int batch, int heads, int d_qk, int d_v, int dtype)
@@ -30,6 +33,8 @@ extern "C" int s2_nattn_fwd(const s2_grid_t *g, int batch, int heads, int d_qk, 
     int rc = check_common(g, batch, heads, d_qk, d_v, dtype);
     if (rc) return rc;
     if (!q || !k || !v || !out || !lse) return s2_fail(S2_ERR_INVALID_ARG, "NULL tensor pointer");
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out) || misaligned(lse))
+        return s2_fail(S2_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     auto *fwd = s2_nattn_fwd_tiled_supported(g->dt, d_qk, d_v) ? s2_nattn_fwd_tiled : s2_nattn_fwd_generic;
     fwd(g->dt, batch * heads, d_qk, d_v, scale, static_cast<const float *>(q), static_cast<const float *>(k),
@@ -47,8 +52,12 @@ extern "C" int s2_nattn_bwd(const s2_grid_t *g, int batch, int heads, int d_qk, 
     if (rc) return rc;
     if (!q || !k || !v || !out || !lse || !dout || !dq || !dk || !dv)
         return s2_fail(S2_ERR_INVALID_ARG, "NULL tensor pointer");
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out) || misaligned(lse) || misaligned(dout) ||
+        misaligned(dq) || misaligned(dk) || misaligned(dv))
+        return s2_fail(S2_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
     if (!workspace || workspace_bytes < s2_nattn_bwd_workspace_bytes(g, batch, heads, d_qk, d_v, dtype))
         return s2_fail(S2_ERR_WORKSPACE, "workspace missing or smaller than s2_nattn_bwd_workspace_bytes()");
+    if (misaligned(workspace)) return s2_fail(S2_ERR_WORKSPACE, "workspace must be 16-byte aligned");
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     auto *bwd = s2_nattn_bwd_tiled_supported(g->dt, d_qk, d_v) ? s2_nattn_bwd_tiled : s2_nattn_bwd_generic;
     if (bwd(g->dt, batch * heads, d_qk, d_v, scale, static_cast<const float *>(q), static_cast<const float *>(k),

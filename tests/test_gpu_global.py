@@ -170,6 +170,16 @@ def test_global_errors():
     with pytest.raises(S.S2Error) as ei:
         S.s2_attn_global_fwd(g, x, x, x, 1.0, workspace=torch.empty(8, dtype=torch.uint8, device=dev))
     assert ei.value.code == S.S2_ERR_WORKSPACE
+    # a workspace that is large enough but not 256-byte aligned, and a tensor that is not 16-byte aligned
+    big = torch.empty(S.s2_attn_global_fwd_workspace_bytes(g, 1, 1, 64) + 512, dtype=torch.uint8, device=dev)
+    with pytest.raises(S.S2Error) as ei:
+        S.s2_attn_global_fwd(g, x, x, x, 1.0, workspace=big[8:])
+    assert ei.value.code == S.S2_ERR_WORKSPACE
+    flat = torch.zeros(144 * 64 + 8, device=dev, dtype=torch.bfloat16)
+    skew = flat[1:1 + 144 * 64].view(1, 1, 144, 64)
+    with pytest.raises(S.S2Error) as ei:
+        S.s2_attn_global_fwd(g, skew, x, x, 1.0)
+    assert ei.value.code == S.S2_ERR_INVALID_ARG
     g2 = S.s2_grid_init(0, 17, 32, 9, 16, 0.5)
     z = torch.zeros((1, 1, 17 * 32, 64), device=dev, dtype=torch.bfloat16)
     with pytest.raises(S.S2Error) as ei:
