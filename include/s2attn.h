@@ -35,6 +35,7 @@ typedef struct s2_grid s2_grid_t; /* opaque; immutable after init; usable from a
 enum {
     S2_GRID_EQUIANGULAR = 0,   /* colat_h = pi*h/(nlat-1), both poles, Clenshaw-Curtis weights */
     S2_GRID_LEGENDRE_GAUSS = 1, /* Gauss-Legendre nodes in cos(colat), north first */
+    S2_GRID_LEGENDRE_GAUSS_LOBATTO = 3, /* Gauss-Lobatto nodes in cos(colat): both poles plus the zeros of P'_{nlat-1} */
     S2_GRID_EQUIANGULAR_TRAPEZOID = 2 /* the grid as printed in App. A.1: colat_i = pi*i/nlat, i < nlat (north pole
                                          only), weights 2 pi^2 / (nlat nlon) sin(colat_i): zero at the pole, whose
                                          points then never contribute; sums to 4 pi only approximately */

@@ -7,6 +7,7 @@ from .s2_oracle import (  # noqa: F401
     EQUIANGULAR,
     EQUIANGULAR_TRAPEZOID,
     LEGENDRE_GAUSS,
+    LEGENDRE_GAUSS_LOBATTO,
     build,
     geodesic,
     global_bwd,

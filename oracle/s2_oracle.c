@@ -52,6 +52,7 @@
 #define S2O_EQUIANGULAR 0
 #define S2O_LEGENDRE_GAUSS 1
 #define S2O_EQUIANGULAR_TRAPEZOID 2
+#define S2O_LEGENDRE_GAUSS_LOBATTO 3
 #define S2O_TIE_TOL 1e-9
 
 static const double S2O_PI = 3.14159265358979323846264338327950288;
@@ -120,6 +121,38 @@ static void equiangular_trapezoid(int nlat, double *colat, double *w)
     }
 }
 
+/* Legendre-Gauss-Lobatto rule with n = nlat points in x = cos(colat): both poles (x = +-1) are
+ * nodes, the interior nodes are the zeros of P'_{n-1}, and w_i = 2 / (n (n-1) P_{n-1}(x_i)^2).
+ * A Gaussian-type grid that, unlike the Legendre-Gauss one, has points at the poles.
+ * Newton on P'_m (m = n-1) from the Chebyshev-Lobatto points; P''_m comes from Legendre's
+ * equation (1-x^2) P'' = 2x P' - m(m+1) P. */
+static void legendre_gauss_lobatto(int nlat, double *colat, double *w)
+{
+    int m = nlat - 1;
+    for (int i = 0; i < nlat; ++i) {
+        double x;
+        if (i == 0) x = 1.0;
+        else if (i == m) x = -1.0;
+        else {
+            x = cos(S2O_PI * (double)i / (double)m);
+            for (int it = 0; it < 100; ++it) {
+                double p, dp;
+                legendre_pn(m, x, &p, &dp);
+                double d2p = (2.0 * x * dp - (double)m * (m + 1.0) * p) / (1.0 - x * x);
+                double dx = dp / d2p;
+                x -= dx;
+                if (fabs(dx) < 1e-15) break;
+            }
+        }
+        double p, dp;
+        if (i == 0) p = 1.0;
+        else if (i == m) p = (m % 2) ? -1.0 : 1.0;
+        else legendre_pn(m, x, &p, &dp);
+        colat[i] = acos(x);
+        w[i] = 2.0 / ((double)nlat * (double)m * p * p);
+    }
+}
+
 /* colat[nlat], wlat[nlat] (wlat sums to 2, approximately for the trapezoid grid).
  * Returns 0, or -1 on bad input. */
 int s2o_grid(int grid_type, int nlat, double *colat, double *wlat)
@@ -128,6 +161,7 @@ int s2o_grid(int grid_type, int nlat, double *colat, double *wlat)
     if (grid_type == S2O_EQUIANGULAR) clenshaw_curtis(nlat, colat, wlat);
     else if (grid_type == S2O_LEGENDRE_GAUSS) legendre_gauss(nlat, colat, wlat);
     else if (grid_type == S2O_EQUIANGULAR_TRAPEZOID) equiangular_trapezoid(nlat, colat, wlat);
+    else if (grid_type == S2O_LEGENDRE_GAUSS_LOBATTO) legendre_gauss_lobatto(nlat, colat, wlat);
     else return -1;
     return 0;
 }

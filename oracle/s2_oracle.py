@@ -12,6 +12,7 @@ import numpy as np
 
 EQUIANGULAR = 0
 LEGENDRE_GAUSS = 1
+LEGENDRE_GAUSS_LOBATTO = 3  # Gauss-Lobatto nodes in cos(colat): a Gaussian-type grid with both poles
 EQUIANGULAR_TRAPEZOID = 2   # the grid exactly as App. A.1 prints it (no south pole, zero weight at the pole)
 
 _HERE = os.path.dirname(os.path.abspath(__file__))

@@ -12,6 +12,7 @@ import numpy as np
 S2_GRID_EQUIANGULAR = 0
 S2_GRID_LEGENDRE_GAUSS = 1
 S2_GRID_EQUIANGULAR_TRAPEZOID = 2
+S2_GRID_LEGENDRE_GAUSS_LOBATTO = 3
 S2_F32 = 0
 S2_BF16 = 1
 S2_OK = 0

@@ -104,11 +104,61 @@ void trapezoid_nodes(int nlat, std::vector<double> &colat, std::vector<double> &
     }
 }
 
+// Gauss-Lobatto rule with n points: x = +-1 and the n-2 zeros of P'_{n-1}, which interlace the zeros of P_{n-1}:
+// each one is bracketed by two neighbouring Gauss-Legendre nodes of order n-1 and found there by bisection on the
+// sign of P'_{n-1} (derivative from the recurrence (1-x^2) P'_m = m (P_{m-1} - x P_m)), then bisected down to the last bit.  Weights 2 / (n (n-1) P_{n-1}(x)^2).
+void gauss_lobatto_nodes(int n, std::vector<double> &colat, std::vector<double> &w)
+{
+    const int m = n - 1;
+    auto eval = [m](double x, double &pm, double &dpm) {
+        double p_prev = 1.0, p = m == 0 ? 1.0 : x;
+        for (int k = 1; k < m; ++k) {
+            const double p_next = ((2.0 * k + 1.0) * x * p - k * p_prev) / (k + 1.0);
+            p_prev = p;
+            p = p_next;
+        }
+        pm = p;
+        dpm = m * (p_prev - x * p) / (1.0 - x * x);
+    };
+    std::vector<double> x(n);
+    x[0] = 1.0;
+    x[m] = -1.0;
+    if (n > 2) {
+        std::vector<double> gc, gw;
+        gauss_legendre_nodes(m, gc, gw);              // zeros of P_m, north first (x decreasing)
+        for (int i = 1; i < m; ++i) {
+            double hi = std::cos(gc[i - 1]), lo = std::cos(gc[i]);      // P_m has one extremum in (lo, hi)
+            double pm, dhi, dlo;
+            eval(hi, pm, dhi);
+            eval(lo, pm, dlo);
+            for (int it = 0; it < 200 && hi - lo > 4e-16 * std::max(1.0, std::fabs(hi)); ++it) {
+                const double mid = 0.5 * (lo + hi);
+                double dmid;
+                eval(mid, pm, dmid);
+                if ((dmid > 0.0) == (dhi > 0.0)) { hi = mid; dhi = dmid; } else { lo = mid; dlo = dmid; }
+                if (mid == lo && mid == hi) break;
+            }
+            x[i] = 0.5 * (lo + hi);
+        }
+    }
+    colat.resize(n);
+    w.resize(n);
+    for (int i = 0; i < n; ++i) {
+        double pm, dpm;
+        if (i == 0) pm = 1.0;
+        else if (i == m) pm = (m % 2) ? -1.0 : 1.0;
+        else eval(x[i], pm, dpm);
+        colat[i] = std::acos(x[i]);
+        w[i] = 2.0 / (double(n) * m * pm * pm);
+    }
+}
+
 int nodes(int grid_type, int nlat, std::vector<double> &colat, std::vector<double> &w)
 {
     if (grid_type == S2_GRID_EQUIANGULAR) clenshaw_curtis_nodes(nlat, colat, w);
     else if (grid_type == S2_GRID_LEGENDRE_GAUSS) gauss_legendre_nodes(nlat, colat, w);
     else if (grid_type == S2_GRID_EQUIANGULAR_TRAPEZOID) trapezoid_nodes(nlat, colat, w);
+    else if (grid_type == S2_GRID_LEGENDRE_GAUSS_LOBATTO) gauss_lobatto_nodes(nlat, colat, w);
     else return -1;
     return 0;
 }
@@ -202,7 +252,7 @@ extern "C" int s2_grid_init(int grid_type, int nlat_in, int nlon_in, int nlat_ou
     if (!out_grid) return s2_fail(S2_ERR_INVALID_ARG, "out_grid is NULL");
     *out_grid = nullptr;
     if (grid_type != S2_GRID_EQUIANGULAR && grid_type != S2_GRID_LEGENDRE_GAUSS &&
-        grid_type != S2_GRID_EQUIANGULAR_TRAPEZOID)
+        grid_type != S2_GRID_EQUIANGULAR_TRAPEZOID && grid_type != S2_GRID_LEGENDRE_GAUSS_LOBATTO)
         return s2_fail(S2_ERR_INVALID_ARG, "unknown grid_type");
     if (nlat_in < 2 || nlat_out < 2 || nlon_in < 1 || nlon_out < 1)
         return s2_fail(S2_ERR_INVALID_ARG, "need nlat >= 2 and nlon >= 1 on both grids");

@@ -18,6 +18,7 @@ import numpy as np
 EQUIANGULAR = 0
 LEGENDRE_GAUSS = 1
 EQUIANGULAR_TRAPEZOID = 2
+LEGENDRE_GAUSS_LOBATTO = 3
 
 CONFIGS = {
     1: dict(kind="nattn", grid_type=EQUIANGULAR, nlat_in=17, nlon_in=32, nlat_out=17, nlon_out=32,

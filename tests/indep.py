@@ -12,6 +12,7 @@ import torch
 EQUIANGULAR = 0
 LEGENDRE_GAUSS = 1
 EQUIANGULAR_TRAPEZOID = 2
+LEGENDRE_GAUSS_LOBATTO = 3
 TIE_TOL = 1e-9
 
 
@@ -21,6 +22,17 @@ def colat_weights(grid_type, nlat):
         x, w = np.polynomial.legendre.leggauss(nlat)
         order = np.argsort(-x)
         return np.arccos(x[order]), w[order]
+    if grid_type == LEGENDRE_GAUSS_LOBATTO:
+        # nodes: +-1 and the roots of the derivative of P_{n-1}, from numpy's polynomial class; weights from the
+        # exactness conditions sum_i w_i P_k(x_i) = int_{-1}^{1} P_k dx = 2 [k = 0] for k = 0..n-1 (the Legendre
+        # basis keeps the linear system well conditioned)
+        m = nlat - 1
+        inner = np.polynomial.legendre.Legendre.basis(m).deriv().roots().real if m > 1 else np.zeros(0)
+        x = np.sort(np.concatenate([[-1.0], inner, [1.0]]))[::-1]
+        A = np.polynomial.legendre.legvander(x, m).T
+        rhs = np.zeros(nlat)
+        rhs[0] = 2.0
+        return np.arccos(np.clip(x, -1.0, 1.0)), np.linalg.solve(A, rhs)
     if grid_type == EQUIANGULAR_TRAPEZOID:
         # composite trapezoid rule for f(t) sin(t) on [0, pi] with nlat intervals; both end points carry sin = 0,
         # which is why the south pole can be left out of the grid

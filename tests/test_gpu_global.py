@@ -50,7 +50,7 @@ def run_global(grid_type, nlat, nlon, B, H, arrs, slices, scale=None, rel=2e-2):
 
 
 @pytest.mark.parametrize("gt,nlat,nlon,B,H", [(0, 9, 16, 1, 2), (1, 8, 12, 2, 1), (0, 5, 7, 1, 1), (0, 17, 32, 1, 3),
-                                             (1, 2, 1, 1, 1), (0, 13, 20, 1, 1), (2, 12, 32, 1, 2), (2, 9, 20, 1, 1)])
+                                             (1, 2, 1, 1, 1), (0, 13, 20, 1, 1), (2, 12, 32, 1, 2), (2, 9, 20, 1, 1), (3, 9, 32, 1, 2)])
 def test_global_small_grids(gt, nlat, nlon, B, H):
     rng = np.random.default_rng(nlat * 100 + nlon)
     N = nlat * nlon

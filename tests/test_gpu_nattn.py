@@ -96,6 +96,9 @@ SMALL = [
     dict(kind="nattn", grid_type=2, nlat_in=16, nlon_in=32, nlat_out=16, nlon_out=32, theta=0.45, batch=1, heads=2, d=8, dtype="f32"),
     dict(kind="nattn", grid_type=2, nlat_in=64, nlon_in=256, nlat_out=64, nlon_out=256, theta=4 * math.pi / 64, batch=1, heads=2, d=32, dtype="f32"),
     dict(kind="nattn", grid_type=2, nlat_in=40, nlon_in=160, nlat_out=20, nlon_out=80, theta=0.35, batch=1, heads=3, d=32, dtype="f32"),
+    # Gauss-Lobatto grid (both poles, Gaussian spacing): generic and tuned kernels
+    dict(kind="nattn", grid_type=3, nlat_in=17, nlon_in=32, nlat_out=17, nlon_out=32, theta=0.45, batch=1, heads=2, d=8, dtype="f32"),
+    dict(kind="nattn", grid_type=3, nlat_in=65, nlon_in=256, nlat_out=65, nlon_out=256, theta=4 * math.pi / 64, batch=1, heads=2, d=32, dtype="f32"),
 ]
 
 

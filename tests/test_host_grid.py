@@ -25,6 +25,10 @@ EXTRA = [
     dict(grid_type=2, nlat_in=16, nlon_in=32, nlat_out=16, nlon_out=32, theta=0.45),
     dict(grid_type=2, nlat_in=128, nlon_in=256, nlat_out=128, nlon_out=256, theta=0.1),
     dict(grid_type=2, nlat_in=64, nlon_in=128, nlat_out=32, nlon_out=64, theta=0.2),
+    # Gauss-Lobatto nodes in cos(colat): a Gaussian-type grid with both poles
+    dict(grid_type=3, nlat_in=17, nlon_in=32, nlat_out=17, nlon_out=32, theta=0.45),
+    dict(grid_type=3, nlat_in=129, nlon_in=256, nlat_out=129, nlon_out=256, theta=0.1),
+    dict(grid_type=3, nlat_in=65, nlon_in=128, nlat_out=33, nlon_out=64, theta=0.2),
 ]
 
 

@@ -29,6 +29,9 @@ SMALL = [
          batch=1, heads=2, d=4, dtype="f32"),
     dict(kind="nattn", grid_type=2, nlat_in=16, nlon_in=32, nlat_out=8, nlon_out=16, theta=0.5,
          batch=1, heads=1, d=5, dtype="f32"),
+    # Gauss-Lobatto grid
+    dict(kind="nattn", grid_type=3, nlat_in=13, nlon_in=24, nlat_out=13, nlon_out=24, theta=0.6,
+         batch=1, heads=2, d=4, dtype="f32"),
 ]
 
 

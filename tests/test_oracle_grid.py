@@ -94,3 +94,36 @@ def test_trapezoid_grid_of_the_paper(nlat, nlon):
     assert abs(total - (4 * math.pi - math.pi ** 3 / (3 * nlat ** 2))) < 2.0 / nlat ** 4 * 10
     # trapezoid rule in colatitude: exact for the first cosine mode only up to O(n^-2)
     assert abs((w * np.cos(colat) ** 2).sum() - 2.0 / 3.0) < 3.0 / nlat ** 2
+
+
+def test_gauss_lobatto_textbook_small():
+    # n = 3: nodes 1, 0, -1, weights 1/3, 4/3, 1/3 (Simpson); n = 4: +-1, +-1/sqrt(5), weights 1/6, 5/6;
+    # n = 5: +-1, +-sqrt(3/7), 0, weights 1/10, 49/90, 32/45
+    table = {3: ([1, 0, -1], [1 / 3, 4 / 3, 1 / 3]),
+             4: ([1, 1 / math.sqrt(5), -1 / math.sqrt(5), -1], [1 / 6, 5 / 6, 5 / 6, 1 / 6]),
+             5: ([1, math.sqrt(3 / 7), 0, -math.sqrt(3 / 7), -1], [1 / 10, 49 / 90, 32 / 45, 49 / 90, 1 / 10])}
+    for n, (x, w) in table.items():
+        colat, wl = O.grid(O.LEGENDRE_GAUSS_LOBATTO, n)
+        assert np.allclose(np.cos(colat), x, rtol=0, atol=1e-15)
+        assert np.allclose(wl, w, rtol=1e-14, atol=0)
+
+
+@pytest.mark.parametrize("nlat", [6, 33, 128])
+def test_gauss_lobatto_exactness_and_independent_construction(nlat):
+    from indep import colat_weights
+    colat, w = O.grid(O.LEGENDRE_GAUSS_LOBATTO, nlat)
+    x = np.cos(colat)
+    assert colat[0] == 0.0 and abs(colat[-1] - math.pi) < 1e-15 and (np.diff(colat) > 0).all()
+    assert abs(w.sum() - 2.0) < 1e-13 and (w > 0).all()
+    assert abs(w[0] - 2.0 / (nlat * (nlat - 1))) < 1e-16            # pole weight, closed form
+    assert np.allclose(w, w[::-1], rtol=1e-12) and np.allclose(x, -x[::-1], atol=1e-15)
+    # exact for polynomials up to degree 2n - 3, and not beyond
+    for k in range(0, 2 * nlat - 2):
+        exact = 2.0 / (k + 1) if k % 2 == 0 else 0.0
+        assert abs((w * x ** k).sum() - exact) < 1e-13, k
+    k = 2 * nlat - 2
+    assert abs((w * x ** k).sum() - 2.0 / (k + 1)) > (1e-9 if nlat < 20 else 0.0)
+    ic, iw = colat_weights(3, nlat)      # numpy's root finder + a moment solve in the Legendre basis
+    assert np.allclose(ic, colat, rtol=0, atol=1e-10) and np.allclose(iw, w, rtol=0, atol=1e-10)
+    om = O.omega(O.LEGENDRE_GAUSS_LOBATTO, nlat, 24)
+    assert abs(om.sum() * 24 - 4 * math.pi) < 1e-12
