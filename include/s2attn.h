@@ -63,15 +63,19 @@ enum {
  * output latitude h the input points (h', w') whose great-circle distance to
  * the output point (h, longitude 0) is <= theta_cutoff + 1e-9 rad.  The lists
  * are reused for every output longitude w by the shift w' -> w' + w*pscale,
- * pscale = nlon_in / nlon_out.  Both grids have the same grid_type.
+ * pscale = nlon_in / nlon_out (equal grids and downsampling).  Upsampling
+ * (nlon_out = r * nlon_in): output longitude w = r*m + s lies between input
+ * meridians unless s = 0, so every latitude gets r lists (one per s), each
+ * reused for every m by the shift w' -> w' + m; these grids run on the
+ * shape-agnostic kernels.  Both grids have the same grid_type.
  *
  * If a HIP device is present the compact tables are uploaded to the current
  * device; without a device the handle is host-only (the introspection calls
  * work, the attention calls return S2_ERR_DEVICE).
  *
  * Errors: S2_ERR_INVALID_ARG (nlat < 2, nlon < 1, theta outside (0, pi], NULL
- * out_grid, unknown grid_type); S2_ERR_UNSUPPORTED (nlon_in not a multiple of
- * nlon_out); S2_ERR_EMPTY_NEIGHBORHOOD (some output point sees no input point);
+ * out_grid, unknown grid_type); S2_ERR_UNSUPPORTED (neither longitude count
+ * is a multiple of the other); S2_ERR_EMPTY_NEIGHBORHOOD (some output point sees no input point);
  * S2_ERR_AMBIGUOUS_CUTOFF (a point lies within 1e-12 rad of the inclusion
  * threshold, so membership would depend on rounding: perturb theta_cutoff);
  * S2_ERR_ALLOC / S2_ERR_DEVICE.
@@ -90,6 +94,12 @@ int64_t s2_grid_num_neighbors(const s2_grid_t *g);
  * h'*nlon_in + w' with w' in [0, nlon_in), ascending within each output
  * latitude; col needs s2_grid_num_neighbors(g) entries. */
 int s2_grid_get_neighbors(const s2_grid_t *g, int64_t *row_ptr, int32_t *col);
+/* Neighbor list of one output point (h, w), eq. (5): absolute input indices h'*nlon_in + w_in,
+ * ascending; *count receives their number, col (if not NULL) needs that many entries.  On
+ * upsampling grids (nlon_out a multiple of nlon_in) the lists of the output longitudes between two
+ * input meridians differ from the one s2_grid_get_neighbors reports for longitude 0.
+ * S2_ERR_INVALID_ARG for a point outside the output grid. */
+int s2_grid_get_neighbors_at(const s2_grid_t *g, int h, int w, int32_t *col, int *count);
 
 /* Bytes of device scratch s2_nattn_bwd needs (0 for the forward pass). */
 size_t s2_nattn_bwd_workspace_bytes(const s2_grid_t *g, int batch, int heads, int d_qk, int d_v, int dtype);

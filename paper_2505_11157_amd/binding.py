@@ -58,6 +58,8 @@ def lib():
         L.s2_grid_num_neighbors.restype = ctypes.c_int64
         L.s2_grid_get_neighbors.argtypes = [_vp, _vp, _vp]
         L.s2_grid_get_neighbors.restype = _i
+        L.s2_grid_get_neighbors_at.argtypes = [_vp, _i, _i, _vp, _vp]
+        L.s2_grid_get_neighbors_at.restype = _i
         L.s2_nattn_bwd_workspace_bytes.argtypes = [_vp, _i, _i, _i, _i, _i]
         L.s2_nattn_bwd_workspace_bytes.restype = ctypes.c_size_t
         L.s2_nattn_fwd.argtypes = [_vp, _i, _i, _i, _i, _i, ctypes.c_float, _vp, _vp, _vp, _vp, _vp, _vp]
@@ -136,6 +138,15 @@ def s2_grid_device_flags(g):
 
 def s2_grid_num_neighbors(g):
     return int(lib().s2_grid_num_neighbors(g.handle))
+
+
+def s2_grid_get_neighbors_at(g, h, w):
+    """Neighbor list of output point (h, w): absolute input indices h'*nlon_in + w_in, ascending."""
+    n = ctypes.c_int(0)
+    _check(lib().s2_grid_get_neighbors_at(g.handle, int(h), int(w), None, ctypes.byref(n)))
+    col = np.empty(n.value, np.int32)
+    _check(lib().s2_grid_get_neighbors_at(g.handle, int(h), int(w), col.ctypes.data, ctypes.byref(n)))
+    return col
 
 
 def s2_grid_get_neighbors(g):

@@ -207,6 +207,8 @@ static int upload_tables(s2_grid *g)
         {g->st_cum.data(), g->st_cum.size() * sizeof(int), 0},
         {g->tst_cum.data(), g->tst_cum.size() * sizeof(int), 0},
         {&zero_word, sizeof(unsigned), 0},
+        {g->ucnt.data(), g->ucnt.size() * sizeof(int), 0},
+        {g->ulo.data(), g->ulo.size() * sizeof(int), 0},
     };
     size_t total = 0;
     for (auto &p : parts) {
@@ -237,6 +239,9 @@ static int upload_tables(s2_grid *g)
     t.st_cum = reinterpret_cast<const int *>(base + parts[10].off);
     t.tst_cum = reinterpret_cast<const int *>(base + parts[11].off);
     t.dev_flags = reinterpret_cast<unsigned *>(base + parts[12].off);
+    t.upscale = g->upscale;
+    t.ucnt = reinterpret_cast<const int *>(base + parts[13].off);
+    t.ulo = reinterpret_cast<const int *>(base + parts[14].off);
     t.band_max = g->band_max;
     t.tband_max = g->tband_max;
     t.nlat_in = g->nlat_in; t.nlon_in = g->nlon_in;
@@ -260,14 +265,16 @@ extern "C" int s2_grid_init(int grid_type, int nlat_in, int nlon_in, int nlat_ou
         return s2_fail(S2_ERR_INVALID_ARG, "grid too large");
     if (!(theta_cutoff > 0.0) || theta_cutoff > kPi + 1e-12)
         return s2_fail(S2_ERR_INVALID_ARG, "theta_cutoff must lie in (0, pi]");
-    if (nlon_in % nlon_out != 0)
-        return s2_fail(S2_ERR_UNSUPPORTED, "nlon_in must be a multiple of nlon_out (longitude shift invariance)");
+    if (nlon_in % nlon_out != 0 && nlon_out % nlon_in != 0)
+        return s2_fail(S2_ERR_UNSUPPORTED,
+                       "nlon_in must be a multiple of nlon_out or the other way round (longitude shift invariance)");
 
     s2_grid *g = new (std::nothrow) s2_grid();
     if (!g) return s2_fail(S2_ERR_ALLOC, "out of host memory");
     g->grid_type = grid_type;
     g->nlat_in = nlat_in; g->nlon_in = nlon_in; g->nlat_out = nlat_out; g->nlon_out = nlon_out;
-    g->pscale = nlon_in / nlon_out;
+    g->upscale = nlon_out > nlon_in ? nlon_out / nlon_in : 1;
+    g->pscale = g->upscale > 1 ? 1 : nlon_in / nlon_out;
     g->theta = theta_cutoff;
     std::vector<double> wlat_in, wlat_out;
     nodes(grid_type, nlat_in, g->colat_in, wlat_in);
@@ -342,6 +349,47 @@ extern "C" int s2_grid_init(int grid_type, int nlat_in, int nlon_in, int nlat_ou
             return s2_fail(S2_ERR_EMPTY_NEIGHBORHOOD,
                            "an output point has no input point of positive weight within theta_cutoff");
         }
+    }
+
+    // upsampling: arcs for the output longitudes between two input meridians (classes s = 1 .. upscale-1; s = 0 is
+    // the centred arc above).  An output point off the input meridians is farther from every input latitude circle
+    // than the one on the meridian, so the band of class 0 covers all classes (arcs may be empty).
+    if (g->upscale > 1) {
+        const int r = g->upscale;
+        g->ucnt.assign(size_t(nlat_out) * r * g->band_max, 0);
+        g->ulo.assign(size_t(nlat_out) * r * g->band_max, 0);
+        for (int h = 0; h < nlat_out; ++h)
+            for (int sc = 0; sc < r; ++sc)
+                for (int b = 0; b < g->band_n[h]; ++b) {
+                    const int hp = g->band_lo[h] + b;
+                    int c = 0;
+                    for (int wp = 0; wp < nlon_in; ++wp) {
+                        const double dphi = 2.0 * kPi * (double(wp) / nlon_in - double(sc) / nlon_out);
+                        const double dist = great_circle(g->colat_out[h], g->colat_in[hp], dphi);
+                        if (std::fabs(dist - limit) < kAmbiguous && limit < kPi) {
+                            delete g;
+                            return s2_fail(S2_ERR_AMBIGUOUS_CUTOFF,
+                                           "a grid point lies within 1e-12 rad of the inclusion threshold; perturb theta_cutoff");
+                        }
+                        member[wp] = dist <= limit;
+                        c += member[wp];
+                    }
+                    int start = 0;
+                    if (c > 0 && c < nlon_in) {
+                        // the arc is one circular interval: it starts where a member follows a non-member
+                        int nstart = 0;
+                        for (int wp = 0; wp < nlon_in; ++wp)
+                            if (member[wp] && !member[(wp + nlon_in - 1) % nlon_in]) { start = wp; ++nstart; }
+                        if (nstart != 1) {
+                            delete g;
+                            return s2_fail(S2_ERR_UNSUPPORTED, "internal: neighborhood is not one arc");
+                        }
+                        if (start > nlon_in / 2) start -= nlon_in;      // signed offset from the meridian at or below
+                    }
+                    const size_t at = (size_t(h) * r + sc) * g->band_max + b;
+                    g->ucnt[at] = c;
+                    g->ulo[at] = start;
+                }
     }
 
     // canonical CSR: ascending h'*nlon_in + w', w' in [0, nlon_in)
@@ -466,6 +514,33 @@ extern "C" int s2_grid_get_weights(const s2_grid_t *g, double *colat_in, double 
 }
 
 extern "C" int64_t s2_grid_num_neighbors(const s2_grid_t *g) { return g ? int64_t(g->col.size()) : 0; }
+
+extern "C" int s2_grid_get_neighbors_at(const s2_grid_t *g, int h, int w, int32_t *col, int *count)
+{
+    if (!g || !count) return s2_fail(S2_ERR_INVALID_ARG, "grid or count is NULL");
+    if (h < 0 || h >= g->nlat_out || w < 0 || w >= g->nlon_out) return s2_fail(S2_ERR_INVALID_ARG, "no such output point");
+    const int r = g->upscale, sc = w % r, m = r > 1 ? w / r : w * g->pscale;
+    std::vector<int32_t> list;
+    for (int b = 0; b < g->band_n[h]; ++b) {
+        const int hp = g->band_lo[h] + b;
+        int c, lo;
+        if (r > 1) {
+            const size_t at = (size_t(h) * r + sc) * g->band_max + b;
+            c = g->ucnt[at];
+            lo = g->ulo[at];
+        } else {
+            c = g->cnt[size_t(h) * g->band_max + b];
+            lo = c == g->nlon_in ? 0 : -((c - 1) / 2);
+        }
+        std::vector<int32_t> row;
+        for (int tt = 0; tt < c; ++tt) row.push_back(hp * g->nlon_in + ((m + lo + tt) % g->nlon_in + g->nlon_in) % g->nlon_in);
+        std::sort(row.begin(), row.end());
+        list.insert(list.end(), row.begin(), row.end());
+    }
+    if (col) std::memcpy(col, list.data(), sizeof(int32_t) * list.size());
+    *count = int(list.size());
+    return S2_OK;
+}
 
 extern "C" int s2_grid_get_neighbors(const s2_grid_t *g, int64_t *row_ptr, int32_t *col)
 {

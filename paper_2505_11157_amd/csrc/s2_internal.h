@@ -45,6 +45,12 @@ struct S2DeviceTables {
     const int *tst_cum;       // [tst_hi - tst_lo + 1]
     float ln_omega_ref;       // ln(max omega): the stored logsumexp is relative to the true omega
     float omega_ref;          // max omega
+    // upsampling (nlon_out = upscale * nlon_in, upscale > 1; pscale is 1 then): output longitude w = upscale*m + s
+    // lies between input meridians, so the arc on input latitude band_lo[h] + b depends on the class s:
+    // input columns m + ulo .. m + ulo + ucnt - 1 (ucnt may be 0), tables indexed [(h*upscale + s)*band_max + b]
+    int upscale;
+    const int *ucnt;
+    const int *ulo;
 };
 
 struct s2_grid {
@@ -54,6 +60,8 @@ struct s2_grid {
     std::vector<double> colat_in, omega_in, colat_out;
     // host copies of the compact tables
     std::vector<int> band_lo, band_n, cnt, tband_lo, tband_n, tcnt, row_order, trow_order, st_cum, tst_cum;
+    int upscale = 1;
+    std::vector<int> ucnt, ulo;      // upsampling only (see S2DeviceTables)
     int band_max = 0, tband_max = 0;
     // canonical CSR
     std::vector<int64_t> row_ptr;

@@ -800,7 +800,7 @@ nattn_bwd_dkdv2_tiled(S2DeviceTables t, int nbh, int first_row, float scale, con
 
 bool s2_nattn_bwd_tiled_supported(const S2DeviceTables &t, int d, int e)
 {
-    return d == 32 && e == 32 && (t.pscale == 1 || t.pscale == 2) && t.nlon_in % 4 == 0 && t.nlon_out % 4 == 0 &&
+    return t.upscale == 1 && d == 32 && e == 32 && (t.pscale == 1 || t.pscale == 2) && t.nlon_in % 4 == 0 && t.nlon_out % 4 == 0 &&
            t.nlon_out >= 72;
 }
 

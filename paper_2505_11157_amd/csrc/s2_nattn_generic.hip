@@ -18,6 +18,22 @@ __device__ __forceinline__ int wrap(int x, int n)
     return x >= n ? x - n : x;
 }
 
+// Arc of output point (h, w) on band row b: first input column (may be negative) and length.  Equal grids and
+// downsampling: the centred arc around input column w*pscale.  Upsampling (w = upscale*m + s): the arc of class s
+// relative to input column m.
+__device__ __forceinline__ void arc_of(const S2DeviceTables &t, int h, int w, int b, int &first, int &c)
+{
+    if (t.upscale > 1) {
+        const int m = w / t.upscale, sc = w - m * t.upscale;
+        const int at = (h * t.upscale + sc) * t.band_max + b;
+        c = t.ucnt[at];
+        first = m + t.ulo[at];
+    } else {
+        c = t.cnt[h * t.band_max + b];
+        first = w * t.pscale + ((c == t.nlon_in) ? 0 : -((c - 1) >> 1));
+    }
+}
+
 // Forward: App. B.1 (second equation) in the index form of App. B.3, with an
 // online softmax in base 2.  q is pre-multiplied by scale*log2(e).  The
 // quadrature weight enters as a factor omega[h']/omega_ref on exp2(s - m)
@@ -48,12 +64,11 @@ nattn_fwd_generic(S2DeviceTables t, int nbh, int d, int e, float qscale,
         acc[l] = 0.f;
     }
     float m = -INFINITY, lsum = 0.f;
-    const int wi0 = w * t.pscale;
     const int nb = t.band_n[h], hp0 = t.band_lo[h];
     for (int b = 0; b < nb; ++b) {
         const int hp = hp0 + b;
-        const int c = t.cnt[h * t.band_max + b];
-        const int lo = (c == t.nlon_in) ? 0 : -((c - 1) >> 1);
+        int first, c;
+        arc_of(t, h, w, b, first, c);
         const float wq = t.omega_rel[hp];
         const float *kb = k + size_t(bh) * d * si + size_t(hp) * t.nlon_in;
         const float *vb = v + size_t(bh) * e * si + size_t(hp) * t.nlon_in;
@@ -63,7 +78,7 @@ nattn_fwd_generic(S2DeviceTables t, int nbh, int d, int e, float qscale,
             float mc = -INFINITY;
 #pragma unroll
             for (int j = 0; j < kChunk; ++j) {
-                col[j] = wrap(wi0 + lo + t0 + j, t.nlon_in);
+                col[j] = wrap(first + t0 + j, t.nlon_in);
                 s[j] = -INFINITY;
                 if (t0 + j < c) {
                     float dot = 0.f;
@@ -133,17 +148,16 @@ nattn_bwd_dq_generic(S2DeviceTables t, int nbh, int d, int e, float scale,
     Dws[size_t(bh) * so + io] = Di;
     // base-2 logsumexp relative to omega_ref: p_ij = omega_rel_j * exp2(s_ij - lse2)
     const float lse2 = (lse[size_t(bh) * so + io] - t.ln_omega_ref) * 1.4426950408889634f;
-    const int wi0 = w * t.pscale;
     const int nb = t.band_n[h], hp0 = t.band_lo[h];
     for (int b = 0; b < nb; ++b) {
         const int hp = hp0 + b;
-        const int c = t.cnt[h * t.band_max + b];
-        const int lo = (c == t.nlon_in) ? 0 : -((c - 1) >> 1);
+        int first, c;
+        arc_of(t, h, w, b, first, c);
         const float wq = t.omega_rel[hp];
         const float *kb = k + size_t(bh) * d * si + size_t(hp) * t.nlon_in;
         const float *vb = v + size_t(bh) * e * si + size_t(hp) * t.nlon_in;
         for (int tt = 0; tt < c; ++tt) {
-            const int col = wrap(wi0 + lo + tt, t.nlon_in);
+            const int col = wrap(first + tt, t.nlon_in);
             float kr[DMAX];
             float dot = 0.f, gv = -Di;
 #pragma unroll
@@ -212,10 +226,7 @@ nattn_bwd_dkdv_generic(S2DeviceTables t, int nbh, int d, int e, float scale,
         const float *gb = go + size_t(bh) * e * so + size_t(h) * t.nlon_out;
         const float *lb = lse + size_t(bh) * so + size_t(h) * t.nlon_out;
         const float *Db = Dws + size_t(bh) * so + size_t(h) * t.nlon_out;
-        for (; x <= x_end; x += ps) {
-            int w = x / ps;
-            w = w >= t.nlon_out ? w - t.nlon_out : w;
-            w = w >= t.nlon_out ? w - t.nlon_out : w;
+        auto visit = [&](int w) {
             float qr[DMAX], gr[DMAX];
             const float lse2 = fmaf(lb[w], log2e, -lref2);
             float dot = 0.f, gv = -Db[w];
@@ -232,6 +243,27 @@ nattn_bwd_dkdv_generic(S2DeviceTables t, int nbh, int d, int e, float scale,
             for (int l = 0; l < DMAX; ++l) {
                 dkr[l] = fmaf(dS, qr[l], dkr[l]);
                 dvr[l] = fmaf(p, gr[l], dvr[l]);
+            }
+        };
+        if (t.upscale > 1) {
+            // upsampling: output longitude w = upscale*m + s holds this input point iff win - m lies in the arc
+            // of class s, i.e. m = win - lo - tt for tt = 0 .. c-1
+            const int bf = hp - t.band_lo[h];
+            for (int sc = 0; sc < t.upscale; ++sc) {
+                const int at = (h * t.upscale + sc) * t.band_max + bf;
+                const int cu = t.ucnt[at], lo = t.ulo[at];
+                for (int tt = 0; tt < cu; ++tt) {
+                    int m = (win - lo - tt) % t.nlon_in;
+                    m = m < 0 ? m + t.nlon_in : m;
+                    visit(m * t.upscale + sc);
+                }
+            }
+        } else {
+            for (; x <= x_end; x += ps) {
+                int w = x / ps;
+                w = w >= t.nlon_out ? w - t.nlon_out : w;
+                w = w >= t.nlon_out ? w - t.nlon_out : w;
+                visit(w);
             }
         }
     }

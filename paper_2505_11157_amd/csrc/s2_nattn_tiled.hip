@@ -466,7 +466,7 @@ int launch_fwd_tiled(const S2DeviceTables &t, int skip_rows, int nbh, float qsca
 
 bool s2_nattn_fwd_tiled_supported(const S2DeviceTables &t, int d, int e)
 {
-    return d == 32 && e == 32 && (t.pscale == 1 || t.pscale == 2) && t.nlon_in % 4 == 0 && t.nlon_out % 4 == 0 &&
+    return t.upscale == 1 && d == 32 && e == 32 && (t.pscale == 1 || t.pscale == 2) && t.nlon_in % 4 == 0 && t.nlon_out % 4 == 0 &&
            t.nlon_out >= 72;   // (window wrap logic handles at most two turns of the circle)
 }
 

@@ -52,8 +52,9 @@ def run_case(c, arrs, slices):
     for s in slices:
         sl = slice(s, s + 1)
         a64 = [a[sl].astype(np.float64) for a in arrs]
-        r_out, r_lse = O.nattn_fwd(gd, a64[0], a64[1], a64[2], scale)
-        r_dq, r_dk, r_dv = O.nattn_bwd(gd, *a64, scale)
+        brute = gd["nlon_in"] % gd["nlon_out"] != 0      # upsampling: the oracle's per-pair form of eq. (5)
+        r_out, r_lse = O.nattn_fwd(gd, a64[0], a64[1], a64[2], scale, brute=brute)
+        r_dq, r_dk, r_dv = O.nattn_bwd(gd, *a64, scale, brute=brute)
         _close_fwd(out[sl], r_out, "out[%d]" % s)
         _close_fwd(lse[sl], r_lse, "lse[%d]" % s)
         _close_grad(dq[sl], r_dq, "dq[%d]" % s)
@@ -99,6 +100,11 @@ SMALL = [
     # Gauss-Lobatto grid (both poles, Gaussian spacing): generic and tuned kernels
     dict(kind="nattn", grid_type=3, nlat_in=17, nlon_in=32, nlat_out=17, nlon_out=32, theta=0.45, batch=1, heads=2, d=8, dtype="f32"),
     dict(kind="nattn", grid_type=3, nlat_in=65, nlon_in=256, nlat_out=65, nlon_out=256, theta=4 * math.pi / 64, batch=1, heads=2, d=32, dtype="f32"),
+    # upsampling (nlon_out = 2, 3, 4 x nlon_in): shape-agnostic kernels with one list per longitude class
+    dict(kind="nattn", grid_type=0, nlat_in=9, nlon_in=16, nlat_out=17, nlon_out=32, theta=0.5, batch=1, heads=2, d=8, dtype="f32"),
+    dict(kind="nattn", grid_type=1, nlat_in=12, nlon_in=24, nlat_out=16, nlon_out=72, theta=0.4, batch=2, heads=1, d=32, dtype="f32"),
+    dict(kind="nattn", grid_type=0, nlat_in=9, nlon_in=20, nlat_out=17, nlon_out=80, theta=0.6, batch=1, heads=1, d=5, dtype="f32"),
+    dict(kind="nattn", grid_type=0, nlat_in=6, nlon_in=10, nlat_out=9, nlon_out=20, theta=math.pi, batch=1, heads=1, d=3, dtype="f32"),
 ]
 
 

@@ -108,3 +108,28 @@ def test_neighborhood_of_zero_weight_points_only_is_rejected():
         S.s2_grid_init(2, 16, 32, 16, 32, 0.1)
     assert ei.value.code == S.S2_ERR_EMPTY_NEIGHBORHOOD
     S.s2_grid_init(2, 16, 32, 16, 32, 0.3)
+
+
+@pytest.mark.parametrize("gd", [
+    dict(grid_type=0, nlat_in=9, nlon_in=16, nlat_out=17, nlon_out=32, theta=0.5),      # upsampling x2
+    dict(grid_type=1, nlat_in=8, nlon_in=12, nlat_out=12, nlon_out=36, theta=0.6),      # upsampling x3
+    dict(grid_type=0, nlat_in=6, nlon_in=10, nlat_out=9, nlon_out=40, theta=math.pi),   # x4, whole sphere
+    dict(grid_type=2, nlat_in=8, nlon_in=16, nlat_out=8, nlon_out=32, theta=0.45),      # x2 on the trapezoid grid
+    dict(grid_type=0, nlat_in=17, nlon_in=32, nlat_out=9, nlon_out=16, theta=0.45),     # downsampling
+    dict(grid_type=1, nlat_in=12, nlon_in=24, nlat_out=12, nlon_out=24, theta=0.6),     # equal grids
+])
+def test_neighbor_lists_at_every_output_point(gd):
+    # eq. (5) evaluated by the oracle for every (output, input) pair against the library's shift-reused lists
+    g = _init(gd)
+    for h in range(gd["nlat_out"]):
+        for w in range(gd["nlon_out"]):
+            want = np.flatnonzero(O.indicator_point(gd["grid_type"], gd["nlat_in"], gd["nlon_in"], gd["nlat_out"],
+                                                    gd["nlon_out"], gd["theta"], h, w).reshape(-1))
+            got = S.s2_grid_get_neighbors_at(g, h, w)
+            assert got.dtype == np.int32 and np.array_equal(got, want), (h, w)
+
+
+def test_incommensurate_longitudes_rejected():
+    with pytest.raises(S.S2Error) as ei:
+        S.s2_grid_init(0, 9, 16, 9, 24, 0.5)
+    assert ei.value.code == S.S2_ERR_UNSUPPORTED

@@ -32,6 +32,9 @@ SMALL = [
     # Gauss-Lobatto grid
     dict(kind="nattn", grid_type=3, nlat_in=13, nlon_in=24, nlat_out=13, nlon_out=24, theta=0.6,
          batch=1, heads=2, d=4, dtype="f32"),
+    # upsampling (more output than input longitudes): only the per-pair form of eq. (5) applies
+    dict(kind="nattn", grid_type=0, nlat_in=7, nlon_in=8, nlat_out=13, nlon_out=24, theta=0.7,
+         batch=1, heads=2, d=4, dtype="f32"),
 ]
 
 
@@ -45,6 +48,10 @@ def _inputs(c, seed):
 def test_forward_backward_vs_dense_torch(ci, brute):
     c = SMALL[ci]
     g = grid_dict(c)
+    if not brute and g["nlon_in"] % g["nlon_out"] != 0:
+        with pytest.raises(Exception):      # the shift form of App. B.3 needs nlon_in = pscale * nlon_out
+            O.nattn_fwd(g, *_inputs(c, 10 + ci)[:3], 1.0, brute=False)
+        return
     q, k, v, dout = _inputs(c, 10 + ci)
     scale = 1 / math.sqrt(c["d"])
     out, lse = O.nattn_fwd(g, q, k, v, scale, brute=brute)
