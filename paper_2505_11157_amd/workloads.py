@@ -31,6 +31,10 @@ CONFIGS = {
             theta=2 * math.pi / 128, batch=2, heads=4, d=32, dtype="f32"),
     5: dict(kind="global", grid_type=EQUIANGULAR, nlat_in=65, nlon_in=128, nlat_out=65, nlon_out=128,
             theta=math.pi, batch=4, heads=8, d=64, dtype="bf16"),
+    # not one of the five reference workloads: the mirror image of workload 4 (a decoder's upsampling layer,
+    # queries on the fine grid, keys and values on the coarse one), used to measure the upsampling path
+    6: dict(kind="nattn", grid_type=EQUIANGULAR, nlat_in=129, nlon_in=256, nlat_out=257, nlon_out=512,
+            theta=2 * math.pi / 128, batch=2, heads=4, d=32, dtype="f32"),
 }
 
 
