@@ -42,7 +42,7 @@ __device__ __forceinline__ void arc_of(const S2DeviceTables &t, int h, int w, in
 // logit stays near 1e-7 instead of growing with |log2 omega| ~ 10..20.
 template <int DMAX>
 __global__ void __launch_bounds__(64)
-nattn_fwd_generic(S2DeviceTables t, int nbh, int d, int e, float qscale,
+nattn_fwd_generic(S2DeviceTables t, int nbh, int first_row, int d, int e, float qscale,
                   const float *__restrict__ q, const float *__restrict__ k, const float *__restrict__ v,
                   float *__restrict__ out, float *__restrict__ lse)
 {
@@ -50,7 +50,7 @@ nattn_fwd_generic(S2DeviceTables t, int nbh, int d, int e, float qscale,
     int id = blockIdx.x;
     const int tile = id % ntile; id /= ntile;
     const int bh = id % nbh;
-    const int h = t.row_order[id / nbh];
+    const int h = t.row_order[first_row + id / nbh];
     const int w = tile * 64 + threadIdx.x;
     if (w >= t.nlon_out) return;
 
@@ -76,35 +76,46 @@ nattn_fwd_generic(S2DeviceTables t, int nbh, int d, int e, float qscale,
             float s[kChunk];
             int col[kChunk];
             float mc = -INFINITY;
+            // channel by channel: the chunk's eight columns of one channel row are neighbours in memory, so the
+            // eight loads of a channel hit the same cache lines (offsets past the arc re-read its last column)
 #pragma unroll
             for (int j = 0; j < kChunk; ++j) {
-                col[j] = wrap(first + t0 + j, t.nlon_in);
-                s[j] = -INFINITY;
-                if (t0 + j < c) {
-                    float dot = 0.f;
+                col[j] = wrap(first + min(t0 + j, c - 1), t.nlon_in);
+                s[j] = 0.f;
+            }
 #pragma unroll
-                    for (int l = 0; l < DMAX; ++l)
-                        if (l < d) dot = fmaf(qr[l], kb[l * si + col[j]], dot);
-                    s[j] = dot;
+            for (int l = 0; l < DMAX; ++l)
+                if (l < d) {
+                    const float *kr = kb + l * si;
+#pragma unroll
+                    for (int j = 0; j < kChunk; ++j) s[j] = fmaf(qr[l], kr[col[j]], s[j]);
                 }
+#pragma unroll
+            for (int j = 0; j < kChunk; ++j) {
+                s[j] = t0 + j < c ? s[j] : -INFINITY;
                 mc = fmaxf(mc, s[j]);
             }
             const float m_new = fmaxf(m, mc);
             const float corr = __builtin_amdgcn_exp2f(m - m_new);
             m = m_new;
             lsum *= corr;
-#pragma unroll
-            for (int l = 0; l < DMAX; ++l) acc[l] *= corr;
+            float p[kChunk];
 #pragma unroll
             for (int j = 0; j < kChunk; ++j) {
-                if (t0 + j < c) {
-                    const float p = wq * __builtin_amdgcn_exp2f(s[j] - m_new);
-                    lsum += p;
-#pragma unroll
-                    for (int l = 0; l < DMAX; ++l)
-                        if (l < e) acc[l] = fmaf(p, vb[l * si + col[j]], acc[l]);
-                }
+                p[j] = wq * __builtin_amdgcn_exp2f(s[j] - m_new);      // 0 past the arc
+                lsum += p[j];
             }
+#pragma unroll
+            for (int l = 0; l < DMAX; ++l)
+                if (l < e) {
+                    const float *vr = vb + l * si;
+                    float a = acc[l] * corr;
+#pragma unroll
+                    for (int j = 0; j < kChunk; ++j) a = fmaf(p[j], vr[col[j]], a);
+                    acc[l] = a;
+                } else {
+                    acc[l] = 0.f;
+                }
         }
     }
     const float inv = 1.f / lsum;
@@ -156,19 +167,43 @@ nattn_bwd_dq_generic(S2DeviceTables t, int nbh, int d, int e, float scale,
         const float wq = t.omega_rel[hp];
         const float *kb = k + size_t(bh) * d * si + size_t(hp) * t.nlon_in;
         const float *vb = v + size_t(bh) * e * si + size_t(hp) * t.nlon_in;
-        for (int tt = 0; tt < c; ++tt) {
-            const int col = wrap(first + tt, t.nlon_in);
-            float kr[DMAX];
-            float dot = 0.f, gv = -Di;
+        for (int t0 = 0; t0 < c; t0 += kChunk) {
+            // channel by channel over a chunk of eight columns (see the forward); K rows are read twice, the
+            // second time from the cache
+            int col[kChunk];
+            float dot[kChunk], gv[kChunk];
 #pragma unroll
-            for (int l = 0; l < DMAX; ++l) {
-                kr[l] = l < d ? kb[l * si + col] : 0.f;
-                dot = fmaf(qr[l], kr[l], dot);
-                if (l < e) gv = fmaf(gr[l], vb[l * si + col], gv);
+            for (int j = 0; j < kChunk; ++j) {
+                col[j] = wrap(first + min(t0 + j, c - 1), t.nlon_in);
+                dot[j] = 0.f;
+                gv[j] = -Di;
             }
-            const float dS = wq * __builtin_amdgcn_exp2f(dot - lse2) * gv;
 #pragma unroll
-            for (int l = 0; l < DMAX; ++l) dqr[l] = fmaf(dS, kr[l], dqr[l]);
+            for (int l = 0; l < DMAX; ++l)
+                if (l < d) {
+                    const float *kr = kb + l * si;
+#pragma unroll
+                    for (int j = 0; j < kChunk; ++j) dot[j] = fmaf(qr[l], kr[col[j]], dot[j]);
+                }
+#pragma unroll
+            for (int l = 0; l < DMAX; ++l)
+                if (l < e) {
+                    const float *vr = vb + l * si;
+#pragma unroll
+                    for (int j = 0; j < kChunk; ++j) gv[j] = fmaf(gr[l], vr[col[j]], gv[j]);
+                }
+#pragma unroll
+            for (int j = 0; j < kChunk; ++j)
+                dot[j] = t0 + j < c ? wq * __builtin_amdgcn_exp2f(dot[j] - lse2) * gv[j] : 0.f;      // dS
+#pragma unroll
+            for (int l = 0; l < DMAX; ++l)
+                if (l < d) {
+                    const float *kr = kb + l * si;
+                    float a = dqr[l];
+#pragma unroll
+                    for (int j = 0; j < kChunk; ++j) a = fmaf(dot[j], kr[col[j]], a);
+                    dqr[l] = a;
+                }
         }
     }
 #pragma unroll
@@ -281,7 +316,7 @@ int launch_fwd(const S2DeviceTables &t, int nbh, int d, int e, float scale, cons
     const int ntile = (t.nlon_out + 63) / 64;
     const long nblk = long(ntile) * nbh * t.nlat_out;
     S2TraceScope tr("nattn_fwd_generic", nbh * (t.fwd_pairs[0] + t.fwd_pairs[1] + t.fwd_pairs[2] + t.fwd_pairs[3]), st);
-    hipLaunchKernelGGL(nattn_fwd_generic<DMAX>, dim3((unsigned)nblk), dim3(64), 0, st, t, nbh, d, e,
+    hipLaunchKernelGGL(nattn_fwd_generic<DMAX>, dim3((unsigned)nblk), dim3(64), 0, st, t, nbh, 0, d, e,
                        scale * 1.4426950408889634f, q, k, v, out, lse);
     return 0;
 }
