@@ -527,6 +527,9 @@ int check_global(const s2_grid_t *g, int batch, int heads, int d, int dtype)
     if (dtype != S2_BF16) return s2_fail(S2_ERR_UNSUPPORTED, "global attention supports S2_BF16 only");
     if (d != kD) return s2_fail(S2_ERR_UNSUPPORTED, "global attention supports head dimension 64 only");
     if (!g->on_device) return s2_fail(S2_ERR_DEVICE, "grid handle has no device tables (no HIP device at init)");
+    // one workgroup per (slice, block of 128 tokens): the launch grid must fit 31 bits
+    const long nunits = long(batch) * heads * ((long(g->nlat_in) * g->nlon_in + 127) / 128);
+    if (nunits > (1l << 30)) return s2_fail(S2_ERR_INVALID_ARG, "batch*heads*tokens too large for one launch");
     return S2_OK;
 }
 
