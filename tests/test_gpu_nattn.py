@@ -256,6 +256,50 @@ def test_hip_graph_replays_match_eager():
             assert torch.equal(a, b), "replay %d: %s differs from the eager result" % (rep, name)
 
 
+def test_upsampling_full_size_invariants():
+    # 129x256 -> 257x512 (the mirror image of workload 4) is too large for the oracle's per-pair form: properties
+    # that hold at any size instead.  One slice, d = 32, shape-agnostic kernels with per-class arc tables.
+    c = dict(CONFIGS[6], batch=1, heads=1)
+    gd = grid_dict(c)
+    g = _grid(gd)
+    d, r = c["d"], c["nlon_out"] // c["nlon_in"]
+    scale = 1 / math.sqrt(d)
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device="cpu").manual_seed(11)
+    q = torch.randn((1, 1, d, c["nlat_out"], c["nlon_out"]), generator=gen).to(dev)
+    k = torch.randn((1, 1, d, c["nlat_in"], c["nlon_in"]), generator=gen).to(dev)
+    v = torch.randn((1, 1, d, c["nlat_in"], c["nlon_in"]), generator=gen).to(dev)
+    go = torch.randn((1, 1, d, c["nlat_out"], c["nlon_out"]), generator=gen).to(dev)
+    out, lse = S.s2_nattn_fwd(g, q, k, v, scale)
+    dq, dk, dv = S.s2_nattn_bwd(g, q, k, v, out, lse, go, scale)
+    # sum_j p_ij = 1: dv sums to dout per channel; the logits are bilinear: sum q.dq = sum k.dk
+    assert torch.allclose(dv.double().sum((3, 4)), go.double().sum((3, 4)), rtol=1e-6, atol=1e-4)
+    a, b = (q.double() * dq.double()).sum().item(), (k.double() * dk.double()).sum().item()
+    assert abs(a - b) <= 1e-6 * max(abs(a), abs(b)) + 1e-4
+    # constant v: the output is that constant and dq, dk vanish; constant k: dq vanishes
+    vc = torch.full_like(v, 0.75)
+    oc, lc = S.s2_nattn_fwd(g, q, k, vc, scale)
+    assert torch.allclose(oc, torch.full_like(oc, 0.75), rtol=0, atol=2e-6)
+    assert torch.equal(lc, lse)
+    dqc, dkc, _ = S.s2_nattn_bwd(g, q, k, vc, oc, lc, go, scale)
+    assert dqc.abs().max().item() < 2e-5 and dkc.abs().max().item() < 2e-5
+    kc = torch.ones_like(k) * 0.3
+    o2, l2 = S.s2_nattn_fwd(g, q, kc, v, scale)
+    dq2, _, _ = S.s2_nattn_bwd(g, q, kc, v, o2, l2, go, scale)
+    assert dq2.abs().max().item() < 2e-5
+    # q = 0: lse = ln(sum of the weights in the disk), between the cap area of a slightly smaller and a slightly
+    # larger cap (2 pi (1 - cos theta)), and out is the weighted mean of v
+    o3, l3 = S.s2_nattn_fwd(g, torch.zeros_like(q), k, v, scale)
+    area = torch.exp(l3.double())
+    th = c["theta"]
+    cap = lambda t: 2 * math.pi * (1 - math.cos(t))
+    assert area.min().item() > cap(0.8 * th) and area.max().item() < cap(1.25 * th)
+    # longitude shift: input rolled by one step = output rolled by r steps, bit for bit
+    o4, l4 = S.s2_nattn_fwd(g, torch.roll(q, r, 4), torch.roll(k, 1, 4), torch.roll(v, 1, 4), scale)
+    assert torch.equal(o4, torch.roll(out, r, 4)) and torch.equal(l4, torch.roll(lse, r, 3))
+    torch.cuda.synchronize()
+
+
 def test_errors_on_device():
     gd = grid_dict(1)
     g = _grid(gd)
