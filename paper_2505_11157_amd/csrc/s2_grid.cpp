@@ -390,6 +390,20 @@ extern "C" int s2_grid_init(int grid_type, int nlat_in, int nlon_in, int nlat_ou
                     g->ucnt[at] = c;
                     g->ulo[at] = start;
                 }
+        // an output between two input meridians is farther from every input point than the one on the meridian:
+        // it can be left without a (positive-weight) neighbor although class 0 has one
+        for (int h = 0; h < nlat_out; ++h)
+            for (int sc = 0; sc < r; ++sc) {
+                bool positive = false;
+                for (int b = 0; b < g->band_n[h]; ++b)
+                    positive = positive || (g->ucnt[(size_t(h) * r + sc) * g->band_max + b] > 0 &&
+                                            g->omega_in[g->band_lo[h] + b] > 0.0);
+                if (!positive) {
+                    delete g;
+                    return s2_fail(S2_ERR_EMPTY_NEIGHBORHOOD,
+                                   "an output point has no input point of positive weight within theta_cutoff");
+                }
+            }
     }
 
     // canonical CSR: ascending h'*nlon_in + w', w' in [0, nlon_in)

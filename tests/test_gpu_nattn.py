@@ -256,6 +256,47 @@ def test_hip_graph_replays_match_eager():
             assert torch.equal(a, b), "replay %d: %s differs from the eager result" % (rep, name)
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_random_small_grids(seed):
+    # seeded random tiny problems over all grid types, equal / downsampling / upsampling longitude ratios,
+    # unequal latitude counts, arbitrary head widths (d != e included), against the oracle's per-pair form
+    rng = np.random.default_rng(9000 + seed)
+    gt = int(rng.integers(0, 4))
+    nlon_lo = int(rng.integers(3, 13))
+    ratio = int(rng.choice([1, 1, 2, 3, 4]))
+    up = bool(rng.integers(0, 2))
+    nlon_in, nlon_out = (nlon_lo, nlon_lo * ratio) if up else (nlon_lo * ratio, nlon_lo)
+    nlat_in, nlat_out = int(rng.integers(3, 15)), int(rng.integers(3, 15))
+    theta = float(rng.uniform(0.6, 2.2))
+    d, e = int(rng.integers(1, 21)), int(rng.integers(1, 21))
+    nbh = int(rng.integers(1, 4))
+    gd = dict(grid_type=gt, nlat_in=nlat_in, nlon_in=nlon_in, nlat_out=nlat_out, nlon_out=nlon_out, theta=theta)
+    try:
+        g = _grid(gd)
+    except S.S2Error as err:      # a cutoff that leaves some output without a (positive-weight) neighbor
+        assert err.code in (S.S2_ERR_EMPTY_NEIGHBORHOOD, S.S2_ERR_AMBIGUOUS_CUTOFF)
+        pytest.skip("cutoff rejected for this random grid")
+    q = rng.standard_normal((nbh, d, nlat_out, nlon_out)).astype(np.float32)
+    k = rng.standard_normal((nbh, d, nlat_in, nlon_in)).astype(np.float32)
+    v = rng.standard_normal((nbh, e, nlat_in, nlon_in)).astype(np.float32)
+    go = rng.standard_normal((nbh, e, nlat_out, nlon_out)).astype(np.float32)
+    scale = float(rng.uniform(0.1, 0.6))
+    dev = torch.device("cuda:0")
+    t = lambda a: torch.from_numpy(a).to(dev).reshape((1,) + a.shape).contiguous()
+    out, lse = S.s2_nattn_fwd(g, t(q), t(k), t(v), scale)
+    dq, dk, dv = S.s2_nattn_bwd(g, t(q), t(k), t(v), out, lse, t(go), scale)
+    torch.cuda.synchronize()
+    a64 = [a.astype(np.float64) for a in (q, k, v, go)]
+    r_out, r_lse = O.nattn_fwd(gd, a64[0], a64[1], a64[2], scale, brute=True)
+    r_dq, r_dk, r_dv = O.nattn_bwd(gd, *a64, scale, brute=True)
+    n = lambda x: x[0].cpu().numpy().astype(np.float64)
+    _close_fwd(n(out), r_out, "out")
+    _close_fwd(n(lse), r_lse, "lse")
+    _close_grad(n(dq), r_dq, "dq")
+    _close_grad(n(dk), r_dk, "dk")
+    _close_grad(n(dv), r_dv, "dv")
+
+
 def test_upsampling_full_size_invariants():
     # 129x256 -> 257x512 (the mirror image of workload 4) is too large for the oracle's per-pair form: properties
     # that hold at any size instead.  One slice, d = 32, shape-agnostic kernels with per-class arc tables.

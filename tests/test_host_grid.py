@@ -133,3 +133,31 @@ def test_incommensurate_longitudes_rejected():
     with pytest.raises(S.S2Error) as ei:
         S.s2_grid_init(0, 9, 16, 9, 24, 0.5)
     assert ei.value.code == S.S2_ERR_UNSUPPORTED
+
+
+@pytest.mark.parametrize("seed", range(120))
+def test_random_grids_neighbor_lists(seed):
+    # seeded random grids (all types, equal / downsampling / upsampling ratios, unequal latitude counts): the library's
+    # arc tables, expanded for every output point, against eq. (5) evaluated per pair by the oracle
+    rng = np.random.default_rng(5000 + seed)
+    gt = int(rng.integers(0, 4))
+    nlon_lo = int(rng.integers(1, 14))
+    ratio = int(rng.choice([1, 2, 3, 4, 5]))
+    up = bool(rng.integers(0, 2))
+    nlon_in, nlon_out = (nlon_lo, nlon_lo * ratio) if up else (nlon_lo * ratio, nlon_lo)
+    gd = dict(grid_type=gt, nlat_in=int(rng.integers(2, 16)), nlon_in=nlon_in, nlat_out=int(rng.integers(2, 16)),
+              nlon_out=nlon_out, theta=float(rng.uniform(0.05, math.pi)))
+    masks = [[O.indicator_point(gd["grid_type"], gd["nlat_in"], gd["nlon_in"], gd["nlat_out"], gd["nlon_out"],
+                                gd["theta"], h, w).reshape(-1) for w in range(nlon_out)] for h in range(gd["nlat_out"])]
+    om = O.omega(gt, gd["nlat_in"], nlon_in)
+    tok_w = np.repeat(om, nlon_in)
+    every_output_sees_weight = all((tok_w[m.astype(bool)] > 0).any() for row in masks for m in row)
+    try:
+        g = _init(gd)
+    except S.S2Error as err:
+        assert err.code == S.S2_ERR_EMPTY_NEIGHBORHOOD and not every_output_sees_weight
+        return
+    assert every_output_sees_weight
+    for h in range(gd["nlat_out"]):
+        for w in range(nlon_out):
+            assert np.array_equal(S.s2_grid_get_neighbors_at(g, h, w), np.flatnonzero(masks[h][w])), (h, w)
