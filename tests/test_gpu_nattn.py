@@ -256,7 +256,7 @@ def test_hip_graph_replays_match_eager():
             assert torch.equal(a, b), "replay %d: %s differs from the eager result" % (rep, name)
 
 
-@pytest.mark.parametrize("seed", range(24))
+@pytest.mark.parametrize("seed", range(64))
 def test_random_small_grids(seed):
     # seeded random tiny problems over all grid types, equal / downsampling / upsampling longitude ratios,
     # unequal latitude counts, arbitrary head widths (d != e included), against the oracle's per-pair form
@@ -295,6 +295,30 @@ def test_random_small_grids(seed):
     _close_grad(n(dq), r_dq, "dq")
     _close_grad(n(dk), r_dk, "dk")
     _close_grad(n(dv), r_dv, "dv")
+
+
+@pytest.mark.parametrize("seed", range(48))
+def test_random_tuned_shapes(seed):
+    # seeded random medium-size problems on the tuned kernels (d = e = 32, longitude counts that are multiples of
+    # 4 from 72 up, equal grids or 2:1 downsampling, all grid types, random cutoffs and slice counts): whichever mix of
+    # matrix-core, streaming, split and one-wave launches the dispatch picks must match the oracle
+    rng = np.random.default_rng(7000 + seed)
+    gt = int(rng.integers(0, 4))
+    ps = int(rng.integers(1, 3))
+    nlon_out = 4 * int(rng.integers(18, 66))
+    nlat_out = int(rng.integers(9, 40))
+    nlat_in = nlat_out if rng.integers(0, 2) else int(rng.integers(9, 40))
+    theta = float(rng.uniform(1.5, 6.0)) * math.pi / nlat_out
+    c = dict(kind="nattn", grid_type=gt, nlat_in=nlat_in, nlon_in=nlon_out * ps, nlat_out=nlat_out, nlon_out=nlon_out,
+             theta=theta, batch=int(rng.integers(1, 4)), heads=int(rng.integers(1, 4)), d=32, dtype="f32")
+    try:
+        _grid(grid_dict(c))
+    except S.S2Error as err:
+        assert err.code in (S.S2_ERR_EMPTY_NEIGHBORHOOD, S.S2_ERR_AMBIGUOUS_CUTOFF)
+        pytest.skip("cutoff rejected for this random grid")
+    c, arrs = make_inputs(c, seed=300 + seed)
+    nbh = c["batch"] * c["heads"]
+    run_case(c, arrs, [int(rng.integers(0, nbh))])
 
 
 def test_upsampling_full_size_invariants():
