@@ -60,6 +60,20 @@ def test_global_small_grids(gt, nlat, nlon, B, H):
     run_global(gt, nlat, nlon, B, H, arrs, range(B * H), rel=4e-2 if N < 8 else 2e-2)
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_global_random_grids(seed):
+    # seeded random grids of every type (token counts that are and are not multiples of 32, 64 and 128; longitude
+    # counts that do and do not make a 32-key tile lie on one latitude), random slice counts and scales
+    rng = np.random.default_rng(4000 + seed)
+    gt = int(rng.integers(0, 4))
+    nlat, nlon = int(rng.integers(2, 30)), int(rng.choice([1, 3, 8, 12, 16, 20, 32, 33, 64]))
+    B, H = int(rng.integers(1, 3)), int(rng.integers(1, 4))
+    N = nlat * nlon
+    arrs = [round_to_bf16(rng.standard_normal((B * H, N, 64)).astype(np.float32)) for _ in range(4)]
+    scale = float(rng.uniform(0.05, 0.2)) * (1 if rng.integers(0, 4) else -1)
+    run_global(gt, nlat, nlon, B, H, arrs, [int(rng.integers(0, B * H))], scale=scale, rel=4e-2 if N < 8 else 2e-2)
+
+
 def test_global_config5_slice():
     c, arrs = make_inputs(5)
     nbh = c["batch"] * c["heads"]
