@@ -422,36 +422,58 @@ extern "C" int s2_grid_init(int grid_type, int nlat_in, int nlon_in, int nlat_ou
         g->row_ptr[h + 1] = int64_t(g->col.size());
     }
 
-    // latitudes sorted by work (pairs per point), heaviest first: launch order for load balance
-    auto order_by_work = [](int n_rows, const std::vector<int> &n, const std::vector<int> &tab, int bmax,
-                            std::vector<int> &order) {
-        std::vector<long> work(n_rows, 0);
-        for (int r = 0; r < n_rows; ++r)
-            for (int b = 0; b < n[r]; ++b) work[r] += tab[size_t(r) * bmax + b];
-        order.resize(n_rows);
+    // work of a latitude: offsets per output point (summed over its band), resp. per input latitude over its
+    // transposed band, with the number of (output, input) pairs it stands for.  Upsampling: mean over the longitude classes
+    // (forward) and the sum over output latitudes and classes of the arcs that hold an input point (backward).
+    std::vector<long> work_out(nlat_out, 0), work_in(nlat_in, 0);
+    std::vector<double> pairs_out(nlat_out, 0.0), pairs_in(nlat_in, 0.0);
+    if (g->upscale > 1) {
+        const int r = g->upscale;
+        for (int h = 0; h < nlat_out; ++h)
+            for (int sc = 0; sc < r; ++sc)
+                for (int b = 0; b < g->band_n[h]; ++b) {
+                    const int c = g->ucnt[(size_t(h) * r + sc) * g->band_max + b];
+                    work_out[h] += c;
+                    work_in[g->band_lo[h] + b] += c;
+                }
+        for (int h = 0; h < nlat_out; ++h) {
+            pairs_out[h] = double(work_out[h]) * nlon_in;
+            work_out[h] = (work_out[h] + r - 1) / r;
+        }
+        for (int hp = 0; hp < nlat_in; ++hp) pairs_in[hp] = double(work_in[hp]) * nlon_in;
+    } else {
+        for (int h = 0; h < nlat_out; ++h)
+            for (int b = 0; b < g->band_n[h]; ++b) work_out[h] += g->cnt[size_t(h) * g->band_max + b];
+        for (int hp = 0; hp < nlat_in; ++hp)
+            for (int b = 0; b < g->tband_n[hp]; ++b) work_in[hp] += g->tcnt[size_t(hp) * g->tband_max + b];
+        for (int h = 0; h < nlat_out; ++h) pairs_out[h] = double(work_out[h]) * nlon_out;
+        for (int hp = 0; hp < nlat_in; ++hp) pairs_in[hp] = double(work_in[hp]) * nlon_out;
+    }
+    // latitudes sorted by work, heaviest first: launch order for load balance
+    auto order_by_work = [](const std::vector<long> &work, std::vector<int> &order) {
+        order.resize(work.size());
         std::iota(order.begin(), order.end(), 0);
         std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return work[a] > work[b]; });
     };
-    order_by_work(nlat_out, g->band_n, g->cnt, g->band_max, g->row_order);
-    order_by_work(nlat_in, g->tband_n, g->tcnt, g->tband_max, g->trow_order);
+    order_by_work(work_out, g->row_order);
+    order_by_work(work_in, g->trow_order);
     // split classes: a latitude whose disk holds more than 260 * P / 2 offsets per point is split P ways
     constexpr long T = 260;
-    auto classify = [](int n_rows, const std::vector<int> &n, const std::vector<int> &tab, int bmax, long thr,
-                       int (&cls)[4], double (&pairs)[4], double per_entry) {
+    auto classify = [](const std::vector<long> &work, const std::vector<double> &row_pairs, long thr, int (&cls)[4],
+                       double (&pairs)[4]) {
         cls[0] = cls[1] = cls[2] = cls[3] = 0;
         pairs[0] = pairs[1] = pairs[2] = pairs[3] = 0.0;
-        for (int r = 0; r < n_rows; ++r) {
-            long work = 0;
-            for (int b = 0; b < n[r]; ++b) work += tab[size_t(r) * bmax + b];
-            const int c = work > 4 * thr ? 0 : work > 2 * thr ? 1 : work > thr ? 2 : 3;
+        for (size_t r = 0; r < work.size(); ++r) {
+            const long w = work[r];
+            const int c = w > 4 * thr ? 0 : w > 2 * thr ? 1 : w > thr ? 2 : 3;
             ++cls[c];
-            pairs[c] += double(work) * per_entry;
+            pairs[c] += row_pairs[r];
         }
     };
-    classify(nlat_out, g->band_n, g->cnt, g->band_max, T, g->dt.fwd_cls, g->dt.fwd_pairs, double(nlon_out));
-    classify(nlat_in, g->tband_n, g->tcnt, g->tband_max, T, g->dt.bwd_cls, g->dt.bwd_pairs, double(nlon_out));
-    classify(nlat_out, g->band_n, g->cnt, g->band_max, T / 4, g->dt.fwd_cls_fine, g->dt.fwd_pairs_fine, double(nlon_out));
-    classify(nlat_in, g->tband_n, g->tcnt, g->tband_max, T / 4, g->dt.bwd_cls_fine, g->dt.bwd_pairs_fine, double(nlon_out));
+    classify(work_out, pairs_out, T, g->dt.fwd_cls, g->dt.fwd_pairs);
+    classify(work_in, pairs_in, T, g->dt.bwd_cls, g->dt.bwd_pairs);
+    classify(work_out, pairs_out, T / 4, g->dt.fwd_cls_fine, g->dt.fwd_pairs_fine);
+    classify(work_in, pairs_in, T / 4, g->dt.bwd_cls_fine, g->dt.bwd_pairs_fine);
 
     // streaming plan for the light latitudes (work <= T): they must form one contiguous range whose bands
     // move monotonically, with short odd arcs (at most 65 offsets) on every row of the band

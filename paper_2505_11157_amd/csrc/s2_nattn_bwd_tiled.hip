@@ -70,16 +70,19 @@ struct StageOff {
 };
 
 // xw = first window column (already in [0, ncol)), ncol = longitudes of the streamed grid
+// Window column x of the streamed row lies at float x * cmul + cadd of that row (1, 0 except for the class view of
+// an upsampling grid, where the outputs of one class are cmul floats apart).
 template <int PS>
-__device__ __forceinline__ StageOff stage_offsets(int xw, int ncol, size_t sstride, int lane)
+__device__ __forceinline__ StageOff stage_offsets(int xw, int ncol, size_t sstride, int lane, int cmul = 1, int cadd = 0)
 {
     StageOff o;
 #pragma unroll
-    for (int a = 0; a < 2; ++a) o.full[a] = 4u * unsigned(wrap2(xw + lane + 64 * a, ncol));
+    for (int a = 0; a < 2; ++a) o.full[a] = 4u * unsigned(wrap2(xw + lane + 64 * a, ncol) * cmul + cadd);
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
         const int e = lane + 64 * u, row = e >> 3, col = e & 7;
-        o.tail[u] = unsigned(chan_of_row(row) * sstride * sizeof(float)) + 4u * unsigned(wrap2(xw + 64 * PS + col, ncol));
+        o.tail[u] = unsigned(chan_of_row(row) * sstride * sizeof(float)) +
+                    4u * unsigned(wrap2(xw + 64 * PS + col, ncol) * cmul + cadd);
     }
     return o;
 }
@@ -301,7 +304,8 @@ __device__ __forceinline__ void merge_sum(float *smem, int wave, int lane, int P
     }
 }
 
-template <int PS, int WAVES>
+// UP: class view of an upsampling grid (see the forward kernel): owners are the outputs w = U*u + s of one class.
+template <int PS, int WAVES, bool UP = false>
 __global__ void __launch_bounds__(64 * WAVES, 2)
 nattn_bwd_dq_tiled(S2DeviceTables t, int nbh, int first_row, float scale, const float *__restrict__ q,
                    const float *__restrict__ k, const float *__restrict__ v, const float *__restrict__ o,
@@ -314,16 +318,22 @@ nattn_bwd_dq_tiled(S2DeviceTables t, int nbh, int first_row, float scale, const 
     const int wave = WAVES == 1 ? 0 : __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
     float *buf0 = smem + wave * 2 * G::TILE, *buf1 = buf0 + G::TILE;
-    const int nseg = (t.nlon_out + kSegB - 1) / kSegB;
+    static_assert(!UP || PS == 1, "class view of an upsampling grid is an equal-grid problem");
+    const int U = UP ? t.upscale : 1;
+    const int nlon_v = UP ? t.nlon_in : t.nlon_out;       // outputs per class
+    const int nseg = ((nlon_v + kSegB - 1) / kSegB) * U;
     const Task tk = decode_task<WAVES>(t.fwd_cls, t.row_order, nseg, nbh, first_row, wave);
     const int h = tk.row, bh = tk.bh;
     const bool wave_active = bh < nbh;
     const int qd = lane & 3;
-    const int w0 = tk.seg * kSegB + 4 * (lane >> 2);
-    const bool active = wave_active && w0 < t.nlon_out;
+    const int sc = UP ? tk.seg % U : 0, seg = UP ? tk.seg / U : tk.seg;
+    const int w0 = seg * kSegB + 4 * (lane >> 2);
+    const bool active = wave_active && w0 < nlon_v;
     const LaneGeo lg = lane_geo<PS>(lane);
     const size_t so = size_t(t.nlat_out) * t.nlon_out, si = size_t(t.nlat_in) * t.nlon_in;
-    const size_t io = size_t(h) * t.nlon_out + w0;
+    const size_t io = size_t(h) * t.nlon_out + (UP ? w0 * U + sc : w0);
+    const int *ctab = (UP ? t.ucnt + size_t(h * U + sc) * t.band_max : t.cnt + size_t(h) * t.band_max);
+    const int *ltab = UP ? t.ulo + size_t(h * U + sc) * t.band_max : nullptr;
     const float qscale = scale * kLog2e;
 
     float qr[4][kDL], gr[4][kDL], dqa[4][kDL], lse2[4], Dr[4] = {0.f, 0.f, 0.f, 0.f};
@@ -332,9 +342,15 @@ nattn_bwd_dq_tiled(S2DeviceTables t, int nbh, int first_row, float scale, const 
         float4 x = make_float4(0.f, 0.f, 0.f, 0.f), y = x, z = x;
         if (active) {
             const size_t off = (size_t(bh) * D + qd * kDL + c) * so + io;
-            x = *reinterpret_cast<const float4 *>(q + off);
-            y = *reinterpret_cast<const float4 *>(go + off);
-            z = *reinterpret_cast<const float4 *>(o + off);
+            if constexpr (UP) {
+                x = make_float4(q[off], q[off + U], q[off + 2 * U], q[off + 3 * U]);
+                y = make_float4(go[off], go[off + U], go[off + 2 * U], go[off + 3 * U]);
+                z = make_float4(o[off], o[off + U], o[off + 2 * U], o[off + 3 * U]);
+            } else {
+                x = *reinterpret_cast<const float4 *>(q + off);
+                y = *reinterpret_cast<const float4 *>(go + off);
+                z = *reinterpret_cast<const float4 *>(o + off);
+            }
         }
         qr[0][c] = x.x * qscale; qr[1][c] = x.y * qscale; qr[2][c] = x.z * qscale; qr[3][c] = x.w * qscale;
         gr[0][c] = y.x; gr[1][c] = y.y; gr[2][c] = y.z; gr[3][c] = y.w;
@@ -346,16 +362,27 @@ nattn_bwd_dq_tiled(S2DeviceTables t, int nbh, int first_row, float scale, const 
     for (int r = 0; r < 4; ++r) Dr[r] = quad_sum(Dr[r]);
     {
         float4 L = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (active) L = *reinterpret_cast<const float4 *>(lse + size_t(bh) * so + io);
+        if constexpr (UP) {
+            const float *lp = lse + size_t(bh) * so + io;
+            if (active) L = make_float4(lp[0], lp[U], lp[2 * U], lp[3 * U]);
+        } else {
+            if (active) L = *reinterpret_cast<const float4 *>(lse + size_t(bh) * so + io);
+        }
         lse2[0] = (L.x - t.ln_omega_ref) * kLog2e; lse2[1] = (L.y - t.ln_omega_ref) * kLog2e;
         lse2[2] = (L.z - t.ln_omega_ref) * kLog2e; lse2[3] = (L.w - t.ln_omega_ref) * kLog2e;
-        if (active && qd == 0 && tk.part == 0)
-            *reinterpret_cast<float4 *>(Dws + size_t(bh) * so + io) = make_float4(Dr[0], Dr[1], Dr[2], Dr[3]);
+        if (active && qd == 0 && tk.part == 0) {
+            if constexpr (UP) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) Dws[size_t(bh) * so + io + r * U] = Dr[r];
+            } else {
+                *reinterpret_cast<float4 *>(Dws + size_t(bh) * so + io) = make_float4(Dr[0], Dr[1], Dr[2], Dr[3]);
+            }
+        }
     }
 
     const int nb = t.band_n[h], hp0 = t.band_lo[h];
     int nrun = 0;
-    for (int b = 0; b < nb; ++b) nrun += (t.cnt[h * t.band_max + b] + kNTMax - 1) / kNTMax;
+    for (int b = 0; b < nb; ++b) nrun += (ctab[b] + kNTMax - 1) / kNTMax;
     const int run_lo = tk.part * nrun / tk.P, run_hi = (tk.part + 1) * nrun / tk.P;
     int run = 0;
     if (wave_active) {
@@ -368,10 +395,11 @@ nattn_bwd_dq_tiled(S2DeviceTables t, int nbh, int first_row, float scale, const 
         for (int bb = 0; bb < nb; ++bb) {
             const int b = bb + rot < nb ? bb + rot : bb + rot - nb;
             const int hp = hp0 + b;
-            const int c = t.cnt[h * t.band_max + b];
+            const int c = ctab[b];
+            if (UP && c == 0) continue;                     // this class misses the latitude
             const int nchunk = (c + kNTMax - 1) / kNTMax;
             if (run + nchunk <= run_lo || run >= run_hi) { run += nchunk; continue; }
-            const int lo = (c == t.nlon_in) ? 0 : -((c - 1) >> 1);
+            const int lo = (c == t.nlon_in) ? 0 : UP ? ltab[b] : -((c - 1) >> 1);
             const float wq = t.omega_rel[hp];
             const float *kb = k + size_t(bh) * D * si + size_t(hp) * t.nlon_in;
             const float *vb = v + size_t(bh) * D * si + size_t(hp) * t.nlon_in;
@@ -380,7 +408,7 @@ nattn_bwd_dq_tiled(S2DeviceTables t, int nbh, int first_row, float scale, const 
             for (int ci = 0; ci < nchunk; ++ci, ++run) {
                 const int nt = base + (ci < rem ? 1 : 0);
                 if (run >= run_lo && run < run_hi) {
-                    const int xw = wrap2(tk.seg * kSegB * PS + lo + t0 + t.nlon_in, t.nlon_in);
+                    const int xw = wrap2(seg * kSegB * PS + lo + t0 + t.nlon_in, t.nlon_in);
 #define S2_RUN(N) case N: run_chunk_dq<PS, N>(buf0, buf1, kb, vb, si, xw, t.nlon_in, lane, lg, wq, qr, gr, lse2, Dr, dqa); break;
                     switch (nt) {
                         S2_RUN(1) S2_RUN(2) S2_RUN(3) S2_RUN(4) S2_RUN(5) S2_RUN(6)
@@ -395,9 +423,16 @@ nattn_bwd_dq_tiled(S2DeviceTables t, int nbh, int first_row, float scale, const 
     if (WAVES > 1 && tk.P > 1) merge_sum<1>(smem, wave, lane, tk.P, tk.part, dqa, dqa);
     if (!active || tk.part != 0) return;
 #pragma unroll
-    for (int c = 0; c < kDL; ++c)
-        *reinterpret_cast<float4 *>(dq + (size_t(bh) * D + qd * kDL + c) * so + io) =
-            make_float4(dqa[0][c] * scale, dqa[1][c] * scale, dqa[2][c] * scale, dqa[3][c] * scale);
+    for (int c = 0; c < kDL; ++c) {
+        float *dp = dq + (size_t(bh) * D + qd * kDL + c) * so + io;
+        if constexpr (UP) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) dp[r * U] = dqa[r][c] * scale;
+        } else {
+            *reinterpret_cast<float4 *>(dp) =
+                make_float4(dqa[0][c] * scale, dqa[1][c] * scale, dqa[2][c] * scale, dqa[3][c] * scale);
+        }
+    }
 }
 
 // -------------------------------------------------------------- dk, dv ----------
@@ -407,7 +442,8 @@ __device__ __forceinline__ void run_chunk_dkdv(float *buf0, float *buf1, float *
                                                const float *__restrict__ gb, const float *__restrict__ lrow,
                                                const float *__restrict__ drow, size_t so, int xw, int nlon, int lane,
                                                const LaneGeo &lg, float wq, float lref2, const float (&kr)[4][kDL],
-                                               const float (&vr)[4][kDL], float (&dk)[4][kDL], float (&dv)[4][kDL])
+                                               const float (&vr)[4][kDL], float (&dk)[4][kDL], float (&dv)[4][kDL],
+                                               int cmul = 1, int cadd = 0)
 {
     using G = GeoB<1>;
     float s[4][NT], dp[4][NT];
@@ -415,13 +451,13 @@ __device__ __forceinline__ void run_chunk_dkdv(float *buf0, float *buf1, float *
     for (int r = 0; r < 4; ++r)
 #pragma unroll
         for (int tt = 0; tt < NT; ++tt) { s[r][tt] = 0.f; dp[r][tt] = 0.f; }
-    StageOff of = stage_offsets<1>(xw, nlon, so, lane);
+    StageOff of = stage_offsets<1>(xw, nlon, so, lane, cmul, cadd);
     // lse and D rows of the window: 64 columns by LDS-direct load, the last 8 by an ordinary load
     // (every lane fetches one of the 16 tail elements; duplicates store the same value)
     __builtin_amdgcn_global_load_lds((gptr_t)(reinterpret_cast<const char *>(lrow) + of.full[0]), (lptr_t)aux, 4, 0, 0);
     __builtin_amdgcn_global_load_lds((gptr_t)(reinterpret_cast<const char *>(drow) + of.full[0]),
                                      (lptr_t)(aux + G::PITCH), 4, 0, 0);
-    const int acol = wrap2(xw + 64 + (lane & 7), nlon);
+    const int acol = wrap2(xw + 64 + (lane & 7), nlon) * cmul + cadd;
     const float atail = ((lane >> 3) & 1) ? drow[acol] : lrow[acol];
     float ta[2], tb[2];
     const float *q1 = qb + size_t(kCGB) * so, *g1 = gb + size_t(kCGB) * so;
@@ -479,7 +515,10 @@ __device__ __forceinline__ void run_chunk_dkdv(float *buf0, float *buf1, float *
     axpy_stage<1, NT>(buf1, lg.sbase, s, kCGB, dv);
 }
 
-template <int WAVES>
+// UP (upsampling, nlon_out = U * nlon_in): the outputs of class s (w = U*u + s) that hold input column j on a
+// latitude are u = j - ulo - c + 1 .. j - ulo, with (c, ulo) the arc of that class; the kernel walks the classes one
+// after the other, streaming every U-th column of the q, dout, lse and D rows.
+template <int WAVES, bool UP = false>
 __global__ void __launch_bounds__(64 * WAVES, 2)
 nattn_bwd_dkdv_tiled(S2DeviceTables t, int nbh, int first_row, float scale, const float *__restrict__ q,
                      const float *__restrict__ k, const float *__restrict__ v, const float *__restrict__ lse,
@@ -493,7 +532,8 @@ nattn_bwd_dkdv_tiled(S2DeviceTables t, int nbh, int first_row, float scale, cons
     const int wave = WAVES == 1 ? 0 : __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
     float *buf0 = smem + wave * WSZ, *buf1 = buf0 + G::TILE, *aux = buf1 + G::TILE;
-    const int nlon = t.nlon_in;                       // equal grids: nlon_out == nlon_in
+    const int nlon = t.nlon_in;                       // equal grids: nlon_out == nlon_in; UP: outputs per class
+    const int nlon_o = UP ? t.nlon_out : nlon, U = UP ? t.upscale : 1;
     const int nseg = (nlon + kSegB - 1) / kSegB;
     const Task tk = decode_task<WAVES>(t.bwd_cls, t.trow_order, nseg, nbh, first_row, wave);
     const int hp = tk.row, bh = tk.bh;
@@ -523,31 +563,50 @@ nattn_bwd_dkdv_tiled(S2DeviceTables t, int nbh, int first_row, float scale, cons
     }
 
     const int nb = t.tband_n[hp], h0 = t.tband_lo[hp];
+    // arc of output offsets (count c, first offset lo) on band row b for the outputs of class sc
+    auto arc = [&](int b, int sc, int &c, int &lo) {
+        if constexpr (UP) {
+            const int h = h0 + b;
+            const int at = (h * U + sc) * t.band_max + (hp - t.band_lo[h]);
+            c = t.ucnt[at];
+            lo = (c == nlon) ? 0 : -(t.ulo[at] + c - 1);
+        } else {
+            c = t.tcnt[hp * t.tband_max + b];
+            lo = (c == nlon) ? 0 : -((c - 1) >> 1);
+        }
+    };
     int nrun = 0;
-    for (int b = 0; b < nb; ++b) nrun += (t.tcnt[hp * t.tband_max + b] + kNTMax - 1) / kNTMax;
+    for (int b = 0; b < nb; ++b)
+        for (int sc = 0; sc < U; ++sc) {
+            int c, lo;
+            arc(b, sc, c, lo);
+            nrun += (c + kNTMax - 1) / kNTMax;
+        }
     const int run_lo = tk.part * nrun / tk.P, run_hi = (tk.part + 1) * nrun / tk.P;
     int run = 0;
     if (wave_active) {
         // rotated band order (see the dq kernel): concurrent workgroups read the same latitudes together
         const int rot = (t.tband_max - h0 % t.tband_max) % t.tband_max % nb;
-        for (int bb = 0; bb < nb; ++bb) {
-            const int b = bb + rot < nb ? bb + rot : bb + rot - nb;
+        for (int bb = 0; bb < nb * U; ++bb) {
+            const int bq = UP ? bb / U : bb, sc = UP ? bb - bq * U : 0;
+            const int b = bq + rot < nb ? bq + rot : bq + rot - nb;
             const int h = h0 + b;
-            const int c = t.tcnt[hp * t.tband_max + b];
+            int c, lo;
+            arc(b, sc, c, lo);
+            if (UP && c == 0) continue;                     // no output of this class holds the owners
             const int nchunk = (c + kNTMax - 1) / kNTMax;
             if (run + nchunk <= run_lo || run >= run_hi) { run += nchunk; continue; }
-            const int lo = (c == nlon) ? 0 : -((c - 1) >> 1);
-            const float *qb = q + size_t(bh) * D * so + size_t(h) * nlon;
-            const float *gb = go + size_t(bh) * D * so + size_t(h) * nlon;
-            const float *lrow = lse + size_t(bh) * so + size_t(h) * nlon;
-            const float *drow = Dws + size_t(bh) * so + size_t(h) * nlon;
+            const float *qb = q + size_t(bh) * D * so + size_t(h) * nlon_o;
+            const float *gb = go + size_t(bh) * D * so + size_t(h) * nlon_o;
+            const float *lrow = lse + size_t(bh) * so + size_t(h) * nlon_o;
+            const float *drow = Dws + size_t(bh) * so + size_t(h) * nlon_o;
             const int base = c / nchunk, rem = c - base * nchunk;
             int t0 = 0;
             for (int ci = 0; ci < nchunk; ++ci, ++run) {
                 const int nt = base + (ci < rem ? 1 : 0);
                 if (run >= run_lo && run < run_hi) {
                     const int xw = wrap2(tk.seg * kSegB + lo + t0 + nlon, nlon);
-#define S2_RUN(N) case N: run_chunk_dkdv<N>(buf0, buf1, aux, qb, gb, lrow, drow, so, xw, nlon, lane, lg, wq, lref2, kr, vr, dka, dva); break;
+#define S2_RUN(N) case N: run_chunk_dkdv<N>(buf0, buf1, aux, qb, gb, lrow, drow, so, xw, nlon, lane, lg, wq, lref2, kr, vr, dka, dva, U, sc); break;
                     switch (nt) {
                         S2_RUN(1) S2_RUN(2) S2_RUN(3) S2_RUN(4) S2_RUN(5) S2_RUN(6)
                         S2_RUN(7) S2_RUN(8) S2_RUN(9)
@@ -800,14 +859,84 @@ nattn_bwd_dkdv2_tiled(S2DeviceTables t, int nbh, int first_row, float scale, con
 
 bool s2_nattn_bwd_tiled_supported(const S2DeviceTables &t, int d, int e)
 {
-    return t.upscale == 1 && d == 32 && e == 32 && (t.pscale == 1 || t.pscale == 2) && t.nlon_in % 4 == 0 && t.nlon_out % 4 == 0 &&
+    if (t.upscale > 1) return d == 32 && e == 32 && t.nlon_in % 4 == 0 && t.nlon_in >= 72;
+    return d == 32 && e == 32 && (t.pscale == 1 || t.pscale == 2) && t.nlon_in % 4 == 0 && t.nlon_out % 4 == 0 &&
            t.nlon_out >= 72;
 }
+
+namespace {
+
+// Upsampling grids: the split vector kernels in their class view (no matrix-core or streaming launches).
+int bwd_tiled_up(const S2DeviceTables &t_all, int nbh, float scale, const float *q, const float *k, const float *v,
+                 const float *o, const float *lse, const float *go, float *dq, float *dk, float *dv, float *Dws,
+                 hipStream_t st)
+{
+    static bool cfg_dq = false, cfg_kv = false;
+    const int nseg_o = ((t_all.nlon_in + kSegB - 1) / kSegB) * t_all.upscale, nseg_i = (t_all.nlon_in + kSegB - 1) / kSegB;
+    {
+        S2DeviceTables t = t_all;
+        s2_pick_split(t, true, nbh, nseg_o, false);
+        const int nsplit = t.fwd_cls[0] + t.fwd_cls[1] + t.fwd_cls[2];
+        const size_t lds_wave = 2 * GeoB<1>::TILE * sizeof(float);
+        if (nsplit > 0) {
+            const long nblk = long((nbh + kWavesB - 1) / kWavesB) * nseg_o * (8 * t.fwd_cls[0] + 4 * t.fwd_cls[1] + 2 * t.fwd_cls[2]);
+            size_t lds = lds_wave * kWavesB;
+            const size_t mg = size_t(kWavesB / 2) * 4 * kDL * 64 * sizeof(float);
+            if (lds < mg) lds = mg;
+            auto k8 = nattn_bwd_dq_tiled<1, kWavesB, true>;
+            if (!cfg_dq) {
+                if (hipFuncSetAttribute(reinterpret_cast<const void *>(k8), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                        int(lds)) != hipSuccess)
+                    return -1;
+                cfg_dq = true;
+            }
+            S2TraceScope tr("nattn_bwd_dq_tiled<8 waves, classes>", nbh * (t.fwd_pairs[0] + t.fwd_pairs[1] + t.fwd_pairs[2]), st);
+            hipLaunchKernelGGL(k8, dim3((unsigned)nblk), dim3(64 * kWavesB), lds, st, t, nbh, 1, scale, q, k, v, o, lse,
+                               go, dq, Dws);
+        }
+        const long nrows = t.nlat_out - nsplit;
+        if (nrows > 0) {
+            S2TraceScope tr("nattn_bwd_dq_tiled<1 wave, classes>", nbh * t.fwd_pairs[3], st);
+            hipLaunchKernelGGL((nattn_bwd_dq_tiled<1, 1, true>), dim3((unsigned)(nrows * nbh * nseg_o)), dim3(64), lds_wave,
+                               st, t, nbh, nsplit, scale, q, k, v, o, lse, go, dq, Dws);
+        }
+    }
+    S2DeviceTables t = t_all;
+    s2_pick_split(t, false, nbh, nseg_i, false);
+    const int nsplit = t.bwd_cls[0] + t.bwd_cls[1] + t.bwd_cls[2];
+    const size_t lds_wave = (2 * GeoB<1>::TILE + 2 * GeoB<1>::PITCH) * sizeof(float);
+    if (nsplit > 0) {
+        const long nblk = long((nbh + kWavesB - 1) / kWavesB) * nseg_i * (8 * t.bwd_cls[0] + 4 * t.bwd_cls[1] + 2 * t.bwd_cls[2]);
+        size_t lds = lds_wave * kWavesB;
+        const size_t mg = size_t(kWavesB / 2) * 2 * 4 * kDL * 64 * sizeof(float);
+        if (lds < mg) lds = mg;
+        auto k8 = nattn_bwd_dkdv_tiled<kWavesB, true>;
+        if (!cfg_kv) {
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(k8), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    int(lds)) != hipSuccess)
+                return -1;
+            cfg_kv = true;
+        }
+        S2TraceScope tr("nattn_bwd_dkdv_tiled<8 waves, classes>", nbh * (t.bwd_pairs[0] + t.bwd_pairs[1] + t.bwd_pairs[2]), st);
+        hipLaunchKernelGGL(k8, dim3((unsigned)nblk), dim3(64 * kWavesB), lds, st, t, nbh, 1, scale, q, k, v, lse, go, Dws,
+                           dk, dv);
+    }
+    const long nrows = t.nlat_in - nsplit;
+    if (nrows > 0) {
+        S2TraceScope tr("nattn_bwd_dkdv_tiled<1 wave, classes>", nbh * t.bwd_pairs[3], st);
+        hipLaunchKernelGGL((nattn_bwd_dkdv_tiled<1, true>), dim3((unsigned)(nrows * nbh * nseg_i)), dim3(64), lds_wave, st,
+                           t, nbh, nsplit, scale, q, k, v, lse, go, Dws, dk, dv);
+    }
+    return 0;
+}
+
+}  // namespace
 
 int s2_nattn_bwd_tiled(const S2DeviceTables &t, int nbh, int d, int e, float scale, const float *q, const float *k,
                        const float *v, const float *o, const float *lse, const float *go, float *dq, float *dk,
                        float *dv, float *Dws, hipStream_t st)
 {
+    if (t.upscale > 1) return bwd_tiled_up(t, nbh, scale, q, k, v, o, lse, go, dq, dk, dv, Dws, st);
     const int nseg_o = (t.nlon_out + kSegB - 1) / kSegB;
     static bool cfg_dq1 = false, cfg_dq2 = false, cfg_kv = false;
     static const bool no_stream = std::getenv("S2_NO_STREAM") != nullptr;   // debugging aid: one-wave kernels instead

@@ -249,7 +249,11 @@ constexpr int kState = 4 * 16 + 8; // floats of softmax state per lane: acc[4][1
 // the end), and the workgroup covers 8 / P different (batch, head) slices.
 // Near the poles of an equiangular grid a disk holds over twenty times more
 // points than at the equator; without the split those rows set the makespan.
-template <int D, int PS, int WAVES>
+//
+// UP (upsampling, nlon_out = U * nlon_in): the output longitudes w = U*u + s of one class s see the input grid
+// exactly as the outputs of an equal-grid problem do, with the arc tables of that class.  A wavefront then owns
+// 128 consecutive u of one class; its q, out and lse elements lie U floats apart.
+template <int D, int PS, int WAVES, bool UP = false>
 __global__ void __launch_bounds__(64 * WAVES, 2)
 nattn_fwd_tiled(S2DeviceTables t, int nbh, int first_row, float qscale, const float *__restrict__ q,
                 const float *__restrict__ k, const float *__restrict__ v, float *__restrict__ out,
@@ -263,7 +267,10 @@ nattn_fwd_tiled(S2DeviceTables t, int nbh, int first_row, float qscale, const fl
     const int lane = threadIdx.x & 63;
     float *buf0 = smem + wave * 2 * G::TILE, *buf1 = buf0 + G::TILE;
 
-    const int nseg = (t.nlon_out + kSeg - 1) / kSeg;
+    static_assert(!UP || PS == 1, "class view of an upsampling grid is an equal-grid problem");
+    const int U = UP ? t.upscale : 1;
+    const int nlon_v = UP ? t.nlon_in : t.nlon_out;       // outputs per class
+    const int nseg = ((nlon_v + kSeg - 1) / kSeg) * U;
     int P, seg, h, part, bh;
     if constexpr (WAVES == 1) {
         // one wavefront per workgroup, no split: block -> (latitude by work, slice, segment)
@@ -297,11 +304,15 @@ nattn_fwd_tiled(S2DeviceTables t, int nbh, int first_row, float qscale, const fl
     const bool wave_active = bh < nbh;
 
     const int p = lane >> 1, half = lane & 1;
+    const int sc = UP ? seg % U : 0;                      // class of the outputs of this workgroup
+    if constexpr (UP) seg /= U;
     const int w0 = seg * kSeg + 4 * p;
-    const bool active = wave_active && w0 < t.nlon_out;   // nlon_out is a multiple of 4: all four outputs or none
+    const bool active = wave_active && w0 < nlon_v;       // nlon_v is a multiple of 4: all four outputs or none
 
     const size_t so = size_t(t.nlat_out) * t.nlon_out, si = size_t(t.nlat_in) * t.nlon_in;
-    const size_t io = size_t(h) * t.nlon_out + w0;
+    const size_t io = size_t(h) * t.nlon_out + (UP ? w0 * U + sc : w0);
+    const int *ctab = (UP ? t.ucnt + size_t(h * U + sc) * t.band_max : t.cnt + size_t(h) * t.band_max);
+    const int *ltab = UP ? t.ulo + size_t(h * U + sc) * t.band_max : nullptr;
     // strip base (floats) in a staged buffer: the lane's channel rows start at half*kCG, its columns at 4*p*PS
     const int sbase = half * kCG * G::PITCH + 4 * p * PS;
     // window tail: lane = (channel row, one of the last 8 columns)
@@ -312,7 +323,14 @@ nattn_fwd_tiled(S2DeviceTables t, int nbh, int first_row, float qscale, const fl
 #pragma unroll
     for (int c = 0; c < DH; ++c) {
         float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (active) x = *reinterpret_cast<const float4 *>(q + (size_t(bh) * D + half * DH + c) * so + io);
+        if constexpr (UP) {
+            if (active) {
+                const float *qp = q + (size_t(bh) * D + half * DH + c) * so + io;
+                x = make_float4(qp[0], qp[U], qp[2 * U], qp[3 * U]);
+            }
+        } else {
+            if (active) x = *reinterpret_cast<const float4 *>(q + (size_t(bh) * D + half * DH + c) * so + io);
+        }
         qr[0][c] = x.x * qscale; qr[1][c] = x.y * qscale; qr[2][c] = x.z * qscale; qr[3][c] = x.w * qscale;
         acc[0][c] = acc[1][c] = acc[2][c] = acc[3][c] = 0.f;
     }
@@ -323,7 +341,8 @@ nattn_fwd_tiled(S2DeviceTables t, int nbh, int first_row, float qscale, const fl
     // this wavefront's share of the runs of latitude h
     int nrun = 0;
     for (int b = 0; b < nb; ++b) {
-        const int cb = t.cnt[h * t.band_max + b];
+        const int cb = ctab[b];
+        if (UP && cb == 0) continue;
         nrun += num_runs<PS>(cb, arc_lo(cb, t.nlon_in));
     }
     const int run_lo = part * nrun / P, run_hi = (part + 1) * nrun / P;
@@ -338,8 +357,9 @@ nattn_fwd_tiled(S2DeviceTables t, int nbh, int first_row, float qscale, const fl
         for (int bb = 0; bb < nb; ++bb) {
             const int b = bb + rot < nb ? bb + rot : bb + rot - nb;
             const int hp = hp0 + b;
-            const int c = t.cnt[h * t.band_max + b];
-            const int lo = arc_lo(c, t.nlon_in);
+            const int c = ctab[b];
+            if (UP && c == 0) continue;                     // this class misses the latitude
+            const int lo = UP && c != t.nlon_in ? ltab[b] : arc_lo(c, t.nlon_in);
             const int nchunk = num_runs<PS>(c, lo);
             if (run + nchunk <= run_lo || run >= run_hi) { run += nchunk; continue; }
             const float wq = t.omega_rel[hp];
@@ -408,22 +428,34 @@ nattn_fwd_tiled(S2DeviceTables t, int nbh, int first_row, float qscale, const fl
 #pragma unroll
     for (int r = 0; r < 4; ++r) inv[r] = 1.f / lsum[r];
 #pragma unroll
-    for (int c = 0; c < DH; ++c)
-        *reinterpret_cast<float4 *>(out + (size_t(bh) * D + half * DH + c) * so + io) =
-            make_float4(acc[0][c] * inv[0], acc[1][c] * inv[1], acc[2][c] * inv[2], acc[3][c] * inv[3]);
+    for (int c = 0; c < DH; ++c) {
+        float *op = out + (size_t(bh) * D + half * DH + c) * so + io;
+        if constexpr (UP) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) op[r * U] = acc[r][c] * inv[r];
+        } else {
+            *reinterpret_cast<float4 *>(op) =
+                make_float4(acc[0][c] * inv[0], acc[1][c] * inv[1], acc[2][c] * inv[2], acc[3][c] * inv[3]);
+        }
+    }
     if (half == 0) {
         float L[4];
 #pragma unroll
         for (int r = 0; r < 4; ++r) L[r] = (mref[r] + log2f(lsum[r] * t.omega_ref)) * 0.6931471805599453f;
-        *reinterpret_cast<float4 *>(lse + size_t(bh) * so + io) = make_float4(L[0], L[1], L[2], L[3]);
+        if constexpr (UP) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) lse[size_t(bh) * so + io + r * U] = L[r];
+        } else {
+            *reinterpret_cast<float4 *>(lse + size_t(bh) * so + io) = make_float4(L[0], L[1], L[2], L[3]);
+        }
     }
 }
 
-template <int D, int PS>
+template <int D, int PS, bool UP = false>
 int launch_fwd_tiled(const S2DeviceTables &t, int skip_rows, int nbh, float qscale, const float *q, const float *k,
                      const float *v, float *out, float *lse, hipStream_t st)
 {   // t.row_order already points past the skip_rows latitudes another kernel has taken
-    const int nseg = (t.nlon_out + kSeg - 1) / kSeg;
+    const int nseg = UP ? ((t.nlon_in + kSeg - 1) / kSeg) * t.upscale : (t.nlon_out + kSeg - 1) / kSeg;
     const int nsplit = t.fwd_cls[0] + t.fwd_cls[1] + t.fwd_cls[2];   // latitudes split over several wavefronts
     constexpr int mode = 0;   // 1: everything through the one-wave kernel, 2: everything through the 8-wave kernel
     // heavy latitudes: 8-wave workgroups with an in-LDS merge
@@ -433,7 +465,7 @@ int launch_fwd_tiled(const S2DeviceTables &t, int skip_rows, int nbh, float qsca
                           (8 * t.fwd_cls[0] + 4 * t.fwd_cls[1] + 2 * t.fwd_cls[2] + (first_row ? 0 : t.fwd_cls[3]));
         constexpr size_t stage_fl = size_t(kWaves) * 2 * Geo<PS>::TILE, merge_fl = size_t(kWaves / 2) * kState * 64;
         const size_t lds = (stage_fl > merge_fl ? stage_fl : merge_fl) * sizeof(float);
-        auto kern = nattn_fwd_tiled<D, PS, kWaves>;
+        auto kern = nattn_fwd_tiled<D, PS, kWaves, UP>;
         static bool configured = false;   // raise the dynamic LDS limit once (above 64 KiB needs the attribute)
         if (!configured) {
             if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -451,12 +483,12 @@ int launch_fwd_tiled(const S2DeviceTables &t, int skip_rows, int nbh, float qsca
     const int first_row = mode == 1 ? 0 : nsplit;
     const long nrows = t.nlat_out - skip_rows - first_row;
     static const bool no_stream = std::getenv("S2_NO_STREAM") != nullptr;   // debugging aid: one-wave kernel instead
-    if (nrows > 0 && mode == 0 && !no_stream && s2_nattn_stream_supported(t, D, D))
+    if (!UP && nrows > 0 && mode == 0 && !no_stream && s2_nattn_stream_supported(t, D, D))
         return s2_nattn_fwd_stream(t, nbh, qscale, q, k, v, out, lse, st);
     if (nrows > 0) {
         S2TraceScope tr("nattn_fwd_tiled<1 wave>",
                         nbh * (t.fwd_pairs[3] + (mode == 1 ? t.fwd_pairs[0] + t.fwd_pairs[1] + t.fwd_pairs[2] : 0.0)), st);
-        hipLaunchKernelGGL((nattn_fwd_tiled<D, PS, 1>), dim3((unsigned)(nrows * nbh * nseg)), dim3(64),
+        hipLaunchKernelGGL((nattn_fwd_tiled<D, PS, 1, UP>), dim3((unsigned)(nrows * nbh * nseg)), dim3(64),
                            2 * Geo<PS>::TILE * sizeof(float), st, t, nbh, first_row, qscale, q, k, v, out, lse);
     }
     return 0;
@@ -466,7 +498,8 @@ int launch_fwd_tiled(const S2DeviceTables &t, int skip_rows, int nbh, float qsca
 
 bool s2_nattn_fwd_tiled_supported(const S2DeviceTables &t, int d, int e)
 {
-    return t.upscale == 1 && d == 32 && e == 32 && (t.pscale == 1 || t.pscale == 2) && t.nlon_in % 4 == 0 && t.nlon_out % 4 == 0 &&
+    if (t.upscale > 1) return d == 32 && e == 32 && t.nlon_in % 4 == 0 && t.nlon_in >= 72;
+    return d == 32 && e == 32 && (t.pscale == 1 || t.pscale == 2) && t.nlon_in % 4 == 0 && t.nlon_out % 4 == 0 &&
            t.nlon_out >= 72;   // (window wrap logic handles at most two turns of the circle)
 }
 
@@ -474,6 +507,12 @@ int s2_nattn_fwd_tiled(const S2DeviceTables &t, int nbh, int d, int e, float sca
                        const float *v, float *out, float *lse, hipStream_t st)
 {
     const float qscale = scale * 1.4426950408889634f;
+    if (t.upscale > 1) {
+        // upsampling: every class of output longitudes is an equal-grid problem for the split vector kernels
+        S2DeviceTables tu = t;
+        s2_pick_split(tu, true, nbh, ((t.nlon_in + kSeg - 1) / kSeg) * t.upscale, false);
+        return launch_fwd_tiled<32, 1, true>(tu, 0, nbh, qscale, q, k, v, out, lse, st);
+    }
     // dense polar latitudes go to the matrix-core kernel; the vector kernels see the remaining latitudes
     S2DeviceTables tv = t;
     const int nm = s2_nattn_fwd_mfma_rows(t, d, e);

@@ -105,6 +105,12 @@ SMALL = [
     dict(kind="nattn", grid_type=1, nlat_in=12, nlon_in=24, nlat_out=16, nlon_out=72, theta=0.4, batch=2, heads=1, d=32, dtype="f32"),
     dict(kind="nattn", grid_type=0, nlat_in=9, nlon_in=20, nlat_out=17, nlon_out=80, theta=0.6, batch=1, heads=1, d=5, dtype="f32"),
     dict(kind="nattn", grid_type=0, nlat_in=6, nlon_in=10, nlat_out=9, nlon_out=20, theta=math.pi, batch=1, heads=1, d=3, dtype="f32"),
+    # upsampling on the tuned kernels (d = 32, at least 72 input longitudes, a multiple of 4): every class of output
+    # longitudes as an equal-grid problem; 2x, 3x, 4x, nine slices, a ragged last segment, full circles at the poles
+    dict(kind="nattn", grid_type=0, nlat_in=13, nlon_in=76, nlat_out=25, nlon_out=152, theta=0.5, batch=3, heads=3, d=32, dtype="f32"),
+    dict(kind="nattn", grid_type=1, nlat_in=12, nlon_in=72, nlat_out=16, nlon_out=216, theta=0.4, batch=1, heads=2, d=32, dtype="f32"),
+    dict(kind="nattn", grid_type=0, nlat_in=17, nlon_in=132, nlat_out=33, nlon_out=528, theta=0.3, batch=1, heads=1, d=32, dtype="f32"),
+    dict(kind="nattn", grid_type=3, nlat_in=9, nlon_in=80, nlat_out=9, nlon_out=160, theta=1.0, batch=1, heads=2, d=32, dtype="f32"),
 ]
 
 
@@ -321,9 +327,31 @@ def test_random_tuned_shapes(seed):
     run_case(c, arrs, [int(rng.integers(0, nbh))])
 
 
+@pytest.mark.parametrize("seed", range(16))
+def test_random_tuned_upsampling(seed):
+    # the same for upsampling grids (2x, 3x, 4x) on the tuned kernels, against the oracle's per-pair form
+    rng = np.random.default_rng(7500 + seed)
+    gt = int(rng.integers(0, 4))
+    up = int(rng.integers(2, 5))
+    nlon_in = 4 * int(rng.integers(18, 41))
+    nlat_in = int(rng.integers(7, 22))
+    nlat_out = nlat_in if rng.integers(0, 2) else int(rng.integers(7, 22))
+    theta = float(rng.uniform(1.5, 6.0)) * math.pi / min(nlat_in, nlat_out)
+    c = dict(kind="nattn", grid_type=gt, nlat_in=nlat_in, nlon_in=nlon_in, nlat_out=nlat_out, nlon_out=nlon_in * up,
+             theta=theta, batch=int(rng.integers(1, 4)), heads=int(rng.integers(1, 4)), d=32, dtype="f32")
+    try:
+        _grid(grid_dict(c))
+    except S.S2Error as err:
+        assert err.code in (S.S2_ERR_EMPTY_NEIGHBORHOOD, S.S2_ERR_AMBIGUOUS_CUTOFF)
+        pytest.skip("cutoff rejected for this random grid")
+    c, arrs = make_inputs(c, seed=400 + seed)
+    nbh = c["batch"] * c["heads"]
+    run_case(c, arrs, [int(rng.integers(0, nbh))])
+
+
 def test_upsampling_full_size_invariants():
     # 129x256 -> 257x512 (the mirror image of workload 4) is too large for the oracle's per-pair form: properties
-    # that hold at any size instead.  One slice, d = 32, shape-agnostic kernels with per-class arc tables.
+    # that hold at any size instead.  One slice, d = 32, tuned kernels in their class view.
     c = dict(CONFIGS[6], batch=1, heads=1)
     gd = grid_dict(c)
     g = _grid(gd)
