@@ -66,8 +66,8 @@ enum {
  * pscale = nlon_in / nlon_out (equal grids and downsampling).  Upsampling
  * (nlon_out = r * nlon_in): output longitude w = r*m + s lies between input
  * meridians unless s = 0, so every latitude gets r lists (one per s), each
- * reused for every m by the shift w' -> w' + m; these grids run on the
- * shape-agnostic kernels.  Both grids have the same grid_type.
+ * reused for every m by the shift w' -> w' + m.  Both grids have the same
+ * grid_type.
  *
  * If a HIP device is present the compact tables are uploaded to the current
  * device; without a device the handle is host-only (the introspection calls
