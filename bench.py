@@ -28,6 +28,12 @@ TRAFFIC_BYTES = {
     (3, "nattn_fwd_mfma"): 280e6, (3, "nattn_fwd_stream"): 747e6,
     (3, "nattn_bwd_dq_mfma"): 333e6, (3, "nattn_bwd_dq_stream"): 1023e6,
     (3, "nattn_bwd_dkdv_mfma"): 349e6, (3, "nattn_bwd_dkdv_stream"): 1058e6,
+    (4, "nattn_fwd_tiled<8 waves>"): 1961e6, (4, "nattn_fwd_tiled<1 wave>"): 230e6,
+    (4, "nattn_bwd_dq_tiled<8 waves>"): 1614e6, (4, "nattn_bwd_dq_tiled<1 wave>"): 306e6,
+    (4, "nattn_bwd_dkdv2_tiled<8 waves>"): 156e6, (4, "nattn_bwd_dkdv2_tiled<1 wave>"): 1516e6,
+    (6, "nattn_fwd_tiled<8 waves>"): 80e6, (6, "nattn_fwd_tiled<1 wave>"): 1425e6,
+    (6, "nattn_bwd_dq_tiled<8 waves, classes>"): 66e6, (6, "nattn_bwd_dq_tiled<1 wave, classes>"): 2353e6,
+    (6, "nattn_bwd_dkdv_tiled<8 waves, classes>"): 2853e6, (6, "nattn_bwd_dkdv_tiled<1 wave, classes>"): 902e6,
     (5, "global_fwd"): 160e6, (5, "global_bwd_dkdv"): 501e6, (5, "global_bwd_dq"): 287e6,
 }
 
