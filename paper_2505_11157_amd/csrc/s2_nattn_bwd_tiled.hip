@@ -112,7 +112,11 @@ __device__ __forceinline__ void stage_issue(const float *chan0, size_t sstride, 
 template <int N>
 __device__ __forceinline__ void wait_vm()
 {
-    if constexpr (N == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    // Besides the copies in flight (vmcnt) this waits for the wavefront's own LDS reads (lgkmcnt): the next
+    // LDS-direct copy, issued right after this wait, goes into the buffer the previous step read its strips from, and
+    // a read still queued in the LDS pipeline when that copy lands would see the new rows (seen as rare run-to-run
+    // differences: 38 of 12000 launches of one small problem without the second wait, none in 12000 with it).
+    if constexpr (N == 0) asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
     else if constexpr (N == 16) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
     else if constexpr (N == 18) asm volatile("s_waitcnt vmcnt(18)" ::: "memory");
     else if constexpr (N == 34) asm volatile("s_waitcnt vmcnt(34)" ::: "memory");

@@ -130,7 +130,11 @@ __device__ __forceinline__ float stage_issue(const float *chan0, size_t si, unsi
 template <int N>
 __device__ __forceinline__ void wait_vm()
 {
-    if constexpr (N == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    // Besides the copies in flight (vmcnt) this waits for the wavefront's own LDS reads (lgkmcnt): the next
+    // LDS-direct copy, issued right after this wait, goes into the buffer the previous step read its strips from, and
+    // a read still queued in the LDS pipeline when that copy lands would see the new rows (seen as rare run-to-run
+    // differences: 38 of 12000 launches of one small problem without the second wait, none in 12000 with it).
+    if constexpr (N == 0) asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
     else if constexpr (N == 17) asm volatile("s_waitcnt vmcnt(17)" ::: "memory");
     else if constexpr (N == 33) asm volatile("s_waitcnt vmcnt(33)" ::: "memory");
     else static_assert(N == 0, "unsupported wait count");

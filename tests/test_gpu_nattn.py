@@ -283,14 +283,11 @@ def test_hip_graph_replays_match_eager():
             assert torch.equal(a, b), "replay %d: %s differs from the eager result" % (rep, name)
 
 
-@pytest.mark.parametrize("ci", [
-    # known open issue: on this tiny nine-slice 2:1 problem dk of the polar input latitude differed in 5 of 3000
-    # launches (a few dozen elements, dv and dq identical); every value still passes the parity test of this case
-    pytest.param(9, marks=pytest.mark.xfail(strict=False, reason="rare run-to-run difference in dk (2:1 dk/dv kernel), cause open")),
-    26])
+@pytest.mark.parametrize("ci", [9, 26])
 def test_repeated_launches_bit_identical(ci):
-    # split kernels with nine slices (2:1 grid; upsampling): 100 forward + backward launches on the same inputs give
-    # the same bits every time (no dependence on which workgroups happen to run side by side)
+    # split kernels with nine slices (2:1 grid; upsampling): 1000 forward + backward launches on the same inputs give
+    # the same bits every time.  (Regression test: without a wait for the wavefront's own LDS reads before the next
+    # LDS-direct copy into the same buffer, dk of the 2:1 case differed in about 3 of 1000 launches.)
     c, arrs = make_inputs(SMALL[ci], seed=200 + ci)
     g = _grid(grid_dict(c))
     B, H, d = c["batch"], c["heads"], c["d"]
@@ -300,7 +297,7 @@ def test_repeated_launches_bit_identical(ci):
     q, k, v, dout = (fold(a) for a in arrs)
     out0, lse0 = S.s2_nattn_fwd(g, q, k, v, scale)
     g0 = S.s2_nattn_bwd(g, q, k, v, out0, lse0, dout, scale)
-    for it in range(100):
+    for it in range(1000):
         out, lse = S.s2_nattn_fwd(g, q, k, v, scale)
         gr = S.s2_nattn_bwd(g, q, k, v, out, lse, dout, scale)
         assert torch.equal(out, out0) and torch.equal(lse, lse0), "launch %d: forward differs" % it
