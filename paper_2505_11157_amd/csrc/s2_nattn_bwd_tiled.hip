@@ -385,10 +385,7 @@ nattn_bwd_dq_tiled(S2DeviceTables t, int nbh, int first_row, float scale, const 
     }
 
     const int nb = t.band_n[h], hp0 = t.band_lo[h];
-    int nrun = 0;
-    for (int b = 0; b < nb; ++b) nrun += (ctab[b] + kNTMax - 1) / kNTMax;
-    const int run_lo = tk.part * nrun / tk.P, run_hi = (tk.part + 1) * nrun / tk.P;
-    int run = 0;
+    int run = 0;   // runs are dealt out to the P wavefronts of a task in turn (see the forward kernel)
     if (wave_active) {
         // Band rows are visited in a rotated order: first the one whose absolute latitude index is 0 modulo
         // the band size, and so on.  Workgroups of neighbouring latitudes run at the same time and advance at
@@ -402,7 +399,7 @@ nattn_bwd_dq_tiled(S2DeviceTables t, int nbh, int first_row, float scale, const 
             const int c = ctab[b];
             if (UP && c == 0) continue;                     // this class misses the latitude
             const int nchunk = (c + kNTMax - 1) / kNTMax;
-            if (run + nchunk <= run_lo || run >= run_hi) { run += nchunk; continue; }
+            if (((tk.part - run) & (tk.P - 1)) >= nchunk) { run += nchunk; continue; }   // none of these runs is mine
             const int lo = (c == t.nlon_in) ? 0 : UP ? ltab[b] : -((c - 1) >> 1);
             const float wq = t.omega_rel[hp];
             const float *kb = k + size_t(bh) * D * si + size_t(hp) * t.nlon_in;
@@ -411,7 +408,7 @@ nattn_bwd_dq_tiled(S2DeviceTables t, int nbh, int first_row, float scale, const 
             int t0 = 0;
             for (int ci = 0; ci < nchunk; ++ci, ++run) {
                 const int nt = base + (ci < rem ? 1 : 0);
-                if (run >= run_lo && run < run_hi) {
+                if ((run & (tk.P - 1)) == tk.part) {
                     const int xw = wrap2(seg * kSegB * PS + lo + t0 + t.nlon_in, t.nlon_in);
 #define S2_RUN(N) case N: run_chunk_dq<PS, N>(buf0, buf1, kb, vb, si, xw, t.nlon_in, lane, lg, wq, qr, gr, lse2, Dr, dqa); break;
                     switch (nt) {
@@ -579,14 +576,6 @@ nattn_bwd_dkdv_tiled(S2DeviceTables t, int nbh, int first_row, float scale, cons
             lo = (c == nlon) ? 0 : -((c - 1) >> 1);
         }
     };
-    int nrun = 0;
-    for (int b = 0; b < nb; ++b)
-        for (int sc = 0; sc < U; ++sc) {
-            int c, lo;
-            arc(b, sc, c, lo);
-            nrun += (c + kNTMax - 1) / kNTMax;
-        }
-    const int run_lo = tk.part * nrun / tk.P, run_hi = (tk.part + 1) * nrun / tk.P;
     int run = 0;
     if (wave_active) {
         // rotated band order (see the dq kernel): concurrent workgroups read the same latitudes together
@@ -599,7 +588,7 @@ nattn_bwd_dkdv_tiled(S2DeviceTables t, int nbh, int first_row, float scale, cons
             arc(b, sc, c, lo);
             if (UP && c == 0) continue;                     // no output of this class holds the owners
             const int nchunk = (c + kNTMax - 1) / kNTMax;
-            if (run + nchunk <= run_lo || run >= run_hi) { run += nchunk; continue; }
+            if (((tk.part - run) & (tk.P - 1)) >= nchunk) { run += nchunk; continue; }   // none of these runs is mine
             const float *qb = q + size_t(bh) * D * so + size_t(h) * nlon_o;
             const float *gb = go + size_t(bh) * D * so + size_t(h) * nlon_o;
             const float *lrow = lse + size_t(bh) * so + size_t(h) * nlon_o;
@@ -608,7 +597,7 @@ nattn_bwd_dkdv_tiled(S2DeviceTables t, int nbh, int first_row, float scale, cons
             int t0 = 0;
             for (int ci = 0; ci < nchunk; ++ci, ++run) {
                 const int nt = base + (ci < rem ? 1 : 0);
-                if (run >= run_lo && run < run_hi) {
+                if ((run & (tk.P - 1)) == tk.part) {
                     const int xw = wrap2(tk.seg * kSegB + lo + t0 + nlon, nlon);
 #define S2_RUN(N) case N: run_chunk_dkdv<N>(buf0, buf1, aux, qb, gb, lrow, drow, so, xw, nlon, lane, lg, wq, lref2, kr, vr, dka, dva, U, sc); break;
                     switch (nt) {
@@ -799,6 +788,7 @@ nattn_bwd_dkdv2_tiled(S2DeviceTables t, int nbh, int first_row, float scale, con
     // slots per band row: full circle -> nlon_o slots from 0; arc of half-width hw -> hw + 1 slots from -(hw / 2)
     const int nb = t.tband_n[hp], h0 = t.tband_lo[hp];
     auto nslots = [&](int c) { return c == nlon_i ? nlon_o : ((c - 1) >> 1) + 1; };
+    // contiguous shares of the run list (dealing the runs out in turn, as the other kernels do, was slower here)
     int nrun = 0;
     for (int b = 0; b < nb; ++b) nrun += (nslots(t.tcnt[hp * t.tband_max + b]) + kNTMax - 1) / kNTMax;
     const int run_lo = tk.part * nrun / tk.P, run_hi = (tk.part + 1) * nrun / tk.P;

@@ -342,14 +342,10 @@ nattn_fwd_tiled(S2DeviceTables t, int nbh, int first_row, float qscale, const fl
     for (int r = 0; r < 4; ++r) { mref[r] = -INFINITY; lsum[r] = 0.f; }
 
     const int nb = t.band_n[h], hp0 = t.band_lo[h];
-    // this wavefront's share of the runs of latitude h
-    int nrun = 0;
-    for (int b = 0; b < nb; ++b) {
-        const int cb = ctab[b];
-        if (UP && cb == 0) continue;
-        nrun += num_runs<PS>(cb, arc_lo(cb, t.nlon_in));
-    }
-    const int run_lo = part * nrun / P, run_hi = (part + 1) * nrun / P;
+    // This wavefront's share of the runs of latitude h: every P-th run.  The P wavefronts then work on neighbouring
+    // runs of the same input latitude at the same time, whose windows overlap almost entirely, so a row is fetched
+    // into the L2 once and staged from there (with contiguous shares each wavefront walked its own band rows and the
+    // workgroup kept eight rows alive).
     int run = 0;
     if (wave_active) {
         // Band rows are visited in a rotated order: first the one whose absolute latitude index is 0 modulo
@@ -365,7 +361,7 @@ nattn_fwd_tiled(S2DeviceTables t, int nbh, int first_row, float qscale, const fl
             if (UP && c == 0) continue;                     // this class misses the latitude
             const int lo = UP && c != t.nlon_in ? ltab[b] : arc_lo(c, t.nlon_in);
             const int nchunk = num_runs<PS>(c, lo);
-            if (run + nchunk <= run_lo || run >= run_hi) { run += nchunk; continue; }
+            if (((part - run) & (P - 1)) >= nchunk) { run += nchunk; continue; }   // none of these runs is mine
             const float wq = t.omega_rel[hp];
             const float *kb = k + size_t(bh) * D * si + size_t(hp) * t.nlon_in;
             const float *vb = v + size_t(bh) * D * si + size_t(hp) * t.nlon_in;
@@ -375,7 +371,7 @@ nattn_fwd_tiled(S2DeviceTables t, int nbh, int first_row, float qscale, const fl
             for (int ci = 0; ci < nchunk; ++ci, ++run) {
                 const int nt = G::ALIGNED ? (ci == nchunk - 1 ? span - 8 * ci : 8) : base + (ci < rem ? 1 : 0);
                 const int lead = ci == 0 ? lead0 : 0;
-                if (run >= run_lo && run < run_hi) {
+                if ((run & (P - 1)) == part) {
                     int xw = seg * kSeg * PS + lo + t0 + 2 * t.nlon_in;      // first window column
                     xw = xw >= t.nlon_in ? xw - t.nlon_in : xw;
                     xw = xw >= t.nlon_in ? xw - t.nlon_in : xw;
