@@ -28,9 +28,9 @@ TRAFFIC_BYTES = {
     (3, "nattn_fwd_mfma"): 280e6, (3, "nattn_fwd_stream"): 747e6,
     (3, "nattn_bwd_dq_mfma"): 333e6, (3, "nattn_bwd_dq_stream"): 1023e6,
     (3, "nattn_bwd_dkdv_mfma"): 349e6, (3, "nattn_bwd_dkdv_stream"): 1058e6,
-    (4, "nattn_fwd_tiled<8 waves>"): 962e6, (4, "nattn_fwd_tiled<1 wave>"): 230e6,
-    (4, "nattn_bwd_dq_tiled<8 waves>"): 528e6, (4, "nattn_bwd_dq_tiled<1 wave>"): 301e6,
-    (4, "nattn_bwd_dkdv2_tiled<8 waves>"): 154e6, (4, "nattn_bwd_dkdv2_tiled<1 wave>"): 1379e6,
+    (4, "nattn_fwd_tiled<8 waves>"): 981e6, (4, "nattn_fwd_tiled<1 wave>"): 228e6,
+    (4, "nattn_bwd_dq_tiled<8 waves>"): 534e6, (4, "nattn_bwd_dq_tiled<1 wave>"): 290e6,
+    (4, "nattn_bwd_dkdv2_tiled<8 waves>"): 159e6, (4, "nattn_bwd_dkdv2_tiled<1 wave>"): 1457e6,
     (6, "nattn_fwd_tiled<8 waves>"): 80e6, (6, "nattn_fwd_tiled<1 wave>"): 1425e6,
     (6, "nattn_bwd_dq_tiled<8 waves, classes>"): 66e6, (6, "nattn_bwd_dq_tiled<1 wave, classes>"): 2353e6,
     (6, "nattn_bwd_dkdv_tiled<8 waves, classes>"): 2853e6, (6, "nattn_bwd_dkdv_tiled<1 wave, classes>"): 902e6,
