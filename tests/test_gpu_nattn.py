@@ -111,6 +111,9 @@ SMALL = [
     dict(kind="nattn", grid_type=1, nlat_in=12, nlon_in=72, nlat_out=16, nlon_out=216, theta=0.4, batch=1, heads=2, d=32, dtype="f32"),
     dict(kind="nattn", grid_type=0, nlat_in=17, nlon_in=132, nlat_out=33, nlon_out=528, theta=0.3, batch=1, heads=1, d=32, dtype="f32"),
     dict(kind="nattn", grid_type=3, nlat_in=9, nlon_in=80, nlat_out=9, nlon_out=160, theta=1.0, batch=1, heads=2, d=32, dtype="f32"),
+    # larger and odd longitude ratios (8x, 5x)
+    dict(kind="nattn", grid_type=0, nlat_in=7, nlon_in=72, nlat_out=9, nlon_out=576, theta=0.7, batch=1, heads=2, d=32, dtype="f32"),
+    dict(kind="nattn", grid_type=1, nlat_in=10, nlon_in=84, nlat_out=6, nlon_out=420, theta=0.45, batch=2, heads=1, d=32, dtype="f32"),
 ]
 
 
