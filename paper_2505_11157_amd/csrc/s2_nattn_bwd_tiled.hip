@@ -33,12 +33,15 @@ constexpr int kDL = 8;       // channels per lane (head dimension 32)
 constexpr int kWavesB = 8;
 constexpr float kLog2e = 1.4426950408889634f;
 
-// Row-major staged window of kRows channel rows x (64*PS + 8) columns.  The
+// Row-major staged window of kRows channel rows x (64*PS + 8) columns.  PS = 1: the
 // pitch is 4 mod 16: the four rows a lane quad reads (r, r+4, r+8, r+12) start
 // 16 banks apart, so 4 quads x 4 lanes x b128 cover the 64 banks exactly once.
+// PS = 2: the strips of neighbouring quads start 8 floats apart, so the rows of the four lane quarters must start
+// at banks 0, 32, 4, 36: pitch 8 mod 16 (quarters 32 banks apart) and the rows of quarters 2 and 3 moved up by 4 floats.
 template <int PS>
 struct GeoB {
-    static constexpr int PITCH = PS == 1 ? 84 : 148;
+    static constexpr int PITCH = PS == 1 ? 84 : 152;
+    static constexpr __host__ __device__ int shift(int row) { return PS == 2 && row >= 8 ? 4 : 0; }
     static constexpr int NFULL = PS;                       // full 64-column loads per row
     static constexpr int NLOAD = kRows * NFULL + 2;        // vector-memory loads per stage (2 = tail)
     static constexpr int TILE = kRows * PITCH;
@@ -104,7 +107,7 @@ __device__ __forceinline__ void stage_issue(const float *chan0, size_t sstride, 
     for (int r = 0; r < kRows; ++r) {
 #pragma unroll
         for (int a = 0; a < G::NFULL; ++a)
-            __builtin_amdgcn_global_load_lds((gptr_t)(rb + o.full[a]), (lptr_t)(buf + r * G::PITCH + 64 * a), 4, 0, 0);
+            __builtin_amdgcn_global_load_lds((gptr_t)(rb + o.full[a]), (lptr_t)(buf + r * G::PITCH + G::shift(r) + 64 * a), 4, 0, 0);
         rb += ((r & 3) == 3) ? rs * (kDL - kCGB + 1) : rs;
     }
 }
@@ -183,11 +186,11 @@ __device__ __forceinline__ LaneGeo lane_geo(int lane)
 {
     using G = GeoB<PS>;
     LaneGeo g;
-    g.sbase = (lane & 3) * kCGB * G::PITCH + 4 * (lane >> 2) * PS;
+    g.sbase = (lane & 3) * kCGB * G::PITCH + G::shift((lane & 3) * kCGB) + 4 * (lane >> 2) * PS;
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
         const int e = lane + 64 * u;
-        g.taddr[u] = (e >> 3) * G::PITCH + 64 * PS + (e & 7);
+        g.taddr[u] = (e >> 3) * G::PITCH + G::shift(e >> 3) + 64 * PS + (e & 7);
     }
     return g;
 }

@@ -44,7 +44,11 @@ constexpr int kCG = 4;       // channels per half staged together
 // instructions, and the copy path moves 16-byte pieces about 1.5 times faster than dwords.
 template <int PS>
 struct Geo {
-    static constexpr int PITCH = kSeg * PS + 8;
+    // PS = 2: the strips of neighbouring lane pairs start 8 floats apart; the rows of the second channel half are
+    // moved up by 4 floats (pitch 8 mod 16 puts them 32 banks on, the shift makes it 36), so that the 16 lanes a
+    // ds_read_b128 serves together cover the 64 banks once
+    static constexpr int PITCH = PS == 2 ? 280 : kSeg * PS + 8;
+    static constexpr __host__ __device__ int shift(int row) { return PS == 2 && row >= kCG ? 4 : 0; }
     static constexpr bool ALIGNED = PS == 2;                  // windows start at a multiple of 4 columns
     static constexpr int LCOLS = ALIGNED ? 4 : 1;             // columns per lane and copy instruction
     static constexpr int NFULL = kSeg * PS / (64 * LCOLS);    // full 64-lane copies per row
@@ -119,7 +123,7 @@ __device__ __forceinline__ float stage_issue(const float *chan0, size_t si, unsi
 #pragma unroll
         for (int a = 0; a < G::NFULL; ++a)
             if constexpr (G::LCOLS == 4)
-                __builtin_amdgcn_global_load_lds((gptr_t)(rb + voff[a]), (lptr_t)(buf + r * G::PITCH + 256 * a), 16, 0, 0);
+                __builtin_amdgcn_global_load_lds((gptr_t)(rb + voff[a]), (lptr_t)(buf + r * G::PITCH + G::shift(r) + 256 * a), 16, 0, 0);
             else
                 __builtin_amdgcn_global_load_lds((gptr_t)(rb + voff[a]), (lptr_t)(buf + r * G::PITCH + 64 * a), 4, 0, 0);
         rb += (r == kCG - 1) ? rs * (D / 2 - kCG + 1) : rs;
@@ -318,11 +322,11 @@ nattn_fwd_tiled(S2DeviceTables t, int nbh, int first_row, float qscale, const fl
     const int *ctab = (UP ? t.ucnt + size_t(h * U + sc) * t.band_max : t.cnt + size_t(h) * t.band_max);
     const int *ltab = UP ? t.ulo + size_t(h * U + sc) * t.band_max : nullptr;
     // strip base (floats) in a staged buffer: the lane's channel rows start at half*kCG, its columns at 4*p*PS
-    const int sbase = half * kCG * G::PITCH + 4 * p * PS;
+    const int sbase = half * kCG * G::PITCH + G::shift(half * kCG) + 4 * p * PS;
     // window tail: lane = (channel row, one of the last 8 columns)
     const int trl = lane >> 3;
     const unsigned trow = unsigned((trl < kCG ? trl : trl - kCG + DH) * si * sizeof(float));
-    const int taddr = trl * G::PITCH + kSeg * PS + (lane & 7);
+    const int taddr = trl * G::PITCH + G::shift(trl) + kSeg * PS + (lane & 7);
     float qr[4][DH], acc[4][DH], mref[4], lsum[4];
 #pragma unroll
     for (int c = 0; c < DH; ++c) {
