@@ -16,6 +16,7 @@ from .s2_oracle import (  # noqa: F401
     indicator,
     indicator_point,
     nattn_bwd,
+    nattn_cond,
     nattn_fwd,
     neighbor_csr,
     omega,

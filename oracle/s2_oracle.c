@@ -417,6 +417,134 @@ int s2o_nattn_bwd(int grid_type, int nlat_in, int nlon_in, int nlat_out, int nlo
     return 0;
 }
 
+/* First-order rounding sensitivity of the forward and backward results (a
+ * yardstick for the float32 parity tolerance, not part of the method).
+ *
+ * Every result of App. B.1 / B.4 is a sum of products of the inputs.  If each
+ * elementary product is perturbed by a relative amount of at most u, the
+ * result moves by at most u times the sum of the absolute values of those
+ * products, each counted once per factor that carries the perturbation:
+ *   a_ij    = |scale| sum_l |q_il| |k_jl|                (terms of the logit)
+ *   c_lse_i = 1 + sum_j p_ij a_ij                        (d lse = sum_j p_ij d s_ij, + the log)
+ *   w_ij    = 1 + a_ij + c_lse_i                         (relative budget of p_ij = exp(s_ij - lse_i))
+ *   c_out_ic = sum_j p_ij |v_jc| w_ij
+ *   G_ij    = sum_c |dout_ic| |v_jc|,   Dabs_i = sum_c |dout_ic| c_out_ic   (D_i = dout_i . out_i)
+ *   t_ij    = |dout_i . v_j - D_i| w_ij + G_ij + Dabs_i  (budget of dS_ij / p_ij)
+ *   c_dq_il = |scale| sum_{j in N(i)} p_ij t_ij |k_jl|
+ *   c_dk_jl = |scale| sum_{i: j in N(i)} p_ij t_ij |q_il|
+ *   c_dv_jc = sum_{i: j in N(i)} p_ij w_ij |dout_ic|
+ * With all inputs positive, scale > 0 and w, t replaced by 1 these sums are
+ * the results themselves (c_out = out, c_dv = dv); the tests pin the full
+ * expressions against a dense evaluation. */
+int s2o_nattn_cond(int grid_type, int nlat_in, int nlon_in, int nlat_out, int nlon_out, double theta,
+                   int brute, int nbh, int d, int e, double scale,
+                   const double *q, const double *k, const double *v, const double *dout,
+                   double *c_out, double *c_lse, double *c_dq, double *c_dk, double *c_dv)
+{
+    s2o_ctx C;
+    int rc = ctx_init(&C, grid_type, nlat_in, nlon_in, nlat_out, nlon_out, theta, brute);
+    if (rc) { ctx_free(&C); return rc; }
+    size_t so = (size_t)nlat_out * nlon_out, si = (size_t)nlat_in * nlon_in;
+    long total_o = (long)nbh * (long)so, total_i = (long)nbh * (long)si;
+    double *lse = malloc(sizeof(double) * (size_t)total_o);
+    double *D = malloc(sizeof(double) * (size_t)total_o);
+    double *Dabs = malloc(sizeof(double) * (size_t)total_o);
+    double ascale = fabs(scale);
+#pragma omp parallel
+    {
+        double *s = malloc(sizeof(double) * si);
+        double *oi = malloc(sizeof(double) * e);
+        double *ci = malloc(sizeof(double) * e);
+#pragma omp for schedule(dynamic, 16)
+        for (long t = 0; t < total_o; ++t) {
+            int b = (int)(t / (long)so);
+            int i = (int)(t % (long)so);
+            int h = i / nlon_out, w = i % nlon_out;
+            const double *qb = q + (size_t)b * d * so, *kb = k + (size_t)b * d * si, *vb = v + (size_t)b * e * si;
+            const double *gb = dout + (size_t)b * e * so;
+            double m = point_logits(&C, d, scale, qb, kb, h, w, s);
+            double Z = 0.0;
+            for (size_t j = 0; j < si; ++j)
+                if (s[j] != -INFINITY) Z += exp(s[j] - m);
+            double L = m + log(Z);
+            /* c_lse, then out and c_out */
+            double cl = 1.0;
+            for (size_t j = 0; j < si; ++j) {
+                if (s[j] == -INFINITY) continue;
+                double a = 0.0;
+                for (int l = 0; l < d; ++l) a += fabs(qb[l * so + i]) * fabs(kb[l * si + j]);
+                cl += exp(s[j] - L) * ascale * a;
+            }
+            for (int c = 0; c < e; ++c) { oi[c] = 0.0; ci[c] = 0.0; }
+            for (size_t j = 0; j < si; ++j) {
+                if (s[j] == -INFINITY) continue;
+                double a = 0.0;
+                for (int l = 0; l < d; ++l) a += fabs(qb[l * so + i]) * fabs(kb[l * si + j]);
+                double p = exp(s[j] - L), wij = 1.0 + ascale * a + cl;
+                for (int c = 0; c < e; ++c) {
+                    oi[c] += p * vb[c * si + j];
+                    ci[c] += p * fabs(vb[c * si + j]) * wij;
+                }
+            }
+            double Di = 0.0, Da = 0.0;
+            for (int c = 0; c < e; ++c) {
+                Di += gb[c * so + i] * oi[c];
+                Da += fabs(gb[c * so + i]) * ci[c];
+                c_out[((size_t)b * e + c) * so + i] = ci[c];
+            }
+            lse[t] = L; D[t] = Di; Dabs[t] = Da;
+            c_lse[t] = cl;
+            for (int l = 0; l < d; ++l) c_dq[((size_t)b * d + l) * so + i] = 0.0;
+            for (size_t j = 0; j < si; ++j) {
+                if (s[j] == -INFINITY) continue;
+                double a = 0.0, gv = 0.0, G = 0.0;
+                for (int l = 0; l < d; ++l) a += fabs(qb[l * so + i]) * fabs(kb[l * si + j]);
+                for (int c = 0; c < e; ++c) {
+                    gv += gb[c * so + i] * vb[c * si + j];
+                    G += fabs(gb[c * so + i]) * fabs(vb[c * si + j]);
+                }
+                double p = exp(s[j] - L), wij = 1.0 + ascale * a + cl;
+                double tij = fabs(gv - Di) * wij + G + Da;
+                for (int l = 0; l < d; ++l) c_dq[((size_t)b * d + l) * so + i] += ascale * p * tij * fabs(kb[l * si + j]);
+            }
+        }
+#pragma omp for schedule(dynamic, 16)
+        for (long t = 0; t < total_i; ++t) {
+            int b = (int)(t / (long)si);
+            size_t j = (size_t)(t % (long)si);
+            int hp = (int)(j / nlon_in), win = (int)(j % nlon_in);
+            const double *qb = q + (size_t)b * d * so, *kb = k + (size_t)b * d * si, *vb = v + (size_t)b * e * si;
+            const double *gb = dout + (size_t)b * e * so;
+            for (int l = 0; l < d; ++l) c_dk[((size_t)b * d + l) * si + j] = 0.0;
+            for (int c = 0; c < e; ++c) c_dv[((size_t)b * e + c) * si + j] = 0.0;
+            for (int h = 0; h < nlat_out; ++h)
+                for (int w = 0; w < nlon_out; ++w) {
+                    if (!member(&C, h, w, hp, win)) continue;
+                    size_t i = (size_t)h * nlon_out + w;
+                    double dot = 0.0, a = 0.0, gv = 0.0, G = 0.0;
+                    for (int l = 0; l < d; ++l) {
+                        dot += qb[l * so + i] * kb[l * si + j];
+                        a += fabs(qb[l * so + i]) * fabs(kb[l * si + j]);
+                    }
+                    for (int c = 0; c < e; ++c) {
+                        gv += gb[c * so + i] * vb[c * si + j];
+                        G += fabs(gb[c * so + i]) * fabs(vb[c * si + j]);
+                    }
+                    size_t ti = (size_t)b * so + i;
+                    double p = exp(dot * scale + C.logw[hp] - lse[ti]);
+                    double wij = 1.0 + ascale * a + c_lse[ti];
+                    double tij = fabs(gv - D[ti]) * wij + G + Dabs[ti];
+                    for (int l = 0; l < d; ++l) c_dk[((size_t)b * d + l) * si + j] += ascale * p * tij * fabs(qb[l * so + i]);
+                    for (int c = 0; c < e; ++c) c_dv[((size_t)b * e + c) * si + j] += p * wij * fabs(gb[c * so + i]);
+                }
+        }
+        free(s); free(oi); free(ci);
+    }
+    free(lse); free(D); free(Dabs);
+    ctx_free(&C);
+    return 0;
+}
+
 /* ------------------------------------------------------ global attention -- */
 
 static double *global_logw(int grid_type, int nlat, int nlon)

@@ -137,6 +137,22 @@ def nattn_bwd(g, q, k, v, dout, scale, brute=False):
     return dq, dk, dv
 
 
+def nattn_cond(g, q, k, v, dout, scale, brute=False):
+    """Rounding sensitivities (sums of absolute terms, see s2o_nattn_cond) of out, lse, dq, dk, dv."""
+    q, qp = _d(q); k, kp = _d(k); v, vp = _d(v); dout, gp = _d(dout)
+    nbh, d = q.shape[0], q.shape[1]
+    e = v.shape[1]
+    assert dout.shape == (nbh, e, g["nlat_out"], g["nlon_out"])
+    c_out = np.empty_like(dout); c_lse = np.empty((nbh, g["nlat_out"], g["nlon_out"]), np.float64)
+    c_dq = np.empty_like(q); c_dk = np.empty_like(k); c_dv = np.empty_like(v)
+    rc = _load().s2o_nattn_cond(*_grid_args(g), int(bool(brute)), nbh, d, e, ctypes.c_double(scale),
+                                qp, kp, vp, gp, c_out.ctypes.data_as(_dp), c_lse.ctypes.data_as(_dp),
+                                c_dq.ctypes.data_as(_dp), c_dk.ctypes.data_as(_dp), c_dv.ctypes.data_as(_dp))
+    if rc:
+        raise ValueError("s2o_nattn_cond failed (%d)" % rc)
+    return c_out, c_lse, c_dq, c_dk, c_dv
+
+
 def global_fwd(grid_type, nlat, nlon, q, k, v, scale):
     """Token-major q,k [nbh,N,d], v [nbh,N,e] -> out [nbh,N,e], lse [nbh,N]."""
     q, qp = _d(q); k, kp = _d(k); v, vp = _d(v)

@@ -104,3 +104,39 @@ def dense_attention(g, q, k, v, scale, dout=None, mask=None):
                 kt.grad.numpy().transpose(0, 2, 1).reshape(k.shape),
                 vt.grad.numpy().transpose(0, 2, 1).reshape(v.shape)]
     return res
+
+
+def dense_cond(g, q, k, v, dout, scale, mask=None):
+    """Rounding sensitivities of out, lse, dq, dk, dv (sums of the absolute values of the elementary products, each
+    weighted by the number of perturbed factors it carries), evaluated with dense matrices in numpy float64:
+    a = |scale| |q|.|k|, c_lse = 1 + sum p a, w = 1 + a + c_lse, c_out = sum p w |v|,
+    t = |dout.v - D| w + |dout|.|v| + |dout|.c_out, c_dq = |scale| (p t) |k|, c_dk = |scale| (p t)^T |q|,
+    c_dv = (p w)^T |dout|."""
+    nbh, d = q.shape[:2]
+    e = v.shape[1]
+    tok = lambda x, c: np.asarray(x, np.float64).reshape(nbh, c, -1).transpose(0, 2, 1)
+    Q, K, V, G = tok(q, d), tok(k, d), tok(v, e), tok(dout, e)
+    if mask is None:
+        mask = dense_mask(g)
+    bias = log_omega_tokens(g)[None, None, :]
+    with np.errstate(invalid="ignore"):
+        S = np.where(mask[None], Q @ K.transpose(0, 2, 1) * scale + bias, -np.inf)
+    m = S.max(-1, keepdims=True)
+    P = np.exp(S - m)
+    P /= P.sum(-1, keepdims=True)
+    A = abs(scale) * (np.abs(Q) @ np.abs(K).transpose(0, 2, 1))
+    A = np.where(P > 0, A, 0.0)
+    c_lse = 1.0 + (P * A).sum(-1)
+    W = 1.0 + A + c_lse[..., None]
+    c_out = (P * W) @ np.abs(V)
+    out = P @ V
+    D = (G * out).sum(-1)
+    Dabs = (np.abs(G) * c_out).sum(-1)
+    T = np.abs(G @ V.transpose(0, 2, 1) - D[..., None]) * W + np.abs(G) @ np.abs(V).transpose(0, 2, 1) + Dabs[..., None]
+    PT = P * T
+    c_dq = abs(scale) * (PT @ np.abs(K))
+    c_dk = abs(scale) * (PT.transpose(0, 2, 1) @ np.abs(Q))
+    c_dv = (P * W).transpose(0, 2, 1) @ np.abs(G)
+    so, si = q.shape[2:], k.shape[2:]
+    back = lambda x, c, s: x.transpose(0, 2, 1).reshape((nbh, c) + tuple(s))
+    return back(c_out, e, so), c_lse.reshape((nbh,) + tuple(so)), back(c_dq, d, so), back(c_dk, d, si), back(c_dv, e, si)

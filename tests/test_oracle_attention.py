@@ -226,3 +226,23 @@ def test_config2_slice_vs_dense_torch():
     ref = dense_attention(g, q, k, v, scale, dout)
     for a, b in zip((out, lse, dq, dk, dv), ref):
         assert np.allclose(a, b, rtol=1e-10, atol=1e-12)
+
+
+@pytest.mark.parametrize("ci", [0, 2, 4, 7])
+def test_rounding_sensitivities_vs_dense_numpy(ci):
+    # the yardstick of the float32 tolerance (sums of absolute terms) against a dense matrix evaluation with an
+    # independent mask and independent weights; it must also dominate the results themselves
+    from indep import dense_cond
+    c = SMALL[ci]
+    g = grid_dict(c)
+    brute = g["nlon_in"] % g["nlon_out"] != 0
+    q, k, v, dout = _inputs(c, 40 + ci)
+    for scale in (1 / math.sqrt(c["d"]), -0.7):
+        got = O.nattn_cond(g, q, k, v, dout, scale, brute=brute)
+        ref = dense_cond(g, q, k, v, dout, scale)
+        for a, b in zip(got, ref):
+            assert np.allclose(a, b, rtol=1e-11, atol=1e-12)
+        out, lse = O.nattn_fwd(g, q, k, v, scale, brute=brute)
+        dq, dk, dv = O.nattn_bwd(g, q, k, v, dout, scale, brute=brute)
+        for cnd, val in zip(got, (out, np.ones_like(lse), dq, dk, dv)):
+            assert (cnd >= np.abs(val) * (1 - 1e-12)).all()
