@@ -71,7 +71,11 @@ enum {
  *
  * If a HIP device is present the compact tables are uploaded to the current
  * device; without a device the handle is host-only (the introspection calls
- * work, the attention calls return S2_ERR_DEVICE).
+ * work, the attention calls return S2_ERR_DEVICE).  The first call on a
+ * device also raises the LDS limits of the library's kernels there (guarded
+ * by a mutex), so that the attention calls only enqueue launches and can be
+ * captured into a HIP graph from their first call on.  A handle must be used
+ * with the device that was current when it was created.
  *
  * Errors: S2_ERR_INVALID_ARG (nlat < 2, nlon < 1, theta outside (0, pi], NULL
  * out_grid, unknown grid_type); S2_ERR_UNSUPPORTED (neither longitude count
@@ -183,12 +187,39 @@ int s2_trace_count(void);
 int s2_trace_get(int index, const char **name, float *ms, double *pairs);
 void s2_trace_reset(void);
 
+/*
+ * Measured ceilings of the current device, for the roofline figures of the benchmark (not part of the method).
+ * Runs a plain kernel of the named kind (allocating and freeing its own buffers, on the default stream,
+ * synchronising) and stores the rate in *value (host pointer):
+ *   S2_PEAK_COPY       streaming copy of 1 GiB, GB/s counting bytes read plus bytes written
+ *   S2_PEAK_FMA_F32    independent v_fma_f32 chains, TFLOP/s
+ *   S2_PEAK_MFMA_F32   v_mfma_f32_32x32x2_f32 chains, TFLOP/s
+ *   S2_PEAK_MFMA_BF16  v_mfma_f32_32x32x16_bf16 chains, TFLOP/s
+ *   S2_PEAK_LDS_READ   conflict-free 16-byte LDS reads, TB/s over the whole device
+ * Errors: S2_ERR_INVALID_ARG, S2_ERR_ALLOC, S2_ERR_DEVICE.
+ */
+enum { S2_PEAK_COPY = 0, S2_PEAK_FMA_F32 = 1, S2_PEAK_MFMA_F32 = 2, S2_PEAK_MFMA_BF16 = 3, S2_PEAK_LDS_READ = 4 };
+int s2_peak_measure(int kind, double *value);
+
 /* Device-side health of a grid handle (Sec. 3.2 / App. B.3 kernels that synchronise wavefronts through counters
  * in LDS bound every wait; a wait that ran out - which would be a defect of the library, the results of that call
  * are then wrong - sets a sticky flag in device memory).  Synchronises the device, copies the flag word to *flags
  * (0 = healthy) and clears it.  Host pointer; S2_ERR_INVALID_ARG for NULL arguments, S2_ERR_DEVICE if the handle
  * has no device tables or the copy fails. */
 int s2_grid_device_flags(const s2_grid_t *g, unsigned *flags);
+
+/*
+ * Test-only dispatch switches (not part of the method; nothing else steers the dispatch: the library reads no
+ * environment variables).  Sets the bits of set_bits, clears those of clear_bits, returns the new word; process
+ * wide, takes effect on the next attention call.
+ *   S2_DEBUG_NO_MFMA        dense polar latitudes go to the split vector kernels instead of the matrix cores
+ *   S2_DEBUG_NO_STREAM      light latitudes go to the one-wavefront kernels instead of the streaming kernels
+ *   S2_DEBUG_NO_ROW_GROUPS  matrix-core kernels never start a second set of wavefronts per workgroup
+ *   S2_DEBUG_FAIL_LAUNCH    the launchers of the tuned neighborhood kernels report failure before launching
+ *                           anything: s2_nattn_fwd / s2_nattn_bwd then return S2_ERR_DEVICE
+ */
+enum { S2_DEBUG_NO_MFMA = 1, S2_DEBUG_NO_STREAM = 2, S2_DEBUG_NO_ROW_GROUPS = 4, S2_DEBUG_FAIL_LAUNCH = 8 };
+unsigned s2_debug_control(unsigned set_bits, unsigned clear_bits);
 
 /* Message for the last error on the calling thread ("" if none). */
 const char *s2_last_error(void);

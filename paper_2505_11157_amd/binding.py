@@ -23,6 +23,10 @@ S2_ERR_ALLOC = -4
 S2_ERR_DEVICE = -5
 S2_ERR_WORKSPACE = -6
 S2_ERR_AMBIGUOUS_CUTOFF = -7
+S2_DEBUG_NO_MFMA = 1
+S2_DEBUG_NO_STREAM = 2
+S2_DEBUG_NO_ROW_GROUPS = 4
+S2_DEBUG_FAIL_LAUNCH = 8
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libs2attn.so")
@@ -86,6 +90,10 @@ def lib():
         L.s2_trace_get.restype = _i
         L.s2_trace_reset.argtypes = []
         L.s2_trace_reset.restype = None
+        L.s2_peak_measure.argtypes = [_i, ctypes.POINTER(ctypes.c_double)]
+        L.s2_peak_measure.restype = _i
+        L.s2_debug_control.argtypes = [ctypes.c_uint, ctypes.c_uint]
+        L.s2_debug_control.restype = ctypes.c_uint
         L.s2_last_error.argtypes = []
         L.s2_last_error.restype = ctypes.c_char_p
         _lib = L
@@ -264,6 +272,21 @@ def s2_attn_global_bwd(g, q, k, v, out, lse, dout, scale, dq=None, dk=None, dv=N
                                     v.data_ptr(), out.data_ptr(), lse.data_ptr(), dout.data_ptr(), dq.data_ptr(),
                                     dk.data_ptr(), dv.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream()))
     return dq, dk, dv
+
+
+S2_PEAK_COPY, S2_PEAK_FMA_F32, S2_PEAK_MFMA_F32, S2_PEAK_MFMA_BF16, S2_PEAK_LDS_READ = range(5)
+
+
+def s2_peak_measure(kind):
+    """Measured ceiling of the current device (see include/s2attn.h for kinds and units)."""
+    val = ctypes.c_double(0.0)
+    _check(lib().s2_peak_measure(int(kind), ctypes.byref(val)))
+    return float(val.value)
+
+
+def s2_debug_control(set_bits=0, clear_bits=0):
+    """Test-only dispatch switches (S2_DEBUG_*): returns the new flag word."""
+    return int(lib().s2_debug_control(int(set_bits), int(clear_bits)))
 
 
 def s2_trace_enable(on):

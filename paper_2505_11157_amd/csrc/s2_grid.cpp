@@ -8,6 +8,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstdlib>
+#include <mutex>
 #include <cstring>
 #include <numeric>
 
@@ -183,6 +184,22 @@ static int upload_tables(s2_grid *g)
         return S2_OK;
     }
     S2_HIP_CHECK(hipGetDevice(&g->device));
+    {
+        // once per device: LDS limits of the kernels (not a stream operation, so it must not happen inside an
+        // attention call that a caller may be capturing into a graph)
+        static std::mutex mu;
+        static std::vector<char> done;
+        std::lock_guard<std::mutex> lock(mu);
+        if (int(done.size()) < ndev) done.resize(ndev, 0);
+        if (!done[g->device]) {
+            if (s2_nattn_tiled_configure() || s2_nattn_bwd_tiled_configure() || s2_nattn_stream_configure() ||
+                s2_nattn_mfma_configure()) {
+                (void)hipGetLastError();
+                return s2_fail(S2_ERR_DEVICE, "raising the LDS limit of a kernel failed");
+            }
+            done[g->device] = 1;
+        }
+    }
     std::vector<float> l2w(g->nlat_in);
     const double omega_ref = *std::max_element(g->omega_in.begin(), g->omega_in.end());
     for (int h = 0; h < g->nlat_in; ++h) l2w[h] = float(g->omega_in[h] / omega_ref);
@@ -422,6 +439,34 @@ extern "C" int s2_grid_init(int grid_type, int nlat_in, int nlon_in, int nlat_ou
         g->row_ptr[h + 1] = int64_t(g->col.size());
     }
 
+    // The introspection calls keep the lists as eq. (5) defines them.  The kernels never meet an input latitude of
+    // weight zero (the pole row of the grid of App. A.1): its points contribute nothing to any sum, but their
+    // logits would enter the running maximum of the softmax, and a pole logit far above all others would let every
+    // positive-weight term underflow.  Equal grids and downsampling: such rows are cut off the ends of the bands;
+    // upsampling (whose dk/dv walk indexes the class tables by input latitude): their arcs are emptied.
+    g->c_band_lo = g->band_lo; g->c_band_n = g->band_n; g->c_cnt = g->cnt; g->c_ucnt = g->ucnt; g->c_ulo = g->ulo;
+    g->c_band_max = g->band_max;
+    for (int hp = 0; hp < nlat_in; ++hp)
+        if (!(g->omega_in[hp] > 0.0)) g->zero_lat.push_back(hp);
+    if (!g->zero_lat.empty()) {
+        if (g->upscale > 1) {
+            for (int h = 0; h < nlat_out; ++h)
+                for (int sc = 0; sc < g->upscale; ++sc)
+                    for (int b = 0; b < g->band_n[h]; ++b)
+                        if (!(g->omega_in[g->band_lo[h] + b] > 0.0)) g->ucnt[(size_t(h) * g->upscale + sc) * g->band_max + b] = 0;
+        } else {
+            for (int h = 0; h < nlat_out; ++h) {
+                int lo = g->band_lo[h], n = g->band_n[h], skip = 0;
+                while (n > 0 && !(g->omega_in[lo + n - 1] > 0.0)) --n;
+                while (n > 0 && !(g->omega_in[lo + skip] > 0.0)) { ++skip; --n; }
+                for (int b = 0; b < g->band_max; ++b)
+                    g->cnt[size_t(h) * g->band_max + b] = b < n ? g->c_cnt[size_t(h) * g->band_max + b + skip] : 0;
+                g->band_lo[h] = lo + skip;
+                g->band_n[h] = n;            // > 0: every neighborhood holds a point of positive weight
+            }
+        }
+    }
+
     // work of a latitude: offsets per output point (summed over its band), resp. per input latitude over its
     // transposed band, with the number of (output, input) pairs it stands for.  Upsampling: mean over the longitude classes
     // (forward) and the sum over output latitudes and classes of the arcs that hold an input point (backward).
@@ -557,15 +602,15 @@ extern "C" int s2_grid_get_neighbors_at(const s2_grid_t *g, int h, int w, int32_
     if (h < 0 || h >= g->nlat_out || w < 0 || w >= g->nlon_out) return s2_fail(S2_ERR_INVALID_ARG, "no such output point");
     const int r = g->upscale, sc = w % r, m = r > 1 ? w / r : w * g->pscale;
     std::vector<int32_t> list;
-    for (int b = 0; b < g->band_n[h]; ++b) {
-        const int hp = g->band_lo[h] + b;
+    for (int b = 0; b < g->c_band_n[h]; ++b) {
+        const int hp = g->c_band_lo[h] + b;
         int c, lo;
         if (r > 1) {
-            const size_t at = (size_t(h) * r + sc) * g->band_max + b;
-            c = g->ucnt[at];
-            lo = g->ulo[at];
+            const size_t at = (size_t(h) * r + sc) * g->c_band_max + b;
+            c = g->c_ucnt[at];
+            lo = g->c_ulo[at];
         } else {
-            c = g->cnt[size_t(h) * g->band_max + b];
+            c = g->c_cnt[size_t(h) * g->c_band_max + b];
             lo = c == g->nlon_in ? 0 : -((c - 1) / 2);
         }
         std::vector<int32_t> row;

@@ -63,6 +63,10 @@ struct s2_grid {
     int upscale = 1;
     std::vector<int> ucnt, ulo;      // upsampling only (see S2DeviceTables)
     int band_max = 0, tband_max = 0;
+    // the band and arc tables exactly as eq. (5) gives them (introspection); the tables above, which the kernels
+    // use, leave out input latitudes of weight zero (listed in zero_lat)
+    std::vector<int> c_band_lo, c_band_n, c_cnt, c_ucnt, c_ulo, zero_lat;
+    int c_band_max = 0;
     // canonical CSR
     std::vector<int64_t> row_ptr;
     std::vector<int32_t> col;
@@ -106,6 +110,18 @@ struct S2TraceScope {
     S2TraceScope(const char *name, double pairs, hipStream_t s) : st(s) { s2_trace_begin(name, pairs, s); }
     ~S2TraceScope() { s2_trace_end(st); }
 };
+
+// Test-only switches (bits of s2_debug_control): which kernel families the dispatch may pick, and a forced
+// launcher failure.
+bool s2_debug_flag(unsigned bit);
+
+// One-time set-up of the kernels of each translation unit on the current device: raises the dynamic LDS limit of
+// every kernel that needs more than the default.  Called from s2_grid_init (once per device), so that the attention
+// calls themselves only enqueue launches.  0 on success.
+int s2_nattn_tiled_configure();
+int s2_nattn_bwd_tiled_configure();
+int s2_nattn_stream_configure();
+int s2_nattn_mfma_configure();
 
 void s2_set_error(const std::string &msg);
 int s2_fail(int code, const std::string &msg);

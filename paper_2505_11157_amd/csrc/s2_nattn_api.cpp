@@ -37,8 +37,9 @@ extern "C" int s2_nattn_fwd(const s2_grid_t *g, int batch, int heads, int d_qk, 
         return s2_fail(S2_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     auto *fwd = s2_nattn_fwd_tiled_supported(g->dt, d_qk, d_v) ? s2_nattn_fwd_tiled : s2_nattn_fwd_generic;
-    fwd(g->dt, batch * heads, d_qk, d_v, scale, static_cast<const float *>(q), static_cast<const float *>(k),
-        static_cast<const float *>(v), static_cast<float *>(out), lse, st);
+    if (fwd(g->dt, batch * heads, d_qk, d_v, scale, static_cast<const float *>(q), static_cast<const float *>(k),
+            static_cast<const float *>(v), static_cast<float *>(out), lse, st))
+        return s2_fail(S2_ERR_DEVICE, "forward launch configuration failed");
     S2_HIP_CHECK(hipGetLastError());
     return S2_OK;
 }
@@ -65,6 +66,11 @@ extern "C" int s2_nattn_bwd(const s2_grid_t *g, int batch, int heads, int d_qk, 
             static_cast<float *>(dq), static_cast<float *>(dk), static_cast<float *>(dv),
             static_cast<float *>(workspace), st))
         return s2_fail(S2_ERR_DEVICE, "backward launch configuration failed");
+    // input latitudes of weight zero (the pole row of the grid of App. A.1): dk = dv = 0 exactly
+    for (int lat : g->zero_lat) {
+        s2_nattn_zero_latitude(g->dt, lat, batch * heads * d_qk, static_cast<float *>(dk), st);
+        s2_nattn_zero_latitude(g->dt, lat, batch * heads * d_v, static_cast<float *>(dv), st);
+    }
     S2_HIP_CHECK(hipGetLastError());
     return S2_OK;
 }

@@ -861,6 +861,24 @@ bool s2_nattn_bwd_tiled_supported(const S2DeviceTables &t, int d, int e)
            t.nlon_out >= 72;
 }
 
+int s2_nattn_bwd_tiled_configure()
+{
+    auto raise = [](auto kern, size_t lds_wave, size_t merge) {
+        size_t lds = lds_wave * kWavesB;
+        if (lds < merge) lds = merge;
+        return hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   int(lds)) == hipSuccess;
+    };
+    // 8-wave kernels: per-wavefront staging buffers, reused for the merge of the partial sums
+    const size_t mg_q = size_t(kWavesB / 2) * 4 * kDL * 64 * sizeof(float), mg_kv = 2 * mg_q;
+    const size_t kv1 = (2 * GeoB<1>::TILE + 2 * GeoB<1>::PITCH) * sizeof(float), kv2 = (2 * kTile2 + 2 * kPitch2) * sizeof(float);
+    return raise(nattn_bwd_dq_tiled<1, kWavesB>, 2 * GeoB<1>::TILE * sizeof(float), mg_q) &&
+           raise(nattn_bwd_dq_tiled<2, kWavesB>, 2 * GeoB<2>::TILE * sizeof(float), mg_q) &&
+           raise(nattn_bwd_dq_tiled<1, kWavesB, true>, 2 * GeoB<1>::TILE * sizeof(float), mg_q) &&
+           raise(nattn_bwd_dkdv_tiled<kWavesB>, kv1, mg_kv) && raise(nattn_bwd_dkdv_tiled<kWavesB, true>, kv1, mg_kv) &&
+           raise(nattn_bwd_dkdv2_tiled<kWavesB>, kv2, mg_kv) ? 0 : -1;
+}
+
 namespace {
 
 // Upsampling grids: the split vector kernels in their class view (no matrix-core or streaming launches).
@@ -868,7 +886,7 @@ int bwd_tiled_up(const S2DeviceTables &t_all, int nbh, float scale, const float 
                  const float *o, const float *lse, const float *go, float *dq, float *dk, float *dv, float *Dws,
                  hipStream_t st)
 {
-    static bool cfg_dq = false, cfg_kv = false;
+    if (s2_debug_flag(S2_DEBUG_FAIL_LAUNCH)) return -1;
     const int nseg_o = ((t_all.nlon_in + kSegB - 1) / kSegB) * t_all.upscale, nseg_i = (t_all.nlon_in + kSegB - 1) / kSegB;
     {
         S2DeviceTables t = t_all;
@@ -881,12 +899,6 @@ int bwd_tiled_up(const S2DeviceTables &t_all, int nbh, float scale, const float 
             const size_t mg = size_t(kWavesB / 2) * 4 * kDL * 64 * sizeof(float);
             if (lds < mg) lds = mg;
             auto k8 = nattn_bwd_dq_tiled<1, kWavesB, true>;
-            if (!cfg_dq) {
-                if (hipFuncSetAttribute(reinterpret_cast<const void *>(k8), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                        int(lds)) != hipSuccess)
-                    return -1;
-                cfg_dq = true;
-            }
             S2TraceScope tr("nattn_bwd_dq_tiled<8 waves, classes>", nbh * (t.fwd_pairs[0] + t.fwd_pairs[1] + t.fwd_pairs[2]), st);
             hipLaunchKernelGGL(k8, dim3((unsigned)nblk), dim3(64 * kWavesB), lds, st, t, nbh, 1, scale, q, k, v, o, lse,
                                go, dq, Dws);
@@ -908,12 +920,6 @@ int bwd_tiled_up(const S2DeviceTables &t_all, int nbh, float scale, const float 
         const size_t mg = size_t(kWavesB / 2) * 2 * 4 * kDL * 64 * sizeof(float);
         if (lds < mg) lds = mg;
         auto k8 = nattn_bwd_dkdv_tiled<kWavesB, true>;
-        if (!cfg_kv) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void *>(k8), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    int(lds)) != hipSuccess)
-                return -1;
-            cfg_kv = true;
-        }
         S2TraceScope tr("nattn_bwd_dkdv_tiled<8 waves, classes>", nbh * (t.bwd_pairs[0] + t.bwd_pairs[1] + t.bwd_pairs[2]), st);
         hipLaunchKernelGGL(k8, dim3((unsigned)nblk), dim3(64 * kWavesB), lds, st, t, nbh, 1, scale, q, k, v, lse, go, Dws,
                            dk, dv);
@@ -935,8 +941,8 @@ int s2_nattn_bwd_tiled(const S2DeviceTables &t, int nbh, int d, int e, float sca
 {
     if (t.upscale > 1) return bwd_tiled_up(t, nbh, scale, q, k, v, o, lse, go, dq, dk, dv, Dws, st);
     const int nseg_o = (t.nlon_out + kSegB - 1) / kSegB;
-    static bool cfg_dq1 = false, cfg_dq2 = false, cfg_kv = false;
-    static const bool no_stream = std::getenv("S2_NO_STREAM") != nullptr;   // debugging aid: one-wave kernels instead
+    if (s2_debug_flag(S2_DEBUG_FAIL_LAUNCH)) return -1;
+    const bool no_stream = s2_debug_flag(S2_DEBUG_NO_STREAM);   // test-only: one-wave kernels instead
     // dense polar latitudes: dq on the matrix cores; the vector kernels see the remaining latitudes
     const S2DeviceTables &t_all = t;
     S2DeviceTables t_dq = t_all;
@@ -954,19 +960,13 @@ int s2_nattn_bwd_tiled(const S2DeviceTables &t, int nbh, int d, int e, float sca
         s2_pick_split(t_dq, true, nbh, nseg_o, nm > 0);
     }
     const int nsplit_o = t_dq.fwd_cls[0] + t_dq.fwd_cls[1] + t_dq.fwd_cls[2];
-    auto run_dq = [&](auto k8, auto k1, size_t lds_wave, bool &cfg) {
+    auto run_dq = [&](auto k8, auto k1, size_t lds_wave) {
         if (nsplit_o > 0) {
             const long nblk = long((nbh + kWavesB - 1) / kWavesB) * nseg_o *
                               (8 * t_dq.fwd_cls[0] + 4 * t_dq.fwd_cls[1] + 2 * t_dq.fwd_cls[2]);
             size_t lds = lds_wave * kWavesB;
             const size_t mg = size_t(kWavesB / 2) * 4 * kDL * 64 * sizeof(float);
             if (lds < mg) lds = mg;
-            if (!cfg) {
-                if (hipFuncSetAttribute(reinterpret_cast<const void *>(k8),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, int(lds)) != hipSuccess)
-                    return -1;
-                cfg = true;
-            }
             S2TraceScope tr("nattn_bwd_dq_tiled<8 waves>", nbh * (t_dq.fwd_pairs[0] + t_dq.fwd_pairs[1] + t_dq.fwd_pairs[2]), st);
             hipLaunchKernelGGL(k8, dim3((unsigned)nblk), dim3(64 * kWavesB), lds, st, t_dq, nbh, 1, scale, q, k, v, o, lse,
                                go, dq, Dws);
@@ -982,9 +982,9 @@ int s2_nattn_bwd_tiled(const S2DeviceTables &t, int nbh, int d, int e, float sca
     };
     int rc;
     if (t.pscale == 1)
-        rc = run_dq(nattn_bwd_dq_tiled<1, kWavesB>, nattn_bwd_dq_tiled<1, 1>, 2 * GeoB<1>::TILE * sizeof(float), cfg_dq1);
+        rc = run_dq(nattn_bwd_dq_tiled<1, kWavesB>, nattn_bwd_dq_tiled<1, 1>, 2 * GeoB<1>::TILE * sizeof(float));
     else
-        rc = run_dq(nattn_bwd_dq_tiled<2, kWavesB>, nattn_bwd_dq_tiled<2, 1>, 2 * GeoB<2>::TILE * sizeof(float), cfg_dq2);
+        rc = run_dq(nattn_bwd_dq_tiled<2, kWavesB>, nattn_bwd_dq_tiled<2, 1>, 2 * GeoB<2>::TILE * sizeof(float));
     if (rc) return rc;
 
     if (t_all.pscale == 2) {
@@ -993,7 +993,6 @@ int s2_nattn_bwd_tiled(const S2DeviceTables &t, int nbh, int d, int e, float sca
         s2_pick_split(t, false, nbh, nseg_i, false);
         const int nsplit_i = t.bwd_cls[0] + t.bwd_cls[1] + t.bwd_cls[2];
         const size_t lds_wave = (2 * kTile2 + 2 * kPitch2) * sizeof(float);
-        static bool cfg_kv2 = false;
         if (nsplit_i > 0) {
             const long nblk = long((nbh + kWavesB - 1) / kWavesB) * nseg_i *
                               (8 * t.bwd_cls[0] + 4 * t.bwd_cls[1] + 2 * t.bwd_cls[2]);
@@ -1001,12 +1000,6 @@ int s2_nattn_bwd_tiled(const S2DeviceTables &t, int nbh, int d, int e, float sca
             const size_t mg = size_t(kWavesB / 2) * 2 * 4 * kDL * 64 * sizeof(float);
             if (lds < mg) lds = mg;
             auto k8 = nattn_bwd_dkdv2_tiled<kWavesB>;
-            if (!cfg_kv2) {
-                if (hipFuncSetAttribute(reinterpret_cast<const void *>(k8),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, int(lds)) != hipSuccess)
-                    return -1;
-                cfg_kv2 = true;
-            }
             S2TraceScope tr("nattn_bwd_dkdv2_tiled<8 waves>", nbh * (t.bwd_pairs[0] + t.bwd_pairs[1] + t.bwd_pairs[2]), st);
             hipLaunchKernelGGL(k8, dim3((unsigned)nblk), dim3(64 * kWavesB), lds, st, t, nbh, 1, scale, q, k, v, lse,
                                go, Dws, dk, dv);
@@ -1043,12 +1036,6 @@ int s2_nattn_bwd_tiled(const S2DeviceTables &t, int nbh, int d, int e, float sca
         const size_t mg = size_t(kWavesB / 2) * 2 * 4 * kDL * 64 * sizeof(float);
         if (lds < mg) lds = mg;
         auto k8 = nattn_bwd_dkdv_tiled<kWavesB>;
-        if (!cfg_kv) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void *>(k8), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    int(lds)) != hipSuccess)
-                return -1;
-            cfg_kv = true;
-        }
         S2TraceScope tr("nattn_bwd_dkdv_tiled<8 waves>", nbh * (t_kv.bwd_pairs[0] + t_kv.bwd_pairs[1] + t_kv.bwd_pairs[2]), st);
         hipLaunchKernelGGL(k8, dim3((unsigned)nblk), dim3(64 * kWavesB), lds, st, t_kv, nbh, 1, scale, q, k, v, lse, go,
                            Dws, dk, dv);

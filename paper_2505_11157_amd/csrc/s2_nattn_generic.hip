@@ -309,6 +309,17 @@ nattn_bwd_dkdv_generic(S2DeviceTables t, int nbh, int d, int e, float scale,
     }
 }
 
+// Input latitudes of weight zero: every p_ij of theirs is zero, so dk = dv = 0 there.  The dk/dv kernels above and
+// in the tuned files form 0 * exp2(.) for them, which is not a number once the exponential overflows; this fill,
+// enqueued after them, writes the exact result.  x: [rows][nlat_in][nlon_in], one block per (row, 256 columns).
+__global__ void __launch_bounds__(256)
+zero_latitude(float *__restrict__ x, int lat, int rows, int nlon_in, size_t si)
+{
+    const int w = blockIdx.x * 256 + threadIdx.x;
+    if (w >= nlon_in) return;
+    for (int r = blockIdx.y; r < rows; r += gridDim.y) x[size_t(r) * si + size_t(lat) * nlon_in + w] = 0.f;
+}
+
 template <int DMAX>
 int launch_fwd(const S2DeviceTables &t, int nbh, int d, int e, float scale, const float *q, const float *k,
                const float *v, float *out, float *lse, hipStream_t st)
@@ -351,6 +362,12 @@ int launch_dkdv(const S2DeviceTables &t, int nbh, int d, int e, float scale, con
 }
 
 }  // namespace
+
+void s2_nattn_zero_latitude(const S2DeviceTables &t, int lat, int rows, float *x, hipStream_t st)
+{
+    hipLaunchKernelGGL(zero_latitude, dim3((t.nlon_in + 255) / 256, rows < 65535 ? rows : 65535), dim3(256), 0, st, x,
+                       lat, rows, t.nlon_in, size_t(t.nlat_in) * t.nlon_in);
+}
 
 int s2_nattn_fwd_generic(const S2DeviceTables &t, int nbh, int d, int e, float scale, const float *q,
                          const float *k, const float *v, float *out, float *lse, hipStream_t st)

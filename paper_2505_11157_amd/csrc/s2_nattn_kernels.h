@@ -9,6 +9,9 @@ int s2_nattn_bwd_generic(const S2DeviceTables &t, int nbh, int d, int e, float s
                          const float *k, const float *v, const float *o, const float *lse, const float *go,
                          float *dq, float *dk, float *dv, float *Dws, hipStream_t st);
 
+// dk, dv of an input latitude of weight zero are zero: x is [rows][nlat_in][nlon_in], rows = slices * channels.
+void s2_nattn_zero_latitude(const S2DeviceTables &t, int lat, int rows, float *x, hipStream_t st);
+
 // Tuned float32 forward for d = e = 32, nlon_in / nlon_out in {1, 2}, longitudes a multiple of 4.
 bool s2_nattn_fwd_tiled_supported(const S2DeviceTables &t, int d, int e);
 int s2_nattn_fwd_tiled(const S2DeviceTables &t, int nbh, int d, int e, float scale, const float *q, const float *k,

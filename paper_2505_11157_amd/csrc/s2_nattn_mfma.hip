@@ -549,14 +549,25 @@ nattn_bwd_dkdv_mfma(S2DeviceTables t, int nbh, int nrows, int rgroups, float sca
 
 }  // namespace
 
+int s2_nattn_mfma_configure()
+{
+    auto raise = [](auto kern, size_t floats) {
+        return hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   int(floats * sizeof(float))) == hipSuccess;
+    };
+    // <2>: two super-tiles per barrier, double buffered, for up to two sets of wavefronts; <1>: one per barrier
+    return raise(nattn_fwd_mfma<2>, 8 * size_t(kTileFloats)) && raise(nattn_fwd_mfma<1>, 4 * size_t(kTileFloats)) &&
+           raise(nattn_bwd_dq_mfma<2>, 8 * size_t(kTileB)) && raise(nattn_bwd_dq_mfma<1>, 4 * size_t(kTileB)) &&
+           raise(nattn_bwd_dkdv_mfma<2>, 8 * size_t(kTileC)) && raise(nattn_bwd_dkdv_mfma<1>, 4 * size_t(kTileC)) ? 0 : -1;
+}
+
 // latitudes whose disk holds more than 260 points per output (the three heaviest classes) take the matrix-core path
 int s2_nattn_fwd_mfma_rows(const S2DeviceTables &t, int d, int e)
 {
     const int nw = t.nlon_out / 32;
     if (d != 32 || e != 32 || t.pscale != 1 || t.nlon_in % kTileCols != 0 || t.nlon_out % 32 != 0 || nw < 2 || nw > 16)
         return 0;
-    static const bool off = std::getenv("S2_NO_MFMA") != nullptr;   // debugging aid: force the vector kernels
-    if (off) return 0;
+    if (s2_debug_flag(S2_DEBUG_NO_MFMA)) return 0;   // test-only: force the vector kernels
     return t.fwd_cls[0] + t.fwd_cls[1] + t.fwd_cls[2];
 }
 
@@ -572,7 +583,7 @@ static int row_groups(const S2DeviceTables &t, int nbh, int nrows)
             hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || ncu <= 0)
             ncu = 256;
     }
-    static const bool off = std::getenv("S2_NO_ROW_GROUPS") != nullptr;   // debugging aid
+    const bool off = s2_debug_flag(S2_DEBUG_NO_ROW_GROUPS);   // test-only
     const bool fits = t.nlon_out * 4 <= 1024 && t.nlon_in % (2 * kTileCols) == 0;
     return (!off && fits && long(nrows) * nbh <= ncu) ? 2 : 1;
 }
@@ -583,15 +594,6 @@ int s2_nattn_fwd_mfma(const S2DeviceTables &t, int nbh, int nrows, float scale, 
     const bool two = t.nlon_in % (2 * kTileCols) == 0;
     const int rgroups = row_groups(t, nbh, nrows);
     const size_t lds = rgroups * (two ? 4 : 2) * size_t(kTileFloats) * sizeof(float);
-    static bool configured = false;
-    if (!configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(nattn_fwd_mfma<2>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, int(8 * kTileFloats * sizeof(float))) != hipSuccess ||
-            hipFuncSetAttribute(reinterpret_cast<const void *>(nattn_fwd_mfma<1>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, int(4 * kTileFloats * sizeof(float))) != hipSuccess)
-            return -1;
-        configured = true;
-    }
     S2TraceScope tr("nattn_fwd_mfma", nbh * (t.fwd_pairs[0] + t.fwd_pairs[1] + t.fwd_pairs[2]), st);
     if (two)
         hipLaunchKernelGGL(nattn_fwd_mfma<2>, dim3((unsigned)(long(nrows) * nbh)), dim3(t.nlon_out * 2 * rgroups), lds, st, t,
@@ -609,13 +611,6 @@ int s2_nattn_bwd_dq_mfma(const S2DeviceTables &t, int nbh, int nrows, float scal
     const bool two = t.nlon_in % (2 * kTileCols) == 0;
     const int rgroups = row_groups(t, nbh, nrows);
     const size_t lds = rgroups * (two ? 4 : 2) * size_t(kTileB) * sizeof(float);
-    static bool configured = false;
-    if (!configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(nattn_bwd_dq_mfma<2>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, int(8 * kTileB * sizeof(float))) != hipSuccess)
-            return -1;
-        configured = true;
-    }
     S2TraceScope tr("nattn_bwd_dq_mfma", nbh * (t.fwd_pairs[0] + t.fwd_pairs[1] + t.fwd_pairs[2]), st);
     if (two)
         hipLaunchKernelGGL(nattn_bwd_dq_mfma<2>, dim3((unsigned)(long(nrows) * nbh)), dim3(t.nlon_out * 2 * rgroups), lds, st,
@@ -630,8 +625,7 @@ int s2_nattn_bwd_dkdv_mfma_rows(const S2DeviceTables &t, int d, int e)
 {
     const int nw = t.nlon_in / 32;
     if (d != 32 || e != 32 || t.pscale != 1 || t.nlon_in % kTileCols != 0 || nw < 2 || nw > 16) return 0;
-    static const bool off = std::getenv("S2_NO_MFMA") != nullptr;
-    if (off) return 0;
+    if (s2_debug_flag(S2_DEBUG_NO_MFMA)) return 0;
     return t.bwd_cls[0] + t.bwd_cls[1] + t.bwd_cls[2];
 }
 
@@ -642,13 +636,6 @@ int s2_nattn_bwd_dkdv_mfma(const S2DeviceTables &t, int nbh, int nrows, float sc
     const bool two = t.nlon_in % (2 * kTileCols) == 0;
     const int rgroups = row_groups(t, nbh, nrows);
     const size_t lds = rgroups * (two ? 4 : 2) * size_t(kTileC) * sizeof(float);
-    static bool configured = false;
-    if (!configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(nattn_bwd_dkdv_mfma<2>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, int(8 * kTileC * sizeof(float))) != hipSuccess)
-            return -1;
-        configured = true;
-    }
     S2TraceScope tr("nattn_bwd_dkdv_mfma", nbh * (t.bwd_pairs[0] + t.bwd_pairs[1] + t.bwd_pairs[2]), st);
     if (two)
         hipLaunchKernelGGL(nattn_bwd_dkdv_mfma<2>, dim3((unsigned)(long(nrows) * nbh)), dim3(t.nlon_in * 2 * rgroups), lds, st,

@@ -825,20 +825,22 @@ int num_segments(int per, int lo, int hi, int nw)
     return nsl > max_nsl ? max_nsl : nsl;
 }
 
-template <class K>
-bool raise_lds(K kern, size_t lds, bool &done)
-{
-    if (!done) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                int(lds)) != hipSuccess)
-            return false;
-        done = true;
-    }
-    return true;
-}
+constexpr size_t kLdsFwdStream = 3 * size_t(kSlot) * sizeof(float);
+constexpr size_t kLdsDqStream = 4 * size_t(2 * kD * kPitchQ) * sizeof(float) + 8 * sizeof(unsigned);
+constexpr size_t kLdsDkdvStream = 4 * size_t((2 * kD + 2) * kPitchQ) * sizeof(float) + 8 * sizeof(unsigned);
 
 }  // namespace
 
+
+int s2_nattn_stream_configure()
+{
+    auto raise = [](auto kern, size_t lds) {
+        return hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   int(lds)) == hipSuccess;
+    };
+    return raise(nattn_fwd_stream, kLdsFwdStream) && raise(nattn_bwd_dq_stream, kLdsDqStream) &&
+           raise(nattn_bwd_dkdv_stream, kLdsDkdvStream) ? 0 : -1;
+}
 
 bool s2_nattn_stream_supported(const S2DeviceTables &t, int d, int e)
 {
@@ -852,9 +854,8 @@ int s2_nattn_fwd_stream(const S2DeviceTables &t, int nbh, float qscale, const fl
     const int nw = t.st_nw;
     const int nseg = (t.nlon_out + kSegS - 1) / kSegS;
     const int nsl = num_segments(nbh * nseg, t.st_lo, t.st_hi, nw);
-    const size_t lds = 3 * size_t(kSlot) * sizeof(float);
-    static bool configured = false;
-    if (!raise_lds(nattn_fwd_stream, lds, configured)) return -1;
+    const size_t lds = kLdsFwdStream;
+    if (s2_debug_flag(S2_DEBUG_FAIL_LAUNCH)) return -1;
     S2TraceScope tr("nattn_fwd_stream", nbh * t.fwd_pairs[3], st);
     hipLaunchKernelGGL(nattn_fwd_stream, dim3(unsigned(nsl * nbh * nseg)), dim3(64 * nw), lds, st, t, nbh, nsl, qscale, q,
                        k, v, out, lse);
@@ -878,9 +879,7 @@ int s2_nattn_bwd_dq_stream(const S2DeviceTables &t, int nbh, float scale, const 
 {
     const int nseg = (t.nlon_out + kSegQ - 1) / kSegQ;
     const int nsl = num_segments(nbh * nseg, t.st_lo, t.st_hi, t.st_nw);
-    const size_t lds = 4 * size_t(2 * kD * kPitchQ) * sizeof(float) + 8 * sizeof(unsigned);
-    static bool configured = false;
-    if (!raise_lds(nattn_bwd_dq_stream, lds, configured)) return -1;
+    const size_t lds = kLdsDqStream;
     S2TraceScope tr("nattn_bwd_dq_stream", nbh * t.fwd_pairs[3], st);
     hipLaunchKernelGGL(nattn_bwd_dq_stream, dim3(unsigned(nsl * nbh * nseg)), dim3(64 * t.st_nw), lds, st, t, nbh, nsl,
                        scale, q, k, v, o, lse, go, dq, Dws);
@@ -893,9 +892,7 @@ int s2_nattn_bwd_dkdv_stream(const S2DeviceTables &t, int nbh, float scale, cons
 {
     const int nseg = (t.nlon_in + kSegQ - 1) / kSegQ;
     const int nsl = num_segments(nbh * nseg, t.tst_lo, t.tst_hi, t.tst_nw);
-    const size_t lds = 4 * size_t((2 * kD + 2) * kPitchQ) * sizeof(float) + 8 * sizeof(unsigned);
-    static bool configured = false;
-    if (!raise_lds(nattn_bwd_dkdv_stream, lds, configured)) return -1;
+    const size_t lds = kLdsDkdvStream;
     S2TraceScope tr("nattn_bwd_dkdv_stream", nbh * t.bwd_pairs[3], st);
     hipLaunchKernelGGL(nattn_bwd_dkdv_stream, dim3(unsigned(nsl * nbh * nseg)), dim3(64 * t.tst_nw), lds, st, t, nbh,
                        nsl, scale, q, k, v, lse, go, Dws, dk, dv);

@@ -455,10 +455,19 @@ nattn_fwd_tiled(S2DeviceTables t, int nbh, int first_row, float qscale, const fl
     }
 }
 
+// dynamic LDS of the 8-wave kernel: the wavefronts' staging buffers, reused for the merge of their softmax states
+template <int PS>
+constexpr size_t fwd_tiled_lds()
+{
+    constexpr size_t stage_fl = size_t(kWaves) * 2 * Geo<PS>::TILE, merge_fl = size_t(kWaves / 2) * kState * 64;
+    return (stage_fl > merge_fl ? stage_fl : merge_fl) * sizeof(float);
+}
+
 template <int D, int PS, bool UP = false>
 int launch_fwd_tiled(const S2DeviceTables &t, int skip_rows, int nbh, float qscale, const float *q, const float *k,
                      const float *v, float *out, float *lse, hipStream_t st)
 {   // t.row_order already points past the skip_rows latitudes another kernel has taken
+    if (s2_debug_flag(S2_DEBUG_FAIL_LAUNCH)) return -1;
     const int nseg = UP ? ((t.nlon_in + kSeg - 1) / kSeg) * t.upscale : (t.nlon_out + kSeg - 1) / kSeg;
     const int nsplit = t.fwd_cls[0] + t.fwd_cls[1] + t.fwd_cls[2];   // latitudes split over several wavefronts
     constexpr int mode = 0;   // 1: everything through the one-wave kernel, 2: everything through the 8-wave kernel
@@ -467,16 +476,8 @@ int launch_fwd_tiled(const S2DeviceTables &t, int skip_rows, int nbh, float qsca
         const int first_row = mode == 2 ? 0 : 1;   // mode 2: every latitude through the 8-wave kernel
         const long nblk = long((nbh + kWaves - 1) / kWaves) * nseg *
                           (8 * t.fwd_cls[0] + 4 * t.fwd_cls[1] + 2 * t.fwd_cls[2] + (first_row ? 0 : t.fwd_cls[3]));
-        constexpr size_t stage_fl = size_t(kWaves) * 2 * Geo<PS>::TILE, merge_fl = size_t(kWaves / 2) * kState * 64;
-        const size_t lds = (stage_fl > merge_fl ? stage_fl : merge_fl) * sizeof(float);
+        const size_t lds = fwd_tiled_lds<PS>();
         auto kern = nattn_fwd_tiled<D, PS, kWaves, UP>;
-        static bool configured = false;   // raise the dynamic LDS limit once (above 64 KiB needs the attribute)
-        if (!configured) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    int(lds)) != hipSuccess)
-                return -1;
-            configured = true;
-        }
         S2TraceScope tr("nattn_fwd_tiled<8 waves>",
                         nbh * (t.fwd_pairs[0] + t.fwd_pairs[1] + t.fwd_pairs[2] + (first_row ? 0.0 : t.fwd_pairs[3])), st);
         hipLaunchKernelGGL(kern, dim3((unsigned)nblk), dim3(64 * kWaves), lds, st, t, nbh, first_row, qscale, q, k, v,
@@ -486,7 +487,7 @@ int launch_fwd_tiled(const S2DeviceTables &t, int skip_rows, int nbh, float qsca
     // the rest: one wavefront per workgroup
     const int first_row = mode == 1 ? 0 : nsplit;
     const long nrows = t.nlat_out - skip_rows - first_row;
-    static const bool no_stream = std::getenv("S2_NO_STREAM") != nullptr;   // debugging aid: one-wave kernel instead
+    const bool no_stream = s2_debug_flag(S2_DEBUG_NO_STREAM);   // test-only: one-wave kernel instead
     if (!UP && nrows > 0 && mode == 0 && !no_stream && s2_nattn_stream_supported(t, D, D))
         return s2_nattn_fwd_stream(t, nbh, qscale, q, k, v, out, lse, st);
     if (nrows > 0) {
@@ -499,6 +500,17 @@ int launch_fwd_tiled(const S2DeviceTables &t, int skip_rows, int nbh, float qsca
 }
 
 }  // namespace
+
+int s2_nattn_tiled_configure()
+{
+    auto raise = [](auto kern, size_t lds) {
+        return hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   int(lds)) == hipSuccess;
+    };
+    return raise(nattn_fwd_tiled<32, 1, kWaves, false>, fwd_tiled_lds<1>()) &&
+           raise(nattn_fwd_tiled<32, 2, kWaves, false>, fwd_tiled_lds<2>()) &&
+           raise(nattn_fwd_tiled<32, 1, kWaves, true>, fwd_tiled_lds<1>()) ? 0 : -1;
+}
 
 bool s2_nattn_fwd_tiled_supported(const S2DeviceTables &t, int d, int e)
 {
@@ -521,7 +533,7 @@ int s2_nattn_fwd_tiled(const S2DeviceTables &t, int nbh, int d, int e, float sca
     S2DeviceTables tv = t;
     const int nm = s2_nattn_fwd_mfma_rows(t, d, e);
     if (nm > 0) {
-        s2_nattn_fwd_mfma(t, nbh, nm, scale, q, k, v, out, lse, st);
+        if (s2_nattn_fwd_mfma(t, nbh, nm, scale, q, k, v, out, lse, st)) return -1;
         tv.row_order = t.row_order + nm;
     }
     if (s2_nattn_stream_supported(t, d, e)) {

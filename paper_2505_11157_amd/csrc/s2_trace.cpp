@@ -1,5 +1,6 @@
 // Per-launch timing for benchmarks: HIP events around each kernel launch, on the launch stream.
 // Off by default; when off the hooks cost one branch.  Not thread safe (a benchmarking aid).
+#include <atomic>
 #include <vector>
 
 #include "s2_internal.h"
@@ -61,4 +62,20 @@ extern "C" int s2_trace_get(int index, const char **name, float *ms, double *pai
     if (ms) *ms = t;
     if (pairs) *pairs = e.pairs;
     return S2_OK;
+}
+
+// Test-only dispatch switches (s2_debug_control in the C ABI).
+namespace {
+std::atomic<unsigned> g_debug{0u};
+}
+
+bool s2_debug_flag(unsigned bit) { return (g_debug.load(std::memory_order_relaxed) & bit) != 0; }
+
+extern "C" unsigned s2_debug_control(unsigned set_bits, unsigned clear_bits)
+{
+    unsigned cur = g_debug.load(), next;
+    do {
+        next = (cur | set_bits) & ~clear_bits;
+    } while (!g_debug.compare_exchange_weak(cur, next));
+    return next;
 }

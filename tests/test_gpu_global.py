@@ -4,7 +4,9 @@ Inputs are rounded to bf16 before either side sees them.  Tolerance for bf16 ten
 |x - ref| <= 2e-2 |ref| + 2e-2 rms(ref) elementwise (a pure relative bound is meaningless at zero
 crossings); the float32 logsumexp is held to 1e-3 absolute.
 """
+import json
 import math
+import os
 
 import numpy as np
 import pytest
@@ -16,15 +18,32 @@ from paper_2505_11157_amd.workloads import CONFIGS, make_inputs, round_to_bf16
 
 pytestmark = pytest.mark.gpu
 
+LSE_TOL = 1e-3      # float32 logsumexp of bf16 inputs, absolute
 
-def _close(x, ref, what, rel=2e-2):
+
+_REPORT = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out", "parity_report.jsonl")
+
+
+def _close(x, ref, what, rel=2e-2, case="", abs_only=None):
+    """bf16 tensors: |x - ref| <= rel |ref| + rel rms(ref); float32 lse: |x - ref| <= abs_only.  Prints and logs what
+    was achieved (largest error, largest error relative to |ref| + rms(ref))."""
     err = np.abs(x - ref)
-    tol = rel * np.abs(ref) + rel * np.sqrt((ref ** 2).mean())
+    rms = np.sqrt((ref ** 2).mean())
+    tol = np.full_like(err, abs_only) if abs_only is not None else rel * np.abs(ref) + rel * rms
+    rec = dict(case=case, what=what, n=int(err.size), max_abs=float(err.max()),
+               max_rel_to_ref_plus_rms=float((err / (np.abs(ref) + rms)).max()), rms_ref=float(rms))
+    print("parity %-24s %-4s max|err| %.3e  max err/(|ref|+rms) %.3e" % (case, what, rec["max_abs"],
+                                                                       rec["max_rel_to_ref_plus_rms"]), flush=True)
+    try:
+        with open(_REPORT, "a") as f:
+            f.write(json.dumps(rec) + "\n")
+    except OSError:
+        pass
     assert np.isfinite(x).all(), what
-    assert (err <= tol).all(), "%s: max err %.3e, max excess %.3e" % (what, err.max(), (err - tol).max())
+    assert (err <= tol).all(), "%s %s: max err %.3e, max excess %.3e" % (case, what, err.max(), (err - tol).max())
 
 
-def run_global(grid_type, nlat, nlon, B, H, arrs, slices, scale=None, rel=2e-2):
+def run_global(grid_type, nlat, nlon, B, H, arrs, slices, scale=None, rel=2e-2, case=""):
     d = arrs[0].shape[-1]
     scale = 1 / math.sqrt(d) if scale is None else scale
     g = S.s2_grid_init(grid_type, nlat, nlon, nlat, nlon, math.pi)
@@ -41,11 +60,12 @@ def run_global(grid_type, nlat, nlon, B, H, arrs, slices, scale=None, rel=2e-2):
         a64 = [a[sl].astype(np.float64) for a in arrs]
         r_out, r_lse = O.global_fwd(grid_type, nlat, nlon, a64[0], a64[1], a64[2], scale)
         r_dq, r_dk, r_dv = O.global_bwd(grid_type, nlat, nlon, *a64, scale)
-        assert np.abs(lse[sl] - r_lse).max() < 1e-3, "lse[%d]: %.3e" % (s, np.abs(lse[sl] - r_lse).max())
-        _close(out[sl], r_out, "out[%d]" % s, rel)
-        _close(dq[sl], r_dq, "dq[%d]" % s, rel)
-        _close(dk[sl], r_dk, "dk[%d]" % s, rel)
-        _close(dv[sl], r_dv, "dv[%d]" % s, rel)
+        cs = "%s[%d]" % (case, s)
+        _close(lse[sl], r_lse, "lse", case=cs, abs_only=LSE_TOL)
+        _close(out[sl], r_out, "out", rel, cs)
+        _close(dq[sl], r_dq, "dq", rel, cs)
+        _close(dk[sl], r_dk, "dk", rel, cs)
+        _close(dv[sl], r_dv, "dv", rel, cs)
     return out, lse, dq, dk, dv
 
 
@@ -57,7 +77,7 @@ def test_global_small_grids(gt, nlat, nlon, B, H):
     arrs = [round_to_bf16(rng.standard_normal((B * H, N, 64)).astype(np.float32)) for _ in range(4)]
     # with a handful of tokens the bf16 rounding of each probability is not averaged over a long sum:
     # the two-token grid gets twice the bound
-    run_global(gt, nlat, nlon, B, H, arrs, range(B * H), rel=4e-2 if N < 8 else 2e-2)
+    run_global(gt, nlat, nlon, B, H, arrs, range(B * H), rel=4e-2 if N < 8 else 2e-2, case="g%dx%d" % (nlat, nlon))
 
 
 @pytest.mark.parametrize("seed", range(24))
@@ -71,13 +91,16 @@ def test_global_random_grids(seed):
     N = nlat * nlon
     arrs = [round_to_bf16(rng.standard_normal((B * H, N, 64)).astype(np.float32)) for _ in range(4)]
     scale = float(rng.uniform(0.05, 0.2)) * (1 if rng.integers(0, 4) else -1)
-    run_global(gt, nlat, nlon, B, H, arrs, [int(rng.integers(0, B * H))], scale=scale, rel=4e-2 if N < 8 else 2e-2)
+    run_global(gt, nlat, nlon, B, H, arrs, [int(rng.integers(0, B * H))], scale=scale, rel=4e-2 if N < 8 else 2e-2,
+               case="grand%d" % seed)
 
 
-def test_global_config5_slice():
+def test_global_config5_slices():
+    # eight of the 32 (batch, head) slices, one per residue mod 8 (workgroups are dealt to the eight XCDs by their id
+    # mod 8 and each XCD walks a contiguous piece of the (slice, block) list)
     c, arrs = make_inputs(5)
-    nbh = c["batch"] * c["heads"]
-    r1 = run_global(c["grid_type"], c["nlat_in"], c["nlon_in"], c["batch"], c["heads"], arrs, [nbh - 1])
+    r1 = run_global(c["grid_type"], c["nlat_in"], c["nlon_in"], c["batch"], c["heads"], arrs,
+                    [0, 9, 18, 27, 4, 13, 22, 31], case="cfg5")
     r2 = run_global(c["grid_type"], c["nlat_in"], c["nlon_in"], c["batch"], c["heads"], arrs, [])
     for a, b in zip(r1, r2):
         assert np.array_equal(a, b)      # no atomics: bit-reproducible

@@ -161,3 +161,22 @@ def test_random_grids_neighbor_lists(seed):
     for h in range(gd["nlat_out"]):
         for w in range(nlon_out):
             assert np.array_equal(S.s2_grid_get_neighbors_at(g, h, w), np.flatnonzero(masks[h][w])), (h, w)
+
+
+def test_debug_switches_and_host_only_handle():
+    # the test-only dispatch switches are plain bits; without a HIP device a handle is host-only and every
+    # attention call reports S2_ERR_DEVICE instead of launching (or falling back to) anything
+    assert S.s2_debug_control(0, 0xFFFFFFFF) == 0
+    assert S.s2_debug_control(S.S2_DEBUG_NO_MFMA | S.S2_DEBUG_FAIL_LAUNCH, 0) == 9
+    assert S.s2_debug_control(S.S2_DEBUG_NO_STREAM, S.S2_DEBUG_NO_MFMA) == 10
+    assert S.s2_debug_control(0, 0xFFFFFFFF) == 0
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a device is present: the handle is not host-only")
+    g = S.s2_grid_init(0, 9, 16, 9, 16, 0.5)
+    L = S.lib()
+    buf = (ctypes.c_float * 64)()
+    p = ctypes.cast(buf, ctypes.c_void_p)
+    assert L.s2_nattn_fwd(g.handle, 1, 1, 4, 4, S.S2_F32, 1.0, p, p, p, p, p, None) == S.S2_ERR_DEVICE
+    assert "no device tables" in S.s2_last_error()
+    assert L.s2_nattn_bwd(g.handle, 1, 1, 4, 4, S.S2_F32, 1.0, p, p, p, p, p, p, p, p, p, p, 1 << 20, None) == S.S2_ERR_DEVICE
