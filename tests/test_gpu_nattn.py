@@ -1,15 +1,16 @@
 """GPU parity of the neighborhood attention (through the C ABI) against the float64 oracle.
 
 Tolerance (float32 path), ref = oracle in float64 on the same float32 inputs:
-  out, lse on unit-variance inputs:  |x - ref| <= 1e-6 + 1e-5 |ref|                      (the stated bound)
-  dq, dk, dv, and out, lse on inputs that make the softmax peaked:
-                                     |x - ref| <= 1e-6 + 1e-5 |ref| + C * 2^-24 * cond
+  out, lse, dq, dk, dv on the workloads and on every unit-variance case:
+                                     |x - ref| <= 1e-6 + 1e-5 |ref|                      (the stated bound)
+  cases whose logits are large (q and k scaled by 6: nearly one-hot softmax; the random tiny grids with scales up to
+  0.6 and disks of up to 2.2 rad):   |x - ref| <= 1e-6 + 1e-5 |ref| + C * 2^-24 * cond
 where cond is the oracle's first-order rounding sensitivity of that element: the sum of the absolute values of the
-elementary products it is made of, each weighted by the number of rounded factors it carries.  A gradient element is
-a sum of hundreds of signed terms whose absolute sum is far above |ref| wherever they cancel, so a bound relative to
-|ref| alone cannot hold there in float32 however the sum is ordered; 2^-24 * cond is what one rounding per product
-costs.  C = 4 (C_GRAD) and C = 2 (C_PEAKED) are twice the largest excess observed over all cases of this file, in units of
-2^-24 * cond (the observed figures per workload are printed by every comparison and recorded in the design notes).
+elementary products it is made of, each weighted by the number of rounded factors it carries.  With logits of
+magnitude 100 one float32 rounding of a logit already changes its probability by 1e-5, so no float32 evaluation can
+meet a bound relative to |ref| alone there; 2^-24 * cond is what one rounding per product costs.  C = 4 is twice
+the largest excess observed over all such cases, in units of 2^-24 * cond (1.9, on dv of a peaked case; every
+comparison prints what it achieved, and the design notes record the figures per workload).
 """
 import json
 import math
@@ -26,8 +27,7 @@ from paper_2505_11157_amd.workloads import CONFIGS, grid_dict, make_inputs
 pytestmark = pytest.mark.gpu
 
 U32 = 2.0 ** -24
-C_GRAD = 64.0      # gradients
-C_PEAKED = 64.0    # out, lse when the logits are tens of units apart
+C_LARGE_LOGITS = 4.0
 _REPORT = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out", "parity_report.jsonl")
 
 
@@ -45,7 +45,7 @@ def compare(x, ref, what, cond=None, C=0.0, case=""):
                max_rel=float((err / np.maximum(np.abs(ref), 1e-30))[np.abs(ref) > 1e-3].max()) if (np.abs(ref) > 1e-3).any() else 0.0,
                n_over_strict=int(over.sum()), max_excess_strict=float((err - strict).max()))
     if cond is not None:
-        rec["C_obs"] = float(((err - strict) / (U32 * cond)).max())
+        rec["C_obs"] = float(((err - strict) / np.maximum(U32 * cond, 1e-300)).max())
     print("parity %-28s %-4s max|err| %.3e  max rel %.3e  over strict %d/%d (excess %.2e)%s" % (
         case, what, rec["max_abs"], rec["max_rel"], rec["n_over_strict"], rec["n"], max(rec["max_excess_strict"], 0.0),
         "  C_obs %.3f" % rec["C_obs"] if cond is not None else ""), flush=True)
@@ -59,7 +59,7 @@ def compare(x, ref, what, cond=None, C=0.0, case=""):
         case, what, err.max(), (err - tol).max(), int((err > tol).sum()))
 
 
-def run_case(c, arrs, slices, peaked=False, case=""):
+def run_case(c, arrs, slices, C=0.0, case=""):
     """Run fwd+bwd on the GPU for the whole batch, compare the (b*heads) slices in `slices` with the oracle."""
     gd = grid_dict(c)
     g = _grid(gd)
@@ -82,15 +82,9 @@ def run_case(c, arrs, slices, peaked=False, case=""):
         r_dq, r_dk, r_dv = O.nattn_bwd(gd, *a64, scale, brute=brute)
         c_out, c_lse, c_dq, c_dk, c_dv = O.nattn_cond(gd, *a64, scale, brute=brute)
         cs = "%s[%d]" % (case, s)
-        if peaked:
-            compare(out[sl], r_out, "out", c_out, C_PEAKED, cs)
-            compare(lse[sl], r_lse, "lse", c_lse, C_PEAKED, cs)
-        else:
-            compare(out[sl], r_out, "out", case=cs)
-            compare(lse[sl], r_lse, "lse", case=cs)
-        compare(dq[sl], r_dq, "dq", c_dq, C_GRAD, cs)
-        compare(dk[sl], r_dk, "dk", c_dk, C_GRAD, cs)
-        compare(dv[sl], r_dv, "dv", c_dv, C_GRAD, cs)
+        for what, x, ref, cnd in (("out", out, r_out, c_out), ("lse", lse, r_lse, c_lse), ("dq", dq, r_dq, c_dq),
+                                  ("dk", dk, r_dk, c_dk), ("dv", dv, r_dv, c_dv)):
+            compare(x[sl], ref, what, cnd, C, cs)
     return out, lse, dq, dk, dv
 
 
@@ -298,7 +292,7 @@ def test_peaked_softmax(ci, sign):
     arrs = [arrs[0] * np.float32(6.0), arrs[1] * np.float32(6.0), arrs[2], arrs[3]]
     c = dict(c, scale=sign / math.sqrt(c["d"]))
     nbh = c["batch"] * c["heads"]
-    run_case(c, arrs, range(min(nbh, 2)), peaked=True, case="peaked%d%s" % (ci, "+" if sign > 0 else "-"))
+    run_case(c, arrs, range(min(nbh, 2)), C=C_LARGE_LOGITS, case="peaked%d%s" % (ci, "+" if sign > 0 else "-"))
 
 
 def test_peaked_softmax_vector_kernels_on_dense_latitudes():
@@ -307,7 +301,7 @@ def test_peaked_softmax_vector_kernels_on_dense_latitudes():
     c, arrs = make_inputs(SMALL[13], seed=613)
     arrs = [arrs[0] * np.float32(6.0), arrs[1] * np.float32(6.0), arrs[2], arrs[3]]
     with debug_switches(S.S2_DEBUG_NO_MFMA | S.S2_DEBUG_NO_STREAM):
-        run_case(c, arrs, [1], peaked=True, case="peaked13-vector")
+        run_case(c, arrs, [1], C=C_LARGE_LOGITS, case="peaked13-vector")
 
 
 @pytest.mark.parametrize("which", ["cfg3", "small11", "small13"])
@@ -433,14 +427,12 @@ def test_random_small_grids(seed):
     a64 = [a.astype(np.float64) for a in (q, k, v, go)]
     r_out, r_lse = O.nattn_fwd(gd, a64[0], a64[1], a64[2], scale, brute=True)
     r_dq, r_dk, r_dv = O.nattn_bwd(gd, *a64, scale, brute=True)
-    _, _, c_dq, c_dk, c_dv = O.nattn_cond(gd, *a64, scale, brute=True)
+    c_out, c_lse, c_dq, c_dk, c_dv = O.nattn_cond(gd, *a64, scale, brute=True)
     n = lambda x: x[0].cpu().numpy().astype(np.float64)
     cs = "rand%d" % seed
-    compare(n(out), r_out, "out", case=cs)
-    compare(n(lse), r_lse, "lse", case=cs)
-    compare(n(dq), r_dq, "dq", c_dq, C_GRAD, cs)
-    compare(n(dk), r_dk, "dk", c_dk, C_GRAD, cs)
-    compare(n(dv), r_dv, "dv", c_dv, C_GRAD, cs)
+    for what, x, ref, cnd in (("out", out, r_out, c_out), ("lse", lse, r_lse, c_lse), ("dq", dq, r_dq, c_dq),
+                              ("dk", dk, r_dk, c_dk), ("dv", dv, r_dv, c_dv)):
+        compare(n(x), ref, what, cnd, C_LARGE_LOGITS, cs)
 
 
 @pytest.mark.parametrize("seed", range(48))
