@@ -143,6 +143,23 @@ int s2_nattn_bwd(const s2_grid_t *g, int batch, int heads, int d_qk, int d_v, in
                  const void *dout, void *dq, void *dk, void *dv,
                  void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/*
+ * s2_nattn_bwd for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and errors as
+ * s2_nattn_bwd without `workspace`: the per-point scratch lives in a fixed array of S2_STATIC_SCRATCH_BYTES in
+ * device memory that each GPU the library runs on holds until the process ends (its address is looked up once per
+ * device in s2_grid_init).  The call allocates nothing and calls no allocating routine (keep s2_trace_enable off:
+ * tracing creates events).  Limit: batch*heads*nlat_out*nlon_out <= s2_nattn_bwd_static_max_points() (2 097 152;
+ * workload 3 needs 1 056 768), otherwise S2_ERR_WORKSPACE; S2_ERR_DEVICE if the handle's device is not the current
+ * device.  All calls on one GPU share the array: calls that overlap on one GPU (different streams or threads)
+ * race; calls on one stream are ordered and each call overwrites what it later reads, so nothing needs clearing.
+ */
+#define S2_STATIC_SCRATCH_BYTES (8u << 20)
+size_t s2_nattn_bwd_static_max_points(void);
+int s2_nattn_bwd_static(const s2_grid_t *g, int batch, int heads, int d_qk, int d_v, int dtype, float scale,
+                        const void *q, const void *k, const void *v, const void *out, const float *lse,
+                        const void *dout, void *dq, void *dk, void *dv, void *hip_stream);
+
 /* Bytes of device scratch s2_attn_global_fwd / s2_attn_global_bwd need (token-transposed
  * copies of the operands that are contracted over tokens, and per-token constants of the
  * backward pass). */

@@ -71,6 +71,11 @@ def lib():
         L.s2_nattn_bwd.argtypes = [_vp, _i, _i, _i, _i, _i, ctypes.c_float, _vp, _vp, _vp, _vp, _vp, _vp,
                                    _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
         L.s2_nattn_bwd.restype = _i
+        L.s2_nattn_bwd_static.argtypes = [_vp, _i, _i, _i, _i, _i, ctypes.c_float, _vp, _vp, _vp, _vp, _vp, _vp,
+                                          _vp, _vp, _vp, _vp]
+        L.s2_nattn_bwd_static.restype = _i
+        L.s2_nattn_bwd_static_max_points.argtypes = []
+        L.s2_nattn_bwd_static_max_points.restype = ctypes.c_size_t
         L.s2_attn_global_fwd_workspace_bytes.argtypes = [_vp, _i, _i, _i, _i]
         L.s2_attn_global_fwd_workspace_bytes.restype = ctypes.c_size_t
         L.s2_attn_global_bwd_workspace_bytes.argtypes = [_vp, _i, _i, _i, _i]
@@ -225,6 +230,25 @@ def s2_nattn_bwd(g, q, k, v, out, lse, dout, scale, dq=None, dk=None, dv=None, w
     _check(lib().s2_nattn_bwd(g.handle, B, H, d, e, _dtype_code(q), float(scale), q.data_ptr(), k.data_ptr(),
                               v.data_ptr(), out.data_ptr(), lse.data_ptr(), dout.data_ptr(), dq.data_ptr(),
                               dk.data_ptr(), dv.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream()))
+    return dq, dk, dv
+
+
+def s2_nattn_bwd_static_max_points():
+    return int(lib().s2_nattn_bwd_static_max_points())
+
+
+def s2_nattn_bwd_static(g, q, k, v, out, lse, dout, scale, dq, dk, dv):
+    """s2_nattn_bwd on the library's static device scratch: allocates nothing, so the gradients are passed in."""
+    _dev(q, k, v, out, lse, dout, dq, dk, dv)
+    B, H, d = q.shape[:3]
+    e = v.shape[2]
+    if out.shape != (B, H, e, g.nlat_out, g.nlon_out) or dout.shape != out.shape \
+            or lse.shape != (B, H, g.nlat_out, g.nlon_out) or k.shape != (B, H, d, g.nlat_in, g.nlon_in) \
+            or dq.shape != q.shape or dk.shape != k.shape or dv.shape != v.shape:
+        raise ValueError("tensor shapes do not match the grid handle")
+    _check(lib().s2_nattn_bwd_static(g.handle, B, H, d, e, _dtype_code(q), float(scale), q.data_ptr(), k.data_ptr(),
+                                     v.data_ptr(), out.data_ptr(), lse.data_ptr(), dout.data_ptr(), dq.data_ptr(),
+                                     dk.data_ptr(), dv.data_ptr(), _stream()))
     return dq, dk, dv
 
 

@@ -12,7 +12,7 @@
 #include <cstring>
 #include <numeric>
 
-#include "s2_internal.h"
+#include "s2_nattn_kernels.h"
 
 namespace {
 
@@ -197,6 +197,7 @@ static int upload_tables(s2_grid *g)
                 (void)hipGetLastError();
                 return s2_fail(S2_ERR_DEVICE, "raising the LDS limit of a kernel failed");
             }
+            (void)s2_static_scratch_setup(g->device);   // on failure s2_nattn_bwd_static reports it
             done[g->device] = 1;
         }
     }

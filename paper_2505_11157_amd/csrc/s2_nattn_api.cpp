@@ -44,10 +44,10 @@ extern "C" int s2_nattn_fwd(const s2_grid_t *g, int batch, int heads, int d_qk, 
     return S2_OK;
 }
 
-extern "C" int s2_nattn_bwd(const s2_grid_t *g, int batch, int heads, int d_qk, int d_v, int dtype, float scale,
-                            const void *q, const void *k, const void *v, const void *out, const float *lse,
-                            const void *dout, void *dq, void *dk, void *dv, void *workspace, size_t workspace_bytes,
-                            void *hip_stream)
+// Argument checks and dispatch shared by s2_nattn_bwd and s2_nattn_bwd_static; Dws: device scratch for D_i.
+int s2_nattn_bwd_run(const s2_grid_t *g, int batch, int heads, int d_qk, int d_v, int dtype, float scale,
+                     const void *q, const void *k, const void *v, const void *out, const float *lse, const void *dout,
+                     void *dq, void *dk, void *dv, float *Dws, hipStream_t st)
 {
     int rc = check_common(g, batch, heads, d_qk, d_v, dtype);
     if (rc) return rc;
@@ -56,15 +56,10 @@ extern "C" int s2_nattn_bwd(const s2_grid_t *g, int batch, int heads, int d_qk, 
     if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out) || misaligned(lse) || misaligned(dout) ||
         misaligned(dq) || misaligned(dk) || misaligned(dv))
         return s2_fail(S2_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
-    if (!workspace || workspace_bytes < s2_nattn_bwd_workspace_bytes(g, batch, heads, d_qk, d_v, dtype))
-        return s2_fail(S2_ERR_WORKSPACE, "workspace missing or smaller than s2_nattn_bwd_workspace_bytes()");
-    if (misaligned(workspace)) return s2_fail(S2_ERR_WORKSPACE, "workspace must be 16-byte aligned");
-    hipStream_t st = static_cast<hipStream_t>(hip_stream);
     auto *bwd = s2_nattn_bwd_tiled_supported(g->dt, d_qk, d_v) ? s2_nattn_bwd_tiled : s2_nattn_bwd_generic;
     if (bwd(g->dt, batch * heads, d_qk, d_v, scale, static_cast<const float *>(q), static_cast<const float *>(k),
             static_cast<const float *>(v), static_cast<const float *>(out), lse, static_cast<const float *>(dout),
-            static_cast<float *>(dq), static_cast<float *>(dk), static_cast<float *>(dv),
-            static_cast<float *>(workspace), st))
+            static_cast<float *>(dq), static_cast<float *>(dk), static_cast<float *>(dv), Dws, st))
         return s2_fail(S2_ERR_DEVICE, "backward launch configuration failed");
     // input latitudes of weight zero (the pole row of the grid of App. A.1): dk = dv = 0 exactly
     for (int lat : g->zero_lat) {
@@ -73,4 +68,17 @@ extern "C" int s2_nattn_bwd(const s2_grid_t *g, int batch, int heads, int d_qk, 
     }
     S2_HIP_CHECK(hipGetLastError());
     return S2_OK;
+}
+
+extern "C" int s2_nattn_bwd(const s2_grid_t *g, int batch, int heads, int d_qk, int d_v, int dtype, float scale,
+                            const void *q, const void *k, const void *v, const void *out, const float *lse,
+                            const void *dout, void *dq, void *dk, void *dv, void *workspace, size_t workspace_bytes,
+                            void *hip_stream)
+{
+    if (!g) return s2_fail(S2_ERR_INVALID_ARG, "grid is NULL");
+    if (!workspace || workspace_bytes < s2_nattn_bwd_workspace_bytes(g, batch, heads, d_qk, d_v, dtype))
+        return s2_fail(S2_ERR_WORKSPACE, "workspace missing or smaller than s2_nattn_bwd_workspace_bytes()");
+    if (misaligned(workspace)) return s2_fail(S2_ERR_WORKSPACE, "workspace must be 16-byte aligned");
+    return s2_nattn_bwd_run(g, batch, heads, d_qk, d_v, dtype, scale, q, k, v, out, lse, dout, dq, dk, dv,
+                            static_cast<float *>(workspace), static_cast<hipStream_t>(hip_stream));
 }

@@ -53,3 +53,11 @@ int s2_nattn_bwd_dq_stream(const S2DeviceTables &t, int nbh, float scale, const 
 int s2_nattn_bwd_dkdv_stream(const S2DeviceTables &t, int nbh, float scale, const float *q, const float *k,
                              const float *v, const float *lse, const float *go, const float *Dws, float *dk, float *dv,
                              hipStream_t st);
+
+// Backward with the scratch for D_i given as a device pointer (checks and dispatch behind both C entry points).
+int s2_nattn_bwd_run(const s2_grid_t *g, int batch, int heads, int d_qk, int d_v, int dtype, float scale,
+                     const void *q, const void *k, const void *v, const void *out, const float *lse, const void *dout,
+                     void *dq, void *dk, void *dv, float *Dws, hipStream_t st);
+
+// Per-device set-up of the static scratch array behind s2_nattn_bwd_static (the device must be current).
+int s2_static_scratch_setup(int device);
