@@ -17,7 +17,8 @@ EQUIANGULAR_TRAPEZOID = 2   # the grid exactly as App. A.1 prints it (no south p
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "s2_oracle.c")
-_LIB = os.path.join(_HERE, "liboracle.so")
+# S2_ORACLE_LIB: load another build of the same source instead (the sanitizer test points it at an ASan/UBSan build)
+_LIB = os.environ.get("S2_ORACLE_LIB") or os.path.join(_HERE, "liboracle.so")
 _lib = None
 
 _dp = ctypes.POINTER(ctypes.c_double)
@@ -26,6 +27,8 @@ _bp = ctypes.POINTER(ctypes.c_uint8)
 
 def build(force=False):
     """Compile s2_oracle.c into liboracle.so next to it (gcc, OpenMP)."""
+    if os.environ.get("S2_ORACLE_LIB"):
+        return _LIB
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         subprocess.check_call(
             ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
