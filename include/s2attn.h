@@ -117,7 +117,10 @@ size_t s2_nattn_bwd_workspace_bytes(const s2_grid_t *g, int batch, int heads, in
  * Layouts (contiguous): q, out [batch][heads][d][nlat_out][nlon_out] (out has
  * d_v channels); k [batch][heads][d_qk][nlat_in][nlon_in]; v likewise with d_v;
  * lse float32 [batch][heads][nlat_out][nlon_out].
- * dtype: S2_F32 (float32 arithmetic throughout).  d_qk, d_v in [1, 128].
+ * dtype: S2_F32 (float32 tensors, float32 arithmetic throughout) or S2_BF16 (q, k, v, out bf16; products on the
+ * bf16 matrix cores where the shape allows - equal grids, d_qk = d_v = 32, longitude count a multiple of 64 - with
+ * float32 accumulation and softmax, otherwise float32 arithmetic on bf16 loads; lse float32 either way).
+ * d_qk, d_v in [1, 128].
  * Errors: S2_ERR_INVALID_ARG (NULL or not 16-byte aligned pointers, sizes < 1),
  * S2_ERR_UNSUPPORTED (dtype, head dims), S2_ERR_DEVICE (host-only handle or
  * launch failure).
@@ -135,7 +138,7 @@ int s2_nattn_fwd(const s2_grid_t *g, int batch, int heads, int d_qk, int d_v, in
  *   dk_j = scale * sum_{i: j in N(i)} dS_ij q_i,   dv_j = sum_{i: j in N(i)} p_ij dout_i.
  * dk and dv are gathered through the transposed neighborhood (input point ->
  * output points): no atomics, bit-reproducible.  omega carries no gradient.
- * dq like q, dk like k, dv like v.  workspace: device scratch of at least
+ * dq like q, dk like k, dv like v (bf16 for S2_BF16; D_i and lse stay float32).  workspace: device scratch of at least
  * s2_nattn_bwd_workspace_bytes(...) bytes (S2_ERR_WORKSPACE if smaller).
  */
 int s2_nattn_bwd(const s2_grid_t *g, int batch, int heads, int d_qk, int d_v, int dtype, float scale,

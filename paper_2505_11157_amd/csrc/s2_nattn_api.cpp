@@ -7,7 +7,7 @@ int check_common(const s2_grid_t *g, int batch, int heads, int d_qk, int d_v, in
 {
     if (!g) return s2_fail(S2_ERR_INVALID_ARG, "grid is NULL");
     if (batch < 1 || heads < 1 || d_qk < 1 || d_v < 1) return s2_fail(S2_ERR_INVALID_ARG, "batch, heads, d must be >= 1");
-    if (dtype != S2_F32) return s2_fail(S2_ERR_UNSUPPORTED, "neighborhood attention supports S2_F32 only");
+    if (dtype != S2_F32 && dtype != S2_BF16) return s2_fail(S2_ERR_UNSUPPORTED, "unknown dtype");
     if (d_qk > 128 || d_v > 128) return s2_fail(S2_ERR_UNSUPPORTED, "head dimensions above 128 are not supported");
     if (long(batch) * heads > (1l << 20)) return s2_fail(S2_ERR_INVALID_ARG, "batch*heads too large");
     if (!g->on_device) return s2_fail(S2_ERR_DEVICE, "grid handle has no device tables (no HIP device at init)");
@@ -36,6 +36,13 @@ extern "C" int s2_nattn_fwd(const s2_grid_t *g, int batch, int heads, int d_qk, 
     if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out) || misaligned(lse))
         return s2_fail(S2_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (dtype == S2_BF16) {
+        auto *fwd16 = s2_nattn_bf16_supported(g->dt, d_qk, d_v) ? s2_nattn_fwd_bf16 : s2_nattn_fwd_generic_bf16;
+        if (fwd16(g->dt, batch * heads, d_qk, d_v, scale, q, k, v, out, lse, st))
+            return s2_fail(S2_ERR_DEVICE, "forward launch configuration failed");
+        S2_HIP_CHECK(hipGetLastError());
+        return S2_OK;
+    }
     auto *fwd = s2_nattn_fwd_tiled_supported(g->dt, d_qk, d_v) ? s2_nattn_fwd_tiled : s2_nattn_fwd_generic;
     if (fwd(g->dt, batch * heads, d_qk, d_v, scale, static_cast<const float *>(q), static_cast<const float *>(k),
             static_cast<const float *>(v), static_cast<float *>(out), lse, st))
@@ -56,15 +63,24 @@ int s2_nattn_bwd_run(const s2_grid_t *g, int batch, int heads, int d_qk, int d_v
     if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out) || misaligned(lse) || misaligned(dout) ||
         misaligned(dq) || misaligned(dk) || misaligned(dv))
         return s2_fail(S2_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
-    auto *bwd = s2_nattn_bwd_tiled_supported(g->dt, d_qk, d_v) ? s2_nattn_bwd_tiled : s2_nattn_bwd_generic;
-    if (bwd(g->dt, batch * heads, d_qk, d_v, scale, static_cast<const float *>(q), static_cast<const float *>(k),
-            static_cast<const float *>(v), static_cast<const float *>(out), lse, static_cast<const float *>(dout),
-            static_cast<float *>(dq), static_cast<float *>(dk), static_cast<float *>(dv), Dws, st))
-        return s2_fail(S2_ERR_DEVICE, "backward launch configuration failed");
+    if (dtype == S2_BF16) {
+        const bool fast = s2_nattn_bf16_supported(g->dt, d_qk, d_v);
+        auto *dq16 = fast ? s2_nattn_bwd_dq_bf16 : s2_nattn_bwd_dq_generic_bf16;
+        auto *kv16 = fast ? s2_nattn_bwd_dkdv_bf16 : s2_nattn_bwd_dkdv_generic_bf16;
+        if (dq16(g->dt, batch * heads, d_qk, d_v, scale, q, k, v, out, lse, dout, dq, Dws, st) ||
+            kv16(g->dt, batch * heads, d_qk, d_v, scale, q, k, v, lse, dout, Dws, dk, dv, st))
+            return s2_fail(S2_ERR_DEVICE, "backward launch configuration failed");
+    } else {
+        auto *bwd = s2_nattn_bwd_tiled_supported(g->dt, d_qk, d_v) ? s2_nattn_bwd_tiled : s2_nattn_bwd_generic;
+        if (bwd(g->dt, batch * heads, d_qk, d_v, scale, static_cast<const float *>(q), static_cast<const float *>(k),
+                static_cast<const float *>(v), static_cast<const float *>(out), lse, static_cast<const float *>(dout),
+                static_cast<float *>(dq), static_cast<float *>(dk), static_cast<float *>(dv), Dws, st))
+            return s2_fail(S2_ERR_DEVICE, "backward launch configuration failed");
+    }
     // input latitudes of weight zero (the pole row of the grid of App. A.1): dk = dv = 0 exactly
     for (int lat : g->zero_lat) {
-        s2_nattn_zero_latitude(g->dt, lat, batch * heads * d_qk, static_cast<float *>(dk), st);
-        s2_nattn_zero_latitude(g->dt, lat, batch * heads * d_v, static_cast<float *>(dv), st);
+        s2_nattn_zero_latitude(g->dt, lat, batch * heads * d_qk, dk, dtype == S2_BF16, st);
+        s2_nattn_zero_latitude(g->dt, lat, batch * heads * d_v, dv, dtype == S2_BF16, st);
     }
     S2_HIP_CHECK(hipGetLastError());
     return S2_OK;

@@ -6,11 +6,25 @@
 //
 // These are the shape-agnostic path.  The tuned kernels in s2_nattn_tiled.hip
 // take over for the head dimensions and grids they are specialised for.
+#include <type_traits>
+
 #include "s2_nattn_kernels.h"
 
 namespace {
 
 constexpr int kChunk = 8;   // logits evaluated together before one softmax rescale
+
+// Storage type of the tensors: float, or bf16 (raw 16-bit words; arithmetic is float32 either way, results are
+// rounded to nearest even on the store).
+typedef unsigned short bf16raw;
+__device__ __forceinline__ float ldf(const float *p) { return *p; }
+__device__ __forceinline__ float ldf(const bf16raw *p) { return __builtin_bit_cast(float, unsigned(*p) << 16); }
+__device__ __forceinline__ void stf(float *p, float x) { *p = x; }
+__device__ __forceinline__ void stf(bf16raw *p, float x)
+{
+    const __bf16 b = (__bf16)x;
+    *p = __builtin_bit_cast(bf16raw, b);
+}
 
 __device__ __forceinline__ int wrap(int x, int n)
 {
@@ -40,11 +54,11 @@ __device__ __forceinline__ void arc_of(const S2DeviceTables &t, int h, int w, in
 // rather than as an additive log term: the running maximum is taken over the
 // bare logits, whose magnitude is a few units, so float32 rounding of the
 // logit stays near 1e-7 instead of growing with |log2 omega| ~ 10..20.
-template <int DMAX>
+template <int DMAX, typename T>
 __global__ void __launch_bounds__(64)
 nattn_fwd_generic(S2DeviceTables t, int nbh, int first_row, int d, int e, float qscale,
-                  const float *__restrict__ q, const float *__restrict__ k, const float *__restrict__ v,
-                  float *__restrict__ out, float *__restrict__ lse)
+                  const T *__restrict__ q, const T *__restrict__ k, const T *__restrict__ v,
+                  T *__restrict__ out, float *__restrict__ lse)
 {
     const int ntile = (t.nlon_out + 63) / 64;
     int id = blockIdx.x;
@@ -56,11 +70,11 @@ nattn_fwd_generic(S2DeviceTables t, int nbh, int first_row, int d, int e, float 
 
     const size_t so = size_t(t.nlat_out) * t.nlon_out, si = size_t(t.nlat_in) * t.nlon_in;
     const size_t io = size_t(h) * t.nlon_out + w;
-    const float *qb = q + size_t(bh) * d * so + io;
+    const T *qb = q + size_t(bh) * d * so + io;
     float qr[DMAX], acc[DMAX];
 #pragma unroll
     for (int l = 0; l < DMAX; ++l) {
-        qr[l] = l < d ? qb[l * so] * qscale : 0.f;
+        qr[l] = l < d ? ldf(qb + l * so) * qscale : 0.f;
         acc[l] = 0.f;
     }
     float m = -INFINITY, lsum = 0.f;
@@ -70,8 +84,8 @@ nattn_fwd_generic(S2DeviceTables t, int nbh, int first_row, int d, int e, float 
         int first, c;
         arc_of(t, h, w, b, first, c);
         const float wq = t.omega_rel[hp];
-        const float *kb = k + size_t(bh) * d * si + size_t(hp) * t.nlon_in;
-        const float *vb = v + size_t(bh) * e * si + size_t(hp) * t.nlon_in;
+        const T *kb = k + size_t(bh) * d * si + size_t(hp) * t.nlon_in;
+        const T *vb = v + size_t(bh) * e * si + size_t(hp) * t.nlon_in;
         for (int t0 = 0; t0 < c; t0 += kChunk) {
             float s[kChunk];
             int col[kChunk];
@@ -86,9 +100,9 @@ nattn_fwd_generic(S2DeviceTables t, int nbh, int first_row, int d, int e, float 
 #pragma unroll
             for (int l = 0; l < DMAX; ++l)
                 if (l < d) {
-                    const float *kr = kb + l * si;
+                    const T *kr = kb + l * si;
 #pragma unroll
-                    for (int j = 0; j < kChunk; ++j) s[j] = fmaf(qr[l], kr[col[j]], s[j]);
+                    for (int j = 0; j < kChunk; ++j) s[j] = fmaf(qr[l], ldf(kr + col[j]), s[j]);
                 }
 #pragma unroll
             for (int j = 0; j < kChunk; ++j) {
@@ -108,10 +122,10 @@ nattn_fwd_generic(S2DeviceTables t, int nbh, int first_row, int d, int e, float 
 #pragma unroll
             for (int l = 0; l < DMAX; ++l)
                 if (l < e) {
-                    const float *vr = vb + l * si;
+                    const T *vr = vb + l * si;
                     float a = acc[l] * corr;
 #pragma unroll
-                    for (int j = 0; j < kChunk; ++j) a = fmaf(p[j], vr[col[j]], a);
+                    for (int j = 0; j < kChunk; ++j) a = fmaf(p[j], ldf(vr + col[j]), a);
                     acc[l] = a;
                 } else {
                     acc[l] = 0.f;
@@ -119,22 +133,22 @@ nattn_fwd_generic(S2DeviceTables t, int nbh, int first_row, int d, int e, float 
         }
     }
     const float inv = 1.f / lsum;
-    float *ob = out + size_t(bh) * e * so + io;
+    T *ob = out + size_t(bh) * e * so + io;
 #pragma unroll
     for (int l = 0; l < DMAX; ++l)
-        if (l < e) ob[l * so] = acc[l] * inv;
+        if (l < e) stf(ob + l * so, acc[l] * inv);
     lse[size_t(bh) * so + io] = (m + log2f(lsum * t.omega_ref)) * 0.6931471805599453f;
 }
 
 // Backward, query side (App. B.4): D_i = dout_i.out_i, then
 // dq_i = scale * sum_j p_ij (dout_i.v_j - D_i) k_j over the same lists as the
 // forward pass, p_ij recomputed from the saved logsumexp.  Also stores D_i.
-template <int DMAX>
+template <int DMAX, typename T>
 __global__ void __launch_bounds__(64)
 nattn_bwd_dq_generic(S2DeviceTables t, int nbh, int d, int e, float scale,
-                     const float *__restrict__ q, const float *__restrict__ k, const float *__restrict__ v,
-                     const float *__restrict__ o, const float *__restrict__ lse, const float *__restrict__ go,
-                     float *__restrict__ dq, float *__restrict__ Dws)
+                     const T *__restrict__ q, const T *__restrict__ k, const T *__restrict__ v,
+                     const T *__restrict__ o, const float *__restrict__ lse, const T *__restrict__ go,
+                     T *__restrict__ dq, float *__restrict__ Dws)
 {
     const int ntile = (t.nlon_out + 63) / 64;
     int id = blockIdx.x;
@@ -151,9 +165,9 @@ nattn_bwd_dq_generic(S2DeviceTables t, int nbh, int d, int e, float scale,
     float Di = 0.f;
 #pragma unroll
     for (int l = 0; l < DMAX; ++l) {
-        qr[l] = l < d ? q[(size_t(bh) * d + l) * so + io] * qscale : 0.f;
-        gr[l] = l < e ? go[(size_t(bh) * e + l) * so + io] : 0.f;
-        if (l < e) Di = fmaf(gr[l], o[(size_t(bh) * e + l) * so + io], Di);
+        qr[l] = l < d ? ldf(q + (size_t(bh) * d + l) * so + io) * qscale : 0.f;
+        gr[l] = l < e ? ldf(go + (size_t(bh) * e + l) * so + io) : 0.f;
+        if (l < e) Di = fmaf(gr[l], ldf(o + (size_t(bh) * e + l) * so + io), Di);
         dqr[l] = 0.f;
     }
     Dws[size_t(bh) * so + io] = Di;
@@ -165,8 +179,8 @@ nattn_bwd_dq_generic(S2DeviceTables t, int nbh, int d, int e, float scale,
         int first, c;
         arc_of(t, h, w, b, first, c);
         const float wq = t.omega_rel[hp];
-        const float *kb = k + size_t(bh) * d * si + size_t(hp) * t.nlon_in;
-        const float *vb = v + size_t(bh) * e * si + size_t(hp) * t.nlon_in;
+        const T *kb = k + size_t(bh) * d * si + size_t(hp) * t.nlon_in;
+        const T *vb = v + size_t(bh) * e * si + size_t(hp) * t.nlon_in;
         for (int t0 = 0; t0 < c; t0 += kChunk) {
             // channel by channel over a chunk of eight columns (see the forward); K rows are read twice, the
             // second time from the cache
@@ -181,16 +195,16 @@ nattn_bwd_dq_generic(S2DeviceTables t, int nbh, int d, int e, float scale,
 #pragma unroll
             for (int l = 0; l < DMAX; ++l)
                 if (l < d) {
-                    const float *kr = kb + l * si;
+                    const T *kr = kb + l * si;
 #pragma unroll
-                    for (int j = 0; j < kChunk; ++j) dot[j] = fmaf(qr[l], kr[col[j]], dot[j]);
+                    for (int j = 0; j < kChunk; ++j) dot[j] = fmaf(qr[l], ldf(kr + col[j]), dot[j]);
                 }
 #pragma unroll
             for (int l = 0; l < DMAX; ++l)
                 if (l < e) {
-                    const float *vr = vb + l * si;
+                    const T *vr = vb + l * si;
 #pragma unroll
-                    for (int j = 0; j < kChunk; ++j) gv[j] = fmaf(gr[l], vr[col[j]], gv[j]);
+                    for (int j = 0; j < kChunk; ++j) gv[j] = fmaf(gr[l], ldf(vr + col[j]), gv[j]);
                 }
 #pragma unroll
             for (int j = 0; j < kChunk; ++j)
@@ -198,17 +212,17 @@ nattn_bwd_dq_generic(S2DeviceTables t, int nbh, int d, int e, float scale,
 #pragma unroll
             for (int l = 0; l < DMAX; ++l)
                 if (l < d) {
-                    const float *kr = kb + l * si;
+                    const T *kr = kb + l * si;
                     float a = dqr[l];
 #pragma unroll
-                    for (int j = 0; j < kChunk; ++j) a = fmaf(dot[j], kr[col[j]], a);
+                    for (int j = 0; j < kChunk; ++j) a = fmaf(dot[j], ldf(kr + col[j]), a);
                     dqr[l] = a;
                 }
         }
     }
 #pragma unroll
     for (int l = 0; l < DMAX; ++l)
-        if (l < d) dq[(size_t(bh) * d + l) * so + io] = dqr[l] * scale;
+        if (l < d) stf(dq + (size_t(bh) * d + l) * so + io, dqr[l] * scale);
 }
 
 // Backward, key/value side (App. B.4): one lane per INPUT point j gathers
@@ -216,12 +230,12 @@ nattn_bwd_dq_generic(S2DeviceTables t, int nbh, int d, int e, float scale,
 // over the output points whose disk contains j.  By the symmetry of the
 // distance these are, on output latitude h, the longitudes w with
 // |w*pscale - w_in| <= half-width(h, h') on the circle.
-template <int DMAX>
+template <int DMAX, typename T>
 __global__ void __launch_bounds__(64)
 nattn_bwd_dkdv_generic(S2DeviceTables t, int nbh, int d, int e, float scale,
-                       const float *__restrict__ q, const float *__restrict__ k, const float *__restrict__ v,
-                       const float *__restrict__ lse, const float *__restrict__ go, const float *__restrict__ Dws,
-                       float *__restrict__ dk, float *__restrict__ dv)
+                       const T *__restrict__ q, const T *__restrict__ k, const T *__restrict__ v,
+                       const float *__restrict__ lse, const T *__restrict__ go, const float *__restrict__ Dws,
+                       T *__restrict__ dk, T *__restrict__ dv)
 {
     const int ntile = (t.nlon_in + 63) / 64;
     int id = blockIdx.x;
@@ -238,8 +252,8 @@ nattn_bwd_dkdv_generic(S2DeviceTables t, int nbh, int d, int e, float scale,
     float kr[DMAX], vr[DMAX], dkr[DMAX], dvr[DMAX];
 #pragma unroll
     for (int l = 0; l < DMAX; ++l) {
-        kr[l] = l < d ? k[(size_t(bh) * d + l) * si + ii] * qscale : 0.f;
-        vr[l] = l < e ? v[(size_t(bh) * e + l) * si + ii] : 0.f;
+        kr[l] = l < d ? ldf(k + (size_t(bh) * d + l) * si + ii) * qscale : 0.f;
+        vr[l] = l < e ? ldf(v + (size_t(bh) * e + l) * si + ii) : 0.f;
         dkr[l] = 0.f;
         dvr[l] = 0.f;
     }
@@ -257,8 +271,8 @@ nattn_bwd_dkdv_generic(S2DeviceTables t, int nbh, int d, int e, float scale,
         const int r = x % ps;
         if (r) x += ps - r;
         const int x_end = (c == t.nlon_in) ? x + t.nlon_in - ps : win + hw + t.nlon_in;
-        const float *qb = q + size_t(bh) * d * so + size_t(h) * t.nlon_out;
-        const float *gb = go + size_t(bh) * e * so + size_t(h) * t.nlon_out;
+        const T *qb = q + size_t(bh) * d * so + size_t(h) * t.nlon_out;
+        const T *gb = go + size_t(bh) * e * so + size_t(h) * t.nlon_out;
         const float *lb = lse + size_t(bh) * so + size_t(h) * t.nlon_out;
         const float *Db = Dws + size_t(bh) * so + size_t(h) * t.nlon_out;
         auto visit = [&](int w) {
@@ -267,8 +281,8 @@ nattn_bwd_dkdv_generic(S2DeviceTables t, int nbh, int d, int e, float scale,
             float dot = 0.f, gv = -Db[w];
 #pragma unroll
             for (int l = 0; l < DMAX; ++l) {
-                qr[l] = l < d ? qb[l * so + w] : 0.f;
-                gr[l] = l < e ? gb[l * so + w] : 0.f;
+                qr[l] = l < d ? ldf(qb + l * so + w) : 0.f;
+                gr[l] = l < e ? ldf(gb + l * so + w) : 0.f;
                 dot = fmaf(qr[l], kr[l], dot);
                 gv = fmaf(gr[l], vr[l], gv);
             }
@@ -304,102 +318,138 @@ nattn_bwd_dkdv_generic(S2DeviceTables t, int nbh, int d, int e, float scale,
     }
 #pragma unroll
     for (int l = 0; l < DMAX; ++l) {
-        if (l < d) dk[(size_t(bh) * d + l) * si + ii] = dkr[l] * scale;
-        if (l < e) dv[(size_t(bh) * e + l) * si + ii] = dvr[l];
+        if (l < d) stf(dk + (size_t(bh) * d + l) * si + ii, dkr[l] * scale);
+        if (l < e) stf(dv + (size_t(bh) * e + l) * si + ii, dvr[l]);
     }
 }
 
 // Input latitudes of weight zero: every p_ij of theirs is zero, so dk = dv = 0 there.  The dk/dv kernels above and
 // in the tuned files form 0 * exp2(.) for them, which is not a number once the exponential overflows; this fill,
 // enqueued after them, writes the exact result.  x: [rows][nlat_in][nlon_in], one block per (row, 256 columns).
+template <typename T>
 __global__ void __launch_bounds__(256)
-zero_latitude(float *__restrict__ x, int lat, int rows, int nlon_in, size_t si)
+zero_latitude(T *__restrict__ x, int lat, int rows, int nlon_in, size_t si)
 {
     const int w = blockIdx.x * 256 + threadIdx.x;
     if (w >= nlon_in) return;
-    for (int r = blockIdx.y; r < rows; r += gridDim.y) x[size_t(r) * si + size_t(lat) * nlon_in + w] = 0.f;
+    for (int r = blockIdx.y; r < rows; r += gridDim.y) x[size_t(r) * si + size_t(lat) * nlon_in + w] = T(0);
 }
 
-template <int DMAX>
-int launch_fwd(const S2DeviceTables &t, int nbh, int d, int e, float scale, const float *q, const float *k,
-               const float *v, float *out, float *lse, hipStream_t st)
+template <int DMAX, typename T>
+int launch_fwd(const S2DeviceTables &t, int nbh, int d, int e, float scale, const T *q, const T *k, const T *v, T *out,
+               float *lse, hipStream_t st)
 {
     const int ntile = (t.nlon_out + 63) / 64;
     const long nblk = long(ntile) * nbh * t.nlat_out;
     S2TraceScope tr("nattn_fwd_generic", nbh * (t.fwd_pairs[0] + t.fwd_pairs[1] + t.fwd_pairs[2] + t.fwd_pairs[3]), st);
-    hipLaunchKernelGGL(nattn_fwd_generic<DMAX>, dim3((unsigned)nblk), dim3(64), 0, st, t, nbh, 0, d, e,
+    hipLaunchKernelGGL((nattn_fwd_generic<DMAX, T>), dim3((unsigned)nblk), dim3(64), 0, st, t, nbh, 0, d, e,
                        scale * 1.4426950408889634f, q, k, v, out, lse);
     return 0;
 }
 
-template <int DMAX>
-int launch_bwd(const S2DeviceTables &t, int nbh, int d, int e, float scale, const float *q, const float *k,
-               const float *v, const float *o, const float *lse, const float *go, float *dq, float *dk, float *dv,
-               float *Dws, hipStream_t st)
+template <int DMAX, typename T>
+int launch_dq(const S2DeviceTables &t, int nbh, int d, int e, float scale, const T *q, const T *k, const T *v,
+              const T *o, const float *lse, const T *go, T *dq, float *Dws, hipStream_t st)
 {
-    const int nto = (t.nlon_out + 63) / 64, nti = (t.nlon_in + 63) / 64;
-    {
+    const int nto = (t.nlon_out + 63) / 64;
     S2TraceScope tr("nattn_bwd_dq_generic", nbh * (t.fwd_pairs[0] + t.fwd_pairs[1] + t.fwd_pairs[2] + t.fwd_pairs[3]), st);
-    hipLaunchKernelGGL(nattn_bwd_dq_generic<DMAX>, dim3((unsigned)(long(nto) * nbh * t.nlat_out)), dim3(64), 0, st,
+    hipLaunchKernelGGL((nattn_bwd_dq_generic<DMAX, T>), dim3((unsigned)(long(nto) * nbh * t.nlat_out)), dim3(64), 0, st,
                        t, nbh, d, e, scale, q, k, v, o, lse, go, dq, Dws);
-    }
+    return 0;
+}
+
+template <int DMAX, typename T>
+int launch_dkdv(const S2DeviceTables &t, int nbh, int d, int e, float scale, const T *q, const T *k, const T *v,
+                const float *lse, const T *go, const float *Dws, T *dk, T *dv, hipStream_t st)
+{
+    const int nti = (t.nlon_in + 63) / 64;
     S2TraceScope tr("nattn_bwd_dkdv_generic", nbh * (t.fwd_pairs[0] + t.fwd_pairs[1] + t.fwd_pairs[2] + t.fwd_pairs[3]), st);
-    hipLaunchKernelGGL(nattn_bwd_dkdv_generic<DMAX>, dim3((unsigned)(long(nti) * nbh * t.nlat_in)), dim3(64), 0, st,
+    hipLaunchKernelGGL((nattn_bwd_dkdv_generic<DMAX, T>), dim3((unsigned)(long(nti) * nbh * t.nlat_in)), dim3(64), 0, st,
                        t, nbh, d, e, scale, q, k, v, lse, go, Dws, dk, dv);
     return 0;
 }
 
-template <int DMAX>
-int launch_dkdv(const S2DeviceTables &t, int nbh, int d, int e, float scale, const float *q, const float *k,
-                const float *v, const float *lse, const float *go, const float *Dws, float *dk, float *dv,
-                hipStream_t st)
+// the kernels are instantiated for channel counts up to 8, 16, 32, 64, 128
+template <typename F>
+int by_width(int d, int e, F f)
 {
-    const int nti = (t.nlon_in + 63) / 64;
-    S2TraceScope tr("nattn_bwd_dkdv_generic", nbh * (t.fwd_pairs[0] + t.fwd_pairs[1] + t.fwd_pairs[2] + t.fwd_pairs[3]), st);
-    hipLaunchKernelGGL(nattn_bwd_dkdv_generic<DMAX>, dim3((unsigned)(long(nti) * nbh * t.nlat_in)), dim3(64), 0, st,
-                       t, nbh, d, e, scale, q, k, v, lse, go, Dws, dk, dv);
-    return 0;
+    const int dm = d > e ? d : e;
+    if (dm <= 8) return f(std::integral_constant<int, 8>());
+    if (dm <= 16) return f(std::integral_constant<int, 16>());
+    if (dm <= 32) return f(std::integral_constant<int, 32>());
+    if (dm <= 64) return f(std::integral_constant<int, 64>());
+    return f(std::integral_constant<int, 128>());
 }
 
 }  // namespace
 
-void s2_nattn_zero_latitude(const S2DeviceTables &t, int lat, int rows, float *x, hipStream_t st)
+void s2_nattn_zero_latitude(const S2DeviceTables &t, int lat, int rows, void *x, bool bf16, hipStream_t st)
 {
-    hipLaunchKernelGGL(zero_latitude, dim3((t.nlon_in + 255) / 256, rows < 65535 ? rows : 65535), dim3(256), 0, st, x,
-                       lat, rows, t.nlon_in, size_t(t.nlat_in) * t.nlon_in);
+    const dim3 grid((t.nlon_in + 255) / 256, rows < 65535 ? rows : 65535);
+    const size_t si = size_t(t.nlat_in) * t.nlon_in;
+    if (bf16)
+        hipLaunchKernelGGL(zero_latitude<bf16raw>, grid, dim3(256), 0, st, static_cast<bf16raw *>(x), lat, rows, t.nlon_in, si);
+    else
+        hipLaunchKernelGGL(zero_latitude<float>, grid, dim3(256), 0, st, static_cast<float *>(x), lat, rows, t.nlon_in, si);
 }
 
 int s2_nattn_fwd_generic(const S2DeviceTables &t, int nbh, int d, int e, float scale, const float *q,
                          const float *k, const float *v, float *out, float *lse, hipStream_t st)
 {
-    const int dm = d > e ? d : e;
-    if (dm <= 8) return launch_fwd<8>(t, nbh, d, e, scale, q, k, v, out, lse, st);
-    if (dm <= 16) return launch_fwd<16>(t, nbh, d, e, scale, q, k, v, out, lse, st);
-    if (dm <= 32) return launch_fwd<32>(t, nbh, d, e, scale, q, k, v, out, lse, st);
-    if (dm <= 64) return launch_fwd<64>(t, nbh, d, e, scale, q, k, v, out, lse, st);
-    return launch_fwd<128>(t, nbh, d, e, scale, q, k, v, out, lse, st);
+    return by_width(d, e, [&](auto W) { return launch_fwd<decltype(W)::value, float>(t, nbh, d, e, scale, q, k, v, out, lse, st); });
 }
 
 int s2_nattn_bwd_dkdv_generic(const S2DeviceTables &t, int nbh, int d, int e, float scale, const float *q,
                               const float *k, const float *v, const float *lse, const float *go, const float *Dws,
                               float *dk, float *dv, hipStream_t st)
 {
-    const int dm = d > e ? d : e;
-    if (dm <= 8) return launch_dkdv<8>(t, nbh, d, e, scale, q, k, v, lse, go, Dws, dk, dv, st);
-    if (dm <= 16) return launch_dkdv<16>(t, nbh, d, e, scale, q, k, v, lse, go, Dws, dk, dv, st);
-    if (dm <= 32) return launch_dkdv<32>(t, nbh, d, e, scale, q, k, v, lse, go, Dws, dk, dv, st);
-    if (dm <= 64) return launch_dkdv<64>(t, nbh, d, e, scale, q, k, v, lse, go, Dws, dk, dv, st);
-    return launch_dkdv<128>(t, nbh, d, e, scale, q, k, v, lse, go, Dws, dk, dv, st);
+    return by_width(d, e, [&](auto W) {
+        return launch_dkdv<decltype(W)::value, float>(t, nbh, d, e, scale, q, k, v, lse, go, Dws, dk, dv, st);
+    });
 }
 
 int s2_nattn_bwd_generic(const S2DeviceTables &t, int nbh, int d, int e, float scale, const float *q,
                          const float *k, const float *v, const float *o, const float *lse, const float *go,
                          float *dq, float *dk, float *dv, float *Dws, hipStream_t st)
 {
-    const int dm = d > e ? d : e;
-    if (dm <= 8) return launch_bwd<8>(t, nbh, d, e, scale, q, k, v, o, lse, go, dq, dk, dv, Dws, st);
-    if (dm <= 16) return launch_bwd<16>(t, nbh, d, e, scale, q, k, v, o, lse, go, dq, dk, dv, Dws, st);
-    if (dm <= 32) return launch_bwd<32>(t, nbh, d, e, scale, q, k, v, o, lse, go, dq, dk, dv, Dws, st);
-    if (dm <= 64) return launch_bwd<64>(t, nbh, d, e, scale, q, k, v, o, lse, go, dq, dk, dv, Dws, st);
-    return launch_bwd<128>(t, nbh, d, e, scale, q, k, v, o, lse, go, dq, dk, dv, Dws, st);
+    return by_width(d, e, [&](auto W) {
+        constexpr int DM = decltype(W)::value;
+        launch_dq<DM, float>(t, nbh, d, e, scale, q, k, v, o, lse, go, dq, Dws, st);
+        return launch_dkdv<DM, float>(t, nbh, d, e, scale, q, k, v, lse, go, Dws, dk, dv, st);
+    });
+}
+
+// bf16 tensors (raw 16-bit words), float32 arithmetic, float32 lse and D
+int s2_nattn_fwd_generic_bf16(const S2DeviceTables &t, int nbh, int d, int e, float scale, const void *q, const void *k,
+                              const void *v, void *out, float *lse, hipStream_t st)
+{
+    return by_width(d, e, [&](auto W) {
+        return launch_fwd<decltype(W)::value, bf16raw>(t, nbh, d, e, scale, static_cast<const bf16raw *>(q),
+                                                       static_cast<const bf16raw *>(k), static_cast<const bf16raw *>(v),
+                                                       static_cast<bf16raw *>(out), lse, st);
+    });
+}
+
+int s2_nattn_bwd_dq_generic_bf16(const S2DeviceTables &t, int nbh, int d, int e, float scale, const void *q,
+                                 const void *k, const void *v, const void *o, const float *lse, const void *go, void *dq,
+                                 float *Dws, hipStream_t st)
+{
+    return by_width(d, e, [&](auto W) {
+        return launch_dq<decltype(W)::value, bf16raw>(
+            t, nbh, d, e, scale, static_cast<const bf16raw *>(q), static_cast<const bf16raw *>(k),
+            static_cast<const bf16raw *>(v), static_cast<const bf16raw *>(o), lse, static_cast<const bf16raw *>(go),
+            static_cast<bf16raw *>(dq), Dws, st);
+    });
+}
+
+int s2_nattn_bwd_dkdv_generic_bf16(const S2DeviceTables &t, int nbh, int d, int e, float scale, const void *q,
+                                   const void *k, const void *v, const float *lse, const void *go, const float *Dws,
+                                   void *dk, void *dv, hipStream_t st)
+{
+    return by_width(d, e, [&](auto W) {
+        return launch_dkdv<decltype(W)::value, bf16raw>(
+            t, nbh, d, e, scale, static_cast<const bf16raw *>(q), static_cast<const bf16raw *>(k),
+            static_cast<const bf16raw *>(v), lse, static_cast<const bf16raw *>(go), Dws, static_cast<bf16raw *>(dk),
+            static_cast<bf16raw *>(dv), st);
+    });
 }

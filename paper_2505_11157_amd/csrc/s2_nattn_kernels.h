@@ -9,8 +9,19 @@ int s2_nattn_bwd_generic(const S2DeviceTables &t, int nbh, int d, int e, float s
                          const float *k, const float *v, const float *o, const float *lse, const float *go,
                          float *dq, float *dk, float *dv, float *Dws, hipStream_t st);
 
-// dk, dv of an input latitude of weight zero are zero: x is [rows][nlat_in][nlon_in], rows = slices * channels.
-void s2_nattn_zero_latitude(const S2DeviceTables &t, int lat, int rows, float *x, hipStream_t st);
+// dk, dv of an input latitude of weight zero are zero: x is [rows][nlat_in][nlon_in], rows = slices * channels,
+// float32 or bf16 elements.
+void s2_nattn_zero_latitude(const S2DeviceTables &t, int lat, int rows, void *x, bool bf16, hipStream_t st);
+
+// Shape-agnostic path on bf16 tensors (float32 arithmetic, float32 lse and D).
+int s2_nattn_fwd_generic_bf16(const S2DeviceTables &t, int nbh, int d, int e, float scale, const void *q, const void *k,
+                              const void *v, void *out, float *lse, hipStream_t st);
+int s2_nattn_bwd_dq_generic_bf16(const S2DeviceTables &t, int nbh, int d, int e, float scale, const void *q,
+                                 const void *k, const void *v, const void *o, const float *lse, const void *go, void *dq,
+                                 float *Dws, hipStream_t st);
+int s2_nattn_bwd_dkdv_generic_bf16(const S2DeviceTables &t, int nbh, int d, int e, float scale, const void *q,
+                                   const void *k, const void *v, const float *lse, const void *go, const float *Dws,
+                                   void *dk, void *dv, hipStream_t st);
 
 // Tuned float32 forward for d = e = 32, nlon_in / nlon_out in {1, 2}, longitudes a multiple of 4.
 bool s2_nattn_fwd_tiled_supported(const S2DeviceTables &t, int d, int e);
@@ -53,6 +64,18 @@ int s2_nattn_bwd_dq_stream(const S2DeviceTables &t, int nbh, float scale, const 
 int s2_nattn_bwd_dkdv_stream(const S2DeviceTables &t, int nbh, float scale, const float *q, const float *k,
                              const float *v, const float *lse, const float *go, const float *Dws, float *dk, float *dv,
                              hipStream_t st);
+
+// bf16 tensors on the bf16 matrix cores (band tiles of 16 keys x 16 outputs, float32 softmax and accumulation): equal
+// grids, d = e = 32, longitude count a multiple of 64.
+bool s2_nattn_bf16_supported(const S2DeviceTables &t, int d, int e);
+int s2_nattn_fwd_bf16(const S2DeviceTables &t, int nbh, int d, int e, float scale, const void *q, const void *k,
+                      const void *v, void *out, float *lse, hipStream_t st);
+int s2_nattn_bwd_dq_bf16(const S2DeviceTables &t, int nbh, int d, int e, float scale, const void *q, const void *k,
+                         const void *v, const void *o, const float *lse, const void *go, void *dq, float *Dws,
+                         hipStream_t st);
+int s2_nattn_bwd_dkdv_bf16(const S2DeviceTables &t, int nbh, int d, int e, float scale, const void *q, const void *k,
+                           const void *v, const float *lse, const void *go, const float *Dws, void *dk, void *dv,
+                           hipStream_t st);
 
 // Backward with the scratch for D_i given as a device pointer (checks and dispatch behind both C entry points).
 int s2_nattn_bwd_run(const s2_grid_t *g, int batch, int heads, int d_qk, int d_v, int dtype, float scale,

@@ -8,8 +8,8 @@ Recipe: numpy Generator(PCG64(1000 + cfg)), standard_normal float32, drawn in
 the order q, k, v, dout in the library's tensor layout.  The grids, cutoffs
 and shapes stand in for the paper's experiment shapes (128x256-class
 equiangular / Gaussian grids, cutoffs of about four grid spacings, heads x 32
-channels).  The global workload rounds the draws to bf16 (round to nearest
-even) before either side sees them.
+channels).  The bf16 workloads (global attention, and workload 7) round the
+draws to bf16 (round to nearest even) before either side sees them.
 """
 import math
 
@@ -35,6 +35,10 @@ CONFIGS = {
     # queries on the fine grid, keys and values on the coarse one), used to measure the upsampling path
     6: dict(kind="nattn", grid_type=EQUIANGULAR, nlat_in=129, nlon_in=256, nlat_out=257, nlon_out=512,
             theta=2 * math.pi / 128, batch=2, heads=4, d=32, dtype="f32"),
+    # workload 3 with bf16 tensors (float32 accumulation and logsumexp): the reduced-precision variant of the
+    # neighborhood path, measured as a secondary workload
+    7: dict(kind="nattn", grid_type=EQUIANGULAR, nlat_in=129, nlon_in=256, nlat_out=129, nlon_out=256,
+            theta=4 * math.pi / 128, batch=4, heads=8, d=32, dtype="bf16"),
 }
 
 

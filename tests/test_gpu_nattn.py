@@ -530,9 +530,10 @@ def test_errors_on_device():
     g = _grid(gd)
     dev = torch.device("cuda:0")
     q = torch.zeros((1, 1, 8, 17, 32), device=dev)
+    wide = torch.zeros((1, 1, 130, 17, 32), device=dev)
     with pytest.raises(S.S2Error) as ei:
-        S.s2_nattn_fwd(g, q.to(torch.bfloat16), q.to(torch.bfloat16), q.to(torch.bfloat16), 1.0)
-    assert ei.value.code == S.S2_ERR_UNSUPPORTED
+        S.s2_nattn_fwd(g, wide, wide, wide, 1.0)
+    assert ei.value.code == S.S2_ERR_UNSUPPORTED          # head dimensions above 128
     out, lse = S.s2_nattn_fwd(g, q, q, q, 1.0)
     with pytest.raises(S.S2Error) as ei:
         S.s2_nattn_bwd(g, q, q, q, out, lse, q, 1.0, workspace=torch.empty(16, dtype=torch.uint8, device=dev))
