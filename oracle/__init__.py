@@ -21,3 +21,4 @@ from .s2_oracle import (  # noqa: F401
     neighbor_csr,
     omega,
 )
+from .s2_layers import disco_bwd, disco_fwd, disco_psi, mha_bwd, mha_fwd  # noqa: F401,E402

@@ -169,7 +169,7 @@ __device__ __forceinline__ bool inside(const RowWindow &r, int Xt, int Wo)
 // ---------------------------------------------------------------------------------------------------------------
 // Forward.  Block -> (output latitude by work, slice, group of 256 longitudes).
 __global__ void __launch_bounds__(256, 3)
-nattn_fwd_bf16(S2DeviceTables t, int nbh, float c2, const bf16raw *__restrict__ q, const bf16raw *__restrict__ k,
+nattn_fwd_bf16(S2DeviceTables t, int nbh, int first_row, float c2, const bf16raw *__restrict__ q, const bf16raw *__restrict__ k,
                const bf16raw *__restrict__ v, bf16raw *__restrict__ out, float *__restrict__ lse)
 {
     __shared__ __attribute__((aligned(16))) char lds[2][kTokBytes + kChanBytes];
@@ -178,7 +178,7 @@ nattn_fwd_bf16(S2DeviceTables t, int nbh, float c2, const bf16raw *__restrict__ 
     int id = blockIdx.x;
     const int grp = id % ngrp; id /= ngrp;
     const int bh = id % nbh;
-    const int h = t.row_order[id / nbh];
+    const int h = t.row_order[first_row + id / nbh];
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 15, g = lane >> 4;
     const int W0 = grp << 8;
@@ -315,7 +315,7 @@ nattn_fwd_bf16(S2DeviceTables t, int nbh, float c2, const bf16raw *__restrict__ 
 // Backward, query side: D_i = dout_i . out_i (stored for the key side), dS_ij = p_ij (dout_i . v_j - D_i),
 // dq_i = scale sum_j dS_ij k_j, with p_ij = omega_j exp(scale q_i.k_j - lse_i) recomputed from the saved logsumexp.
 __global__ void __launch_bounds__(256, 3)
-nattn_bwd_dq_bf16(S2DeviceTables t, int nbh, float scale, const bf16raw *__restrict__ q, const bf16raw *__restrict__ k,
+nattn_bwd_dq_bf16(S2DeviceTables t, int nbh, int first_row, float scale, const bf16raw *__restrict__ q, const bf16raw *__restrict__ k,
                   const bf16raw *__restrict__ v, const bf16raw *__restrict__ o_, const float *__restrict__ lse,
                   const bf16raw *__restrict__ go, bf16raw *__restrict__ dq, float *__restrict__ Dws)
 {
@@ -326,7 +326,7 @@ nattn_bwd_dq_bf16(S2DeviceTables t, int nbh, float scale, const bf16raw *__restr
     int id = blockIdx.x;
     const int grp = id % ngrp; id /= ngrp;
     const int bh = id % nbh;
-    const int h = t.row_order[id / nbh];
+    const int h = t.row_order[first_row + id / nbh];
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 15, g = lane >> 4;
     const int W0 = grp << 8;
@@ -450,7 +450,7 @@ nattn_bwd_dq_bf16(S2DeviceTables t, int nbh, float scale, const bf16raw *__restr
 // are, on every output latitude of the transposed band, the columns within the same half-width of j.
 // dk_j = scale sum_i dS_ij q_i, dv_j = sum_i p_ij dout_i: gathered, no atomics.
 __global__ void __launch_bounds__(256)
-nattn_bwd_dkdv_bf16(S2DeviceTables t, int nbh, float scale, const bf16raw *__restrict__ q, const bf16raw *__restrict__ k,
+nattn_bwd_dkdv_bf16(S2DeviceTables t, int nbh, int first_row, float scale, const bf16raw *__restrict__ q, const bf16raw *__restrict__ k,
                     const bf16raw *__restrict__ v, const float *__restrict__ lse, const bf16raw *__restrict__ go,
                     const float *__restrict__ Dws, bf16raw *__restrict__ dk, bf16raw *__restrict__ dv)
 {
@@ -461,7 +461,7 @@ nattn_bwd_dkdv_bf16(S2DeviceTables t, int nbh, float scale, const bf16raw *__res
     int id = blockIdx.x;
     const int grp = id % ngrp; id /= ngrp;
     const int bh = id % nbh;
-    const int hp = t.trow_order[id / nbh];
+    const int hp = t.trow_order[first_row + id / nbh];
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 15, g = lane >> 4;
     const int W0 = grp << 8;
@@ -604,8 +604,6 @@ nattn_bwd_dkdv_bf16(S2DeviceTables t, int nbh, float scale, const bf16raw *__res
     }
 }
 
-double all_pairs(const S2DeviceTables &t) { return t.fwd_pairs[0] + t.fwd_pairs[1] + t.fwd_pairs[2] + t.fwd_pairs[3]; }
-
 }  // namespace
 
 bool s2_nattn_bf16_supported(const S2DeviceTables &t, int d, int e)
@@ -614,15 +612,35 @@ bool s2_nattn_bf16_supported(const S2DeviceTables &t, int d, int e)
            t.nlon_in % 64 == 0 && !s2_debug_flag(S2_DEBUG_NO_MFMA);
 }
 
+// Two launches per kernel: the latitudes of the three heavy classes (dense neighborhoods near the poles), then the
+// light ones; the library's launch trace reports them separately.
+template <class F>
+static void launch_by_class(const S2DeviceTables &t, bool fwd_side, int nbh, const char *dense_name, const char *light_name,
+                            hipStream_t st, F launch)
+{
+    const int *cls = fwd_side ? t.fwd_cls : t.bwd_cls;
+    const double *pairs = fwd_side ? t.fwd_pairs : t.bwd_pairs;
+    const int ngrp = (t.nlon_in + 255) / 256;
+    const int ndense = cls[0] + cls[1] + cls[2];
+    if (ndense > 0) {
+        S2TraceScope tr(dense_name, nbh * (pairs[0] + pairs[1] + pairs[2]), st);
+        launch(0, unsigned(long(nbh) * ndense * ngrp));
+    }
+    if (cls[3] > 0) {
+        S2TraceScope tr(light_name, nbh * pairs[3], st);
+        launch(ndense, unsigned(long(nbh) * cls[3] * ngrp));
+    }
+}
+
 int s2_nattn_fwd_bf16(const S2DeviceTables &t, int nbh, int, int, float scale, const void *q, const void *k,
                       const void *v, void *out, float *lse, hipStream_t st)
 {
     if (s2_debug_flag(S2_DEBUG_FAIL_LAUNCH)) return -1;
-    const long nblk = long(nbh) * t.nlat_out * ((t.nlon_in + 255) / 256);
-    S2TraceScope tr("nattn_fwd_bf16", nbh * all_pairs(t), st);
-    hipLaunchKernelGGL(nattn_fwd_bf16, dim3(unsigned(nblk)), dim3(256), 0, st, t, nbh, scale * kLog2e,
-                       static_cast<const bf16raw *>(q), static_cast<const bf16raw *>(k), static_cast<const bf16raw *>(v),
-                       static_cast<bf16raw *>(out), lse);
+    launch_by_class(t, true, nbh, "nattn_fwd_bf16<dense>", "nattn_fwd_bf16<light>", st, [&](int first, unsigned nblk) {
+        hipLaunchKernelGGL(nattn_fwd_bf16, dim3(nblk), dim3(256), 0, st, t, nbh, first, scale * kLog2e,
+                           static_cast<const bf16raw *>(q), static_cast<const bf16raw *>(k),
+                           static_cast<const bf16raw *>(v), static_cast<bf16raw *>(out), lse);
+    });
     return 0;
 }
 
@@ -631,12 +649,12 @@ int s2_nattn_bwd_dq_bf16(const S2DeviceTables &t, int nbh, int, int, float scale
                          hipStream_t st)
 {
     if (s2_debug_flag(S2_DEBUG_FAIL_LAUNCH)) return -1;
-    const long nblk = long(nbh) * t.nlat_out * ((t.nlon_in + 255) / 256);
-    S2TraceScope tr("nattn_bwd_dq_bf16", nbh * all_pairs(t), st);
-    hipLaunchKernelGGL(nattn_bwd_dq_bf16, dim3(unsigned(nblk)), dim3(256), 0, st, t, nbh, scale,
-                       static_cast<const bf16raw *>(q), static_cast<const bf16raw *>(k), static_cast<const bf16raw *>(v),
-                       static_cast<const bf16raw *>(o), lse, static_cast<const bf16raw *>(go), static_cast<bf16raw *>(dq),
-                       Dws);
+    launch_by_class(t, true, nbh, "nattn_bwd_dq_bf16<dense>", "nattn_bwd_dq_bf16<light>", st, [&](int first, unsigned nblk) {
+        hipLaunchKernelGGL(nattn_bwd_dq_bf16, dim3(nblk), dim3(256), 0, st, t, nbh, first, scale,
+                           static_cast<const bf16raw *>(q), static_cast<const bf16raw *>(k),
+                           static_cast<const bf16raw *>(v), static_cast<const bf16raw *>(o), lse,
+                           static_cast<const bf16raw *>(go), static_cast<bf16raw *>(dq), Dws);
+    });
     return 0;
 }
 
@@ -645,10 +663,11 @@ int s2_nattn_bwd_dkdv_bf16(const S2DeviceTables &t, int nbh, int, int, float sca
                            hipStream_t st)
 {
     if (s2_debug_flag(S2_DEBUG_FAIL_LAUNCH)) return -1;
-    const long nblk = long(nbh) * t.nlat_in * ((t.nlon_in + 255) / 256);
-    S2TraceScope tr("nattn_bwd_dkdv_bf16", nbh * all_pairs(t), st);
-    hipLaunchKernelGGL(nattn_bwd_dkdv_bf16, dim3(unsigned(nblk)), dim3(256), 0, st, t, nbh, scale,
-                       static_cast<const bf16raw *>(q), static_cast<const bf16raw *>(k), static_cast<const bf16raw *>(v), lse,
-                       static_cast<const bf16raw *>(go), Dws, static_cast<bf16raw *>(dk), static_cast<bf16raw *>(dv));
+    launch_by_class(t, false, nbh, "nattn_bwd_dkdv_bf16<dense>", "nattn_bwd_dkdv_bf16<light>", st, [&](int first, unsigned nblk) {
+        hipLaunchKernelGGL(nattn_bwd_dkdv_bf16, dim3(nblk), dim3(256), 0, st, t, nbh, first, scale,
+                           static_cast<const bf16raw *>(q), static_cast<const bf16raw *>(k),
+                           static_cast<const bf16raw *>(v), lse, static_cast<const bf16raw *>(go), Dws,
+                           static_cast<bf16raw *>(dk), static_cast<bf16raw *>(dv));
+    });
     return 0;
 }
