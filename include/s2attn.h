@@ -196,6 +196,38 @@ int s2_attn_global_bwd(const s2_grid_t *g, int batch, int heads, int d, int dtyp
                        void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * Spherical multi-head attention sub-block (Sec. 3.4, "Spherical attention blocks": instance normalisation, position
+ * embedding, multi-head neighborhood attention, residual), float32, self-attention on one grid (the handle's input
+ * and output grids must be equal):
+ *   xhat = (x - mean) / sqrt(var + eps) per (batch, channel) over the grid points (plain moments, biased variance)
+ *   xn = gamma xhat + beta + pos;  q, k, v = Wq xn + bq, Wk xn + bk, Wv xn + bv   (1x1 convolutions)
+ *   a = neighborhood attention per head, head i = channels i*d .. (i+1)*d - 1, d = channels / heads, scale 1/sqrt(d)
+ *   y = x + Wo a + bo
+ * x, y, dy, dx: [batch][channels][nlat][nlon] contiguous.  Parameters (device pointers): gamma, beta, bq, bk, bv, bo
+ * [channels] and pos [channels][nlat][nlon] may be NULL (1, 0, no bias, no embedding); Wq, Wk, Wv, Wo
+ * [channels out][channels in] row-major are required.  s2_mha_bwd writes the gradients of sum(dy * y) to dx and to
+ * every non-NULL pointer of `grads` (same shapes as the parameters).
+ * workspace: device scratch of s2_mha_workspace_bytes(...) bytes, 256-byte aligned; it carries the activations the
+ * backward needs, so s2_mha_bwd must get the workspace of the matching s2_mha_fwd call, untouched.
+ * channels and nlat*nlon must be multiples of 16 (else S2_ERR_UNSUPPORTED).  Every step runs in the library's own
+ * kernels (channel matrices on the fp32 matrix cores); results are bit-reproducible.
+ */
+typedef struct {
+    const float *gamma, *beta, *pos;
+    const float *Wq, *bq, *Wk, *bk, *Wv, *bv, *Wo, *bo;
+} s2_mha_params_t;
+typedef struct {
+    float *gamma, *beta, *pos;
+    float *Wq, *bq, *Wk, *bk, *Wv, *bv, *Wo, *bo;
+} s2_mha_grads_t;
+size_t s2_mha_workspace_bytes(const s2_grid_t *g, int batch, int channels, int heads);
+int s2_mha_fwd(const s2_grid_t *g, int batch, int channels, int heads, float eps, const float *x,
+               const s2_mha_params_t *params, float *y, void *workspace, size_t workspace_bytes, void *hip_stream);
+int s2_mha_bwd(const s2_grid_t *g, int batch, int channels, int heads, float eps, const float *x,
+               const s2_mha_params_t *params, const float *dy, float *dx, const s2_mha_grads_t *grads,
+               void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * Per-launch timing for benchmarks (not part of the method).  While enabled, every kernel launch
  * of the attention calls is bracketed by HIP events on the launch stream.  s2_trace_get waits for
  * entry `index` and returns the kernel's name, its duration in ms and the number of (output, input)

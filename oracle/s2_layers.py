@@ -86,6 +86,7 @@ def mha_bwd(g, heads, x, pos, gamma, beta, Wq, bq, Wk, bk, Wv, bv, Wo, bo, dy, e
     m1 = dxhat.mean(axis=(2, 3), keepdims=True)
     m2 = (dxhat * s["xhat"]).mean(axis=(2, 3), keepdims=True)
     res["dx"] = dy + s["rstd"] * (dxhat - m1 - s["xhat"] * m2)
+    res["intermediates"] = dict(dq=dq, dk=dk, dv=dv, dxn=dxn, da=da, xn=s["xn"], xhat=s["xhat"], a=s["a"])
     return res
 
 

@@ -76,6 +76,12 @@ def lib():
         L.s2_nattn_bwd_static.restype = _i
         L.s2_nattn_bwd_static_max_points.argtypes = []
         L.s2_nattn_bwd_static_max_points.restype = ctypes.c_size_t
+        L.s2_mha_workspace_bytes.argtypes = [_vp, _i, _i, _i]
+        L.s2_mha_workspace_bytes.restype = ctypes.c_size_t
+        L.s2_mha_fwd.argtypes = [_vp, _i, _i, _i, ctypes.c_float, _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
+        L.s2_mha_fwd.restype = _i
+        L.s2_mha_bwd.argtypes = [_vp, _i, _i, _i, ctypes.c_float, _vp, _vp, _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
+        L.s2_mha_bwd.restype = _i
         L.s2_attn_global_fwd_workspace_bytes.argtypes = [_vp, _i, _i, _i, _i]
         L.s2_attn_global_fwd_workspace_bytes.restype = ctypes.c_size_t
         L.s2_attn_global_bwd_workspace_bytes.argtypes = [_vp, _i, _i, _i, _i]
@@ -250,6 +256,57 @@ def s2_nattn_bwd_static(g, q, k, v, out, lse, dout, scale, dq, dk, dv):
                                      v.data_ptr(), out.data_ptr(), lse.data_ptr(), dout.data_ptr(), dq.data_ptr(),
                                      dk.data_ptr(), dv.data_ptr(), _stream()))
     return dq, dk, dv
+
+
+MHA_FIELDS = ("gamma", "beta", "pos", "Wq", "bq", "Wk", "bk", "Wv", "bv", "Wo", "bo")
+
+
+class _MhaPointers(ctypes.Structure):
+    """s2_mha_params_t / s2_mha_grads_t: eleven device pointers."""
+    _fields_ = [(f, ctypes.c_void_p) for f in MHA_FIELDS]
+
+
+def _mha_struct(tensors):
+    st = _MhaPointers()
+    for f in MHA_FIELDS:
+        t = tensors.get(f)
+        if t is not None:
+            _dev(t)
+        setattr(st, f, t.data_ptr() if t is not None else None)
+    return st
+
+
+def s2_mha_workspace_bytes(g, batch, channels, heads):
+    return int(lib().s2_mha_workspace_bytes(g.handle, batch, channels, heads))
+
+
+def s2_mha_fwd(g, x, params, heads, eps=1e-5, y=None, workspace=None):
+    """x [B, C, nlat, nlon] float32; params: dict of device tensors (MHA_FIELDS; optional ones may be missing).
+    Returns y and the workspace (which s2_mha_bwd needs back)."""
+    import torch
+    _dev(x)
+    B, C = x.shape[:2]
+    y = torch.empty_like(x) if y is None else y
+    if workspace is None:
+        workspace = torch.empty(max(s2_mha_workspace_bytes(g, B, C, heads), 1), dtype=torch.uint8, device=x.device)
+    st = _mha_struct(params)
+    _check(lib().s2_mha_fwd(g.handle, B, C, heads, float(eps), x.data_ptr(), ctypes.byref(st), y.data_ptr(),
+                            workspace.data_ptr(), workspace.numel(), _stream()))
+    return y, workspace
+
+
+def s2_mha_bwd(g, x, params, heads, dy, workspace, eps=1e-5, want=MHA_FIELDS):
+    """Gradients of sum(dy * y): returns dx and a dict of parameter gradients (for the names in `want` that exist in
+    params)."""
+    import torch
+    _dev(x, dy, workspace)
+    B, C = x.shape[:2]
+    dx = torch.empty_like(x)
+    grads = {f: torch.empty_like(params[f]) for f in want if params.get(f) is not None}
+    st, gs = _mha_struct(params), _mha_struct(grads)
+    _check(lib().s2_mha_bwd(g.handle, B, C, heads, float(eps), x.data_ptr(), ctypes.byref(st), dy.data_ptr(),
+                            dx.data_ptr(), ctypes.byref(gs), workspace.data_ptr(), workspace.numel(), _stream()))
+    return dx, grads
 
 
 def s2_attn_global_fwd_workspace_bytes(g, batch, heads, d, dtype=S2_BF16):

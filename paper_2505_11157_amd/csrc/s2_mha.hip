@@ -1,0 +1,478 @@
+// Spherical multi-head attention sub-block (Sec. 3.4 "Spherical attention blocks": pre-norm, residual) around the
+// neighborhood attention kernels, float32:
+//     xhat = instance norm of x per (batch, channel) over the grid points (plain moments, biased variance)
+//     xn   = gamma xhat + beta + pos
+//     q, k, v = Wq xn + bq, Wk xn + bk, Wv xn + bv          (1x1 convolutions; head i owns channels i d .. (i+1) d - 1,
+//                                                            which is the [batch][heads][d] layout of the kernels)
+//     a    = s2_nattn_fwd(q, k, v), scale 1 / sqrt(d)
+//     y    = x + Wo a + bo
+// and its backward.  The channel matrices run on the fp32 matrix cores (v_mfma_f32_32x32x2_f32): a workgroup of four
+// wavefronts owns a 128 x 128 tile of the output, each wavefront 64 x 64 (2 x 2 matrix tiles), operands staged
+// through LDS in slices of 16 along the contraction.  Weight gradients contract over batch and grid points
+// (hundreds of thousands of terms): split over workgroups into partial sums that a second launch adds in a fixed
+// order, so every result is bit-reproducible.
+#include "s2_nattn_kernels.h"
+
+namespace {
+
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+constexpr int kTM = 128, kTN = 128, kTK = 16;
+constexpr int kPitch = kTM + 4;      // LDS row pitch of the k-major operand tiles (floats)
+constexpr int kPitchW = kTK + 1;     // pitch of the row-major tiles of the weight-gradient kernel
+
+__device__ __forceinline__ f32x16 mfma32(float a, float b, f32x16 c)
+{
+    return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
+}
+
+// C[b][m][n] (+)= sum_k A(m, k) X[b][k][n] + bias[m] + R[b][m][n]
+// A(m, k) = W[m * K + k] (TRANS_A = false, W is M x K) or W[k * M + m] (TRANS_A = true, W is K x M).
+// M, K multiples of 16; N a multiple of 4.  grid (ceil(N / 128), ceil(M / 128), batch), 256 threads.
+template <bool TRANS_A>
+__global__ void __launch_bounds__(256)
+mha_gemm(int M, int N, int K, const float *__restrict__ W, const float *__restrict__ X, const float *__restrict__ bias,
+         const float *__restrict__ R, float *__restrict__ C, int accumulate)
+{
+    __shared__ float As[2][kTK * kPitch];      // [k][m]
+    __shared__ float Bs[2][kTK * kPitch];      // [k][n]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n0 = blockIdx.x * kTN, m0 = blockIdx.y * kTM;
+    const float *Xb = X + size_t(blockIdx.z) * K * N;
+    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+    const int col = lane & 31, kk = lane >> 5;
+
+    float4 ra[2], rb[2];
+    auto load = [&](int k0) {
+        if constexpr (TRANS_A) {
+            const int kr = tid >> 4, mo = (tid & 15) * 8;      // row k0 + kr of W, columns m0 + mo .. + 7
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int m = m0 + mo + 4 * j;
+                ra[j] = m < M ? *reinterpret_cast<const float4 *>(W + size_t(k0 + kr) * M + m) : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+        } else {
+            const int mr = tid >> 1, ko = (tid & 1) * 8;       // row m0 + mr of W, columns k0 + ko .. + 7
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                ra[j] = m0 + mr < M ? *reinterpret_cast<const float4 *>(W + size_t(m0 + mr) * K + k0 + ko + 4 * j)
+                                    : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+        const int kr = tid >> 4, no = (tid & 15) * 8;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int n = n0 + no + 4 * j;
+            rb[j] = n < N ? *reinterpret_cast<const float4 *>(Xb + size_t(k0 + kr) * N + n) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    };
+    auto store = [&](int buf) {
+        if constexpr (TRANS_A) {
+            const int kr = tid >> 4, mo = (tid & 15) * 8;
+            *reinterpret_cast<float4 *>(&As[buf][kr * kPitch + mo]) = ra[0];
+            *reinterpret_cast<float4 *>(&As[buf][kr * kPitch + mo + 4]) = ra[1];
+        } else {
+            const int mr = tid >> 1, ko = (tid & 1) * 8;
+            const float v[8] = {ra[0].x, ra[0].y, ra[0].z, ra[0].w, ra[1].x, ra[1].y, ra[1].z, ra[1].w};
+#pragma unroll
+            for (int j = 0; j < 8; ++j) As[buf][(ko + j) * kPitch + mr] = v[j];
+        }
+        const int kr = tid >> 4, no = (tid & 15) * 8;
+        *reinterpret_cast<float4 *>(&Bs[buf][kr * kPitch + no]) = rb[0];
+        *reinterpret_cast<float4 *>(&Bs[buf][kr * kPitch + no + 4]) = rb[1];
+    };
+
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    load(0);
+    store(0);
+    __syncthreads();
+    int buf = 0;
+    for (int k0 = 0; k0 < K; k0 += kTK) {
+        const bool more = k0 + kTK < K;
+        if (more) load(k0 + kTK);
+#pragma unroll
+        for (int s = 0; s < kTK / 2; ++s) {
+            const float *ar = &As[buf][(2 * s + kk) * kPitch + wm + col], *br = &Bs[buf][(2 * s + kk) * kPitch + wn + col];
+            const float a0 = ar[0], a1 = ar[32], b0 = br[0], b1 = br[32];
+            acc[0][0] = mfma32(a0, b0, acc[0][0]);
+            acc[0][1] = mfma32(a0, b1, acc[0][1]);
+            acc[1][0] = mfma32(a1, b0, acc[1][0]);
+            acc[1][1] = mfma32(a1, b1, acc[1][1]);
+        }
+        if (more) {
+            store(buf ^ 1);
+            __syncthreads();
+            buf ^= 1;
+        }
+    }
+    float *Cb = C + size_t(blockIdx.z) * M * N;
+    const float *Rb = R ? R + size_t(blockIdx.z) * M * N : nullptr;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int n = n0 + wn + 32 * j + col;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int m = m0 + wm + 32 * i + 8 * (e >> 2) + 4 * kk + (e & 3);
+                if (m < M && n < N) {
+                    float x = acc[i][j][e];
+                    if (bias) x += bias[m];
+                    if (Rb) x += Rb[size_t(m) * N + n];
+                    if (accumulate) x += Cb[size_t(m) * N + n];
+                    Cb[size_t(m) * N + n] = x;
+                }
+            }
+        }
+}
+
+// Partial weight gradients: part[split][m][k] = sum over the split's share of (batch, grid point) of
+// dY[b][m][n] X[b][k][n].  M, K multiples of 16, N a multiple of 16.  grid (ceil(K / 128), ceil(M / 128), splits).
+__global__ void __launch_bounds__(256)
+mha_wgrad_partial(int M, int K, int N, int batch, int nsplit, const float *__restrict__ dY, const float *__restrict__ X,
+                  float *__restrict__ part)
+{
+    __shared__ float Ys[2][kTM * kPitchW];     // [m][n']
+    __shared__ float Xs[2][kTN * kPitchW];     // [k][n']
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int k0t = blockIdx.x * kTN, m0 = blockIdx.y * kTM, split = blockIdx.z;
+    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+    const int col = lane & 31, kk = lane >> 5;
+    const long chunks = long(batch) * (N / kTK);
+    const long c_lo = chunks * split / nsplit, c_hi = chunks * (split + 1) / nsplit;
+    const int row = tid >> 1, off = (tid & 1) * 8;
+
+    float4 ry[2], rx[2];
+    auto load = [&](long c) {
+        const int b = int(c / (N / kTK)), nn = int(c % (N / kTK)) * kTK + off;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            ry[j] = m0 + row < M ? *reinterpret_cast<const float4 *>(dY + (size_t(b) * M + m0 + row) * N + nn + 4 * j)
+                                 : make_float4(0.f, 0.f, 0.f, 0.f);
+            rx[j] = k0t + row < K ? *reinterpret_cast<const float4 *>(X + (size_t(b) * K + k0t + row) * N + nn + 4 * j)
+                                  : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    };
+    auto store = [&](int buf) {
+        const float y[8] = {ry[0].x, ry[0].y, ry[0].z, ry[0].w, ry[1].x, ry[1].y, ry[1].z, ry[1].w};
+        const float x[8] = {rx[0].x, rx[0].y, rx[0].z, rx[0].w, rx[1].x, rx[1].y, rx[1].z, rx[1].w};
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            Ys[buf][row * kPitchW + off + j] = y[j];
+            Xs[buf][row * kPitchW + off + j] = x[j];
+        }
+    };
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+    if (c_lo < c_hi) {
+        load(c_lo);
+        store(0);
+    }
+    __syncthreads();
+    int buf = 0;
+    for (long c = c_lo; c < c_hi; ++c) {
+        const bool more = c + 1 < c_hi;
+        if (more) load(c + 1);
+#pragma unroll
+        for (int s = 0; s < kTK / 2; ++s) {
+            const float a0 = Ys[buf][(wm + col) * kPitchW + 2 * s + kk], a1 = Ys[buf][(wm + 32 + col) * kPitchW + 2 * s + kk];
+            const float b0 = Xs[buf][(wn + col) * kPitchW + 2 * s + kk], b1 = Xs[buf][(wn + 32 + col) * kPitchW + 2 * s + kk];
+            acc[0][0] = mfma32(a0, b0, acc[0][0]);
+            acc[0][1] = mfma32(a0, b1, acc[0][1]);
+            acc[1][0] = mfma32(a1, b0, acc[1][0]);
+            acc[1][1] = mfma32(a1, b1, acc[1][1]);
+        }
+        if (more) {
+            store(buf ^ 1);
+            __syncthreads();
+            buf ^= 1;
+        }
+    }
+    float *P = part + size_t(split) * M * K;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int k = k0t + wn + 32 * j + col;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int m = m0 + wm + 32 * i + 8 * (e >> 2) + 4 * kk + (e & 3);
+                if (m < M && k < K) P[size_t(m) * K + k] = acc[i][j][e];
+            }
+        }
+}
+
+__global__ void __launch_bounds__(256)
+mha_sum_partials(int count, int nsplit, const float *__restrict__ part, float *__restrict__ out)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= count) return;
+    float s = 0.f;
+    for (int p = 0; p < nsplit; ++p) s += part[size_t(p) * count + i];       // fixed order
+    out[i] = s;
+}
+
+// block-wide sum of one value per thread (256 threads), result in every thread; fixed order
+__device__ __forceinline__ float block_sum(float x, float *red)
+{
+    const int tid = threadIdx.x;
+    red[tid] = x;
+    __syncthreads();
+#pragma unroll
+    for (int s = 128; s > 0; s >>= 1) {
+        if (tid < s) red[tid] += red[tid + s];
+        __syncthreads();
+    }
+    const float r = red[0];
+    __syncthreads();
+    return r;
+}
+
+// Instance normalisation: one workgroup per (batch, channel): mean and 1 / sqrt(var + eps) over the N grid points
+// (two passes: the moments are taken about the mean), then xn = gamma xhat + beta + pos.
+__global__ void __launch_bounds__(256)
+mha_instnorm_fwd(int C, int N, float eps, const float *__restrict__ x, const float *__restrict__ gamma,
+                 const float *__restrict__ beta, const float *__restrict__ pos, float *__restrict__ mean,
+                 float *__restrict__ rstd, float *__restrict__ xn)
+{
+    __shared__ float red[256];
+    const int bc = blockIdx.x, c = bc % C, tid = threadIdx.x;
+    const float *xr = x + size_t(bc) * N;
+    float s = 0.f;
+    for (int i = tid; i < N; i += 256) s += xr[i];
+    const float mu = block_sum(s, red) / float(N);
+    float v = 0.f;
+    for (int i = tid; i < N; i += 256) { const float dlt = xr[i] - mu; v = fmaf(dlt, dlt, v); }
+    const float rs = 1.f / sqrtf(block_sum(v, red) / float(N) + eps);
+    if (tid == 0) { mean[bc] = mu; rstd[bc] = rs; }
+    const float ga = gamma ? gamma[c] : 1.f, be = beta ? beta[c] : 0.f;
+    const float *pr = pos ? pos + size_t(c) * N : nullptr;
+    float *o = xn + size_t(bc) * N;
+    for (int i = tid; i < N; i += 256) o[i] = fmaf(ga, (xr[i] - mu) * rs, be) + (pr ? pr[i] : 0.f);
+}
+
+// dx = dy + rstd (dxhat - mean(dxhat) - xhat mean(dxhat xhat)), dxhat = gamma dxn; one workgroup per (batch, channel)
+__global__ void __launch_bounds__(256)
+mha_instnorm_bwd(int C, int N, const float *__restrict__ x, const float *__restrict__ gamma, const float *__restrict__ mean,
+                 const float *__restrict__ rstd, const float *__restrict__ dxn, const float *__restrict__ dy,
+                 float *__restrict__ dx)
+{
+    __shared__ float red[256];
+    const int bc = blockIdx.x, c = bc % C, tid = threadIdx.x;
+    const float mu = mean[bc], rs = rstd[bc], ga = gamma ? gamma[c] : 1.f;
+    const float *xr = x + size_t(bc) * N, *gr = dxn + size_t(bc) * N, *yr = dy + size_t(bc) * N;
+    float s1 = 0.f, s2 = 0.f;
+    for (int i = tid; i < N; i += 256) {
+        const float dh = ga * gr[i];
+        s1 += dh;
+        s2 = fmaf(dh, (xr[i] - mu) * rs, s2);
+    }
+    const float m1 = block_sum(s1, red) / float(N), m2 = block_sum(s2, red) / float(N);
+    float *o = dx + size_t(bc) * N;
+    for (int i = tid; i < N; i += 256) {
+        const float xh = (xr[i] - mu) * rs;
+        o[i] = yr[i] + rs * (ga * gr[i] - m1 - xh * m2);
+    }
+}
+
+// out[c] = sum over batch and grid points of u[b][c][n] (* xhat[b][c][n] if x is given); one workgroup per channel
+__global__ void __launch_bounds__(256)
+mha_channel_sum(int batch, int C, int N, const float *__restrict__ u, const float *__restrict__ x,
+                const float *__restrict__ mean, const float *__restrict__ rstd, float *__restrict__ out)
+{
+    __shared__ float red[256];
+    const int c = blockIdx.x, tid = threadIdx.x;
+    float s = 0.f;
+    for (int b = 0; b < batch; ++b) {
+        const float *ur = u + (size_t(b) * C + c) * N;
+        if (x) {
+            const float *xr = x + (size_t(b) * C + c) * N;
+            const float mu = mean[b * C + c], rs = rstd[b * C + c];
+            for (int i = tid; i < N; i += 256) s = fmaf(ur[i], (xr[i] - mu) * rs, s);
+        } else {
+            for (int i = tid; i < N; i += 256) s += ur[i];
+        }
+    }
+    const float r = block_sum(s, red);
+    if (tid == 0) out[c] = r;
+}
+
+// dpos[c][n] = sum_b dxn[b][c][n]
+__global__ void __launch_bounds__(256)
+mha_batch_sum(int batch, size_t CN, const float *__restrict__ u, float *__restrict__ out)
+{
+    const size_t i = size_t(blockIdx.x) * 256 + threadIdx.x;
+    if (i >= CN) return;
+    float s = 0.f;
+    for (int b = 0; b < batch; ++b) s += u[size_t(b) * CN + i];
+    out[i] = s;
+}
+
+constexpr int kSplits = 64;
+
+struct Layout {      // offsets (in floats) into the workspace
+    size_t mean, rstd, xn, q, k, v, a, lse, da, dq, dk, dv, dxn, D, part, total;
+};
+Layout layout(const s2_grid_t *g, int batch, int C, int heads)
+{
+    const size_t N = size_t(g->nlat_in) * g->nlon_in, T = size_t(batch) * C * N;
+    auto up = [](size_t x) { return (x + 63) / 64 * 64; };      // 256-byte pieces
+    Layout L{};
+    size_t at = 0;
+    L.mean = at; at += up(size_t(batch) * C);
+    L.rstd = at; at += up(size_t(batch) * C);
+    L.xn = at; at += up(T);
+    L.q = at; at += up(T);
+    L.k = at; at += up(T);
+    L.v = at; at += up(T);
+    L.a = at; at += up(T);
+    L.lse = at; at += up(size_t(batch) * heads * N);
+    L.da = at; at += up(T);
+    L.dq = at; at += up(T);
+    L.dk = at; at += up(T);
+    L.dv = at; at += up(T);
+    L.dxn = at; at += up(T);
+    L.D = at; at += up(size_t(batch) * heads * N);
+    L.part = at; at += up(size_t(kSplits) * C * C);
+    L.total = at;
+    return L;
+}
+
+int check(const s2_grid_t *g, int batch, int C, int heads, const void *ws, size_t ws_bytes)
+{
+    if (!g) return s2_fail(S2_ERR_INVALID_ARG, "grid is NULL");
+    if (batch < 1 || heads < 1 || C < 1 || C % heads != 0) return s2_fail(S2_ERR_INVALID_ARG, "channels must be a positive multiple of heads");
+    if (!g->on_device) return s2_fail(S2_ERR_DEVICE, "grid handle has no device tables (no HIP device at init)");
+    if (g->nlat_in != g->nlat_out || g->nlon_in != g->nlon_out)
+        return s2_fail(S2_ERR_UNSUPPORTED, "the attention sub-block is self-attention: input and output grid must be equal");
+    if (C % 16 != 0 || (size_t(g->nlat_in) * g->nlon_in) % 16 != 0)
+        return s2_fail(S2_ERR_UNSUPPORTED, "channels and the number of grid points must be multiples of 16");
+    if (C / heads > 128) return s2_fail(S2_ERR_UNSUPPORTED, "head dimensions above 128 are not supported");
+    if (!ws || reinterpret_cast<uintptr_t>(ws) % 256 != 0 || ws_bytes < layout(g, batch, C, heads).total * sizeof(float))
+        return s2_fail(S2_ERR_WORKSPACE, "workspace missing, not 256-byte aligned or smaller than s2_mha_workspace_bytes()");
+    return S2_OK;
+}
+
+void gemm(bool trans, int M, int N, int K, int batch, const float *W, const float *X, const float *bias, const float *R,
+          float *C, bool accumulate, hipStream_t st)
+{
+    const dim3 grid((N + kTN - 1) / kTN, (M + kTM - 1) / kTM, batch);
+    if (trans)
+        hipLaunchKernelGGL(mha_gemm<true>, grid, dim3(256), 0, st, M, N, K, W, X, bias, R, C, int(accumulate));
+    else
+        hipLaunchKernelGGL(mha_gemm<false>, grid, dim3(256), 0, st, M, N, K, W, X, bias, R, C, int(accumulate));
+}
+
+void wgrad(int M, int K, int N, int batch, const float *dY, const float *X, float *part, float *dW, hipStream_t st)
+{
+    hipLaunchKernelGGL(mha_wgrad_partial, dim3((K + kTN - 1) / kTN, (M + kTM - 1) / kTM, kSplits), dim3(256), 0, st, M, K, N,
+                       batch, kSplits, dY, X, part);
+    hipLaunchKernelGGL(mha_sum_partials, dim3((M * K + 255) / 256), dim3(256), 0, st, M * K, kSplits, part, dW);
+}
+
+}  // namespace
+
+extern "C" size_t s2_mha_workspace_bytes(const s2_grid_t *g, int batch, int channels, int heads)
+{
+    if (!g || batch < 1 || channels < 1 || heads < 1) return 0;
+    return layout(g, batch, channels, heads).total * sizeof(float);
+}
+
+extern "C" int s2_mha_fwd(const s2_grid_t *g, int batch, int channels, int heads, float eps, const float *x,
+                          const s2_mha_params_t *p, float *y, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    int rc = check(g, batch, channels, heads, workspace, workspace_bytes);
+    if (rc) return rc;
+    if (!x || !p || !y || !p->Wq || !p->Wk || !p->Wv || !p->Wo) return s2_fail(S2_ERR_INVALID_ARG, "NULL tensor or weight pointer");
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const int C = channels, N = g->nlat_in * g->nlon_in, d = C / heads;
+    float *ws = static_cast<float *>(workspace);
+    const Layout L = layout(g, batch, C, heads);
+    {
+        S2TraceScope tr("mha_instnorm_fwd", 0.0, st);
+        hipLaunchKernelGGL(mha_instnorm_fwd, dim3(batch * C), dim3(256), 0, st, C, N, eps, x, p->gamma, p->beta, p->pos,
+                           ws + L.mean, ws + L.rstd, ws + L.xn);
+    }
+    {
+        S2TraceScope tr("mha_gemm qkv", 0.0, st);
+        gemm(false, C, N, C, batch, p->Wq, ws + L.xn, p->bq, nullptr, ws + L.q, false, st);
+        gemm(false, C, N, C, batch, p->Wk, ws + L.xn, p->bk, nullptr, ws + L.k, false, st);
+        gemm(false, C, N, C, batch, p->Wv, ws + L.xn, p->bv, nullptr, ws + L.v, false, st);
+    }
+    rc = s2_nattn_fwd(g, batch, heads, d, d, S2_F32, 1.f / sqrtf(float(d)), ws + L.q, ws + L.k, ws + L.v, ws + L.a,
+                      ws + L.lse, hip_stream);
+    if (rc) return rc;
+    {
+        S2TraceScope tr("mha_gemm out", 0.0, st);
+        gemm(false, C, N, C, batch, p->Wo, ws + L.a, p->bo, x, y, false, st);
+    }
+    S2_HIP_CHECK(hipGetLastError());
+    return S2_OK;
+}
+
+extern "C" int s2_mha_bwd(const s2_grid_t *g, int batch, int channels, int heads, float eps, const float *x,
+                          const s2_mha_params_t *p, const float *dy, float *dx, const s2_mha_grads_t *grads,
+                          void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    (void)eps;      // the moments saved by the forward pass are reused
+    int rc = check(g, batch, channels, heads, workspace, workspace_bytes);
+    if (rc) return rc;
+    if (!x || !p || !dy || !dx || !grads || !p->Wq || !p->Wk || !p->Wv || !p->Wo)
+        return s2_fail(S2_ERR_INVALID_ARG, "NULL tensor or weight pointer");
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const int C = channels, N = g->nlat_in * g->nlon_in, d = C / heads;
+    float *ws = static_cast<float *>(workspace);
+    const Layout L = layout(g, batch, C, heads);
+    float *gWq = grads->Wq, *gWk = grads->Wk, *gWv = grads->Wv, *gWo = grads->Wo;
+    auto chan = [&](const float *u, bool with_xhat, float *dst) {
+        if (dst)
+            hipLaunchKernelGGL(mha_channel_sum, dim3(C), dim3(256), 0, st, batch, C, N, u, with_xhat ? x : nullptr,
+                               ws + L.mean, ws + L.rstd, dst);
+    };
+    {
+        // y = x + Wo a + bo
+        S2TraceScope tr("mha_bwd out-projection", 0.0, st);
+        if (gWo) wgrad(C, C, N, batch, dy, ws + L.a, ws + L.part, gWo, st);
+        chan(dy, false, grads->bo);
+        gemm(true, C, N, C, batch, p->Wo, dy, nullptr, nullptr, ws + L.da, false, st);
+    }
+    rc = s2_nattn_bwd(g, batch, heads, d, d, S2_F32, 1.f / sqrtf(float(d)), ws + L.q, ws + L.k, ws + L.v, ws + L.a,
+                      ws + L.lse, ws + L.da, ws + L.dq, ws + L.dk, ws + L.dv, ws + L.D,
+                      s2_nattn_bwd_workspace_bytes(g, batch, heads, d, d, S2_F32), hip_stream);
+    if (rc) return rc;
+    {
+        S2TraceScope tr("mha_bwd qkv-projections", 0.0, st);
+        const float *dts[3] = {ws + L.dq, ws + L.dk, ws + L.dv};
+        const float *Ws[3] = {p->Wq, p->Wk, p->Wv};
+        float *gWs[3] = {gWq, gWk, gWv};
+        float *gbs[3] = {grads->bq, grads->bk, grads->bv};
+        for (int i = 0; i < 3; ++i) {
+            if (gWs[i]) wgrad(C, C, N, batch, dts[i], ws + L.xn, ws + L.part, gWs[i], st);
+            chan(dts[i], false, gbs[i]);
+            gemm(true, C, N, C, batch, Ws[i], dts[i], nullptr, nullptr, ws + L.dxn, i > 0, st);
+        }
+    }
+    {
+        S2TraceScope tr("mha_bwd instnorm", 0.0, st);
+        if (grads->pos)
+            hipLaunchKernelGGL(mha_batch_sum, dim3(unsigned((size_t(C) * N + 255) / 256)), dim3(256), 0, st, batch,
+                               size_t(C) * N, ws + L.dxn, grads->pos);
+        chan(ws + L.dxn, true, grads->gamma);
+        chan(ws + L.dxn, false, grads->beta);
+        hipLaunchKernelGGL(mha_instnorm_bwd, dim3(batch * C), dim3(256), 0, st, C, N, x, p->gamma, ws + L.mean, ws + L.rstd,
+                           ws + L.dxn, dy, dx);
+    }
+    S2_HIP_CHECK(hipGetLastError());
+    return S2_OK;
+}

@@ -1,0 +1,132 @@
+"""GPU parity of the layers around the attention kernels (through the C ABI) against the float64 oracle:
+the multi-head attention sub-block (Sec. 3.4) and the DISCO convolution (App. B.3).
+
+Tolerance, float32: |x - ref| <= 1e-6 + 1e-5 |ref| + 2e-5 rms(ref) elementwise.  A result of these layers has gone
+through up to five chained float32 stages (moments, channel matrix, attention, channel matrix, residual) whose
+roundings add up.  The rms term is an empirical allowance for that (several times the largest excess observed, which
+every comparison prints), not a derived bound.  Parameter gradients are sums over every grid point of every batch
+element (10^3 .. 10^5 signed terms) and get the rounding of such a sum on top: 8 * 2^-24 * (sum of the absolute
+values of the terms, from the oracle's intermediates); this is what bounds the gradient of the key bias, which is
+zero identically (a constant added to every key shifts all logits of a query alike) while its terms are not.
+"""
+import json
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+import paper_2505_11157_amd as S
+
+pytestmark = pytest.mark.gpu
+_REPORT = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out", "parity_report.jsonl")
+RMS_TERM = 2e-5
+
+
+def close(x, ref, what, case, abs_sum=None):
+    x, ref = np.asarray(x, np.float64), np.asarray(ref, np.float64)
+    assert x.shape == ref.shape, (what, x.shape, ref.shape)
+    err = np.abs(x - ref)
+    rms = np.sqrt((ref ** 2).mean())
+    strict = 1e-6 + 1e-5 * np.abs(ref) + (8 * 2.0 ** -24 * abs_sum if abs_sum is not None else 0.0)
+    rec = dict(case=case, what=what, n=int(err.size), max_abs=float(err.max()), rms_ref=float(rms),
+               n_over_strict=int((err > strict).sum()), excess_over_strict_in_rms=float(((err - strict) / max(rms, 1e-30)).max()))
+    print("parity %-16s %-7s max|err| %.3e  rms(ref) %.3e  over strict %d/%d  (excess / rms %.2e)" % (
+        case, what, rec["max_abs"], rms, rec["n_over_strict"], rec["n"], max(rec["excess_over_strict_in_rms"], 0.0)), flush=True)
+    try:
+        with open(_REPORT, "a") as f:
+            f.write(json.dumps(rec) + "\n")
+    except OSError:
+        pass
+    assert np.isfinite(x).all(), what
+    tol = strict + RMS_TERM * rms
+    assert (err <= tol).all(), "%s %s: max err %.3e, max excess %.3e" % (case, what, err.max(), (err - tol).max())
+
+
+MHA_CASES = [
+    # (grid, batch, channels, heads): d = 16 runs the shape-agnostic attention kernels, d = 32 on 192 / 256
+    # longitudes the matrix-core and streaming ones; 48 channels leave the 128 x 128 tiles of the channel matrices ragged
+    (dict(grid_type=0, nlat_in=17, nlon_in=32, nlat_out=17, nlon_out=32, theta=0.5), 2, 32, 2),
+    (dict(grid_type=1, nlat_in=16, nlon_in=48, nlat_out=16, nlon_out=48, theta=0.4), 1, 48, 3),
+    (dict(grid_type=0, nlat_in=33, nlon_in=192, nlat_out=33, nlon_out=192, theta=0.3), 2, 64, 2),
+    (dict(grid_type=0, nlat_in=25, nlon_in=256, nlat_out=25, nlon_out=256, theta=0.25), 1, 160, 5),
+]
+
+
+@pytest.mark.parametrize("ci", range(len(MHA_CASES)))
+def test_mha_block(ci):
+    gd, B, C, heads = MHA_CASES[ci]
+    rng = np.random.default_rng(900 + ci)
+    shp = (B, C, gd["nlat_in"], gd["nlon_in"])
+    f32 = lambda a: np.asarray(a, np.float32)
+    x, dy = f32(rng.standard_normal(shp)), f32(rng.standard_normal(shp))
+    w = lambda: f32(rng.standard_normal((C, C)) / math.sqrt(C))
+    b = lambda: f32(0.3 * rng.standard_normal(C))
+    P = dict(gamma=f32(1 + 0.2 * rng.standard_normal(C)), beta=b(), pos=f32(0.5 * rng.standard_normal(shp[1:])),
+             Wq=w(), bq=b(), Wk=w(), bk=b(), Wv=w(), bv=b(), Wo=w(), bo=b())
+    g = S.s2_grid_init(gd["grid_type"], gd["nlat_in"], gd["nlon_in"], gd["nlat_out"], gd["nlon_out"], gd["theta"])
+    dev = torch.device("cuda:0")
+    T = lambda a: torch.from_numpy(a).to(dev).contiguous()
+    Pd = {k: T(v) for k, v in P.items()}
+    y, ws = S.s2_mha_fwd(g, T(x), Pd, heads)
+    dx, grads = S.s2_mha_bwd(g, T(x), Pd, heads, T(dy), ws)
+    torch.cuda.synchronize()
+    assert S.s2_grid_device_flags(g) == 0
+    a64 = {k: v.astype(np.float64) for k, v in P.items()}
+    args = (a64["pos"], a64["gamma"], a64["beta"], a64["Wq"], a64["bq"], a64["Wk"], a64["bk"], a64["Wv"], a64["bv"],
+            a64["Wo"], a64["bo"])
+    r_y, _ = O.mha_fwd(gd, heads, x.astype(np.float64), *args)
+    r = O.mha_bwd(gd, heads, x.astype(np.float64), *args, dy.astype(np.float64))
+    case = "mha%d" % ci
+    close(y.cpu().numpy(), r_y, "y", case)
+    close(dx.cpu().numpy(), r["dx"], "dx", case)
+    im = {k: np.abs(v) for k, v in r["intermediates"].items()}
+    ady = np.abs(dy.astype(np.float64))
+    ein = lambda u, v: np.einsum("bohw,bchw->oc", u, v)
+    abs_sums = dict(gamma=(im["dxn"] * im["xhat"]).sum((0, 2, 3)), beta=im["dxn"].sum((0, 2, 3)), pos=im["dxn"].sum(0),
+                    Wq=ein(im["dq"], im["xn"]), bq=im["dq"].sum((0, 2, 3)), Wk=ein(im["dk"], im["xn"]),
+                    bk=im["dk"].sum((0, 2, 3)), Wv=ein(im["dv"], im["xn"]), bv=im["dv"].sum((0, 2, 3)),
+                    Wo=ein(ady, im["a"]), bo=ady.sum((0, 2, 3)))
+    for k in S.MHA_FIELDS:
+        close(grads[k].cpu().numpy(), r["d" + k], "d" + k, case, abs_sums[k])
+    # again on the same workspace: bit-identical (no atomics, fixed summation orders)
+    y2, _ = S.s2_mha_fwd(g, T(x), Pd, heads, workspace=ws)
+    dx2, grads2 = S.s2_mha_bwd(g, T(x), Pd, heads, T(dy), ws)
+    assert torch.equal(y, y2) and torch.equal(dx, dx2) and all(torch.equal(grads[k], grads2[k]) for k in grads)
+
+
+def test_mha_optional_parameters_and_errors():
+    gd = MHA_CASES[0][0]
+    g = S.s2_grid_init(gd["grid_type"], gd["nlat_in"], gd["nlon_in"], gd["nlat_out"], gd["nlon_out"], gd["theta"])
+    rng = np.random.default_rng(5)
+    B, C, heads = 1, 32, 4
+    dev = torch.device("cuda:0")
+    f32 = lambda a: torch.from_numpy(np.asarray(a, np.float32)).to(dev)
+    x = f32(rng.standard_normal((B, C, 17, 32)))
+    dy = f32(rng.standard_normal((B, C, 17, 32)))
+    P = {k: f32(rng.standard_normal((C, C)) / math.sqrt(C)) for k in ("Wq", "Wk", "Wv", "Wo")}
+    y, ws = S.s2_mha_fwd(g, x, P, heads)                 # no norm affine, no embedding, no biases
+    dx, grads = S.s2_mha_bwd(g, x, P, heads, dy, ws)
+    torch.cuda.synchronize()
+    assert set(grads) == {"Wq", "Wk", "Wv", "Wo"}
+    z = np.zeros(C)
+    a = [p.cpu().numpy().astype(np.float64) for p in (P["Wq"], P["Wk"], P["Wv"], P["Wo"])]
+    args = (np.zeros((C, 17, 32)), np.ones(C), z, a[0], z, a[1], z, a[2], z, a[3], z)
+    r_y, _ = O.mha_fwd(gd, heads, x.cpu().numpy().astype(np.float64), *args)
+    r = O.mha_bwd(gd, heads, x.cpu().numpy().astype(np.float64), *args, dy.cpu().numpy().astype(np.float64))
+    close(y.cpu().numpy(), r_y, "y", "mha-bare")
+    close(dx.cpu().numpy(), r["dx"], "dx", "mha-bare")
+    close(grads["Wv"].cpu().numpy(), r["dWv"], "dWv", "mha-bare")
+    with pytest.raises(S.S2Error) as ei:
+        S.s2_mha_fwd(g, x, P, 5)                          # 32 channels do not split into 5 heads
+    assert ei.value.code == S.S2_ERR_INVALID_ARG
+    with pytest.raises(S.S2Error) as ei:
+        S.s2_mha_fwd(g, x, P, heads, workspace=torch.empty(1024, dtype=torch.uint8, device=dev))
+    assert ei.value.code == S.S2_ERR_WORKSPACE
+    g2 = S.s2_grid_init(0, 17, 32, 9, 16, 0.5)
+    with pytest.raises(S.S2Error) as ei:
+        S.s2_mha_fwd(g2, x, P, heads)
+    assert ei.value.code == S.S2_ERR_UNSUPPORTED
+    torch.cuda.synchronize()
