@@ -228,6 +228,31 @@ int s2_mha_bwd(const s2_grid_t *g, int batch, int channels, int heads, float eps
                void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * Discrete-continuous (DISCO) convolution on the disk tables of a grid handle (App. B.3, first equation):
+ *   z[b,c,k,h,w] = sum_{(h',w') in list(h)} psi_k[h,h',w'] x[b,c,h',(w' + w*pscale) mod nlon_in]
+ *   y[b,o,h,w]   = sum_{c,k} weight[o,c,k] z[b,c,k,h,w] + bias[o]
+ * with psi_k = hat_k(r) * omega[h'], r the geodesic distance of the input point from the output point and
+ * hat_k(r) = max(0, 1 - |r * nbasis / theta_cutoff - k|), k = 0 .. nbasis-1 (piecewise-linear, isotropic; the paper
+ * leaves the basis open).  s2_disco_init tabulates psi in float64 on the host for the handle's grids (equal grids or
+ * downsampling; upsampling handles: S2_ERR_UNSUPPORTED); nbasis in [1, 8].  The disco handle refers to the grid
+ * handle, which must outlive it; release with s2_disco_destroy.
+ * Layouts (contiguous float32, device): x [batch][cin][nlat_in][nlon_in], y, dy [batch][cout][nlat_out][nlon_out],
+ * weight [cout][cin][nbasis], bias [cout] (may be NULL).  s2_disco_bwd writes dx and, where the pointers are not
+ * NULL, dweight and dbias; it needs the workspace of the matching s2_disco_fwd call, untouched (z is kept there).
+ * cin*nbasis, cout and nlat_out*nlon_out must be multiples of 16 (else S2_ERR_UNSUPPORTED); batch*cin <= 65535.
+ * workspace: s2_disco_workspace_bytes(...) bytes, 256-byte aligned.  No atomics: results are bit-reproducible.
+ */
+typedef struct s2_disco s2_disco_t;
+int s2_disco_init(const s2_grid_t *g, int nbasis, s2_disco_t **out);
+void s2_disco_destroy(s2_disco_t *dc);
+size_t s2_disco_workspace_bytes(const s2_disco_t *dc, int batch, int cin, int cout);
+int s2_disco_fwd(const s2_disco_t *dc, int batch, int cin, int cout, const float *x, const float *weight,
+                 const float *bias, float *y, void *workspace, size_t workspace_bytes, void *hip_stream);
+int s2_disco_bwd(const s2_disco_t *dc, int batch, int cin, int cout, const float *x, const float *weight,
+                 const float *dy, float *dx, float *dweight, float *dbias, void *workspace, size_t workspace_bytes,
+                 void *hip_stream);
+
+/*
  * Per-launch timing for benchmarks (not part of the method).  While enabled, every kernel launch
  * of the attention calls is bracketed by HIP events on the launch stream.  s2_trace_get waits for
  * entry `index` and returns the kernel's name, its duration in ms and the number of (output, input)

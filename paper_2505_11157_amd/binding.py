@@ -82,6 +82,16 @@ def lib():
         L.s2_mha_fwd.restype = _i
         L.s2_mha_bwd.argtypes = [_vp, _i, _i, _i, ctypes.c_float, _vp, _vp, _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
         L.s2_mha_bwd.restype = _i
+        L.s2_disco_init.argtypes = [_vp, _i, ctypes.POINTER(_vp)]
+        L.s2_disco_init.restype = _i
+        L.s2_disco_destroy.argtypes = [_vp]
+        L.s2_disco_destroy.restype = None
+        L.s2_disco_workspace_bytes.argtypes = [_vp, _i, _i, _i]
+        L.s2_disco_workspace_bytes.restype = ctypes.c_size_t
+        L.s2_disco_fwd.argtypes = [_vp, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
+        L.s2_disco_fwd.restype = _i
+        L.s2_disco_bwd.argtypes = [_vp, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
+        L.s2_disco_bwd.restype = _i
         L.s2_attn_global_fwd_workspace_bytes.argtypes = [_vp, _i, _i, _i, _i]
         L.s2_attn_global_fwd_workspace_bytes.restype = ctypes.c_size_t
         L.s2_attn_global_bwd_workspace_bytes.argtypes = [_vp, _i, _i, _i, _i]
@@ -307,6 +317,59 @@ def s2_mha_bwd(g, x, params, heads, dy, workspace, eps=1e-5, want=MHA_FIELDS):
     _check(lib().s2_mha_bwd(g.handle, B, C, heads, float(eps), x.data_ptr(), ctypes.byref(st), dy.data_ptr(),
                             dx.data_ptr(), ctypes.byref(gs), workspace.data_ptr(), workspace.numel(), _stream()))
     return dx, grads
+
+
+class Disco:
+    """Owner of an s2_disco_t* (keeps its grid handle alive; released on garbage collection)."""
+
+    def __init__(self, handle, grid, nbasis):
+        self.handle, self.grid, self.nbasis = handle, grid, nbasis
+
+    def __del__(self):
+        if getattr(self, "handle", None) and _lib is not None:
+            _lib.s2_disco_destroy(self.handle)
+            self.handle = None
+
+
+def s2_disco_init(g, nbasis):
+    h = _vp()
+    _check(lib().s2_disco_init(g.handle, int(nbasis), ctypes.byref(h)))
+    return Disco(h, g, nbasis)
+
+
+def s2_disco_workspace_bytes(dc, batch, cin, cout):
+    return int(lib().s2_disco_workspace_bytes(dc.handle, batch, cin, cout))
+
+
+def s2_disco_fwd(dc, x, weight, bias=None, y=None, workspace=None):
+    """x [B, cin, nlat_in, nlon_in], weight [cout, cin, nbasis] -> y [B, cout, nlat_out, nlon_out], workspace."""
+    import torch
+    _dev(x, weight)
+    B, cin = x.shape[:2]
+    cout = weight.shape[0]
+    g = dc.grid
+    if x.shape[2:] != (g.nlat_in, g.nlon_in) or weight.shape != (cout, cin, dc.nbasis):
+        raise ValueError("tensor shapes do not match the handles")
+    y = torch.empty((B, cout, g.nlat_out, g.nlon_out), dtype=x.dtype, device=x.device) if y is None else y
+    if workspace is None:
+        workspace = torch.empty(max(s2_disco_workspace_bytes(dc, B, cin, cout), 1), dtype=torch.uint8, device=x.device)
+    _check(lib().s2_disco_fwd(dc.handle, B, cin, cout, x.data_ptr(), weight.data_ptr(),
+                              bias.data_ptr() if bias is not None else None, y.data_ptr(), workspace.data_ptr(),
+                              workspace.numel(), _stream()))
+    return y, workspace
+
+
+def s2_disco_bwd(dc, x, weight, dy, workspace, with_bias=True):
+    import torch
+    _dev(x, weight, dy, workspace)
+    B, cin = x.shape[:2]
+    cout = weight.shape[0]
+    dx, dw = torch.empty_like(x), torch.empty_like(weight)
+    db = torch.empty(cout, dtype=x.dtype, device=x.device) if with_bias else None
+    _check(lib().s2_disco_bwd(dc.handle, B, cin, cout, x.data_ptr(), weight.data_ptr(), dy.data_ptr(), dx.data_ptr(),
+                              dw.data_ptr(), db.data_ptr() if db is not None else None, workspace.data_ptr(),
+                              workspace.numel(), _stream()))
+    return dx, dw, db
 
 
 def s2_attn_global_fwd_workspace_bytes(g, batch, heads, d, dtype=S2_BF16):

@@ -1,0 +1,238 @@
+// Discrete-continuous (DISCO) convolution on the sphere (App. B.3, first equation), float32, on the same compact
+// form of the indicator as the attention kernels: for output latitude h the disk meets the input latitudes of its
+// band in arcs of consecutive longitude offsets, and the filter basis is tabulated per (h, band row, offset):
+//     z[b, c, k, h, w] = sum_{h', w'} psi_k[h, h', w'] x[b, c, h', (w' + w pscale) mod nlon_in]
+//     y[b, o, h, w]    = sum_{c, k} weight[o, c, k] z[b, c, k, h, w] + bias[o]
+// psi_k = hat_k(r) * omega[h'] with K piecewise-linear hats of the geodesic distance r (hat_k(r) = max(0,
+// 1 - |r K / theta_cutoff - k|): isotropic filters that vanish on the rim of the disk); the paper leaves the basis
+// open.  The contraction with psi is a gather per output point (lanes on consecutive longitudes, the basis values
+// of a (latitude, offset) are uniform over a wavefront); the channel mixing is a channel matrix on the fp32 matrix
+// cores.  Backward: dx is gathered through the transposed neighborhood (no atomics), dweight is the split-K
+// weight-gradient product summed in a fixed order.
+#include <cmath>
+#include <new>
+
+#include "s2_nattn_kernels.h"
+
+struct s2_disco {
+    const s2_grid_t *g;
+    int K;
+    float *dev_psi = nullptr;     // [entry][K], entry = poff[h * band_max + b] + offset
+    int *dev_poff = nullptr;      // [nlat_out * band_max]
+};
+
+namespace {
+
+constexpr int kMaxBasis = 8;
+
+__device__ __forceinline__ int wrapn(int x, int n)
+{
+    x = x < 0 ? x + n : x;
+    return x >= n ? x - n : x;
+}
+
+// z[bc][k][h][w]: one lane per output point, block -> (64 longitudes, latitude, bc)
+template <int KB>
+__global__ void __launch_bounds__(64)
+disco_z_fwd(S2DeviceTables t, const float *__restrict__ psi, const int *__restrict__ poff, int K,
+            const float *__restrict__ x, float *__restrict__ z)
+{
+    const int w = blockIdx.x * 64 + threadIdx.x, h = blockIdx.y, bc = blockIdx.z;
+    if (w >= t.nlon_out) return;
+    const size_t si = size_t(t.nlat_in) * t.nlon_in, so = size_t(t.nlat_out) * t.nlon_out;
+    float acc[KB];
+#pragma unroll
+    for (int k = 0; k < KB; ++k) acc[k] = 0.f;
+    const int nb = t.band_n[h], hp0 = t.band_lo[h];
+    for (int b = 0; b < nb; ++b) {
+        const int c = t.cnt[h * t.band_max + b];
+        const int first = w * t.pscale + (c == t.nlon_in ? 0 : -((c - 1) >> 1));
+        const float *xr = x + size_t(bc) * si + size_t(hp0 + b) * t.nlon_in;
+        const float *pr = psi + size_t(poff[h * t.band_max + b]) * K;
+        int col = wrapn(first, t.nlon_in);
+        for (int tt = 0; tt < c; ++tt) {
+            const float xv = xr[col];
+#pragma unroll
+            for (int k = 0; k < KB; ++k)
+                if (k < K) acc[k] = fmaf(pr[tt * K + k], xv, acc[k]);
+            col = col + 1 == t.nlon_in ? 0 : col + 1;
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < KB; ++k)
+        if (k < K) z[(size_t(bc) * K + k) * so + size_t(h) * t.nlon_out + w] = acc[k];
+}
+
+// dx[bc][h'][w_in] = sum over the output points (h, w) whose disk holds the input point, and over k, of
+// psi_k[h, h', w_in - w pscale] dz[bc][k][h][w]: one lane per input point
+template <int KB>
+__global__ void __launch_bounds__(64)
+disco_dx(S2DeviceTables t, const float *__restrict__ psi, const int *__restrict__ poff, int K,
+         const float *__restrict__ dz, float *__restrict__ dx)
+{
+    const int win = blockIdx.x * 64 + threadIdx.x, hp = blockIdx.y, bc = blockIdx.z;
+    if (win >= t.nlon_in) return;
+    const size_t si = size_t(t.nlat_in) * t.nlon_in, so = size_t(t.nlat_out) * t.nlon_out;
+    float acc = 0.f;
+    const int ps = t.pscale;
+    const int nb = t.omega_rel[hp] > 0.f ? t.tband_n[hp] : 0;       // a latitude of weight zero receives nothing
+    const int h0 = t.tband_lo[hp];
+    for (int b = 0; b < nb; ++b) {
+        const int h = h0 + b;
+        const int bf = hp - t.band_lo[h];                            // row of h' in the band of h
+        const int c = t.cnt[h * t.band_max + bf];
+        const int lo = c == t.nlon_in ? 0 : -((c - 1) >> 1);
+        const float *pr = psi + size_t(poff[h * t.band_max + bf]) * K;
+        const float *dr = dz + size_t(bc) * K * so + size_t(h) * t.nlon_out;
+        // offset tt of the arc of output w is input column w ps + lo + tt: w ps = win - lo - tt (mod nlon_in)
+        int xw = wrapn(win - lo, t.nlon_in);
+        for (int tt = 0; tt < c; ++tt) {
+            if (ps == 1 || xw % ps == 0) {
+                const int w = xw / ps;
+#pragma unroll
+                for (int k = 0; k < KB; ++k)
+                    if (k < K) acc = fmaf(pr[tt * K + k], dr[size_t(k) * so + w], acc);
+            }
+            xw = xw == 0 ? t.nlon_in - 1 : xw - 1;
+        }
+    }
+    dx[size_t(bc) * si + size_t(hp) * t.nlon_in + win] = acc;
+}
+
+int check(const s2_disco_t *dc, int batch, int cin, int cout, const void *ws, size_t ws_bytes)
+{
+    if (!dc) return s2_fail(S2_ERR_INVALID_ARG, "disco handle is NULL");
+    if (batch < 1 || cin < 1 || cout < 1) return s2_fail(S2_ERR_INVALID_ARG, "batch and channel counts must be >= 1");
+    const size_t n_out = size_t(dc->g->nlat_out) * dc->g->nlon_out;
+    if ((cin * dc->K) % 16 != 0 || cout % 16 != 0 || n_out % 16 != 0)
+        return s2_fail(S2_ERR_UNSUPPORTED, "channels_in * nbasis, channels_out and the number of output points must be multiples of 16");
+    if (long(batch) * cin > 65535) return s2_fail(S2_ERR_INVALID_ARG, "batch * channels_in too large");
+    if (!ws || reinterpret_cast<uintptr_t>(ws) % 256 != 0 || ws_bytes < s2_disco_workspace_bytes(dc, batch, cin, cout))
+        return s2_fail(S2_ERR_WORKSPACE, "workspace missing, not 256-byte aligned or smaller than s2_disco_workspace_bytes()");
+    return S2_OK;
+}
+
+template <class F>
+void by_basis(int K, F f)
+{
+    if (K <= 2) f(std::integral_constant<int, 2>());
+    else if (K <= 4) f(std::integral_constant<int, 4>());
+    else f(std::integral_constant<int, kMaxBasis>());
+}
+
+}  // namespace
+
+extern "C" int s2_disco_init(const s2_grid_t *g, int nbasis, s2_disco_t **out)
+{
+    if (!out) return s2_fail(S2_ERR_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    if (!g) return s2_fail(S2_ERR_INVALID_ARG, "grid is NULL");
+    if (nbasis < 1 || nbasis > kMaxBasis) return s2_fail(S2_ERR_INVALID_ARG, "nbasis must lie in [1, 8]");
+    if (g->upscale > 1) return s2_fail(S2_ERR_UNSUPPORTED, "the DISCO convolution covers equal grids and downsampling");
+    s2_disco *dc = new (std::nothrow) s2_disco();
+    if (!dc) return s2_fail(S2_ERR_ALLOC, "out of host memory");
+    dc->g = g;
+    dc->K = nbasis;
+    // basis values along the arcs of the kernels' tables (zero-weight latitudes are not in them)
+    const double kPi = 3.141592653589793238462643383279502884, dr = g->theta / nbasis;
+    std::vector<int> poff(size_t(g->nlat_out) * g->band_max, 0);
+    std::vector<float> psi;
+    for (int h = 0; h < g->nlat_out; ++h)
+        for (int b = 0; b < g->band_n[h]; ++b) {
+            const int hp = g->band_lo[h] + b, c = g->cnt[size_t(h) * g->band_max + b];
+            const int lo = c == g->nlon_in ? 0 : -((c - 1) / 2);
+            poff[size_t(h) * g->band_max + b] = int(psi.size() / nbasis);
+            for (int tt = 0; tt < c; ++tt) {
+                const int wp = ((lo + tt) % g->nlon_in + g->nlon_in) % g->nlon_in;
+                const double r = s2_great_circle(g->colat_out[h], g->colat_in[hp], 2.0 * kPi * wp / g->nlon_in);
+                for (int k = 0; k < nbasis; ++k)
+                    psi.push_back(float(std::max(0.0, 1.0 - std::fabs(r / dr - k)) * g->omega_in[hp]));
+            }
+        }
+    if (g->on_device) {
+        if (hipMalloc(&dc->dev_psi, std::max<size_t>(psi.size(), 1) * sizeof(float)) != hipSuccess ||
+            hipMalloc(&dc->dev_poff, poff.size() * sizeof(int)) != hipSuccess) {
+            (void)hipGetLastError();
+            s2_disco_destroy(dc);
+            return s2_fail(S2_ERR_ALLOC, "hipMalloc of the basis tables failed");
+        }
+        if (hipMemcpy(dc->dev_psi, psi.data(), psi.size() * sizeof(float), hipMemcpyHostToDevice) != hipSuccess ||
+            hipMemcpy(dc->dev_poff, poff.data(), poff.size() * sizeof(int), hipMemcpyHostToDevice) != hipSuccess) {
+            (void)hipGetLastError();
+            s2_disco_destroy(dc);
+            return s2_fail(S2_ERR_DEVICE, "upload of the basis tables failed");
+        }
+    }
+    *out = dc;
+    return S2_OK;
+}
+
+extern "C" void s2_disco_destroy(s2_disco_t *dc)
+{
+    if (!dc) return;
+    if (dc->dev_psi) (void)hipFree(dc->dev_psi);
+    if (dc->dev_poff) (void)hipFree(dc->dev_poff);
+    delete dc;
+}
+
+extern "C" size_t s2_disco_workspace_bytes(const s2_disco_t *dc, int batch, int cin, int cout)
+{
+    if (!dc || batch < 1 || cin < 1 || cout < 1) return 0;
+    const size_t n_out = size_t(dc->g->nlat_out) * dc->g->nlon_out;
+    auto up = [](size_t x) { return (x + 63) / 64 * 64; };
+    // z, dz: [batch][cin * K][n_out]; partial sums of the weight gradient
+    return (2 * up(size_t(batch) * cin * dc->K * n_out) + up(s2_wgrad_part_floats(cout, cin * dc->K))) * sizeof(float);
+}
+
+extern "C" int s2_disco_fwd(const s2_disco_t *dc, int batch, int cin, int cout, const float *x, const float *weight,
+                            const float *bias, float *y, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    int rc = check(dc, batch, cin, cout, workspace, workspace_bytes);
+    if (rc) return rc;
+    if (!x || !weight || !y) return s2_fail(S2_ERR_INVALID_ARG, "NULL tensor pointer");
+    const s2_grid_t *g = dc->g;
+    if (!g->on_device) return s2_fail(S2_ERR_DEVICE, "grid handle has no device tables (no HIP device at init)");
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    float *z = static_cast<float *>(workspace);
+    const int n_out = g->nlat_out * g->nlon_out, K = dc->K;
+    {
+        S2TraceScope tr("disco_z_fwd", 0.0, st);
+        const dim3 grid((g->nlon_out + 63) / 64, g->nlat_out, batch * cin);
+        by_basis(K, [&](auto KB) {
+            hipLaunchKernelGGL((disco_z_fwd<decltype(KB)::value>), grid, dim3(64), 0, st, g->dt, dc->dev_psi, dc->dev_poff, K, x, z);
+        });
+    }
+    S2TraceScope tr("disco_mix", 0.0, st);
+    s2_gemm_f32(false, cout, n_out, cin * K, batch, weight, z, bias, nullptr, y, false, st);
+    S2_HIP_CHECK(hipGetLastError());
+    return S2_OK;
+}
+
+extern "C" int s2_disco_bwd(const s2_disco_t *dc, int batch, int cin, int cout, const float *x, const float *weight,
+                            const float *dy, float *dx, float *dweight, float *dbias, void *workspace,
+                            size_t workspace_bytes, void *hip_stream)
+{
+    (void)x;       // z = psi * x was kept in the workspace by the forward pass
+    int rc = check(dc, batch, cin, cout, workspace, workspace_bytes);
+    if (rc) return rc;
+    if (!weight || !dy || !dx) return s2_fail(S2_ERR_INVALID_ARG, "NULL tensor pointer");
+    const s2_grid_t *g = dc->g;
+    if (!g->on_device) return s2_fail(S2_ERR_DEVICE, "grid handle has no device tables (no HIP device at init)");
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const int n_out = g->nlat_out * g->nlon_out, K = dc->K;
+    auto up = [](size_t v) { return (v + 63) / 64 * 64; };
+    float *z = static_cast<float *>(workspace), *dz = z + up(size_t(batch) * cin * K * n_out), *part = dz + up(size_t(batch) * cin * K * n_out);
+    {
+        S2TraceScope tr("disco_bwd mix", 0.0, st);
+        if (dweight) s2_wgrad_f32(cout, cin * K, n_out, batch, dy, z, part, dweight, st);
+        if (dbias) s2_channel_sum_f32(batch, cout, n_out, dy, dbias, st);
+        s2_gemm_f32(true, cin * K, n_out, cout, batch, weight, dy, nullptr, nullptr, dz, false, st);
+    }
+    S2TraceScope tr("disco_dx", 0.0, st);
+    const dim3 grid((g->nlon_in + 63) / 64, g->nlat_in, batch * cin);
+    by_basis(K, [&](auto KB) {
+        hipLaunchKernelGGL((disco_dx<decltype(KB)::value>), grid, dim3(64), 0, st, g->dt, dc->dev_psi, dc->dev_poff, K, dz, dx);
+    });
+    S2_HIP_CHECK(hipGetLastError());
+    return S2_OK;
+}

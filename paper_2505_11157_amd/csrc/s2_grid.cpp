@@ -570,6 +570,8 @@ extern "C" int s2_grid_init(int grid_type, int nlat_in, int nlon_in, int nlat_ou
     return S2_OK;
 }
 
+double s2_great_circle(double colat_a, double colat_b, double dphi) { return great_circle(colat_a, colat_b, dphi); }
+
 extern "C" void s2_grid_destroy(s2_grid_t *g)
 {
     if (!g) return;

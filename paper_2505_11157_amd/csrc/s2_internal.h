@@ -123,6 +123,21 @@ int s2_nattn_bwd_tiled_configure();
 int s2_nattn_stream_configure();
 int s2_nattn_mfma_configure();
 
+// great-circle angle between two points given by their colatitudes and their difference in longitude (float64)
+double s2_great_circle(double colat_a, double colat_b, double dphi);
+
+// Channel matrices on the fp32 matrix cores (s2_mha.hip), all tensors [batch][channels][N] contiguous:
+//   s2_gemm_f32:  C[b][m][n] (+)= sum_k A(m, k) X[b][k][n] + bias[m] + R[b][m][n],  A = W (M x K) or W^T (W is K x M)
+//   s2_wgrad_f32: dW[m][k] = sum_{b, n} dY[b][m][n] X[b][k][n]  (partial sums in `part`, s2_wgrad_part_floats(M, K)
+//                 floats, added in a fixed order)
+//   s2_channel_sum_f32: out[c] = sum_{b, n} u[b][c][n]
+// M, K multiples of 16 and N a multiple of 16.
+void s2_gemm_f32(bool trans_a, int M, int N, int K, int batch, const float *W, const float *X, const float *bias,
+                 const float *R, float *C, bool accumulate, hipStream_t st);
+size_t s2_wgrad_part_floats(int M, int K);
+void s2_wgrad_f32(int M, int K, int N, int batch, const float *dY, const float *X, float *part, float *dW, hipStream_t st);
+void s2_channel_sum_f32(int batch, int C, int N, const float *u, float *out, hipStream_t st);
+
 void s2_set_error(const std::string &msg);
 int s2_fail(int code, const std::string &msg);
 

@@ -383,6 +383,22 @@ void wgrad(int M, int K, int N, int batch, const float *dY, const float *X, floa
 
 }  // namespace
 
+void s2_gemm_f32(bool trans_a, int M, int N, int K, int batch, const float *W, const float *X, const float *bias,
+                 const float *R, float *C, bool accumulate, hipStream_t st)
+{
+    gemm(trans_a, M, N, K, batch, W, X, bias, R, C, accumulate, st);
+}
+size_t s2_wgrad_part_floats(int M, int K) { return size_t(kSplits) * M * K; }
+void s2_wgrad_f32(int M, int K, int N, int batch, const float *dY, const float *X, float *part, float *dW, hipStream_t st)
+{
+    wgrad(M, K, N, batch, dY, X, part, dW, st);
+}
+void s2_channel_sum_f32(int batch, int C, int N, const float *u, float *out, hipStream_t st)
+{
+    hipLaunchKernelGGL(mha_channel_sum, dim3(C), dim3(256), 0, st, batch, C, N, u, static_cast<const float *>(nullptr),
+                       static_cast<const float *>(nullptr), static_cast<const float *>(nullptr), out);
+}
+
 extern "C" size_t s2_mha_workspace_bytes(const s2_grid_t *g, int batch, int channels, int heads)
 {
     if (!g || batch < 1 || channels < 1 || heads < 1) return 0;

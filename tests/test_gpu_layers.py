@@ -130,3 +130,59 @@ def test_mha_optional_parameters_and_errors():
         S.s2_mha_fwd(g2, x, P, heads)
     assert ei.value.code == S.S2_ERR_UNSUPPORTED
     torch.cuda.synchronize()
+
+
+DISCO_CASES = [
+    # (grid, batch, channels in, basis functions, channels out)
+    (dict(grid_type=0, nlat_in=17, nlon_in=32, nlat_out=17, nlon_out=32, theta=0.5), 2, 8, 4, 16),
+    (dict(grid_type=0, nlat_in=33, nlon_in=64, nlat_out=17, nlon_out=32, theta=0.4), 1, 16, 2, 32),
+    (dict(grid_type=2, nlat_in=16, nlon_in=32, nlat_out=16, nlon_out=32, theta=0.45), 1, 4, 4, 16),
+    (dict(grid_type=1, nlat_in=24, nlon_in=48, nlat_out=24, nlon_out=48, theta=0.35), 2, 2, 8, 48),
+    (dict(grid_type=0, nlat_in=9, nlon_in=80, nlat_out=9, nlon_out=16, theta=0.6), 1, 16, 1, 16),     # pscale 5
+]
+
+
+@pytest.mark.parametrize("ci", range(len(DISCO_CASES)))
+def test_disco_convolution(ci):
+    gd, B, cin, K, cout = DISCO_CASES[ci]
+    rng = np.random.default_rng(950 + ci)
+    f32 = lambda a: np.asarray(a, np.float32)
+    x = f32(rng.standard_normal((B, cin, gd["nlat_in"], gd["nlon_in"])))
+    dy = f32(rng.standard_normal((B, cout, gd["nlat_out"], gd["nlon_out"])))
+    weight, bias = f32(rng.standard_normal((cout, cin, K))), f32(rng.standard_normal(cout))
+    g = S.s2_grid_init(gd["grid_type"], gd["nlat_in"], gd["nlon_in"], gd["nlat_out"], gd["nlon_out"], gd["theta"])
+    dc = S.s2_disco_init(g, K)
+    dev = torch.device("cuda:0")
+    T = lambda a: torch.from_numpy(a).to(dev).contiguous()
+    y, ws = S.s2_disco_fwd(dc, T(x), T(weight), T(bias))
+    dx, dw, db = S.s2_disco_bwd(dc, T(x), T(weight), T(dy), ws)
+    torch.cuda.synchronize()
+    d64 = lambda a: a.astype(np.float64)
+    r_y, r_z = O.disco_fwd(gd, K, d64(x), d64(weight), d64(bias))
+    r_dx, r_dw, r_db = O.disco_bwd(gd, K, d64(x), d64(weight), d64(bias), d64(dy))
+    case = "disco%d" % ci
+    close(y.cpu().numpy(), r_y, "y", case)
+    close(dx.cpu().numpy(), r_dx, "dx", case)
+    close(dw.cpu().numpy(), r_dw, "dweight", case, np.einsum("bohw,bckhw->ock", np.abs(d64(dy)), np.abs(r_z)))
+    close(db.cpu().numpy(), r_db, "dbias", case, np.abs(d64(dy)).sum((0, 2, 3)))
+    y2, _ = S.s2_disco_fwd(dc, T(x), T(weight), T(bias), workspace=ws)
+    dx2, dw2, db2 = S.s2_disco_bwd(dc, T(x), T(weight), T(dy), ws)
+    assert torch.equal(y, y2) and torch.equal(dx, dx2) and torch.equal(dw, dw2) and torch.equal(db, db2)
+
+
+def test_disco_errors():
+    g = S.s2_grid_init(0, 9, 16, 17, 32, 0.5)         # upsampling handle
+    with pytest.raises(S.S2Error) as ei:
+        S.s2_disco_init(g, 3)
+    assert ei.value.code == S.S2_ERR_UNSUPPORTED
+    g = S.s2_grid_init(0, 17, 32, 17, 32, 0.5)
+    with pytest.raises(S.S2Error) as ei:
+        S.s2_disco_init(g, 9)
+    assert ei.value.code == S.S2_ERR_INVALID_ARG
+    dc = S.s2_disco_init(g, 3)
+    dev = torch.device("cuda:0")
+    x = torch.zeros((1, 5, 17, 32), device=dev)
+    with pytest.raises(S.S2Error) as ei:
+        S.s2_disco_fwd(dc, x, torch.zeros((16, 5, 3), device=dev))       # 5 * 3 is not a multiple of 16
+    assert ei.value.code == S.S2_ERR_UNSUPPORTED
+    torch.cuda.synchronize()
