@@ -226,10 +226,13 @@ int s2o_indicator_point(int grid_type, int nlat_in, int nlon_in, int nlat_out, i
 /* ------------------------------------------------ neighborhood attention -- */
 
 typedef struct {
-    int brute;              /* 1: dense [N_out][N_in] mask from per-pair distances */
+    int brute;              /* 1: dense [N_out][N_in] mask from per-pair distances; 2: per-pair distances evaluated
+                               on the fly, nothing stored (any grid size) */
     int nlat_in, nlon_in, nlat_out, nlon_out, pscale;
     uint8_t *m;
     double *logw;           /* ln omega per input latitude */
+    double *ci, *co;        /* colatitudes of the input and output grids (brute == 2) */
+    double theta;
 } s2o_ctx;
 
 static int ctx_init(s2o_ctx *C, int grid_type, int nlat_in, int nlon_in, int nlat_out, int nlon_out,
@@ -246,6 +249,16 @@ static int ctx_init(s2o_ctx *C, int grid_type, int nlat_in, int nlon_in, int nla
     if (s2o_grid(grid_type, nlat_in, ci, wi)) { free(ci); free(wi); return -1; }
     C->logw = malloc(sizeof(double) * nlat_in);
     for (int hp = 0; hp < nlat_in; ++hp) C->logw[hp] = log(wi[hp] * 2.0 * S2O_PI / (double)nlon_in);
+    C->theta = theta;
+    if (brute == 2) {
+        /* eq. (5) per pair at the moment it is asked for: keeps the colatitudes, stores no mask */
+        double *wo = malloc(sizeof(double) * nlat_out);
+        C->ci = ci;
+        C->co = malloc(sizeof(double) * nlat_out);
+        int rc2 = s2o_grid(grid_type, nlat_out, C->co, wo);
+        free(wi); free(wo);
+        return rc2;
+    }
     free(ci); free(wi);
     int rc = 0;
     if (brute) {
@@ -261,11 +274,19 @@ static int ctx_init(s2o_ctx *C, int grid_type, int nlat_in, int nlon_in, int nla
     return rc;
 }
 
-static void ctx_free(s2o_ctx *C) { free(C->m); free(C->logw); }
+static void ctx_free(s2o_ctx *C) { free(C->m); free(C->logw); free(C->ci); free(C->co); }
 
 /* Is input point (hp, win) [absolute longitude index] in the disk of output (h, w)? */
 static inline int member(const s2o_ctx *C, int h, int w, int hp, int win)
 {
+    if (C->brute == 2) {
+        /* the distance is at least the difference of the colatitudes (the two meridian arcs to the pole and the
+         * geodesic form a spherical triangle), so most pairs are decided without the trigonometry */
+        if (fabs(C->co[h] - C->ci[hp]) > C->theta + 1e-6) return 0;
+        double dist = s2o_geodesic(C->co[h], 2.0 * S2O_PI * w / (double)C->nlon_out,
+                                   C->ci[hp], 2.0 * S2O_PI * win / (double)C->nlon_in);
+        return dist <= C->theta + S2O_TIE_TOL;
+    }
     if (C->brute)
         return C->m[((size_t)h * C->nlon_out + w) * ((size_t)C->nlat_in * C->nlon_in) + (size_t)hp * C->nlon_in + win];
     int wp = (win - w * C->pscale) % C->nlon_in;

@@ -110,6 +110,8 @@ def _grid_args(g):
 
 def nattn_fwd(g, q, k, v, scale, brute=False):
     """g: dict(grid_type, nlat_in, nlon_in, nlat_out, nlon_out, theta).
+    brute: False = shift-invariant indicator of App. B.3; True (1) = eq. (5) per (output, input) pair, mask stored;
+    2 = eq. (5) per pair evaluated on the fly (no N_out * N_in bytes: any grid size).
     q [nbh,d,Ho,Wo], k [nbh,d,Hi,Wi], v [nbh,e,Hi,Wi] -> out [nbh,e,Ho,Wo], lse [nbh,Ho,Wo]."""
     q, qp = _d(q); k, kp = _d(k); v, vp = _d(v)
     nbh, d = q.shape[0], q.shape[1]
@@ -118,7 +120,7 @@ def nattn_fwd(g, q, k, v, scale, brute=False):
     assert v.shape == (nbh, e, g["nlat_in"], g["nlon_in"])
     out = np.empty((nbh, e, g["nlat_out"], g["nlon_out"]), np.float64)
     lse = np.empty((nbh, g["nlat_out"], g["nlon_out"]), np.float64)
-    rc = _load().s2o_nattn_fwd(*_grid_args(g), int(bool(brute)), nbh, d, e, ctypes.c_double(scale),
+    rc = _load().s2o_nattn_fwd(*_grid_args(g), int(brute), nbh, d, e, ctypes.c_double(scale),
                                qp, kp, vp, out.ctypes.data_as(_dp), lse.ctypes.data_as(_dp))
     if rc:
         raise ValueError("s2o_nattn_fwd failed (%d)" % rc)
@@ -132,7 +134,7 @@ def nattn_bwd(g, q, k, v, dout, scale, brute=False):
     e = v.shape[1]
     assert dout.shape == (nbh, e, g["nlat_out"], g["nlon_out"])
     dq = np.empty_like(q); dk = np.empty_like(k); dv = np.empty_like(v)
-    rc = _load().s2o_nattn_bwd(*_grid_args(g), int(bool(brute)), nbh, d, e, ctypes.c_double(scale),
+    rc = _load().s2o_nattn_bwd(*_grid_args(g), int(brute), nbh, d, e, ctypes.c_double(scale),
                                qp, kp, vp, gp, dq.ctypes.data_as(_dp), dk.ctypes.data_as(_dp),
                                dv.ctypes.data_as(_dp))
     if rc:
@@ -148,7 +150,7 @@ def nattn_cond(g, q, k, v, dout, scale, brute=False):
     assert dout.shape == (nbh, e, g["nlat_out"], g["nlon_out"])
     c_out = np.empty_like(dout); c_lse = np.empty((nbh, g["nlat_out"], g["nlon_out"]), np.float64)
     c_dq = np.empty_like(q); c_dk = np.empty_like(k); c_dv = np.empty_like(v)
-    rc = _load().s2o_nattn_cond(*_grid_args(g), int(bool(brute)), nbh, d, e, ctypes.c_double(scale),
+    rc = _load().s2o_nattn_cond(*_grid_args(g), int(brute), nbh, d, e, ctypes.c_double(scale),
                                 qp, kp, vp, gp, c_out.ctypes.data_as(_dp), c_lse.ctypes.data_as(_dp),
                                 c_dq.ctypes.data_as(_dp), c_dk.ctypes.data_as(_dp), c_dv.ctypes.data_as(_dp))
     if rc:

@@ -77,7 +77,11 @@ def run_case(c, arrs, slices, C=0.0, case=""):
     for s in slices:
         sl = slice(s, s + 1)
         a64 = [a[sl].astype(np.float64) for a in arrs]
-        brute = gd["nlon_in"] % gd["nlon_out"] != 0      # upsampling: the oracle's per-pair form of eq. (5)
+        # upsampling: the oracle's per-pair form of eq. (5), evaluated on the fly where the N_out x N_in mask would
+        # not fit
+        brute = 0 if gd["nlon_in"] % gd["nlon_out"] == 0 else 1
+        if brute and gd["nlat_out"] * gd["nlon_out"] * gd["nlat_in"] * gd["nlon_in"] > 1 << 28:
+            brute = 2
         r_out, r_lse = O.nattn_fwd(gd, a64[0], a64[1], a64[2], scale, brute=brute)
         r_dq, r_dk, r_dv = O.nattn_bwd(gd, *a64, scale, brute=brute)
         c_out, c_lse, c_dq, c_dk, c_dv = O.nattn_cond(gd, *a64, scale, brute=brute)
@@ -479,6 +483,13 @@ def test_random_tuned_upsampling(seed):
     c, arrs = make_inputs(c, seed=400 + seed)
     nbh = c["batch"] * c["heads"]
     run_case(c, arrs, [int(rng.integers(0, nbh))], case="tuned-up%d" % seed)
+
+
+def test_upsampling_full_size_parity():
+    # 129x256 -> 257x512 (the mirror image of workload 4), all 8 slices on the GPU, two of them against the oracle's
+    # per-pair form of eq. (5) evaluated on the fly
+    c, arrs = make_inputs(6)
+    run_case(c, arrs, [0, 5], case="cfg6")
 
 
 def test_upsampling_full_size_invariants():

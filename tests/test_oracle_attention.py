@@ -246,3 +246,17 @@ def test_rounding_sensitivities_vs_dense_numpy(ci):
         dq, dk, dv = O.nattn_bwd(g, q, k, v, dout, scale, brute=brute)
         for cnd, val in zip(got, (out, np.ones_like(lse), dq, dk, dv)):
             assert (cnd >= np.abs(val) * (1 - 1e-12)).all()
+
+
+@pytest.mark.parametrize("ci", [1, 3, 5, 7])
+def test_on_the_fly_pair_form_equals_stored_mask_form(ci):
+    # brute = 2 evaluates eq. (5) per pair when asked (no N_out x N_in mask, so it runs at any grid size); it must
+    # give the very same numbers as the stored-mask form, which the dense torch pins above cover
+    c = SMALL[ci]
+    g = grid_dict(c)
+    q, k, v, dout = _inputs(c, 60 + ci)
+    scale = 1 / math.sqrt(c["d"])
+    a = O.nattn_fwd(g, q, k, v, scale, brute=1) + O.nattn_bwd(g, q, k, v, dout, scale, brute=1)
+    b = O.nattn_fwd(g, q, k, v, scale, brute=2) + O.nattn_bwd(g, q, k, v, dout, scale, brute=2)
+    for x, y in zip(a, b):
+        assert np.array_equal(x, y)
