@@ -564,6 +564,33 @@ extern "C" int s2_grid_init(int grid_type, int nlat_in, int nlon_in, int nlat_ou
     stream_plan(nlat_in, g->tband_lo, g->tband_n, g->tcnt, g->tband_max, g->dt.tst_lo, g->dt.tst_hi, g->dt.tst_nw,
                 g->tst_cum);
 
+    // light range for the bf16 band-tile kernels: the latitudes of the last class must be one contiguous range with
+    // odd arcs of at most 57 offsets (a 128-column stage then holds the window of 64 owners on every band row)
+    auto light_range = [](int n_rows, const std::vector<int> &n, const std::vector<int> &tab, int bmax, int &lo, int &hi) {
+        lo = hi = 0;
+        int first = -1, last = -1, count = 0;
+        for (int r = 0; r < n_rows; ++r) {
+            long work = 0;
+            for (int b = 0; b < n[r]; ++b) work += tab[size_t(r) * bmax + b];
+            if (work > T) continue;
+            if (first < 0) first = r;
+            last = r;
+            ++count;
+        }
+        if (count == 0 || last - first + 1 != count) return;
+        for (int r = first; r <= last; ++r) {
+            if (n[r] < 1) return;
+            for (int b = 0; b < n[r]; ++b) {
+                const int c = tab[size_t(r) * bmax + b];
+                if (c < 1 || c > 57 || c % 2 == 0) return;
+            }
+        }
+        lo = first;
+        hi = last + 1;
+    };
+    light_range(nlat_out, g->band_n, g->cnt, g->band_max, g->dt.bl_lo, g->dt.bl_hi);
+    light_range(nlat_in, g->tband_n, g->tcnt, g->tband_max, g->dt.tbl_lo, g->dt.tbl_hi);
+
     int rc = upload_tables(g);
     if (rc != S2_OK) { delete g; return rc; }
     *out_grid = g;

@@ -40,6 +40,10 @@ struct S2DeviceTables {
     // tst_*: the same for input latitudes and the transposed bands.
     int st_lo, st_hi, st_nw;
     int tst_lo, tst_hi, tst_nw;
+    // bf16 band-tile kernels, light variant: contiguous range [bl_lo, bl_hi) of output latitudes of the last class whose
+    // arcs are all odd and at most 57 offsets long (0, 0 if the light latitudes do not have that structure);
+    // tbl_*: the same for input latitudes and the transposed bands.
+    int bl_lo, bl_hi, tbl_lo, tbl_hi;
     unsigned *dev_flags;      // one word in device memory: bit 0 = a bounded wait inside a kernel ran out
     const int *st_cum;        // [st_hi - st_lo + 1]   running cost of the light latitudes (for equal-work segments)
     const int *tst_cum;       // [tst_hi - tst_lo + 1]

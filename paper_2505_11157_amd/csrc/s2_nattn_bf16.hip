@@ -612,6 +612,492 @@ bool s2_nattn_bf16_supported(const S2DeviceTables &t, int d, int e)
            t.nlon_in % 64 == 0 && !s2_debug_flag(S2_DEBUG_NO_MFMA);
 }
 
+namespace {
+
+// ===================================================================================================================
+// Light latitudes (short arcs: at most 57 offsets on every band row, one contiguous range of latitudes).  With 256
+// longitudes of ONE latitude per workgroup a 64-column stage gives a wavefront one or two tiles of work per barrier,
+// and the windows of the nine band rows are fetched again for every latitude.  Here a workgroup owns 64 longitudes of
+// FOUR consecutive latitudes (one per wavefront): an input row is staged once, as one stage of 128 columns (the
+// window of 64 owners for half-widths up to 28), and serves every wavefront whose band holds it; behind each pair of
+// barriers lies the arithmetic of a whole band row.  Every 16-owner tile walks its own key tiles from the staged row,
+// starting at the first column of its band rounded down to a multiple of four (operand reads stay 8-byte aligned), so
+// no tile is computed that the band does not touch.  The staged tiles carry 32 zeroed rows / columns of padding:
+// a tile that reaches past the window reads zeros, never stale bits that a matrix instruction could turn into NaN.
+constexpr int kLRows = 160;                      // 128 staged columns + 32 of zero padding
+constexpr int kLPitchC = 2 * kLRows + 16;        // bytes per channel row
+constexpr int kLTok = kLRows * kPitchT;
+constexpr int kLChan = kD * kLPitchC;
+
+// piece i of 512: channel i >> 4, the eight columns X0 + 8 (i & 15) .. + 7
+__device__ __forceinline__ uint4 load_piece128(const bf16raw *slice, size_t plane, int lat, int nlon, int X0, int i)
+{
+    int col = X0 + 8 * (i & 15);               // below 3 nlon
+    col = col >= nlon ? col - nlon : col;
+    col = col >= nlon ? col - nlon : col;
+    return *reinterpret_cast<const uint4 *>(slice + size_t(i >> 4) * plane + size_t(lat) * nlon + col);
+}
+__device__ __forceinline__ void store_chan128(char *tile, uint4 v, int i)
+{
+    *reinterpret_cast<uint4 *>(tile + (i >> 4) * kLPitchC + 16 * (i & 15)) = v;
+}
+__device__ __forceinline__ void store_tok128(char *tile, uint4 v, int i)
+{
+    const int c = i >> 4, p = i & 15;
+    char *dst = tile + 8 * p * kPitchT + (((c >> 3) ^ ((p >> 1) & 3)) << 4) + 2 * (c & 7);
+    const unsigned w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+        *reinterpret_cast<bf16raw *>(dst + u * kPitchT) = bf16raw(w[u >> 1] >> (16 * (u & 1)));
+}
+// operands of a 16-token tile that starts at row / column R0 (a multiple of 4) of the staged window
+__device__ __forceinline__ bf16x8 tok_operand_at(const char *tile, int R0, int lane)
+{
+    const int row = R0 + (lane & 15), g = lane >> 4;
+    return *reinterpret_cast<const bf16x8 *>(tile + row * kPitchT + ((g ^ ((row >> 4) & 3)) << 4));
+}
+__device__ __forceinline__ bf16x8 chan_operand_at(const char *tile, int mt, int Ca, int Cb, int lane)
+{
+    const int m = lane & 15, g = lane >> 4;
+    const char *row = tile + (16 * mt + m) * kLPitchC + 8 * g;
+    const uint2 a = *reinterpret_cast<const uint2 *>(row + 2 * Ca);
+    const uint2 b = *reinterpret_cast<const uint2 *>(row + 2 * Cb);
+    const uint4 r = {a.x, a.y, b.x, b.y};
+    return __builtin_bit_cast(bf16x8, r);
+}
+__device__ __forceinline__ void zero_lds(char *lds, int bytes, int tid)
+{
+    for (int i = tid; i < bytes / 4; i += 256) reinterpret_cast<unsigned *>(lds)[i] = 0u;
+}
+
+// The rows a workgroup of four consecutive latitudes [first, first + 4) ∩ [.., end) has to stage, and per row the
+// largest half-width among them (uniform scalar code).
+struct LightRows {
+    int rmin, rmax;
+    __device__ __forceinline__ void set(const int *blo, const int *bn, int first, int end)
+    {
+        rmin = 1 << 30;
+        rmax = -1;
+        for (int w = 0; w < 4; ++w) {
+            const int hh = first + w;
+            if (hh >= end) break;
+            rmin = min(rmin, blo[hh]);
+            rmax = max(rmax, blo[hh] + bn[hh] - 1);
+        }
+    }
+};
+__device__ __forceinline__ int light_hwmax(const int *blo, const int *bn, const int *cnt, int bmax, int first, int end, int r)
+{
+    int hwm = 0;
+    for (int w = 0; w < 4; ++w) {
+        const int hh = first + w;
+        if (hh >= end) break;
+        const int b = r - blo[hh];
+        if (b >= 0 && b < bn[hh]) hwm = max(hwm, (cnt[hh * bmax + b] - 1) >> 1);
+    }
+    return hwm;
+}
+
+__global__ void __launch_bounds__(256, 3)
+nattn_fwd_bf16_light(S2DeviceTables t, int nbh, float c2, const bf16raw *__restrict__ q, const bf16raw *__restrict__ k,
+                     const bf16raw *__restrict__ v, bf16raw *__restrict__ out, float *__restrict__ lse)
+{
+    __shared__ __attribute__((aligned(16))) char lds[kLTok + kLChan];
+    const int nlon = t.nlon_in, ngrp = nlon >> 6, nseg = (t.bl_hi - t.bl_lo + 3) >> 2;
+    int id = blockIdx.x;
+    const int grp = id % ngrp; id /= ngrp;
+    const int seg = id % nseg, bh = id / nseg;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n = lane & 15, g = lane >> 4;
+    const int first = t.bl_lo + 4 * seg, h = first + wave;
+    const bool active = h < t.bl_hi;
+    const int W0 = grp << 6, Wb = nlon + W0;
+    const size_t plane = size_t(t.nlat_in) * nlon;
+    const bf16raw *qs = q + size_t(bh) * kD * plane, *ks = k + size_t(bh) * kD * plane, *vs = v + size_t(bh) * kD * plane;
+    char *Kt = lds, *Vc = lds + kLTok;
+
+    bf16x8 qreg[4];
+    f32x4 acc[4][2];
+    float m[4], l[4];
+#pragma unroll
+    for (int o = 0; o < 4; ++o) {
+        if (active) qreg[o] = gather_point(qs, plane, size_t(h) * nlon + (W0 + 16 * o + n), g);
+        acc[o][0] = acc[o][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+        m[o] = -INFINITY;
+        l[o] = 0.f;
+    }
+    const int my_lo = active ? t.band_lo[h] : 0, my_n = active ? t.band_n[h] : 0;
+    LightRows rows;
+    rows.set(t.band_lo, t.band_n, first, t.bl_hi);
+    zero_lds(lds, kLTok + kLChan, tid);
+    int X0 = (Wb - light_hwmax(t.band_lo, t.band_n, t.cnt, t.band_max, first, t.bl_hi, rows.rmin)) & ~7;
+    uint4 rk[2], rv[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        rk[j] = load_piece128(ks, plane, rows.rmin, nlon, X0, tid + 256 * j);
+        rv[j] = load_piece128(vs, plane, rows.rmin, nlon, X0, tid + 256 * j);
+    }
+    for (int r = rows.rmin; r <= rows.rmax; ++r) {
+        __syncthreads();                    // everybody is done with the previous row (first pass: with the zero fill)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            store_tok128(Kt, rk[j], tid + 256 * j);
+            store_chan128(Vc, rv[j], tid + 256 * j);
+        }
+        __syncthreads();
+        const int Xr = X0;                  // first staged column of this row
+        if (r < rows.rmax) {
+            X0 = (Wb - light_hwmax(t.band_lo, t.band_n, t.cnt, t.band_max, first, t.bl_hi, r + 1)) & ~7;
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                rk[j] = load_piece128(ks, plane, r + 1, nlon, X0, tid + 256 * j);
+                rv[j] = load_piece128(vs, plane, r + 1, nlon, X0, tid + 256 * j);
+            }
+        }
+        const int b = r - my_lo;
+        if (!active || b < 0 || b >= my_n) continue;
+        const int hw = (t.cnt[h * t.band_max + b] - 1) >> 1;
+        const float lw2 = __log2f(t.omega_rel[r]);
+#pragma unroll
+        for (int o = 0; o < 4; ++o) {
+            const int Wo = Wb + 16 * o;
+            const int Xo = (Wo - hw) & ~3;                       // first key tile of this owner tile
+            const int nt = (Wo + 16 + hw - Xo + 15) >> 4;        // key tiles that touch its band (at most 5)
+#pragma unroll
+            for (int p = 0; p < 3; ++p) {
+                if (2 * p >= nt) break;
+                const int Xt0 = Xo + 32 * p, R0 = Xt0 - Xr;
+                const bool two = 2 * p + 1 < nt;
+                f32x4 x[2];
+                float mx = -INFINITY;
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    if (u == 1 && !two) break;
+                    const int Xt = Xt0 + 16 * u;
+                    const f32x4 sc = mfma16(tok_operand_at(Kt, R0 + 16 * u, lane), qreg[o], f32x4{0.f, 0.f, 0.f, 0.f});
+#pragma unroll
+                    for (int rr = 0; rr < 4; ++rr) x[u][rr] = fmaf(sc[rr], c2, lw2);
+                    const int dlt = Xt > Wo ? Xt - Wo : Wo - Xt;
+                    if (hw < 15 + dlt) {
+                        const unsigned uu = unsigned(Xt + 4 * g - (Wo + n) + hw), lim = unsigned(2 * hw);
+#pragma unroll
+                        for (int rr = 0; rr < 4; ++rr) x[u][rr] = uu + rr <= lim ? x[u][rr] : -INFINITY;
+                    }
+                    mx = fmaxf(mx, fmaxf(fmaxf(x[u][0], x[u][1]), fmaxf(x[u][2], x[u][3])));
+                }
+                if (__any(mx > m[o] + 8.f)) {
+                    mx = group_max(mx);
+                    const float m_new = mx > m[o] + 8.f ? mx : m[o];
+                    const float corr = m_new == m[o] ? 1.f : __builtin_amdgcn_exp2f(m[o] - m_new);
+                    m[o] = m_new;
+                    l[o] *= corr;
+#pragma unroll
+                    for (int rr = 0; rr < 4; ++rr) { acc[o][0][rr] *= corr; acc[o][1][rr] *= corr; }
+                }
+                const float ms = m[o] == -INFINITY ? 0.f : m[o];
+                float ps = 0.f;
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    if (u == 0 || two) {
+#pragma unroll
+                        for (int rr = 0; rr < 4; ++rr) {
+                            x[u][rr] = __builtin_amdgcn_exp2f(x[u][rr] - ms);
+                            ps += x[u][rr];
+                        }
+                    } else {
+                        x[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    }
+                }
+                l[o] += ps;
+                const bf16x8 pb = pack2(x[0], x[1]);
+                acc[o][0] = mfma16(chan_operand_at(Vc, 0, R0, R0 + 16, lane), pb, acc[o][0]);
+                acc[o][1] = mfma16(chan_operand_at(Vc, 1, R0, R0 + 16, lane), pb, acc[o][1]);
+            }
+        }
+    }
+    if (!active) return;
+#pragma unroll
+    for (int o = 0; o < 4; ++o) {
+        const float lt = group_sum(l[o]);
+        const float inv = 1.f / lt;
+        const size_t at = size_t(h) * nlon + (W0 + 16 * o + n);
+        bf16raw *ob = out + size_t(bh) * kD * plane + at;
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) ob[size_t(16 * mt + 4 * g + rr) * plane] = bf16_bits(acc[o][mt][rr] * inv);
+        if (g == 0) lse[size_t(bh) * plane + at] = (m[o] + __log2f(lt)) * 0.6931471805599453f + t.ln_omega_ref;
+    }
+}
+
+__global__ void __launch_bounds__(256, 2)
+nattn_bwd_dq_bf16_light(S2DeviceTables t, int nbh, float scale, const bf16raw *__restrict__ q, const bf16raw *__restrict__ k,
+                        const bf16raw *__restrict__ v, const bf16raw *__restrict__ o_, const float *__restrict__ lse,
+                        const bf16raw *__restrict__ go, bf16raw *__restrict__ dq, float *__restrict__ Dws)
+{
+    __shared__ __attribute__((aligned(16))) char lds[2 * kLTok + kLChan];
+    const int nlon = t.nlon_in, ngrp = nlon >> 6, nseg = (t.bl_hi - t.bl_lo + 3) >> 2;
+    int id = blockIdx.x;
+    const int grp = id % ngrp; id /= ngrp;
+    const int seg = id % nseg, bh = id / nseg;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n = lane & 15, g = lane >> 4;
+    const int first = t.bl_lo + 4 * seg, h = first + wave;
+    const bool active = h < t.bl_hi;
+    const int W0 = grp << 6, Wb = nlon + W0;
+    const size_t plane = size_t(t.nlat_in) * nlon;
+    const bf16raw *qs = q + size_t(bh) * kD * plane, *ks = k + size_t(bh) * kD * plane, *vs = v + size_t(bh) * kD * plane;
+    const bf16raw *os = o_ + size_t(bh) * kD * plane, *gs = go + size_t(bh) * kD * plane;
+    const float c2 = scale * kLog2e;
+    char *Kt = lds, *Vt = lds + kLTok, *Kc = lds + 2 * kLTok;
+
+    bf16x8 qreg[4], greg[4];
+    f32x4 acc[4][2];
+    float L2[4], Dn[4];
+#pragma unroll
+    for (int o = 0; o < 4; ++o) {
+        acc[o][0] = acc[o][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+        L2[o] = 0.f;
+        Dn[o] = 0.f;
+        if (active) {
+            const size_t at = size_t(h) * nlon + (W0 + 16 * o + n);
+            qreg[o] = gather_point(qs, plane, at, g);
+            greg[o] = gather_point(gs, plane, at, g);
+            const bf16x8 oo = gather_point(os, plane, at, g);
+            float dsum = 0.f;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) dsum = fmaf(float(greg[o][j]), float(oo[j]), dsum);
+            dsum = group_sum(dsum);
+            if (g == 0) Dws[size_t(bh) * plane + at] = dsum;
+            Dn[o] = -dsum;
+            L2[o] = (lse[size_t(bh) * plane + at] - t.ln_omega_ref) * kLog2e;
+        }
+    }
+    const int my_lo = active ? t.band_lo[h] : 0, my_n = active ? t.band_n[h] : 0;
+    LightRows rows;
+    rows.set(t.band_lo, t.band_n, first, t.bl_hi);
+    zero_lds(lds, 2 * kLTok + kLChan, tid);
+    int X0 = (Wb - light_hwmax(t.band_lo, t.band_n, t.cnt, t.band_max, first, t.bl_hi, rows.rmin)) & ~7;
+    uint4 rk[2], rv[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        rk[j] = load_piece128(ks, plane, rows.rmin, nlon, X0, tid + 256 * j);
+        rv[j] = load_piece128(vs, plane, rows.rmin, nlon, X0, tid + 256 * j);
+    }
+    for (int r = rows.rmin; r <= rows.rmax; ++r) {
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            store_tok128(Kt, rk[j], tid + 256 * j);
+            store_tok128(Vt, rv[j], tid + 256 * j);
+            store_chan128(Kc, rk[j], tid + 256 * j);
+        }
+        __syncthreads();
+        const int Xr = X0;
+        if (r < rows.rmax) {
+            X0 = (Wb - light_hwmax(t.band_lo, t.band_n, t.cnt, t.band_max, first, t.bl_hi, r + 1)) & ~7;
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                rk[j] = load_piece128(ks, plane, r + 1, nlon, X0, tid + 256 * j);
+                rv[j] = load_piece128(vs, plane, r + 1, nlon, X0, tid + 256 * j);
+            }
+        }
+        const int b = r - my_lo;
+        if (!active || b < 0 || b >= my_n) continue;
+        const int hw = (t.cnt[h * t.band_max + b] - 1) >> 1;
+        const float lw2 = __log2f(t.omega_rel[r]);
+#pragma unroll
+        for (int o = 0; o < 4; ++o) {
+            const int Wo = Wb + 16 * o;
+            const int Xo = (Wo - hw) & ~3;
+            const int nt = (Wo + 16 + hw - Xo + 15) >> 4;
+            const float bias = lw2 - L2[o];
+#pragma unroll
+            for (int p = 0; p < 3; ++p) {
+                if (2 * p >= nt) break;
+                const int Xt0 = Xo + 32 * p, R0 = Xt0 - Xr;
+                const bool two = 2 * p + 1 < nt;
+                f32x4 ds[2];
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    ds[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    if (u == 1 && !two) break;
+                    const int Xt = Xt0 + 16 * u;
+                    const f32x4 sc = mfma16(tok_operand_at(Kt, R0 + 16 * u, lane), qreg[o], f32x4{0.f, 0.f, 0.f, 0.f});
+                    const f32x4 dp = mfma16(tok_operand_at(Vt, R0 + 16 * u, lane), greg[o], f32x4{Dn[o], Dn[o], Dn[o], Dn[o]});
+#pragma unroll
+                    for (int rr = 0; rr < 4; ++rr) ds[u][rr] = __builtin_amdgcn_exp2f(fmaf(sc[rr], c2, bias)) * dp[rr];
+                    const int dlt = Xt > Wo ? Xt - Wo : Wo - Xt;
+                    if (hw < 15 + dlt) {
+                        const unsigned uu = unsigned(Xt + 4 * g - (Wo + n) + hw), lim = unsigned(2 * hw);
+#pragma unroll
+                        for (int rr = 0; rr < 4; ++rr) ds[u][rr] = uu + rr <= lim ? ds[u][rr] : 0.f;
+                    }
+                }
+                bf16x8 dh, dl;
+                pack2_split(ds[0], ds[1], dh, dl);
+                const bf16x8 k0 = chan_operand_at(Kc, 0, R0, R0 + 16, lane), k1 = chan_operand_at(Kc, 1, R0, R0 + 16, lane);
+                acc[o][0] = mfma16(k0, dl, mfma16(k0, dh, acc[o][0]));
+                acc[o][1] = mfma16(k1, dl, mfma16(k1, dh, acc[o][1]));
+            }
+        }
+    }
+    if (!active) return;
+#pragma unroll
+    for (int o = 0; o < 4; ++o) {
+        bf16raw *ob = dq + size_t(bh) * kD * plane + size_t(h) * nlon + (W0 + 16 * o + n);
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) ob[size_t(16 * mt + 4 * g + rr) * plane] = bf16_bits(acc[o][mt][rr] * scale);
+    }
+}
+
+__global__ void __launch_bounds__(256, 2)
+nattn_bwd_dkdv_bf16_light(S2DeviceTables t, int nbh, float scale, const bf16raw *__restrict__ q, const bf16raw *__restrict__ k,
+                          const bf16raw *__restrict__ v, const float *__restrict__ lse, const bf16raw *__restrict__ go,
+                          const float *__restrict__ Dws, bf16raw *__restrict__ dk, bf16raw *__restrict__ dv)
+{
+    constexpr int kStats = 2 * kLRows * 4;
+    __shared__ __attribute__((aligned(16))) char lds[2 * kLTok + 2 * kLChan + kStats];
+    const int nlon = t.nlon_in, ngrp = nlon >> 6, nseg = (t.tbl_hi - t.tbl_lo + 3) >> 2;
+    int id = blockIdx.x;
+    const int grp = id % ngrp; id /= ngrp;
+    const int seg = id % nseg, bh = id / nseg;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n = lane & 15, g = lane >> 4;
+    const int first = t.tbl_lo + 4 * seg, hp = first + wave;
+    const bool active = hp < t.tbl_hi;
+    const int W0 = grp << 6, Wb = nlon + W0;
+    const size_t plane = size_t(t.nlat_in) * nlon;
+    const bf16raw *qs = q + size_t(bh) * kD * plane, *ks = k + size_t(bh) * kD * plane, *vs = v + size_t(bh) * kD * plane;
+    const bf16raw *gs = go + size_t(bh) * kD * plane;
+    const float *ls = lse + size_t(bh) * plane, *Ds = Dws + size_t(bh) * plane;
+    const float c2 = scale * kLog2e, lref = t.ln_omega_ref;
+    const float lw2 = active ? __log2f(t.omega_rel[hp]) : 0.f;
+    char *Qt = lds, *Gt = lds + kLTok, *Qc = lds + 2 * kLTok, *Gc = Qc + kLChan;
+    float *Ls = reinterpret_cast<float *>(Gc + kLChan), *Dn = Ls + kLRows;
+
+    bf16x8 kreg[4], vreg[4];
+    f32x4 adk[4][2], adv[4][2];
+#pragma unroll
+    for (int o = 0; o < 4; ++o) {
+        adk[o][0] = adk[o][1] = adv[o][0] = adv[o][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (active) {
+            const size_t at = size_t(hp) * nlon + (W0 + 16 * o + n);
+            kreg[o] = gather_point(ks, plane, at, g);
+            vreg[o] = gather_point(vs, plane, at, g);
+        }
+    }
+    const int my_lo = active ? t.tband_lo[hp] : 0, my_n = active ? t.tband_n[hp] : 0;
+    LightRows rows;
+    rows.set(t.tband_lo, t.tband_n, first, t.tbl_hi);
+    zero_lds(lds, 2 * kLTok + 2 * kLChan + kStats, tid);
+    auto load_stat = [&](int lat, int Xs) -> float {      // threads 0..127: logsumexp (base 2, relative), 128..255: -D
+        int col = Xs + (tid & 127);
+        col = col >= nlon ? col - nlon : col;
+        col = col >= nlon ? col - nlon : col;
+        return tid < 128 ? (ls[size_t(lat) * nlon + col] - lref) * kLog2e : -Ds[size_t(lat) * nlon + col];
+    };
+    int X0 = (Wb - light_hwmax(t.tband_lo, t.tband_n, t.tcnt, t.tband_max, first, t.tbl_hi, rows.rmin)) & ~7;
+    uint4 rq[2], rg[2];
+    float rs;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        rq[j] = load_piece128(qs, plane, rows.rmin, nlon, X0, tid + 256 * j);
+        rg[j] = load_piece128(gs, plane, rows.rmin, nlon, X0, tid + 256 * j);
+    }
+    rs = load_stat(rows.rmin, X0);
+    for (int r = rows.rmin; r <= rows.rmax; ++r) {
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            store_tok128(Qt, rq[j], tid + 256 * j);
+            store_tok128(Gt, rg[j], tid + 256 * j);
+            store_chan128(Qc, rq[j], tid + 256 * j);
+            store_chan128(Gc, rg[j], tid + 256 * j);
+        }
+        (tid < 128 ? Ls : Dn)[tid & 127] = rs;
+        __syncthreads();
+        const int Xr = X0;
+        if (r < rows.rmax) {
+            X0 = (Wb - light_hwmax(t.tband_lo, t.tband_n, t.tcnt, t.tband_max, first, t.tbl_hi, r + 1)) & ~7;
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                rq[j] = load_piece128(qs, plane, r + 1, nlon, X0, tid + 256 * j);
+                rg[j] = load_piece128(gs, plane, r + 1, nlon, X0, tid + 256 * j);
+            }
+            rs = load_stat(r + 1, X0);
+        }
+        const int b = r - my_lo;
+        if (!active || b < 0 || b >= my_n) continue;
+        const int hw = (t.tcnt[hp * t.tband_max + b] - 1) >> 1;
+#pragma unroll
+        for (int o = 0; o < 4; ++o) {
+            const int Wo = Wb + 16 * o;
+            const int Xo = (Wo - hw) & ~3;
+            const int nt = (Wo + 16 + hw - Xo + 15) >> 4;
+#pragma unroll
+            for (int p = 0; p < 3; ++p) {
+                if (2 * p >= nt) break;
+                const int Xt0 = Xo + 32 * p, R0 = Xt0 - Xr;
+                const bool two = 2 * p + 1 < nt;
+                f32x4 pr[2], ds[2];
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    pr[u] = ds[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    if (u == 1 && !two) break;
+                    const int Xt = Xt0 + 16 * u, Ru = R0 + 16 * u;
+                    const f32x4 L = *reinterpret_cast<const f32x4 *>(Ls + Ru + 4 * g);
+                    const f32x4 Dm = *reinterpret_cast<const f32x4 *>(Dn + Ru + 4 * g);
+                    const f32x4 sc = mfma16(tok_operand_at(Qt, Ru, lane), kreg[o], f32x4{0.f, 0.f, 0.f, 0.f});
+                    const f32x4 dp = mfma16(tok_operand_at(Gt, Ru, lane), vreg[o], Dm);
+#pragma unroll
+                    for (int rr = 0; rr < 4; ++rr) {
+                        pr[u][rr] = __builtin_amdgcn_exp2f(fmaf(sc[rr], c2, lw2 - L[rr]));
+                        ds[u][rr] = pr[u][rr] * dp[rr];
+                    }
+                    // both matrix results are consumed above, in the block that issues them: a consumer behind the
+                    // uniform branch below is not covered by the compiler's wait-state bookkeeping for matrix results
+                    const int dlt = Xt > Wo ? Xt - Wo : Wo - Xt;
+                    if (hw < 15 + dlt) {
+                        const unsigned uu = unsigned(Xt + 4 * g - (Wo + n) + hw), lim = unsigned(2 * hw);
+#pragma unroll
+                        for (int rr = 0; rr < 4; ++rr) {
+                            const bool in = uu + rr <= lim;
+                            pr[u][rr] = in ? pr[u][rr] : 0.f;
+                            ds[u][rr] = in ? ds[u][rr] : 0.f;
+                        }
+                    }
+                }
+                bf16x8 ph, pl, dh, dl;
+                pack2_split(pr[0], pr[1], ph, pl);
+                pack2_split(ds[0], ds[1], dh, dl);
+                const bf16x8 g0 = chan_operand_at(Gc, 0, R0, R0 + 16, lane), g1 = chan_operand_at(Gc, 1, R0, R0 + 16, lane);
+                adv[o][0] = mfma16(g0, pl, mfma16(g0, ph, adv[o][0]));
+                adv[o][1] = mfma16(g1, pl, mfma16(g1, ph, adv[o][1]));
+                const bf16x8 q0 = chan_operand_at(Qc, 0, R0, R0 + 16, lane), q1 = chan_operand_at(Qc, 1, R0, R0 + 16, lane);
+                adk[o][0] = mfma16(q0, dl, mfma16(q0, dh, adk[o][0]));
+                adk[o][1] = mfma16(q1, dl, mfma16(q1, dh, adk[o][1]));
+            }
+        }
+    }
+    if (!active) return;
+#pragma unroll
+    for (int o = 0; o < 4; ++o) {
+        const size_t at = size_t(bh) * kD * plane + size_t(hp) * nlon + (W0 + 16 * o + n);
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) {
+                dk[at + size_t(16 * mt + 4 * g + rr) * plane] = bf16_bits(adk[o][mt][rr] * scale);
+                dv[at + size_t(16 * mt + 4 * g + rr) * plane] = bf16_bits(adv[o][mt][rr]);
+            }
+    }
+}
+
+}  // namespace
+
 // Two launches per kernel: the latitudes of the three heavy classes (dense neighborhoods near the poles), then the
 // light ones; the library's launch trace reports them separately.
 template <class F>
@@ -628,7 +1114,11 @@ static void launch_by_class(const S2DeviceTables &t, bool fwd_side, int nbh, con
     }
     if (cls[3] > 0) {
         S2TraceScope tr(light_name, nbh * pairs[3], st);
-        launch(ndense, unsigned(long(nbh) * cls[3] * ngrp));
+        const int lo = fwd_side ? t.bl_lo : t.tbl_lo, hi = fwd_side ? t.bl_hi : t.tbl_hi;
+        if (hi - lo == cls[3])      // the light latitudes are a contiguous range of short arcs: four latitudes per workgroup
+            launch(-1, unsigned(long(nbh) * ((hi - lo + 3) / 4) * (t.nlon_in / 64)));
+        else
+            launch(ndense, unsigned(long(nbh) * cls[3] * ngrp));
     }
 }
 
@@ -637,6 +1127,12 @@ int s2_nattn_fwd_bf16(const S2DeviceTables &t, int nbh, int, int, float scale, c
 {
     if (s2_debug_flag(S2_DEBUG_FAIL_LAUNCH)) return -1;
     launch_by_class(t, true, nbh, "nattn_fwd_bf16<dense>", "nattn_fwd_bf16<light>", st, [&](int first, unsigned nblk) {
+        if (first < 0) {
+            hipLaunchKernelGGL(nattn_fwd_bf16_light, dim3(nblk), dim3(256), 0, st, t, nbh, scale * kLog2e,
+                               static_cast<const bf16raw *>(q), static_cast<const bf16raw *>(k),
+                               static_cast<const bf16raw *>(v), static_cast<bf16raw *>(out), lse);
+            return;
+        }
         hipLaunchKernelGGL(nattn_fwd_bf16, dim3(nblk), dim3(256), 0, st, t, nbh, first, scale * kLog2e,
                            static_cast<const bf16raw *>(q), static_cast<const bf16raw *>(k),
                            static_cast<const bf16raw *>(v), static_cast<bf16raw *>(out), lse);
@@ -650,6 +1146,13 @@ int s2_nattn_bwd_dq_bf16(const S2DeviceTables &t, int nbh, int, int, float scale
 {
     if (s2_debug_flag(S2_DEBUG_FAIL_LAUNCH)) return -1;
     launch_by_class(t, true, nbh, "nattn_bwd_dq_bf16<dense>", "nattn_bwd_dq_bf16<light>", st, [&](int first, unsigned nblk) {
+        if (first < 0) {
+            hipLaunchKernelGGL(nattn_bwd_dq_bf16_light, dim3(nblk), dim3(256), 0, st, t, nbh, scale,
+                               static_cast<const bf16raw *>(q), static_cast<const bf16raw *>(k),
+                               static_cast<const bf16raw *>(v), static_cast<const bf16raw *>(o), lse,
+                               static_cast<const bf16raw *>(go), static_cast<bf16raw *>(dq), Dws);
+            return;
+        }
         hipLaunchKernelGGL(nattn_bwd_dq_bf16, dim3(nblk), dim3(256), 0, st, t, nbh, first, scale,
                            static_cast<const bf16raw *>(q), static_cast<const bf16raw *>(k),
                            static_cast<const bf16raw *>(v), static_cast<const bf16raw *>(o), lse,
@@ -664,6 +1167,13 @@ int s2_nattn_bwd_dkdv_bf16(const S2DeviceTables &t, int nbh, int, int, float sca
 {
     if (s2_debug_flag(S2_DEBUG_FAIL_LAUNCH)) return -1;
     launch_by_class(t, false, nbh, "nattn_bwd_dkdv_bf16<dense>", "nattn_bwd_dkdv_bf16<light>", st, [&](int first, unsigned nblk) {
+        if (first < 0) {
+            hipLaunchKernelGGL(nattn_bwd_dkdv_bf16_light, dim3(nblk), dim3(256), 0, st, t, nbh, scale,
+                               static_cast<const bf16raw *>(q), static_cast<const bf16raw *>(k),
+                               static_cast<const bf16raw *>(v), lse, static_cast<const bf16raw *>(go), Dws,
+                               static_cast<bf16raw *>(dk), static_cast<bf16raw *>(dv));
+            return;
+        }
         hipLaunchKernelGGL(nattn_bwd_dkdv_bf16, dim3(nblk), dim3(256), 0, st, t, nbh, first, scale,
                            static_cast<const bf16raw *>(q), static_cast<const bf16raw *>(k),
                            static_cast<const bf16raw *>(v), lse, static_cast<const bf16raw *>(go), Dws,
