@@ -565,8 +565,10 @@ extern "C" int s2_grid_init(int grid_type, int nlat_in, int nlon_in, int nlat_ou
                 g->tst_cum);
 
     // light range for the bf16 band-tile kernels: the latitudes of the last class must be one contiguous range with
-    // odd arcs of at most 57 offsets (a 128-column stage then holds the window of 64 owners on every band row)
-    auto light_range = [](int n_rows, const std::vector<int> &n, const std::vector<int> &tab, int bmax, int &lo, int &hi) {
+    // odd arcs of at most 57 offsets (a 128-column stage then holds the window of 64 owners on every band row), and
+    // the bands of four consecutive latitudes together span at most 64 rows (a workgroup keeps one row per lane)
+    auto light_range = [](int n_rows, const std::vector<int> &blo, const std::vector<int> &n, const std::vector<int> &tab,
+                          int bmax, int &lo, int &hi) {
         lo = hi = 0;
         int first = -1, last = -1, count = 0;
         for (int r = 0; r < n_rows; ++r) {
@@ -585,11 +587,19 @@ extern "C" int s2_grid_init(int grid_type, int nlat_in, int nlon_in, int nlat_ou
                 if (c < 1 || c > 57 || c % 2 == 0) return;
             }
         }
+        for (int f = first; f <= last; f += 4) {
+            int rmin = 1 << 30, rmax = -1;
+            for (int r = f; r <= std::min(f + 3, last); ++r) {
+                rmin = std::min(rmin, blo[r]);
+                rmax = std::max(rmax, blo[r] + n[r] - 1);
+            }
+            if (rmax - rmin + 1 > 64) return;
+        }
         lo = first;
         hi = last + 1;
     };
-    light_range(nlat_out, g->band_n, g->cnt, g->band_max, g->dt.bl_lo, g->dt.bl_hi);
-    light_range(nlat_in, g->tband_n, g->tcnt, g->tband_max, g->dt.tbl_lo, g->dt.tbl_hi);
+    light_range(nlat_out, g->band_lo, g->band_n, g->cnt, g->band_max, g->dt.bl_lo, g->dt.bl_hi);
+    light_range(nlat_in, g->tband_lo, g->tband_n, g->tcnt, g->tband_max, g->dt.tbl_lo, g->dt.tbl_hi);
 
     int rc = upload_tables(g);
     if (rc != S2_OK) { delete g; return rc; }

@@ -686,17 +686,41 @@ struct LightRows {
         }
     }
 };
-__device__ __forceinline__ int light_hwmax(const int *blo, const int *bn, const int *cnt, int bmax, int first, int end, int r)
-{
-    int hwm = 0;
-    for (int w = 0; w < 4; ++w) {
-        const int hh = first + w;
-        if (hh >= end) break;
-        const int b = r - blo[hh];
-        if (b >= 0 && b < bn[hh]) hwm = max(hwm, (cnt[hh * bmax + b] - 1) >> 1);
+// Row metadata of a workgroup, read from the grid tables ONCE before the row loop and kept in registers (lane i
+// holds row rmin + i; the host guarantees at most 64 rows per workgroup): a table read inside the loop is a vector
+// load whose wait also waits for the row prefetch in flight, which serialises the loop on memory latency.
+//   hwm: largest half-width on that row among the workgroup's latitudes (defines the staged window)
+//   hw:  this wavefront's half-width on that row, -1 if the row is not in its band
+//   lw2: log2 of the row's relative quadrature weight
+struct LightMeta {
+    int hwm_v, hw_v;
+    float lw2_v;
+    __device__ __forceinline__ void load(const int *blo, const int *bn, const int *cnt, int bmax, const float *omega_rel,
+                                         int first, int end, int own, bool active, const LightRows &rows, int lane)
+    {
+        const int r = rows.rmin + lane;
+        const bool valid = r <= rows.rmax;
+        hwm_v = 0;
+        hw_v = -1;
+        for (int w = 0; w < 4; ++w) {
+            const int hh = first + w;
+            if (hh >= end) break;
+            const int b = r - blo[hh];
+            if (valid && b >= 0 && b < bn[hh]) {
+                const int x = (cnt[hh * bmax + b] - 1) >> 1;
+                hwm_v = max(hwm_v, x);
+                if (active && hh == own) hw_v = x;
+            }
+        }
+        lw2_v = valid ? __log2f(omega_rel[r]) : 0.f;
     }
-    return hwm;
-}
+    __device__ __forceinline__ int hwmax(int i) const { return __builtin_amdgcn_readlane(hwm_v, i); }
+    __device__ __forceinline__ int hw(int i) const { return __builtin_amdgcn_readlane(hw_v, i); }
+    __device__ __forceinline__ float lw2(int i) const
+    {
+        return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, lw2_v), i));
+    }
+};
 
 __global__ void __launch_bounds__(256, 3)
 nattn_fwd_bf16_light(S2DeviceTables t, int nbh, float c2, const bf16raw *__restrict__ q, const bf16raw *__restrict__ k,
@@ -726,11 +750,12 @@ nattn_fwd_bf16_light(S2DeviceTables t, int nbh, float c2, const bf16raw *__restr
         m[o] = -INFINITY;
         l[o] = 0.f;
     }
-    const int my_lo = active ? t.band_lo[h] : 0, my_n = active ? t.band_n[h] : 0;
     LightRows rows;
     rows.set(t.band_lo, t.band_n, first, t.bl_hi);
+    LightMeta meta;
+    meta.load(t.band_lo, t.band_n, t.cnt, t.band_max, t.omega_rel, first, t.bl_hi, h, active, rows, lane);
     zero_lds(lds, kLTok + kLChan, tid);
-    int X0 = (Wb - light_hwmax(t.band_lo, t.band_n, t.cnt, t.band_max, first, t.bl_hi, rows.rmin)) & ~7;
+    int X0 = (Wb - meta.hwmax(0)) & ~7;
     uint4 rk[2], rv[2];
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
@@ -747,17 +772,16 @@ nattn_fwd_bf16_light(S2DeviceTables t, int nbh, float c2, const bf16raw *__restr
         __syncthreads();
         const int Xr = X0;                  // first staged column of this row
         if (r < rows.rmax) {
-            X0 = (Wb - light_hwmax(t.band_lo, t.band_n, t.cnt, t.band_max, first, t.bl_hi, r + 1)) & ~7;
+            X0 = (Wb - meta.hwmax(r + 1 - rows.rmin)) & ~7;
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
                 rk[j] = load_piece128(ks, plane, r + 1, nlon, X0, tid + 256 * j);
                 rv[j] = load_piece128(vs, plane, r + 1, nlon, X0, tid + 256 * j);
             }
         }
-        const int b = r - my_lo;
-        if (!active || b < 0 || b >= my_n) continue;
-        const int hw = (t.cnt[h * t.band_max + b] - 1) >> 1;
-        const float lw2 = __log2f(t.omega_rel[r]);
+        const int hw = meta.hw(r - rows.rmin);
+        if (hw < 0) continue;
+        const float lw2 = meta.lw2(r - rows.rmin);
 #pragma unroll
         for (int o = 0; o < 4; ++o) {
             const int Wo = Wb + 16 * o;
@@ -873,11 +897,12 @@ nattn_bwd_dq_bf16_light(S2DeviceTables t, int nbh, float scale, const bf16raw *_
             L2[o] = (lse[size_t(bh) * plane + at] - t.ln_omega_ref) * kLog2e;
         }
     }
-    const int my_lo = active ? t.band_lo[h] : 0, my_n = active ? t.band_n[h] : 0;
     LightRows rows;
     rows.set(t.band_lo, t.band_n, first, t.bl_hi);
+    LightMeta meta;
+    meta.load(t.band_lo, t.band_n, t.cnt, t.band_max, t.omega_rel, first, t.bl_hi, h, active, rows, lane);
     zero_lds(lds, 2 * kLTok + kLChan, tid);
-    int X0 = (Wb - light_hwmax(t.band_lo, t.band_n, t.cnt, t.band_max, first, t.bl_hi, rows.rmin)) & ~7;
+    int X0 = (Wb - meta.hwmax(0)) & ~7;
     uint4 rk[2], rv[2];
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
@@ -895,17 +920,16 @@ nattn_bwd_dq_bf16_light(S2DeviceTables t, int nbh, float scale, const bf16raw *_
         __syncthreads();
         const int Xr = X0;
         if (r < rows.rmax) {
-            X0 = (Wb - light_hwmax(t.band_lo, t.band_n, t.cnt, t.band_max, first, t.bl_hi, r + 1)) & ~7;
+            X0 = (Wb - meta.hwmax(r + 1 - rows.rmin)) & ~7;
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
                 rk[j] = load_piece128(ks, plane, r + 1, nlon, X0, tid + 256 * j);
                 rv[j] = load_piece128(vs, plane, r + 1, nlon, X0, tid + 256 * j);
             }
         }
-        const int b = r - my_lo;
-        if (!active || b < 0 || b >= my_n) continue;
-        const int hw = (t.cnt[h * t.band_max + b] - 1) >> 1;
-        const float lw2 = __log2f(t.omega_rel[r]);
+        const int hw = meta.hw(r - rows.rmin);
+        if (hw < 0) continue;
+        const float lw2 = meta.lw2(r - rows.rmin);
 #pragma unroll
         for (int o = 0; o < 4; ++o) {
             const int Wo = Wb + 16 * o;
@@ -989,9 +1013,10 @@ nattn_bwd_dkdv_bf16_light(S2DeviceTables t, int nbh, float scale, const bf16raw 
             vreg[o] = gather_point(vs, plane, at, g);
         }
     }
-    const int my_lo = active ? t.tband_lo[hp] : 0, my_n = active ? t.tband_n[hp] : 0;
     LightRows rows;
     rows.set(t.tband_lo, t.tband_n, first, t.tbl_hi);
+    LightMeta meta;
+    meta.load(t.tband_lo, t.tband_n, t.tcnt, t.tband_max, t.omega_rel, first, t.tbl_hi, hp, active, rows, lane);
     zero_lds(lds, 2 * kLTok + 2 * kLChan + kStats, tid);
     auto load_stat = [&](int lat, int Xs) -> float {      // threads 0..127: logsumexp (base 2, relative), 128..255: -D
         int col = Xs + (tid & 127);
@@ -999,7 +1024,7 @@ nattn_bwd_dkdv_bf16_light(S2DeviceTables t, int nbh, float scale, const bf16raw 
         col = col >= nlon ? col - nlon : col;
         return tid < 128 ? (ls[size_t(lat) * nlon + col] - lref) * kLog2e : -Ds[size_t(lat) * nlon + col];
     };
-    int X0 = (Wb - light_hwmax(t.tband_lo, t.tband_n, t.tcnt, t.tband_max, first, t.tbl_hi, rows.rmin)) & ~7;
+    int X0 = (Wb - meta.hwmax(0)) & ~7;
     uint4 rq[2], rg[2];
     float rs;
 #pragma unroll
@@ -1021,7 +1046,7 @@ nattn_bwd_dkdv_bf16_light(S2DeviceTables t, int nbh, float scale, const bf16raw 
         __syncthreads();
         const int Xr = X0;
         if (r < rows.rmax) {
-            X0 = (Wb - light_hwmax(t.tband_lo, t.tband_n, t.tcnt, t.tband_max, first, t.tbl_hi, r + 1)) & ~7;
+            X0 = (Wb - meta.hwmax(r + 1 - rows.rmin)) & ~7;
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
                 rq[j] = load_piece128(qs, plane, r + 1, nlon, X0, tid + 256 * j);
@@ -1029,9 +1054,8 @@ nattn_bwd_dkdv_bf16_light(S2DeviceTables t, int nbh, float scale, const bf16raw 
             }
             rs = load_stat(r + 1, X0);
         }
-        const int b = r - my_lo;
-        if (!active || b < 0 || b >= my_n) continue;
-        const int hw = (t.tcnt[hp * t.tband_max + b] - 1) >> 1;
+        const int hw = meta.hw(r - rows.rmin);
+        if (hw < 0) continue;
 #pragma unroll
         for (int o = 0; o < 4; ++o) {
             const int Wo = Wb + 16 * o;
