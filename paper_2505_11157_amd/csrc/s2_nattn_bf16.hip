@@ -626,7 +626,7 @@ namespace {
 // a tile that reaches past the window reads zeros, never stale bits that a matrix instruction could turn into NaN.
 constexpr int kLRows = 160;                      // 128 staged columns + 32 of zero padding
 constexpr int kLPitchC = 2 * kLRows + 16;        // bytes per channel row
-constexpr int kLTok = kLRows * kPitchT;
+constexpr int kLTok = kLRows * kPitchT + 64;     // rows 64..127 sit 64 bytes further on (see store_tok128)
 constexpr int kLChan = kD * kLPitchC;
 
 // piece i of 512: channel i >> 4, the eight columns X0 + 8 (i & 15) .. + 7
@@ -644,7 +644,9 @@ __device__ __forceinline__ void store_chan128(char *tile, uint4 v, int i)
 __device__ __forceinline__ void store_tok128(char *tile, uint4 v, int i)
 {
     const int c = i >> 4, p = i & 15;
-    char *dst = tile + 8 * p * kPitchT + (((c >> 3) ^ ((p >> 1) & 3)) << 4) + 2 * (c & 7);
+    // rows r and r + 64 would share their banks (64 * 80 bytes = 20 * 64 words): the second 64 rows are shifted by 16
+    // words, into the banks the 16 pieces of a wavefront's scatter leave free
+    char *dst = tile + 8 * p * kPitchT + ((p >> 3) << 6) + (((c >> 3) ^ ((p >> 1) & 3)) << 4) + 2 * (c & 7);
     const unsigned w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
     for (int u = 0; u < 8; ++u)
@@ -654,7 +656,7 @@ __device__ __forceinline__ void store_tok128(char *tile, uint4 v, int i)
 __device__ __forceinline__ bf16x8 tok_operand_at(const char *tile, int R0, int lane)
 {
     const int row = R0 + (lane & 15), g = lane >> 4;
-    return *reinterpret_cast<const bf16x8 *>(tile + row * kPitchT + ((g ^ ((row >> 4) & 3)) << 4));
+    return *reinterpret_cast<const bf16x8 *>(tile + row * kPitchT + (((row >> 6) & 1) << 6) + ((g ^ ((row >> 4) & 3)) << 4));
 }
 __device__ __forceinline__ bf16x8 chan_operand_at(const char *tile, int mt, int Ca, int Cb, int lane)
 {
