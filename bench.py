@@ -261,6 +261,8 @@ def main():
     ap.add_argument("--config", type=int, default=3,
                     help="headline workload (1-5; 6 = upsampling, 7 = workload 3 with bf16 tensors), default 3 = 129x256 equiangular")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--force-band", action="store_true",
+                    help="float32 d = 32 workloads on the band-tile matrix-core kernels that serve d = 16 and 64")
     ap.add_argument("--no-workloads", action="store_true", help="skip the extra `workloads` measurements")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run three 1 GiB device copies (scale for the rocprofv3 HBM counters)")
@@ -279,6 +281,11 @@ def main():
         return
 
     from paper_2505_11157_amd.workloads import CONFIGS
+    if args.force_band:
+        import torch                       # torch's HIP runtime first: the library must load into that process image
+        torch.cuda.init()
+        import paper_2505_11157_amd as S
+        S.s2_debug_control(S.S2_DEBUG_FORCE_BAND, 0)
 
     traffic = load_traffic()
     m = measure(args.config, args.steps, args.warmup, traffic)

@@ -294,8 +294,11 @@ int s2_grid_device_flags(const s2_grid_t *g, unsigned *flags);
  *   S2_DEBUG_NO_ROW_GROUPS  matrix-core kernels never start a second set of wavefronts per workgroup
  *   S2_DEBUG_FAIL_LAUNCH    the launchers of the tuned neighborhood kernels report failure before launching
  *                           anything: s2_nattn_fwd / s2_nattn_bwd then return S2_ERR_DEVICE
+ *   S2_DEBUG_FORCE_BAND     float32 tensors with d = e = 32 always run on the band-tile matrix-core kernels that
+ *                           serve d = e = 16 and 64 (by default only where the streaming kernels do not apply)
+ *   S2_DEBUG_NO_BAND        the band-tile matrix-core kernels are never used (d = 16, 64: shape-agnostic kernels)
  */
-enum { S2_DEBUG_NO_MFMA = 1, S2_DEBUG_NO_STREAM = 2, S2_DEBUG_NO_ROW_GROUPS = 4, S2_DEBUG_FAIL_LAUNCH = 8 };
+enum { S2_DEBUG_NO_MFMA = 1, S2_DEBUG_NO_STREAM = 2, S2_DEBUG_NO_ROW_GROUPS = 4, S2_DEBUG_FAIL_LAUNCH = 8, S2_DEBUG_FORCE_BAND = 16, S2_DEBUG_NO_BAND = 32 };
 unsigned s2_debug_control(unsigned set_bits, unsigned clear_bits);
 
 /* Message for the last error on the calling thread ("" if none). */

@@ -27,6 +27,8 @@ S2_DEBUG_NO_MFMA = 1
 S2_DEBUG_NO_STREAM = 2
 S2_DEBUG_NO_ROW_GROUPS = 4
 S2_DEBUG_FAIL_LAUNCH = 8
+S2_DEBUG_FORCE_BAND = 16
+S2_DEBUG_NO_BAND = 32
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libs2attn.so")

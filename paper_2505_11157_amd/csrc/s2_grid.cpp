@@ -193,7 +193,7 @@ static int upload_tables(s2_grid *g)
         if (int(done.size()) < ndev) done.resize(ndev, 0);
         if (!done[g->device]) {
             if (s2_nattn_tiled_configure() || s2_nattn_bwd_tiled_configure() || s2_nattn_stream_configure() ||
-                s2_nattn_mfma_configure()) {
+                s2_nattn_mfma_configure() || s2_nattn_band_configure()) {
                 (void)hipGetLastError();
                 return s2_fail(S2_ERR_DEVICE, "raising the LDS limit of a kernel failed");
             }
@@ -598,6 +598,19 @@ extern "C" int s2_grid_init(int grid_type, int nlat_in, int nlon_in, int nlat_ou
         lo = first;
         hi = last + 1;
     };
+    auto rows_ok = [](int n_rows, const std::vector<int> &blo, const std::vector<int> &n) {
+        for (int f = 0; f < n_rows; f += 4) {
+            int rmin = 1 << 30, rmax = -1;
+            for (int r = f; r < std::min(f + 4, n_rows); ++r)
+                if (n[r] > 0) {
+                    rmin = std::min(rmin, blo[r]);
+                    rmax = std::max(rmax, blo[r] + n[r] - 1);
+                }
+            if (rmax - rmin + 1 > 64) return false;
+        }
+        return true;
+    };
+    g->dt.band_rows_ok = rows_ok(nlat_out, g->band_lo, g->band_n) && rows_ok(nlat_in, g->tband_lo, g->tband_n);
     light_range(nlat_out, g->band_lo, g->band_n, g->cnt, g->band_max, g->dt.bl_lo, g->dt.bl_hi);
     light_range(nlat_in, g->tband_lo, g->tband_n, g->tcnt, g->tband_max, g->dt.tbl_lo, g->dt.tbl_hi);
 

@@ -44,6 +44,9 @@ struct S2DeviceTables {
     // arcs are all odd and at most 57 offsets long (0, 0 if the light latitudes do not have that structure);
     // tbl_*: the same for input latitudes and the transposed bands.
     int bl_lo, bl_hi, tbl_lo, tbl_hi;
+    // fp32 band-tile kernels: on both sides the bands of any four consecutive latitudes 4 s .. 4 s + 3 together span
+    // at most 64 rows (a workgroup keeps one row per lane)
+    int band_rows_ok;
     unsigned *dev_flags;      // one word in device memory: bit 0 = a bounded wait inside a kernel ran out
     const int *st_cum;        // [st_hi - st_lo + 1]   running cost of the light latitudes (for equal-work segments)
     const int *tst_cum;       // [tst_hi - tst_lo + 1]
@@ -126,6 +129,7 @@ int s2_nattn_tiled_configure();
 int s2_nattn_bwd_tiled_configure();
 int s2_nattn_stream_configure();
 int s2_nattn_mfma_configure();
+int s2_nattn_band_configure();
 
 // great-circle angle between two points given by their colatitudes and their difference in longitude (float64)
 double s2_great_circle(double colat_a, double colat_b, double dphi);

@@ -27,6 +27,18 @@ extern "C" size_t s2_nattn_bwd_workspace_bytes(const s2_grid_t *g, int batch, in
     return size_t(batch) * heads * g->nlat_out * g->nlon_out * sizeof(float);
 }
 
+// The fp32 band-tile kernels take the head dimensions the hand-tuned d = 32 kernels do not cover, and d = 32 itself on
+// grids whose light latitudes do not have the structure the streaming kernels need (bands of more than nine rows,
+// e.g. the 64 x 128 Gauss grid: measured 0.56 against 0.71 ms per step there, but 3.1 against 2.5 ms on the
+// 129 x 256 grid, where the streaming kernels run).
+static bool use_band(const S2DeviceTables &t, int d, int e)
+{
+    if (!s2_nattn_band_supported(t, d, e) || s2_debug_flag(S2_DEBUG_NO_BAND)) return false;
+    if (d != 32 || s2_debug_flag(S2_DEBUG_FORCE_BAND)) return true;
+    return !(s2_nattn_stream_supported(t, d, e) && s2_nattn_stream_dq_supported(t, d, e) &&
+             s2_nattn_stream_dkdv_supported(t, d, e));
+}
+
 extern "C" int s2_nattn_fwd(const s2_grid_t *g, int batch, int heads, int d_qk, int d_v, int dtype, float scale,
                             const void *q, const void *k, const void *v, void *out, float *lse, void *hip_stream)
 {
@@ -43,7 +55,9 @@ extern "C" int s2_nattn_fwd(const s2_grid_t *g, int batch, int heads, int d_qk, 
         S2_HIP_CHECK(hipGetLastError());
         return S2_OK;
     }
-    auto *fwd = s2_nattn_fwd_tiled_supported(g->dt, d_qk, d_v) ? s2_nattn_fwd_tiled : s2_nattn_fwd_generic;
+    auto *fwd = use_band(g->dt, d_qk, d_v)                       ? s2_nattn_fwd_band
+                : s2_nattn_fwd_tiled_supported(g->dt, d_qk, d_v) ? s2_nattn_fwd_tiled
+                                                                 : s2_nattn_fwd_generic;
     if (fwd(g->dt, batch * heads, d_qk, d_v, scale, static_cast<const float *>(q), static_cast<const float *>(k),
             static_cast<const float *>(v), static_cast<float *>(out), lse, st))
         return s2_fail(S2_ERR_DEVICE, "forward launch configuration failed");
@@ -71,7 +85,9 @@ int s2_nattn_bwd_run(const s2_grid_t *g, int batch, int heads, int d_qk, int d_v
             kv16(g->dt, batch * heads, d_qk, d_v, scale, q, k, v, lse, dout, Dws, dk, dv, st))
             return s2_fail(S2_ERR_DEVICE, "backward launch configuration failed");
     } else {
-        auto *bwd = s2_nattn_bwd_tiled_supported(g->dt, d_qk, d_v) ? s2_nattn_bwd_tiled : s2_nattn_bwd_generic;
+        auto *bwd = use_band(g->dt, d_qk, d_v)                       ? s2_nattn_bwd_band
+                    : s2_nattn_bwd_tiled_supported(g->dt, d_qk, d_v) ? s2_nattn_bwd_tiled
+                                                                     : s2_nattn_bwd_generic;
         if (bwd(g->dt, batch * heads, d_qk, d_v, scale, static_cast<const float *>(q), static_cast<const float *>(k),
                 static_cast<const float *>(v), static_cast<const float *>(out), lse, static_cast<const float *>(dout),
                 static_cast<float *>(dq), static_cast<float *>(dk), static_cast<float *>(dv), Dws, st))

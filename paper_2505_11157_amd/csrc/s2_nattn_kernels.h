@@ -77,6 +77,15 @@ int s2_nattn_bwd_dkdv_bf16(const S2DeviceTables &t, int nbh, int d, int e, float
                            const void *v, const float *lse, const void *go, const float *Dws, void *dk, void *dv,
                            hipStream_t st);
 
+// float32 tensors on the fp32 matrix cores (band tiles of 16 keys x 16 outputs) for head dimensions the hand-tuned
+// kernels do not cover: equal grids, d = e in {16, 32, 64}, longitude count a multiple of 64.
+bool s2_nattn_band_supported(const S2DeviceTables &t, int d, int e);
+int s2_nattn_fwd_band(const S2DeviceTables &t, int nbh, int d, int e, float scale, const float *q, const float *k,
+                      const float *v, float *out, float *lse, hipStream_t st);
+int s2_nattn_bwd_band(const S2DeviceTables &t, int nbh, int d, int e, float scale, const float *q, const float *k,
+                      const float *v, const float *o, const float *lse, const float *go, float *dq, float *dk, float *dv,
+                      float *Dws, hipStream_t st);
+
 // Backward with the scratch for D_i given as a device pointer (checks and dispatch behind both C entry points).
 int s2_nattn_bwd_run(const s2_grid_t *g, int batch, int heads, int d_qk, int d_v, int dtype, float scale,
                      const void *q, const void *k, const void *v, const void *out, const float *lse, const void *dout,

@@ -39,6 +39,12 @@ CONFIGS = {
     # neighborhood path, measured as a secondary workload
     7: dict(kind="nattn", grid_type=EQUIANGULAR, nlat_in=129, nlon_in=256, nlat_out=129, nlon_out=256,
             theta=4 * math.pi / 128, batch=4, heads=8, d=32, dtype="bf16"),
+    # workload 3 with other head dimensions (the paper's models vary the head width, App. C): the fp32 band-tile
+    # matrix-core kernels
+    8: dict(kind="nattn", grid_type=EQUIANGULAR, nlat_in=129, nlon_in=256, nlat_out=129, nlon_out=256,
+            theta=4 * math.pi / 128, batch=4, heads=8, d=16, dtype="f32"),
+    9: dict(kind="nattn", grid_type=EQUIANGULAR, nlat_in=129, nlon_in=256, nlat_out=129, nlon_out=256,
+            theta=4 * math.pi / 128, batch=4, heads=8, d=64, dtype="f32"),
 }
 
 

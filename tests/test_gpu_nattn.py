@@ -252,8 +252,20 @@ def test_one_wave_kernels_on_streaming_shapes():
     with debug_switches(S.S2_DEBUG_NO_MFMA | S.S2_DEBUG_NO_STREAM):
         run_case(c, arrs, [0, 2], case="edge11-no-mfma-no-stream")
     c, arrs = make_inputs(2)
-    with debug_switches(S.S2_DEBUG_NO_ROW_GROUPS):
+    with debug_switches(S.S2_DEBUG_NO_ROW_GROUPS | S.S2_DEBUG_NO_BAND):
         run_case(c, arrs, [3], case="cfg2-no-row-groups")
+
+
+def test_tuned_kernels_where_band_tiles_are_the_default():
+    # equal grids with d = 32 whose light latitudes lack the streaming structure run on the band-tile matrix-core
+    # kernels by default; S2_DEBUG_NO_BAND keeps them on the matrix-core + one-wavefront kernels tuned for d = 32
+    # (what such shapes ran on before, and still run on when the longitude count is not a multiple of 64)
+    with debug_switches(S.S2_DEBUG_NO_BAND):
+        c, arrs = make_inputs(2)
+        run_case(c, arrs, range(c["batch"] * c["heads"]), case="cfg2-no-band")
+        for i in (10, 15):
+            c, arrs = make_inputs(SMALL[i], seed=40 + i)
+            run_case(c, arrs, [0, 1], case="edge%d-no-band" % i)
 
 
 def test_launcher_failure_is_reported():
