@@ -324,12 +324,13 @@ nattn_fwd_band(S2DeviceTables t, int nbh, float c2, const float *__restrict__ q,
                     l[o] += x[rr];
                 }
                 const float *vp = Vc + n * G::PITCH + 4 * ((n >> 2) & 3) + col0 + 4 * g;
+                f32x4 va[D / 16];
 #pragma unroll
-                for (int mt = 0; mt < D / 16; ++mt) {
-                    const f32x4 va = *reinterpret_cast<const f32x4 *>(vp + mt * 16 * G::PITCH);
+                for (int mt = 0; mt < D / 16; ++mt) va[mt] = *reinterpret_cast<const f32x4 *>(vp + mt * 16 * G::PITCH);
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) acc[o][mt] = mfma4(va[j], x[j], acc[o][mt]);
-                }
+                for (int j = 0; j < 4; ++j)          // consecutive instructions belong to different accumulators
+#pragma unroll
+                    for (int mt = 0; mt < D / 16; ++mt) acc[o][mt] = mfma4(va[mt][j], x[j], acc[o][mt]);
             }
         }
     }
@@ -462,12 +463,13 @@ nattn_bwd_dq_band(S2DeviceTables t, int nbh, float scale, const float *__restric
                     for (int rr = 0; rr < 4; ++rr) ds[rr] = keep[rr] ? ds[rr] : 0.f;
                 }
                 const float *kq = Kc + n * G::PITCH + 4 * ((n >> 2) & 3) + col0 + 4 * g;
+                f32x4 ka[D / 16];
 #pragma unroll
-                for (int mt = 0; mt < D / 16; ++mt) {
-                    const f32x4 ka = *reinterpret_cast<const f32x4 *>(kq + mt * 16 * G::PITCH);
+                for (int mt = 0; mt < D / 16; ++mt) ka[mt] = *reinterpret_cast<const f32x4 *>(kq + mt * 16 * G::PITCH);
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) acc[o][mt] = mfma4(ka[j], ds[j], acc[o][mt]);
-                }
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int mt = 0; mt < D / 16; ++mt) acc[o][mt] = mfma4(ka[mt][j], ds[j], acc[o][mt]);
             }
         }
     }
@@ -602,16 +604,19 @@ nattn_bwd_dkdv_band(S2DeviceTables t, int nbh, float scale, const float *__restr
                     }
                 }
                 const float *gq = Gc + n * G::PITCH + 4 * ((n >> 2) & 3) + col0 + 4 * g, *qq = Qc + n * G::PITCH + 4 * ((n >> 2) & 3) + col0 + 4 * g;
+                f32x4 ga[D / 16], qa[D / 16];
 #pragma unroll
                 for (int mt = 0; mt < D / 16; ++mt) {
-                    const f32x4 ga = *reinterpret_cast<const f32x4 *>(gq + mt * 16 * G::PITCH);
-                    const f32x4 qa = *reinterpret_cast<const f32x4 *>(qq + mt * 16 * G::PITCH);
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        adv[o][mt] = mfma4(ga[j], pr[j], adv[o][mt]);
-                        adk[o][mt] = mfma4(qa[j], ds[j], adk[o][mt]);
-                    }
+                    ga[mt] = *reinterpret_cast<const f32x4 *>(gq + mt * 16 * G::PITCH);
+                    qa[mt] = *reinterpret_cast<const f32x4 *>(qq + mt * 16 * G::PITCH);
                 }
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int mt = 0; mt < D / 16; ++mt) {
+                        adv[o][mt] = mfma4(ga[mt][j], pr[j], adv[o][mt]);
+                        adk[o][mt] = mfma4(qa[mt][j], ds[j], adk[o][mt]);
+                    }
             }
         }
     }
