@@ -303,7 +303,7 @@ def main():
     if not args.no_workloads and args.config == 3:
         # the other full-size workloads, same measurement with fewer steps (a few hundred ms of GPU time in all)
         others = {}
-        for cfg in (2, 4, 5, 7):
+        for cfg in (2, 4, 5, 7, 8, 9):
             if cfg not in CONFIGS:
                 continue
             o = measure(cfg, max(args.steps // 2, 5), max(args.warmup, 2), traffic)
