@@ -229,6 +229,68 @@ def measure(cfg, steps, warmup, traffic):
             "units": units, "P": P, "roofline": roof, "kernels": kernels, "is_global": is_global}
 
 
+def measure_layers(steps):
+    """Forward + backward of the two layers built around the kernels (Sec. 3.4, App. B.3) on the 129x256 grid of the
+    headline workload, timed with HIP events on the launch stream: reported as they stand (no roofline: a chain of
+    norm, projection, attention and split-K launches)."""
+    import torch
+
+    import paper_2505_11157_amd as S
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device="cpu").manual_seed(7)
+    rnd = lambda *shape: torch.randn(*shape, generator=gen).to(dev)
+    nlat, nlon, theta, B = 129, 256, 4 * math.pi / 128, 4
+    g = S.s2_grid_init(0, nlat, nlon, nlat, nlon, theta)
+
+    def ev_time(fn, n):
+        fn()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(n):
+            fn()
+        b.record()
+        b.synchronize()
+        return a.elapsed_time(b) / n
+
+    out = {}
+    # attention sub-block with the head width of the SegFormer stages of App. C (embedding 128, 8 heads of 16)
+    C, H = 128, 8
+    x, dy = rnd(B, C, nlat, nlon), rnd(B, C, nlat, nlon)
+    params = {"gamma": rnd(C), "beta": rnd(C), "pos": rnd(C, nlat, nlon)}
+    for n in "qkvo":
+        params["W" + n] = rnd(C, C) / math.sqrt(C)
+        params["b" + n] = rnd(C)
+    state = {}
+
+    def mha_fwd():
+        state["y"], state["ws"] = S.s2_mha_fwd(g, x, params, H)
+
+    def mha_bwd():
+        S.s2_mha_bwd(g, x, params, H, dy, state["ws"])
+
+    t_f = ev_time(mha_fwd, steps)
+    t_b = ev_time(mha_bwd, steps)
+    out["mha"] = {"workload": "attention sub-block 129x256 B%d C%d heads%d d%d f32" % (B, C, H, C // H), "ms_fwd": t_f,
+                  "ms_bwd": t_b, "ms_per_step": t_f + t_b}
+    # DISCO convolution, 64 -> 64 channels, 9 radial basis functions, same grid
+    cin = cout = 64
+    dc = S.s2_disco_init(g, 9)
+    xd, dyd = rnd(B, cin, nlat, nlon), rnd(B, cout, nlat, nlon)
+    w, bias = rnd(cout, cin, 9) / math.sqrt(9 * cin), rnd(cout)
+
+    def disco_fwd():
+        state["yd"], state["wsd"] = S.s2_disco_fwd(dc, xd, w, bias)
+
+    def disco_bwd():
+        S.s2_disco_bwd(dc, xd, w, dyd, state["wsd"])
+
+    t_f = ev_time(disco_fwd, steps)
+    t_b = ev_time(disco_bwd, steps)
+    out["disco"] = {"workload": "DISCO convolution 129x256 B%d %d->%d channels K9 f32" % (B, cin, cout), "ms_fwd": t_f,
+                    "ms_bwd": t_b, "ms_per_step": t_f + t_b}
+    return out
+
+
 def cpu_baseline(m, cpu_slices):
     """The oracle as it stands, timed on the host cores on a bounded sample of the same workload."""
     import numpy as np
@@ -316,6 +378,7 @@ def main():
                 "step_frac": r["step"]["step_frac"], "hbm_frac": r["step"]["hbm_frac"],
                 "kernels_ms": {n: kk["ms"] for n, kk in o["kernels"].items()}}
         res["workloads"] = others
+        res["layers"] = measure_layers(5)
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(m, args.cpu_slices)
     print(json.dumps(res))

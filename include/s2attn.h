@@ -234,7 +234,7 @@ int s2_mha_bwd(const s2_grid_t *g, int batch, int channels, int heads, float eps
  * with psi_k = hat_k(r) * omega[h'], r the geodesic distance of the input point from the output point and
  * hat_k(r) = max(0, 1 - |r * nbasis / theta_cutoff - k|), k = 0 .. nbasis-1 (piecewise-linear, isotropic; the paper
  * leaves the basis open).  s2_disco_init tabulates psi in float64 on the host for the handle's grids (equal grids or
- * downsampling; upsampling handles: S2_ERR_UNSUPPORTED); nbasis in [1, 8].  The disco handle refers to the grid
+ * downsampling; upsampling handles: S2_ERR_UNSUPPORTED); nbasis in [1, 16].  The disco handle refers to the grid
  * handle, which must outlive it; release with s2_disco_destroy.
  * Layouts (contiguous float32, device): x [batch][cin][nlat_in][nlon_in], y, dy [batch][cout][nlat_out][nlon_out],
  * weight [cout][cin][nbasis], bias [cout] (may be NULL).  s2_disco_bwd writes dx and, where the pointers are not

@@ -23,7 +23,7 @@ struct s2_disco {
 
 namespace {
 
-constexpr int kMaxBasis = 8;
+constexpr int kMaxBasis = 16;     // a 4 x 4 planar kernel's worth of basis functions (App. C)
 
 __device__ __forceinline__ int wrapn(int x, int n)
 {
@@ -117,6 +117,7 @@ void by_basis(int K, F f)
 {
     if (K <= 2) f(std::integral_constant<int, 2>());
     else if (K <= 4) f(std::integral_constant<int, 4>());
+    else if (K <= 8) f(std::integral_constant<int, 8>());
     else f(std::integral_constant<int, kMaxBasis>());
 }
 
@@ -127,7 +128,7 @@ extern "C" int s2_disco_init(const s2_grid_t *g, int nbasis, s2_disco_t **out)
     if (!out) return s2_fail(S2_ERR_INVALID_ARG, "out is NULL");
     *out = nullptr;
     if (!g) return s2_fail(S2_ERR_INVALID_ARG, "grid is NULL");
-    if (nbasis < 1 || nbasis > kMaxBasis) return s2_fail(S2_ERR_INVALID_ARG, "nbasis must lie in [1, 8]");
+    if (nbasis < 1 || nbasis > kMaxBasis) return s2_fail(S2_ERR_INVALID_ARG, "nbasis must lie in [1, 16]");
     if (g->upscale > 1) return s2_fail(S2_ERR_UNSUPPORTED, "the DISCO convolution covers equal grids and downsampling");
     s2_disco *dc = new (std::nothrow) s2_disco();
     if (!dc) return s2_fail(S2_ERR_ALLOC, "out of host memory");

@@ -46,12 +46,15 @@ def close(x, ref, what, case, abs_sum=None):
 
 
 MHA_CASES = [
-    # (grid, batch, channels, heads): d = 16 runs the shape-agnostic attention kernels, d = 32 on 192 / 256
-    # longitudes the matrix-core and streaming ones; 48 channels leave the 128 x 128 tiles of the channel matrices ragged
+    # (grid, batch, channels, heads): d = 16 on 32 / 48 longitudes runs the shape-agnostic attention kernels, d = 32 on
+    # 192 / 256 longitudes the matrix-core and streaming ones, d = 16 and 64 on 192 / 128 longitudes the fp32 band
+    # tiles; 48 channels leave the 128 x 128 tiles of the channel matrices ragged
     (dict(grid_type=0, nlat_in=17, nlon_in=32, nlat_out=17, nlon_out=32, theta=0.5), 2, 32, 2),
     (dict(grid_type=1, nlat_in=16, nlon_in=48, nlat_out=16, nlon_out=48, theta=0.4), 1, 48, 3),
     (dict(grid_type=0, nlat_in=33, nlon_in=192, nlat_out=33, nlon_out=192, theta=0.3), 2, 64, 2),
     (dict(grid_type=0, nlat_in=25, nlon_in=256, nlat_out=25, nlon_out=256, theta=0.25), 1, 160, 5),
+    (dict(grid_type=0, nlat_in=33, nlon_in=192, nlat_out=33, nlon_out=192, theta=0.3), 1, 48, 3),
+    (dict(grid_type=1, nlat_in=16, nlon_in=128, nlat_out=16, nlon_out=128, theta=0.45), 1, 128, 2),
 ]
 
 
@@ -139,6 +142,9 @@ DISCO_CASES = [
     (dict(grid_type=2, nlat_in=16, nlon_in=32, nlat_out=16, nlon_out=32, theta=0.45), 1, 4, 4, 16),
     (dict(grid_type=1, nlat_in=24, nlon_in=48, nlat_out=24, nlon_out=48, theta=0.35), 2, 2, 8, 48),
     (dict(grid_type=0, nlat_in=9, nlon_in=80, nlat_out=9, nlon_out=16, theta=0.6), 1, 16, 1, 16),     # pscale 5
+    # 9 and 16 basis functions: the counts the paper pairs with 3 x 3 and 4 x 4 planar kernels (App. C)
+    (dict(grid_type=0, nlat_in=17, nlon_in=32, nlat_out=17, nlon_out=32, theta=0.5), 1, 16, 9, 16),
+    (dict(grid_type=1, nlat_in=16, nlon_in=32, nlat_out=8, nlon_out=16, theta=0.6), 2, 2, 16, 16),
 ]
 
 
@@ -177,7 +183,7 @@ def test_disco_errors():
     assert ei.value.code == S.S2_ERR_UNSUPPORTED
     g = S.s2_grid_init(0, 17, 32, 17, 32, 0.5)
     with pytest.raises(S.S2Error) as ei:
-        S.s2_disco_init(g, 9)
+        S.s2_disco_init(g, 17)
     assert ei.value.code == S.S2_ERR_INVALID_ARG
     dc = S.s2_disco_init(g, 3)
     dev = torch.device("cuda:0")
