@@ -226,8 +226,8 @@ __device__ __forceinline__ bool xcd_unit(int nunits, int &unit)
 // Forward.  A workgroup owns 128 queries of one slice (one 32-query MFMA tile per wavefront) and streams
 // the keys in stages of 64.  omega enters as a factor, not as a bias: V^T arrives premultiplied by
 // w_j = omega_j / max omega (prepare_operands does that), the running sum is l_i = sum_j w_j 2^(x_ij - m_i)
-// with x = log2(e) scale q.k, and the reference m_i follows the bare logits (it moves only when a logit
-// exceeds it by more than 2^8).  lse_i = ln 2 (m_i + log2 l_i) + ln max omega.
+// with x = log2(e) scale q.k, and the reference m_i follows the bare logits of the keys of positive weight (it moves
+// only when a logit exceeds it by more than 2^8).  lse_i = ln 2 (m_i + log2 l_i) + ln max omega.
 // UNIFORM_W: the longitude count is a multiple of 32, so a 32-key tile never straddles two latitudes.
 template <bool UNIFORM_W>
 __global__ void __launch_bounds__(256, 3)
@@ -260,19 +260,44 @@ global_fwd(const bf16raw *__restrict__ q, const bf16raw *__restrict__ k, const b
         copy_col_tile(vb, 64 * st, Npad, buf + kTileBytes, wave, lane);
         if (wave == 0) copy_floats(wtok + 64 * st, buf + 2 * kTileBytes, lane);
     };
+    bool started = false;      // has a tile with a key of positive weight been seen (wavefront-uniform)
     auto stage = [&](const char *cur, char *nxt, int st) {
         if (st + 1 < nst) request(nxt, st + 1);
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt) {
+            // Keys of weight zero (the pole row of the grid of App. A.1, the padding behind the last token) have no
+            // term in the sums, so they must not enter the reference maximum either: a tile without a live key is
+            // skipped, and in a mixed tile (longitude count not a multiple of 32) their logits are set to -inf.
+            const float *wp = reinterpret_cast<const float *>(cur + 2 * kTileBytes) + 32 * kt + 16 * hl;
+            float wk[16];
+            bool live;
+            if (UNIFORM_W) {
+                live = __builtin_amdgcn_readfirstlane(__float_as_int(wp[0])) != 0;
+            } else {
+                bool any = false;
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const float4 w = *reinterpret_cast<const float4 *>(wp + 4 * g);
+                    wk[4 * g + 0] = w.x; wk[4 * g + 1] = w.y; wk[4 * g + 2] = w.z; wk[4 * g + 3] = w.w;
+                    any |= w.x > 0.f || w.y > 0.f || w.z > 0.f || w.w > 0.f;
+                }
+                live = __any(any);
+            }
+            if (!live) continue;
             f32x16 s = {0};
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) s = mfma(row_operand(cur, col, hl, kt, ks), qop[ks], s);
             float x[16];
             float mx = -INFINITY;
 #pragma unroll
-            for (int i = 0; i < 16; ++i) { x[i] = fmaf(s[i], c2, -m); mx = fmaxf(mx, x[i]); }
+            for (int i = 0; i < 16; ++i) {
+                x[i] = fmaf(s[i], c2, -m);
+                if (!UNIFORM_W) x[i] = wk[i] > 0.f ? x[i] : -INFINITY;
+                mx = fmaxf(mx, x[i]);
+            }
             // the two half-wavefronts of a query exchange their maxima only when the reference has to move
-            const bool first = st == 0 && kt == 0;
+            const bool first = !started;
+            started = true;
             if (first || __any(mx > 8.f)) {
                 mx = fmaxf(mx, __shfl_xor(mx, 32));
                 const float delta = first ? mx : (mx > 8.f ? mx : 0.f);
@@ -282,7 +307,6 @@ global_fwd(const bf16raw *__restrict__ q, const bf16raw *__restrict__ k, const b
 #pragma unroll
                 for (int i = 0; i < 16; ++i) { o0[i] *= corr; o1[i] *= corr; x[i] -= delta; }
             }
-            const float *wp = reinterpret_cast<const float *>(cur + 2 * kTileBytes) + 32 * kt + 16 * hl;
             if (UNIFORM_W) {
                 // all 32 keys of the tile lie on one latitude: one weight for the whole tile
                 float psum = 0.f;
@@ -291,12 +315,9 @@ global_fwd(const bf16raw *__restrict__ q, const bf16raw *__restrict__ k, const b
                 l = fmaf(psum, wp[0], l);
             } else {
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const float4 w = *reinterpret_cast<const float4 *>(wp + 4 * g);
-                    x[4 * g + 0] = __builtin_amdgcn_exp2f(x[4 * g + 0]); l = fmaf(x[4 * g + 0], w.x, l);
-                    x[4 * g + 1] = __builtin_amdgcn_exp2f(x[4 * g + 1]); l = fmaf(x[4 * g + 1], w.y, l);
-                    x[4 * g + 2] = __builtin_amdgcn_exp2f(x[4 * g + 2]); l = fmaf(x[4 * g + 2], w.z, l);
-                    x[4 * g + 3] = __builtin_amdgcn_exp2f(x[4 * g + 3]); l = fmaf(x[4 * g + 3], w.w, l);
+                for (int i = 0; i < 16; ++i) {
+                    x[i] = __builtin_amdgcn_exp2f(x[i]);
+                    l = fmaf(x[i], wk[i], l);
                 }
             }
 #pragma unroll
@@ -422,14 +443,17 @@ global_bwd_dkdv(const bf16raw *__restrict__ q, const bf16raw *__restrict__ k, co
     }
     if (ki < N) {
         const float wk = wtok[ki], wks = wk * scale;
+        const bool live = wk > 0.f;
         bf16raw *dkb = dk + (size_t(bh) * N + ki) * kD + 4 * hl, *dvb = dv + (size_t(bh) * N + ki) * kD + 4 * hl;
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
             bf16x4 a, b, c, d;
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                a[u] = (__bf16)(dk0[4 * g + u] * wks); b[u] = (__bf16)(dk1[4 * g + u] * wks);
-                c[u] = (__bf16)(dv0[4 * g + u] * wk); d[u] = (__bf16)(dv1[4 * g + u] * wk);
+                // a key of weight zero gets exactly zero (its unweighted sums may have overflowed: its logits are not
+                // bounded by any logsumexp)
+                a[u] = (__bf16)(live ? dk0[4 * g + u] * wks : 0.f); b[u] = (__bf16)(live ? dk1[4 * g + u] * wks : 0.f);
+                c[u] = (__bf16)(live ? dv0[4 * g + u] * wk : 0.f); d[u] = (__bf16)(live ? dv1[4 * g + u] * wk : 0.f);
             }
             *reinterpret_cast<bf16x4 *>(dkb + 8 * g) = a;
             *reinterpret_cast<bf16x4 *>(dkb + 32 + 8 * g) = b;
@@ -442,6 +466,11 @@ global_bwd_dkdv(const bf16raw *__restrict__ q, const bf16raw *__restrict__ k, co
 // Query side: a workgroup owns 128 queries and streams the keys in stages of 64: K and V token-major
 // (S^T = K Q^T and dP^T = V dout^T land with lane = query, registers = 16 keys) and w K^T channel-major
 // (dQ^T += (w K)^T dSt^T).
+// DEAD: some keys have weight zero (a pole row of weight zero, padding behind the last token).  Their logits are not
+// bounded by the logsumexp, so 2^(x - L) may overflow and inf * (w k = 0) would poison dq: the exponent is capped at
+// 100 there (a key of positive weight stays below log2(max omega / omega_j), a few tens at most), which keeps the
+// factor finite and the product with the zero row exactly zero.
+template <bool DEAD>
 __global__ void __launch_bounds__(256, 3)
 global_bwd_dq(const bf16raw *__restrict__ q, const bf16raw *__restrict__ k, const bf16raw *__restrict__ v,
               const bf16raw *__restrict__ go, const bf16raw *__restrict__ ktw, const float *__restrict__ L2,
@@ -488,7 +517,10 @@ global_bwd_dq(const bf16raw *__restrict__ q, const bf16raw *__restrict__ k, cons
             }
             float ds[16];
 #pragma unroll
-            for (int i = 0; i < 16; ++i) ds[i] = __builtin_amdgcn_exp2f(fmaf(s[i], c2, -Lq)) * dp[i];
+            for (int i = 0; i < 16; ++i) {
+                const float a = fmaf(s[i], c2, -Lq);
+                ds[i] = __builtin_amdgcn_exp2f(DEAD ? fminf(a, 100.f) : a) * dp[i];
+            }
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
                 const bf16x8 sb = pack8(ds + 8 * j);
@@ -633,7 +665,9 @@ extern "C" int s2_attn_global_bwd(const s2_grid_t *g, int batch, int heads, int 
                        static_cast<bf16raw *>(dk), static_cast<bf16raw *>(dv), N, Npad, nblk, nunits, c2, scale);
     }
     S2TraceScope tr("global_bwd_dq", double(nbh) * N * N, st);
-    hipLaunchKernelGGL(global_bwd_dq, grid, dim3(256), 0, st, static_cast<const bf16raw *>(q),
+    const bool dead = Npad != N || !g->zero_lat.empty();      // keys of weight zero exist
+    auto dq_kernel = dead ? global_bwd_dq<true> : global_bwd_dq<false>;
+    hipLaunchKernelGGL(dq_kernel, grid, dim3(256), 0, st, static_cast<const bf16raw *>(q),
                        static_cast<const bf16raw *>(k), static_cast<const bf16raw *>(v),
                        static_cast<const bf16raw *>(dout), kt, L2, Dv, static_cast<bf16raw *>(dq), N, Npad, nblk,
                        nunits, c2, scale);

@@ -145,6 +145,29 @@ def test_global_large_logits_and_negative_scale():
     run_global(0, nlat, nlon, B, H, arrs, range(B * H), scale=-0.125)
 
 
+@pytest.mark.parametrize("nlat,nlon", [(16, 64), (12, 48), (9, 24)])
+def test_global_zero_weight_keys_stay_out_of_the_maximum(nlat, nlon):
+    # Keys of weight zero have no term in the sums (App. B.1), so the result must not depend on their logits:
+    #  * grid of App. A.1 (pole row of weight zero) with pole keys whose logits exceed all others by hundreds of
+    #    units: with those logits inside the running maximum every real term would underflow (l = 0, NaN);
+    #  * the padding behind the last token (9 x 24 = 216 tokens, staged as 256) with all real logits near -280.
+    # Longitude counts 64 (a 32-key tile lies on one latitude), 48 and 24 (mixed tiles).
+    rng = np.random.default_rng(31)
+    B, H, N = 1, 2, nlat * nlon
+    q, k, v, dout = (round_to_bf16(rng.standard_normal((B * H, N, 64)).astype(np.float32)) for _ in range(4))
+    k[:, :nlon] = round_to_bf16(40.0 * np.sign(q[:, :nlon]).astype(np.float32))      # q.k of the order of +2000 on the pole row
+    run_global(2, nlat, nlon, B, H, [q, k, v, dout], range(B * H), case="pole-keys-%dx%d" % (nlat, nlon))
+    flat = round_to_bf16(np.full((B * H, N, 64), 1.25, np.float32))
+    g = S.s2_grid_init(0, nlat, nlon, nlat, nlon, math.pi)
+    dev = torch.device("cuda:0")
+    fold = lambda a: torch.from_numpy(a).to(dev).reshape(B, H, N, 64).to(torch.bfloat16).contiguous()
+    out, lse = S.s2_attn_global_fwd(g, fold(flat), fold(flat), fold(v), -2.0)         # every logit = -200
+    torch.cuda.synchronize()
+    r_out, r_lse = O.global_fwd(0, nlat, nlon, flat.astype(np.float64), flat.astype(np.float64), v.astype(np.float64), -2.0)
+    _close(lse.reshape(B * H, N).cpu().numpy().astype(np.float64), r_lse, "lse", case="flat-%dx%d" % (nlat, nlon), f32=True)
+    _close(out.float().reshape(B * H, N, 64).cpu().numpy().astype(np.float64), r_out, "out", case="flat-%dx%d" % (nlat, nlon))
+
+
 def test_global_hip_graph_replays_match_eager():
     # forward + backward only enqueue kernels (the preparation pass, then the three matrix-core launches): a captured
     # graph must reproduce the eager results bit for bit on every replay, with new inputs in between
