@@ -1,6 +1,6 @@
 // Neighborhood attention (Sec. 3.3, eq. (9)-(10); gradients App. B.4) on the fp32 matrix cores for head dimensions
 // other than the hand-tuned 32: band tiles of 16 keys x 16 outputs on v_mfma_f32_16x16x4_f32, float32 throughout.
-// Equal grids, d = e in {16, 32, 64}, longitude count a multiple of 64.
+// Equal grids, d = e in {16, 32, 64}, longitude count a multiple of 16 (at least 64).
 //
 // Structure.  A workgroup of four wavefronts owns OW = 16 NO consecutive longitudes of FOUR consecutive latitudes, one
 // latitude per wavefront (forward and dq: output latitudes; dk/dv: input latitudes, walking the transposed
@@ -222,7 +222,7 @@ nattn_fwd_band(S2DeviceTables t, int nbh, float c2, const float *__restrict__ q,
     using G = Geo<D, NO>;
     extern __shared__ __attribute__((aligned(16))) float lds[];
     float *Kc = lds, *Vc = lds + G::TILE;
-    const int nlon = t.nlon_in, ngrp = nlon / G::OW, nseg = (t.nlat_out + 3) >> 2;
+    const int nlon = t.nlon_in, ngrp = (nlon + G::OW - 1) / G::OW, nseg = (t.nlat_out + 3) >> 2;
     int id = blockIdx.x;
     const int grp = id % ngrp; id /= ngrp;
     const int bh = id % nbh, seg = segment_of(id / nbh, nseg);
@@ -239,9 +239,10 @@ nattn_fwd_band(S2DeviceTables t, int nbh, float c2, const float *__restrict__ q,
     float m[NO], l[NO];
 #pragma unroll
     for (int o = 0; o < NO; ++o) {
+        const bool own = active && W0 + 16 * o < nlon;      // the last group of a latitude may be ragged (by whole tiles)
 #pragma unroll
         for (int kb = 0; kb < D / 4; ++kb)
-            qreg[o][kb] = active ? qs[size_t(4 * kb + g) * plane + size_t(h) * nlon + (W0 + 16 * o + n)] : 0.f;
+            qreg[o][kb] = own ? qs[size_t(4 * kb + g) * plane + size_t(h) * nlon + (W0 + 16 * o + n)] : 0.f;
 #pragma unroll
         for (int mt = 0; mt < D / 16; ++mt) acc[o][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
         m[o] = kMinRef;
@@ -285,6 +286,7 @@ nattn_fwd_band(S2DeviceTables t, int nbh, float c2, const float *__restrict__ q,
         const int Xlim = min(Xst + G::SW + (now.multi ? 0 : 32), now.Xend);
 #pragma unroll
         for (int o = 0; o < NO; ++o) {
+            if (W0 + 16 * o >= nlon) break;
             const int Wo = Wb + 16 * o;
             const int T0 = now.multi ? Xst : (Wo - hw) & ~3;
             const int Tend = now.multi ? Xlim : Wo + 16 + hw;
@@ -337,6 +339,7 @@ nattn_fwd_band(S2DeviceTables t, int nbh, float c2, const float *__restrict__ q,
     if (!active) return;
 #pragma unroll
     for (int o = 0; o < NO; ++o) {
+        if (W0 + 16 * o >= nlon) break;
         const float lt = group_sum(l[o]);
         const float inv = 1.f / lt;
         const size_t at = size_t(h) * nlon + (W0 + 16 * o + n);
@@ -360,7 +363,7 @@ nattn_bwd_dq_band(S2DeviceTables t, int nbh, float scale, const float *__restric
     using G = Geo<D, NO>;
     extern __shared__ __attribute__((aligned(16))) float lds[];
     float *Kc = lds, *Vc = lds + G::TILE;
-    const int nlon = t.nlon_in, ngrp = nlon / G::OW, nseg = (t.nlat_out + 3) >> 2;
+    const int nlon = t.nlon_in, ngrp = (nlon + G::OW - 1) / G::OW, nseg = (t.nlat_out + 3) >> 2;
     int id = blockIdx.x;
     const int grp = id % ngrp; id /= ngrp;
     const int bh = id % nbh, seg = segment_of(id / nbh, nseg);
@@ -385,15 +388,16 @@ nattn_bwd_dq_band(S2DeviceTables t, int nbh, float scale, const float *__restric
         Dn[o] = 0.f;
         float dsum = 0.f;
         const size_t at = size_t(h) * nlon + (W0 + 16 * o + n);
+        const bool own = active && W0 + 16 * o < nlon;
 #pragma unroll
         for (int kb = 0; kb < D / 4; ++kb) {
             const size_t e = size_t(4 * kb + g) * plane + at;
-            qreg[o][kb] = active ? qs[e] : 0.f;
-            greg[o][kb] = active ? gs[e] : 0.f;
-            dsum = fmaf(greg[o][kb], active ? os[e] : 0.f, dsum);
+            qreg[o][kb] = own ? qs[e] : 0.f;
+            greg[o][kb] = own ? gs[e] : 0.f;
+            dsum = fmaf(greg[o][kb], own ? os[e] : 0.f, dsum);
         }
         dsum = group_sum(dsum);
-        if (active) {
+        if (own) {
             if (g == 0) Dws[size_t(bh) * plane + at] = dsum;
             Dn[o] = -dsum;
             L2[o] = (lse[size_t(bh) * plane + at] - t.ln_omega_ref) * kLog2e;
@@ -437,6 +441,7 @@ nattn_bwd_dq_band(S2DeviceTables t, int nbh, float scale, const float *__restric
         const int Xlim = min(Xst + G::SW + (now.multi ? 0 : 32), now.Xend);
 #pragma unroll
         for (int o = 0; o < NO; ++o) {
+            if (W0 + 16 * o >= nlon) break;
             const int Wo = Wb + 16 * o;
             const int T0 = now.multi ? Xst : (Wo - hw) & ~3;
             const int Tend = now.multi ? Xlim : Wo + 16 + hw;
@@ -476,6 +481,7 @@ nattn_bwd_dq_band(S2DeviceTables t, int nbh, float scale, const float *__restric
     if (!active) return;
 #pragma unroll
     for (int o = 0; o < NO; ++o) {
+        if (W0 + 16 * o >= nlon) break;
         float *ob = dq + size_t(bh) * D * plane + size_t(h) * nlon + (W0 + 16 * o + n);
 #pragma unroll
         for (int mt = 0; mt < D / 16; ++mt)
@@ -496,7 +502,7 @@ nattn_bwd_dkdv_band(S2DeviceTables t, int nbh, float scale, const float *__restr
     using G = Geo<D, NO>;
     extern __shared__ __attribute__((aligned(16))) float lds[];
     float *Qc = lds, *Gc = lds + G::TILE, *Ls = lds + 2 * G::TILE, *Dn = Ls + G::COLS;
-    const int nlon = t.nlon_in, ngrp = nlon / G::OW, nseg = (t.nlat_in + 3) >> 2;
+    const int nlon = t.nlon_in, ngrp = (nlon + G::OW - 1) / G::OW, nseg = (t.nlat_in + 3) >> 2;
     int id = blockIdx.x;
     const int grp = id % ngrp; id /= ngrp;
     const int bh = id % nbh, seg = segment_of(id / nbh, nseg);
@@ -521,8 +527,8 @@ nattn_bwd_dkdv_band(S2DeviceTables t, int nbh, float scale, const float *__restr
 #pragma unroll
         for (int kb = 0; kb < D / 4; ++kb) {
             const size_t e = size_t(4 * kb + g) * plane + size_t(hp) * nlon + (W0 + 16 * o + n);
-            kreg[o][kb] = active ? ks[e] : 0.f;
-            vreg[o][kb] = active ? vs[e] : 0.f;
+            kreg[o][kb] = active && W0 + 16 * o < nlon ? ks[e] : 0.f;
+            vreg[o][kb] = active && W0 + 16 * o < nlon ? vs[e] : 0.f;
         }
     }
     BandRows rows;
@@ -572,6 +578,7 @@ nattn_bwd_dkdv_band(S2DeviceTables t, int nbh, float scale, const float *__restr
         const int Xlim = min(Xst + G::SW + (now.multi ? 0 : 32), now.Xend);
 #pragma unroll
         for (int o = 0; o < NO; ++o) {
+            if (W0 + 16 * o >= nlon) break;
             const int Wo = Wb + 16 * o;
             const int T0 = now.multi ? Xst : (Wo - hw) & ~3;
             const int Tend = now.multi ? Xlim : Wo + 16 + hw;
@@ -623,6 +630,7 @@ nattn_bwd_dkdv_band(S2DeviceTables t, int nbh, float scale, const float *__restr
     if (!active) return;
 #pragma unroll
     for (int o = 0; o < NO; ++o) {
+        if (W0 + 16 * o >= nlon) break;
         const size_t at = size_t(bh) * D * plane + size_t(hp) * nlon + (W0 + 16 * o + n);
 #pragma unroll
         for (int mt = 0; mt < D / 16; ++mt)
@@ -657,7 +665,7 @@ int configure_one()
 template <int D, int NO>
 unsigned blocks(const S2DeviceTables &t, int nbh, int nlat)
 {
-    return unsigned(long((nlat + 3) / 4) * nbh * (t.nlon_in / Geo<D, NO>::OW));
+    return unsigned(long((nlat + 3) / 4) * nbh * ((t.nlon_in + Geo<D, NO>::OW - 1) / Geo<D, NO>::OW));
 }
 
 double pair_count(const S2DeviceTables &t, bool fwd_side, int nbh)
@@ -706,7 +714,7 @@ int s2_nattn_band_configure()
 bool s2_nattn_band_supported(const S2DeviceTables &t, int d, int e)
 {
     return d == e && (d == 16 || d == 32 || d == 64) && t.upscale == 1 && t.pscale == 1 && t.nlon_in == t.nlon_out &&
-           t.nlat_in == t.nlat_out && t.nlon_in % 64 == 0 && t.band_rows_ok && !s2_debug_flag(S2_DEBUG_NO_MFMA);
+           t.nlat_in == t.nlat_out && t.nlon_in % 16 == 0 && t.nlon_in >= 64 && t.band_rows_ok && !s2_debug_flag(S2_DEBUG_NO_MFMA);
 }
 
 int s2_nattn_fwd_band(const S2DeviceTables &t, int nbh, int d, int, float scale, const float *q, const float *k,

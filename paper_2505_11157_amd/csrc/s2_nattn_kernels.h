@@ -78,7 +78,7 @@ int s2_nattn_bwd_dkdv_bf16(const S2DeviceTables &t, int nbh, int d, int e, float
                            hipStream_t st);
 
 // float32 tensors on the fp32 matrix cores (band tiles of 16 keys x 16 outputs) for head dimensions the hand-tuned
-// kernels do not cover: equal grids, d = e in {16, 32, 64}, longitude count a multiple of 64.
+// kernels do not cover: equal grids, d = e in {16, 32, 64}, longitude count a multiple of 16 (at least 64).
 bool s2_nattn_band_supported(const S2DeviceTables &t, int d, int e);
 int s2_nattn_fwd_band(const S2DeviceTables &t, int nbh, int d, int e, float scale, const float *q, const float *k,
                       const float *v, float *out, float *lse, hipStream_t st);

@@ -25,6 +25,8 @@ def _c(grid_type, nlat, nlon, theta, batch, heads, d):
 SHAPES = [
     (0, 17, 64, 0.9), (0, 33, 192, 0.3), (1, 16, 128, 0.45), (0, 41, 256, 4 * math.pi / 40), (1, 3, 64, 0.7),
     (2, 32, 128, 0.4), (0, 9, 64, math.pi), (0, 9, 256, 0.5), (3, 33, 128, 0.35), (0, 65, 256, 2 * math.pi / 64),
+    # longitude counts that leave the last group of a latitude ragged (16, 16 and 48 owners of 64; 16 of 32 at d = 64)
+    (0, 21, 80, 0.5), (1, 18, 144, 0.3), (0, 25, 240, 0.2),
 ]
 
 
