@@ -39,6 +39,13 @@ static bool use_band(const S2DeviceTables &t, int d, int e)
              s2_nattn_stream_dkdv_supported(t, d, e));
 }
 
+// bf16 tensors: what the bf16 matrix-core kernels (d = 32, longitude count a multiple of 64) do not cover goes to the
+// fp32 band tiles with bf16 loads and stores where those apply.
+static bool band_bf16(const S2DeviceTables &t, int d, int e)
+{
+    return s2_nattn_band_supported(t, d, e) && !s2_debug_flag(S2_DEBUG_NO_BAND);
+}
+
 extern "C" int s2_nattn_fwd(const s2_grid_t *g, int batch, int heads, int d_qk, int d_v, int dtype, float scale,
                             const void *q, const void *k, const void *v, void *out, float *lse, void *hip_stream)
 {
@@ -49,7 +56,9 @@ extern "C" int s2_nattn_fwd(const s2_grid_t *g, int batch, int heads, int d_qk, 
         return s2_fail(S2_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     if (dtype == S2_BF16) {
-        auto *fwd16 = s2_nattn_bf16_supported(g->dt, d_qk, d_v) ? s2_nattn_fwd_bf16 : s2_nattn_fwd_generic_bf16;
+        auto *fwd16 = s2_nattn_bf16_supported(g->dt, d_qk, d_v) ? s2_nattn_fwd_bf16
+                      : band_bf16(g->dt, d_qk, d_v)             ? s2_nattn_fwd_band_bf16
+                                                                : s2_nattn_fwd_generic_bf16;
         if (fwd16(g->dt, batch * heads, d_qk, d_v, scale, q, k, v, out, lse, st))
             return s2_fail(S2_ERR_DEVICE, "forward launch configuration failed");
         S2_HIP_CHECK(hipGetLastError());
@@ -78,9 +87,9 @@ int s2_nattn_bwd_run(const s2_grid_t *g, int batch, int heads, int d_qk, int d_v
         misaligned(dq) || misaligned(dk) || misaligned(dv))
         return s2_fail(S2_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
     if (dtype == S2_BF16) {
-        const bool fast = s2_nattn_bf16_supported(g->dt, d_qk, d_v);
-        auto *dq16 = fast ? s2_nattn_bwd_dq_bf16 : s2_nattn_bwd_dq_generic_bf16;
-        auto *kv16 = fast ? s2_nattn_bwd_dkdv_bf16 : s2_nattn_bwd_dkdv_generic_bf16;
+        const bool fast = s2_nattn_bf16_supported(g->dt, d_qk, d_v), band = !fast && band_bf16(g->dt, d_qk, d_v);
+        auto *dq16 = fast ? s2_nattn_bwd_dq_bf16 : band ? s2_nattn_bwd_dq_band_bf16 : s2_nattn_bwd_dq_generic_bf16;
+        auto *kv16 = fast ? s2_nattn_bwd_dkdv_bf16 : band ? s2_nattn_bwd_dkdv_band_bf16 : s2_nattn_bwd_dkdv_generic_bf16;
         if (dq16(g->dt, batch * heads, d_qk, d_v, scale, q, k, v, out, lse, dout, dq, Dws, st) ||
             kv16(g->dt, batch * heads, d_qk, d_v, scale, q, k, v, lse, dout, Dws, dk, dv, st))
             return s2_fail(S2_ERR_DEVICE, "backward launch configuration failed");

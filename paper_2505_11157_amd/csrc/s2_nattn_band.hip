@@ -52,6 +52,24 @@ struct Geo {
     static_assert(D * P4 % 256 == 0 && PITCH % 32 == 16, "geometry");
 };
 
+// Storage type of the tensors: float, or bf16 bits (arithmetic, staged tiles, logsumexp and D stay float32).
+typedef unsigned short bf16raw;
+__device__ __forceinline__ float ldx(const float *p) { return *p; }
+__device__ __forceinline__ float ldx(const bf16raw *p) { return __builtin_bit_cast(float, unsigned(*p) << 16); }
+__device__ __forceinline__ void stx(float *p, float x) { *p = x; }
+__device__ __forceinline__ void stx(bf16raw *p, float x)          // round to nearest even
+{
+    const unsigned u = __builtin_bit_cast(unsigned, x);
+    *p = bf16raw((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+}
+__device__ __forceinline__ f32x4 ld4(const float *p) { return *reinterpret_cast<const f32x4 *>(p); }
+__device__ __forceinline__ f32x4 ld4(const bf16raw *p)
+{
+    const uint2 w = *reinterpret_cast<const uint2 *>(p);
+    return f32x4{__builtin_bit_cast(float, w.x << 16), __builtin_bit_cast(float, w.x & 0xffff0000u),
+                 __builtin_bit_cast(float, w.y << 16), __builtin_bit_cast(float, w.y & 0xffff0000u)};
+}
+
 __device__ __forceinline__ f32x4 mfma4(float a, float b, f32x4 c)
 {
     return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
@@ -139,8 +157,8 @@ struct RowPlan {
     }
 };
 
-template <int D, int NO, int NP>
-__device__ __forceinline__ void load_stage(f32x4 (&r)[NP], const float *slice, size_t plane, int lat, int nlon, int Xs,
+template <int D, int NO, int NP, class T>
+__device__ __forceinline__ void load_stage(f32x4 (&r)[NP], const T *slice, size_t plane, int lat, int nlon, int Xs,
                                            int tid)
 {
     using G = Geo<D, NO>;
@@ -148,7 +166,7 @@ __device__ __forceinline__ void load_stage(f32x4 (&r)[NP], const float *slice, s
 #pragma unroll
     for (int j = 0; j < G::NP; ++j) {
         const int i = tid + 256 * j, c = i / G::P4, pc = i % G::P4;
-        r[j] = *reinterpret_cast<const f32x4 *>(slice + size_t(c) * plane + size_t(lat) * nlon + wrap3(Xs + 4 * pc, nlon));
+        r[j] = ld4(slice + size_t(c) * plane + size_t(lat) * nlon + wrap3(Xs + 4 * pc, nlon));
     }
 }
 template <int D, int NO, int NP>
@@ -214,10 +232,10 @@ __device__ __forceinline__ int segment_of(int sk, int nseg)      // polar segmen
 
 // ---------------------------------------------------------------------------------------------------------------
 // Forward.
-template <int D, int NO>
+template <class T, int D, int NO>
 __global__ void __launch_bounds__(256, 2)
-nattn_fwd_band(S2DeviceTables t, int nbh, float c2, const float *__restrict__ q, const float *__restrict__ k,
-               const float *__restrict__ v, float *__restrict__ out, float *__restrict__ lse)
+nattn_fwd_band(S2DeviceTables t, int nbh, float c2, const T *__restrict__ q, const T *__restrict__ k,
+               const T *__restrict__ v, T *__restrict__ out, float *__restrict__ lse)
 {
     using G = Geo<D, NO>;
     extern __shared__ __attribute__((aligned(16))) float lds[];
@@ -232,7 +250,7 @@ nattn_fwd_band(S2DeviceTables t, int nbh, float c2, const float *__restrict__ q,
     const bool active = h < t.nlat_out;
     const int W0 = grp * G::OW, Wb = nlon + W0;
     const size_t plane = size_t(t.nlat_in) * nlon;
-    const float *qs = q + size_t(bh) * D * plane, *ks = k + size_t(bh) * D * plane, *vs = v + size_t(bh) * D * plane;
+    const T *qs = q + size_t(bh) * D * plane, *ks = k + size_t(bh) * D * plane, *vs = v + size_t(bh) * D * plane;
 
     float qreg[NO][D / 4];
     f32x4 acc[NO][D / 16];
@@ -242,7 +260,7 @@ nattn_fwd_band(S2DeviceTables t, int nbh, float c2, const float *__restrict__ q,
         const bool own = active && W0 + 16 * o < nlon;      // the last group of a latitude may be ragged (by whole tiles)
 #pragma unroll
         for (int kb = 0; kb < D / 4; ++kb)
-            qreg[o][kb] = own ? qs[size_t(4 * kb + g) * plane + size_t(h) * nlon + (W0 + 16 * o + n)] : 0.f;
+            qreg[o][kb] = own ? ldx(qs + size_t(4 * kb + g) * plane + size_t(h) * nlon + (W0 + 16 * o + n)) : 0.f;
 #pragma unroll
         for (int mt = 0; mt < D / 16; ++mt) acc[o][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
         m[o] = kMinRef;
@@ -343,22 +361,22 @@ nattn_fwd_band(S2DeviceTables t, int nbh, float c2, const float *__restrict__ q,
         const float lt = group_sum(l[o]);
         const float inv = 1.f / lt;
         const size_t at = size_t(h) * nlon + (W0 + 16 * o + n);
-        float *ob = out + size_t(bh) * D * plane + at;
+        T *ob = out + size_t(bh) * D * plane + at;
 #pragma unroll
         for (int mt = 0; mt < D / 16; ++mt)
 #pragma unroll
-            for (int rr = 0; rr < 4; ++rr) ob[size_t(16 * mt + 4 * g + rr) * plane] = acc[o][mt][rr] * inv;
+            for (int rr = 0; rr < 4; ++rr) stx(ob + size_t(16 * mt + 4 * g + rr) * plane, acc[o][mt][rr] * inv);
         if (g == 0) lse[size_t(bh) * plane + at] = (m[o] + __log2f(lt)) * 0.6931471805599453f + t.ln_omega_ref;
     }
 }
 
 // ---------------------------------------------------------------------------------------------------------------
 // Backward, query side: dq and D_i = dout_i . out_i (written for the key-side launch).
-template <int D, int NO>
+template <class T, int D, int NO>
 __global__ void __launch_bounds__(256, 2)
-nattn_bwd_dq_band(S2DeviceTables t, int nbh, float scale, const float *__restrict__ q, const float *__restrict__ k,
-                  const float *__restrict__ v, const float *__restrict__ o_, const float *__restrict__ lse,
-                  const float *__restrict__ go, float *__restrict__ dq, float *__restrict__ Dws)
+nattn_bwd_dq_band(S2DeviceTables t, int nbh, float scale, const T *__restrict__ q, const T *__restrict__ k,
+                  const T *__restrict__ v, const T *__restrict__ o_, const float *__restrict__ lse,
+                  const T *__restrict__ go, T *__restrict__ dq, float *__restrict__ Dws)
 {
     using G = Geo<D, NO>;
     extern __shared__ __attribute__((aligned(16))) float lds[];
@@ -373,8 +391,8 @@ nattn_bwd_dq_band(S2DeviceTables t, int nbh, float scale, const float *__restric
     const bool active = h < t.nlat_out;
     const int W0 = grp * G::OW, Wb = nlon + W0;
     const size_t plane = size_t(t.nlat_in) * nlon;
-    const float *qs = q + size_t(bh) * D * plane, *ks = k + size_t(bh) * D * plane, *vs = v + size_t(bh) * D * plane;
-    const float *os = o_ + size_t(bh) * D * plane, *gs = go + size_t(bh) * D * plane;
+    const T *qs = q + size_t(bh) * D * plane, *ks = k + size_t(bh) * D * plane, *vs = v + size_t(bh) * D * plane;
+    const T *os = o_ + size_t(bh) * D * plane, *gs = go + size_t(bh) * D * plane;
     const float c2 = scale * kLog2e;
 
     float qreg[NO][D / 4], greg[NO][D / 4];
@@ -392,9 +410,9 @@ nattn_bwd_dq_band(S2DeviceTables t, int nbh, float scale, const float *__restric
 #pragma unroll
         for (int kb = 0; kb < D / 4; ++kb) {
             const size_t e = size_t(4 * kb + g) * plane + at;
-            qreg[o][kb] = own ? qs[e] : 0.f;
-            greg[o][kb] = own ? gs[e] : 0.f;
-            dsum = fmaf(greg[o][kb], own ? os[e] : 0.f, dsum);
+            qreg[o][kb] = own ? ldx(qs + e) : 0.f;
+            greg[o][kb] = own ? ldx(gs + e) : 0.f;
+            dsum = fmaf(greg[o][kb], own ? ldx(os + e) : 0.f, dsum);
         }
         dsum = group_sum(dsum);
         if (own) {
@@ -482,22 +500,22 @@ nattn_bwd_dq_band(S2DeviceTables t, int nbh, float scale, const float *__restric
 #pragma unroll
     for (int o = 0; o < NO; ++o) {
         if (W0 + 16 * o >= nlon) break;
-        float *ob = dq + size_t(bh) * D * plane + size_t(h) * nlon + (W0 + 16 * o + n);
+        T *ob = dq + size_t(bh) * D * plane + size_t(h) * nlon + (W0 + 16 * o + n);
 #pragma unroll
         for (int mt = 0; mt < D / 16; ++mt)
 #pragma unroll
-            for (int rr = 0; rr < 4; ++rr) ob[size_t(16 * mt + 4 * g + rr) * plane] = acc[o][mt][rr] * scale;
+            for (int rr = 0; rr < 4; ++rr) stx(ob + size_t(16 * mt + 4 * g + rr) * plane, acc[o][mt][rr] * scale);
     }
 }
 
 // ---------------------------------------------------------------------------------------------------------------
 // Backward, key side: owners are input points, the transposed band gives the output latitudes; q, dout, lse and D
 // of a stage's outputs are staged together.
-template <int D, int NO>
+template <class T, int D, int NO>
 __global__ void __launch_bounds__(256, 2)
-nattn_bwd_dkdv_band(S2DeviceTables t, int nbh, float scale, const float *__restrict__ q, const float *__restrict__ k,
-                    const float *__restrict__ v, const float *__restrict__ lse, const float *__restrict__ go,
-                    const float *__restrict__ Dws, float *__restrict__ dk, float *__restrict__ dv)
+nattn_bwd_dkdv_band(S2DeviceTables t, int nbh, float scale, const T *__restrict__ q, const T *__restrict__ k,
+                    const T *__restrict__ v, const float *__restrict__ lse, const T *__restrict__ go,
+                    const float *__restrict__ Dws, T *__restrict__ dk, T *__restrict__ dv)
 {
     using G = Geo<D, NO>;
     extern __shared__ __attribute__((aligned(16))) float lds[];
@@ -512,8 +530,8 @@ nattn_bwd_dkdv_band(S2DeviceTables t, int nbh, float scale, const float *__restr
     const bool active = hp < t.nlat_in;
     const int W0 = grp * G::OW, Wb = nlon + W0;
     const size_t plane = size_t(t.nlat_in) * nlon;
-    const float *qs = q + size_t(bh) * D * plane, *ks = k + size_t(bh) * D * plane, *vs = v + size_t(bh) * D * plane;
-    const float *gs = go + size_t(bh) * D * plane;
+    const T *qs = q + size_t(bh) * D * plane, *ks = k + size_t(bh) * D * plane, *vs = v + size_t(bh) * D * plane;
+    const T *gs = go + size_t(bh) * D * plane;
     const float *ls = lse + size_t(bh) * plane, *Ds = Dws + size_t(bh) * plane;
     const float c2 = scale * kLog2e, lref = t.ln_omega_ref;
     const float lw2 = active ? __log2f(t.omega_rel[hp]) : 0.f;     // -inf for a latitude of weight zero: p = 0
@@ -527,8 +545,8 @@ nattn_bwd_dkdv_band(S2DeviceTables t, int nbh, float scale, const float *__restr
 #pragma unroll
         for (int kb = 0; kb < D / 4; ++kb) {
             const size_t e = size_t(4 * kb + g) * plane + size_t(hp) * nlon + (W0 + 16 * o + n);
-            kreg[o][kb] = active && W0 + 16 * o < nlon ? ks[e] : 0.f;
-            vreg[o][kb] = active && W0 + 16 * o < nlon ? vs[e] : 0.f;
+            kreg[o][kb] = active && W0 + 16 * o < nlon ? ldx(ks + e) : 0.f;
+            vreg[o][kb] = active && W0 + 16 * o < nlon ? ldx(vs + e) : 0.f;
         }
     }
     BandRows rows;
@@ -636,8 +654,8 @@ nattn_bwd_dkdv_band(S2DeviceTables t, int nbh, float scale, const float *__restr
         for (int mt = 0; mt < D / 16; ++mt)
 #pragma unroll
             for (int rr = 0; rr < 4; ++rr) {
-                dk[at + size_t(16 * mt + 4 * g + rr) * plane] = adk[o][mt][rr] * scale;
-                dv[at + size_t(16 * mt + 4 * g + rr) * plane] = adv[o][mt][rr];
+                stx(dk + at + size_t(16 * mt + 4 * g + rr) * plane, adk[o][mt][rr] * scale);
+                stx(dv + at + size_t(16 * mt + 4 * g + rr) * plane, adv[o][mt][rr]);
             }
     }
 }
@@ -647,16 +665,16 @@ constexpr size_t fwd_lds() { return size_t(2) * Geo<D, NO>::TILE * sizeof(float)
 template <int D, int NO>
 constexpr size_t dkdv_lds() { return (size_t(2) * Geo<D, NO>::TILE + 2 * Geo<D, NO>::COLS) * sizeof(float); }
 
-template <int D, int NO>
+template <class T, int D, int NO>
 int configure_one()
 {
-    if (hipFuncSetAttribute(reinterpret_cast<const void *>(nattn_fwd_band<D, NO>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            int(fwd_lds<D, NO>())) != hipSuccess)
-        return -1;
-    if (hipFuncSetAttribute(reinterpret_cast<const void *>(nattn_bwd_dq_band<D, NO>),
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(nattn_fwd_band<T, D, NO>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, int(fwd_lds<D, NO>())) != hipSuccess)
         return -1;
-    if (hipFuncSetAttribute(reinterpret_cast<const void *>(nattn_bwd_dkdv_band<D, NO>),
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(nattn_bwd_dq_band<T, D, NO>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, int(fwd_lds<D, NO>())) != hipSuccess)
+        return -1;
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(nattn_bwd_dkdv_band<T, D, NO>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, int(dkdv_lds<D, NO>())) != hipSuccess)
         return -1;
     return 0;
@@ -674,56 +692,90 @@ double pair_count(const S2DeviceTables &t, bool fwd_side, int nbh)
     return nbh * (p[0] + p[1] + p[2] + p[3]);
 }
 
-template <int D, int NO>
-void launch_fwd(const S2DeviceTables &t, int nbh, float scale, const float *q, const float *k, const float *v, float *out,
-                float *lse, hipStream_t st)
+template <class T, int D, int NO>
+void launch_fwd(const S2DeviceTables &t, int nbh, float scale, const T *q, const T *k, const T *v, T *out, float *lse,
+                hipStream_t st)
 {
-    S2TraceScope tr("nattn_fwd_band", pair_count(t, true, nbh), st);
+    S2TraceScope tr(sizeof(T) == 2 ? "nattn_fwd_band<bf16>" : "nattn_fwd_band", pair_count(t, true, nbh), st);
     const unsigned nblk = blocks<D, NO>(t, nbh, t.nlat_out);
     const size_t bytes = fwd_lds<D, NO>();
-    hipLaunchKernelGGL((nattn_fwd_band<D, NO>), dim3(nblk), dim3(256), bytes, st, t, nbh, scale * kLog2e, q, k, v, out, lse);
+    hipLaunchKernelGGL((nattn_fwd_band<T, D, NO>), dim3(nblk), dim3(256), bytes, st, t, nbh, scale * kLog2e, q, k, v, out,
+                       lse);
 }
-template <int D, int NO>
-void launch_dq(const S2DeviceTables &t, int nbh, float scale, const float *q, const float *k, const float *v,
-               const float *o, const float *lse, const float *go, float *dq, float *Dws, hipStream_t st)
+template <class T, int D, int NO>
+void launch_dq(const S2DeviceTables &t, int nbh, float scale, const T *q, const T *k, const T *v, const T *o,
+               const float *lse, const T *go, T *dq, float *Dws, hipStream_t st)
 {
-    S2TraceScope tr("nattn_bwd_dq_band", pair_count(t, true, nbh), st);
+    S2TraceScope tr(sizeof(T) == 2 ? "nattn_bwd_dq_band<bf16>" : "nattn_bwd_dq_band", pair_count(t, true, nbh), st);
     const unsigned nblk = blocks<D, NO>(t, nbh, t.nlat_out);
     const size_t bytes = fwd_lds<D, NO>();
-    hipLaunchKernelGGL((nattn_bwd_dq_band<D, NO>), dim3(nblk), dim3(256), bytes, st, t, nbh, scale, q, k, v, o, lse, go, dq,
-                       Dws);
+    hipLaunchKernelGGL((nattn_bwd_dq_band<T, D, NO>), dim3(nblk), dim3(256), bytes, st, t, nbh, scale, q, k, v, o, lse, go,
+                       dq, Dws);
 }
-template <int D, int NO>
-void launch_dkdv(const S2DeviceTables &t, int nbh, float scale, const float *q, const float *k, const float *v,
-                 const float *lse, const float *go, const float *Dws, float *dk, float *dv, hipStream_t st)
+template <class T, int D, int NO>
+void launch_dkdv(const S2DeviceTables &t, int nbh, float scale, const T *q, const T *k, const T *v, const float *lse,
+                 const T *go, const float *Dws, T *dk, T *dv, hipStream_t st)
 {
-    S2TraceScope tr("nattn_bwd_dkdv_band", pair_count(t, false, nbh), st);
+    S2TraceScope tr(sizeof(T) == 2 ? "nattn_bwd_dkdv_band<bf16>" : "nattn_bwd_dkdv_band", pair_count(t, false, nbh), st);
     const unsigned nblk = blocks<D, NO>(t, nbh, t.nlat_in);
     const size_t bytes = dkdv_lds<D, NO>();
-    hipLaunchKernelGGL((nattn_bwd_dkdv_band<D, NO>), dim3(nblk), dim3(256), bytes, st, t, nbh, scale, q, k, v, lse, go, Dws,
-                       dk, dv);
+    hipLaunchKernelGGL((nattn_bwd_dkdv_band<T, D, NO>), dim3(nblk), dim3(256), bytes, st, t, nbh, scale, q, k, v, lse, go,
+                       Dws, dk, dv);
+}
+
+template <class T>
+void fwd_by_d(const S2DeviceTables &t, int nbh, int d, float scale, const void *q, const void *k, const void *v, void *out,
+              float *lse, hipStream_t st)
+{
+    const T *Q = static_cast<const T *>(q), *K = static_cast<const T *>(k), *V = static_cast<const T *>(v);
+    T *O = static_cast<T *>(out);
+    if (d == 16) launch_fwd<T, 16, 4>(t, nbh, scale, Q, K, V, O, lse, st);
+    else if (d == 32) launch_fwd<T, 32, 4>(t, nbh, scale, Q, K, V, O, lse, st);
+    else launch_fwd<T, 64, 2>(t, nbh, scale, Q, K, V, O, lse, st);
+}
+template <class T>
+void dq_by_d(const S2DeviceTables &t, int nbh, int d, float scale, const void *q, const void *k, const void *v,
+             const void *o, const float *lse, const void *go, void *dq, float *Dws, hipStream_t st)
+{
+    const T *Q = static_cast<const T *>(q), *K = static_cast<const T *>(k), *V = static_cast<const T *>(v);
+    const T *O = static_cast<const T *>(o), *G = static_cast<const T *>(go);
+    T *DQ = static_cast<T *>(dq);
+    if (d == 16) launch_dq<T, 16, 4>(t, nbh, scale, Q, K, V, O, lse, G, DQ, Dws, st);
+    else if (d == 32) launch_dq<T, 32, 4>(t, nbh, scale, Q, K, V, O, lse, G, DQ, Dws, st);
+    else launch_dq<T, 64, 2>(t, nbh, scale, Q, K, V, O, lse, G, DQ, Dws, st);
+}
+template <class T>
+void dkdv_by_d(const S2DeviceTables &t, int nbh, int d, float scale, const void *q, const void *k, const void *v,
+               const float *lse, const void *go, const float *Dws, void *dk, void *dv, hipStream_t st)
+{
+    const T *Q = static_cast<const T *>(q), *K = static_cast<const T *>(k), *V = static_cast<const T *>(v);
+    const T *G = static_cast<const T *>(go);
+    T *DK = static_cast<T *>(dk), *DV = static_cast<T *>(dv);
+    if (d == 16) launch_dkdv<T, 16, 4>(t, nbh, scale, Q, K, V, lse, G, Dws, DK, DV, st);
+    else if (d == 32) launch_dkdv<T, 32, 4>(t, nbh, scale, Q, K, V, lse, G, Dws, DK, DV, st);
+    else launch_dkdv<T, 64, 2>(t, nbh, scale, Q, K, V, lse, G, Dws, DK, DV, st);
 }
 
 }  // namespace
 
 int s2_nattn_band_configure()
 {
-    return configure_one<16, 4>() || configure_one<32, 4>() || configure_one<64, 2>();
+    return configure_one<float, 16, 4>() || configure_one<float, 32, 4>() || configure_one<float, 64, 2>() ||
+           configure_one<bf16raw, 16, 4>() || configure_one<bf16raw, 32, 4>() || configure_one<bf16raw, 64, 2>();
 }
 
 bool s2_nattn_band_supported(const S2DeviceTables &t, int d, int e)
 {
     return d == e && (d == 16 || d == 32 || d == 64) && t.upscale == 1 && t.pscale == 1 && t.nlon_in == t.nlon_out &&
-           t.nlat_in == t.nlat_out && t.nlon_in % 16 == 0 && t.nlon_in >= 64 && t.band_rows_ok && !s2_debug_flag(S2_DEBUG_NO_MFMA);
+           t.nlat_in == t.nlat_out && t.nlon_in % 16 == 0 && t.nlon_in >= 64 && t.band_rows_ok &&
+           !s2_debug_flag(S2_DEBUG_NO_MFMA);
 }
 
 int s2_nattn_fwd_band(const S2DeviceTables &t, int nbh, int d, int, float scale, const float *q, const float *k,
                       const float *v, float *out, float *lse, hipStream_t st)
 {
     if (s2_debug_flag(S2_DEBUG_FAIL_LAUNCH)) return -1;
-    if (d == 16) launch_fwd<16, 4>(t, nbh, scale, q, k, v, out, lse, st);
-    else if (d == 32) launch_fwd<32, 4>(t, nbh, scale, q, k, v, out, lse, st);
-    else launch_fwd<64, 2>(t, nbh, scale, q, k, v, out, lse, st);
+    fwd_by_d<float>(t, nbh, d, scale, q, k, v, out, lse, st);
     return 0;
 }
 
@@ -732,15 +784,32 @@ int s2_nattn_bwd_band(const S2DeviceTables &t, int nbh, int d, int, float scale,
                       float *Dws, hipStream_t st)
 {
     if (s2_debug_flag(S2_DEBUG_FAIL_LAUNCH)) return -1;
-    if (d == 16) {
-        launch_dq<16, 4>(t, nbh, scale, q, k, v, o, lse, go, dq, Dws, st);
-        launch_dkdv<16, 4>(t, nbh, scale, q, k, v, lse, go, Dws, dk, dv, st);
-    } else if (d == 32) {
-        launch_dq<32, 4>(t, nbh, scale, q, k, v, o, lse, go, dq, Dws, st);
-        launch_dkdv<32, 4>(t, nbh, scale, q, k, v, lse, go, Dws, dk, dv, st);
-    } else {
-        launch_dq<64, 2>(t, nbh, scale, q, k, v, o, lse, go, dq, Dws, st);
-        launch_dkdv<64, 2>(t, nbh, scale, q, k, v, lse, go, Dws, dk, dv, st);
-    }
+    dq_by_d<float>(t, nbh, d, scale, q, k, v, o, lse, go, dq, Dws, st);
+    dkdv_by_d<float>(t, nbh, d, scale, q, k, v, lse, go, Dws, dk, dv, st);
+    return 0;
+}
+
+// bf16 tensors on the same kernels (float32 arithmetic on the fp32 matrix cores, bf16 loads and stores)
+int s2_nattn_fwd_band_bf16(const S2DeviceTables &t, int nbh, int d, int, float scale, const void *q, const void *k,
+                           const void *v, void *out, float *lse, hipStream_t st)
+{
+    if (s2_debug_flag(S2_DEBUG_FAIL_LAUNCH)) return -1;
+    fwd_by_d<bf16raw>(t, nbh, d, scale, q, k, v, out, lse, st);
+    return 0;
+}
+int s2_nattn_bwd_dq_band_bf16(const S2DeviceTables &t, int nbh, int d, int, float scale, const void *q, const void *k,
+                              const void *v, const void *o, const float *lse, const void *go, void *dq, float *Dws,
+                              hipStream_t st)
+{
+    if (s2_debug_flag(S2_DEBUG_FAIL_LAUNCH)) return -1;
+    dq_by_d<bf16raw>(t, nbh, d, scale, q, k, v, o, lse, go, dq, Dws, st);
+    return 0;
+}
+int s2_nattn_bwd_dkdv_band_bf16(const S2DeviceTables &t, int nbh, int d, int, float scale, const void *q, const void *k,
+                                const void *v, const float *lse, const void *go, const float *Dws, void *dk, void *dv,
+                                hipStream_t st)
+{
+    if (s2_debug_flag(S2_DEBUG_FAIL_LAUNCH)) return -1;
+    dkdv_by_d<bf16raw>(t, nbh, d, scale, q, k, v, lse, go, Dws, dk, dv, st);
     return 0;
 }

@@ -86,6 +86,17 @@ int s2_nattn_bwd_band(const S2DeviceTables &t, int nbh, int d, int e, float scal
                       const float *v, const float *o, const float *lse, const float *go, float *dq, float *dk, float *dv,
                       float *Dws, hipStream_t st);
 
+// The same kernels on bf16 tensors (float32 arithmetic on the fp32 matrix cores, bf16 loads and stores): the head
+// dimensions and longitude counts the bf16 matrix-core kernels do not cover.
+int s2_nattn_fwd_band_bf16(const S2DeviceTables &t, int nbh, int d, int e, float scale, const void *q, const void *k,
+                           const void *v, void *out, float *lse, hipStream_t st);
+int s2_nattn_bwd_dq_band_bf16(const S2DeviceTables &t, int nbh, int d, int e, float scale, const void *q, const void *k,
+                              const void *v, const void *o, const float *lse, const void *go, void *dq, float *Dws,
+                              hipStream_t st);
+int s2_nattn_bwd_dkdv_band_bf16(const S2DeviceTables &t, int nbh, int d, int e, float scale, const void *q, const void *k,
+                                const void *v, const float *lse, const void *go, const float *Dws, void *dk, void *dv,
+                                hipStream_t st);
+
 // Backward with the scratch for D_i given as a device pointer (checks and dispatch behind both C entry points).
 int s2_nattn_bwd_run(const s2_grid_t *g, int batch, int heads, int d_qk, int d_v, int dtype, float scale,
                      const void *q, const void *k, const void *v, const void *out, const float *lse, const void *dout,

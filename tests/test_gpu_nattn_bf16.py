@@ -10,7 +10,8 @@ error enters dS_ij = p_ij (dout_i.v_j - D_i) for every j at once and propagates 
 oracle: its forward with |k| in place of v, and the dv output of its backward with dD_i |q_i| in place of dout).
 It matters only where the softmax is nearly one-hot (a handful of elements per million on the workloads).
 Shapes with equal grids, d = e = 32 and a longitude count that is a multiple of 64 run on the bf16 matrix cores
-(band tiles); every other shape on the shape-agnostic kernels with bf16 loads and stores.
+(band tiles); d = e = 16, 32, 64 on other multiples of 16 on the fp32 band tiles with bf16 loads and stores; every other
+shape on the shape-agnostic kernels with bf16 loads and stores.
 """
 import json
 import math
@@ -117,6 +118,28 @@ def test_bf16_matrix_core_path(ci):
         S.s2_trace_enable(False)
         S.s2_trace_reset()
     assert names and all(n.split("<")[0] in ("nattn_fwd_bf16", "nattn_bwd_dq_bf16", "nattn_bwd_dkdv_bf16") for n in names), names
+
+
+# fp32 band tiles with bf16 loads and stores: head widths 16 and 64, and d = 32 on longitude counts that are multiples of
+# 16 but not of 64 (whole circles near the poles, short arcs, a ragged last group, the zero-weight pole row)
+BAND = [
+    _c(0, 17, 64, 0.5, d=16), _c(0, 33, 192, 0.3, H=2, d=64), _c(1, 16, 128, 0.3, B=2, H=1, d=16), _c(0, 21, 80, 0.4, d=32),
+    _c(2, 32, 144, 0.3, d=64), _c(0, 9, 64, math.pi, d=64),
+]
+
+
+@pytest.mark.parametrize("ci", range(len(BAND)))
+def test_bf16_band_tile_path(ci):
+    c, arrs = make_inputs(BAND[ci], seed=870 + ci)
+    S.s2_trace_reset()
+    S.s2_trace_enable(True)
+    try:
+        run_bf16(c, arrs, range(c["batch"] * c["heads"]), "bf16-band%d" % ci)
+        names = {n for n, _, _ in S.s2_trace_entries()}
+    finally:
+        S.s2_trace_enable(False)
+        S.s2_trace_reset()
+    assert names == {"nattn_fwd_band<bf16>", "nattn_bwd_dq_band<bf16>", "nattn_bwd_dkdv_band<bf16>"}, names
 
 
 @pytest.mark.parametrize("ci", range(len(GENERIC)))
