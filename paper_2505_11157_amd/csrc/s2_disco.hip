@@ -17,7 +17,7 @@
 struct s2_disco {
     const s2_grid_t *g;
     int K;
-    float *dev_psi = nullptr;     // [entry][K], entry = poff[h * band_max + b] + offset
+    float *dev_psi = nullptr;     // [entry][KP], KP = K rounded up to a multiple of 4; entry = poff[h * band_max + b] + offset
     int *dev_poff = nullptr;      // [nlat_out * band_max]
 };
 
@@ -31,8 +31,9 @@ __device__ __forceinline__ int wrapn(int x, int n)
     return x >= n ? x - n : x;
 }
 
-// z[bc][k][h][w]: one lane per output point, block -> (64 longitudes, latitude, bc)
-template <int KB>
+// z[bc][k][h][w]: one lane per output point, block -> (64 longitudes, latitude, bc).  KP: the basis count rounded up to
+// a multiple of four; the basis table holds KP values per arc offset (zeros behind the K-th).
+template <int KP>
 __global__ void __launch_bounds__(64)
 disco_z_fwd(S2DeviceTables t, const float *__restrict__ psi, const int *__restrict__ poff, int K,
             const float *__restrict__ x, float *__restrict__ z)
@@ -40,41 +41,57 @@ disco_z_fwd(S2DeviceTables t, const float *__restrict__ psi, const int *__restri
     const int w = blockIdx.x * 64 + threadIdx.x, h = blockIdx.y, bc = blockIdx.z;
     if (w >= t.nlon_out) return;
     const size_t si = size_t(t.nlat_in) * t.nlon_in, so = size_t(t.nlat_out) * t.nlon_out;
-    float acc[KB];
+    float acc[KP];
 #pragma unroll
-    for (int k = 0; k < KB; ++k) acc[k] = 0.f;
+    for (int k = 0; k < KP; ++k) acc[k] = 0.f;
     const int nb = t.band_n[h], hp0 = t.band_lo[h];
     for (int b = 0; b < nb; ++b) {
         const int c = t.cnt[h * t.band_max + b];
         const int first = w * t.pscale + (c == t.nlon_in ? 0 : -((c - 1) >> 1));
         const float *xr = x + size_t(bc) * si + size_t(hp0 + b) * t.nlon_in;
-        const float *pr = psi + size_t(poff[h * t.band_max + b]) * K;
+        const float *pr = psi + size_t(poff[h * t.band_max + b]) * KP;
         int col = wrapn(first, t.nlon_in);
         for (int tt = 0; tt < c; ++tt) {
             const float xv = xr[col];
 #pragma unroll
-            for (int k = 0; k < KB; ++k)
-                if (k < K) acc[k] = fmaf(pr[tt * K + k], xv, acc[k]);
+            for (int k = 0; k < KP; ++k) acc[k] = fmaf(pr[tt * KP + k], xv, acc[k]);
             col = col + 1 == t.nlon_in ? 0 : col + 1;
         }
     }
 #pragma unroll
-    for (int k = 0; k < KB; ++k)
+    for (int k = 0; k < KP; ++k)
         if (k < K) z[(size_t(bc) * K + k) * so + size_t(h) * t.nlon_out + w] = acc[k];
 }
 
+// dz[bc][k][n] -> dzt[bc][n][KP] (zeros behind the K-th value): the gather of disco_dx then reads the K values of an
+// output point as KP/4 16-byte loads instead of K loads from K planes
+template <int KP>
+__global__ void __launch_bounds__(256)
+disco_dz_transpose(int K, size_t so, const float *__restrict__ dz, float *__restrict__ dzt)
+{
+    const size_t n = size_t(blockIdx.x) * 256 + threadIdx.x;
+    const int bc = blockIdx.y;
+    if (n >= so) return;
+    float v[KP];
+#pragma unroll
+    for (int k = 0; k < KP; ++k) v[k] = k < K ? dz[(size_t(bc) * K + k) * so + n] : 0.f;
+    float4 *o = reinterpret_cast<float4 *>(dzt + (size_t(bc) * so + n) * KP);
+#pragma unroll
+    for (int q = 0; q < KP / 4; ++q) o[q] = make_float4(v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]);
+}
+
 // dx[bc][h'][w_in] = sum over the output points (h, w) whose disk holds the input point, and over k, of
-// psi_k[h, h', w_in - w pscale] dz[bc][k][h][w]: one lane per input point
-template <int KB>
+// psi_k[h, h', w_in - w pscale] dz[bc][k][h][w]: one lane per input point; dzt is dz with the basis index innermost
+template <int KP, bool PS1>      // PS1: equal longitude counts (no division in the walk over the arc)
 __global__ void __launch_bounds__(64)
-disco_dx(S2DeviceTables t, const float *__restrict__ psi, const int *__restrict__ poff, int K,
-         const float *__restrict__ dz, float *__restrict__ dx)
+disco_dx(S2DeviceTables t, const float *__restrict__ psi, const int *__restrict__ poff,
+         const float *__restrict__ dzt, float *__restrict__ dx)
 {
     const int win = blockIdx.x * 64 + threadIdx.x, hp = blockIdx.y, bc = blockIdx.z;
     if (win >= t.nlon_in) return;
     const size_t si = size_t(t.nlat_in) * t.nlon_in, so = size_t(t.nlat_out) * t.nlon_out;
     float acc = 0.f;
-    const int ps = t.pscale;
+    const int ps = PS1 ? 1 : t.pscale;
     const int nb = t.omega_rel[hp] > 0.f ? t.tband_n[hp] : 0;       // a latitude of weight zero receives nothing
     const int h0 = t.tband_lo[hp];
     for (int b = 0; b < nb; ++b) {
@@ -82,16 +99,22 @@ disco_dx(S2DeviceTables t, const float *__restrict__ psi, const int *__restrict_
         const int bf = hp - t.band_lo[h];                            // row of h' in the band of h
         const int c = t.cnt[h * t.band_max + bf];
         const int lo = c == t.nlon_in ? 0 : -((c - 1) >> 1);
-        const float *pr = psi + size_t(poff[h * t.band_max + bf]) * K;
-        const float *dr = dz + size_t(bc) * K * so + size_t(h) * t.nlon_out;
+        const float *pr = psi + size_t(poff[h * t.band_max + bf]) * KP;
+        const float *dr = dzt + (size_t(bc) * so + size_t(h) * t.nlon_out) * KP;
         // offset tt of the arc of output w is input column w ps + lo + tt: w ps = win - lo - tt (mod nlon_in)
         int xw = wrapn(win - lo, t.nlon_in);
         for (int tt = 0; tt < c; ++tt) {
-            if (ps == 1 || xw % ps == 0) {
-                const int w = xw / ps;
+            if (PS1 || xw % ps == 0) {
+                const int w = PS1 ? xw : xw / ps;
+                const float4 *dp = reinterpret_cast<const float4 *>(dr + size_t(w) * KP);
 #pragma unroll
-                for (int k = 0; k < KB; ++k)
-                    if (k < K) acc = fmaf(pr[tt * K + k], dr[size_t(k) * so + w], acc);
+                for (int q = 0; q < KP / 4; ++q) {
+                    const float4 v = dp[q];
+                    acc = fmaf(pr[tt * KP + 4 * q + 0], v.x, acc);
+                    acc = fmaf(pr[tt * KP + 4 * q + 1], v.y, acc);
+                    acc = fmaf(pr[tt * KP + 4 * q + 2], v.z, acc);
+                    acc = fmaf(pr[tt * KP + 4 * q + 3], v.w, acc);
+                }
             }
             xw = xw == 0 ? t.nlon_in - 1 : xw - 1;
         }
@@ -112,13 +135,15 @@ int check(const s2_disco_t *dc, int batch, int cin, int cout, const void *ws, si
     return S2_OK;
 }
 
+inline int padded(int K) { return (K + 3) / 4 * 4; }
+
 template <class F>
-void by_basis(int K, F f)
+void by_basis(int K, F f)       // f(KP), KP = the basis count rounded up to a multiple of four
 {
-    if (K <= 2) f(std::integral_constant<int, 2>());
-    else if (K <= 4) f(std::integral_constant<int, 4>());
+    if (K <= 4) f(std::integral_constant<int, 4>());
     else if (K <= 8) f(std::integral_constant<int, 8>());
-    else f(std::integral_constant<int, kMaxBasis>());
+    else if (K <= 12) f(std::integral_constant<int, 12>());
+    else f(std::integral_constant<int, 16>());
 }
 
 }  // namespace
@@ -136,18 +161,19 @@ extern "C" int s2_disco_init(const s2_grid_t *g, int nbasis, s2_disco_t **out)
     dc->K = nbasis;
     // basis values along the arcs of the kernels' tables (zero-weight latitudes are not in them)
     const double kPi = 3.141592653589793238462643383279502884, dr = g->theta / nbasis;
+    const int KP = padded(nbasis);      // values per arc offset in the table (zeros behind the last basis function)
     std::vector<int> poff(size_t(g->nlat_out) * g->band_max, 0);
     std::vector<float> psi;
     for (int h = 0; h < g->nlat_out; ++h)
         for (int b = 0; b < g->band_n[h]; ++b) {
             const int hp = g->band_lo[h] + b, c = g->cnt[size_t(h) * g->band_max + b];
             const int lo = c == g->nlon_in ? 0 : -((c - 1) / 2);
-            poff[size_t(h) * g->band_max + b] = int(psi.size() / nbasis);
+            poff[size_t(h) * g->band_max + b] = int(psi.size() / KP);
             for (int tt = 0; tt < c; ++tt) {
                 const int wp = ((lo + tt) % g->nlon_in + g->nlon_in) % g->nlon_in;
                 const double r = s2_great_circle(g->colat_out[h], g->colat_in[hp], 2.0 * kPi * wp / g->nlon_in);
-                for (int k = 0; k < nbasis; ++k)
-                    psi.push_back(float(std::max(0.0, 1.0 - std::fabs(r / dr - k)) * g->omega_in[hp]));
+                for (int k = 0; k < KP; ++k)
+                    psi.push_back(k < nbasis ? float(std::max(0.0, 1.0 - std::fabs(r / dr - k)) * g->omega_in[hp]) : 0.f);
             }
         }
     if (g->on_device) {
@@ -181,8 +207,10 @@ extern "C" size_t s2_disco_workspace_bytes(const s2_disco_t *dc, int batch, int 
     if (!dc || batch < 1 || cin < 1 || cout < 1) return 0;
     const size_t n_out = size_t(dc->g->nlat_out) * dc->g->nlon_out;
     auto up = [](size_t x) { return (x + 63) / 64 * 64; };
-    // z, dz: [batch][cin * K][n_out]; partial sums of the weight gradient
-    return (2 * up(size_t(batch) * cin * dc->K * n_out) + up(s2_wgrad_part_floats(cout, cin * dc->K))) * sizeof(float);
+    // z, dz: [batch][cin * K][n_out]; dz with the basis index innermost [batch * cin][n_out][KP]; partial sums of the
+    // weight gradient
+    return (2 * up(size_t(batch) * cin * dc->K * n_out) + up(size_t(batch) * cin * padded(dc->K) * n_out) +
+            up(s2_wgrad_part_floats(cout, cin * dc->K))) * sizeof(float);
 }
 
 extern "C" int s2_disco_fwd(const s2_disco_t *dc, int batch, int cin, int cout, const float *x, const float *weight,
@@ -222,7 +250,8 @@ extern "C" int s2_disco_bwd(const s2_disco_t *dc, int batch, int cin, int cout, 
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const int n_out = g->nlat_out * g->nlon_out, K = dc->K;
     auto up = [](size_t v) { return (v + 63) / 64 * 64; };
-    float *z = static_cast<float *>(workspace), *dz = z + up(size_t(batch) * cin * K * n_out), *part = dz + up(size_t(batch) * cin * K * n_out);
+    float *z = static_cast<float *>(workspace), *dz = z + up(size_t(batch) * cin * K * n_out);
+    float *dzt = dz + up(size_t(batch) * cin * K * n_out), *part = dzt + up(size_t(batch) * cin * padded(K) * n_out);
     {
         S2TraceScope tr("disco_bwd mix", 0.0, st);
         if (dweight) s2_wgrad_f32(cout, cin * K, n_out, batch, dy, z, part, dweight, st);
@@ -231,8 +260,13 @@ extern "C" int s2_disco_bwd(const s2_disco_t *dc, int batch, int cin, int cout, 
     }
     S2TraceScope tr("disco_dx", 0.0, st);
     const dim3 grid((g->nlon_in + 63) / 64, g->nlat_in, batch * cin);
-    by_basis(K, [&](auto KB) {
-        hipLaunchKernelGGL((disco_dx<decltype(KB)::value>), grid, dim3(64), 0, st, g->dt, dc->dev_psi, dc->dev_poff, K, dz, dx);
+    by_basis(K, [&](auto KP) {
+        const dim3 tgrid(unsigned((size_t(n_out) + 255) / 256), batch * cin);
+        hipLaunchKernelGGL((disco_dz_transpose<decltype(KP)::value>), tgrid, dim3(256), 0, st, K, size_t(n_out), dz, dzt);
+        if (g->pscale == 1)
+            hipLaunchKernelGGL((disco_dx<decltype(KP)::value, true>), grid, dim3(64), 0, st, g->dt, dc->dev_psi, dc->dev_poff, dzt, dx);
+        else
+            hipLaunchKernelGGL((disco_dx<decltype(KP)::value, false>), grid, dim3(64), 0, st, g->dt, dc->dev_psi, dc->dev_poff, dzt, dx);
     });
     S2_HIP_CHECK(hipGetLastError());
     return S2_OK;
