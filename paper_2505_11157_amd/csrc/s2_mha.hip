@@ -213,14 +213,21 @@ mha_wgrad_partial(int M, int K, int N, int batch, int nsplit, const float *__res
         }
 }
 
+// out[i] = sum of the nsplit partial values of element i.  A workgroup owns 64 elements; thread (q, e) adds the
+// partials q, q + 4, q + 8, ... of element e (four chains of loads in flight per element), and the four chain sums
+// are added in a fixed order: bit-reproducible.
 __global__ void __launch_bounds__(256)
 mha_sum_partials(int count, int nsplit, const float *__restrict__ part, float *__restrict__ out)
 {
-    const int i = blockIdx.x * 256 + threadIdx.x;
-    if (i >= count) return;
+    __shared__ float red[4][64];
+    const int e = threadIdx.x & 63, q = threadIdx.x >> 6;
+    const int i = blockIdx.x * 64 + e;
     float s = 0.f;
-    for (int p = 0; p < nsplit; ++p) s += part[size_t(p) * count + i];       // fixed order
-    out[i] = s;
+    if (i < count)
+        for (int p = q; p < nsplit; p += 4) s += part[size_t(p) * count + i];
+    red[q][e] = s;
+    __syncthreads();
+    if (q == 0 && i < count) out[i] = (red[0][e] + red[1][e]) + (red[2][e] + red[3][e]);
 }
 
 // block-wide sum of one value per thread (256 threads), result in every thread; fixed order
@@ -286,25 +293,53 @@ mha_instnorm_bwd(int C, int N, const float *__restrict__ x, const float *__restr
     }
 }
 
-// out[c] = sum over batch and grid points of u[b][c][n] (* xhat[b][c][n] if x is given); one workgroup per channel
+// out[c] = sum over batch and grid points of u[b][c][n] (* xhat[b][c][n] if x is given); one workgroup per channel.
+// 16-byte loads, four independent partial sums per thread (several loads in flight; the order of the additions is
+// fixed, so the result is bit-reproducible).
 __global__ void __launch_bounds__(256)
 mha_channel_sum(int batch, int C, int N, const float *__restrict__ u, const float *__restrict__ x,
                 const float *__restrict__ mean, const float *__restrict__ rstd, float *__restrict__ out)
 {
     __shared__ float red[256];
     const int c = blockIdx.x, tid = threadIdx.x;
-    float s = 0.f;
+    float s[4] = {0.f, 0.f, 0.f, 0.f};
+    const int n4 = (N % 4 == 0) ? N / 4 : 0;          // rows that are not 16-byte multiples take the scalar loop
     for (int b = 0; b < batch; ++b) {
         const float *ur = u + (size_t(b) * C + c) * N;
+        const float4 *u4 = reinterpret_cast<const float4 *>(ur);
         if (x) {
             const float *xr = x + (size_t(b) * C + c) * N;
+            const float4 *x4 = reinterpret_cast<const float4 *>(xr);
             const float mu = mean[b * C + c], rs = rstd[b * C + c];
-            for (int i = tid; i < N; i += 256) s = fmaf(ur[i], (xr[i] - mu) * rs, s);
+            for (int i0 = tid; i0 < n4; i0 += 1024) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int i = i0 + 256 * j;
+                    if (i < n4) {
+                        const float4 a = u4[i], v = x4[i];
+                        s[j] = fmaf(a.x, (v.x - mu) * rs, s[j]);
+                        s[j] = fmaf(a.y, (v.y - mu) * rs, s[j]);
+                        s[j] = fmaf(a.z, (v.z - mu) * rs, s[j]);
+                        s[j] = fmaf(a.w, (v.w - mu) * rs, s[j]);
+                    }
+                }
+            }
+            for (int i = 4 * n4 + tid; i < N; i += 256) s[0] = fmaf(ur[i], (xr[i] - mu) * rs, s[0]);
         } else {
-            for (int i = tid; i < N; i += 256) s += ur[i];
+            for (int i0 = tid; i0 < n4; i0 += 1024) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int i = i0 + 256 * j;
+                    if (i < n4) {
+                        const float4 a = u4[i];
+                        s[j] += (a.x + a.y) + (a.z + a.w);
+                    }
+                }
+            }
+            for (int i = 4 * n4 + tid; i < N; i += 256) s[0] += ur[i];
         }
     }
-    const float r = block_sum(s, red);
+    const float r = block_sum((s[0] + s[1]) + (s[2] + s[3]), red);
     if (tid == 0) out[c] = r;
 }
 
@@ -319,7 +354,13 @@ mha_batch_sum(int batch, size_t CN, const float *__restrict__ u, float *__restri
     out[i] = s;
 }
 
-constexpr int kSplits = 64;
+// Split-K weight gradients: enough splits that the launch has about three workgroups per compute unit (at least 64, at
+// most 512); the partial sums are added in split order by a second launch, so the result does not depend on timing.
+inline int wgrad_splits(int M, int K)
+{
+    const int tiles = ((M + 127) / 128) * ((K + 127) / 128);
+    return std::min(512, std::max(64, 768 / tiles));
+}
 
 struct Layout {      // offsets (in floats) into the workspace
     size_t mean, rstd, xn, q, k, v, a, lse, da, dq, dk, dv, dxn, D, part, total;
@@ -344,7 +385,7 @@ Layout layout(const s2_grid_t *g, int batch, int C, int heads)
     L.dv = at; at += up(T);
     L.dxn = at; at += up(T);
     L.D = at; at += up(size_t(batch) * heads * N);
-    L.part = at; at += up(size_t(kSplits) * C * C);
+    L.part = at; at += up(size_t(wgrad_splits(C, C)) * C * C);
     L.total = at;
     return L;
 }
@@ -376,9 +417,10 @@ void gemm(bool trans, int M, int N, int K, int batch, const float *W, const floa
 
 void wgrad(int M, int K, int N, int batch, const float *dY, const float *X, float *part, float *dW, hipStream_t st)
 {
-    hipLaunchKernelGGL(mha_wgrad_partial, dim3((K + kTN - 1) / kTN, (M + kTM - 1) / kTM, kSplits), dim3(256), 0, st, M, K, N,
-                       batch, kSplits, dY, X, part);
-    hipLaunchKernelGGL(mha_sum_partials, dim3((M * K + 255) / 256), dim3(256), 0, st, M * K, kSplits, part, dW);
+    const int nsplit = wgrad_splits(M, K);
+    hipLaunchKernelGGL(mha_wgrad_partial, dim3((K + kTN - 1) / kTN, (M + kTM - 1) / kTM, nsplit), dim3(256), 0, st, M, K, N,
+                       batch, nsplit, dY, X, part);
+    hipLaunchKernelGGL(mha_sum_partials, dim3((M * K + 63) / 64), dim3(256), 0, st, M * K, nsplit, part, dW);
 }
 
 }  // namespace
@@ -388,7 +430,7 @@ void s2_gemm_f32(bool trans_a, int M, int N, int K, int batch, const float *W, c
 {
     gemm(trans_a, M, N, K, batch, W, X, bias, R, C, accumulate, st);
 }
-size_t s2_wgrad_part_floats(int M, int K) { return size_t(kSplits) * M * K; }
+size_t s2_wgrad_part_floats(int M, int K) { return size_t(wgrad_splits(M, K)) * M * K; }
 void s2_wgrad_f32(int M, int K, int N, int batch, const float *dY, const float *X, float *part, float *dW, hipStream_t st)
 {
     wgrad(M, K, N, batch, dY, X, part, dW, st);
