@@ -329,6 +329,7 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run three 1 GiB device copies (scale for the rocprofv3 HBM counters)")
     ap.add_argument("--peaks", action="store_true", help="only measure the device ceilings (copy, FMA, MFMA, LDS)")
+    ap.add_argument("--layers", action="store_true", help="only time the attention sub-block and the DISCO convolution")
     ap.add_argument("--cpu-slices", type=int, default=0, help="(batch*head) slices the oracle is timed on (0 = auto)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -340,6 +341,9 @@ def main():
         return
     if args.peaks:
         peaks()
+        return
+    if args.layers:
+        print(json.dumps({"layers": measure_layers(max(args.steps // 4, 3))}))
         return
 
     from paper_2505_11157_amd.workloads import CONFIGS
