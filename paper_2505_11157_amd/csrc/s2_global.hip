@@ -287,39 +287,44 @@ global_fwd(const bf16raw *__restrict__ q, const bf16raw *__restrict__ k, const b
             f32x16 s = {0};
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) s = mfma(row_operand(cur, col, hl, kt, ks), qop[ks], s);
-            float x[16];
-            float mx = -INFINITY;
+            float x[16], e[16];
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 x[i] = fmaf(s[i], c2, -m);
                 if (!UNIFORM_W) x[i] = wk[i] > 0.f ? x[i] : -INFINITY;
-                mx = fmaxf(mx, x[i]);
             }
-            // the two half-wavefronts of a query exchange their maxima only when the reference has to move
+            // Fast path: exponentials relative to the current reference; a logit more than 2^8 above it shows in the
+            // tile sum (all terms are positive), so the sum is the overflow test and no per-element maximum is taken.
+            float psum = 0.f;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                e[i] = __builtin_amdgcn_exp2f(x[i]);
+                psum += UNIFORM_W ? e[i] : e[i] * wk[i];
+            }
             const bool first = !started;
             started = true;
-            if (first || __any(mx > 8.f)) {
+            // the two half-wavefronts of a query exchange their maxima only when the reference has to move
+            if (first || __any(!(psum <= 256.f))) {
+                float mx = -INFINITY;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) mx = fmaxf(mx, x[i]);
                 mx = fmaxf(mx, __shfl_xor(mx, 32));
                 const float delta = first ? mx : (mx > 8.f ? mx : 0.f);
                 const float corr = first ? 1.f : __builtin_amdgcn_exp2f(-delta);
                 m += delta;
                 l *= corr;
-#pragma unroll
-                for (int i = 0; i < 16; ++i) { o0[i] *= corr; o1[i] *= corr; x[i] -= delta; }
-            }
-            if (UNIFORM_W) {
-                // all 32 keys of the tile lie on one latitude: one weight for the whole tile
-                float psum = 0.f;
-#pragma unroll
-                for (int i = 0; i < 16; ++i) { x[i] = __builtin_amdgcn_exp2f(x[i]); psum += x[i]; }
-                l = fmaf(psum, wp[0], l);
-            } else {
+                psum = 0.f;
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
-                    x[i] = __builtin_amdgcn_exp2f(x[i]);
-                    l = fmaf(x[i], wk[i], l);
+                    o0[i] *= corr;
+                    o1[i] *= corr;
+                    e[i] = __builtin_amdgcn_exp2f(x[i] - delta);
+                    psum += UNIFORM_W ? e[i] : e[i] * wk[i];
                 }
             }
+            l = UNIFORM_W ? fmaf(psum, wp[0], l) : l + psum;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) x[i] = e[i];
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
                 const bf16x8 pb = pack8(x + 8 * j);
