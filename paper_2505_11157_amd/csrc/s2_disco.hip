@@ -19,6 +19,11 @@ struct s2_disco {
     int K;
     float *dev_psi = nullptr;     // [entry][KP], KP = K rounded up to a multiple of 4; entry = poff[h * band_max + b] + offset
     int *dev_poff = nullptr;      // [nlat_out * band_max]
+    // matrix-core path (equal longitude counts): the same values with 16 floats per offset and every arc padded with
+    // zero entries to a multiple of four offsets; row pitch (floats) of the staged input rows
+    float *dev_psi16 = nullptr;
+    int *dev_poff16 = nullptr;
+    int pitch16 = 0;
 };
 
 namespace {
@@ -122,6 +127,75 @@ disco_dx(S2DeviceTables t, const float *__restrict__ psi, const int *__restrict_
     dx[size_t(bc) * si + size_t(hp) * t.nlon_in + win] = acc;
 }
 
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// z on the fp32 matrix cores (equal longitude counts).  For ONE output point the contraction over the offsets of an
+// arc is a small dense product: Z[k][c] += sum_d psi[d][k] x[c][w + lo + d] -- basis index k as the row dimension
+// of v_mfma_f32_16x16x4_f32 (16 rows: the basis count padded), 16 channels as its columns, four offsets per
+// instruction.  No mask is needed (the arcs are exact; only their length is padded to a multiple of four, with zero
+// basis values) and A = psi[d0 + g][k = lane & 15] is one coalesced 256-byte read shared by every output point of the
+// latitude.  A wavefront owns 16 consecutive output longitudes (16 accumulators), a workgroup 64 longitudes x 16
+// channels of one latitude; each input row of the band is copied to LDS once (channel-major, pitch 4 mod 64 words:
+// B = x[c = lane & 15][w + lo + d0 + g] is conflict-free).  Lane (c, g) ends with z[k = 4 g + 0..3][c] of its 16
+// points: 64 contiguous bytes per (k, c).
+__global__ void __launch_bounds__(256)
+disco_z_band(S2DeviceTables t, const float *__restrict__ psi16, const int *__restrict__ poff16, int K, int pitch,
+             const float *__restrict__ x, float *__restrict__ z)
+{
+    extern __shared__ __attribute__((aligned(16))) float xs[];       // [16 channels][pitch]
+    const int nlon = t.nlon_in;
+    const int h = blockIdx.y, bc0 = blockIdx.z * 16;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n = lane & 15, g = lane >> 4;
+    const int w0g = blockIdx.x * 64, w0 = w0g + 16 * wave;
+    const bool active = w0 < nlon;
+    const size_t si = size_t(t.nlat_in) * nlon, so = size_t(t.nlat_out) * nlon;
+    f32x4 acc[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const int nb = t.band_n[h], hp0 = t.band_lo[h];
+    const int sc = tid >> 4, sp = tid & 15;         // staging: channel, first 16-byte piece
+    for (int b = 0; b < nb; ++b) {
+        const int cnt = t.cnt[h * t.band_max + b];
+        const int lo = cnt == nlon ? 0 : -((cnt - 1) >> 1), npad = (cnt + 3) & ~3;
+        const int Xs = (w0g + lo + nlon) & ~3;                                // first staged column (unwrapped)
+        const int np4 = (w0g + 63 + lo + nlon + npad - Xs + 3) >> 2;           // 16-byte pieces per channel row
+        __syncthreads();                            // the previous row has been consumed
+        const float *xr = x + size_t(bc0 + sc) * si + size_t(hp0 + b) * nlon;
+        for (int pc = sp; pc < np4; pc += 16) {
+            int col = Xs + 4 * pc;
+            col = col >= 2 * nlon ? col - 2 * nlon : col;
+            col = col >= nlon ? col - nlon : col;
+            col = col >= nlon ? col - nlon : col;
+            *reinterpret_cast<f32x4 *>(xs + sc * pitch + 4 * pc) = *reinterpret_cast<const f32x4 *>(xr + col);
+        }
+        __syncthreads();
+        if (!active) continue;
+        const float *pa = psi16 + size_t(poff16[h * t.band_max + b]) * 16 + lane;
+        const float *xb = xs + n * pitch + (w0 + lo + nlon - Xs) + g;
+        float a = pa[0];
+        for (int d0 = 0; d0 < npad; d0 += 4) {
+            const float an = d0 + 4 < npad ? pa[(d0 + 4) * 16] : 0.f;          // next step's basis values
+#pragma unroll
+            for (int wi = 0; wi < 16; ++wi)
+                acc[wi] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, xb[d0 + wi], acc[wi], 0, 0, 0);
+            a = an;
+        }
+    }
+    if (!active) return;
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr) {
+        const int k = 4 * g + rr;
+        if (k < K) {
+            float *zo = z + (size_t(bc0 + n) * K + k) * so + size_t(h) * nlon + w0;
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                *reinterpret_cast<f32x4 *>(zo + 4 * q) =
+                    f32x4{acc[4 * q][rr], acc[4 * q + 1][rr], acc[4 * q + 2][rr], acc[4 * q + 3][rr]};
+        }
+    }
+}
+
 int check(const s2_disco_t *dc, int batch, int cin, int cout, const void *ws, size_t ws_bytes)
 {
     if (!dc) return s2_fail(S2_ERR_INVALID_ARG, "disco handle is NULL");
@@ -176,7 +250,36 @@ extern "C" int s2_disco_init(const s2_grid_t *g, int nbasis, s2_disco_t **out)
                     psi.push_back(k < nbasis ? float(std::max(0.0, 1.0 - std::fabs(r / dr - k)) * g->omega_in[hp]) : 0.f);
             }
         }
+    // matrix-core path: 16 floats per offset, arcs padded to a multiple of four offsets
+    std::vector<int> poff16(poff.size(), 0);
+    std::vector<float> psi16;
+    int maxnpad = 4;
+    const bool band_ok = g->pscale == 1 && g->nlon_in == g->nlon_out && g->nlon_in % 16 == 0 && g->nlon_in >= 64 &&
+                         g->nlon_in <= 2048;
+    if (band_ok)
+        for (int h = 0; h < g->nlat_out; ++h)
+            for (int b = 0; b < g->band_n[h]; ++b) {
+                const int c = g->cnt[size_t(h) * g->band_max + b], npad = (c + 3) / 4 * 4;
+                const size_t src = size_t(poff[size_t(h) * g->band_max + b]) * KP;
+                poff16[size_t(h) * g->band_max + b] = int(psi16.size() / 16);
+                maxnpad = std::max(maxnpad, npad);
+                for (int tt = 0; tt < npad; ++tt)
+                    for (int k = 0; k < 16; ++k) psi16.push_back(tt < c && k < nbasis ? psi[src + size_t(tt) * KP + k] : 0.f);
+            }
+    dc->pitch16 = band_ok ? (64 + maxnpad + 8 + 63) / 64 * 64 + 4 : 0;
     if (g->on_device) {
+        if (band_ok) {
+            if (hipMalloc(&dc->dev_psi16, std::max<size_t>(psi16.size(), 1) * sizeof(float)) != hipSuccess ||
+                hipMalloc(&dc->dev_poff16, poff16.size() * sizeof(int)) != hipSuccess ||
+                hipMemcpy(dc->dev_psi16, psi16.data(), psi16.size() * sizeof(float), hipMemcpyHostToDevice) != hipSuccess ||
+                hipMemcpy(dc->dev_poff16, poff16.data(), poff16.size() * sizeof(int), hipMemcpyHostToDevice) != hipSuccess ||
+                hipFuncSetAttribute(reinterpret_cast<const void *>(disco_z_band), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    16 * dc->pitch16 * int(sizeof(float))) != hipSuccess) {
+                (void)hipGetLastError();
+                s2_disco_destroy(dc);
+                return s2_fail(S2_ERR_ALLOC, "set-up of the matrix-core basis tables failed");
+            }
+        }
         if (hipMalloc(&dc->dev_psi, std::max<size_t>(psi.size(), 1) * sizeof(float)) != hipSuccess ||
             hipMalloc(&dc->dev_poff, poff.size() * sizeof(int)) != hipSuccess) {
             (void)hipGetLastError();
@@ -199,6 +302,8 @@ extern "C" void s2_disco_destroy(s2_disco_t *dc)
     if (!dc) return;
     if (dc->dev_psi) (void)hipFree(dc->dev_psi);
     if (dc->dev_poff) (void)hipFree(dc->dev_poff);
+    if (dc->dev_psi16) (void)hipFree(dc->dev_psi16);
+    if (dc->dev_poff16) (void)hipFree(dc->dev_poff16);
     delete dc;
 }
 
@@ -226,10 +331,16 @@ extern "C" int s2_disco_fwd(const s2_disco_t *dc, int batch, int cin, int cout, 
     const int n_out = g->nlat_out * g->nlon_out, K = dc->K;
     {
         S2TraceScope tr("disco_z_fwd", 0.0, st);
-        const dim3 grid((g->nlon_out + 63) / 64, g->nlat_out, batch * cin);
-        by_basis(K, [&](auto KB) {
-            hipLaunchKernelGGL((disco_z_fwd<decltype(KB)::value>), grid, dim3(64), 0, st, g->dt, dc->dev_psi, dc->dev_poff, K, x, z);
-        });
+        if (dc->dev_psi16 && (batch * cin) % 16 == 0) {
+            const dim3 grid((g->nlon_out + 63) / 64, g->nlat_out, batch * cin / 16);
+            hipLaunchKernelGGL(disco_z_band, grid, dim3(256), size_t(16) * dc->pitch16 * sizeof(float), st, g->dt,
+                               dc->dev_psi16, dc->dev_poff16, K, dc->pitch16, x, z);
+        } else {
+            const dim3 grid((g->nlon_out + 63) / 64, g->nlat_out, batch * cin);
+            by_basis(K, [&](auto KB) {
+                hipLaunchKernelGGL((disco_z_fwd<decltype(KB)::value>), grid, dim3(64), 0, st, g->dt, dc->dev_psi, dc->dev_poff, K, x, z);
+            });
+        }
     }
     S2TraceScope tr("disco_mix", 0.0, st);
     s2_gemm_f32(false, cout, n_out, cin * K, batch, weight, z, bias, nullptr, y, false, st);

@@ -145,6 +145,13 @@ DISCO_CASES = [
     # 9 and 16 basis functions: the counts the paper pairs with 3 x 3 and 4 x 4 planar kernels (App. C)
     (dict(grid_type=0, nlat_in=17, nlon_in=32, nlat_out=17, nlon_out=32, theta=0.5), 1, 16, 9, 16),
     (dict(grid_type=1, nlat_in=16, nlon_in=32, nlat_out=8, nlon_out=16, theta=0.6), 2, 2, 16, 16),
+    # equal longitude counts of at least 64 and batch * channels a multiple of 16: the matrix-core kernels (short arcs
+    # and whole circles, 80 longitudes = a ragged last group, fewer output than input latitudes, the zero-weight pole row)
+    (dict(grid_type=0, nlat_in=17, nlon_in=64, nlat_out=17, nlon_out=64, theta=0.5), 2, 8, 4, 16),
+    (dict(grid_type=1, nlat_in=16, nlon_in=128, nlat_out=16, nlon_out=128, theta=0.3), 1, 16, 9, 16),
+    (dict(grid_type=0, nlat_in=9, nlon_in=80, nlat_out=9, nlon_out=80, theta=1.2), 1, 16, 3, 32),
+    (dict(grid_type=0, nlat_in=33, nlon_in=64, nlat_out=17, nlon_out=64, theta=0.4), 1, 32, 16, 16),
+    (dict(grid_type=2, nlat_in=32, nlon_in=192, nlat_out=32, nlon_out=192, theta=0.25), 1, 16, 5, 16),
 ]
 
 
