@@ -5,10 +5,11 @@
 //     y[b, o, h, w]    = sum_{c, k} weight[o, c, k] z[b, c, k, h, w] + bias[o]
 // psi_k = hat_k(r) * omega[h'] with K piecewise-linear hats of the geodesic distance r (hat_k(r) = max(0,
 // 1 - |r K / theta_cutoff - k|): isotropic filters that vanish on the rim of the disk); the paper leaves the basis
-// open.  The contraction with psi is a gather per output point (lanes on consecutive longitudes, the basis values
-// of a (latitude, offset) are uniform over a wavefront); the channel mixing is a channel matrix on the fp32 matrix
-// cores.  Backward: dx is gathered through the transposed neighborhood (no atomics), dweight is the split-K
-// weight-gradient product summed in a fixed order.
+// open.  Equal longitude counts (at least 64, a multiple of 16; batch * channels a multiple of 16) run the contraction
+// with psi on the fp32 matrix cores (disco_z_band, disco_dx_band below); other shapes use a gather per point (lanes on
+// consecutive longitudes, the basis values of a (latitude, offset) uniform over a wavefront).  The channel mixing is a
+// channel matrix on the fp32 matrix cores.  Backward: dx goes through the transposed neighborhood (no atomics), dweight
+// is the split-K weight-gradient product summed in a fixed order.
 #include <cmath>
 #include <new>
 
@@ -24,6 +25,7 @@ struct s2_disco {
     float *dev_psi16 = nullptr;
     int *dev_poff16 = nullptr;
     int pitch16 = 0;
+    int dx_lds_bytes = 0;         // dynamic LDS of the matrix-core dx kernel (0: not available)
 };
 
 namespace {
@@ -196,6 +198,79 @@ disco_z_band(S2DeviceTables t, const float *__restrict__ psi16, const int *__res
     }
 }
 
+// dx on the fp32 matrix cores (equal longitude counts, at most 512 longitudes).  For 16 consecutive input
+// longitudes x of latitude h' and 16 channels, one output latitude h of the transposed band contributes
+//     dx[c][x] += sum_{w, k} dz[c][h][w][k] psi[h, h'][x - w - lo][k],
+// a product of the 16 x (w, k) slab of dz (basis index innermost: A = dzt[c = lane & 15][w][4 q + g], one LDS word per
+// lane) with the banded matrix psi[x - w - lo][k] (B, taken from a copy of the arc's basis values in LDS that carries
+// 16 zero entries on either side, so that offsets outside the arc need no mask; entry stride 20 words: the 16 x 4
+// words a wavefront reads fall into 64 different banks).  dz is walked in chunks of 32 output longitudes; a
+// wavefront skips the output longitudes whose arcs miss its 16 inputs.  No atomics: every dx element is owned by one
+// lane.
+template <int KP>
+__global__ void __launch_bounds__(256)
+disco_dx_band(S2DeviceTables t, const float *__restrict__ psi, const int *__restrict__ poff,
+              const float *__restrict__ dzt, float *__restrict__ dx)
+{
+    constexpr int kChunk = 32, kPitchG = kChunk * KP + 4, kStride = 20, kMargin = 16, kQ = KP / 4;
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    float *G = lds, *P = lds + 16 * kPitchG;            // dz chunk [16 channels][32 w * KP]; basis values of the arc
+    const int nlon = t.nlon_in;
+    const int hp = blockIdx.y, bc0 = blockIdx.z * 16;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n = lane & 15, g = lane >> 4;
+    const int x0g = blockIdx.x * 64, x0 = x0g + 16 * wave;
+    const bool active = x0 < nlon;
+    const size_t si = size_t(t.nlat_in) * nlon, so = size_t(t.nlat_out) * nlon;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    const int nb = t.omega_rel[hp] > 0.f ? t.tband_n[hp] : 0;       // a latitude of weight zero receives nothing
+    const int h0 = t.tband_lo[hp];
+    const int sc = tid >> 4, sp = tid & 15;
+    for (int b = 0; b < nb; ++b) {
+        const int h = h0 + b;
+        const int bf = hp - t.band_lo[h];
+        const int cnt = t.cnt[h * t.band_max + bf];
+        const int lo = cnt == nlon ? 0 : -((cnt - 1) >> 1);
+        const float *pr = psi + size_t(poff[h * t.band_max + bf]) * KP;
+        __syncthreads();                               // the previous row's basis values are no longer read
+        for (int i = tid; i < (cnt + 2 * kMargin) * kStride; i += 256) P[i] = 0.f;
+        __syncthreads();
+        for (int i = tid; i < cnt * KP; i += 256) P[(i / KP + kMargin) * kStride + i % KP] = pr[i];
+        // output longitudes (unwrapped, offset by 2 nlon so that they stay positive) whose arcs meet the workgroup's /
+        // the wavefront's inputs: x - w - lo in [0, cnt)
+        const int base = 2 * nlon;
+        const int wg_lo = base + x0g - lo - cnt + 1, wg_hi = base + x0g + 63 - lo;
+        const int wv_lo = base + x0 - lo - cnt + 1, wv_hi = base + x0 + 15 - lo;
+        for (int wc = wg_lo; wc <= wg_hi; wc += kChunk) {
+            __syncthreads();                           // the previous chunk has been consumed (and P is complete)
+            {
+                const float *src = dzt + (size_t(bc0 + sc) * so + size_t(h) * nlon) * KP;
+#pragma unroll
+                for (int j = 0; j < KP / 2; ++j) {
+                    const int pc = sp + 16 * j, wo = pc / kQ, part = pc % kQ;
+                    int wphys = wc + wo;
+                    wphys -= (wphys / nlon) * nlon;
+                    *reinterpret_cast<f32x4 *>(G + sc * kPitchG + wo * KP + 4 * part) =
+                        *reinterpret_cast<const f32x4 *>(src + size_t(wphys) * KP + 4 * part);
+                }
+            }
+            __syncthreads();
+            if (!active) continue;
+            const int a = max(wc, wv_lo), e = min(wc + kChunk - 1, wv_hi);
+            for (int w = a; w <= e; ++w) {
+                const float *ga = G + n * kPitchG + (w - wc) * KP + g;
+                const float *pb = P + (base + x0 + n - w - lo + kMargin) * kStride + g;
+#pragma unroll
+                for (int q = 0; q < kQ; ++q) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(ga[4 * q], pb[4 * q], acc, 0, 0, 0);
+            }
+        }
+    }
+    if (!active) return;
+    // lane (x = n, g) holds channels 4 g + 0..3
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr) dx[size_t(bc0 + 4 * g + rr) * si + size_t(hp) * nlon + x0 + n] = acc[rr];
+}
+
 int check(const s2_disco_t *dc, int batch, int cin, int cout, const void *ws, size_t ws_bytes)
 {
     if (!dc) return s2_fail(S2_ERR_INVALID_ARG, "disco handle is NULL");
@@ -218,6 +293,16 @@ void by_basis(int K, F f)       // f(KP), KP = the basis count rounded up to a m
     else if (K <= 8) f(std::integral_constant<int, 8>());
     else if (K <= 12) f(std::integral_constant<int, 12>());
     else f(std::integral_constant<int, 16>());
+}
+
+int raise_dx_lds(int K, int bytes)
+{
+    int rc = 0;
+    by_basis(K, [&](auto KP) {
+        rc = hipFuncSetAttribute(reinterpret_cast<const void *>(disco_dx_band<decltype(KP)::value>),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess;
+    });
+    return rc;
 }
 
 }  // namespace
@@ -267,6 +352,7 @@ extern "C" int s2_disco_init(const s2_grid_t *g, int nbasis, s2_disco_t **out)
                     for (int k = 0; k < 16; ++k) psi16.push_back(tt < c && k < nbasis ? psi[src + size_t(tt) * KP + k] : 0.f);
             }
     dc->pitch16 = band_ok ? (64 + maxnpad + 8 + 63) / 64 * 64 + 4 : 0;
+    if (band_ok && g->nlon_in <= 512) dc->dx_lds_bytes = (16 * (32 * KP + 4) + (maxnpad + 32) * 20) * int(sizeof(float));
     if (g->on_device) {
         if (band_ok) {
             if (hipMalloc(&dc->dev_psi16, std::max<size_t>(psi16.size(), 1) * sizeof(float)) != hipSuccess ||
@@ -274,7 +360,8 @@ extern "C" int s2_disco_init(const s2_grid_t *g, int nbasis, s2_disco_t **out)
                 hipMemcpy(dc->dev_psi16, psi16.data(), psi16.size() * sizeof(float), hipMemcpyHostToDevice) != hipSuccess ||
                 hipMemcpy(dc->dev_poff16, poff16.data(), poff16.size() * sizeof(int), hipMemcpyHostToDevice) != hipSuccess ||
                 hipFuncSetAttribute(reinterpret_cast<const void *>(disco_z_band), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    16 * dc->pitch16 * int(sizeof(float))) != hipSuccess) {
+                                    16 * dc->pitch16 * int(sizeof(float))) != hipSuccess ||
+                (dc->dx_lds_bytes && raise_dx_lds(nbasis, dc->dx_lds_bytes))) {
                 (void)hipGetLastError();
                 s2_disco_destroy(dc);
                 return s2_fail(S2_ERR_ALLOC, "set-up of the matrix-core basis tables failed");
@@ -374,7 +461,11 @@ extern "C" int s2_disco_bwd(const s2_disco_t *dc, int batch, int cin, int cout, 
     by_basis(K, [&](auto KP) {
         const dim3 tgrid(unsigned((size_t(n_out) + 255) / 256), batch * cin);
         hipLaunchKernelGGL((disco_dz_transpose<decltype(KP)::value>), tgrid, dim3(256), 0, st, K, size_t(n_out), dz, dzt);
-        if (g->pscale == 1)
+        if (dc->dx_lds_bytes && (batch * cin) % 16 == 0) {
+            const dim3 bgrid((g->nlon_in + 63) / 64, g->nlat_in, batch * cin / 16);
+            hipLaunchKernelGGL((disco_dx_band<decltype(KP)::value>), bgrid, dim3(256), size_t(dc->dx_lds_bytes), st, g->dt,
+                               dc->dev_psi, dc->dev_poff, dzt, dx);
+        } else if (g->pscale == 1)
             hipLaunchKernelGGL((disco_dx<decltype(KP)::value, true>), grid, dim3(64), 0, st, g->dt, dc->dev_psi, dc->dev_poff, dzt, dx);
         else
             hipLaunchKernelGGL((disco_dx<decltype(KP)::value, false>), grid, dim3(64), 0, st, g->dt, dc->dev_psi, dc->dev_poff, dzt, dx);
