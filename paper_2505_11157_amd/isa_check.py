@@ -20,6 +20,7 @@ import re
 NEED = {
     "f32_32x32x2_f32": 18,       # 16 passes, fp32 inputs
     "f32_16x16x4_f32": 10,       # 8 passes
+    "f32_4x4x1_16b_f32": 4,      # 2 passes
     "f32_32x32x16_bf16": 12,     # 8 passes
     "f32_16x16x32_bf16": 8,      # 4 passes
 }
