@@ -209,7 +209,8 @@ int s2_attn_global_bwd(const s2_grid_t *g, int batch, int heads, int d, int dtyp
  * every non-NULL pointer of `grads` (same shapes as the parameters).
  * workspace: device scratch of s2_mha_workspace_bytes(...) bytes, 256-byte aligned; it carries the activations the
  * backward needs, so s2_mha_bwd must get the workspace of the matching s2_mha_fwd call, untouched.
- * channels and nlat*nlon must be multiples of 16 (else S2_ERR_UNSUPPORTED).  Every step runs in the library's own
+ * channels and nlat*nlon must be multiples of 16 (else S2_ERR_UNSUPPORTED); x, y, dy, dx, pos and the weight
+ * matrices must be 16-byte aligned (else S2_ERR_INVALID_ARG).  Every step runs in the library's own
  * kernels (channel matrices on the fp32 matrix cores); results are bit-reproducible.
  */
 typedef struct {
@@ -240,6 +241,7 @@ int s2_mha_bwd(const s2_grid_t *g, int batch, int channels, int heads, float eps
  * weight [cout][cin][nbasis], bias [cout] (may be NULL).  s2_disco_bwd writes dx and, where the pointers are not
  * NULL, dweight and dbias; it needs the workspace of the matching s2_disco_fwd call, untouched (z is kept there).
  * cin*nbasis, cout and nlat_out*nlon_out must be multiples of 16 (else S2_ERR_UNSUPPORTED); batch*cin <= 65535.
+ * x, y, dy, dx and weight must be 16-byte aligned (else S2_ERR_INVALID_ARG).
  * workspace: s2_disco_workspace_bytes(...) bytes, 256-byte aligned.  No atomics: results are bit-reproducible.
  */
 typedef struct s2_disco s2_disco_t;

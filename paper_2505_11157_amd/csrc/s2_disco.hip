@@ -411,6 +411,8 @@ extern "C" int s2_disco_fwd(const s2_disco_t *dc, int batch, int cin, int cout, 
     int rc = check(dc, batch, cin, cout, workspace, workspace_bytes);
     if (rc) return rc;
     if (!x || !weight || !y) return s2_fail(S2_ERR_INVALID_ARG, "NULL tensor pointer");
+    if ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(weight) | reinterpret_cast<uintptr_t>(y)) % 16 != 0)
+        return s2_fail(S2_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
     const s2_grid_t *g = dc->g;
     if (!g->on_device) return s2_fail(S2_ERR_DEVICE, "grid handle has no device tables (no HIP device at init)");
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
@@ -443,6 +445,8 @@ extern "C" int s2_disco_bwd(const s2_disco_t *dc, int batch, int cin, int cout, 
     int rc = check(dc, batch, cin, cout, workspace, workspace_bytes);
     if (rc) return rc;
     if (!weight || !dy || !dx) return s2_fail(S2_ERR_INVALID_ARG, "NULL tensor pointer");
+    if ((reinterpret_cast<uintptr_t>(weight) | reinterpret_cast<uintptr_t>(dy) | reinterpret_cast<uintptr_t>(dx)) % 16 != 0)
+        return s2_fail(S2_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
     const s2_grid_t *g = dc->g;
     if (!g->on_device) return s2_fail(S2_ERR_DEVICE, "grid handle has no device tables (no HIP device at init)");
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
@@ -453,7 +457,7 @@ extern "C" int s2_disco_bwd(const s2_disco_t *dc, int batch, int cin, int cout, 
     {
         S2TraceScope tr("disco_bwd mix", 0.0, st);
         if (dweight) s2_wgrad_f32(cout, cin * K, n_out, batch, dy, z, part, dweight, st);
-        if (dbias) s2_channel_sum_f32(batch, cout, n_out, dy, dbias, st);
+        if (dbias) s2_channel_sum_f32(batch, cout, n_out, dy, dbias, part, s2_wgrad_part_floats(cout, cin * K), st);
         s2_gemm_f32(true, cin * K, n_out, cout, batch, weight, dy, nullptr, nullptr, dz, false, st);
     }
     S2TraceScope tr("disco_dx", 0.0, st);

@@ -138,13 +138,15 @@ double s2_great_circle(double colat_a, double colat_b, double dphi);
 //   s2_gemm_f32:  C[b][m][n] (+)= sum_k A(m, k) X[b][k][n] + bias[m] + R[b][m][n],  A = W (M x K) or W^T (W is K x M)
 //   s2_wgrad_f32: dW[m][k] = sum_{b, n} dY[b][m][n] X[b][k][n]  (partial sums in `part`, s2_wgrad_part_floats(M, K)
 //                 floats, added in a fixed order)
-//   s2_channel_sum_f32: out[c] = sum_{b, n} u[b][c][n]
+//   s2_channel_sum_f32: out[c] = sum_{b, n} u[b][c][n]  (`part`: scratch of part_floats floats for partial sums, may be
+//                       NULL: then one workgroup per channel does the whole sum)
 // M, K multiples of 16 and N a multiple of 16.
 void s2_gemm_f32(bool trans_a, int M, int N, int K, int batch, const float *W, const float *X, const float *bias,
                  const float *R, float *C, bool accumulate, hipStream_t st);
 size_t s2_wgrad_part_floats(int M, int K);
 void s2_wgrad_f32(int M, int K, int N, int batch, const float *dY, const float *X, float *part, float *dW, hipStream_t st);
-void s2_channel_sum_f32(int batch, int C, int N, const float *u, float *out, hipStream_t st);
+void s2_channel_sum_f32(int batch, int C, int N, const float *u, float *out, float *part, size_t part_floats,
+                        hipStream_t st);
 
 void s2_set_error(const std::string &msg);
 int s2_fail(int code, const std::string &msg);

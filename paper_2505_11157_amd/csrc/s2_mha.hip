@@ -6,11 +6,17 @@
 //                                                            which is the [batch][heads][d] layout of the kernels)
 //     a    = s2_nattn_fwd(q, k, v), scale 1 / sqrt(d)
 //     y    = x + Wo a + bo
-// and its backward.  The channel matrices run on the fp32 matrix cores (v_mfma_f32_32x32x2_f32): a workgroup of four
-// wavefronts owns a 128 x 128 tile of the output, each wavefront 64 x 64 (2 x 2 matrix tiles), operands staged
-// through LDS in slices of 16 along the contraction.  Weight gradients contract over batch and grid points
+// and its backward.  The channel matrices run on the fp32 matrix cores (v_mfma_f32_32x32x2_f32).  Up to 128 channels
+// (multiples of 32 rows, 64 columns) the weight matrix stays in LDS and every wavefront streams its own 32 grid
+// points of the activations straight from memory (mha_gemm_wres); otherwise a workgroup of four wavefronts owns a
+// 128 x 128 tile of the output, each wavefront 64 x 64 (2 x 2 matrix tiles), operands staged through LDS in slices
+// of 16 along the contraction (mha_gemm).  Weight gradients contract over batch and grid points
 // (hundreds of thousands of terms): split over workgroups into partial sums that a second launch adds in a fixed
 // order, so every result is bit-reproducible.
+#include <algorithm>
+#include <initializer_list>
+#include <mutex>
+
 #include "s2_nattn_kernels.h"
 
 namespace {
@@ -132,6 +138,188 @@ mha_gemm(int M, int N, int K, const float *__restrict__ W, const float *__restri
         }
 }
 
+// The same product for small channel counts (M <= 128 a multiple of 32, K a multiple of 64, the whole weight matrix in
+// LDS): no staging of X and no barrier in the loop.  A workgroup of eight wavefronts copies W to LDS once ([k][m],
+// pitch = 33 mod 64: the two k rows one matrix instruction reads lie 33 banks apart) and then walks over tiles of 32
+// grid points; a wavefront owns a whole tile (all M rows, MT = M / 32 accumulators), reads its operand of X straight
+// from memory (lane (column, half) reads X[2 s + half][n0 + column]: each element of X is read once, by one lane, in
+// 128-byte row pieces, 16 steps ahead of their use; the first 16 steps of the NEXT tile are requested before the
+// results of this one are stored, so they do not queue behind the stores) and its operand of W from LDS.
+// The tiles are dealt out in whole rounds; what is left over after the last whole round (fewer tiles than wavefronts)
+// is cut into its MT row blocks and dealt out again, so the last round costs 1 / MT of a tile.
+struct WresTile {       // where a wavefront's operand of X starts and where its results go
+    const char *rp;     // uniform: row 0 of X[b]
+    unsigned lane_off;  // bytes: (half * N + column); lanes past the last column read column 0 (a valid address, no
+                        // branch around the loads: a branch per load makes the compiler wait for all loads in flight
+                        // at every merge) and store nothing
+    int b, n;
+    bool ok;
+};
+__device__ __forceinline__ WresTile wres_tile(int t, int tiles_per_batch, int N, int K, const float *X, int col, int kk)
+{
+    WresTile w;
+    w.b = t / tiles_per_batch;
+    w.n = (t - w.b * tiles_per_batch) * 32 + col;
+    w.ok = w.n < N;
+    w.rp = reinterpret_cast<const char *>(X + size_t(w.b) * K * N);
+    w.lane_off = unsigned((size_t(kk) * N + (w.ok ? w.n : 0)) * sizeof(float));
+    // a uniform running row pointer plus one 32-bit lane offset, kept opaque so that the compiler does not park a
+    // 64-bit lane address per load in registers
+    asm volatile("" : "+s"(w.rp));
+    asm volatile("" : "+v"(w.lane_off));
+    return w;
+}
+__device__ __forceinline__ void wres_fetch(WresTile &w, size_t step_bytes, float (&x)[16])
+{
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+        // (an explicitly global load: a flat one also counts as an LDS access, and every wait for an operand of W
+        // would then wait for all the loads of X in flight)
+        x[j] = *(const __attribute__((address_space(1))) float *)(w.rp + w.lane_off);
+        w.rp += step_bytes;
+    }
+    __builtin_amdgcn_sched_barrier(0);      // the requests stay in front of the arithmetic they are meant to overlap
+}
+// all K steps of one tile for MT row blocks starting at row m0 of W; xa holds the first 16 steps on entry
+template <int MT>
+__device__ __forceinline__ void wres_contract(WresTile &w, size_t step_bytes, int K, int pitch, const float *wl,
+                                              float (&xa)[16], f32x16 (&acc)[MT])
+{
+    float xb[16];
+    for (int s0 = 0; s0 < K / 2; s0 += 32) {       // 32 steps (64 values of k) per pass, in two halves
+        wres_fetch(w, step_bytes, xb);
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const float *wr = wl + 2 * (s0 + j) * pitch;
+#pragma unroll
+            for (int i = 0; i < MT; ++i) acc[i] = mfma32(wr[32 * i], xa[j], acc[i]);
+        }
+        if (s0 + 32 < K / 2) wres_fetch(w, step_bytes, xa);
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const float *wr = wl + 2 * (s0 + 16 + j) * pitch;
+#pragma unroll
+            for (int i = 0; i < MT; ++i) acc[i] = mfma32(wr[32 * i], xb[j], acc[i]);
+        }
+    }
+}
+// results of one tile: per row block all the reads (bias, residual, old value) are issued before the first store, so
+// they overlap instead of each waiting for the store in front of it
+template <int MT>
+__device__ __forceinline__ void wres_store(const f32x16 (&acc)[MT], int M, int N, int m0, int b, int n, int kk,
+                                           const float *__restrict__ bias, const float *__restrict__ R,
+                                           float *__restrict__ C, int accumulate)
+{
+    float *Cb = C + size_t(b) * M * N + n;
+    const float *Rb = R ? R + size_t(b) * M * N + n : nullptr;
+#pragma unroll
+    for (int i = 0; i < 2 * MT; ++i) {      // half a row block (eight rows per lane) at a time
+        float add[8], res[8], old[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int m = m0 + 16 * i + 8 * (e >> 2) + 4 * kk + (e & 3);
+            add[e] = bias ? bias[m] : 0.f;
+            res[e] = Rb ? Rb[size_t(m) * N] : 0.f;
+            old[e] = accumulate ? Cb[size_t(m) * N] : 0.f;
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int m = m0 + 16 * i + 8 * (e >> 2) + 4 * kk + (e & 3);
+            Cb[size_t(m) * N] = ((acc[i >> 1][8 * (i & 1) + e] + add[e]) + res[e]) + old[e];
+        }
+    }
+}
+
+template <bool TRANS_A, int MT>
+__global__ void __launch_bounds__(512)
+mha_gemm_wres(int M, int N, int K, int pitch, int tiles_per_batch, int ntiles, const float *__restrict__ W,
+              const float *__restrict__ X, const float *__restrict__ bias, const float *__restrict__ R,
+              float *__restrict__ C, int accumulate)
+{
+    extern __shared__ __attribute__((aligned(16))) float Ws[];      // [K][pitch]
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int col = lane & 31, kk = lane >> 5;
+    const int nwaves = gridDim.x * 8, me = blockIdx.x * 8 + wave;
+    const int whole = ntiles / nwaves * nwaves;         // tiles of the whole rounds
+    const size_t step_bytes = size_t(2) * N * sizeof(float);
+    const float *wl = Ws + kk * pitch + col;
+
+    // the first operands are requested before W is copied
+    float xa[16];
+    WresTile cur = wres_tile(me < whole ? me : 0, tiles_per_batch, N, K, X, col, kk);
+    if (me < whole) wres_fetch(cur, step_bytes, xa);
+
+    for (int i0 = tid; i0 < (M * K) >> 2; i0 += 4 * 512) {      // four 16-byte pieces in flight per thread
+        float4 w4[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int i = i0 + 512 * u;
+            w4[u] = i < (M * K) >> 2 ? *reinterpret_cast<const float4 *>(W + 4 * i) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int i = i0 + 512 * u;
+            if (i >= (M * K) >> 2) break;
+            const float4 w = w4[u];
+            if constexpr (TRANS_A) {      // W is K x M: rows are copied as they are
+                const int k = (4 * i) / M, m = 4 * i - k * M;
+                float *d = Ws + k * pitch + m;
+                d[0] = w.x; d[1] = w.y; d[2] = w.z; d[3] = w.w;
+            } else {                      // W is M x K: transposed on the way
+                const int m = (4 * i) / K, k = 4 * i - m * K;
+                float *d = Ws + k * pitch + m;
+                d[0] = w.x; d[pitch] = w.y; d[2 * pitch] = w.z; d[3 * pitch] = w.w;
+            }
+        }
+    }
+    __syncthreads();
+
+    for (int t = me; t < whole; t += nwaves) {
+        f32x16 acc[MT];
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+        wres_contract<MT>(cur, step_bytes, K, pitch, wl, xa, acc);
+        const int b = cur.b, n = cur.n;
+        const bool ok = cur.ok;
+        if (t + nwaves < whole) {
+            cur = wres_tile(t + nwaves, tiles_per_batch, N, K, X, col, kk);
+            wres_fetch(cur, step_bytes, xa);
+        }
+        if (ok) wres_store<MT>(acc, M, N, 0, b, n, kk, bias, R, C, accumulate);
+    }
+    // the tiles of the last, partial round, one row block per wavefront
+    for (int u = me; u < (ntiles - whole) * MT; u += nwaves) {
+        const int t = whole + u / MT, m0 = 32 * (u % MT);
+        WresTile w = wres_tile(t, tiles_per_batch, N, K, X, col, kk);
+        wres_fetch(w, step_bytes, xa);
+        f32x16 acc[1];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[0][e] = 0.f;
+        wres_contract<1>(w, step_bytes, K, pitch, wl + m0, xa, acc);
+        if (w.ok) wres_store<1>(acc, M, N, m0, w.b, w.n, kk, bias, R, C, accumulate);
+    }
+}
+
+// LDS row pitch of the resident weight matrix: the smallest p >= M with p = 33 mod 64
+inline int wres_pitch(int M) { return (M + 30) / 64 * 64 + 33; }
+inline int num_compute_units()
+{
+    static const int ncu = [] {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1)
+            n = 256;
+        return n;
+    }();
+    return ncu;
+}
+inline bool wres_ok(int M, int K)
+{
+    return M % 32 == 0 && M <= 128 && K % 64 == 0 && size_t(K) * wres_pitch(M) * sizeof(float) <= 160 * 1024;
+}
+
 // Partial weight gradients: part[split][m][k] = sum over the split's share of (batch, grid point) of
 // dY[b][m][n] X[b][k][n].  M, K multiples of 16, N a multiple of 16.  grid (ceil(K / 128), ceil(M / 128), splits).
 __global__ void __launch_bounds__(256)
@@ -247,26 +435,44 @@ __device__ __forceinline__ float block_sum(float x, float *red)
 }
 
 // Instance normalisation: one workgroup per (batch, channel): mean and 1 / sqrt(var + eps) over the N grid points
-// (two passes: the moments are taken about the mean), then xn = gamma xhat + beta + pos.
+// (two passes: the moments are taken about the mean), then xn = gamma xhat + beta + pos.  N is a multiple of 4 and the
+// rows are 16-byte aligned: 16-byte accesses, each lane with four running sums (one per component) that are added in a
+// fixed order.
+__device__ __forceinline__ float sum4(float4 a) { return (a.x + a.y) + (a.z + a.w); }
+
 __global__ void __launch_bounds__(256)
 mha_instnorm_fwd(int C, int N, float eps, const float *__restrict__ x, const float *__restrict__ gamma,
                  const float *__restrict__ beta, const float *__restrict__ pos, float *__restrict__ mean,
                  float *__restrict__ rstd, float *__restrict__ xn)
 {
     __shared__ float red[256];
-    const int bc = blockIdx.x, c = bc % C, tid = threadIdx.x;
-    const float *xr = x + size_t(bc) * N;
-    float s = 0.f;
-    for (int i = tid; i < N; i += 256) s += xr[i];
-    const float mu = block_sum(s, red) / float(N);
-    float v = 0.f;
-    for (int i = tid; i < N; i += 256) { const float dlt = xr[i] - mu; v = fmaf(dlt, dlt, v); }
-    const float rs = 1.f / sqrtf(block_sum(v, red) / float(N) + eps);
+    const int bc = blockIdx.x, c = bc % C, tid = threadIdx.x, n4 = N >> 2;
+    const float4 *xr = reinterpret_cast<const float4 *>(x + size_t(bc) * N);
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll 4
+    for (int i = tid; i < n4; i += 256) {
+        const float4 a = xr[i];
+        s.x += a.x; s.y += a.y; s.z += a.z; s.w += a.w;
+    }
+    const float mu = block_sum(sum4(s), red) / float(N);
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll 4
+    for (int i = tid; i < n4; i += 256) {
+        const float4 a = xr[i];
+        const float dx = a.x - mu, dy = a.y - mu, dz = a.z - mu, dw = a.w - mu;
+        v.x = fmaf(dx, dx, v.x); v.y = fmaf(dy, dy, v.y); v.z = fmaf(dz, dz, v.z); v.w = fmaf(dw, dw, v.w);
+    }
+    const float rs = 1.f / sqrtf(block_sum(sum4(v), red) / float(N) + eps);
     if (tid == 0) { mean[bc] = mu; rstd[bc] = rs; }
     const float ga = gamma ? gamma[c] : 1.f, be = beta ? beta[c] : 0.f;
-    const float *pr = pos ? pos + size_t(c) * N : nullptr;
-    float *o = xn + size_t(bc) * N;
-    for (int i = tid; i < N; i += 256) o[i] = fmaf(ga, (xr[i] - mu) * rs, be) + (pr ? pr[i] : 0.f);
+    const float4 *pr = pos ? reinterpret_cast<const float4 *>(pos + size_t(c) * N) : nullptr;
+    float4 *o = reinterpret_cast<float4 *>(xn + size_t(bc) * N);
+#pragma unroll 4
+    for (int i = tid; i < n4; i += 256) {
+        const float4 a = xr[i], p = pr ? pr[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+        o[i] = make_float4(fmaf(ga, (a.x - mu) * rs, be) + p.x, fmaf(ga, (a.y - mu) * rs, be) + p.y,
+                           fmaf(ga, (a.z - mu) * rs, be) + p.z, fmaf(ga, (a.w - mu) * rs, be) + p.w);
+    }
 }
 
 // dx = dy + rstd (dxhat - mean(dxhat) - xhat mean(dxhat xhat)), dxhat = gamma dxn; one workgroup per (batch, channel)
@@ -276,20 +482,27 @@ mha_instnorm_bwd(int C, int N, const float *__restrict__ x, const float *__restr
                  float *__restrict__ dx)
 {
     __shared__ float red[256];
-    const int bc = blockIdx.x, c = bc % C, tid = threadIdx.x;
+    const int bc = blockIdx.x, c = bc % C, tid = threadIdx.x, n4 = N >> 2;
     const float mu = mean[bc], rs = rstd[bc], ga = gamma ? gamma[c] : 1.f;
-    const float *xr = x + size_t(bc) * N, *gr = dxn + size_t(bc) * N, *yr = dy + size_t(bc) * N;
-    float s1 = 0.f, s2 = 0.f;
-    for (int i = tid; i < N; i += 256) {
-        const float dh = ga * gr[i];
-        s1 += dh;
-        s2 = fmaf(dh, (xr[i] - mu) * rs, s2);
+    const float4 *xr = reinterpret_cast<const float4 *>(x + size_t(bc) * N);
+    const float4 *gr = reinterpret_cast<const float4 *>(dxn + size_t(bc) * N);
+    const float4 *yr = reinterpret_cast<const float4 *>(dy + size_t(bc) * N);
+    float4 s1 = make_float4(0.f, 0.f, 0.f, 0.f), s2 = s1;
+#pragma unroll 2
+    for (int i = tid; i < n4; i += 256) {
+        const float4 g = gr[i], a = xr[i];
+        const float hx = ga * g.x, hy = ga * g.y, hz = ga * g.z, hw = ga * g.w;
+        s1.x += hx; s1.y += hy; s1.z += hz; s1.w += hw;
+        s2.x = fmaf(hx, (a.x - mu) * rs, s2.x); s2.y = fmaf(hy, (a.y - mu) * rs, s2.y);
+        s2.z = fmaf(hz, (a.z - mu) * rs, s2.z); s2.w = fmaf(hw, (a.w - mu) * rs, s2.w);
     }
-    const float m1 = block_sum(s1, red) / float(N), m2 = block_sum(s2, red) / float(N);
-    float *o = dx + size_t(bc) * N;
-    for (int i = tid; i < N; i += 256) {
-        const float xh = (xr[i] - mu) * rs;
-        o[i] = yr[i] + rs * (ga * gr[i] - m1 - xh * m2);
+    const float m1 = block_sum(sum4(s1), red) / float(N), m2 = block_sum(sum4(s2), red) / float(N);
+    float4 *o = reinterpret_cast<float4 *>(dx + size_t(bc) * N);
+#pragma unroll 2
+    for (int i = tid; i < n4; i += 256) {
+        const float4 g = gr[i], a = xr[i], y = yr[i];
+        o[i] = make_float4(y.x + rs * (ga * g.x - m1 - (a.x - mu) * rs * m2), y.y + rs * (ga * g.y - m1 - (a.y - mu) * rs * m2),
+                           y.z + rs * (ga * g.z - m1 - (a.z - mu) * rs * m2), y.w + rs * (ga * g.w - m1 - (a.w - mu) * rs * m2));
     }
 }
 
@@ -343,6 +556,50 @@ mha_channel_sum(int batch, int C, int N, const float *__restrict__ u, const floa
     if (tid == 0) out[c] = r;
 }
 
+// The same sum in two launches for rows that are multiples of 16 bytes: workgroup (c, p) adds piece p % seg of row
+// (batch element p / seg, channel c) into part[p][c]; mha_sum_partials adds the pieces in order.  Many more workgroups
+// than channels (one workgroup per channel leaves most of the device idle), still a fixed order of additions.
+__global__ void __launch_bounds__(256)
+mha_channel_sum_pieces(int C, int N, int seg, const float *__restrict__ u, const float *__restrict__ x,
+                       const float *__restrict__ mean, const float *__restrict__ rstd, float *__restrict__ part)
+{
+    __shared__ float red[256];
+    const int c = blockIdx.x, p = blockIdx.y, b = p / seg, tid = threadIdx.x;
+    const int n4 = N >> 2, len = (n4 + seg - 1) / seg, lo = (p - b * seg) * len, hi = min(n4, lo + len);
+    const float4 *u4 = reinterpret_cast<const float4 *>(u + (size_t(b) * C + c) * N);
+    float s[4] = {0.f, 0.f, 0.f, 0.f};
+    if (x) {
+        const float4 *x4 = reinterpret_cast<const float4 *>(x + (size_t(b) * C + c) * N);
+        const float mu = mean[b * C + c], rs = rstd[b * C + c];
+        for (int i0 = lo + tid; i0 < hi; i0 += 1024) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int i = i0 + 256 * j;
+                if (i < hi) {
+                    const float4 a = u4[i], v = x4[i];
+                    s[j] = fmaf(a.x, (v.x - mu) * rs, s[j]);
+                    s[j] = fmaf(a.y, (v.y - mu) * rs, s[j]);
+                    s[j] = fmaf(a.z, (v.z - mu) * rs, s[j]);
+                    s[j] = fmaf(a.w, (v.w - mu) * rs, s[j]);
+                }
+            }
+        }
+    } else {
+        for (int i0 = lo + tid; i0 < hi; i0 += 1024) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int i = i0 + 256 * j;
+                if (i < hi) {
+                    const float4 a = u4[i];
+                    s[j] += (a.x + a.y) + (a.z + a.w);
+                }
+            }
+        }
+    }
+    const float r = block_sum((s[0] + s[1]) + (s[2] + s[3]), red);
+    if (tid == 0) part[size_t(p) * C + c] = r;
+}
+
 // dpos[c][n] = sum_b dxn[b][c][n]
 __global__ void __launch_bounds__(256)
 mha_batch_sum(int batch, size_t CN, const float *__restrict__ u, float *__restrict__ out)
@@ -390,6 +647,14 @@ Layout layout(const s2_grid_t *g, int batch, int C, int heads)
     return L;
 }
 
+// the kernels read tensors and weight matrices in 16-byte pieces (NULL = an optional tensor that is absent)
+bool aligned16(std::initializer_list<const void *> ptrs)
+{
+    for (const void *q : ptrs)
+        if (reinterpret_cast<uintptr_t>(q) % 16 != 0) return false;
+    return true;
+}
+
 int check(const s2_grid_t *g, int batch, int C, int heads, const void *ws, size_t ws_bytes)
 {
     if (!g) return s2_fail(S2_ERR_INVALID_ARG, "grid is NULL");
@@ -405,9 +670,51 @@ int check(const s2_grid_t *g, int batch, int C, int heads, const void *ws, size_
     return S2_OK;
 }
 
+// out[c] = sum over batch and grid points of u (times xhat if x is given).  With scratch for the pieces (`part`,
+// part_floats floats) and rows that are multiples of 16 bytes the sum is cut into about 2048 workgroups.
+void channel_sum(int batch, int C, int N, const float *u, const float *x, const float *mean, const float *rstd, float *out,
+                 float *part, size_t part_floats, hipStream_t st)
+{
+    const int seg = std::min(16, std::max(1, (2048 + C * batch - 1) / (C * batch)));
+    const size_t pieces = size_t(batch) * seg;
+    if (N % 4 != 0 || !part || pieces * C > part_floats || pieces > 65535) {
+        hipLaunchKernelGGL(mha_channel_sum, dim3(C), dim3(256), 0, st, batch, C, N, u, x, mean, rstd, out);
+        return;
+    }
+    hipLaunchKernelGGL(mha_channel_sum_pieces, dim3(C, unsigned(pieces)), dim3(256), 0, st, C, N, seg, u, x, mean, rstd, part);
+    hipLaunchKernelGGL(mha_sum_partials, dim3((C + 63) / 64), dim3(256), 0, st, C, int(pieces), part, out);
+}
+
 void gemm(bool trans, int M, int N, int K, int batch, const float *W, const float *X, const float *bias, const float *R,
           float *C, bool accumulate, hipStream_t st)
 {
+    if (wres_ok(M, K)) {
+        const int pitch = wres_pitch(M), tpb = (N + 31) / 32, ntiles = tpb * batch;
+        const size_t lds = size_t(K) * pitch * sizeof(float);
+        const int nwg = std::min((ntiles + 7) / 8, num_compute_units());
+#define S2_WRES(T, MT)                                                                                                 \
+    do {                                                                                                               \
+        static std::once_flag once;                                                                                    \
+        std::call_once(once, [] {                                                                                      \
+            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(mha_gemm_wres<T, MT>),                            \
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);                         \
+        });                                                                                                            \
+        hipLaunchKernelGGL((mha_gemm_wres<T, MT>), dim3(nwg), dim3(512), lds, st, M, N, K, pitch, tpb, ntiles, W, X,  \
+                           bias, R, C, int(accumulate));                                                               \
+    } while (0)
+        switch (M / 32 + (trans ? 4 : 0)) {
+        case 1: S2_WRES(false, 1); break;
+        case 2: S2_WRES(false, 2); break;
+        case 3: S2_WRES(false, 3); break;
+        case 4: S2_WRES(false, 4); break;
+        case 5: S2_WRES(true, 1); break;
+        case 6: S2_WRES(true, 2); break;
+        case 7: S2_WRES(true, 3); break;
+        default: S2_WRES(true, 4); break;
+        }
+#undef S2_WRES
+        return;
+    }
     const dim3 grid((N + kTN - 1) / kTN, (M + kTM - 1) / kTM, batch);
     if (trans)
         hipLaunchKernelGGL(mha_gemm<true>, grid, dim3(256), 0, st, M, N, K, W, X, bias, R, C, int(accumulate));
@@ -435,10 +742,10 @@ void s2_wgrad_f32(int M, int K, int N, int batch, const float *dY, const float *
 {
     wgrad(M, K, N, batch, dY, X, part, dW, st);
 }
-void s2_channel_sum_f32(int batch, int C, int N, const float *u, float *out, hipStream_t st)
+void s2_channel_sum_f32(int batch, int C, int N, const float *u, float *out, float *part, size_t part_floats,
+                        hipStream_t st)
 {
-    hipLaunchKernelGGL(mha_channel_sum, dim3(C), dim3(256), 0, st, batch, C, N, u, static_cast<const float *>(nullptr),
-                       static_cast<const float *>(nullptr), static_cast<const float *>(nullptr), out);
+    channel_sum(batch, C, N, u, nullptr, nullptr, nullptr, out, part, part_floats, st);
 }
 
 extern "C" size_t s2_mha_workspace_bytes(const s2_grid_t *g, int batch, int channels, int heads)
@@ -453,6 +760,8 @@ extern "C" int s2_mha_fwd(const s2_grid_t *g, int batch, int channels, int heads
     int rc = check(g, batch, channels, heads, workspace, workspace_bytes);
     if (rc) return rc;
     if (!x || !p || !y || !p->Wq || !p->Wk || !p->Wv || !p->Wo) return s2_fail(S2_ERR_INVALID_ARG, "NULL tensor or weight pointer");
+    if (!aligned16({x, y, p->pos, p->Wq, p->Wk, p->Wv, p->Wo}))
+        return s2_fail(S2_ERR_INVALID_ARG, "x, y, pos and the weight matrices must be 16-byte aligned");
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const int C = channels, N = g->nlat_in * g->nlon_in, d = C / heads;
     float *ws = static_cast<float *>(workspace);
@@ -488,6 +797,8 @@ extern "C" int s2_mha_bwd(const s2_grid_t *g, int batch, int channels, int heads
     if (rc) return rc;
     if (!x || !p || !dy || !dx || !grads || !p->Wq || !p->Wk || !p->Wv || !p->Wo)
         return s2_fail(S2_ERR_INVALID_ARG, "NULL tensor or weight pointer");
+    if (!aligned16({x, dy, dx, p->pos, p->Wq, p->Wk, p->Wv, p->Wo}))
+        return s2_fail(S2_ERR_INVALID_ARG, "x, dy, dx, pos and the weight matrices must be 16-byte aligned");
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const int C = channels, N = g->nlat_in * g->nlon_in, d = C / heads;
     float *ws = static_cast<float *>(workspace);
@@ -495,8 +806,8 @@ extern "C" int s2_mha_bwd(const s2_grid_t *g, int batch, int channels, int heads
     float *gWq = grads->Wq, *gWk = grads->Wk, *gWv = grads->Wv, *gWo = grads->Wo;
     auto chan = [&](const float *u, bool with_xhat, float *dst) {
         if (dst)
-            hipLaunchKernelGGL(mha_channel_sum, dim3(C), dim3(256), 0, st, batch, C, N, u, with_xhat ? x : nullptr,
-                               ws + L.mean, ws + L.rstd, dst);
+            channel_sum(batch, C, N, u, with_xhat ? x : nullptr, ws + L.mean, ws + L.rstd, dst, ws + L.part,
+                        L.total - L.part, st);
     };
     {
         // y = x + Wo a + bo

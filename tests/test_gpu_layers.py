@@ -55,6 +55,8 @@ MHA_CASES = [
     (dict(grid_type=0, nlat_in=25, nlon_in=256, nlat_out=25, nlon_out=256, theta=0.25), 1, 160, 5),
     (dict(grid_type=0, nlat_in=33, nlon_in=192, nlat_out=33, nlon_out=192, theta=0.3), 1, 48, 3),
     (dict(grid_type=1, nlat_in=16, nlon_in=128, nlat_out=16, nlon_out=128, theta=0.45), 1, 128, 2),
+    # 64 channels on 816 grid points: the weight-resident channel products with a last tile of 16 of 32 points
+    (dict(grid_type=0, nlat_in=17, nlon_in=48, nlat_out=17, nlon_out=48, theta=0.5), 1, 64, 4),
 ]
 
 
@@ -100,6 +102,34 @@ def test_mha_block(ci):
     assert torch.equal(y, y2) and torch.equal(dx, dx2) and all(torch.equal(grads[k], grads2[k]) for k in grads)
 
 
+def test_mha_channel_products_at_full_size_do_not_depend_on_the_tile_schedule():
+    # 4 x 65 x 512 points, 128 channels: the weight-resident channel products run two whole rounds of tiles per
+    # wavefront (operands of the next tile requested before the results of the last are stored) plus a partial round
+    # cut into row blocks; one batch element alone is a single round with another tile-to-wavefront map.  Every output
+    # column is the same sequence of matrix instructions either way, so y and dx must agree bit for bit (the small
+    # cases above pin both kinds of round to the oracle; the weight gradients sum over the batch and are left out).
+    gd = dict(grid_type=0, nlat_in=65, nlon_in=512, nlat_out=65, nlon_out=512, theta=0.06)
+    B, C, heads = 4, 128, 8
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device="cpu").manual_seed(977)
+    rnd = lambda *shape: torch.randn(*shape, generator=gen).to(dev)
+    x, dy = rnd(B, C, 65, 512), rnd(B, C, 65, 512)
+    P = dict(gamma=1 + 0.2 * rnd(C), beta=0.3 * rnd(C), pos=0.5 * rnd(C, 65, 512))
+    for n in "qkvo":
+        P["W" + n] = rnd(C, C) / math.sqrt(C)
+        P["b" + n] = 0.3 * rnd(C)
+    g = S.s2_grid_init(gd["grid_type"], gd["nlat_in"], gd["nlon_in"], gd["nlat_out"], gd["nlon_out"], gd["theta"])
+    y, ws = S.s2_mha_fwd(g, x, P, heads)
+    dx, _ = S.s2_mha_bwd(g, x, P, heads, dy, ws)
+    torch.cuda.synchronize()
+    assert S.s2_grid_device_flags(g) == 0
+    assert torch.isfinite(y).all() and torch.isfinite(dx).all()
+    for b in range(B):
+        y1, ws1 = S.s2_mha_fwd(g, x[b:b + 1].contiguous(), P, heads)
+        dx1, _ = S.s2_mha_bwd(g, x[b:b + 1].contiguous(), P, heads, dy[b:b + 1].contiguous(), ws1)
+        assert torch.equal(y[b:b + 1], y1) and torch.equal(dx[b:b + 1], dx1), "batch element %d" % b
+
+
 def test_mha_optional_parameters_and_errors():
     gd = MHA_CASES[0][0]
     g = S.s2_grid_init(gd["grid_type"], gd["nlat_in"], gd["nlon_in"], gd["nlat_out"], gd["nlon_out"], gd["theta"])
@@ -132,6 +162,15 @@ def test_mha_optional_parameters_and_errors():
     with pytest.raises(S.S2Error) as ei:
         S.s2_mha_fwd(g2, x, P, heads)
     assert ei.value.code == S.S2_ERR_UNSUPPORTED
+    buf = torch.zeros(x.numel() + 1, dtype=torch.float32, device=dev)
+    x_off = buf[1:].view_as(x)                            # contiguous, but 4 bytes off a 16-byte boundary
+    x_off.copy_(x)
+    with pytest.raises(S.S2Error) as ei:
+        S.s2_mha_fwd(g, x_off, P, heads)
+    assert ei.value.code == S.S2_ERR_INVALID_ARG
+    with pytest.raises(S.S2Error) as ei:
+        S.s2_mha_bwd(g, x, P, heads, x_off, ws)
+    assert ei.value.code == S.S2_ERR_INVALID_ARG
     torch.cuda.synchronize()
 
 
