@@ -686,6 +686,26 @@ unsigned blocks(const S2DeviceTables &t, int nbh, int nlat)
     return unsigned(long((nlat + 3) / 4) * nbh * ((t.nlon_in + Geo<D, NO>::OW - 1) / Geo<D, NO>::OW));
 }
 
+// Few workgroups (small grids, few slices): d = 32 then runs with two owner tiles per wavefront instead of four:
+// twice the workgroups for a device that would otherwise be half empty, at the price of staging 96 columns for 32
+// owners instead of 128 for 64.
+inline int num_cus()
+{
+    static const int ncu = [] {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1)
+            n = 256;
+        return n;
+    }();
+    return ncu;
+}
+template <int D>
+bool narrow(const S2DeviceTables &t, int nbh, int nlat)
+{
+    return blocks<D, 4>(t, nbh, nlat) < unsigned(2 * num_cus());
+}
+
 double pair_count(const S2DeviceTables &t, bool fwd_side, int nbh)
 {
     const double *p = fwd_side ? t.fwd_pairs : t.bwd_pairs;
@@ -730,6 +750,7 @@ void fwd_by_d(const S2DeviceTables &t, int nbh, int d, float scale, const void *
     const T *Q = static_cast<const T *>(q), *K = static_cast<const T *>(k), *V = static_cast<const T *>(v);
     T *O = static_cast<T *>(out);
     if (d == 16) launch_fwd<T, 16, 4>(t, nbh, scale, Q, K, V, O, lse, st);
+    else if (d == 32 && narrow<32>(t, nbh, t.nlat_out)) launch_fwd<T, 32, 2>(t, nbh, scale, Q, K, V, O, lse, st);
     else if (d == 32) launch_fwd<T, 32, 4>(t, nbh, scale, Q, K, V, O, lse, st);
     else launch_fwd<T, 64, 2>(t, nbh, scale, Q, K, V, O, lse, st);
 }
@@ -741,6 +762,7 @@ void dq_by_d(const S2DeviceTables &t, int nbh, int d, float scale, const void *q
     const T *O = static_cast<const T *>(o), *G = static_cast<const T *>(go);
     T *DQ = static_cast<T *>(dq);
     if (d == 16) launch_dq<T, 16, 4>(t, nbh, scale, Q, K, V, O, lse, G, DQ, Dws, st);
+    else if (d == 32 && narrow<32>(t, nbh, t.nlat_out)) launch_dq<T, 32, 2>(t, nbh, scale, Q, K, V, O, lse, G, DQ, Dws, st);
     else if (d == 32) launch_dq<T, 32, 4>(t, nbh, scale, Q, K, V, O, lse, G, DQ, Dws, st);
     else launch_dq<T, 64, 2>(t, nbh, scale, Q, K, V, O, lse, G, DQ, Dws, st);
 }
@@ -752,6 +774,7 @@ void dkdv_by_d(const S2DeviceTables &t, int nbh, int d, float scale, const void 
     const T *G = static_cast<const T *>(go);
     T *DK = static_cast<T *>(dk), *DV = static_cast<T *>(dv);
     if (d == 16) launch_dkdv<T, 16, 4>(t, nbh, scale, Q, K, V, lse, G, Dws, DK, DV, st);
+    else if (d == 32 && narrow<32>(t, nbh, t.nlat_in)) launch_dkdv<T, 32, 2>(t, nbh, scale, Q, K, V, lse, G, Dws, DK, DV, st);
     else if (d == 32) launch_dkdv<T, 32, 4>(t, nbh, scale, Q, K, V, lse, G, Dws, DK, DV, st);
     else launch_dkdv<T, 64, 2>(t, nbh, scale, Q, K, V, lse, G, Dws, DK, DV, st);
 }
@@ -761,7 +784,9 @@ void dkdv_by_d(const S2DeviceTables &t, int nbh, int d, float scale, const void 
 int s2_nattn_band_configure()
 {
     return configure_one<float, 16, 4>() || configure_one<float, 32, 4>() || configure_one<float, 64, 2>() ||
-           configure_one<bf16raw, 16, 4>() || configure_one<bf16raw, 32, 4>() || configure_one<bf16raw, 64, 2>();
+           configure_one<float, 32, 2>() ||
+           configure_one<bf16raw, 16, 4>() || configure_one<bf16raw, 32, 4>() || configure_one<bf16raw, 64, 2>() ||
+           configure_one<bf16raw, 32, 2>();
 }
 
 bool s2_nattn_band_supported(const S2DeviceTables &t, int d, int e)

@@ -39,6 +39,16 @@ def test_band_kernels(i, d):
         run_case(c, arrs, [0, 2], case="band%d[d%d]" % (i, d))
 
 
+@pytest.mark.parametrize("i", [1, 12])
+def test_band_kernels_d32_many_slices(i):
+    # d = 32 runs with two owner tiles per wavefront while a launch has few workgroups (every case above) and with four
+    # from about two workgroups per compute unit on: 20 slices reach that; three of them against the oracle
+    gt, nlat, nlon, theta = SHAPES[i]
+    c, arrs = make_inputs(_c(gt, nlat, nlon, theta, 4, 5, 32), seed=930 + i)
+    with debug_switches(S.S2_DEBUG_FORCE_BAND):
+        run_case(c, arrs, [0, 7, 19], case="band%d[d32,20 slices]" % i)
+
+
 @pytest.mark.parametrize("d", [16, 64])
 @pytest.mark.parametrize("factor,sign", [(6.0, 1.0), (6.0, -1.0)])
 def test_band_kernels_peaked(d, factor, sign):
