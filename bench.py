@@ -333,8 +333,8 @@ def main():
     ap.add_argument("--cpu-slices", type=int, default=0, help="(batch*head) slices the oracle is timed on (0 = auto)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (--gpus 1); batch*heads shards need no exchange, "
-              "see DESIGN.md", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (--gpus 1): every (batch, head) slice is an independent "
+              "problem, so several GPUs would each take a share of the slices with no exchange", file=sys.stderr)
         sys.exit(2)
     if args.copy_calibration:
         copy_calibration()
