@@ -193,7 +193,7 @@ static int upload_tables(s2_grid *g)
         if (int(done.size()) < ndev) done.resize(ndev, 0);
         if (!done[g->device]) {
             if (s2_nattn_tiled_configure() || s2_nattn_bwd_tiled_configure() || s2_nattn_stream_configure() ||
-                s2_nattn_mfma_configure() || s2_nattn_band_configure()) {
+                s2_nattn_mfma_configure() || s2_nattn_band_configure() || s2_mha_configure()) {
                 (void)hipGetLastError();
                 return s2_fail(S2_ERR_DEVICE, "raising the LDS limit of a kernel failed");
             }

@@ -130,6 +130,7 @@ int s2_nattn_bwd_tiled_configure();
 int s2_nattn_stream_configure();
 int s2_nattn_mfma_configure();
 int s2_nattn_band_configure();
+int s2_mha_configure();
 
 // great-circle angle between two points given by their colatitudes and their difference in longitude (float64)
 double s2_great_circle(double colat_a, double colat_b, double dphi);

@@ -15,7 +15,6 @@
 // order, so every result is bit-reproducible.
 #include <algorithm>
 #include <initializer_list>
-#include <mutex>
 
 #include "s2_nattn_kernels.h"
 
@@ -693,15 +692,8 @@ void gemm(bool trans, int M, int N, int K, int batch, const float *W, const floa
         const size_t lds = size_t(K) * pitch * sizeof(float);
         const int nwg = std::min((ntiles + 7) / 8, num_compute_units());
 #define S2_WRES(T, MT)                                                                                                 \
-    do {                                                                                                               \
-        static std::once_flag once;                                                                                    \
-        std::call_once(once, [] {                                                                                      \
-            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(mha_gemm_wres<T, MT>),                            \
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);                         \
-        });                                                                                                            \
-        hipLaunchKernelGGL((mha_gemm_wres<T, MT>), dim3(nwg), dim3(512), lds, st, M, N, K, pitch, tpb, ntiles, W, X,  \
-                           bias, R, C, int(accumulate));                                                               \
-    } while (0)
+    hipLaunchKernelGGL((mha_gemm_wres<T, MT>), dim3(nwg), dim3(512), lds, st, M, N, K, pitch, tpb, ntiles, W, X, bias, \
+                       R, C, int(accumulate))
         switch (M / 32 + (trans ? 4 : 0)) {
         case 1: S2_WRES(false, 1); break;
         case 2: S2_WRES(false, 2); break;
@@ -731,6 +723,20 @@ void wgrad(int M, int K, int N, int batch, const float *dY, const float *X, floa
 }
 
 }  // namespace
+
+// once per device (from s2_grid_init): the weight-resident channel products keep up to 160 KB of LDS
+int s2_mha_configure()
+{
+    auto raise = [](auto kern) {
+        return hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   160 * 1024) == hipSuccess;
+    };
+    return raise(mha_gemm_wres<false, 1>) && raise(mha_gemm_wres<false, 2>) && raise(mha_gemm_wres<false, 3>) &&
+                   raise(mha_gemm_wres<false, 4>) && raise(mha_gemm_wres<true, 1>) && raise(mha_gemm_wres<true, 2>) &&
+                   raise(mha_gemm_wres<true, 3>) && raise(mha_gemm_wres<true, 4>)
+               ? 0
+               : -1;
+}
 
 void s2_gemm_f32(bool trans_a, int M, int N, int K, int batch, const float *W, const float *X, const float *bias,
                  const float *R, float *C, bool accumulate, hipStream_t st)

@@ -13,6 +13,7 @@ int s2_nattn_bwd_tiled_configure() { return 0; }
 int s2_nattn_stream_configure() { return 0; }
 int s2_nattn_mfma_configure() { return 0; }
 int s2_nattn_band_configure() { return 0; }
+int s2_mha_configure() { return 0; }
 int s2_static_scratch_setup(int) { return 0; }
 
 static int check_grid(int type, int nlat_in, int nlon_in, int nlat_out, int nlon_out, double theta)
