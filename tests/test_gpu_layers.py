@@ -60,9 +60,24 @@ MHA_CASES = [
 ]
 
 
-@pytest.mark.parametrize("ci", range(len(MHA_CASES)))
+def _random_mha_case(seed):
+    # seeded random sub-blocks: equal grids with 9 to 24 latitudes and 32 to 160 longitudes (multiples of 16), 64 or 128
+    # channels (weight-resident channel products: ragged last tiles, one or several rounds) or 32, 96, 160 (tiled ones)
+    rng = np.random.default_rng(9900 + seed)
+    C = (64, 128, 32, 96, 128, 64, 160, 128)[seed % 8]
+    d = int(rng.choice([8, 16, 32]))
+    nlat, nlon = int(rng.integers(9, 25)), 16 * int(rng.integers(2, 11))
+    gd = dict(grid_type=int(rng.integers(0, 2)), nlat_in=nlat, nlon_in=nlon, nlat_out=nlat, nlon_out=nlon,
+              theta=float(rng.uniform(2.0, 4.0)) * math.pi / nlat)
+    return gd, int(rng.integers(1, 4)), C, C // d
+
+
+MHA_RANDOM = 8
+
+
+@pytest.mark.parametrize("ci", range(len(MHA_CASES) + MHA_RANDOM))
 def test_mha_block(ci):
-    gd, B, C, heads = MHA_CASES[ci]
+    gd, B, C, heads = MHA_CASES[ci] if ci < len(MHA_CASES) else _random_mha_case(ci - len(MHA_CASES))
     rng = np.random.default_rng(900 + ci)
     shp = (B, C, gd["nlat_in"], gd["nlon_in"])
     f32 = lambda a: np.asarray(a, np.float32)

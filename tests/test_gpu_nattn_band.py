@@ -49,6 +49,30 @@ def test_band_kernels_d32_many_slices(i):
         run_case(c, arrs, [0, 7, 19], case="band%d[d32,20 slices]" % i)
 
 
+@pytest.mark.parametrize("seed", range(30))
+def test_band_kernels_random_shapes(seed):
+    # seeded random equal grids (all grid types, 5 to 40 latitudes, longitude counts that are multiples of 16 from 64 to
+    # 320, random cutoffs, 1 to 24 slices: few and many workgroups, ragged last groups and segments, short arcs, long
+    # arcs and whole circles in whatever mix comes up) for d = 16, 32 (routed to the band tiles) and 64; one random slice
+    # against the oracle
+    rng = np.random.default_rng(8100 + seed)
+    d = (16, 32, 64)[seed % 3]
+    gt = int(rng.integers(0, 4))
+    nlat = int(rng.integers(5, 41))
+    nlon = 16 * int(rng.integers(4, 21))
+    theta = float(rng.uniform(1.2, 7.0)) * math.pi / nlat
+    batch, heads = int(rng.integers(1, 5)), int(rng.integers(1, 7))
+    c = _c(gt, nlat, nlon, theta, batch, heads, d)
+    try:
+        S.s2_grid_init(gt, nlat, nlon, nlat, nlon, theta)
+    except S.S2Error as err:
+        assert err.code in (S.S2_ERR_EMPTY_NEIGHBORHOOD, S.S2_ERR_AMBIGUOUS_CUTOFF)
+        pytest.skip("cutoff rejected for this random grid")
+    c, arrs = make_inputs(c, seed=8200 + seed)
+    with debug_switches(S.S2_DEBUG_FORCE_BAND if d == 32 else 0):
+        run_case(c, arrs, [int(rng.integers(0, batch * heads))], case="band-random%d[d%d]" % (seed, d))
+
+
 @pytest.mark.parametrize("d", [16, 64])
 @pytest.mark.parametrize("factor,sign", [(6.0, 1.0), (6.0, -1.0)])
 def test_band_kernels_peaked(d, factor, sign):
