@@ -29,7 +29,7 @@ extern "C" size_t s2_nattn_bwd_workspace_bytes(const s2_grid_t *g, int batch, in
 
 // The fp32 band-tile kernels take the head dimensions the hand-tuned d = 32 kernels do not cover, and d = 32 itself on
 // grids whose light latitudes do not have the structure the streaming kernels need (bands of more than nine rows,
-// e.g. the 64 x 128 Gauss grid: measured 0.56 against 0.71 ms per step there, but 3.1 against 2.5 ms on the
+// e.g. the 64 x 128 Gauss grid: measured 0.41 against 0.71 ms per step there, but 2.9 against 2.5 ms on the
 // 129 x 256 grid, where the streaming kernels run).
 static bool use_band(const S2DeviceTables &t, int d, int e)
 {

@@ -48,8 +48,9 @@ struct Geo {
     static constexpr int PITCH = COLS + 16;      // floats per channel row (16 mod 32); row c starts 4 ((c >> 2) & 3) floats in
     static constexpr int TILE = D * PITCH;       // floats per staged tensor
     static constexpr int P4 = SW / 4;            // 16-byte pieces per channel row
-    static constexpr int NP = D * P4 / 256;      // pieces per thread and tensor
-    static_assert(D * P4 % 256 == 0 && PITCH % 32 == 16, "geometry");
+    static constexpr int NP = (D * P4 + 255) / 256;      // pieces per thread and tensor (the last may be partial)
+    static constexpr bool EVEN = D * P4 % 256 == 0;
+    static_assert(PITCH % 32 == 16, "geometry");
 };
 
 // Storage type of the tensors: float, or bf16 bits (arithmetic, staged tiles, logsumexp and D stay float32).
@@ -166,7 +167,7 @@ __device__ __forceinline__ void load_stage(f32x4 (&r)[NP], const T *slice, size_
 #pragma unroll
     for (int j = 0; j < G::NP; ++j) {
         const int i = tid + 256 * j, c = i / G::P4, pc = i % G::P4;
-        r[j] = ld4(slice + size_t(c) * plane + size_t(lat) * nlon + wrap3(Xs + 4 * pc, nlon));
+        if (G::EVEN || i < D * G::P4) r[j] = ld4(slice + size_t(c) * plane + size_t(lat) * nlon + wrap3(Xs + 4 * pc, nlon));
     }
 }
 template <int D, int NO, int NP>
@@ -177,7 +178,7 @@ __device__ __forceinline__ void store_stage(float *tile, const f32x4 (&r)[NP], i
 #pragma unroll
     for (int j = 0; j < G::NP; ++j) {
         const int i = tid + 256 * j, c = i / G::P4, pc = i % G::P4;
-        *reinterpret_cast<f32x4 *>(tile + c * G::PITCH + 4 * ((c >> 2) & 3) + 4 * pc) = r[j];
+        if (G::EVEN || i < D * G::P4) *reinterpret_cast<f32x4 *>(tile + c * G::PITCH + 4 * ((c >> 2) & 3) + 4 * pc) = r[j];
     }
 }
 
@@ -686,9 +687,10 @@ unsigned blocks(const S2DeviceTables &t, int nbh, int nlat)
     return unsigned(long((nlat + 3) / 4) * nbh * ((t.nlon_in + Geo<D, NO>::OW - 1) / Geo<D, NO>::OW));
 }
 
-// Few workgroups (small grids, few slices): d = 32 then runs with two owner tiles per wavefront instead of four:
-// twice the workgroups for a device that would otherwise be half empty, at the price of staging 96 columns for 32
-// owners instead of 128 for 64.
+// Owner tiles per wavefront.  d = 32 and 64: two (for d = 32 four were measured too: 3.13 against 2.88 ms on workload 3,
+// 0.58 against 0.41 ms on workload 2 with its 256 workgroups: smaller tiles in LDS and fewer registers put more
+// workgroups on a compute unit, which outweighs staging 96 columns per 32 owners instead of 128 per 64).  d = 16: four
+// (two measured the same on workload 8), two while a launch would have fewer than two workgroups per compute unit.
 inline int num_cus()
 {
     static const int ncu = [] {
@@ -700,10 +702,9 @@ inline int num_cus()
     }();
     return ncu;
 }
-template <int D>
-bool narrow(const S2DeviceTables &t, int nbh, int nlat)
+inline bool narrow16(const S2DeviceTables &t, int nbh, int nlat)
 {
-    return blocks<D, 4>(t, nbh, nlat) < unsigned(2 * num_cus());
+    return blocks<16, 4>(t, nbh, nlat) < unsigned(2 * num_cus());
 }
 
 double pair_count(const S2DeviceTables &t, bool fwd_side, int nbh)
@@ -749,9 +750,9 @@ void fwd_by_d(const S2DeviceTables &t, int nbh, int d, float scale, const void *
 {
     const T *Q = static_cast<const T *>(q), *K = static_cast<const T *>(k), *V = static_cast<const T *>(v);
     T *O = static_cast<T *>(out);
-    if (d == 16) launch_fwd<T, 16, 4>(t, nbh, scale, Q, K, V, O, lse, st);
-    else if (d == 32 && narrow<32>(t, nbh, t.nlat_out)) launch_fwd<T, 32, 2>(t, nbh, scale, Q, K, V, O, lse, st);
-    else if (d == 32) launch_fwd<T, 32, 4>(t, nbh, scale, Q, K, V, O, lse, st);
+    if (d == 16 && narrow16(t, nbh, t.nlat_out)) launch_fwd<T, 16, 2>(t, nbh, scale, Q, K, V, O, lse, st);
+    else if (d == 16) launch_fwd<T, 16, 4>(t, nbh, scale, Q, K, V, O, lse, st);
+    else if (d == 32) launch_fwd<T, 32, 2>(t, nbh, scale, Q, K, V, O, lse, st);
     else launch_fwd<T, 64, 2>(t, nbh, scale, Q, K, V, O, lse, st);
 }
 template <class T>
@@ -761,9 +762,9 @@ void dq_by_d(const S2DeviceTables &t, int nbh, int d, float scale, const void *q
     const T *Q = static_cast<const T *>(q), *K = static_cast<const T *>(k), *V = static_cast<const T *>(v);
     const T *O = static_cast<const T *>(o), *G = static_cast<const T *>(go);
     T *DQ = static_cast<T *>(dq);
-    if (d == 16) launch_dq<T, 16, 4>(t, nbh, scale, Q, K, V, O, lse, G, DQ, Dws, st);
-    else if (d == 32 && narrow<32>(t, nbh, t.nlat_out)) launch_dq<T, 32, 2>(t, nbh, scale, Q, K, V, O, lse, G, DQ, Dws, st);
-    else if (d == 32) launch_dq<T, 32, 4>(t, nbh, scale, Q, K, V, O, lse, G, DQ, Dws, st);
+    if (d == 16 && narrow16(t, nbh, t.nlat_out)) launch_dq<T, 16, 2>(t, nbh, scale, Q, K, V, O, lse, G, DQ, Dws, st);
+    else if (d == 16) launch_dq<T, 16, 4>(t, nbh, scale, Q, K, V, O, lse, G, DQ, Dws, st);
+    else if (d == 32) launch_dq<T, 32, 2>(t, nbh, scale, Q, K, V, O, lse, G, DQ, Dws, st);
     else launch_dq<T, 64, 2>(t, nbh, scale, Q, K, V, O, lse, G, DQ, Dws, st);
 }
 template <class T>
@@ -773,9 +774,9 @@ void dkdv_by_d(const S2DeviceTables &t, int nbh, int d, float scale, const void 
     const T *Q = static_cast<const T *>(q), *K = static_cast<const T *>(k), *V = static_cast<const T *>(v);
     const T *G = static_cast<const T *>(go);
     T *DK = static_cast<T *>(dk), *DV = static_cast<T *>(dv);
-    if (d == 16) launch_dkdv<T, 16, 4>(t, nbh, scale, Q, K, V, lse, G, Dws, DK, DV, st);
-    else if (d == 32 && narrow<32>(t, nbh, t.nlat_in)) launch_dkdv<T, 32, 2>(t, nbh, scale, Q, K, V, lse, G, Dws, DK, DV, st);
-    else if (d == 32) launch_dkdv<T, 32, 4>(t, nbh, scale, Q, K, V, lse, G, Dws, DK, DV, st);
+    if (d == 16 && narrow16(t, nbh, t.nlat_in)) launch_dkdv<T, 16, 2>(t, nbh, scale, Q, K, V, lse, G, Dws, DK, DV, st);
+    else if (d == 16) launch_dkdv<T, 16, 4>(t, nbh, scale, Q, K, V, lse, G, Dws, DK, DV, st);
+    else if (d == 32) launch_dkdv<T, 32, 2>(t, nbh, scale, Q, K, V, lse, G, Dws, DK, DV, st);
     else launch_dkdv<T, 64, 2>(t, nbh, scale, Q, K, V, lse, G, Dws, DK, DV, st);
 }
 
@@ -783,10 +784,9 @@ void dkdv_by_d(const S2DeviceTables &t, int nbh, int d, float scale, const void 
 
 int s2_nattn_band_configure()
 {
-    return configure_one<float, 16, 4>() || configure_one<float, 32, 4>() || configure_one<float, 64, 2>() ||
-           configure_one<float, 32, 2>() ||
-           configure_one<bf16raw, 16, 4>() || configure_one<bf16raw, 32, 4>() || configure_one<bf16raw, 64, 2>() ||
-           configure_one<bf16raw, 32, 2>();
+    return configure_one<float, 16, 4>() || configure_one<float, 16, 2>() || configure_one<float, 32, 2>() ||
+           configure_one<float, 64, 2>() || configure_one<bf16raw, 16, 4>() || configure_one<bf16raw, 16, 2>() ||
+           configure_one<bf16raw, 32, 2>() || configure_one<bf16raw, 64, 2>();
 }
 
 bool s2_nattn_band_supported(const S2DeviceTables &t, int d, int e)

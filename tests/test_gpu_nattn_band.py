@@ -41,8 +41,8 @@ def test_band_kernels(i, d):
 
 @pytest.mark.parametrize("i", [1, 12])
 def test_band_kernels_d32_many_slices(i):
-    # d = 32 runs with two owner tiles per wavefront while a launch has few workgroups (every case above) and with four
-    # from about two workgroups per compute unit on: 20 slices reach that; three of them against the oracle
+    # 20 slices (more than two workgroups per compute unit; d = 16 switches from two to four owner tiles per wavefront
+    # at that point, see the random shapes): three of them against the oracle
     gt, nlat, nlon, theta = SHAPES[i]
     c, arrs = make_inputs(_c(gt, nlat, nlon, theta, 4, 5, 32), seed=930 + i)
     with debug_switches(S.S2_DEBUG_FORCE_BAND):
