@@ -724,7 +724,7 @@ struct LightMeta {
     }
 };
 
-__global__ void __launch_bounds__(256, 3)
+__global__ void __launch_bounds__(256, 4)
 nattn_fwd_bf16_light(S2DeviceTables t, int nbh, float c2, const bf16raw *__restrict__ q, const bf16raw *__restrict__ k,
                      const bf16raw *__restrict__ v, bf16raw *__restrict__ out, float *__restrict__ lse)
 {
@@ -979,7 +979,7 @@ nattn_bwd_dq_bf16_light(S2DeviceTables t, int nbh, float scale, const bf16raw *_
     }
 }
 
-__global__ void __launch_bounds__(256, 2)
+__global__ void __launch_bounds__(256, 3)
 nattn_bwd_dkdv_bf16_light(S2DeviceTables t, int nbh, float scale, const bf16raw *__restrict__ q, const bf16raw *__restrict__ k,
                           const bf16raw *__restrict__ v, const float *__restrict__ lse, const bf16raw *__restrict__ go,
                           const float *__restrict__ Dws, bf16raw *__restrict__ dk, bf16raw *__restrict__ dv)
