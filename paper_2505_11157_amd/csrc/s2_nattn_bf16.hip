@@ -14,8 +14,8 @@
 // next matrix instruction (O^T += V P^T) without moving data between lanes.  The four lanes of an output share the
 // running reference maximum, which moves only when a logit exceeds it by more than 2^8.
 //
-// Staging.  A workgroup of four wavefronts owns 256 consecutive points of one latitude (64 per wavefront, four
-// 16-point tiles) and streams the other side in stages of 64 columns through LDS, double buffered, one barrier per
+// Staging.  A workgroup of four wavefronts owns 128 consecutive points of one latitude (32 per wavefront, two
+// 16-point tiles; the kernels carry the tile count as a template parameter) and streams the other side in stages of 64 columns through LDS, double buffered, one barrier per
 // stage.  Operands contracted over channels (K for the scores, V for dP, q and dout in the dk/dv kernel) are needed
 // token-major (a key's 32 channels contiguous), but the tensors are channel-major: the 16-byte pieces a thread
 // loads (8 columns of one channel) are scattered into a token-major tile with eight 2-byte LDS writes; the operands
@@ -167,33 +167,35 @@ __device__ __forceinline__ bool inside(const RowWindow &r, int Xt, int Wo)
 }
 
 // ---------------------------------------------------------------------------------------------------------------
-// Forward.  Block -> (output latitude by work, slice, group of 256 longitudes).
+// Forward.  Block -> (output latitude by work, slice, group of 64 NOW longitudes); NOW = owner tiles per wavefront.
+template <int NOW>
 __global__ void __launch_bounds__(256, 3)
 nattn_fwd_bf16(S2DeviceTables t, int nbh, int first_row, float c2, const bf16raw *__restrict__ q, const bf16raw *__restrict__ k,
                const bf16raw *__restrict__ v, bf16raw *__restrict__ out, float *__restrict__ lse)
 {
     __shared__ __attribute__((aligned(16))) char lds[2][kTokBytes + kChanBytes];
     const int nlon = t.nlon_in;
-    const int ngrp = (nlon + 255) >> 8;
+    constexpr int GW = 64 * NOW, WW = 16 * NOW;          // owners per workgroup and per wavefront
+    const int ngrp = (nlon + GW - 1) / GW;
     int id = blockIdx.x;
     const int grp = id % ngrp; id /= ngrp;
     const int bh = id % nbh;
     const int h = t.row_order[first_row + id / nbh];
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 15, g = lane >> 4;
-    const int W0 = grp << 8;
-    const int nown = nlon - W0 < 256 ? nlon - W0 : 256;
-    const bool active = W0 + 64 * wave < nlon;          // longitude counts are multiples of 64: all or nothing
+    const int W0 = grp * GW;
+    const int nown = nlon - W0 < GW ? nlon - W0 : GW;
+    const bool active = W0 + WW * wave < nlon;          // longitude counts are multiples of 64: all or nothing
     const size_t plane = size_t(t.nlat_in) * nlon;      // equal grids
     const bf16raw *qs = q + size_t(bh) * kD * plane, *ks = k + size_t(bh) * kD * plane, *vs = v + size_t(bh) * kD * plane;
-    const int Wb = nlon + W0 + 64 * wave;               // unwrapped column of the wavefront's first owner
+    const int Wb = nlon + W0 + WW * wave;               // unwrapped column of the wavefront's first owner
 
-    bf16x8 qreg[4];
-    f32x4 acc[4][2];
-    float m[4], l[4];
+    bf16x8 qreg[NOW];
+    f32x4 acc[NOW][2];
+    float m[NOW], l[NOW];
 #pragma unroll
-    for (int o = 0; o < 4; ++o) {
-        if (active) qreg[o] = gather_point(qs, plane, size_t(h) * nlon + (W0 + 64 * wave + 16 * o + n), g);
+    for (int o = 0; o < NOW; ++o) {
+        if (active) qreg[o] = gather_point(qs, plane, size_t(h) * nlon + (W0 + WW * wave + 16 * o + n), g);
         acc[o][0] = acc[o][1] = f32x4{0.f, 0.f, 0.f, 0.f};
         m[o] = -INFINITY;
         l[o] = 0.f;
@@ -234,7 +236,7 @@ nattn_fwd_bf16(S2DeviceTables t, int nbh, int first_row, float c2, const bf16raw
             for (int j = 0; j < 2; ++j) {
                 const bf16x8 v0 = chan_operand(Vc, 0, 2 * j, 2 * j + 1, lane), v1 = chan_operand(Vc, 1, 2 * j, 2 * j + 1, lane);
 #pragma unroll
-                for (int o = 0; o < 4; ++o) {
+                for (int o = 0; o < NOW; ++o) {
                     const int Wo = Wb + 16 * o;
                     f32x4 x[2];
                     bool tch[2];
@@ -298,10 +300,10 @@ nattn_fwd_bf16(S2DeviceTables t, int nbh, int first_row, float c2, const bf16raw
     if (!active) return;
     const size_t so = plane;
 #pragma unroll
-    for (int o = 0; o < 4; ++o) {
+    for (int o = 0; o < NOW; ++o) {
         const float lt = group_sum(l[o]);
         const float inv = 1.f / lt;
-        const size_t at = size_t(h) * nlon + (W0 + 64 * wave + 16 * o + n);
+        const size_t at = size_t(h) * nlon + (W0 + WW * wave + 16 * o + n);
         bf16raw *ob = out + size_t(bh) * kD * so + at;
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt)
@@ -314,6 +316,7 @@ nattn_fwd_bf16(S2DeviceTables t, int nbh, int first_row, float c2, const bf16raw
 // ---------------------------------------------------------------------------------------------------------------
 // Backward, query side: D_i = dout_i . out_i (stored for the key side), dS_ij = p_ij (dout_i . v_j - D_i),
 // dq_i = scale sum_j dS_ij k_j, with p_ij = omega_j exp(scale q_i.k_j - lse_i) recomputed from the saved logsumexp.
+template <int NOW>
 __global__ void __launch_bounds__(256, 3)
 nattn_bwd_dq_bf16(S2DeviceTables t, int nbh, int first_row, float scale, const bf16raw *__restrict__ q, const bf16raw *__restrict__ k,
                   const bf16raw *__restrict__ v, const bf16raw *__restrict__ o_, const float *__restrict__ lse,
@@ -322,32 +325,33 @@ nattn_bwd_dq_bf16(S2DeviceTables t, int nbh, int first_row, float scale, const b
     constexpr int kStage = 2 * kTokBytes + kChanBytes;       // K and V token-major, K channel-major
     __shared__ __attribute__((aligned(16))) char lds[2][kStage];
     const int nlon = t.nlon_in;
-    const int ngrp = (nlon + 255) >> 8;
+    constexpr int GW = 64 * NOW, WW = 16 * NOW;          // owners per workgroup and per wavefront
+    const int ngrp = (nlon + GW - 1) / GW;
     int id = blockIdx.x;
     const int grp = id % ngrp; id /= ngrp;
     const int bh = id % nbh;
     const int h = t.row_order[first_row + id / nbh];
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 15, g = lane >> 4;
-    const int W0 = grp << 8;
-    const int nown = nlon - W0 < 256 ? nlon - W0 : 256;
-    const bool active = W0 + 64 * wave < nlon;
+    const int W0 = grp * GW;
+    const int nown = nlon - W0 < GW ? nlon - W0 : GW;
+    const bool active = W0 + WW * wave < nlon;
     const size_t plane = size_t(t.nlat_in) * nlon;
     const bf16raw *qs = q + size_t(bh) * kD * plane, *ks = k + size_t(bh) * kD * plane, *vs = v + size_t(bh) * kD * plane;
     const bf16raw *os = o_ + size_t(bh) * kD * plane, *gs = go + size_t(bh) * kD * plane;
-    const int Wb = nlon + W0 + 64 * wave;
+    const int Wb = nlon + W0 + WW * wave;
     const float c2 = scale * kLog2e;
 
-    bf16x8 qreg[4], greg[4];
-    f32x4 acc[4][2];
-    float L2[4], Dn[4];
+    bf16x8 qreg[NOW], greg[NOW];
+    f32x4 acc[NOW][2];
+    float L2[NOW], Dn[NOW];
 #pragma unroll
-    for (int o = 0; o < 4; ++o) {
+    for (int o = 0; o < NOW; ++o) {
         acc[o][0] = acc[o][1] = f32x4{0.f, 0.f, 0.f, 0.f};
         L2[o] = 0.f;
         Dn[o] = 0.f;
         if (active) {
-            const size_t at = size_t(h) * nlon + (W0 + 64 * wave + 16 * o + n);
+            const size_t at = size_t(h) * nlon + (W0 + WW * wave + 16 * o + n);
             qreg[o] = gather_point(qs, plane, at, g);
             greg[o] = gather_point(gs, plane, at, g);
             const bf16x8 oo = gather_point(os, plane, at, g);
@@ -393,7 +397,7 @@ nattn_bwd_dq_bf16(S2DeviceTables t, int nbh, int first_row, float scale, const b
             for (int j = 0; j < 2; ++j) {
                 const bf16x8 k0 = chan_operand(Kc, 0, 2 * j, 2 * j + 1, lane), k1 = chan_operand(Kc, 1, 2 * j, 2 * j + 1, lane);
 #pragma unroll
-                for (int o = 0; o < 4; ++o) {
+                for (int o = 0; o < NOW; ++o) {
                     const int Wo = Wb + 16 * o;
                     f32x4 ds[2];
                     bool any_tile = false;
@@ -436,8 +440,8 @@ nattn_bwd_dq_bf16(S2DeviceTables t, int nbh, int first_row, float scale, const b
     }
     if (!active) return;
 #pragma unroll
-    for (int o = 0; o < 4; ++o) {
-        bf16raw *ob = dq + size_t(bh) * kD * plane + size_t(h) * nlon + (W0 + 64 * wave + 16 * o + n);
+    for (int o = 0; o < NOW; ++o) {
+        bf16raw *ob = dq + size_t(bh) * kD * plane + size_t(h) * nlon + (W0 + WW * wave + 16 * o + n);
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
@@ -449,6 +453,7 @@ nattn_bwd_dq_bf16(S2DeviceTables t, int nbh, int first_row, float scale, const b
 // Backward, key side: the owners are input points j (lane = (key n, output group g)); the outputs whose disk holds j
 // are, on every output latitude of the transposed band, the columns within the same half-width of j.
 // dk_j = scale sum_i dS_ij q_i, dv_j = sum_i p_ij dout_i: gathered, no atomics.
+template <int NOW>
 __global__ void __launch_bounds__(256)
 nattn_bwd_dkdv_bf16(S2DeviceTables t, int nbh, int first_row, float scale, const bf16raw *__restrict__ q, const bf16raw *__restrict__ k,
                     const bf16raw *__restrict__ v, const float *__restrict__ lse, const bf16raw *__restrict__ go,
@@ -457,32 +462,33 @@ nattn_bwd_dkdv_bf16(S2DeviceTables t, int nbh, int first_row, float scale, const
     constexpr int kStage = 2 * kTokBytes + 2 * kChanBytes + 512;     // q, dout token-major; q, dout channel-major; L2, -D
     __shared__ __attribute__((aligned(16))) char lds[2][kStage];
     const int nlon = t.nlon_in;
-    const int ngrp = (nlon + 255) >> 8;
+    constexpr int GW = 64 * NOW, WW = 16 * NOW;          // owners per workgroup and per wavefront
+    const int ngrp = (nlon + GW - 1) / GW;
     int id = blockIdx.x;
     const int grp = id % ngrp; id /= ngrp;
     const int bh = id % nbh;
     const int hp = t.trow_order[first_row + id / nbh];
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 15, g = lane >> 4;
-    const int W0 = grp << 8;
-    const int nown = nlon - W0 < 256 ? nlon - W0 : 256;
-    const bool active = W0 + 64 * wave < nlon;
+    const int W0 = grp * GW;
+    const int nown = nlon - W0 < GW ? nlon - W0 : GW;
+    const bool active = W0 + WW * wave < nlon;
     const size_t plane = size_t(t.nlat_in) * nlon;
     const bf16raw *qs = q + size_t(bh) * kD * plane, *ks = k + size_t(bh) * kD * plane, *vs = v + size_t(bh) * kD * plane;
     const bf16raw *gs = go + size_t(bh) * kD * plane;
     const float *ls = lse + size_t(bh) * plane, *Ds = Dws + size_t(bh) * plane;
-    const int Wb = nlon + W0 + 64 * wave;
+    const int Wb = nlon + W0 + WW * wave;
     const float c2 = scale * kLog2e;
     const float lw2 = __log2f(t.omega_rel[hp]);     // -inf for a latitude of weight zero: p = 0
     const float lref = t.ln_omega_ref;
 
-    bf16x8 kreg[4], vreg[4];
-    f32x4 adk[4][2], adv[4][2];
+    bf16x8 kreg[NOW], vreg[NOW];
+    f32x4 adk[NOW][2], adv[NOW][2];
 #pragma unroll
-    for (int o = 0; o < 4; ++o) {
+    for (int o = 0; o < NOW; ++o) {
         adk[o][0] = adk[o][1] = adv[o][0] = adv[o][1] = f32x4{0.f, 0.f, 0.f, 0.f};
         if (active) {
-            const size_t at = size_t(hp) * nlon + (W0 + 64 * wave + 16 * o + n);
+            const size_t at = size_t(hp) * nlon + (W0 + WW * wave + 16 * o + n);
             kreg[o] = gather_point(ks, plane, at, g);
             vreg[o] = gather_point(vs, plane, at, g);
         }
@@ -544,7 +550,7 @@ nattn_bwd_dkdv_bf16(S2DeviceTables t, int nbh, int first_row, float scale, const
                     Dm[u] = *reinterpret_cast<const f32x4 *>(Dn + 16 * (2 * j + u) + 4 * g);
                 }
 #pragma unroll
-                for (int o = 0; o < 4; ++o) {
+                for (int o = 0; o < NOW; ++o) {
                     const int Wo = Wb + 16 * o;
                     f32x4 p[2], ds[2];
                     bool any_tile = false;
@@ -592,8 +598,8 @@ nattn_bwd_dkdv_bf16(S2DeviceTables t, int nbh, int first_row, float scale, const
     }
     if (!active) return;
 #pragma unroll
-    for (int o = 0; o < 4; ++o) {
-        const size_t at = size_t(bh) * kD * plane + size_t(hp) * nlon + (W0 + 64 * wave + 16 * o + n);
+    for (int o = 0; o < NOW; ++o) {
+        const size_t at = size_t(bh) * kD * plane + size_t(hp) * nlon + (W0 + WW * wave + 16 * o + n);
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
@@ -1126,13 +1132,18 @@ nattn_bwd_dkdv_bf16_light(S2DeviceTables t, int nbh, float scale, const bf16raw 
 
 // Two launches per kernel: the latitudes of the three heavy classes (dense neighborhoods near the poles), then the
 // light ones; the library's launch trace reports them separately.
+// Owner tiles per wavefront of the one-latitude kernels: two (a workgroup owns 128 points).  With four the dense
+// latitudes of the 129 x 256 workload are 512 workgroups, two wavefronts per SIMD, and the launches wait half of their
+// time; with two: forward 0.145 -> 0.077 ms, dq 0.150 -> 0.087, dk/dv 0.203 -> 0.159 (one tile: the same again).
+constexpr int kDenseTiles = 2;
+
 template <class F>
 static void launch_by_class(const S2DeviceTables &t, bool fwd_side, int nbh, const char *dense_name, const char *light_name,
                             hipStream_t st, F launch)
 {
     const int *cls = fwd_side ? t.fwd_cls : t.bwd_cls;
     const double *pairs = fwd_side ? t.fwd_pairs : t.bwd_pairs;
-    const int ngrp = (t.nlon_in + 255) / 256;
+    const int ngrp = (t.nlon_in + 64 * kDenseTiles - 1) / (64 * kDenseTiles);
     const int ndense = cls[0] + cls[1] + cls[2];
     if (ndense > 0) {
         S2TraceScope tr(dense_name, nbh * (pairs[0] + pairs[1] + pairs[2]), st);
@@ -1159,7 +1170,7 @@ int s2_nattn_fwd_bf16(const S2DeviceTables &t, int nbh, int, int, float scale, c
                                static_cast<const bf16raw *>(v), static_cast<bf16raw *>(out), lse);
             return;
         }
-        hipLaunchKernelGGL(nattn_fwd_bf16, dim3(nblk), dim3(256), 0, st, t, nbh, first, scale * kLog2e,
+        hipLaunchKernelGGL(nattn_fwd_bf16<kDenseTiles>, dim3(nblk), dim3(256), 0, st, t, nbh, first, scale * kLog2e,
                            static_cast<const bf16raw *>(q), static_cast<const bf16raw *>(k),
                            static_cast<const bf16raw *>(v), static_cast<bf16raw *>(out), lse);
     });
@@ -1179,7 +1190,7 @@ int s2_nattn_bwd_dq_bf16(const S2DeviceTables &t, int nbh, int, int, float scale
                                static_cast<const bf16raw *>(go), static_cast<bf16raw *>(dq), Dws);
             return;
         }
-        hipLaunchKernelGGL(nattn_bwd_dq_bf16, dim3(nblk), dim3(256), 0, st, t, nbh, first, scale,
+        hipLaunchKernelGGL(nattn_bwd_dq_bf16<kDenseTiles>, dim3(nblk), dim3(256), 0, st, t, nbh, first, scale,
                            static_cast<const bf16raw *>(q), static_cast<const bf16raw *>(k),
                            static_cast<const bf16raw *>(v), static_cast<const bf16raw *>(o), lse,
                            static_cast<const bf16raw *>(go), static_cast<bf16raw *>(dq), Dws);
@@ -1200,7 +1211,7 @@ int s2_nattn_bwd_dkdv_bf16(const S2DeviceTables &t, int nbh, int, int, float sca
                                static_cast<bf16raw *>(dk), static_cast<bf16raw *>(dv));
             return;
         }
-        hipLaunchKernelGGL(nattn_bwd_dkdv_bf16, dim3(nblk), dim3(256), 0, st, t, nbh, first, scale,
+        hipLaunchKernelGGL(nattn_bwd_dkdv_bf16<kDenseTiles>, dim3(nblk), dim3(256), 0, st, t, nbh, first, scale,
                            static_cast<const bf16raw *>(q), static_cast<const bf16raw *>(k),
                            static_cast<const bf16raw *>(v), lse, static_cast<const bf16raw *>(go), Dws,
                            static_cast<bf16raw *>(dk), static_cast<bf16raw *>(dv));
