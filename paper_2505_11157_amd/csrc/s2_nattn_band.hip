@@ -45,7 +45,7 @@ struct Geo {
     static constexpr int OW = 16 * NO;           // longitudes per workgroup
     static constexpr int SW = OW + 64;           // staged columns
     static constexpr int COLS = SW + 32;         // + zeroed padding (a tile may reach past the window)
-    static constexpr int PITCH = COLS + 16;      // floats per channel row (16 mod 32); row c starts 4 ((c >> 2) & 3) floats in
+    static constexpr int PITCH = (COLS + 16) % 32 == 16 ? COLS + 16 : COLS + 32;      // floats per channel row (16 mod 32); row c starts 4 ((c >> 2) & 3) floats in
     static constexpr int TILE = D * PITCH;       // floats per staged tensor
     static constexpr int P4 = SW / 4;            // 16-byte pieces per channel row
     static constexpr int NP = (D * P4 + 255) / 256;      // pieces per thread and tensor (the last may be partial)
@@ -691,6 +691,7 @@ unsigned blocks(const S2DeviceTables &t, int nbh, int nlat)
 // 0.58 against 0.41 ms on workload 2 with its 256 workgroups: smaller tiles in LDS and fewer registers put more
 // workgroups on a compute unit, which outweighs staging 96 columns per 32 owners instead of 128 per 64).  d = 16: four
 // (two measured the same on workload 8), two while a launch would have fewer than two workgroups per compute unit.
+// d = 32 on launches that would still leave the device half empty (fewer than four workgroups per compute unit): one.
 inline int num_cus()
 {
     static const int ncu = [] {
@@ -701,6 +702,10 @@ inline int num_cus()
         return n;
     }();
     return ncu;
+}
+inline bool tiny32(const S2DeviceTables &t, int nbh, int nlat)
+{
+    return blocks<32, 2>(t, nbh, nlat) < unsigned(4 * num_cus());
 }
 inline bool narrow16(const S2DeviceTables &t, int nbh, int nlat)
 {
@@ -752,6 +757,7 @@ void fwd_by_d(const S2DeviceTables &t, int nbh, int d, float scale, const void *
     T *O = static_cast<T *>(out);
     if (d == 16 && narrow16(t, nbh, t.nlat_out)) launch_fwd<T, 16, 2>(t, nbh, scale, Q, K, V, O, lse, st);
     else if (d == 16) launch_fwd<T, 16, 4>(t, nbh, scale, Q, K, V, O, lse, st);
+    else if (d == 32 && tiny32(t, nbh, t.nlat_out)) launch_fwd<T, 32, 1>(t, nbh, scale, Q, K, V, O, lse, st);
     else if (d == 32) launch_fwd<T, 32, 2>(t, nbh, scale, Q, K, V, O, lse, st);
     else launch_fwd<T, 64, 2>(t, nbh, scale, Q, K, V, O, lse, st);
 }
@@ -764,6 +770,7 @@ void dq_by_d(const S2DeviceTables &t, int nbh, int d, float scale, const void *q
     T *DQ = static_cast<T *>(dq);
     if (d == 16 && narrow16(t, nbh, t.nlat_out)) launch_dq<T, 16, 2>(t, nbh, scale, Q, K, V, O, lse, G, DQ, Dws, st);
     else if (d == 16) launch_dq<T, 16, 4>(t, nbh, scale, Q, K, V, O, lse, G, DQ, Dws, st);
+    else if (d == 32 && tiny32(t, nbh, t.nlat_out)) launch_dq<T, 32, 1>(t, nbh, scale, Q, K, V, O, lse, G, DQ, Dws, st);
     else if (d == 32) launch_dq<T, 32, 2>(t, nbh, scale, Q, K, V, O, lse, G, DQ, Dws, st);
     else launch_dq<T, 64, 2>(t, nbh, scale, Q, K, V, O, lse, G, DQ, Dws, st);
 }
@@ -776,6 +783,7 @@ void dkdv_by_d(const S2DeviceTables &t, int nbh, int d, float scale, const void 
     T *DK = static_cast<T *>(dk), *DV = static_cast<T *>(dv);
     if (d == 16 && narrow16(t, nbh, t.nlat_in)) launch_dkdv<T, 16, 2>(t, nbh, scale, Q, K, V, lse, G, Dws, DK, DV, st);
     else if (d == 16) launch_dkdv<T, 16, 4>(t, nbh, scale, Q, K, V, lse, G, Dws, DK, DV, st);
+    else if (d == 32 && tiny32(t, nbh, t.nlat_in)) launch_dkdv<T, 32, 1>(t, nbh, scale, Q, K, V, lse, G, Dws, DK, DV, st);
     else if (d == 32) launch_dkdv<T, 32, 2>(t, nbh, scale, Q, K, V, lse, G, Dws, DK, DV, st);
     else launch_dkdv<T, 64, 2>(t, nbh, scale, Q, K, V, lse, G, Dws, DK, DV, st);
 }
@@ -785,6 +793,7 @@ void dkdv_by_d(const S2DeviceTables &t, int nbh, int d, float scale, const void 
 int s2_nattn_band_configure()
 {
     return configure_one<float, 16, 4>() || configure_one<float, 16, 2>() || configure_one<float, 32, 2>() ||
+           configure_one<float, 32, 1>() || configure_one<bf16raw, 32, 1>() ||
            configure_one<float, 64, 2>() || configure_one<bf16raw, 16, 4>() || configure_one<bf16raw, 16, 2>() ||
            configure_one<bf16raw, 32, 2>() || configure_one<bf16raw, 64, 2>();
 }
